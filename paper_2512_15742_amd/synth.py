@@ -1,0 +1,141 @@
+"""Seeded synthetic inputs for the VQ-KAN forward pass.
+
+This module only draws random parameters and inputs with the shapes, dtypes
+and distributions of the benchmark configurations; it contains none of the
+method's arithmetic (no spline evaluation, no reconstruction, no summation),
+so both the CPU oracle's tests and the GPU tests may use it.  numpy only.
+
+Stand-in note: the paper evaluates on detection heads fed by backbone features
+of real images.  Those datasets and weights are not available; the cost of the
+forward pass depends only on shapes, dtypes and the index distribution, so
+seeded synthetic tensors of the stated shapes stand in for them.  Uniform
+random indices are the worst case for gather locality.
+
+Draw order per layer (fixed): codebook, idx, gain, bias.  Inputs x are drawn
+from their own generator.  "N(0, s)" means standard deviation s.
+"""
+from __future__ import annotations
+
+from dataclasses import dataclass
+
+import numpy as np
+
+G = 10
+
+
+@dataclass
+class VQLayerParams:
+    n_in: int
+    n_out: int
+    K: int
+    codebook: np.ndarray      # [K][10] float32 or int8
+    scale: np.float32         # Int8: value = scale * q; 1.0 for float codebooks
+    idx: np.ndarray           # [in][out] uint16 or uint32
+    gain: np.ndarray          # [in][out] float32 or float16
+    bias: np.ndarray          # [in][out] float32 or float16
+
+    def as_dict(self):
+        return {"codebook": self.codebook, "scale": self.scale, "idx": self.idx,
+                "gain": self.gain, "bias": self.bias}
+
+    @property
+    def metadata_bytes(self) -> int:
+        return self.idx.nbytes + self.gain.nbytes + self.bias.nbytes
+
+    @property
+    def edges(self) -> int:
+        return self.n_in * self.n_out
+
+
+def make_shapes(rng: np.random.Generator, K: int) -> np.ndarray:
+    """K rows of N(0,1)^10, made zero-mean and unit-L2-norm, as float32."""
+    s = rng.standard_normal((K, G))
+    s -= s.mean(axis=1, keepdims=True)
+    s /= np.linalg.norm(s, axis=1, keepdims=True)
+    return s.astype(np.float32)
+
+
+def quantise_shapes(shapes: np.ndarray):
+    """Int8 codebook with one scale per layer: scale = max|shape| / 127,
+    q = clip(rint(shape / scale), -127, 127)."""
+    scale = np.float32(np.abs(shapes).max() / 127.0)
+    q = np.clip(np.rint(shapes.astype(np.float64) / np.float64(scale)), -127, 127).astype(np.int8)
+    return q, scale
+
+
+def make_layer(seed: int, n_in: int, n_out: int, K: int, *, cb_dtype="f32",
+               gb_dtype="f32", idx_dtype=None) -> VQLayerParams:
+    rng = np.random.default_rng(seed)
+    shapes = make_shapes(rng, K)
+    if cb_dtype == "i8":
+        codebook, scale = quantise_shapes(shapes)
+    elif cb_dtype == "f32":
+        codebook, scale = shapes, np.float32(1.0)
+    else:
+        raise ValueError(cb_dtype)
+    if idx_dtype is None:
+        idx_dtype = "u16" if K <= 65536 else "u32"
+    np_idx = {"u16": np.uint16, "u32": np.uint32}[idx_dtype]
+    if idx_dtype == "u16" and K > 65536:
+        raise ValueError("K does not fit a 16-bit index")
+    idx = rng.integers(0, K, size=(n_in, n_out), dtype=np.int64).astype(np_idx)
+    np_gb = {"f32": np.float32, "f16": np.float16}[gb_dtype]
+    gain = np.abs(rng.normal(0.0, 0.1, size=(n_in, n_out))).astype(np_gb)
+    bias = rng.normal(0.0, 0.01, size=(n_in, n_out)).astype(np_gb)
+    return VQLayerParams(n_in, n_out, K, codebook, scale, idx, gain, bias)
+
+
+def make_x(seed: int, B: int, n_in: int, dist: str = "uniform") -> np.ndarray:
+    """Inputs [B][in] float32: 'uniform' = U[-1,1]; 'normal' = clamp(N(0,0.4),-1,1)."""
+    rng = np.random.default_rng(seed)
+    if dist == "uniform":
+        x = rng.uniform(-1.0, 1.0, size=(B, n_in))
+    elif dist == "normal":
+        x = np.clip(rng.normal(0.0, 0.4, size=(B, n_in)), -1.0, 1.0)
+    else:
+        raise ValueError(dist)
+    return x.astype(np.float32)
+
+
+# ---- the five benchmark configurations ------------------------------------
+# Seeds: configuration n, layer l -> 1000*n + l; x -> 1000*n + 900 + variant.
+# Configuration 4: head h uses seed h for its first layer and h + 100 for its
+# second.
+
+def config1():
+    """Single fp32 layer 64 -> 32, K = 256, batch 16."""
+    return [make_layer(1000, 64, 32, 256)], make_x(1900, 16, 64, "uniform")
+
+
+def config2(B: int):
+    """Backbone-feature head layer 2048 -> 512, fp32 codebook K = 65,536."""
+    return [make_layer(2000, 2048, 512, 65536)], make_x(2900 + B, B, 2048, "normal")
+
+
+def config3_layers():
+    """Two-layer Int8 head 2048 -> 1024 -> 256, fp16 gain/bias, K = 65,536 each."""
+    return [make_layer(3000, 2048, 1024, 65536, cb_dtype="i8", gb_dtype="f16"),
+            make_layer(3001, 1024, 256, 65536, cb_dtype="i8", gb_dtype="f16")]
+
+
+def config3(B: int):
+    return config3_layers(), make_x(3900 + B, B, 2048, "uniform")
+
+
+def config4_head(h: int):
+    """Task head h of the multi-expert deployment: 2048 -> 256 -> 21, Int8."""
+    return [make_layer(h, 2048, 256, 65536, cb_dtype="i8", gb_dtype="f16"),
+            make_layer(h + 100, 256, 21, 65536, cb_dtype="i8", gb_dtype="f16")]
+
+
+def config4(n_heads: int = 50, B: int = 64):
+    return [config4_head(h) for h in range(n_heads)], make_x(4900, B, 2048, "uniform")
+
+
+def config5(variant: str = "i8", B: int = 8192, n_in: int = 4096, n_out: int = 4096):
+    """Large layer, K = 262,144, uint32 indices; 'i8' (fp16 gain/bias) or 'f32'."""
+    if variant == "i8":
+        L = make_layer(5000, n_in, n_out, 262144, cb_dtype="i8", gb_dtype="f16", idx_dtype="u32")
+    else:
+        L = make_layer(5001, n_in, n_out, 262144, cb_dtype="f32", gb_dtype="f32", idx_dtype="u32")
+    return [L], make_x(5900, B, n_in, "uniform")

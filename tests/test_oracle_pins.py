@@ -1,0 +1,305 @@
+"""Pins for the CPU oracle: facts fixed by the paper and by the mathematics of
+B-splines, none of which re-type the oracle's own formula.
+
+Each pin names the part of the oracle it would catch a mistake in.
+"""
+import math
+import os
+
+import numpy as np
+import pytest
+from scipy.interpolate import BSpline
+
+from oracle import kan_oracle as ko
+from paper_2512_15742_amd import synth
+
+H = 2.0 / 7.0
+
+
+def _probe_points():
+    """[-1, 1] densely, both ends, every knot and its float32/float64 neighbours."""
+    t = ko.knots()
+    pts = [np.linspace(-1.0, 1.0, 2001)]
+    for k in t[3:11]:
+        f = np.float32(k)
+        pts.append(np.array([k, np.nextafter(k, -2), np.nextafter(k, 2), float(f),
+                             float(np.nextafter(f, np.float32(-2))),
+                             float(np.nextafter(f, np.float32(2)))]))
+    x = np.concatenate(pts)
+    return x[(x >= -1.0) & (x <= 1.0)]
+
+
+def _golden():
+    path = os.path.join(os.path.dirname(__file__), "golden", "paper_constants.txt")
+    out = {}
+    for line in open(path):
+        line = line.split("#")[0].strip()
+        if line:
+            k, v = line.split("=")
+            out[k.strip()] = int(v)
+    return out
+
+
+# ---- constants the paper prints ------------------------------------------------
+
+def test_paper_constants():
+    g = _golden()
+    assert ko.DEGREE == g["spline_degree"]
+    assert ko.G == g["grid_size_G"]
+    assert (ko.X_LO, ko.X_HI) == (g["range_lo"], g["range_hi"])
+    t = ko.knots()
+    assert len(t) == ko.G + ko.DEGREE + 1
+    assert t[3] == -1.0 and t[10] == 1.0
+    assert np.allclose(np.diff(t), H, rtol=0, atol=1e-15)
+    # storage arithmetic of the Int8 codebook and of a dense edge
+    L = synth.make_layer(7, 4, 4, g["codebook_entries_K"], cb_dtype="i8", gb_dtype="f16")
+    assert L.codebook.nbytes == g["int8_codebook_bytes"]
+    assert L.idx.dtype.itemsize * 8 == g["index_bits_at_K"]
+    assert ko.G * 4 == g["dense_bytes_per_edge"]
+
+
+# ---- P1: partition of unity, four nonzero bases at span..span+3 ----------------
+
+def test_partition_of_unity_and_support():
+    x = _probe_points()
+    Bm = ko.basis_matrix(x)
+    assert Bm.shape == (x.size, 10)
+    assert np.abs(Bm.sum(axis=1) - 1.0).max() < 1e-14
+    assert (Bm >= 0).all()
+    sp = ko.span_index(x).astype(int)
+    assert sp.min() == 0 and sp.max() == 6
+    m = np.arange(10)[None, :]
+    outside = (m < sp[:, None]) | (m > sp[:, None] + 3)
+    assert (Bm[outside] == 0.0).all()
+    # strictly inside an interval all four are positive
+    t = ko.knots()
+    xin = (t[3:10] + 0.37 * H)
+    Bin = ko.basis_matrix(xin)
+    for r, l in enumerate(range(7)):
+        assert (Bin[r, l:l + 4] > 0).all()
+
+
+def test_span_matches_scalar_search_and_ends():
+    x = _probe_points()
+    sp = ko.span_index(x)
+    for xv, s in zip(x[::7], sp[::7]):
+        assert ko.span_scalar(xv) == s
+    assert ko.span_index(np.array([-1.0]))[0] == 0
+    assert ko.span_index(np.array([1.0]))[0] == 6
+    assert ko.span_index(np.array([-3.0, 5.0])).tolist() == [0, 6]      # clamped
+    # an x just below / at / above the float32 neighbours of an interior knot
+    t = ko.knots()
+    for l in range(1, 7):
+        k = t[l + 3]
+        f = np.float32(k)
+        lo, hi = (f, np.nextafter(f, np.float32(2))) if float(f) < k else (np.nextafter(f, np.float32(-2)), f)
+        assert float(lo) < k <= float(hi)
+        assert ko.span_index(np.array([float(lo)]))[0] == l - 1
+        assert ko.span_index(np.array([float(hi)]))[0] == l
+
+
+# ---- P5: closed-form values at knots and mid-interval --------------------------
+
+def test_closed_form_weights_at_knot_and_midpoint():
+    t = ko.knots()
+    for l in range(7):
+        Bk = ko.basis_matrix(np.array([t[l + 3]]))[0]
+        np.testing.assert_allclose(Bk[l:l + 4], [1 / 6, 2 / 3, 1 / 6, 0.0], atol=1e-15)
+        Bmid = ko.basis_matrix(np.array([t[l + 3] + H / 2]))[0]
+        np.testing.assert_allclose(Bmid[l:l + 4], [1 / 48, 23 / 48, 23 / 48, 1 / 48], atol=1e-15)
+    # right end is closed: x = +1 uses coefficients 6..9 with (0, 1/6, 2/3, 1/6)
+    Bend = ko.basis_matrix(np.array([1.0]))[0]
+    np.testing.assert_allclose(Bend[6:10], [0.0, 1 / 6, 2 / 3, 1 / 6], atol=1e-15)
+    assert (Bend[:6] == 0).all()
+    # scalar definition agrees at the same points
+    for m in range(10):
+        assert abs(ko.basis_scalar(m, 3, 1.0) - Bend[m]) < 1e-15
+
+
+# ---- P4: integral of a single basis over its support equals h ------------------
+
+def test_basis_integrals():
+    t = ko.knots()
+    n = 200001
+    xs = np.linspace(t[0], t[-1], n)
+    Bm = ko.basis_matrix(xs, clamp=False, close_right=False)
+    dx = xs[1] - xs[0]
+    integ = (Bm[:-1] + Bm[1:]).sum(axis=0) * dx / 2            # trapezoid, brute force
+    np.testing.assert_allclose(integ, np.full(10, H), rtol=1e-8)
+    # restricted to [-1, 1] the end bases lose part of their support
+    inside = (xs >= -1) & (xs <= 1)
+    Bi = Bm[inside]
+    integ_in = (Bi[:-1] + Bi[1:]).sum(axis=0) * dx / 2
+    expect = np.array([1 / 24, 1 / 2, 23 / 24, 1, 1, 1, 1, 23 / 24, 1 / 2, 1 / 24]) * H
+    np.testing.assert_allclose(integ_in, expect, rtol=2e-4)
+    assert abs(integ_in.sum() - 2.0) < 1e-4
+
+
+# ---- P6 / P7: linear and quadratic precision -----------------------------------
+
+def test_linear_precision_greville():
+    t = ko.knots()
+    c = np.array([(t[m + 1] + t[m + 2] + t[m + 3]) / 3 for m in range(10)])
+    x = _probe_points()
+    phi = ko.basis_matrix(x) @ c
+    assert np.abs(phi - x).max() < 1e-15 * 4
+    for xv in (-1.0, -0.3, 0.0, 0.99, 1.0):
+        assert abs(ko.edge_phi_scalar(c, xv) - xv) < 1e-15
+
+
+def test_quadratic_precision_marsden():
+    t = ko.knots()
+    c = np.array([(t[m + 1] * t[m + 2] + t[m + 1] * t[m + 3] + t[m + 2] * t[m + 3]) / 3
+                  for m in range(10)])
+    x = _probe_points()
+    phi = ko.basis_matrix(x) @ c
+    assert np.abs(phi - x * x).max() < 1e-15 * 4
+
+
+def test_layer_closed_form_linear_shapes():
+    """A codebook whose rows are multiples of the Greville vector makes every
+    edge linear: y_j = sum_i (g_ij * a_k * x_i + b_ij), a plain mat-vec."""
+    rng = np.random.default_rng(11)
+    t = ko.knots()
+    grev = np.array([(t[m + 1] + t[m + 2] + t[m + 3]) / 3 for m in range(10)])
+    K, n_in, n_out, B = 7, 9, 5, 6
+    a = rng.normal(size=K)
+    cb = (a[:, None] * grev[None, :])
+    idx = rng.integers(0, K, size=(n_in, n_out)).astype(np.uint16)
+    gain = rng.normal(size=(n_in, n_out))
+    bias = rng.normal(size=(n_in, n_out))
+    x = rng.uniform(-1, 1, size=(B, n_in))
+    y = ko.vq_layer_forward(x, cb, 1.0, idx, gain, bias)
+    W = gain * a[idx]
+    expect = x @ W + bias.sum(axis=0)[None, :]
+    np.testing.assert_allclose(y, expect, atol=1e-13)
+    # a transposed idx/gain layout or a swapped (i, j) would break this
+    assert n_in != n_out
+
+
+# ---- P2: constant codeword => gain * v + bias ----------------------------------
+
+def test_constant_codeword():
+    rng = np.random.default_rng(5)
+    K, n_in, n_out, B = 4, 6, 3, 8
+    v = rng.normal(size=K)
+    cb = np.repeat(v[:, None], 10, axis=1)
+    idx = rng.integers(0, K, size=(n_in, n_out)).astype(np.uint16)
+    gain = rng.normal(size=(n_in, n_out))
+    bias = rng.normal(size=(n_in, n_out))
+    x = rng.uniform(-1.5, 1.5, size=(B, n_in))                  # includes clamped values
+    y = ko.vq_layer_forward(x, cb, 1.0, idx, gain, bias)
+    expect = (gain * v[idx] + bias).sum(axis=0)
+    np.testing.assert_allclose(y, np.broadcast_to(expect, (B, n_out)), atol=1e-13)
+
+
+# ---- P8: scipy's B-spline routines ---------------------------------------------
+
+def test_against_scipy_bspline():
+    t = ko.knots()
+    rng = np.random.default_rng(3)
+    x = _probe_points()
+    for _ in range(5):
+        c = rng.normal(size=10)
+        ref = BSpline(t, c, 3, extrapolate=False)(x)
+        got = ko.basis_matrix(x) @ c
+        np.testing.assert_allclose(got, ref, atol=1e-14)
+    dm = BSpline.design_matrix(x, t, 3).toarray()
+    np.testing.assert_allclose(ko.basis_matrix(x), dm, atol=1e-14)
+
+
+# ---- P9: brute force on tiny inputs, invariances --------------------------------
+
+def _tiny(seed=0, n_in=3, n_out=2, B=4, K=5, int8=False):
+    rng = np.random.default_rng(seed)
+    shapes = synth.make_shapes(rng, K)
+    if int8:
+        cb, scale = synth.quantise_shapes(shapes)
+    else:
+        cb, scale = shapes, np.float32(1.0)
+    idx = rng.integers(0, K, size=(n_in, n_out)).astype(np.uint16)
+    gain = np.abs(rng.normal(0, 0.1, size=(n_in, n_out))).astype(np.float32)
+    bias = rng.normal(0, 0.01, size=(n_in, n_out)).astype(np.float32)
+    x = rng.uniform(-1, 1, size=(B, n_in)).astype(np.float32)
+    x[0, 0], x[1, 0] = -1.0, 1.0
+    return x, cb, scale, idx, gain, bias
+
+
+@pytest.mark.parametrize("int8", [False, True])
+def test_scalar_definition_vs_vectorised(int8):
+    x, cb, scale, idx, gain, bias = _tiny(int8=int8)
+    y_def = ko.vq_layer_forward_scalar(x.tolist(), cb.tolist(), float(scale), idx.tolist(),
+                                       gain.tolist(), bias.tolist())
+    y_vec, A = ko.vq_layer_forward(x, cb, scale, idx, gain, bias, return_abs=True)
+    np.testing.assert_allclose(y_vec, y_def, atol=1e-15)
+    assert (A >= np.abs(y_vec) - 1e-15).all()
+    bs, js = [0, 3, 2], [1, 0, 1]
+    ys, As = ko.vq_layer_outputs_at(x, cb, scale, idx, gain, bias, bs, js, return_abs=True)
+    np.testing.assert_allclose(ys, y_vec[bs, js], atol=1e-15)
+    np.testing.assert_allclose(As, A[bs, js], atol=1e-15)
+
+
+def test_vq_equals_dense_on_reconstructed():          # P3
+    x, cb, scale, idx, gain, bias = _tiny(seed=2, n_in=7, n_out=5, B=6, K=9)
+    coef = ko.reconstruct_coefficients(cb, scale, idx, gain, bias)
+    assert coef.shape == (7, 5, 10)
+    # each reconstructed row is gain * shape + bias of the indexed codeword
+    i, j = 4, 3
+    np.testing.assert_allclose(coef[i, j], float(gain[i, j]) * cb[idx[i, j]].astype(np.float64)
+                               + float(bias[i, j]), atol=0)
+    assert np.array_equal(ko.vq_layer_forward(x, cb, scale, idx, gain, bias),
+                          ko.dense_layer_forward(coef, x))
+
+
+def test_permutation_linearity_additivity():
+    x, cb, scale, idx, gain, bias = _tiny(seed=4, n_in=8, n_out=3, B=5, K=6)
+    y = ko.vq_layer_forward(x, cb, scale, idx, gain, bias)
+    perm = np.random.default_rng(1).permutation(8)
+    yp = ko.vq_layer_forward(x[:, perm], cb, scale, idx[perm], gain[perm], bias[perm])
+    np.testing.assert_allclose(yp, y, atol=1e-15)
+    y0 = ko.vq_layer_forward(x, cb, scale, idx, gain * 0, bias)
+    np.testing.assert_allclose(y0, np.broadcast_to(bias.astype(np.float64).sum(0), y.shape), atol=1e-15)
+    y2 = ko.vq_layer_forward(x, cb, scale, idx, 2 * gain, bias)
+    np.testing.assert_allclose(y2 - y0, 2 * (y - y0), atol=1e-14)
+    db = np.random.default_rng(2).normal(size=bias.shape).astype(np.float32)
+    yb = ko.vq_layer_forward(x, cb, scale, idx, gain, bias.astype(np.float64) + db)
+    np.testing.assert_allclose(yb - y, np.broadcast_to(db.astype(np.float64).sum(0), y.shape), atol=1e-13)
+
+
+# ---- P10: Int8 layer equals its fp32 twin --------------------------------------
+
+def test_int8_equals_fp32_twin():
+    x, q, scale, idx, gain, bias = _tiny(seed=6, n_in=5, n_out=4, B=3, K=8, int8=True)
+    assert q.dtype == np.int8 and np.abs(q).max() <= 127
+    twin = (np.float64(scale) * q.astype(np.float64))
+    y_q = ko.vq_layer_forward(x, q, scale, idx, gain.astype(np.float16), bias.astype(np.float16))
+    y_t = ko.vq_layer_forward(x, twin, 1.0, idx, gain.astype(np.float16).astype(np.float64),
+                              bias.astype(np.float16).astype(np.float64))
+    assert np.array_equal(y_q, y_t)
+    # scale is ignored for floating codebooks
+    y_f = ko.vq_layer_forward(x, twin, 123.0, idx, gain, bias)
+    y_g = ko.vq_layer_forward(x, twin, 1.0, idx, gain, bias)
+    assert np.array_equal(y_f, y_g)
+
+
+# ---- heads ---------------------------------------------------------------------
+
+def test_head_is_layers_with_tanh_between():
+    rng = np.random.default_rng(9)
+    L1 = synth.make_layer(21, 6, 5, 16, cb_dtype="i8", gb_dtype="f16")
+    L2 = synth.make_layer(22, 5, 3, 16, cb_dtype="i8", gb_dtype="f16")
+    x = rng.uniform(-1, 1, size=(4, 6)).astype(np.float32)
+    y, hidden = ko.vq_head_forward(x, [L1.as_dict(), L2.as_dict()], return_hidden=True)
+    y1 = ko.vq_layer_forward(x, **L1.as_dict())
+    a = np.array([[math.tanh(v) for v in row] for row in y1])
+    np.testing.assert_allclose(hidden[0], a, atol=1e-15)
+    y2 = ko.vq_layer_forward(a, **L2.as_dict())
+    np.testing.assert_allclose(y, y2, atol=1e-15)
+    assert np.abs(y).max() > 1e-3          # no tanh after the last layer would not bound it; sanity only
+
+
+def test_error_report():
+    y = np.array([[1.0, -2.0], [0.0, 4.0]])
+    rep = ko.error_report(y + 1e-3, y, np.full_like(y, 10.0))
+    assert abs(rep["headline"] - 1e-3 / 4) < 1e-12
+    assert abs(rep["strict"] - 1e-4) < 1e-12
