@@ -1,0 +1,144 @@
+/*
+ * kan.h - C-ABI of the MI355X (gfx950) forward pass of vector-quantised
+ * Kolmogorov-Arnold layers (SHARe-KAN compression, LUTHAM-style runtime).
+ *
+ * What a layer computes (paper section 3 and Eq. (1), section 4.2):
+ *     c_ij   = gain_ij * C[idx_ij] + bias_ij          reconstructed coefficients
+ *     phi_ij = sum_m B_{m,3}(x_i) * c_ij[m]            cubic B-spline, G = 10
+ *     y_j    = sum_i phi_ij(x_i)
+ * with one K x G codebook C per layer (fp32, or Int8 with value = scale * q,
+ * the one-byte-per-coefficient codebook of sections 4.3 / 5.4), splines on the
+ * range [-1, 1] (App. A.1): 7 uniform intervals, 14 knots t_m = -1 + (m-3)*2/7.
+ * Inputs are clamped to [-1, 1].  x = +1 belongs to the last interval.
+ *
+ * Conventions for every entry point
+ *   - All data pointers are DEVICE pointers owned by the caller.  Descriptor
+ *     structs (kan_vq_layer) live in HOST memory and are read during the call
+ *     only.  The library never allocates, frees or keeps device memory: scratch
+ *     space comes in through the caller's workspace (ws, ws_bytes), whose
+ *     required size the *_workspace_bytes functions return (fixed buffers, no
+ *     runtime malloc: paper section 4.3).  ws must be 256-byte aligned.
+ *   - Work is enqueued on `stream` (a hipStream_t passed as void*; NULL is the
+ *     default stream).  No call synchronises the device or reads results back.
+ *   - Arguments are validated on the host first; on any error a status other
+ *     than KAN_OK is returned and NOTHING has been enqueued.
+ *   - Layouts: x[B][in] and y[B][out] row-major fp32; per-edge arrays
+ *     idx/gain/bias[in][out] with edge e = i*out + j (j fastest); codebook
+ *     [K][10] row-major, unpadded; dense coefficients coef[in][out][10].
+ *   - idx values must be < K; they are not checked by the forward calls (use
+ *     kan_vq_count_bad_indices).  y must not alias x or the workspace.
+ */
+#ifndef KAN_MI355X_H
+#define KAN_MI355X_H
+
+#include <stddef.h>
+#include <stdint.h>
+
+#ifdef __cplusplus
+extern "C" {
+#endif
+
+typedef enum kan_status {
+  KAN_OK = 0,
+  KAN_ERR_NULL = 1,        /* a required pointer is NULL                          */
+  KAN_ERR_SHAPE = 2,       /* a size is <= 0, too large, or inconsistent          */
+  KAN_ERR_DTYPE = 3,       /* dtype code not allowed for that operand             */
+  KAN_ERR_WORKSPACE = 4,   /* ws NULL, misaligned or smaller than required        */
+  KAN_ERR_UNSUPPORTED = 5, /* G != 10, degree != 3, unknown path, ...             */
+  KAN_ERR_LAUNCH = 6       /* the HIP runtime rejected a launch                   */
+} kan_status;
+
+typedef enum kan_dtype { KAN_F32 = 0, KAN_F16 = 1, KAN_I8 = 2, KAN_U16 = 3, KAN_U32 = 4 } kan_dtype;
+
+/* Which kernels carry the edge evaluation.
+ *   KAN_PATH_GATHER  fp32 vector arithmetic, one codeword gather per edge and
+ *                    batch tile; matches the float64 definition to ~1e-6.
+ *   KAN_PATH_MFMA    coefficient tile dequantised to bf16 in LDS and contracted
+ *                    against the bf16 basis tile on the matrix cores, fp32
+ *                    accumulation; ~1e-3 relative (bound: 2e-2).
+ *   KAN_PATH_AUTO    GATHER below a batch threshold, MFMA above it.           */
+typedef enum kan_path { KAN_PATH_AUTO = 0, KAN_PATH_GATHER = 1, KAN_PATH_MFMA = 2 } kan_path;
+
+/* One VQ-KAN layer (Eq. (1)): host struct, device pointers. */
+typedef struct kan_vq_layer {
+  int32_t in, out;       /* N_in, N_out, both >= 1                                  */
+  int32_t G, degree;     /* must be 10 and 3 (App. A.1), else KAN_ERR_UNSUPPORTED   */
+  int32_t K;             /* codebook entries, >= 1; <= 65536 when idx is KAN_U16    */
+  int32_t idx_dtype;     /* KAN_U16 | KAN_U32                                       */
+  int32_t gb_dtype;      /* KAN_F32 | KAN_F16 (gain and bias share it)              */
+  int32_t cb_dtype;      /* KAN_F32 | KAN_I8                                        */
+  const void* idx;       /* [in][out]                                               */
+  const void* gain;      /* [in][out]                                               */
+  const void* bias;      /* [in][out]                                               */
+  const void* codebook;  /* [K][10]                                                 */
+  float scale;           /* Int8: value = scale * q.  Ignored for KAN_F32 codebooks */
+  int32_t reserved;      /* set to 0                                                */
+} kan_vq_layer;
+
+/* Spans and basis weights of step "index lookup" (section 4.1) for the cubic
+ * family of App. A.1: for every x[n] (clamped to [-1,1]) the interval index
+ * span[n] in 0..6 and the four nonzero Cox-de Boor weights w[n][0..3], which
+ * multiply coefficients span..span+3.  Parity/debug entry point; the forward
+ * calls compute the same quantities internally with the same device function.
+ * x, span, w: device.  n >= 0 (n == 0 is a no-op).                               */
+kan_status kan_bspline_basis(const float* x, int64_t n, uint8_t* span, float* w, void* stream);
+
+/* Bytes of workspace kan_vq_layer_forward / kan_vq_head_forward need for these
+ * descriptors (host array [n_heads][n_layers]), batch B and path.  Returns 0
+ * when none is needed and (size_t)-1 when the arguments are invalid.            */
+size_t kan_vq_workspace_bytes(const kan_vq_layer* layers, int32_t n_layers, int32_t n_heads,
+                              int64_t B, int32_t path);
+
+/* y[B][out] = forward of one VQ layer (section 3 sum over Eq. (1) edges).
+ * B == 0 is a no-op returning KAN_OK.                                            */
+kan_status kan_vq_layer_forward(const kan_vq_layer* L, const float* x, int64_t B, float* y,
+                                void* ws, size_t ws_bytes, int32_t path, void* stream);
+
+/* Dense-coefficient KAN layer (the uncompressed 40-bytes-per-edge form of
+ * section 4.2): y[b][j] = sum_i sum_m B_m(x_bi) * coef[i][j][m].  G must be 10.  */
+size_t kan_dense_workspace_bytes(int32_t in, int32_t out, int64_t B);
+kan_status kan_dense_layer_forward(const float* coef, int32_t in, int32_t out, int32_t G,
+                                   const float* x, int64_t B, float* y,
+                                   void* ws, size_t ws_bytes, void* stream);
+
+/* n_heads independent heads of n_layers VQ layers each, applied to the same
+ * x[B][in0] (multi-expert deployment, section 5.6); tanh between layers, none
+ * after the last.  layers: host array [n_heads][n_layers]; layer l of every
+ * head must have the same in/out/K/dtypes (else KAN_ERR_UNSUPPORTED) and
+ * out of layer l == in of layer l+1.  y: [n_heads][B][out_last].
+ * n_heads <= 64 per call group is handled internally (any n_heads >= 1).        */
+kan_status kan_vq_head_forward(const kan_vq_layer* layers, int32_t n_layers, int32_t n_heads,
+                               const float* x, int64_t B, float* y,
+                               void* ws, size_t ws_bytes, int32_t path, void* stream);
+
+/* Debug / parity: what the kernels' own load routines fetch for every edge.
+ * ids[e] = zero-extended codeword id of edge e; rows[e][0..9] = dequantised
+ * codeword (scale*q or the fp32 row) before gain/bias.  Either output may be
+ * NULL.  ids, rows: device.                                                      */
+kan_status kan_vq_debug_gather(const kan_vq_layer* L, uint32_t* ids, float* rows, void* stream);
+
+/* Debug: *count (device uint32, overwritten) = number of edges with idx >= K.   */
+kan_status kan_vq_count_bad_indices(const kan_vq_layer* L, uint32_t* count, void* stream);
+
+/* Per-kernel timing with HIP events on the launch stream, for benchmarks.
+ * kan_prof_begin creates up to max_launches event pairs (this is the one place
+ * the library creates HIP objects) and brackets every kernel it launches from
+ * then on.  kan_prof_end synchronises those events, aggregates by kernel name
+ * into out[0..cap) (host), stores the number of distinct kernels in *n_out,
+ * destroys the events and stops recording.  Not thread-safe.                     */
+typedef struct kan_prof_record {
+  char name[56];
+  int32_t launches;
+  float total_ms;
+} kan_prof_record;
+kan_status kan_prof_begin(int32_t max_launches);
+kan_status kan_prof_end(kan_prof_record* out, int32_t cap, int32_t* n_out);
+
+const char* kan_status_string(int32_t status);
+/* Name of the kernel family the dispatcher would pick (for reports). */
+const char* kan_vq_planned_kernel(const kan_vq_layer* L, int64_t B, int32_t n_heads, int32_t path);
+
+#ifdef __cplusplus
+}
+#endif
+#endif /* KAN_MI355X_H */

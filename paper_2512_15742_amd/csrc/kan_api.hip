@@ -1,0 +1,396 @@
+// C-ABI of the library (include/kan.h): host-side validation, launch planning
+// and dispatch.  All arithmetic of the method runs in the kernels; this file
+// only decides which kernels run, with what grid, and where their scratch data
+// lives inside the caller's workspace.
+
+#include "../../include/kan.h"
+
+#include <hip/hip_runtime.h>
+#include <string.h>
+
+#include <vector>
+
+#include "kan_internal.hpp"
+
+namespace kan {
+namespace {
+
+// ---- per-kernel event timing ---------------------------------------------------
+struct Prof {
+  bool on = false;
+  int cap = 0, n = 0;
+  std::vector<hipEvent_t> ev;
+  std::vector<const char*> names;
+} g_prof;
+
+template <typename F>
+kan_status run(const char* name, hipStream_t s, F&& f) {
+  hipError_t err;
+  if (g_prof.on && g_prof.n < g_prof.cap) {
+    const int n = g_prof.n++;
+    g_prof.names[n] = name;
+    (void)hipEventRecord(g_prof.ev[2 * n], s);
+    err = f();
+    (void)hipEventRecord(g_prof.ev[2 * n + 1], s);
+  } else {
+    err = f();
+  }
+  return err == hipSuccess ? KAN_OK : KAN_ERR_LAUNCH;
+}
+
+// ---- validation ------------------------------------------------------------------
+constexpr int64_t kMaxDim = 1 << 20;
+constexpr int64_t kMaxBatch = 1 << 24;
+
+inline bool aligned(const void* p, size_t a) { return ((uintptr_t)p % a) == 0; }
+inline size_t round_up(size_t v, size_t a) { return (v + a - 1) / a * a; }
+
+kan_status validate_layer(const kan_vq_layer* L) {
+  if (!L) return KAN_ERR_NULL;
+  if (L->G != 10 || L->degree != 3) return KAN_ERR_UNSUPPORTED;
+  if (L->in < 1 || L->out < 1 || L->in > kMaxDim || L->out > kMaxDim || L->K < 1) return KAN_ERR_SHAPE;
+  if (L->idx_dtype != KAN_U16 && L->idx_dtype != KAN_U32) return KAN_ERR_DTYPE;
+  if (L->gb_dtype != KAN_F32 && L->gb_dtype != KAN_F16) return KAN_ERR_DTYPE;
+  if (L->cb_dtype != KAN_F32 && L->cb_dtype != KAN_I8) return KAN_ERR_DTYPE;
+  if (L->idx_dtype == KAN_U16 && L->K > 65536) return KAN_ERR_SHAPE;
+  if (!L->idx || !L->gain || !L->bias || !L->codebook) return KAN_ERR_NULL;
+  const size_t idx_sz = L->idx_dtype == KAN_U16 ? 2 : 4, gb_sz = L->gb_dtype == KAN_F16 ? 2 : 4;
+  if (!aligned(L->idx, idx_sz) || !aligned(L->gain, gb_sz) || !aligned(L->bias, gb_sz)) return KAN_ERR_SHAPE;
+  if (!aligned(L->codebook, L->cb_dtype == KAN_F32 ? 8 : 2)) return KAN_ERR_SHAPE;
+  return KAN_OK;
+}
+
+// ---- planning -----------------------------------------------------------------------
+// Everything below is a pure function of shapes, dtypes, batch, head count and
+// pointer alignment, so the workspace query and the forward call always agree.
+
+struct LayerPlan {
+  GatherCfg cfg;
+  int n_jt, n_bt, n_chunks, rows_per_chunk;
+  const char* name;
+};
+
+constexpr int kTargetWorkgroups = 1024;   // ~4 workgroups of 4 waves per CU
+constexpr int kMinRowsPerWave = 4;
+
+LayerPlan plan_gather(int n_in, int n_out, int64_t B, int n_heads, int idx_u32, int gb_f16, int code,
+                      bool vec_ok) {
+  LayerPlan p;
+  p.cfg.idx_u32 = idx_u32;
+  p.cfg.gb_f16 = gb_f16;
+  p.cfg.code = code;
+  p.cfg.bt = B <= 1 ? 1 : (B <= 4 ? 4 : 16);
+  p.name = p.cfg.bt == 1 ? "kan_gather_bt1" : (p.cfg.bt == 4 ? "kan_gather_bt4" : "kan_gather_bt16");
+  const int jpl_max = p.cfg.bt == 16 ? 4 : 8;
+  int jpl = 1;
+  if (vec_ok) {
+    for (int c = jpl_max; c > 1; c >>= 1)
+      if (n_out % c == 0 && n_out / c >= 64) { jpl = c; break; }
+  }
+  p.cfg.jpl = jpl;
+  const int lanes_j = (n_out + jpl - 1) / jpl;
+  p.cfg.wj = lanes_j > 128 ? 4 : (lanes_j > 64 ? 2 : 1);
+  const int wi = 4 / p.cfg.wj;
+  p.n_jt = (lanes_j + 64 * p.cfg.wj - 1) / (64 * p.cfg.wj);
+  p.n_bt = (int)((B + p.cfg.bt - 1) / p.cfg.bt);
+  const long long base = (long long)n_heads * p.n_jt * p.n_bt;
+  long long chunks = kTargetWorkgroups / (base > 0 ? base : 1);
+  const long long max_chunks = n_in / (wi * kMinRowsPerWave);
+  if (chunks > max_chunks) chunks = max_chunks;
+  if (chunks < 1) chunks = 1;
+  int rows = (int)((n_in + chunks - 1) / chunks);
+  rows = (rows + wi - 1) / wi * wi;
+  p.rows_per_chunk = rows;
+  p.n_chunks = (n_in + rows - 1) / rows;
+  return p;
+}
+
+LayerPlan plan_vq(const kan_vq_layer& L, int64_t B, int n_heads, bool vec_ok) {
+  return plan_gather(L.in, L.out, B, n_heads, L.idx_dtype == KAN_U32, L.gb_dtype == KAN_F16,
+                     L.cb_dtype == KAN_I8 ? kCbI8 : kCbF32, vec_ok);
+}
+
+bool layer_vec_ok(const kan_vq_layer& L) {
+  return aligned(L.idx, 16) && aligned(L.gain, 16) && aligned(L.bias, 16);
+}
+
+size_t partial_bytes(const LayerPlan& p, int n_out, int64_t B, int heads_in_group) {
+  if (p.n_chunks <= 1) return 0;
+  return round_up((size_t)heads_in_group * p.n_chunks * (size_t)B * n_out * sizeof(float), 256);
+}
+
+hipError_t launch_gather(const LayerPlan& p, const GatherArgs& a, int heads, hipStream_t s) {
+  dim3 grid((unsigned)(p.n_jt * p.n_bt), (unsigned)p.n_chunks, (unsigned)heads);
+  switch (p.cfg.bt) {
+    case 1: return launch_gather_bt1(p.cfg, a, grid, s);
+    case 4: return launch_gather_bt4(p.cfg, a, grid, s);
+    default: return launch_gather_bt16(p.cfg, a, grid, s);
+  }
+}
+
+// One layer of a group of heads: gather kernel, then (if i was split) the
+// fixed-order reduction.  `final_dst` receives act(y).
+kan_status run_layer_group(const LayerPlan& p, GatherArgs& a, int heads, float* final_dst,
+                           long long final_head_stride, float* partial, int apply_tanh, hipStream_t s) {
+  const long long count = (long long)a.B * a.n_out;
+  if (p.n_chunks <= 1) {
+    a.dst = final_dst;
+    a.dst_head_stride = final_head_stride;
+    a.dst_chunk_stride = 0;
+    a.apply_tanh = apply_tanh;
+    return run(p.name, s, [&] { return launch_gather(p, a, heads, s); });
+  }
+  a.dst = partial;
+  a.dst_chunk_stride = count;
+  a.dst_head_stride = count * p.n_chunks;
+  a.apply_tanh = 0;
+  kan_status st = run(p.name, s, [&] { return launch_gather(p, a, heads, s); });
+  if (st != KAN_OK) return st;
+  return run("kan_reduce", s, [&] {
+    return launch_reduce(partial, a.dst_head_stride, count, p.n_chunks, final_dst, final_head_stride,
+                         count, heads, apply_tanh, s);
+  });
+}
+
+kan_status check_path(int32_t path) {
+  if (path == KAN_PATH_AUTO || path == KAN_PATH_GATHER) return KAN_OK;
+  return KAN_ERR_UNSUPPORTED;
+}
+
+// Validates a [n_heads][n_layers] descriptor table; fills per-layer plans.
+kan_status plan_head(const kan_vq_layer* layers, int32_t n_layers, int32_t n_heads, int64_t B, int32_t path,
+                     std::vector<LayerPlan>* plans, size_t* hidden_bytes, size_t* partial_max) {
+  if (!layers) return KAN_ERR_NULL;
+  if (n_layers < 1 || n_heads < 1 || n_layers > 64 || n_heads > (1 << 16)) return KAN_ERR_SHAPE;
+  if (B < 0 || B > kMaxBatch) return KAN_ERR_SHAPE;
+  kan_status st = check_path(path);
+  if (st != KAN_OK) return st;
+  for (int h = 0; h < n_heads; ++h)
+    for (int l = 0; l < n_layers; ++l) {
+      const kan_vq_layer& L = layers[(size_t)h * n_layers + l];
+      st = validate_layer(&L);
+      if (st != KAN_OK) return st;
+      const kan_vq_layer& R = layers[l];
+      if (L.in != R.in || L.out != R.out || L.K != R.K || L.idx_dtype != R.idx_dtype ||
+          L.gb_dtype != R.gb_dtype || L.cb_dtype != R.cb_dtype)
+        return KAN_ERR_UNSUPPORTED;
+      if (l > 0 && L.in != layers[(size_t)h * n_layers + l - 1].out) return KAN_ERR_SHAPE;
+    }
+  const int group = n_heads < kMaxGroup ? n_heads : kMaxGroup;
+  *hidden_bytes = 0;
+  *partial_max = 0;
+  plans->clear();
+  for (int l = 0; l < n_layers; ++l) {
+    bool vec_ok = true;
+    for (int h = 0; h < n_heads; ++h) vec_ok = vec_ok && layer_vec_ok(layers[(size_t)h * n_layers + l]);
+    LayerPlan p = plan_vq(layers[l], B, group, vec_ok);
+    plans->push_back(p);
+    const size_t pb = partial_bytes(p, layers[l].out, B, group);
+    if (pb > *partial_max) *partial_max = pb;
+    if (l + 1 < n_layers) {
+      const size_t hb = round_up((size_t)n_heads * (size_t)B * layers[l].out * sizeof(float), 256);
+      if (hb > *hidden_bytes) *hidden_bytes = hb;
+    }
+  }
+  return KAN_OK;
+}
+
+}  // namespace
+}  // namespace kan
+
+using namespace kan;
+
+extern "C" {
+
+const char* kan_status_string(int32_t status) {
+  switch (status) {
+    case KAN_OK: return "ok";
+    case KAN_ERR_NULL: return "required pointer is NULL";
+    case KAN_ERR_SHAPE: return "invalid or inconsistent size or alignment";
+    case KAN_ERR_DTYPE: return "dtype not allowed for this operand";
+    case KAN_ERR_WORKSPACE: return "workspace missing, misaligned or too small";
+    case KAN_ERR_UNSUPPORTED: return "unsupported configuration";
+    case KAN_ERR_LAUNCH: return "HIP launch failed";
+    default: return "unknown status";
+  }
+}
+
+kan_status kan_bspline_basis(const float* x, int64_t n, uint8_t* span, float* w, void* stream) {
+  if (n < 0) return KAN_ERR_SHAPE;
+  if (n == 0) return KAN_OK;
+  if (!x || !span || !w) return KAN_ERR_NULL;
+  if (!aligned(w, 16) || !aligned(x, 4)) return KAN_ERR_SHAPE;
+  hipStream_t s = (hipStream_t)stream;
+  return run("kan_basis", s, [&] { return launch_basis(x, n, span, w, s); });
+}
+
+size_t kan_vq_workspace_bytes(const kan_vq_layer* layers, int32_t n_layers, int32_t n_heads, int64_t B,
+                              int32_t path) {
+  std::vector<LayerPlan> plans;
+  size_t hidden = 0, partial = 0;
+  if (plan_head(layers, n_layers, n_heads, B, path, &plans, &hidden, &partial) != KAN_OK) return (size_t)-1;
+  if (B == 0) return 0;
+  return (n_layers > 1 ? 2 * hidden : 0) + partial;
+}
+
+kan_status kan_vq_head_forward(const kan_vq_layer* layers, int32_t n_layers, int32_t n_heads, const float* x,
+                               int64_t B, float* y, void* ws, size_t ws_bytes, int32_t path, void* stream) {
+  std::vector<LayerPlan> plans;
+  size_t hidden = 0, partial = 0;
+  kan_status st = plan_head(layers, n_layers, n_heads, B, path, &plans, &hidden, &partial);
+  if (st != KAN_OK) return st;
+  if (B == 0) return KAN_OK;
+  if (!x || !y) return KAN_ERR_NULL;
+  if (!aligned(x, 4) || !aligned(y, 4)) return KAN_ERR_SHAPE;
+  const size_t need = (n_layers > 1 ? 2 * hidden : 0) + partial;
+  if (need > 0 && (!ws || !aligned(ws, 256) || ws_bytes < need)) return KAN_ERR_WORKSPACE;
+
+  hipStream_t s = (hipStream_t)stream;
+  char* wsp = (char*)ws;
+  float* hid[2] = {(float*)wsp, (float*)(wsp + hidden)};
+  float* part = (float*)(wsp + (n_layers > 1 ? 2 * hidden : 0));
+
+  for (int l = 0; l < n_layers; ++l) {
+    const kan_vq_layer& R = layers[l];
+    const bool last = (l + 1 == n_layers);
+    const float* src = (l == 0) ? x : hid[(l - 1) & 1];
+    const long long src_head_stride = (l == 0) ? 0 : (long long)B * R.in;
+    float* dst = last ? y : hid[l & 1];
+    const long long dst_head_stride = (long long)B * R.out;
+    for (int h0 = 0; h0 < n_heads; h0 += kMaxGroup) {
+      const int heads = (n_heads - h0) < kMaxGroup ? (n_heads - h0) : kMaxGroup;
+      GatherArgs a;
+      memset(&a, 0, sizeof(a));
+      a.x = src + (long long)h0 * src_head_stride;
+      a.x_head_stride = src_head_stride;
+      a.n_in = R.in;
+      a.n_out = R.out;
+      a.B = (int)B;
+      a.rows_per_chunk = plans[l].rows_per_chunk;
+      a.n_jt = plans[l].n_jt;
+      for (int h = 0; h < heads; ++h) {
+        const kan_vq_layer& L = layers[(size_t)(h0 + h) * n_layers + l];
+        a.h[h].idx = L.idx;
+        a.h[h].gain = L.gain;
+        a.h[h].bias = L.bias;
+        a.h[h].cb = L.codebook;
+        a.h[h].scale = L.scale;
+      }
+      st = run_layer_group(plans[l], a, heads, dst + (long long)h0 * dst_head_stride, dst_head_stride, part,
+                           last ? 0 : 1, s);
+      if (st != KAN_OK) return st;
+    }
+  }
+  return KAN_OK;
+}
+
+kan_status kan_vq_layer_forward(const kan_vq_layer* L, const float* x, int64_t B, float* y, void* ws,
+                                size_t ws_bytes, int32_t path, void* stream) {
+  return kan_vq_head_forward(L, 1, 1, x, B, y, ws, ws_bytes, path, stream);
+}
+
+size_t kan_dense_workspace_bytes(int32_t in, int32_t out, int64_t B) {
+  if (in < 1 || out < 1 || in > kMaxDim || out > kMaxDim || B < 0 || B > kMaxBatch) return (size_t)-1;
+  if (B == 0) return 0;
+  const LayerPlan p = plan_gather(in, out, B, 1, 0, 0, kDense, true);
+  return partial_bytes(p, out, B, 1);
+}
+
+kan_status kan_dense_layer_forward(const float* coef, int32_t in, int32_t out, int32_t G, const float* x,
+                                   int64_t B, float* y, void* ws, size_t ws_bytes, void* stream) {
+  if (G != 10) return KAN_ERR_UNSUPPORTED;
+  if (in < 1 || out < 1 || in > kMaxDim || out > kMaxDim || B < 0 || B > kMaxBatch) return KAN_ERR_SHAPE;
+  if (B == 0) return KAN_OK;
+  if (!coef || !x || !y) return KAN_ERR_NULL;
+  if (!aligned(coef, 8) || !aligned(x, 4) || !aligned(y, 4)) return KAN_ERR_SHAPE;
+  LayerPlan p = plan_gather(in, out, B, 1, 0, 0, kDense, true);
+  p.name = "kan_dense";
+  const size_t need = partial_bytes(p, out, B, 1);
+  if (need > 0 && (!ws || !aligned(ws, 256) || ws_bytes < need)) return KAN_ERR_WORKSPACE;
+  GatherArgs a;
+  memset(&a, 0, sizeof(a));
+  a.x = x;
+  a.n_in = in;
+  a.n_out = out;
+  a.B = (int)B;
+  a.rows_per_chunk = p.rows_per_chunk;
+  a.n_jt = p.n_jt;
+  a.h[0].cb = coef;
+  a.h[0].scale = 1.0f;
+  return run_layer_group(p, a, 1, y, (long long)B * out, (float*)ws, 0, (hipStream_t)stream);
+}
+
+kan_status kan_vq_debug_gather(const kan_vq_layer* L, uint32_t* ids, float* rows, void* stream) {
+  kan_status st = validate_layer(L);
+  if (st != KAN_OK) return st;
+  if (!ids && !rows) return KAN_ERR_NULL;
+  LayerPtrs h = {L->idx, L->gain, L->bias, L->codebook, L->scale, 0};
+  hipStream_t s = (hipStream_t)stream;
+  return run("kan_debug_gather", s, [&] {
+    return launch_debug_gather(h, L->idx_dtype == KAN_U32, L->cb_dtype == KAN_I8,
+                               (long long)L->in * L->out, ids, rows, s);
+  });
+}
+
+kan_status kan_vq_count_bad_indices(const kan_vq_layer* L, uint32_t* count, void* stream) {
+  kan_status st = validate_layer(L);
+  if (st != KAN_OK) return st;
+  if (!count) return KAN_ERR_NULL;
+  hipStream_t s = (hipStream_t)stream;
+  return run("kan_count_bad", s, [&] {
+    return launch_count_bad(L->idx, L->idx_dtype == KAN_U32, (long long)L->in * L->out, (uint32_t)L->K,
+                            count, s);
+  });
+}
+
+const char* kan_vq_planned_kernel(const kan_vq_layer* L, int64_t B, int32_t n_heads, int32_t path) {
+  if (validate_layer(L) != KAN_OK || check_path(path) != KAN_OK || B < 1 || n_heads < 1) return "invalid";
+  return plan_vq(*L, B, n_heads < kMaxGroup ? n_heads : kMaxGroup, layer_vec_ok(*L)).name;
+}
+
+kan_status kan_prof_begin(int32_t max_launches) {
+  if (max_launches < 1 || max_launches > (1 << 20)) return KAN_ERR_SHAPE;
+  if (g_prof.on) return KAN_ERR_UNSUPPORTED;
+  g_prof.ev.assign(2 * (size_t)max_launches, nullptr);
+  g_prof.names.assign(max_launches, nullptr);
+  for (auto& e : g_prof.ev)
+    if (hipEventCreate(&e) != hipSuccess) return KAN_ERR_LAUNCH;
+  g_prof.cap = max_launches;
+  g_prof.n = 0;
+  g_prof.on = true;
+  return KAN_OK;
+}
+
+kan_status kan_prof_end(kan_prof_record* out, int32_t cap, int32_t* n_out) {
+  if (!g_prof.on) return KAN_ERR_UNSUPPORTED;
+  g_prof.on = false;
+  int n_rec = 0;
+  kan_status st = KAN_OK;
+  for (int n = 0; n < g_prof.n; ++n) {
+    float ms = 0.f;
+    if (hipEventSynchronize(g_prof.ev[2 * n + 1]) != hipSuccess ||
+        hipEventElapsedTime(&ms, g_prof.ev[2 * n], g_prof.ev[2 * n + 1]) != hipSuccess) {
+      st = KAN_ERR_LAUNCH;
+      break;
+    }
+    int r = 0;
+    for (; r < n_rec; ++r)
+      if (strcmp(out[r].name, g_prof.names[n]) == 0) break;
+    if (r == n_rec) {
+      if (!out || n_rec >= cap) continue;
+      memset(&out[r], 0, sizeof(out[r]));
+      strncpy(out[r].name, g_prof.names[n], sizeof(out[r].name) - 1);
+      ++n_rec;
+    }
+    out[r].launches += 1;
+    out[r].total_ms += ms;
+  }
+  for (auto& e : g_prof.ev)
+    if (e) (void)hipEventDestroy(e);
+  g_prof.ev.clear();
+  g_prof.names.clear();
+  if (n_out) *n_out = n_rec;
+  return st;
+}
+
+}  // extern "C"

@@ -1,0 +1,161 @@
+// Device-side building blocks shared by the gfx950 kernels: the span/basis
+// routine for the cubic, G = 10, [-1,1] spline family (paper App. A.1), and the
+// loaders for per-edge metadata and codeword rows (paper Eq. (1), section 4.2).
+#pragma once
+
+#include <hip/hip_fp16.h>
+#include <hip/hip_runtime.h>
+#include <stdint.h>
+
+namespace kan {
+
+constexpr int kG = 10;        // coefficients per edge
+constexpr int kSpans = 7;     // uniform intervals on [-1, 1]
+constexpr int kWave = 64;
+
+typedef uint32_t u32x2 __attribute__((ext_vector_type(2)));
+typedef uint32_t u32x4 __attribute__((ext_vector_type(4)));
+
+struct BasisW {
+  float w0, w1, w2, w3;   // weights of coefficients span .. span+3
+  int span;               // 0..6
+};
+
+// Span and the four nonzero cubic weights at x (clamped to [-1,1]).
+//
+// The knots are the rationals (2l-7)/7.  7*x is exact in fp64 for an fp32 x, so
+// "x >= knot" is decided exactly by comparing 7x with the odd integers -5..5,
+// and the local coordinate u = (x - t_{l+3}) / h = (7x + 7 - 2l) / 2 is exact as
+// well.  x = +1 gives l = 6, u = 1 (closed right end).  The weights are the
+// uniform cubic B-spline blending polynomials, evaluated in fp64 and rounded
+// once to fp32.
+__device__ __forceinline__ BasisW basis_eval(float xf) {
+  const float xc = fminf(fmaxf(xf, -1.0f), 1.0f);
+  const double x7 = 7.0 * (double)xc;
+  const int l = (int)(x7 >= -5.0) + (int)(x7 >= -3.0) + (int)(x7 >= -1.0) +
+                (int)(x7 >= 1.0) + (int)(x7 >= 3.0) + (int)(x7 >= 5.0);
+  const double u = (x7 + (double)(7 - 2 * l)) * 0.5;
+  const double u2 = u * u, u3 = u2 * u, om = 1.0 - u;
+  const double sixth = 1.0 / 6.0;
+  BasisW r;
+  r.w0 = (float)(om * om * om * sixth);
+  r.w1 = (float)((3.0 * u3 - 6.0 * u2 + 4.0) * sixth);
+  r.w2 = (float)((-3.0 * u3 + 3.0 * u2 + 3.0 * u + 1.0) * sixth);
+  r.w3 = (float)(u3 * sixth);
+  r.span = l;
+  return r;
+}
+
+// ---- streaming loads of N consecutive per-edge values ------------------------
+// The metadata stream is read once per batch tile and never reused, so it is
+// loaded non-temporally to keep it from displacing the codebook in L2.
+
+template <int BYTES> struct RawVec;
+template <> struct RawVec<2> { typedef uint16_t type; };
+template <> struct RawVec<4> { typedef uint32_t type; };
+template <> struct RawVec<8> { typedef u32x2 type; };
+template <> struct RawVec<16> { typedef u32x4 type; };
+template <> struct RawVec<32> { struct type { u32x4 a, b; }; };
+
+template <int BYTES>
+__device__ __forceinline__ void stream_load(const void* p, void* dst) {
+  if constexpr (BYTES == 32) {
+    const u32x4* q = (const u32x4*)p;
+    u32x4 a = __builtin_nontemporal_load(q);
+    u32x4 b = __builtin_nontemporal_load(q + 1);
+    ((u32x4*)dst)[0] = a;
+    ((u32x4*)dst)[1] = b;
+  } else {
+    typedef typename RawVec<BYTES>::type V;
+    V v = __builtin_nontemporal_load((const V*)p);
+    *(V*)dst = v;
+  }
+}
+
+template <typename IdxT, int N>
+__device__ __forceinline__ void load_idx(const IdxT* p, uint32_t (&id)[N]) {
+  alignas(16) IdxT raw[N];
+  stream_load<sizeof(IdxT) * N>(p, raw);
+#pragma unroll
+  for (int n = 0; n < N; ++n) id[n] = (uint32_t)raw[n];   // zero-extends
+}
+
+template <typename T, int N>
+__device__ __forceinline__ void load_gb(const T* p, float (&v)[N]) {
+  alignas(16) T raw[N];
+  stream_load<sizeof(T) * N>(p, raw);
+#pragma unroll
+  for (int n = 0; n < N; ++n) {
+    if constexpr (sizeof(T) == 2) v[n] = __half2float(raw[n]);
+    else v[n] = raw[n];
+  }
+}
+
+// ---- codeword rows -------------------------------------------------------------
+
+__device__ __forceinline__ uint32_t ld_u32_any(const uint8_t* p) {
+  uint32_t v;
+  __builtin_memcpy(&v, p, 4);
+  return v;
+}
+__device__ __forceinline__ uint32_t ld_u16_any(const uint8_t* p) {
+  uint16_t v;
+  __builtin_memcpy(&v, p, 2);
+  return v;
+}
+
+// mul * q for the four signed bytes of w: q + 128 is read as an unsigned byte by
+// the byte-to-float converts, and the offset is folded into one fma, so each
+// coefficient costs one convert and one fma, rounded once.
+__device__ __forceinline__ void dequant4(uint32_t w, float mul, float off, float* c) {
+  const uint32_t b = w ^ 0x80808080u;
+  c[0] = fmaf((float)(b & 0xffu), mul, off);
+  c[1] = fmaf((float)((b >> 8) & 0xffu), mul, off);
+  c[2] = fmaf((float)((b >> 16) & 0xffu), mul, off);
+  c[3] = fmaf((float)(b >> 24), mul, off);
+}
+
+// Whole row: c[m] = mul * C[id][m], m = 0..9.
+template <typename CbT>
+__device__ __forceinline__ void fetch_row(const CbT* cb, uint32_t id, float mul, float (&c)[kG]) {
+  if constexpr (sizeof(CbT) == 1) {
+    const uint8_t* p = (const uint8_t*)cb + (size_t)id * kG;       // 2-byte aligned
+    const uint32_t a = ld_u32_any(p), b = ld_u32_any(p + 4), d = ld_u16_any(p + 8);
+    const float off = -128.0f * mul;
+    float t[4];
+    dequant4(a, mul, off, &c[0]);
+    dequant4(b, mul, off, &c[4]);
+    dequant4(d, mul, off, t);
+    c[8] = t[0];
+    c[9] = t[1];
+  } else {
+    const float2* p = (const float2*)(cb + (size_t)id * kG);       // 8-byte aligned
+#pragma unroll
+    for (int m = 0; m < kG / 2; ++m) {
+      const float2 v = p[m];
+      c[2 * m] = mul * v.x;
+      c[2 * m + 1] = mul * v.y;
+    }
+  }
+}
+
+// Window of four: c[r] = mul * C[id][span + r], r = 0..3 (batch-1 path: only the
+// four coefficients under the nonzero bases are fetched).
+template <typename CbT>
+__device__ __forceinline__ void fetch_window(const CbT* cb, uint32_t id, int span, float mul,
+                                             float (&c)[4]) {
+  if constexpr (sizeof(CbT) == 1) {
+    const uint8_t* p = (const uint8_t*)cb + (size_t)id * kG + span;
+    dequant4(ld_u32_any(p), mul, -128.0f * mul, c);
+  } else {
+    const float* p = cb + (size_t)id * kG + span;
+    float4 v;
+    __builtin_memcpy(&v, p, 16);
+    c[0] = mul * v.x;
+    c[1] = mul * v.y;
+    c[2] = mul * v.z;
+    c[3] = mul * v.w;
+  }
+}
+
+}  // namespace kan

@@ -1,0 +1,281 @@
+// Gather path of the VQ-KAN forward pass for gfx950: fp32 vector arithmetic.
+//
+// Mapping.  Lanes own outputs j (JPL consecutive ones each), so the per-edge
+// metadata idx/gain/bias[i][j..] of paper Eq. (1) is one contiguous, coalesced,
+// read-once stream per i-row, and everything that depends on x_bi alone (the
+// interval index and the four basis weights, App. A.1 / section 4.1) is the same
+// for all lanes of a wave: it is computed once per (b, i) into LDS and broadcast.
+// For one sample per tile only the 4 coefficients under the nonzero bases are
+// fetched; for larger tiles the weights are stored as a 10-vector (zeros outside
+// span..span+3) so that the edge evaluation is 10 branch-free fmas against the
+// whole dequantised row, with no register indexing by span.
+// The codeword C[idx] is fetched once per edge and batch tile (from L2), scaled
+// by gain (and the Int8 scale) while it is unpacked, and reused for all BT
+// samples of the tile; bias is summed once per edge because the bases sum to 1.
+// A workgroup is 4 waves: WJ of them side by side along j, 4/WJ interleaved
+// along i, whose partial sums meet in LDS.  Workgroups split i into chunks; the
+// chunk partial sums are written out and reduced in a fixed order by
+// kan_reduce (deterministic: no atomics).
+//
+// This file is compiled once per batch tile (KAN_BT = 1, 4, 16).
+
+#include "kan_device.hpp"
+#include "kan_internal.hpp"
+
+#ifndef KAN_BT
+#error "compile with -DKAN_BT=<batch tile>"
+#endif
+
+namespace kan {
+namespace {
+
+constexpr int kThreads = 256;
+constexpr int kWaves = kThreads / kWave;
+constexpr int kSub = 32;   // i-rows whose basis data is staged in LDS at a time
+
+template <typename IdxT, typename GbT, typename CbT, int CODE, int BT, int JPL>
+__global__ __launch_bounds__(kThreads) void kan_gather_kernel(const GatherArgs a, const int wj_count) {
+  // LDS: basis data for kSub rows x BT samples; later reused for the cross-wave sum.
+  constexpr bool kWindow = (BT == 1 && CODE != kDense);
+  constexpr int kWStride = kWindow ? 5 : 12;             // floats of basis data per (row, sample)
+  constexpr int kBasisFloats = kSub * BT * kWStride;
+  constexpr int kRedFloats = (kWaves - 1) * BT * kWave * JPL;
+  constexpr int kLdsFloats = kBasisFloats > kRedFloats ? kBasisFloats : kRedFloats;
+  __shared__ __attribute__((aligned(16))) float lds[kLdsFloats];
+  float4* const sw = (float4*)lds;                       // window form: [kSub] weights
+  int* const ss = (int*)(lds + kSub * BT * 4);           // window form: [kSub] spans
+
+  const int tid = threadIdx.x;
+  const int lane = tid & (kWave - 1);
+  const int wave = tid >> 6;
+  const int wi_count = kWaves / wj_count;
+  const int wj = wave % wj_count;
+  const int wi = wave / wj_count;
+
+  const int head = blockIdx.z;
+  const int chunk = blockIdx.y;
+  const int jt = blockIdx.x % a.n_jt;
+  const int btile = blockIdx.x / a.n_jt;
+
+  const LayerPtrs hp = a.h[head];
+  const int n_in = a.n_in, n_out = a.n_out;
+  const int b0 = btile * BT;
+  const int i_begin = chunk * a.rows_per_chunk;
+  const int i_end = min(n_in, i_begin + a.rows_per_chunk);
+  const int j0 = (jt * wj_count + wj) * (kWave * JPL) + lane * JPL;
+  const bool j_ok = j0 < n_out;          // n_out % JPL == 0, so the whole group is in range
+
+  const float* xh = a.x + (long long)head * a.x_head_stride;
+  const IdxT* idx = (const IdxT*)hp.idx;
+  const GbT* gain = (const GbT*)hp.gain;
+  const GbT* bias = (const GbT*)hp.bias;
+  const CbT* cb = (const CbT*)hp.cb;
+  const float scale = (CODE == kCbI8) ? hp.scale : 1.0f;
+
+  float acc[BT][JPL];
+  float bsum[JPL];
+#pragma unroll
+  for (int p = 0; p < JPL; ++p) {
+    bsum[p] = 0.f;
+#pragma unroll
+    for (int bb = 0; bb < BT; ++bb) acc[bb][p] = 0.f;
+  }
+
+  for (int s0 = i_begin; s0 < i_end; s0 += kSub) {
+    const int rows = min(kSub, i_end - s0);
+    __syncthreads();
+    // ---- span + weights for (row, sample) of this sub-chunk ----------------------
+    for (int t = tid; t < kSub * BT; t += kThreads) {
+      const int bb = t / kSub, r = t % kSub;
+      BasisW bw = {0.f, 0.f, 0.f, 0.f, 0};
+      if (r < rows && b0 + bb < a.B) bw = basis_eval(xh[(long long)(b0 + bb) * n_in + s0 + r]);
+      if constexpr (kWindow) {
+        sw[r] = make_float4(bw.w0, bw.w1, bw.w2, bw.w3);
+        ss[r] = bw.span;
+      } else {
+        // 10-vector of weights, zeros outside span..span+3 (same thread: LDS keeps order)
+        float* w10 = lds + (r * BT + bb) * kWStride;
+        const float4 z = make_float4(0.f, 0.f, 0.f, 0.f);
+        ((float4*)w10)[0] = z;
+        ((float4*)w10)[1] = z;
+        ((float4*)w10)[2] = z;
+        w10[bw.span] = bw.w0;
+        w10[bw.span + 1] = bw.w1;
+        w10[bw.span + 2] = bw.w2;
+        w10[bw.span + 3] = bw.w3;
+      }
+    }
+    __syncthreads();
+
+    if (j_ok) {
+      for (int r = wi; r < rows; r += wi_count) {
+        const long long e = (long long)(s0 + r) * n_out + j0;
+        if constexpr (kWindow) {
+          // one sample: fetch only the 4 coefficients under the nonzero bases
+          uint32_t id[JPL];
+          float g[JPL], bv[JPL];
+          load_idx<IdxT, JPL>(idx + e, id);
+          load_gb<GbT, JPL>(gain + e, g);
+          load_gb<GbT, JPL>(bias + e, bv);
+          const float4 w = sw[r];
+          const int sp = ss[r];
+#pragma unroll
+          for (int p = 0; p < JPL; ++p) {
+            float c[4];
+            fetch_window<CbT>(cb, id[p], sp, g[p] * scale, c);
+            float v = acc[0][p];
+            v = fmaf(w.x, c[0], v);
+            v = fmaf(w.y, c[1], v);
+            v = fmaf(w.z, c[2], v);
+            v = fmaf(w.w, c[3], v);
+            acc[0][p] = v;
+            bsum[p] += bv[p];
+          }
+        } else {
+          float c[JPL][kG];
+          if constexpr (CODE == kDense) {
+            typedef float f32x2 __attribute__((ext_vector_type(2)));
+            const f32x2* row = (const f32x2*)((const float*)cb + e * kG);
+#pragma unroll
+            for (int p = 0; p < JPL; ++p)
+#pragma unroll
+              for (int m = 0; m < kG / 2; ++m) {
+                const f32x2 v = __builtin_nontemporal_load(row + p * (kG / 2) + m);
+                c[p][2 * m] = v.x;
+                c[p][2 * m + 1] = v.y;
+              }
+          } else {
+            uint32_t id[JPL];
+            float g[JPL], bv[JPL];
+            load_idx<IdxT, JPL>(idx + e, id);
+            load_gb<GbT, JPL>(gain + e, g);
+            load_gb<GbT, JPL>(bias + e, bv);
+#pragma unroll
+            for (int p = 0; p < JPL; ++p) {
+              fetch_row<CbT>(cb, id[p], g[p] * scale, c[p]);
+              bsum[p] += bv[p];
+            }
+          }
+#pragma unroll
+          for (int bb = 0; bb < BT; ++bb) {
+            const float4* w10 = (const float4*)(lds + (r * BT + bb) * kWStride);
+            const float4 wa = w10[0], wb = w10[1], wc = w10[2];
+#pragma unroll
+            for (int p = 0; p < JPL; ++p) {
+              float v = acc[bb][p];
+              v = fmaf(wa.x, c[p][0], v);
+              v = fmaf(wa.y, c[p][1], v);
+              v = fmaf(wa.z, c[p][2], v);
+              v = fmaf(wa.w, c[p][3], v);
+              v = fmaf(wb.x, c[p][4], v);
+              v = fmaf(wb.y, c[p][5], v);
+              v = fmaf(wb.z, c[p][6], v);
+              v = fmaf(wb.w, c[p][7], v);
+              v = fmaf(wc.x, c[p][8], v);
+              v = fmaf(wc.y, c[p][9], v);
+              acc[bb][p] = v;
+            }
+          }
+        }
+      }
+    }
+  }
+
+  // ---- sum over the waves interleaved along i ------------------------------------
+  if (wi_count > 1) {
+    __syncthreads();
+    float* red = lds;    // [(wi-1)][wj][BT][JPL][lane]
+    if (wi > 0) {
+      float* dstp = red + (((wi - 1) * wj_count + wj) * BT * JPL) * kWave + lane;
+#pragma unroll
+      for (int bb = 0; bb < BT; ++bb)
+#pragma unroll
+        for (int p = 0; p < JPL; ++p) dstp[(bb * JPL + p) * kWave] = acc[bb][p];
+    }
+    __syncthreads();
+    if (wi == 0) {
+      for (int o = 1; o < wi_count; ++o) {
+        const float* srcp = red + (((o - 1) * wj_count + wj) * BT * JPL) * kWave + lane;
+#pragma unroll
+        for (int bb = 0; bb < BT; ++bb)
+#pragma unroll
+          for (int p = 0; p < JPL; ++p) acc[bb][p] += srcp[(bb * JPL + p) * kWave];
+      }
+    }
+    __syncthreads();   // bias sums travel in a second pass through the same buffer
+    if (wi > 0) {
+      float* dstp = red + (((wi - 1) * wj_count + wj) * JPL) * kWave + lane;
+#pragma unroll
+      for (int p = 0; p < JPL; ++p) dstp[p * kWave] = bsum[p];
+    }
+    __syncthreads();
+    if (wi == 0) {
+      for (int o = 1; o < wi_count; ++o) {
+        const float* srcp = red + (((o - 1) * wj_count + wj) * JPL) * kWave + lane;
+#pragma unroll
+        for (int p = 0; p < JPL; ++p) bsum[p] += srcp[p * kWave];
+      }
+    }
+  }
+
+  // ---- write y, the hidden activation, or this chunk's partial sums -------------
+  if (wi == 0 && j_ok) {
+    float* dst = a.dst + (long long)head * a.dst_head_stride + (long long)chunk * a.dst_chunk_stride;
+#pragma unroll
+    for (int bb = 0; bb < BT; ++bb) {
+      if (b0 + bb < a.B) {
+        float* o = dst + (long long)(b0 + bb) * n_out + j0;
+#pragma unroll
+        for (int p = 0; p < JPL; ++p) {
+          float v = acc[bb][p] + bsum[p];
+          if (a.apply_tanh) v = tanhf(v);
+          o[p] = v;
+        }
+      }
+    }
+  }
+}
+
+template <typename IdxT, typename GbT, typename CbT, int CODE, int JPL>
+hipError_t launch_one(const GatherCfg& c, const GatherArgs& a, dim3 grid, hipStream_t s) {
+  hipLaunchKernelGGL((kan_gather_kernel<IdxT, GbT, CbT, CODE, KAN_BT, JPL>), grid, dim3(kThreads), 0, s,
+                     a, c.wj);
+  return hipGetLastError();
+}
+
+template <typename IdxT, typename GbT, typename CbT, int CODE>
+hipError_t launch_jpl(const GatherCfg& c, const GatherArgs& a, dim3 grid, hipStream_t s) {
+  switch (c.jpl) {
+    case 1: return launch_one<IdxT, GbT, CbT, CODE, 1>(c, a, grid, s);
+    case 2: return launch_one<IdxT, GbT, CbT, CODE, 2>(c, a, grid, s);
+    case 4: return launch_one<IdxT, GbT, CbT, CODE, 4>(c, a, grid, s);
+#if KAN_BT <= 4
+    case 8: return launch_one<IdxT, GbT, CbT, CODE, 8>(c, a, grid, s);
+#endif
+    default: return hipErrorInvalidValue;
+  }
+}
+
+template <typename IdxT>
+hipError_t launch_types(const GatherCfg& c, const GatherArgs& a, dim3 grid, hipStream_t s) {
+  if (c.code == kCbI8) {
+    return c.gb_f16 ? launch_jpl<IdxT, __half, int8_t, kCbI8>(c, a, grid, s)
+                    : launch_jpl<IdxT, float, int8_t, kCbI8>(c, a, grid, s);
+  }
+  return c.gb_f16 ? launch_jpl<IdxT, __half, float, kCbF32>(c, a, grid, s)
+                  : launch_jpl<IdxT, float, float, kCbF32>(c, a, grid, s);
+}
+
+}  // namespace
+
+#define KAN_CAT2(a, b) a##b
+#define KAN_CAT(a, b) KAN_CAT2(a, b)
+
+hipError_t KAN_CAT(launch_gather_bt, KAN_BT)(const GatherCfg& c, const GatherArgs& a, dim3 grid,
+                                              hipStream_t s) {
+  if (c.bt != KAN_BT) return hipErrorInvalidValue;
+  if (c.code == kDense) return launch_jpl<uint16_t, float, float, kDense>(c, a, grid, s);
+  return c.idx_u32 ? launch_types<uint32_t>(c, a, grid, s) : launch_types<uint16_t>(c, a, grid, s);
+}
+
+}  // namespace kan

@@ -1,0 +1,65 @@
+// Host-side structures shared by the dispatcher (kan_api.hip) and the kernel
+// translation units.  Nothing here is part of the public C-ABI.
+#pragma once
+
+#include <hip/hip_runtime.h>
+#include <stdint.h>
+
+namespace kan {
+
+constexpr int kMaxGroup = 64;   // heads per grouped launch (descriptor table lives in kernarg)
+
+// Pointers of one layer of one head (device pointers).  For the dense baseline
+// `cb` points at coef[in][out][10] and the other three are unused.
+struct LayerPtrs {
+  const void* idx;
+  const void* gain;
+  const void* bias;
+  const void* cb;
+  float scale;
+  int pad;
+};
+
+enum CodeKind : int { kCbF32 = 0, kCbI8 = 1, kDense = 2 };
+
+// ---- gather path (fp32 vector arithmetic) --------------------------------------
+struct GatherCfg {
+  int bt;          // batch tile: 1, 4 or 16 samples per workgroup
+  int jpl;         // consecutive outputs per lane: 1, 2, 4 or 8
+  int wj;          // waves of the 4-wave workgroup laid along j (1, 2 or 4); 4/wj along i
+  int idx_u32;     // 0: uint16 indices, 1: uint32
+  int gb_f16;      // 0: fp32 gain/bias, 1: fp16
+  int code;        // CodeKind
+};
+
+struct GatherArgs {
+  const float* x;              // [heads or 1][B][n_in]
+  long long x_head_stride;     // elements between heads; 0 when all heads share x
+  float* dst;                  // y, hidden activation, or partial sums
+  long long dst_head_stride;   // elements
+  long long dst_chunk_stride;  // elements between i-chunks (partials); unused when n_chunks == 1
+  int n_in, n_out, B;
+  int rows_per_chunk;          // i-rows per workgroup (multiple of 4/wj)
+  int n_jt;                    // j-tiles; blockIdx.x = bt_index * n_jt + jt
+  int apply_tanh;              // only honoured when the kernel writes final values
+  LayerPtrs h[kMaxGroup];
+};
+
+hipError_t launch_gather_bt1(const GatherCfg&, const GatherArgs&, dim3 grid, hipStream_t);
+hipError_t launch_gather_bt4(const GatherCfg&, const GatherArgs&, dim3 grid, hipStream_t);
+hipError_t launch_gather_bt16(const GatherCfg&, const GatherArgs&, dim3 grid, hipStream_t);
+
+// ---- reduction of i-chunk partial sums ------------------------------------------
+// dst[n] = act( sum_c partial[c * chunk_stride + n] ), n < count, for every head.
+hipError_t launch_reduce(const float* partial, long long head_stride, long long chunk_stride,
+                         int n_chunks, float* dst, long long dst_head_stride, long long count,
+                         int n_heads, int apply_tanh, hipStream_t);
+
+// ---- debug / parity kernels -------------------------------------------------------
+hipError_t launch_basis(const float* x, long long n, uint8_t* span, float* w, hipStream_t);
+hipError_t launch_debug_gather(const LayerPtrs&, int idx_u32, int cb_i8, long long edges,
+                               uint32_t* ids, float* rows, hipStream_t);
+hipError_t launch_count_bad(const void* idx, int idx_u32, long long edges, uint32_t K,
+                            uint32_t* count, hipStream_t);
+
+}  // namespace kan

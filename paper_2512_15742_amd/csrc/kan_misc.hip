@@ -1,0 +1,124 @@
+// Small kernels around the main paths: fixed-order reduction of i-chunk partial
+// sums (+ the inter-layer tanh), the stand-alone span/basis kernel, and the
+// debug kernels that expose what the load routines fetch.
+
+#include "kan_device.hpp"
+#include "kan_internal.hpp"
+
+namespace kan {
+namespace {
+
+__global__ __launch_bounds__(256) void kan_reduce_kernel(const float* __restrict__ partial,
+                                                         long long head_stride, long long chunk_stride,
+                                                         int n_chunks, float* __restrict__ dst,
+                                                         long long dst_head_stride, long long count,
+                                                         int apply_tanh) {
+  const int head = blockIdx.y;
+  const float* p = partial + (long long)head * head_stride;
+  float* d = dst + (long long)head * dst_head_stride;
+  for (long long n = (long long)blockIdx.x * blockDim.x + threadIdx.x; n < count;
+       n += (long long)gridDim.x * blockDim.x) {
+    float s = 0.f;
+    for (int c = 0; c < n_chunks; ++c) s += __builtin_nontemporal_load(p + (long long)c * chunk_stride + n);
+    d[n] = apply_tanh ? tanhf(s) : s;
+  }
+}
+
+__global__ __launch_bounds__(256) void kan_basis_kernel(const float* __restrict__ x, long long n,
+                                                        uint8_t* __restrict__ span, float* __restrict__ w) {
+  for (long long t = (long long)blockIdx.x * blockDim.x + threadIdx.x; t < n;
+       t += (long long)gridDim.x * blockDim.x) {
+    const BasisW b = basis_eval(x[t]);
+    span[t] = (uint8_t)b.span;
+    ((float4*)w)[t] = make_float4(b.w0, b.w1, b.w2, b.w3);
+  }
+}
+
+template <typename IdxT, typename CbT>
+__global__ __launch_bounds__(256) void kan_debug_gather_kernel(const IdxT* __restrict__ idx,
+                                                               const CbT* __restrict__ cb, float scale,
+                                                               long long edges, uint32_t* __restrict__ ids,
+                                                               float* __restrict__ rows) {
+  for (long long e = (long long)blockIdx.x * blockDim.x + threadIdx.x; e < edges;
+       e += (long long)gridDim.x * blockDim.x) {
+    uint32_t id[1];
+    load_idx<IdxT, 1>(idx + e, id);
+    if (ids) ids[e] = id[0];
+    if (rows) {
+      float c[kG];
+      fetch_row<CbT>(cb, id[0], scale, c);
+#pragma unroll
+      for (int m = 0; m < kG; ++m) rows[e * kG + m] = c[m];
+    }
+  }
+}
+
+template <typename IdxT>
+__global__ __launch_bounds__(256) void kan_count_bad_kernel(const IdxT* __restrict__ idx, long long edges,
+                                                            uint32_t K, uint32_t* __restrict__ count) {
+  uint32_t bad = 0;
+  for (long long e = (long long)blockIdx.x * blockDim.x + threadIdx.x; e < edges;
+       e += (long long)gridDim.x * blockDim.x)
+    bad += ((uint32_t)idx[e] >= K) ? 1u : 0u;
+  if (bad) atomicAdd(count, bad);
+}
+
+__global__ void kan_zero_u32_kernel(uint32_t* p) { *p = 0u; }
+
+inline int blocks_for(long long n, int cap = 65536) {
+  long long b = (n + 255) / 256;
+  if (b < 1) b = 1;
+  if (b > cap) b = cap;
+  return (int)b;
+}
+
+}  // namespace
+
+hipError_t launch_reduce(const float* partial, long long head_stride, long long chunk_stride, int n_chunks,
+                         float* dst, long long dst_head_stride, long long count, int n_heads,
+                         int apply_tanh, hipStream_t s) {
+  dim3 grid(blocks_for(count, 4096), n_heads);
+  hipLaunchKernelGGL(kan_reduce_kernel, grid, dim3(256), 0, s, partial, head_stride, chunk_stride,
+                     n_chunks, dst, dst_head_stride, count, apply_tanh);
+  return hipGetLastError();
+}
+
+hipError_t launch_basis(const float* x, long long n, uint8_t* span, float* w, hipStream_t s) {
+  hipLaunchKernelGGL(kan_basis_kernel, dim3(blocks_for(n)), dim3(256), 0, s, x, n, span, w);
+  return hipGetLastError();
+}
+
+hipError_t launch_debug_gather(const LayerPtrs& h, int idx_u32, int cb_i8, long long edges, uint32_t* ids,
+                               float* rows, hipStream_t s) {
+  dim3 grid(blocks_for(edges)), block(256);
+  const float scale = cb_i8 ? h.scale : 1.0f;
+  if (idx_u32) {
+    if (cb_i8)
+      hipLaunchKernelGGL((kan_debug_gather_kernel<uint32_t, int8_t>), grid, block, 0, s,
+                         (const uint32_t*)h.idx, (const int8_t*)h.cb, scale, edges, ids, rows);
+    else
+      hipLaunchKernelGGL((kan_debug_gather_kernel<uint32_t, float>), grid, block, 0, s,
+                         (const uint32_t*)h.idx, (const float*)h.cb, scale, edges, ids, rows);
+  } else {
+    if (cb_i8)
+      hipLaunchKernelGGL((kan_debug_gather_kernel<uint16_t, int8_t>), grid, block, 0, s,
+                         (const uint16_t*)h.idx, (const int8_t*)h.cb, scale, edges, ids, rows);
+    else
+      hipLaunchKernelGGL((kan_debug_gather_kernel<uint16_t, float>), grid, block, 0, s,
+                         (const uint16_t*)h.idx, (const float*)h.cb, scale, edges, ids, rows);
+  }
+  return hipGetLastError();
+}
+
+hipError_t launch_count_bad(const void* idx, int idx_u32, long long edges, uint32_t K, uint32_t* count,
+                            hipStream_t s) {
+  hipLaunchKernelGGL(kan_zero_u32_kernel, dim3(1), dim3(1), 0, s, count);
+  dim3 grid(blocks_for(edges, 2048)), block(256);
+  if (idx_u32)
+    hipLaunchKernelGGL((kan_count_bad_kernel<uint32_t>), grid, block, 0, s, (const uint32_t*)idx, edges, K, count);
+  else
+    hipLaunchKernelGGL((kan_count_bad_kernel<uint16_t>), grid, block, 0, s, (const uint16_t*)idx, edges, K, count);
+  return hipGetLastError();
+}
+
+}  // namespace kan

@@ -1,0 +1,132 @@
+"""Host-side checks of the C-ABI that need no GPU: the library loads, exports
+every function include/kan.h declares, rejects invalid arguments before any
+launch, and plans workspaces consistently.  No compute call is made here."""
+import ctypes as C
+import os
+import re
+
+import pytest
+
+from paper_2512_15742_amd import binding as kb
+
+ROOT = os.path.dirname(os.path.dirname(os.path.abspath(__file__)))
+
+pytestmark = pytest.mark.skipif(not os.path.exists(kb.LIB_PATH), reason="library not built")
+
+
+def _declared():
+    text = open(os.path.join(ROOT, "include", "kan.h")).read()
+    text = re.sub(r"/\*.*?\*/", "", text, flags=re.S)
+    return sorted(set(re.findall(r"\b(kan_[a-z0-9_]+)\s*\(", text)))
+
+
+def test_exports_match_header():
+    names = _declared()
+    assert set(names) == set(kb.EXPORTS)
+    L = kb.lib()
+    for n in names:
+        assert hasattr(L, n), n
+
+
+def test_struct_layout_matches_header():
+    # 8 int32, 4 pointers, float, int32 -> 72 bytes on LP64; profile record 56 + 4 + 4
+    assert C.sizeof(kb.kan_vq_layer) == 72
+    assert C.sizeof(kb.kan_prof_record) == 64
+
+
+def test_status_strings():
+    seen = {kb.status_string(s) for s in range(7)}
+    assert len(seen) == 7
+    assert kb.status_string(99) == "unknown status"
+
+
+def _desc(**kw):
+    base = dict(n_in=8, n_out=8, G=10, degree=3, K=16, idx_dtype=kb.KAN_U16, gb_dtype=kb.KAN_F32,
+                cb_dtype=kb.KAN_F32, idx=0x1000, gain=0x2000, bias=0x3000, codebook=0x4000,
+                scale=1.0, reserved=0)
+    base.update(kw)
+    return kb.kan_vq_layer(**base)
+
+
+FAKE = C.c_void_p(0x10000)
+
+
+@pytest.mark.parametrize("kw,status", [
+    (dict(G=8), kb.KAN_ERR_UNSUPPORTED),
+    (dict(degree=2), kb.KAN_ERR_UNSUPPORTED),
+    (dict(n_in=0), kb.KAN_ERR_SHAPE),
+    (dict(n_out=-3), kb.KAN_ERR_SHAPE),
+    (dict(K=0), kb.KAN_ERR_SHAPE),
+    (dict(K=65537), kb.KAN_ERR_SHAPE),                       # does not fit a 16-bit index
+    (dict(idx_dtype=kb.KAN_F32), kb.KAN_ERR_DTYPE),
+    (dict(gb_dtype=kb.KAN_I8), kb.KAN_ERR_DTYPE),
+    (dict(cb_dtype=kb.KAN_F16), kb.KAN_ERR_DTYPE),
+    (dict(idx=0), kb.KAN_ERR_NULL),
+    (dict(codebook=0), kb.KAN_ERR_NULL),
+    (dict(gain=0x2001), kb.KAN_ERR_SHAPE),                   # misaligned fp32
+    (dict(codebook=0x4004), kb.KAN_ERR_SHAPE),               # fp32 rows need 8-byte alignment
+])
+def test_layer_validation_rejects_before_launch(kw, status):
+    d = _desc(**kw)
+    st = kb.lib().kan_vq_layer_forward(C.byref(d), FAKE, 4, FAKE, FAKE, 1 << 20, kb.KAN_PATH_AUTO, None)
+    assert st == status
+    assert kb.lib().kan_vq_workspace_bytes(C.byref(d), 1, 1, 4, kb.KAN_PATH_AUTO) == kb.SIZE_INVALID
+    assert kb.lib().kan_vq_debug_gather(C.byref(d), FAKE, FAKE, None) == status
+    assert kb.lib().kan_vq_count_bad_indices(C.byref(d), FAKE, None) == status
+
+
+def test_forward_argument_errors():
+    L = kb.lib()
+    d = _desc()
+    assert L.kan_vq_layer_forward(None, FAKE, 4, FAKE, FAKE, 1 << 20, 0, None) == kb.KAN_ERR_NULL
+    assert L.kan_vq_layer_forward(C.byref(d), None, 4, FAKE, FAKE, 1 << 20, 0, None) == kb.KAN_ERR_NULL
+    assert L.kan_vq_layer_forward(C.byref(d), FAKE, 4, None, FAKE, 1 << 20, 0, None) == kb.KAN_ERR_NULL
+    assert L.kan_vq_layer_forward(C.byref(d), FAKE, -1, FAKE, FAKE, 1 << 20, 0, None) == kb.KAN_ERR_SHAPE
+    assert L.kan_vq_layer_forward(C.byref(d), FAKE, 4, FAKE, FAKE, 1 << 20, 17, None) == kb.KAN_ERR_UNSUPPORTED
+    # B == 0 is a no-op
+    assert L.kan_vq_layer_forward(C.byref(d), None, 0, None, None, 0, 0, None) == kb.KAN_OK
+    assert L.kan_bspline_basis(None, 0, None, None, None) == kb.KAN_OK
+    assert L.kan_bspline_basis(None, 5, FAKE, FAKE, None) == kb.KAN_ERR_NULL
+    assert L.kan_bspline_basis(FAKE, -1, FAKE, FAKE, None) == kb.KAN_ERR_SHAPE
+    assert L.kan_dense_layer_forward(FAKE, 8, 8, 9, FAKE, 4, FAKE, None, 0, None) == kb.KAN_ERR_UNSUPPORTED
+    assert L.kan_dense_layer_forward(FAKE, 0, 8, 10, FAKE, 4, FAKE, None, 0, None) == kb.KAN_ERR_SHAPE
+    assert L.kan_dense_layer_forward(None, 8, 8, 10, FAKE, 4, FAKE, None, 0, None) == kb.KAN_ERR_NULL
+    assert L.kan_dense_layer_forward(None, 8, 8, 10, None, 0, None, None, 0, None) == kb.KAN_OK
+
+
+def test_workspace_required_and_checked():
+    L = kb.lib()
+    # a layer wide enough that i is split into chunks needs room for partial sums
+    d = _desc(n_in=2048, n_out=1024, K=65536, cb_dtype=kb.KAN_I8, gb_dtype=kb.KAN_F16)
+    need = L.kan_vq_workspace_bytes(C.byref(d), 1, 1, 1, kb.KAN_PATH_GATHER)
+    assert 0 < need < (64 << 20) and need % 256 == 0
+    assert L.kan_vq_layer_forward(C.byref(d), FAKE, 1, FAKE, None, 0, kb.KAN_PATH_GATHER, None) == kb.KAN_ERR_WORKSPACE
+    assert L.kan_vq_layer_forward(C.byref(d), FAKE, 1, FAKE, FAKE, need - 1, kb.KAN_PATH_GATHER, None) == kb.KAN_ERR_WORKSPACE
+    assert L.kan_vq_layer_forward(C.byref(d), FAKE, 1, FAKE, C.c_void_p(0x10010), need, kb.KAN_PATH_GATHER, None) == kb.KAN_ERR_WORKSPACE
+    assert L.kan_vq_workspace_bytes(C.byref(d), 1, 1, 0, kb.KAN_PATH_AUTO) == 0
+    assert L.kan_dense_workspace_bytes(2048, 512, 1) > 0
+    assert L.kan_dense_workspace_bytes(0, 512, 1) == kb.SIZE_INVALID
+
+
+def test_head_table_consistency():
+    L = kb.lib()
+    arr = (kb.kan_vq_layer * 4)()
+    arr[0] = _desc(n_in=32, n_out=16)
+    arr[1] = _desc(n_in=16, n_out=4)
+    arr[2] = _desc(n_in=32, n_out=16)
+    arr[3] = _desc(n_in=16, n_out=4)
+    assert L.kan_vq_workspace_bytes(arr, 2, 2, 8, 0) != kb.SIZE_INVALID
+    arr[3] = _desc(n_in=16, n_out=5)            # heads must share layer shapes
+    assert L.kan_vq_head_forward(arr, 2, 2, FAKE, 8, FAKE, FAKE, 1 << 24, 0, None) == kb.KAN_ERR_UNSUPPORTED
+    arr[1] = _desc(n_in=15, n_out=4)            # layer chain broken: 16 -> 15
+    arr[3] = _desc(n_in=15, n_out=4)
+    assert L.kan_vq_head_forward(arr, 2, 2, FAKE, 8, FAKE, FAKE, 1 << 24, 0, None) == kb.KAN_ERR_SHAPE
+    assert L.kan_vq_head_forward(arr, 0, 2, FAKE, 8, FAKE, FAKE, 1 << 24, 0, None) == kb.KAN_ERR_SHAPE
+    assert L.kan_vq_head_forward(None, 2, 2, FAKE, 8, FAKE, FAKE, 1 << 24, 0, None) == kb.KAN_ERR_NULL
+
+
+def test_prof_state_machine_without_gpu_work():
+    L = kb.lib()
+    n = C.c_int32(-1)
+    assert L.kan_prof_end(None, 0, C.byref(n)) == kb.KAN_ERR_UNSUPPORTED      # not begun
+    assert L.kan_prof_begin(0) == kb.KAN_ERR_SHAPE
