@@ -1,0 +1,220 @@
+#!/usr/bin/env python3
+"""Benchmark of the VQ-KAN forward pass on one MI355X.
+
+    python bench.py [--gpus 1] [--steps K] [--warmup W] [--batch 1024] [--path auto|gather|mfma]
+
+Workload: the two-layer Int8 VQ-KAN head 2048 -> 1024 -> 256 (K = 65,536 per
+layer, uint16 idx, fp16 gain/bias, tanh between layers), synthetic seeded
+parameters and inputs resident in HBM before the timed region.  A step is one
+forward of the whole head over one batch.  The headline `value` is edge
+evaluations per second at --batch (default 1024); the same line also carries
+the batch-1 figures (edge-evals/s and metadata-stream GB/s), the roofline of
+the dominant kernel, and the CPU oracle timed on a bounded sample.
+
+To keep the metadata stream coming from HBM rather than from the 256 MB
+memory-side cache, the steps rotate over enough independent parameter copies
+to exceed that cache; a second, single-copy ("cache-warm") figure is reported
+next to it.
+"""
+from __future__ import annotations
+
+import argparse
+import json
+import os
+import sys
+import time
+
+ROOT = os.path.dirname(os.path.abspath(__file__))
+if ROOT not in sys.path:
+    sys.path.insert(0, ROOT)
+
+PEAK_HBM_GBPS = 8000.0          # MI355X HBM3E
+PEAK_FP32_VECTOR_TFLOPS = 157.3
+PEAK_BF16_MFMA_TFLOPS = 2500.0
+FLOP_PER_EDGE_EVAL = 8.0        # 4 multiply-adds under the nonzero cubic bases
+FLOP_PER_EDGE_RECON = 20.0      # gain * C[idx] + bias over G = 10, once per launch
+MALL_BYTES = 256 << 20
+
+# HBM bytes per launch of the dominant kernel measured with rocprofv3 --pmc
+# (FETCH_SIZE / WRITE_SIZE runs scaled by a copy kernel of known size); see the
+# summaries under profiles/.  None until such a run exists for the workload.
+MEASURED_TRAFFIC = {}
+
+
+def parse():
+    ap = argparse.ArgumentParser()
+    ap.add_argument("--gpus", type=int, default=1)
+    ap.add_argument("--steps", type=int, default=200)
+    ap.add_argument("--warmup", type=int, default=20)
+    ap.add_argument("--batch", type=int, default=1024)
+    ap.add_argument("--path", default="auto", choices=["auto", "gather", "mfma"])
+    ap.add_argument("--no-cpu-baseline", action="store_true")
+    ap.add_argument("--copies", type=int, default=0, help="parameter copies to rotate over (0 = enough to exceed the memory-side cache)")
+    return ap.parse_args()
+
+
+def time_steps(torch, fn, steps, warmup):
+    for s in range(warmup):
+        fn(s)
+    torch.cuda.synchronize()
+    t0 = time.perf_counter()
+    for s in range(steps):
+        fn(warmup + s)
+    torch.cuda.synchronize()
+    return (time.perf_counter() - t0) / steps
+
+
+def kernel_times(kb, torch, fn, steps, warmup):
+    """Average duration per launch of every kernel, HIP events on the launch stream."""
+    for s in range(min(warmup, 5)):
+        fn(s)
+    torch.cuda.synchronize()
+    kb.kan_prof_begin(steps * 8)
+    for s in range(steps):
+        fn(warmup + s)
+    torch.cuda.synchronize()
+    rec = kb.kan_prof_end()
+    return {k: {"launches": v["launches"], "avg_us": 1e3 * v["total_ms"] / max(v["launches"], 1)}
+            for k, v in rec.items()}
+
+
+def run_batch(kb, torch, synth, copies, B, path, steps, warmup):
+    x = torch.from_numpy(synth.make_x(3900 + B, B, 2048, "uniform")).cuda()
+    ws_bytes = kb.kan_vq_workspace_bytes([copies[0]], B, path)
+    ws = torch.empty(max(ws_bytes, 256), dtype=torch.uint8, device="cuda")
+    y = torch.empty((1, B, 256), dtype=torch.float32, device="cuda")
+    n = len(copies)
+
+    def cold(s):
+        kb.kan_vq_head_forward([copies[s % n]], x, path=path, ws=ws, y=y)
+
+    def warm(s):
+        kb.kan_vq_head_forward([copies[0]], x, path=path, ws=ws, y=y)
+
+    t_cold = time_steps(torch, cold, steps, warmup)
+    t_warm = time_steps(torch, warm, steps, warmup)
+    kt = kernel_times(kb, torch, cold, min(steps, 100), warmup)
+    return t_cold, t_warm, kt
+
+
+def main():
+    args = parse()
+    if args.gpus != 1:
+        print("bench.py measures one MI355X; runs with --gpus above 1 are not part of this build", file=sys.stderr)
+        sys.exit(2)
+    import numpy as np
+    import torch
+
+    from paper_2512_15742_amd import binding as kb
+    from paper_2512_15742_amd import synth
+
+    assert torch.cuda.is_available(), "bench.py needs a GPU"
+    kb.lib()
+    path = {"auto": kb.KAN_PATH_AUTO, "gather": kb.KAN_PATH_GATHER, "mfma": kb.KAN_PATH_MFMA}[args.path]
+
+    layers = synth.config3_layers()
+    edges = [p.edges for p in layers]
+    meta = [p.metadata_bytes for p in layers]
+    param_bytes = sum(meta) + sum(p.codebook.nbytes for p in layers)
+    n_copies = args.copies or (MALL_BYTES * 5 // 4 + param_bytes - 1) // param_bytes
+    base = [kb.VQLayer(p) for p in layers]
+    copies = [base]
+    for _ in range(n_copies - 1):           # independent device copies of the same parameters
+        cp = []
+        for p in layers:
+            cp.append(kb.VQLayer(p))
+        copies.append(cp)
+
+    results = {}
+    for B in sorted({1, args.batch}):
+        steps = args.steps if B > 1 else max(args.steps, 500)
+        t_cold, t_warm, kt = run_batch(kb, torch, synth, copies, B, path, steps, args.warmup)
+        ee = sum(edges) * B
+        dom = max((k for k in kt if k.startswith("kan_gather") or k.startswith("kan_mfma")),
+                  key=lambda k: kt[k]["avg_us"] * kt[k]["launches"])
+        # the dominant kernel runs once per layer; split its time by layer using the per-layer work
+        results[B] = {
+            "batch": B, "steps": steps,
+            "ms_per_step": 1e3 * t_cold, "edge_evals_per_s": ee / t_cold,
+            "metadata_GBps": sum(meta) / t_cold / 1e9,
+            "ms_per_step_cache_warm": 1e3 * t_warm, "edge_evals_per_s_cache_warm": ee / t_warm,
+            "kernels_avg_us": {k: round(v["avg_us"], 3) for k, v in kt.items()},
+            "kernels_launches_per_step": {k: v["launches"] / min(steps, 100) for k, v in kt.items()},
+            "planned_kernel_layer1": kb.kan_vq_planned_kernel(base[0], B, 1, path),
+            "dominant": dom,
+        }
+
+    B = args.batch
+    r = results[B]
+    dom = r["dominant"]
+    # Layer 1 and layer 2 launch the same kernel family; its average launch moves
+    # (edges_l1 + edges_l2) / 2 edges, which is what `achieved` is priced on.
+    launches_per_step = r["kernels_launches_per_step"][dom]
+    avg_s = r["kernels_avg_us"][dom] * 1e-6
+    edges_per_launch = sum(edges) / launches_per_step
+    is_mfma = dom.startswith("kan_mfma")
+    if B >= 16:
+        # compute-bound regime (the metadata stream stops being the limit near B = 12-20)
+        flops = edges_per_launch * (B * FLOP_PER_EDGE_EVAL + FLOP_PER_EDGE_RECON)
+        peak = PEAK_BF16_MFMA_TFLOPS if is_mfma else PEAK_FP32_VECTOR_TFLOPS
+        roof = {"bound": "mfma" if is_mfma else "alu", "achieved": flops / avg_s / 1e12, "peak": peak,
+                "unit": "TFLOP/s", "kernel": dom, "avg_launch_us": r["kernels_avg_us"][dom],
+                "traffic": MEASURED_TRAFFIC.get((dom, B))}
+    else:
+        nbytes = sum(meta) / launches_per_step
+        roof = {"bound": "hbm", "achieved": nbytes / avg_s / 1e9, "peak": PEAK_HBM_GBPS, "unit": "GB/s",
+                "kernel": dom, "avg_launch_us": r["kernels_avg_us"][dom],
+                "traffic": MEASURED_TRAFFIC.get((dom, B))}
+    roof["frac"] = roof["achieved"] / roof["peak"]
+
+    r1 = results[1]
+    dom1 = r1["dominant"]
+    l1 = r1["kernels_launches_per_step"][dom1]
+    roof1 = {"bound": "hbm", "achieved": (sum(meta) / l1) / (r1["kernels_avg_us"][dom1] * 1e-6) / 1e9,
+             "peak": PEAK_HBM_GBPS, "unit": "GB/s", "kernel": dom1, "avg_launch_us": r1["kernels_avg_us"][dom1],
+             "traffic": MEASURED_TRAFFIC.get((dom1, 1))}
+    roof1["frac"] = roof1["achieved"] / roof1["peak"]
+    r1["roofline"] = roof1
+
+    cpu = None
+    if not args.no_cpu_baseline:
+        from oracle import kan_oracle as ko
+        try:
+            from threadpoolctl import threadpool_info
+            threads = max([p.get("num_threads", 1) for p in threadpool_info()] or [1])
+        except Exception:
+            threads = os.cpu_count()
+        rows = 128
+        xs = synth.make_x(3900 + 1024, 1024, 2048, "uniform")[:rows]
+        dl = [p.as_dict() for p in layers]
+        ko.vq_head_forward(xs[:8], dl)                       # warm-up (untimed)
+        ts = []
+        for _ in range(3):
+            t0 = time.perf_counter()
+            ko.vq_head_forward(xs, dl)
+            ts.append(time.perf_counter() - t0)
+        t = sorted(ts)[1]
+        cpu = {"value": sum(edges) * rows / t, "unit": "edge-evals/s", "cores": int(threads), "kind": "oracle",
+               "sample": f"float64 numpy oracle, whole head on {rows} of the 1024 batch rows, median of 3 ({t:.2f} s each)"}
+
+    out = {
+        "metric": "VQ-KAN edge-evals/sec (Int8 K=65536 head 2048->1024->256)",
+        "value": r["edge_evals_per_s"], "unit": "edge-evals/s",
+        "n_gpus": 1, "steps": r["steps"], "warmup": args.warmup, "ms_per_step": r["ms_per_step"],
+        "higher_is_better": True, "scaling": "weak", "vs_baseline": None,
+        "dtype": "bf16" if roof["kernel"].startswith("kan_mfma") else "f32", "data": "synthetic",
+        "config": {"workload": f"config 3: two-layer Int8 VQ-KAN head 2048->1024->256, K=65536 per layer, "
+                               f"uint16 idx, fp16 gain/bias, tanh between layers, batch {B}",
+                   "batch": B, "path": args.path, "parameter_copies_rotated": n_copies,
+                   "edges": sum(edges), "metadata_bytes": sum(meta)},
+        "metadata_GBps": r["metadata_GBps"],
+        "roofline": roof,
+        "cpu_baseline": cpu,
+        "batch1": r1,
+        "batch%d" % B: r,
+    }
+    print(json.dumps(out))
+
+
+if __name__ == "__main__":
+    main()

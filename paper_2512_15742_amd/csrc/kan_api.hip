@@ -67,6 +67,7 @@ kan_status validate_layer(const kan_vq_layer* L) {
 struct LayerPlan {
   GatherCfg cfg;
   int n_jt, n_bt, n_chunks, rows_per_chunk;
+  bool mfma;
   const char* name;
 };
 
@@ -76,6 +77,7 @@ constexpr int kMinRowsPerWave = 4;
 LayerPlan plan_gather(int n_in, int n_out, int64_t B, int n_heads, int idx_u32, int gb_f16, int code,
                       bool vec_ok) {
   LayerPlan p;
+  p.mfma = false;
   p.cfg.idx_u32 = idx_u32;
   p.cfg.gb_f16 = gb_f16;
   p.cfg.code = code;
@@ -105,9 +107,47 @@ LayerPlan plan_gather(int n_in, int n_out, int64_t B, int n_heads, int idx_u32, 
   return p;
 }
 
-LayerPlan plan_vq(const kan_vq_layer& L, int64_t B, int n_heads, bool vec_ok) {
-  return plan_gather(L.in, L.out, B, n_heads, L.idx_dtype == KAN_U32, L.gb_dtype == KAN_F16,
-                     L.cb_dtype == KAN_I8 ? kCbI8 : kCbF32, vec_ok);
+// Matrix-core path: 128 x 128 (samples x outputs) tiles, i split so that about
+// three workgroups per CU are in flight.
+constexpr int kMfmaTile = 128;
+constexpr int kMfmaRowsStep = 8;
+constexpr int kMfmaTargetWorkgroups = 768;
+constexpr int kMfmaMinRows = 64;
+constexpr int64_t kAutoMfmaBatch = 64;    // KAN_PATH_AUTO switches to the matrix cores from here
+
+LayerPlan plan_mfma(int n_in, int n_out, int64_t B, int n_heads, int idx_u32, int gb_f16, int code) {
+  LayerPlan p;
+  p.mfma = true;
+  p.name = "kan_mfma";
+  p.cfg.bt = kMfmaTile;
+  p.cfg.jpl = 1;
+  p.cfg.wj = 2;
+  p.cfg.idx_u32 = idx_u32;
+  p.cfg.gb_f16 = gb_f16;
+  p.cfg.code = code;
+  p.n_jt = (n_out + kMfmaTile - 1) / kMfmaTile;
+  p.n_bt = (int)((B + kMfmaTile - 1) / kMfmaTile);
+  const long long base = (long long)n_heads * p.n_jt * p.n_bt;
+  long long chunks = kMfmaTargetWorkgroups / (base > 0 ? base : 1);
+  const long long max_chunks = n_in / kMfmaMinRows;
+  if (chunks > max_chunks) chunks = max_chunks;
+  if (chunks < 1) chunks = 1;
+  int rows = (int)((n_in + chunks - 1) / chunks);
+  rows = (rows + kMfmaRowsStep - 1) / kMfmaRowsStep * kMfmaRowsStep;
+  p.rows_per_chunk = rows;
+  p.n_chunks = (n_in + rows - 1) / rows;
+  return p;
+}
+
+bool use_mfma(int32_t path, int64_t B) {
+  return path == KAN_PATH_MFMA || (path == KAN_PATH_AUTO && B >= kAutoMfmaBatch);
+}
+
+LayerPlan plan_vq(const kan_vq_layer& L, int64_t B, int n_heads, bool vec_ok, int32_t path) {
+  const int code = L.cb_dtype == KAN_I8 ? kCbI8 : kCbF32;
+  if (use_mfma(path, B))
+    return plan_mfma(L.in, L.out, B, n_heads, L.idx_dtype == KAN_U32, L.gb_dtype == KAN_F16, code);
+  return plan_gather(L.in, L.out, B, n_heads, L.idx_dtype == KAN_U32, L.gb_dtype == KAN_F16, code, vec_ok);
 }
 
 bool layer_vec_ok(const kan_vq_layer& L) {
@@ -121,6 +161,7 @@ size_t partial_bytes(const LayerPlan& p, int n_out, int64_t B, int heads_in_grou
 
 hipError_t launch_gather(const LayerPlan& p, const GatherArgs& a, int heads, hipStream_t s) {
   dim3 grid((unsigned)(p.n_jt * p.n_bt), (unsigned)p.n_chunks, (unsigned)heads);
+  if (p.mfma) return launch_mfma(p.cfg, a, grid, s);
   switch (p.cfg.bt) {
     case 1: return launch_gather_bt1(p.cfg, a, grid, s);
     case 4: return launch_gather_bt4(p.cfg, a, grid, s);
@@ -153,7 +194,7 @@ kan_status run_layer_group(const LayerPlan& p, GatherArgs& a, int heads, float* 
 }
 
 kan_status check_path(int32_t path) {
-  if (path == KAN_PATH_AUTO || path == KAN_PATH_GATHER) return KAN_OK;
+  if (path == KAN_PATH_AUTO || path == KAN_PATH_GATHER || path == KAN_PATH_MFMA) return KAN_OK;
   return KAN_ERR_UNSUPPORTED;
 }
 
@@ -183,7 +224,7 @@ kan_status plan_head(const kan_vq_layer* layers, int32_t n_layers, int32_t n_hea
   for (int l = 0; l < n_layers; ++l) {
     bool vec_ok = true;
     for (int h = 0; h < n_heads; ++h) vec_ok = vec_ok && layer_vec_ok(layers[(size_t)h * n_layers + l]);
-    LayerPlan p = plan_vq(layers[l], B, group, vec_ok);
+    LayerPlan p = plan_vq(layers[l], B, group, vec_ok, path);
     plans->push_back(p);
     const size_t pb = partial_bytes(p, layers[l].out, B, group);
     if (pb > *partial_max) *partial_max = pb;
@@ -345,7 +386,7 @@ kan_status kan_vq_count_bad_indices(const kan_vq_layer* L, uint32_t* count, void
 
 const char* kan_vq_planned_kernel(const kan_vq_layer* L, int64_t B, int32_t n_heads, int32_t path) {
   if (validate_layer(L) != KAN_OK || check_path(path) != KAN_OK || B < 1 || n_heads < 1) return "invalid";
-  return plan_vq(*L, B, n_heads < kMaxGroup ? n_heads : kMaxGroup, layer_vec_ok(*L)).name;
+  return plan_vq(*L, B, n_heads < kMaxGroup ? n_heads : kMaxGroup, layer_vec_ok(*L), path).name;
 }
 
 kan_status kan_prof_begin(int32_t max_launches) {

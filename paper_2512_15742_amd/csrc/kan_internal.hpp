@@ -49,6 +49,9 @@ hipError_t launch_gather_bt1(const GatherCfg&, const GatherArgs&, dim3 grid, hip
 hipError_t launch_gather_bt4(const GatherCfg&, const GatherArgs&, dim3 grid, hipStream_t);
 hipError_t launch_gather_bt16(const GatherCfg&, const GatherArgs&, dim3 grid, hipStream_t);
 
+// ---- matrix-core path (bf16 tiles in LDS, fp32 accumulate); same argument block ----
+hipError_t launch_mfma(const GatherCfg&, const GatherArgs&, dim3 grid, hipStream_t);
+
 // ---- reduction of i-chunk partial sums ------------------------------------------
 // dst[n] = act( sum_c partial[c * chunk_stride + n] ), n < count, for every head.
 hipError_t launch_reduce(const float* partial, long long head_stride, long long chunk_stride,

@@ -1,0 +1,111 @@
+"""GPU parity of the matrix-core (bf16 tiles, fp32 accumulate) path against the
+float64 oracle: outputs within 2e-2 relative; everything integer (spans, ids)
+is covered by the exact routines in test_gpu_parity.py."""
+import numpy as np
+import pytest
+
+from oracle import kan_oracle as ko
+from paper_2512_15742_amd import synth
+
+from kan_testlib import TOL_MFMA, check_layer_output, gpu_layers, to_dev
+
+pytestmark = pytest.mark.gpu
+
+torch = pytest.importorskip("torch")
+
+
+@pytest.fixture(scope="module")
+def kb():
+    if not torch.cuda.is_available():
+        pytest.skip("no GPU")
+    from paper_2512_15742_amd import binding
+    binding.lib()
+    return binding
+
+
+@pytest.mark.parametrize("n_in,n_out,B", [(1, 1, 1), (8, 32, 32), (3, 21, 2), (130, 67, 5), (257, 130, 150),
+                                          (64, 520, 33), (1000, 264, 300), (2048, 8, 129)])
+def test_mfma_ragged_shapes(kb, n_in, n_out, B):
+    P = synth.make_layer(n_in * 7 + n_out, n_in, n_out, 1000, cb_dtype="i8", gb_dtype="f16")
+    x = synth.make_x(B, B, n_in)
+    x[0, 0] = 1.0
+    x[-1, -1] = -1.0
+    (L,) = gpu_layers([P])
+    y = kb.kan_vq_layer_forward(L, to_dev(x), path=kb.KAN_PATH_MFMA).cpu().numpy()
+    y_ref, A = ko.vq_layer_forward(x, **P.as_dict(), return_abs=True)
+    rep = ko.error_report(y, y_ref, A)
+    assert rep["headline"] <= TOL_MFMA and rep["strict"] <= TOL_MFMA, rep
+    assert rep["headline"] >= 0 and np.isfinite(y).all()
+
+
+@pytest.mark.parametrize("gb,cb,idx", [("f32", "i8", "u16"), ("f16", "f32", "u16"), ("f32", "f32", "u32"), ("f16", "i8", "u32")])
+def test_mfma_dtype_combinations(kb, gb, cb, idx):
+    P = synth.make_layer(9, 96, 160, 70000 if idx == "u32" else 4096, cb_dtype=cb, gb_dtype=gb, idx_dtype=idx)
+    x = synth.make_x(4, 200, 96, "normal")
+    (L,) = gpu_layers([P])
+    y = kb.kan_vq_layer_forward(L, to_dev(x), path=kb.KAN_PATH_MFMA).cpu().numpy()
+    y_ref, A = ko.vq_layer_forward(x, **P.as_dict(), return_abs=True)
+    rep = ko.error_report(y, y_ref, A)
+    assert rep["headline"] <= TOL_MFMA and rep["strict"] <= TOL_MFMA, rep
+
+
+def test_mfma_config1(kb):
+    (P,), x = synth.config1()
+    (L,) = gpu_layers([P])
+    y = kb.kan_vq_layer_forward(L, to_dev(x), path=kb.KAN_PATH_MFMA).cpu().numpy()
+    y_ref, A = ko.vq_layer_forward(x, **P.as_dict(), return_abs=True)
+    rep = ko.error_report(y, y_ref, A)
+    assert rep["headline"] <= TOL_MFMA and rep["strict"] <= TOL_MFMA, rep
+
+
+def test_mfma_config2_b256(kb):
+    (P,), x = synth.config2(256)
+    (L,) = gpu_layers([P])
+    y = kb.kan_vq_layer_forward(L, to_dev(x), path=kb.KAN_PATH_MFMA).cpu().numpy()
+    rep = check_layer_output(y, x, P, TOL_MFMA)
+    print("config2 B=256 mfma", rep)
+
+
+@pytest.mark.parametrize("B", [256, 1024, 4096])
+def test_mfma_config3_head(kb, B):
+    Ps, x = synth.config3(B)
+    Ls = gpu_layers(Ps)
+    y = kb.kan_vq_head_forward([Ls], to_dev(x), path=kb.KAN_PATH_MFMA)[0].cpu().numpy()
+    rows = np.sort(np.random.default_rng(B).choice(B, 64, replace=False))
+    y_ref = ko.vq_head_forward(x[rows], [p.as_dict() for p in Ps])
+    rep = ko.error_report(y[rows], y_ref)
+    print("config3 mfma", B, rep)
+    assert rep["headline"] <= TOL_MFMA, rep
+    # the automatic dispatcher takes the same path at these batch sizes
+    assert kb.kan_vq_planned_kernel(Ls[0], B, 1, kb.KAN_PATH_AUTO) == "kan_mfma"
+    y_auto = kb.kan_vq_head_forward([Ls], to_dev(x), path=kb.KAN_PATH_AUTO)[0]
+    assert np.array_equal(y_auto.cpu().numpy(), y)
+
+
+def test_mfma_config4_multi_head(kb):
+    n_heads, B = 50, 64
+    heads_p, x = synth.config4(n_heads, B)
+    heads = [gpu_layers(ps) for ps in heads_p]
+    y = kb.kan_vq_head_forward(heads, to_dev(x), path=kb.KAN_PATH_MFMA).cpu().numpy()
+    for h in (0, 23, 49):
+        y_ref = ko.vq_head_forward(x, [p.as_dict() for p in heads_p[h]])
+        assert ko.error_report(y[h], y_ref)["headline"] <= TOL_MFMA
+
+
+@pytest.mark.parametrize("variant", ["i8", "f32"])
+def test_mfma_config5_sampled(kb, variant):
+    (P,), x = synth.config5(variant)
+    (L,) = gpu_layers([P])
+    y = kb.kan_vq_layer_forward(L, to_dev(x), path=kb.KAN_PATH_MFMA).cpu().numpy()
+    assert np.isfinite(y).all()
+    rep = check_layer_output(y, x, P, TOL_MFMA, n_samples=64, full=False, seed=5)
+    print("config5 mfma", variant, rep)
+
+
+def test_mfma_deterministic(kb):
+    Ps, x = synth.config3(256)
+    Ls = gpu_layers(Ps)
+    xd = to_dev(x)
+    y1 = kb.kan_vq_head_forward([Ls], xd, path=kb.KAN_PATH_MFMA).clone()
+    y2 = kb.kan_vq_head_forward([Ls], xd, path=kb.KAN_PATH_MFMA)
+    assert torch.equal(y1, y2)
