@@ -107,11 +107,12 @@ LayerPlan plan_gather(int n_in, int n_out, int64_t B, int n_heads, int idx_u32, 
   return p;
 }
 
-// Matrix-core path: 128 x 128 (samples x outputs) tiles, i split so that about
-// three workgroups per CU are in flight.
-constexpr int kMfmaTile = 128;
-constexpr int kMfmaRowsStep = 8;
-constexpr int kMfmaTargetWorkgroups = 768;
+// Matrix-core path: 128 x 256 (samples x outputs) tiles, i split so that every
+// CU has work.
+constexpr int kMfmaTileM = 128;
+constexpr int kMfmaTileN = 256;
+constexpr int kMfmaRowsStep = kMfmaPrepRows;   // chunk boundaries coincide with partial bias sums
+constexpr int kMfmaTargetWorkgroups = 256;
 constexpr int kMfmaMinRows = 64;
 constexpr int64_t kAutoMfmaBatch = 64;    // KAN_PATH_AUTO switches to the matrix cores from here
 
@@ -119,14 +120,14 @@ LayerPlan plan_mfma(int n_in, int n_out, int64_t B, int n_heads, int idx_u32, in
   LayerPlan p;
   p.mfma = true;
   p.name = "kan_mfma";
-  p.cfg.bt = kMfmaTile;
+  p.cfg.bt = kMfmaTileM;
   p.cfg.jpl = 1;
   p.cfg.wj = 2;
   p.cfg.idx_u32 = idx_u32;
   p.cfg.gb_f16 = gb_f16;
   p.cfg.code = code;
-  p.n_jt = (n_out + kMfmaTile - 1) / kMfmaTile;
-  p.n_bt = (int)((B + kMfmaTile - 1) / kMfmaTile);
+  p.n_jt = (n_out + kMfmaTileN - 1) / kMfmaTileN;
+  p.n_bt = (int)((B + kMfmaTileM - 1) / kMfmaTileM);
   const long long base = (long long)n_heads * p.n_jt * p.n_bt;
   long long chunks = kMfmaTargetWorkgroups / (base > 0 ? base : 1);
   const long long max_chunks = n_in / kMfmaMinRows;
@@ -159,9 +160,23 @@ size_t partial_bytes(const LayerPlan& p, int n_out, int64_t B, int heads_in_grou
   return round_up((size_t)heads_in_group * p.n_chunks * (size_t)B * n_out * sizeof(float), 256);
 }
 
+// Scratch regions inside the caller's workspace (each a multiple of 256 bytes;
+// sized for the largest layer and for one group of heads).
+struct WsLayout {
+  size_t hidden = 0;    // one of two ping-pong hidden-activation buffers, [n_heads][B][out]
+  size_t partial = 0;   // i-chunk partial sums
+  size_t cf = 0;        // matrix-core path: fp16 coefficient fragments
+  size_t bp = 0;        // matrix-core path: partial bias sums
+  size_t u = 0;         // matrix-core path: packed span + local coordinate
+  int n_layers = 1;
+  size_t total() const { return (n_layers > 1 ? 2 * hidden : 0) + partial + cf + bp + u; }
+};
+
+size_t mfma_cf_records(int n_in, int n_out) { return (size_t)((n_in + 7) / 8) * 5 * (size_t)n_out * 2; }
+size_t mfma_bp_floats(int n_in, int n_out) { return (size_t)((n_in + kMfmaPrepRows - 1) / kMfmaPrepRows) * n_out; }
+
 hipError_t launch_gather(const LayerPlan& p, const GatherArgs& a, int heads, hipStream_t s) {
   dim3 grid((unsigned)(p.n_jt * p.n_bt), (unsigned)p.n_chunks, (unsigned)heads);
-  if (p.mfma) return launch_mfma(p.cfg, a, grid, s);
   switch (p.cfg.bt) {
     case 1: return launch_gather_bt1(p.cfg, a, grid, s);
     case 4: return launch_gather_bt4(p.cfg, a, grid, s);
@@ -169,27 +184,75 @@ hipError_t launch_gather(const LayerPlan& p, const GatherArgs& a, int heads, hip
   }
 }
 
-// One layer of a group of heads: gather kernel, then (if i was split) the
-// fixed-order reduction.  `final_dst` receives act(y).
-kan_status run_layer_group(const LayerPlan& p, GatherArgs& a, int heads, float* final_dst,
-                           long long final_head_stride, float* partial, int apply_tanh, hipStream_t s) {
+// Pointers of the scratch regions for the current call.
+struct WsPtrs {
+  float* hid[2];
+  float* partial;
+  uint4* cf;
+  float* bp;
+  uint32_t* u;
+};
+
+// One layer of a group of heads.  `a` carries x, shapes and the per-head pointers;
+// `final_dst` receives act(y).  Gather path: main kernel, then (if i was split) the
+// fixed-order reduction.  Matrix-core path: coefficient and basis preparation first.
+kan_status run_layer_group(const LayerPlan& p, GatherArgs& a, int heads, bool x_shared, float* final_dst,
+                           long long final_head_stride, const WsPtrs& w, int apply_tanh, hipStream_t s) {
   const long long count = (long long)a.B * a.n_out;
-  if (p.n_chunks <= 1) {
-    a.dst = final_dst;
-    a.dst_head_stride = final_head_stride;
-    a.dst_chunk_stride = 0;
-    a.apply_tanh = apply_tanh;
-    return run(p.name, s, [&] { return launch_gather(p, a, heads, s); });
+  const bool split = p.n_chunks > 1;
+  float* dst = split ? w.partial : final_dst;
+  const long long dst_head_stride = split ? count * p.n_chunks : final_head_stride;
+  const long long dst_chunk_stride = split ? count : 0;
+  const int tanh_in_kernel = split ? 0 : apply_tanh;
+  kan_status st;
+  if (p.mfma) {
+    PrepCoefArgs pc;
+    memset(&pc, 0, sizeof(pc));
+    pc.cf = w.cf;
+    pc.cf_head_stride = (long long)mfma_cf_records(a.n_in, a.n_out);
+    pc.bias_partial = w.bp;
+    pc.bp_head_stride = (long long)mfma_bp_floats(a.n_in, a.n_out);
+    pc.n_in = a.n_in;
+    pc.n_out = a.n_out;
+    memcpy(pc.h, a.h, sizeof(pc.h));
+    st = run("kan_prep_coef", s, [&] { return launch_prep_coef(p.cfg, pc, heads, s); });
+    if (st != KAN_OK) return st;
+    const long long u_stride = x_shared ? 0 : (long long)a.n_in * a.B;
+    st = run("kan_prep_basis", s, [&] {
+      return launch_prep_basis(a.x, a.x_head_stride, w.u, u_stride, a.n_in, a.B, x_shared ? 1 : heads, s);
+    });
+    if (st != KAN_OK) return st;
+    MfmaArgs m;
+    memset(&m, 0, sizeof(m));
+    m.cf = w.cf;
+    m.cf_head_stride = pc.cf_head_stride;
+    m.U = w.u;
+    m.u_head_stride = u_stride;
+    m.bias_partial = w.bp;
+    m.bp_head_stride = pc.bp_head_stride;
+    m.dst = dst;
+    m.dst_head_stride = dst_head_stride;
+    m.dst_chunk_stride = dst_chunk_stride;
+    m.n_in = a.n_in;
+    m.n_out = a.n_out;
+    m.B = a.B;
+    m.rows_per_chunk = p.rows_per_chunk;
+    m.n_jt = p.n_jt;
+    m.apply_tanh = tanh_in_kernel;
+    for (int h = 0; h < heads; ++h) m.scale[h] = p.cfg.code == kCbI8 ? a.h[h].scale : 1.0f;
+    dim3 grid((unsigned)(p.n_jt * p.n_bt), (unsigned)p.n_chunks, (unsigned)heads);
+    st = run(p.name, s, [&] { return launch_mfma(m, grid, s); });
+  } else {
+    a.dst = dst;
+    a.dst_head_stride = dst_head_stride;
+    a.dst_chunk_stride = dst_chunk_stride;
+    a.apply_tanh = tanh_in_kernel;
+    st = run(p.name, s, [&] { return launch_gather(p, a, heads, s); });
   }
-  a.dst = partial;
-  a.dst_chunk_stride = count;
-  a.dst_head_stride = count * p.n_chunks;
-  a.apply_tanh = 0;
-  kan_status st = run(p.name, s, [&] { return launch_gather(p, a, heads, s); });
-  if (st != KAN_OK) return st;
+  if (st != KAN_OK || !split) return st;
   return run("kan_reduce", s, [&] {
-    return launch_reduce(partial, a.dst_head_stride, count, p.n_chunks, final_dst, final_head_stride,
-                         count, heads, apply_tanh, s);
+    return launch_reduce(w.partial, dst_head_stride, count, p.n_chunks, final_dst, final_head_stride, count,
+                         heads, apply_tanh, s);
   });
 }
 
@@ -198,9 +261,9 @@ kan_status check_path(int32_t path) {
   return KAN_ERR_UNSUPPORTED;
 }
 
-// Validates a [n_heads][n_layers] descriptor table; fills per-layer plans.
+// Validates a [n_heads][n_layers] descriptor table; fills per-layer plans and scratch sizes.
 kan_status plan_head(const kan_vq_layer* layers, int32_t n_layers, int32_t n_heads, int64_t B, int32_t path,
-                     std::vector<LayerPlan>* plans, size_t* hidden_bytes, size_t* partial_max) {
+                     std::vector<LayerPlan>* plans, WsLayout* ws) {
   if (!layers) return KAN_ERR_NULL;
   if (n_layers < 1 || n_heads < 1 || n_layers > 64 || n_heads > (1 << 16)) return KAN_ERR_SHAPE;
   if (B < 0 || B > kMaxBatch) return KAN_ERR_SHAPE;
@@ -218,20 +281,23 @@ kan_status plan_head(const kan_vq_layer* layers, int32_t n_layers, int32_t n_hea
       if (l > 0 && L.in != layers[(size_t)h * n_layers + l - 1].out) return KAN_ERR_SHAPE;
     }
   const int group = n_heads < kMaxGroup ? n_heads : kMaxGroup;
-  *hidden_bytes = 0;
-  *partial_max = 0;
+  *ws = WsLayout();
+  ws->n_layers = n_layers;
   plans->clear();
   for (int l = 0; l < n_layers; ++l) {
+    const kan_vq_layer& R = layers[l];
     bool vec_ok = true;
     for (int h = 0; h < n_heads; ++h) vec_ok = vec_ok && layer_vec_ok(layers[(size_t)h * n_layers + l]);
-    LayerPlan p = plan_vq(layers[l], B, group, vec_ok, path);
+    LayerPlan p = plan_vq(R, B, group, vec_ok, path);
     plans->push_back(p);
-    const size_t pb = partial_bytes(p, layers[l].out, B, group);
-    if (pb > *partial_max) *partial_max = pb;
-    if (l + 1 < n_layers) {
-      const size_t hb = round_up((size_t)n_heads * (size_t)B * layers[l].out * sizeof(float), 256);
-      if (hb > *hidden_bytes) *hidden_bytes = hb;
+    auto grow = [](size_t& dst, size_t v) { if (v > dst) dst = v; };
+    grow(ws->partial, partial_bytes(p, R.out, B, group));
+    if (p.mfma) {
+      grow(ws->cf, round_up((size_t)group * mfma_cf_records(R.in, R.out) * sizeof(uint4), 256));
+      grow(ws->bp, round_up((size_t)group * mfma_bp_floats(R.in, R.out) * sizeof(float), 256));
+      grow(ws->u, round_up((size_t)(l == 0 ? 1 : group) * (size_t)R.in * (size_t)B * sizeof(uint32_t), 256));
     }
+    if (l + 1 < n_layers) grow(ws->hidden, round_up((size_t)n_heads * (size_t)B * R.out * sizeof(float), 256));
   }
   return KAN_OK;
 }
@@ -268,35 +334,41 @@ kan_status kan_bspline_basis(const float* x, int64_t n, uint8_t* span, float* w,
 size_t kan_vq_workspace_bytes(const kan_vq_layer* layers, int32_t n_layers, int32_t n_heads, int64_t B,
                               int32_t path) {
   std::vector<LayerPlan> plans;
-  size_t hidden = 0, partial = 0;
-  if (plan_head(layers, n_layers, n_heads, B, path, &plans, &hidden, &partial) != KAN_OK) return (size_t)-1;
+  WsLayout wl;
+  if (plan_head(layers, n_layers, n_heads, B, path, &plans, &wl) != KAN_OK) return (size_t)-1;
   if (B == 0) return 0;
-  return (n_layers > 1 ? 2 * hidden : 0) + partial;
+  return wl.total();
 }
 
 kan_status kan_vq_head_forward(const kan_vq_layer* layers, int32_t n_layers, int32_t n_heads, const float* x,
                                int64_t B, float* y, void* ws, size_t ws_bytes, int32_t path, void* stream) {
   std::vector<LayerPlan> plans;
-  size_t hidden = 0, partial = 0;
-  kan_status st = plan_head(layers, n_layers, n_heads, B, path, &plans, &hidden, &partial);
+  WsLayout wl;
+  kan_status st = plan_head(layers, n_layers, n_heads, B, path, &plans, &wl);
   if (st != KAN_OK) return st;
   if (B == 0) return KAN_OK;
   if (!x || !y) return KAN_ERR_NULL;
   if (!aligned(x, 4) || !aligned(y, 4)) return KAN_ERR_SHAPE;
-  const size_t need = (n_layers > 1 ? 2 * hidden : 0) + partial;
+  const size_t need = wl.total();
   if (need > 0 && (!ws || !aligned(ws, 256) || ws_bytes < need)) return KAN_ERR_WORKSPACE;
 
   hipStream_t s = (hipStream_t)stream;
   char* wsp = (char*)ws;
-  float* hid[2] = {(float*)wsp, (float*)(wsp + hidden)};
-  float* part = (float*)(wsp + (n_layers > 1 ? 2 * hidden : 0));
+  WsPtrs w;
+  const size_t hid2 = n_layers > 1 ? 2 * wl.hidden : 0;
+  w.hid[0] = (float*)wsp;
+  w.hid[1] = (float*)(wsp + wl.hidden);
+  w.partial = (float*)(wsp + hid2);
+  w.cf = (uint4*)(wsp + hid2 + wl.partial);
+  w.bp = (float*)(wsp + hid2 + wl.partial + wl.cf);
+  w.u = (uint32_t*)(wsp + hid2 + wl.partial + wl.cf + wl.bp);
 
   for (int l = 0; l < n_layers; ++l) {
     const kan_vq_layer& R = layers[l];
     const bool last = (l + 1 == n_layers);
-    const float* src = (l == 0) ? x : hid[(l - 1) & 1];
+    const float* src = (l == 0) ? x : w.hid[(l - 1) & 1];
     const long long src_head_stride = (l == 0) ? 0 : (long long)B * R.in;
-    float* dst = last ? y : hid[l & 1];
+    float* dst = last ? y : w.hid[l & 1];
     const long long dst_head_stride = (long long)B * R.out;
     for (int h0 = 0; h0 < n_heads; h0 += kMaxGroup) {
       const int heads = (n_heads - h0) < kMaxGroup ? (n_heads - h0) : kMaxGroup;
@@ -317,7 +389,7 @@ kan_status kan_vq_head_forward(const kan_vq_layer* layers, int32_t n_layers, int
         a.h[h].cb = L.codebook;
         a.h[h].scale = L.scale;
       }
-      st = run_layer_group(plans[l], a, heads, dst + (long long)h0 * dst_head_stride, dst_head_stride, part,
+      st = run_layer_group(plans[l], a, heads, l == 0, dst + (long long)h0 * dst_head_stride, dst_head_stride, w,
                            last ? 0 : 1, s);
       if (st != KAN_OK) return st;
     }
@@ -358,7 +430,10 @@ kan_status kan_dense_layer_forward(const float* coef, int32_t in, int32_t out, i
   a.n_jt = p.n_jt;
   a.h[0].cb = coef;
   a.h[0].scale = 1.0f;
-  return run_layer_group(p, a, 1, y, (long long)B * out, (float*)ws, 0, (hipStream_t)stream);
+  WsPtrs w;
+  memset(&w, 0, sizeof(w));
+  w.partial = (float*)ws;
+  return run_layer_group(p, a, 1, true, y, (long long)B * out, w, 0, (hipStream_t)stream);
 }
 
 kan_status kan_vq_debug_gather(const kan_vq_layer* L, uint32_t* ids, float* rows, void* stream) {

@@ -49,8 +49,38 @@ hipError_t launch_gather_bt1(const GatherCfg&, const GatherArgs&, dim3 grid, hip
 hipError_t launch_gather_bt4(const GatherCfg&, const GatherArgs&, dim3 grid, hipStream_t);
 hipError_t launch_gather_bt16(const GatherCfg&, const GatherArgs&, dim3 grid, hipStream_t);
 
-// ---- matrix-core path (bf16 tiles in LDS, fp32 accumulate); same argument block ----
-hipError_t launch_mfma(const GatherCfg&, const GatherArgs&, dim3 grid, hipStream_t);
+// ---- matrix-core path (fp16 operands, fp32 accumulate) ----------------------------
+constexpr int kMfmaPrepRows = 32;   // input rows per partial bias sum (and per prep workgroup)
+
+struct PrepCoefArgs {
+  uint4* cf;                   // coefficient fragments, [head][step][5][n_out][2] records of 16 bytes
+  long long cf_head_stride;    // in records
+  float* bias_partial;         // [head][ceil(n_in / 32)][n_out]
+  long long bp_head_stride;    // in floats
+  int n_in, n_out;
+  LayerPtrs h[kMaxGroup];
+};
+
+struct MfmaArgs {
+  const uint4* cf;
+  long long cf_head_stride;
+  const uint32_t* U;           // packed span + local coordinate, [head or 1][n_in][B]
+  long long u_head_stride;     // 0 when all heads share the input
+  const float* bias_partial;
+  long long bp_head_stride;
+  float* dst;
+  long long dst_head_stride, dst_chunk_stride;
+  int n_in, n_out, B;
+  int rows_per_chunk;          // multiple of kMfmaPrepRows
+  int n_jt;
+  int apply_tanh;
+  float scale[kMaxGroup];      // Int8 scale per head (1 for fp32 codebooks)
+};
+
+hipError_t launch_prep_coef(const GatherCfg&, const PrepCoefArgs&, int heads, hipStream_t);
+hipError_t launch_prep_basis(const float* x, long long x_head_stride, uint32_t* U, long long u_head_stride,
+                             int n_in, int B, int heads, hipStream_t);
+hipError_t launch_mfma(const MfmaArgs&, dim3 grid, hipStream_t);
 
 // ---- reduction of i-chunk partial sums ------------------------------------------
 // dst[n] = act( sum_c partial[c * chunk_stride + n] ), n < count, for every head.

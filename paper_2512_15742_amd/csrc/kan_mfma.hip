@@ -3,19 +3,35 @@
 // The layer sum y[b][j] = sum_i sum_m B_m(x_bi) * c_ij[m] (paper section 3 with
 // the reconstructed coefficients of section 4.2) is a contraction over
 // k = (i, m), m = 0..9:
-//     Y[b][j] = sum_k Phi[b][k] * Chat[k][j] + sum_i bias_ij
-//     Phi[b][i*10+m]  = B_m(x_bi)                (4 nonzeros per 10, App. A.1 family)
-//     Chat[i*10+m][j] = gain_ij * scale * C[idx_ij][m]
-// Neither operand exists in memory.  Per step of 8 input rows a workgroup
-//   - evaluates span + weights for its 128 samples x 8 inputs (span exactly, in
-//     fp64; weights in fp32) and scatters them as bf16 into a zeroed LDS tile,
-//   - reads idx/gain/bias of its 8 x 128 edges (coalesced, read once per batch
-//     tile), gathers the codewords, dequantises, scales by gain and writes the
-//     bf16 coefficient tile to LDS (bias is kept out of the bf16 product: the
-//     bases sum to one, so it is summed in fp32 and added at the end),
-//   - contracts the two tiles with v_mfma_f32_32x32x16_bf16 (fp32 accumulate).
-// Workgroups tile (batch, outputs) as 128 x 128 and split i into chunks; chunk
-// partial sums go through the same fixed-order reduction as the gather path.
+//     Y[b][j] = scale * sum_k Phi[b][k] * Chat[k][j] + sum_i bias_ij
+//     Phi[b][(i,m)]  = B_m(x_bi)            (4 nonzeros per 10, App. A.1 family)
+//     Chat[(i,m)][j] = gain_ij * q_ij[m]    (q = Int8 codeword, or the fp32 row)
+// Both operands are fp16 (11-bit significand, same matrix-core rate as bf16, all
+// values lie in [-2, 2]); products accumulate in fp32 in v_mfma_f32_32x32x16_f16.
+// The per-layer Int8 scale and the bias sum (the bases sum to one) stay in fp32
+// and are applied to the accumulators at the end.
+//
+// Three kernels per layer:
+//   kan_prep_coef   every edge once per forward: read idx/gain/bias (coalesced),
+//                   gather the codeword from L2, dequantise with packed fp16 math,
+//                   write Chat in the exact order the MFMA B-operand lanes read
+//                   it, and write per-32-row partial bias sums.  A random 10-byte
+//                   gather costs the L1 a whole cache line, so it is done once per
+//                   edge here instead of once per edge and batch tile.
+//   kan_prep_basis  every (sample, input) once: exact span (fp64) and local
+//                   coordinate u, packed into one word and stored transposed
+//                   ([input][sample]) so that the contraction kernel reads it
+//                   coalesced.
+//   kan_mfma        128 samples x 256 outputs per workgroup, 4 waves side by side
+//                   along the outputs (wave tile 128 x 64).  Per step of 8 inputs:
+//                   the Phi tile is built in LDS (double buffered) from the packed
+//                   basis words, the Chat fragments stream from memory straight
+//                   into registers two steps ahead, 40 MFMAs per wave.
+// k order inside a step of 8 inputs (80 slots = 5 MFMA k-steps x 2 lane halves x 8):
+// k-step s < 4, half h carries coefficients 0..7 of input 4h+s; k-step 4, half h
+// carries coefficients 8, 9 of inputs 4h..4h+3.
+
+#include <type_traits>
 
 #include "kan_device.hpp"
 #include "kan_internal.hpp"
@@ -23,169 +39,315 @@
 namespace kan {
 namespace {
 
-typedef __bf16 bf16x2 __attribute__((ext_vector_type(2)));
-typedef __bf16 bf16x8 __attribute__((ext_vector_type(8)));
+typedef _Float16 h16x2 __attribute__((ext_vector_type(2)));
+typedef _Float16 h16x8 __attribute__((ext_vector_type(8)));
 typedef float f32x16 __attribute__((ext_vector_type(16)));
 
 constexpr int kThreads = 256;
-constexpr int BM = 128, BN = 128;      // workgroup tile: samples x outputs
-constexpr int IT = 8;                  // input rows per step
-constexpr int KT = IT * kG;            // 80 = 5 MFMA k-steps of 16
-constexpr int LDK = 88;                // LDS row stride in bf16 (176 B = 11 x 16 B)
+constexpr int BM = 128, BN = 256;      // workgroup tile: samples x outputs
+constexpr int IT = 8;                  // input rows per step (80 k-slots = 5 MFMA k-steps)
+constexpr int LDK = 88;                // LDS row stride in halves (176 B = 11 x 16 B)
+constexpr int MB = BM / 32;            // MFMA row blocks per wave
+constexpr int NB = 2;                  // MFMA column blocks per wave (64 outputs)
 
-__device__ __forceinline__ uint32_t pack_bf16(float a, float b) {
-  bf16x2 v = {(__bf16)a, (__bf16)b};
+__device__ __forceinline__ uint32_t pack_h2(float a, float b) {
+  h16x2 v = {(_Float16)a, (_Float16)b};
   return __builtin_bit_cast(uint32_t, v);
 }
 
+// fp16 pair (g*q[p], g*q[p+1]) from bytes p, p+1 of w, where w holds q + 128 as
+// unsigned bytes: 0x6400 | byte is the half 1024 + byte, so subtracting 1152 is
+// exact and leaves q.
+template <int P>
+__device__ __forceinline__ uint32_t dq_pair(uint32_t w, h16x2 g2) {
+  const uint32_t sel = 0x04000400u | ((uint32_t)(P + 1) << 16) | (uint32_t)P;
+  const uint32_t m = __builtin_amdgcn_perm(0x64646464u, w, sel);
+  const h16x2 off = {(_Float16)-1152.0f, (_Float16)-1152.0f};
+  const h16x2 v = (__builtin_bit_cast(h16x2, m) + off) * g2;
+  return __builtin_bit_cast(uint32_t, v);
+}
+
+// Raw codeword of one edge as loaded from the codebook.
+template <typename CbT> struct RawRow;
+template <> struct RawRow<int8_t> { uint32_t a, b, d; };
+template <> struct RawRow<float> { float c[kG]; };
+
+template <typename CbT>
+__device__ __forceinline__ void load_row(const CbT* cb, uint32_t id, RawRow<CbT>& r) {
+  if constexpr (sizeof(CbT) == 1) {
+    const uint8_t* p = (const uint8_t*)cb + (size_t)id * kG;
+    r.a = ld_u32_any(p);
+    r.b = ld_u32_any(p + 4);
+    r.d = ld_u16_any(p + 8);
+  } else {
+    const float2* p = (const float2*)(cb + (size_t)id * kG);
+#pragma unroll
+    for (int m = 0; m < kG / 2; ++m) {
+      const float2 v = p[m];
+      r.c[2 * m] = v.x;
+      r.c[2 * m + 1] = v.y;
+    }
+  }
+}
+
+// w[0..3] = fp16 pairs of g*coef 0..7, w[4] = g*coef 8, 9.
+template <typename CbT>
+__device__ __forceinline__ void dequant_row(const RawRow<CbT>& r, float g, uint32_t (&w)[5]) {
+  if constexpr (sizeof(CbT) == 1) {
+    const _Float16 gh = (_Float16)g;
+    const h16x2 g2 = {gh, gh};
+    const uint32_t a = r.a ^ 0x80808080u, b = r.b ^ 0x80808080u, d = r.d ^ 0x00008080u;
+    w[0] = dq_pair<0>(a, g2);
+    w[1] = dq_pair<2>(a, g2);
+    w[2] = dq_pair<0>(b, g2);
+    w[3] = dq_pair<2>(b, g2);
+    w[4] = dq_pair<0>(d, g2);
+  } else {
+#pragma unroll
+    for (int m = 0; m < 5; ++m) w[m] = pack_h2(g * r.c[2 * m], g * r.c[2 * m + 1]);
+  }
+}
+
+// ---- kan_prep_coef ------------------------------------------------------------------
+// Chat as uint4 records: rec[((step*5 + ks) * n_out + j) * 2 + h], step = i / 8.
+// A thread owns one output column and walks kMfmaPrepRows input rows (4 steps).
 template <typename IdxT, typename GbT, typename CbT>
-__global__ __launch_bounds__(kThreads) void kan_mfma_kernel(const GatherArgs a) {
-  __shared__ __attribute__((aligned(16))) uint16_t sA[BM * LDK];   // Phi tile   [b][k]
-  __shared__ __attribute__((aligned(16))) uint16_t sB[BN * LDK];   // Chat tile  [j][k]
-
-  const int tid = threadIdx.x;
-  const int lane = tid & 63, wave = tid >> 6;
-  const int head = blockIdx.z, chunk = blockIdx.y;
-  const int jt = blockIdx.x % a.n_jt, bt = blockIdx.x / a.n_jt;
-  const int b0 = bt * BM, j0 = jt * BN;
-  const int n_in = a.n_in, n_out = a.n_out;
-  const int i_begin = chunk * a.rows_per_chunk;
-  const int i_end = min(n_in, i_begin + a.rows_per_chunk);
-
+__global__ __launch_bounds__(kThreads) void kan_prep_coef_kernel(const PrepCoefArgs a) {
+  const int head = blockIdx.z;
+  const int j = blockIdx.x * kThreads + threadIdx.x;
+  if (j >= a.n_out) return;
   const LayerPtrs hp = a.h[head];
-  const float* xh = a.x + (long long)head * a.x_head_stride;
   const IdxT* idx = (const IdxT*)hp.idx;
   const GbT* gain = (const GbT*)hp.gain;
   const GbT* bias = (const GbT*)hp.bias;
   const CbT* cb = (const CbT*)hp.cb;
-  const float scale = sizeof(CbT) == 1 ? hp.scale : 1.0f;
-
-  // basis generation: this thread owns sample pb and inputs pi..pi+3 of every step
-  const int pb = tid >> 1, pi = (tid & 1) * 4;
-  const bool b_ok = (b0 + pb) < a.B;
-  // coefficient generation: input row ci of the step, outputs cj + 32*p, p = 0..3
-  const int ci = tid >> 5, cj = tid & 31;
-
-  const int wm = wave >> 1, wn = wave & 1;     // 2 x 2 waves, 64 x 64 each
-  f32x16 acc[2][2];
+  uint4* cf = a.cf + (long long)head * a.cf_head_stride;
+  float* bp = a.bias_partial + (long long)head * a.bp_head_stride;
+  const int n_in = a.n_in, n_out = a.n_out;
+  const int i0 = blockIdx.y * kMfmaPrepRows;
+  float bs = 0.f;
+#pragma unroll 1
+  for (int st = 0; st < kMfmaPrepRows / IT; ++st) {
+    const int ib = i0 + st * IT;
+    if (ib >= n_in) break;
+    const long long step = ib / IT;
+    uint32_t id[IT];
+    float g[IT];
 #pragma unroll
-  for (int m = 0; m < 2; ++m)
-#pragma unroll
-    for (int n = 0; n < 2; ++n)
-#pragma unroll
-      for (int r = 0; r < 16; ++r) acc[m][n][r] = 0.f;
-  float bsum[4] = {0.f, 0.f, 0.f, 0.f};
-
-  for (int s0 = i_begin; s0 < i_end; s0 += IT) {
-    __syncthreads();   // previous step's MFMA reads are done
-    // ---- Phi tile --------------------------------------------------------------------
-    {
-      uint32_t* rowp = (uint32_t*)(sA + pb * LDK + pi * kG);     // 80 B, 16-byte aligned
-      const uint4 z = make_uint4(0u, 0u, 0u, 0u);
-#pragma unroll
-      for (int q = 0; q < 5; ++q) ((uint4*)rowp)[q] = z;
-      if (b_ok) {
-        const float* xp = xh + (long long)(b0 + pb) * n_in + s0 + pi;
-#pragma unroll
-        for (int q = 0; q < 4; ++q) {
-          if (s0 + pi + q < i_end) {
-            const float xc = fminf(fmaxf(xp[q], -1.0f), 1.0f);
-            // exact span: t = (7x + 7) / 2 is exact in fp64; span = min(floor(t), 6)
-            const double t = fma((double)xc, 3.5, 3.5);
-            const int l = min((int)t, kSpans - 1);
-            const float u = (float)(t - (double)l);
-            const float u2 = u * u, u3 = u2 * u, om = 1.0f - u;
-            const float w0 = om * om * om * (1.0f / 6.0f);
-            const float w3 = u3 * (1.0f / 6.0f);
-            const float w1 = fmaf(0.5f, u3, fmaf(-1.0f, u2, 2.0f / 3.0f));
-            const float w2 = fmaf(-0.5f, u3, fmaf(0.5f, u2, fmaf(0.5f, u, 1.0f / 6.0f)));
-            const uint32_t w01 = pack_bf16(w0, w1), w23 = pack_bf16(w2, w3);
-            const bool odd = l & 1;
-            const uint32_t t0 = odd ? (w01 << 16) : w01;
-            const uint32_t t1 = odd ? ((w01 >> 16) | (w23 << 16)) : w23;
-            const uint32_t t2 = odd ? (w23 >> 16) : 0u;
-            uint32_t* d = rowp + q * 5 + (l >> 1);    // words (l>>1) .. (l>>1)+2 of this input's 5
-            d[0] = t0;
-            d[1] = t1;
-            if (odd) d[2] = t2;                       // l odd => l <= 5, word index <= 4
-          }
-        }
-      }
+    for (int r = 0; r < IT; ++r) {
+      const int i = ib + r;
+      const bool ok = i < n_in;
+      const long long e = (long long)min(i, n_in - 1) * n_out + j;
+      uint32_t idv[1];
+      float gv[1], bv[1];
+      load_idx<IdxT, 1>(idx + e, idv);
+      load_gb<GbT, 1>(gain + e, gv);
+      load_gb<GbT, 1>(bias + e, bv);
+      id[r] = idv[0];
+      g[r] = ok ? gv[0] : 0.f;          // rows past the end of a ragged last step are zero
+      bs += ok ? bv[0] : 0.f;
     }
-    // ---- coefficient tile ---------------------------------------------------------------
-    {
-      const int i = s0 + ci;
-      const bool i_ok = i < i_end;
+    RawRow<CbT> raw[IT];
 #pragma unroll
-      for (int p = 0; p < 4; ++p) {
-        const int jl = cj + 32 * p;
-        const int j = j0 + jl;
-        uint32_t w[5] = {0u, 0u, 0u, 0u, 0u};
-        if (i_ok && j < n_out) {
-          const long long e = (long long)i * n_out + j;
-          uint32_t id[1];
-          float g[1], bv[1];
-          load_idx<IdxT, 1>(idx + e, id);
-          load_gb<GbT, 1>(gain + e, g);
-          load_gb<GbT, 1>(bias + e, bv);
-          float c[kG];
-          fetch_row<CbT>(cb, id[0], g[0] * scale, c);
+    for (int r = 0; r < IT; ++r) load_row<CbT>(cb, id[r], raw[r]);
 #pragma unroll
-          for (int m = 0; m < 5; ++m) w[m] = pack_bf16(c[2 * m], c[2 * m + 1]);
-          bsum[p] += bv[0];
-        }
-        uint32_t* d = (uint32_t*)(sB + jl * LDK + ci * kG);
+    for (int h = 0; h < 2; ++h) {
+      uint32_t tail[4];
 #pragma unroll
-        for (int m = 0; m < 5; ++m) d[m] = w[m];
+      for (int s = 0; s < 4; ++s) {
+        uint32_t w[5];
+        dequant_row<CbT>(raw[4 * h + s], g[4 * h + s], w);
+        cf[((step * 5 + s) * n_out + j) * 2 + h] = make_uint4(w[0], w[1], w[2], w[3]);
+        tail[s] = w[4];
       }
-    }
-    __syncthreads();
-    // ---- contraction ------------------------------------------------------------------------
-#pragma unroll
-    for (int ks = 0; ks < KT / 16; ++ks) {
-      const int ko = ks * 16 + (lane >> 5) * 8;
-      bf16x8 fa[2], fb[2];
-#pragma unroll
-      for (int m = 0; m < 2; ++m)
-        fa[m] = __builtin_bit_cast(bf16x8, *(const uint4*)(sA + (wm * 64 + m * 32 + (lane & 31)) * LDK + ko));
-#pragma unroll
-      for (int n = 0; n < 2; ++n)
-        fb[n] = __builtin_bit_cast(bf16x8, *(const uint4*)(sB + (wn * 64 + n * 32 + (lane & 31)) * LDK + ko));
-#pragma unroll
-      for (int m = 0; m < 2; ++m)
-#pragma unroll
-        for (int n = 0; n < 2; ++n)
-          acc[m][n] = __builtin_amdgcn_mfma_f32_32x32x16_bf16(fa[m], fb[n], acc[m][n], 0, 0, 0);
+      cf[((step * 5 + 4) * n_out + j) * 2 + h] = make_uint4(tail[0], tail[1], tail[2], tail[3]);
     }
   }
+  bp[(long long)blockIdx.y * n_out + j] = bs;
+}
 
-  // ---- bias: sum the 8 per-row partial sums of every output column ---------------------------
-  __syncthreads();
-  float* sBias = (float*)sA;                 // [IT][BN]
+// ---- kan_prep_basis -----------------------------------------------------------------
+// U[i][b] = bits(u) with the low 3 mantissa bits replaced by the span (u loses 2^-21).
+__global__ __launch_bounds__(256) void kan_prep_basis_kernel(const float* __restrict__ x, long long x_head_stride,
+                                                             uint32_t* __restrict__ U, long long u_head_stride,
+                                                             int n_in, int B) {
+  __shared__ uint32_t tile[32][33];
+  const int head = blockIdx.z;
+  const float* xh = x + (long long)head * x_head_stride;
+  uint32_t* uh = U + (long long)head * u_head_stride;
+  const int tx = threadIdx.x & 31, ty = threadIdx.x >> 5;      // 32 x 8
+  const int ib = blockIdx.x * 32, bb = blockIdx.y * 32;
 #pragma unroll
-  for (int p = 0; p < 4; ++p) sBias[ci * BN + cj + 32 * p] = bsum[p];
+  for (int r = 0; r < 4; ++r) {
+    const int b = bb + ty + 8 * r, i = ib + tx;
+    uint32_t v = 0u;
+    if (b < B && i < n_in) {
+      const float xc = fminf(fmaxf(xh[(long long)b * n_in + i], -1.0f), 1.0f);
+      // exact span: t = (7x + 7) / 2 is exact in fp64; span = min(floor(t), 6)
+      const double t = fma((double)xc, 3.5, 3.5);
+      const int l = min((int)t, kSpans - 1);
+      const float u = (float)(t - (double)l);
+      v = (__float_as_uint(u) & ~7u) | (uint32_t)l;
+    }
+    tile[ty + 8 * r][tx] = v;
+  }
   __syncthreads();
+#pragma unroll
+  for (int r = 0; r < 4; ++r) {
+    const int i = ib + ty + 8 * r, b = bb + tx;
+    if (i < n_in && b < B) uh[(long long)i * B + b] = tile[tx][ty + 8 * r];
+  }
+}
 
-  // ---- epilogue: D layout of the 32x32 MFMA: lane holds column (lane & 31), rows
+// ---- kan_mfma ---------------------------------------------------------------------------
+__global__ __launch_bounds__(kThreads) void kan_mfma_kernel(const MfmaArgs a) {
+  __shared__ __attribute__((aligned(16))) uint16_t sA[2][BM * LDK];   // Phi tiles [b][k], 2 x 22.5 KB
+
+  const int tid = threadIdx.x;
+  const int lane = tid & 63, wave = tid >> 6;
+  const int ln = lane & 31, lh = lane >> 5;
+  const int head = blockIdx.z, chunk = blockIdx.y;
+  const int jt = blockIdx.x % a.n_jt, bt = blockIdx.x / a.n_jt;
+  const int b0 = bt * BM, j0 = jt * BN;
+  const int n_in = a.n_in, n_out = a.n_out, B = a.B;
+  const int i_begin = chunk * a.rows_per_chunk;
+  const int i_end = min(n_in, i_begin + a.rows_per_chunk);
+  const int n_steps = (i_end - i_begin + IT - 1) / IT;
+  const int step0 = i_begin / IT;
+  const int last_step = (n_in + IT - 1) / IT - 1;
+
+  const uint4* cf = a.cf + (long long)head * a.cf_head_stride;
+  const uint32_t* U = a.U + (long long)head * a.u_head_stride;
+
+  // Phi generation: this thread owns sample row pb and inputs 4*ph .. 4*ph+3 of every step.
+  const int pb = tid & (BM - 1), ph = tid >> 7;
+  const uint32_t* ucol = U + min(b0 + pb, B - 1);
+  // B operand: columns jc[nb]
+  int jc[NB];
+  bool j_ok[NB];
+#pragma unroll
+  for (int nb = 0; nb < NB; ++nb) {
+    const int j = j0 + wave * 64 + nb * 32 + ln;
+    j_ok[nb] = j < n_out;
+    jc[nb] = min(j, n_out - 1);
+  }
+
+  f32x16 acc[MB][NB];
+#pragma unroll
+  for (int m = 0; m < MB; ++m)
+#pragma unroll
+    for (int n = 0; n < NB; ++n)
+#pragma unroll
+      for (int r = 0; r < 16; ++r) acc[m][n][r] = 0.f;
+
+  auto load_u = [&](int k, uint32_t (&uv)[4]) {       // step index relative to the chunk
+    const int i = i_begin + k * IT + 4 * ph;
+#pragma unroll
+    for (int s = 0; s < 4; ++s) uv[s] = ucol[(long long)min(i + s, n_in - 1) * B];
+  };
+
+  auto gen_phi = [&](const uint32_t (&uv)[4], uint16_t* tile) {
+    uint16_t* rowp = tile + pb * LDK;
+#pragma unroll
+    for (int s = 0; s < 4; ++s) {
+      const int l = uv[s] & 7u;
+      const float u = __uint_as_float(uv[s] & ~7u);
+      const float u2 = u * u, u3 = u2 * u, om = 1.0f - u;
+      const float w0 = om * om * om * (1.0f / 6.0f);
+      const float w3 = u3 * (1.0f / 6.0f);
+      const float w1 = fmaf(0.5f, u3, fmaf(-1.0f, u2, 2.0f / 3.0f));
+      const float w2 = fmaf(-0.5f, u3, fmaf(0.5f, u2, fmaf(0.5f, u, 1.0f / 6.0f)));
+      const uint32_t w01 = pack_h2(w0, w1), w23 = pack_h2(w2, w3);
+      // the 4 weights sit at half-word offset l of this input's 10 slots (5 words)
+      const bool odd = l & 1;
+      const uint32_t t0 = odd ? (w01 << 16) : w01;
+      const uint32_t t1 = odd ? ((w01 >> 16) | (w23 << 16)) : w23;
+      const uint32_t t2 = odd ? (w23 >> 16) : 0u;
+      const int q = l >> 1;
+      uint4 lo;
+      lo.x = q == 0 ? t0 : 0u;
+      lo.y = q == 1 ? t0 : (q == 0 ? t1 : 0u);
+      lo.z = q == 2 ? t0 : (q == 1 ? t1 : (q == 0 ? t2 : 0u));
+      lo.w = q == 3 ? t0 : (q == 2 ? t1 : (q == 1 ? t2 : 0u));
+      const uint32_t hi = q == 3 ? t1 : (q == 2 ? t2 : 0u);
+      *(uint4*)(rowp + 16 * s + 8 * ph) = lo;                   // coefficients 0..7: k-step s, half ph
+      *(uint32_t*)(rowp + 64 + 8 * ph + 2 * s) = hi;            // coefficients 8, 9: k-step 4
+    }
+  };
+
+  auto load_b = [&](int k, uint4 (&bf)[NB][5]) {
+    const long long step = min(step0 + k, last_step);     // past the end: valid memory, never used
+#pragma unroll
+    for (int ks = 0; ks < 5; ++ks)
+#pragma unroll
+      for (int nb = 0; nb < NB; ++nb) bf[nb][ks] = cf[((step * 5 + ks) * n_out + jc[nb]) * 2 + lh];
+  };
+
+  auto mfma_step = [&](const uint16_t* tile, const uint4 (&bf)[NB][5]) {
+#pragma unroll
+    for (int ks = 0; ks < 5; ++ks) {
+      h16x8 fa[MB];
+#pragma unroll
+      for (int m = 0; m < MB; ++m)
+        fa[m] = __builtin_bit_cast(h16x8, *(const uint4*)(tile + (m * 32 + ln) * LDK + ks * 16 + lh * 8));
+#pragma unroll
+      for (int n = 0; n < NB; ++n) {
+        const h16x8 fb = __builtin_bit_cast(h16x8, bf[n][ks]);
+#pragma unroll
+        for (int m = 0; m < MB; ++m)
+          acc[m][n] = __builtin_amdgcn_mfma_f32_32x32x16_f16(fa[m], fb, acc[m][n], 0, 0, 0);
+      }
+    }
+  };
+
+  // ---- pipeline: rings indexed by compile-time slots (loop unrolled by 6 = lcm(3, 2)) -------
+  // Top of step k: Phi tile k and fragments k are ready, fragments k+1 and basis words k+1
+  // are in flight.  Step k issues fragments k+2 and basis words k+2.
+  uint4 bfr[3][NB][5];
+  uint32_t uv[2][4];
+  load_u(0, uv[0]);
+  load_b(0, bfr[0]);
+  load_u(1, uv[1]);
+  load_b(1, bfr[1]);
+  gen_phi(uv[0], sA[0]);
+
+  auto step = [&](auto T, int k) {
+    constexpr int t = decltype(T)::value;          // k mod 6
+    __syncthreads();     // tile k is complete; every wave is done reading tile k-1
+    load_b(k + 2, bfr[(t + 2) % 3]);
+    mfma_step(sA[t & 1], bfr[t % 3]);
+    gen_phi(uv[(t + 1) & 1], sA[(t + 1) & 1]);     // step k+1 basis tile
+    load_u(k + 2, uv[t & 1]);
+  };
+  for (int k = 0; k < n_steps; k += 6) {
+    step(std::integral_constant<int, 0>{}, k);
+    if (k + 1 < n_steps) step(std::integral_constant<int, 1>{}, k + 1);
+    if (k + 2 < n_steps) step(std::integral_constant<int, 2>{}, k + 2);
+    if (k + 3 < n_steps) step(std::integral_constant<int, 3>{}, k + 3);
+    if (k + 4 < n_steps) step(std::integral_constant<int, 4>{}, k + 4);
+    if (k + 5 < n_steps) step(std::integral_constant<int, 5>{}, k + 5);
+  }
+
+  // ---- epilogue.  D layout of the 32x32 MFMA: lane holds column (lane & 31), rows
   //      8*(r/4) + 4*(lane/32) + r%4 for r = 0..15 -------------------------------------------
+  const float* bp = a.bias_partial + (long long)head * a.bp_head_stride;
+  const int rb0 = i_begin / kMfmaPrepRows, rb1 = (i_end + kMfmaPrepRows - 1) / kMfmaPrepRows;
+  const float scale = a.scale[head];
   float* dst = a.dst + (long long)head * a.dst_head_stride + (long long)chunk * a.dst_chunk_stride;
 #pragma unroll
-  for (int n = 0; n < 2; ++n) {
-    const int jl = wn * 64 + n * 32 + (lane & 31);
-    const int j = j0 + jl;
+  for (int n = 0; n < NB; ++n) {
     float bs = 0.f;
+    for (int rb = rb0; rb < rb1; ++rb) bs += bp[(long long)rb * n_out + jc[n]];
+    if (j_ok[n]) {
 #pragma unroll
-    for (int r = 0; r < IT; ++r) bs += sBias[r * BN + jl];
-    if (j < n_out) {
-#pragma unroll
-      for (int m = 0; m < 2; ++m)
+      for (int m = 0; m < MB; ++m)
 #pragma unroll
         for (int r = 0; r < 16; ++r) {
-          const int b = b0 + wm * 64 + m * 32 + 8 * (r >> 2) + 4 * (lane >> 5) + (r & 3);
-          if (b < a.B) {
-            float v = acc[m][n][r] + bs;
+          const int b = b0 + m * 32 + 8 * (r >> 2) + 4 * lh + (r & 3);
+          if (b < B) {
+            float v = fmaf(scale, acc[m][n][r], bs);
             if (a.apply_tanh) v = tanhf(v);
-            dst[(long long)b * n_out + j] = v;
+            dst[(long long)b * n_out + jc[n]] = v;
           }
         }
     }
@@ -193,26 +355,39 @@ __global__ __launch_bounds__(kThreads) void kan_mfma_kernel(const GatherArgs a) 
 }
 
 template <typename IdxT>
-hipError_t launch_types(const GatherCfg& c, const GatherArgs& a, dim3 grid, hipStream_t s) {
+hipError_t prep_types(const GatherCfg& c, const PrepCoefArgs& a, dim3 grid, hipStream_t s) {
   if (c.code == kCbI8) {
     if (c.gb_f16)
-      hipLaunchKernelGGL((kan_mfma_kernel<IdxT, __half, int8_t>), grid, dim3(kThreads), 0, s, a);
+      hipLaunchKernelGGL((kan_prep_coef_kernel<IdxT, __half, int8_t>), grid, dim3(kThreads), 0, s, a);
     else
-      hipLaunchKernelGGL((kan_mfma_kernel<IdxT, float, int8_t>), grid, dim3(kThreads), 0, s, a);
+      hipLaunchKernelGGL((kan_prep_coef_kernel<IdxT, float, int8_t>), grid, dim3(kThreads), 0, s, a);
   } else {
     if (c.gb_f16)
-      hipLaunchKernelGGL((kan_mfma_kernel<IdxT, __half, float>), grid, dim3(kThreads), 0, s, a);
+      hipLaunchKernelGGL((kan_prep_coef_kernel<IdxT, __half, float>), grid, dim3(kThreads), 0, s, a);
     else
-      hipLaunchKernelGGL((kan_mfma_kernel<IdxT, float, float>), grid, dim3(kThreads), 0, s, a);
+      hipLaunchKernelGGL((kan_prep_coef_kernel<IdxT, float, float>), grid, dim3(kThreads), 0, s, a);
   }
   return hipGetLastError();
 }
 
 }  // namespace
 
-hipError_t launch_mfma(const GatherCfg& c, const GatherArgs& a, dim3 grid, hipStream_t s) {
+hipError_t launch_prep_coef(const GatherCfg& c, const PrepCoefArgs& a, int heads, hipStream_t s) {
   if (c.code == kDense) return hipErrorInvalidValue;
-  return c.idx_u32 ? launch_types<uint32_t>(c, a, grid, s) : launch_types<uint16_t>(c, a, grid, s);
+  dim3 grid((a.n_out + kThreads - 1) / kThreads, (a.n_in + kMfmaPrepRows - 1) / kMfmaPrepRows, heads);
+  return c.idx_u32 ? prep_types<uint32_t>(c, a, grid, s) : prep_types<uint16_t>(c, a, grid, s);
+}
+
+hipError_t launch_prep_basis(const float* x, long long x_head_stride, uint32_t* U, long long u_head_stride,
+                             int n_in, int B, int heads, hipStream_t s) {
+  dim3 grid((n_in + 31) / 32, (B + 31) / 32, heads);
+  hipLaunchKernelGGL(kan_prep_basis_kernel, grid, dim3(256), 0, s, x, x_head_stride, U, u_head_stride, n_in, B);
+  return hipGetLastError();
+}
+
+hipError_t launch_mfma(const MfmaArgs& a, dim3 grid, hipStream_t s) {
+  hipLaunchKernelGGL(kan_mfma_kernel, grid, dim3(kThreads), 0, s, a);
+  return hipGetLastError();
 }
 
 }  // namespace kan

@@ -8,19 +8,46 @@
 namespace kan {
 namespace {
 
+// dst[n] = act(sum_c partial[c][n]).  A workgroup covers 256 / CG consecutive
+// outputs; CG threads share one output, each summing every CG-th chunk with
+// four independent loads in flight, and their CG sums are added in fixed order
+// through LDS, so the result does not depend on scheduling.
+template <int CG>
 __global__ __launch_bounds__(256) void kan_reduce_kernel(const float* __restrict__ partial,
                                                          long long head_stride, long long chunk_stride,
                                                          int n_chunks, float* __restrict__ dst,
                                                          long long dst_head_stride, long long count,
                                                          int apply_tanh) {
+  constexpr int NPB = 256 / CG;     // outputs per workgroup
+  __shared__ float red[CG][NPB];
   const int head = blockIdx.y;
   const float* p = partial + (long long)head * head_stride;
   float* d = dst + (long long)head * dst_head_stride;
-  for (long long n = (long long)blockIdx.x * blockDim.x + threadIdx.x; n < count;
-       n += (long long)gridDim.x * blockDim.x) {
-    float s = 0.f;
-    for (int c = 0; c < n_chunks; ++c) s += __builtin_nontemporal_load(p + (long long)c * chunk_stride + n);
-    d[n] = apply_tanh ? tanhf(s) : s;
+  const int nn = threadIdx.x % NPB, cg = threadIdx.x / NPB;
+  for (long long n0 = (long long)blockIdx.x * NPB; n0 < count; n0 += (long long)gridDim.x * NPB) {
+    const long long n = n0 + nn;
+    float s0 = 0.f, s1 = 0.f, s2 = 0.f, s3 = 0.f;
+    if (n < count) {
+      int c = cg;
+      for (; c + 3 * CG < n_chunks; c += 4 * CG) {
+        s0 += __builtin_nontemporal_load(p + (long long)c * chunk_stride + n);
+        s1 += __builtin_nontemporal_load(p + (long long)(c + CG) * chunk_stride + n);
+        s2 += __builtin_nontemporal_load(p + (long long)(c + 2 * CG) * chunk_stride + n);
+        s3 += __builtin_nontemporal_load(p + (long long)(c + 3 * CG) * chunk_stride + n);
+      }
+      for (; c < n_chunks; c += CG) s0 += __builtin_nontemporal_load(p + (long long)c * chunk_stride + n);
+    }
+    float s = (s0 + s1) + (s2 + s3);
+    if constexpr (CG > 1) {
+      red[cg][nn] = s;
+      __syncthreads();
+      if (cg == 0) {
+#pragma unroll
+        for (int g = 1; g < CG; ++g) s += red[g][nn];
+      }
+      __syncthreads();
+    }
+    if (cg == 0 && n < count) d[n] = apply_tanh ? tanhf(s) : s;
   }
 }
 
@@ -77,9 +104,22 @@ inline int blocks_for(long long n, int cap = 65536) {
 hipError_t launch_reduce(const float* partial, long long head_stride, long long chunk_stride, int n_chunks,
                          float* dst, long long dst_head_stride, long long count, int n_heads,
                          int apply_tanh, hipStream_t s) {
-  dim3 grid(blocks_for(count, 4096), n_heads);
-  hipLaunchKernelGGL(kan_reduce_kernel, grid, dim3(256), 0, s, partial, head_stride, chunk_stride,
-                     n_chunks, dst, dst_head_stride, count, apply_tanh);
+  // few outputs and many chunks: spread the chunks of one output over several threads
+  const long long total = count * n_heads;
+  const int cg = (n_chunks >= 32 && total <= (1 << 16)) ? 16 : ((n_chunks >= 8 && total <= (1 << 20)) ? 4 : 1);
+  const int npb = 256 / cg;
+  long long blocks = (count + npb - 1) / npb;
+  if (blocks > 8192) blocks = 8192;
+  dim3 grid((unsigned)blocks, n_heads);
+  if (cg == 16)
+    hipLaunchKernelGGL(kan_reduce_kernel<16>, grid, dim3(256), 0, s, partial, head_stride, chunk_stride,
+                       n_chunks, dst, dst_head_stride, count, apply_tanh);
+  else if (cg == 4)
+    hipLaunchKernelGGL(kan_reduce_kernel<4>, grid, dim3(256), 0, s, partial, head_stride, chunk_stride,
+                       n_chunks, dst, dst_head_stride, count, apply_tanh);
+  else
+    hipLaunchKernelGGL(kan_reduce_kernel<1>, grid, dim3(256), 0, s, partial, head_stride, chunk_stride,
+                       n_chunks, dst, dst_head_stride, count, apply_tanh);
   return hipGetLastError();
 }
 
