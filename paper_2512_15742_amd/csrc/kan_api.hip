@@ -74,21 +74,8 @@ struct LayerPlan {
 constexpr int kTargetWorkgroups = 1024;   // ~4 workgroups of 4 waves per CU
 constexpr int kMinRowsPerWave = 4;
 
-LayerPlan plan_gather(int n_in, int n_out, int64_t B, int n_heads, int idx_u32, int gb_f16, int code,
-                      bool vec_ok) {
-  LayerPlan p;
-  p.mfma = false;
-  p.cfg.idx_u32 = idx_u32;
-  p.cfg.gb_f16 = gb_f16;
-  p.cfg.code = code;
-  p.cfg.bt = B <= 1 ? 1 : (B <= 4 ? 4 : 16);
-  p.name = p.cfg.bt == 1 ? "kan_gather_bt1" : (p.cfg.bt == 4 ? "kan_gather_bt4" : "kan_gather_bt16");
-  const int jpl_max = p.cfg.bt == 16 ? 4 : 8;
-  int jpl = 1;
-  if (vec_ok) {
-    for (int c = jpl_max; c > 1; c >>= 1)
-      if (n_out % c == 0 && n_out / c >= 64) { jpl = c; break; }
-  }
+// Geometry for one choice of outputs-per-lane.
+void gather_geometry(LayerPlan& p, int n_in, int n_out, int64_t B, int n_heads, int jpl) {
   p.cfg.jpl = jpl;
   const int lanes_j = (n_out + jpl - 1) / jpl;
   p.cfg.wj = lanes_j > 128 ? 4 : (lanes_j > 64 ? 2 : 1);
@@ -104,15 +91,39 @@ LayerPlan plan_gather(int n_in, int n_out, int64_t B, int n_heads, int idx_u32, 
   rows = (rows + wi - 1) / wi * wi;
   p.rows_per_chunk = rows;
   p.n_chunks = (n_in + rows - 1) / rows;
+}
+
+LayerPlan plan_gather(int n_in, int n_out, int64_t B, int n_heads, int idx_u32, int gb_f16, int code,
+                      bool vec_ok) {
+  LayerPlan p;
+  p.mfma = false;
+  p.cfg.idx_u32 = idx_u32;
+  p.cfg.gb_f16 = gb_f16;
+  p.cfg.code = code;
+  p.cfg.bt = B <= 1 ? 1 : (B <= 4 ? 4 : 16);
+  p.name = p.cfg.bt == 1 ? "kan_gather_bt1" : (p.cfg.bt == 4 ? "kan_gather_bt4" : "kan_gather_bt16");
+  const int jpl_max = p.cfg.bt == 16 ? 4 : 8;
+  // Widest per-lane vector that divides the row and still leaves every CU a workgroup;
+  // narrow layers trade vector width for more workgroups.
+  int best = 1;
+  long long best_wgs = -1;
+  for (int c = vec_ok ? jpl_max : 1; c >= 1; c >>= 1) {
+    if (n_out % c != 0 || (c > 1 && n_out / c < 64)) continue;
+    gather_geometry(p, n_in, n_out, B, n_heads, c);
+    const long long wgs = (long long)n_heads * p.n_jt * p.n_bt * p.n_chunks;
+    if (wgs >= 256) { best = c; break; }
+    if (wgs > best_wgs) { best = c; best_wgs = wgs; }
+  }
+  gather_geometry(p, n_in, n_out, B, n_heads, best);
   return p;
 }
 
-// Matrix-core path: 128 x 256 (samples x outputs) tiles, i split so that every
-// CU has work.
-constexpr int kMfmaTileM = 128;
+// Matrix-core path: 64 x 256 (samples x outputs) tiles, i split so that every CU
+// has two workgroups.
+constexpr int kMfmaTileM = 64;
 constexpr int kMfmaTileN = 256;
 constexpr int kMfmaRowsStep = kMfmaPrepRows;   // chunk boundaries coincide with partial bias sums
-constexpr int kMfmaTargetWorkgroups = 256;
+constexpr int kMfmaTargetWorkgroups = 512;
 constexpr int kMfmaMinRows = 64;
 constexpr int64_t kAutoMfmaBatch = 64;    // KAN_PATH_AUTO switches to the matrix cores from here
 
@@ -167,7 +178,7 @@ struct WsLayout {
   size_t partial = 0;   // i-chunk partial sums
   size_t cf = 0;        // matrix-core path: fp16 coefficient fragments
   size_t bp = 0;        // matrix-core path: partial bias sums
-  size_t u = 0;         // matrix-core path: packed span + local coordinate
+  size_t u = 0;         // matrix-core path: packed basis weights + span
   int n_layers = 1;
   size_t total() const { return (n_layers > 1 ? 2 * hidden : 0) + partial + cf + bp + u; }
 };
@@ -190,7 +201,7 @@ struct WsPtrs {
   float* partial;
   uint4* cf;
   float* bp;
-  uint32_t* u;
+  uint2* u;
 };
 
 // One layer of a group of heads.  `a` carries x, shapes and the per-head pointers;
@@ -226,8 +237,8 @@ kan_status run_layer_group(const LayerPlan& p, GatherArgs& a, int heads, bool x_
     memset(&m, 0, sizeof(m));
     m.cf = w.cf;
     m.cf_head_stride = pc.cf_head_stride;
-    m.U = w.u;
-    m.u_head_stride = u_stride;
+    m.W = w.u;
+    m.w_head_stride = u_stride;
     m.bias_partial = w.bp;
     m.bp_head_stride = pc.bp_head_stride;
     m.dst = dst;
@@ -295,7 +306,7 @@ kan_status plan_head(const kan_vq_layer* layers, int32_t n_layers, int32_t n_hea
     if (p.mfma) {
       grow(ws->cf, round_up((size_t)group * mfma_cf_records(R.in, R.out) * sizeof(uint4), 256));
       grow(ws->bp, round_up((size_t)group * mfma_bp_floats(R.in, R.out) * sizeof(float), 256));
-      grow(ws->u, round_up((size_t)(l == 0 ? 1 : group) * (size_t)R.in * (size_t)B * sizeof(uint32_t), 256));
+      grow(ws->u, round_up((size_t)(l == 0 ? 1 : group) * (size_t)R.in * (size_t)B * sizeof(uint2), 256));
     }
     if (l + 1 < n_layers) grow(ws->hidden, round_up((size_t)n_heads * (size_t)B * R.out * sizeof(float), 256));
   }
@@ -361,7 +372,7 @@ kan_status kan_vq_head_forward(const kan_vq_layer* layers, int32_t n_layers, int
   w.partial = (float*)(wsp + hid2);
   w.cf = (uint4*)(wsp + hid2 + wl.partial);
   w.bp = (float*)(wsp + hid2 + wl.partial + wl.cf);
-  w.u = (uint32_t*)(wsp + hid2 + wl.partial + wl.cf + wl.bp);
+  w.u = (uint2*)(wsp + hid2 + wl.partial + wl.cf + wl.bp);
 
   for (int l = 0; l < n_layers; ++l) {
     const kan_vq_layer& R = layers[l];

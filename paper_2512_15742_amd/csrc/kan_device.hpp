@@ -140,21 +140,32 @@ __device__ __forceinline__ void fetch_row(const CbT* cb, uint32_t id, float mul,
 }
 
 // Window of four: c[r] = mul * C[id][span + r], r = 0..3 (batch-1 path: only the
-// four coefficients under the nonzero bases are fetched).
+// four coefficients under the nonzero bases are fetched).  Load and dequantisation
+// are separate so that many gathers can be issued before the first one is used.
+template <typename CbT> struct WindowRaw;
+template <> struct WindowRaw<int8_t> { typedef uint32_t type; };
+template <> struct WindowRaw<float> { typedef float4 type; };
+
 template <typename CbT>
-__device__ __forceinline__ void fetch_window(const CbT* cb, uint32_t id, int span, float mul,
-                                             float (&c)[4]) {
+__device__ __forceinline__ typename WindowRaw<CbT>::type load_window(const CbT* cb, uint32_t id, int span) {
   if constexpr (sizeof(CbT) == 1) {
-    const uint8_t* p = (const uint8_t*)cb + (size_t)id * kG + span;
-    dequant4(ld_u32_any(p), mul, -128.0f * mul, c);
+    return ld_u32_any((const uint8_t*)cb + (size_t)id * kG + span);
   } else {
-    const float* p = cb + (size_t)id * kG + span;
     float4 v;
-    __builtin_memcpy(&v, p, 16);
-    c[0] = mul * v.x;
-    c[1] = mul * v.y;
-    c[2] = mul * v.z;
-    c[3] = mul * v.w;
+    __builtin_memcpy(&v, cb + (size_t)id * kG + span, 16);
+    return v;
+  }
+}
+
+template <typename CbT>
+__device__ __forceinline__ void dequant_window(typename WindowRaw<CbT>::type raw, float mul, float (&c)[4]) {
+  if constexpr (sizeof(CbT) == 1) {
+    dequant4(raw, mul, -128.0f * mul, c);
+  } else {
+    c[0] = mul * raw.x;
+    c[1] = mul * raw.y;
+    c[2] = mul * raw.z;
+    c[3] = mul * raw.w;
   }
 }
 

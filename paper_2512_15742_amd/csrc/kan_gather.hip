@@ -107,31 +107,56 @@ __global__ __launch_bounds__(kThreads) void kan_gather_kernel(const GatherArgs a
     }
     __syncthreads();
 
-    if (j_ok) {
+    if constexpr (kWindow) {
+      // one sample: only the 4 coefficients under the nonzero bases are fetched.  Rows are
+      // taken four at a time so that all metadata loads, then all gathers, are in flight
+      // together (rows past the end are clamped and contribute nothing).
+      constexpr int R = 4;
+      if (j_ok) {
+        for (int r0 = wi; r0 < rows; r0 += wi_count * R) {
+          uint32_t id[R][JPL];
+          float g[R][JPL], bv[R][JPL];
+#pragma unroll
+          for (int q = 0; q < R; ++q) {
+            const int r = min(r0 + q * wi_count, rows - 1);
+            const long long e = (long long)(s0 + r) * n_out + j0;
+            load_idx<IdxT, JPL>(idx + e, id[q]);
+            load_gb<GbT, JPL>(gain + e, g[q]);
+            load_gb<GbT, JPL>(bias + e, bv[q]);
+          }
+          typename WindowRaw<CbT>::type raw[R][JPL];
+          int sp[R];
+          float4 w[R];
+#pragma unroll
+          for (int q = 0; q < R; ++q) {
+            const int r = min(r0 + q * wi_count, rows - 1);
+            sp[q] = ss[r];
+            w[q] = sw[r];
+#pragma unroll
+            for (int p = 0; p < JPL; ++p) raw[q][p] = load_window<CbT>(cb, id[q][p], sp[q]);
+          }
+#pragma unroll
+          for (int q = 0; q < R; ++q) {
+            const float live = (r0 + q * wi_count < rows) ? 1.0f : 0.0f;
+#pragma unroll
+            for (int p = 0; p < JPL; ++p) {
+              float c[4];
+              dequant_window<CbT>(raw[q][p], live * g[q][p] * scale, c);
+              float v = acc[0][p];
+              v = fmaf(w[q].x, c[0], v);
+              v = fmaf(w[q].y, c[1], v);
+              v = fmaf(w[q].z, c[2], v);
+              v = fmaf(w[q].w, c[3], v);
+              acc[0][p] = v;
+              bsum[p] = fmaf(live, bv[q][p], bsum[p]);
+            }
+          }
+        }
+      }
+    } else if (j_ok) {
       for (int r = wi; r < rows; r += wi_count) {
         const long long e = (long long)(s0 + r) * n_out + j0;
-        if constexpr (kWindow) {
-          // one sample: fetch only the 4 coefficients under the nonzero bases
-          uint32_t id[JPL];
-          float g[JPL], bv[JPL];
-          load_idx<IdxT, JPL>(idx + e, id);
-          load_gb<GbT, JPL>(gain + e, g);
-          load_gb<GbT, JPL>(bias + e, bv);
-          const float4 w = sw[r];
-          const int sp = ss[r];
-#pragma unroll
-          for (int p = 0; p < JPL; ++p) {
-            float c[4];
-            fetch_window<CbT>(cb, id[p], sp, g[p] * scale, c);
-            float v = acc[0][p];
-            v = fmaf(w.x, c[0], v);
-            v = fmaf(w.y, c[1], v);
-            v = fmaf(w.z, c[2], v);
-            v = fmaf(w.w, c[3], v);
-            acc[0][p] = v;
-            bsum[p] += bv[p];
-          }
-        } else {
+        {
           float c[JPL][kG];
           if constexpr (CODE == kDense) {
             typedef float f32x2 __attribute__((ext_vector_type(2)));

@@ -53,7 +53,7 @@ hipError_t launch_gather_bt16(const GatherCfg&, const GatherArgs&, dim3 grid, hi
 constexpr int kMfmaPrepRows = 32;   // input rows per partial bias sum (and per prep workgroup)
 
 struct PrepCoefArgs {
-  uint4* cf;                   // coefficient fragments, [head][step][5][n_out][2] records of 16 bytes
+  uint4* cf;                   // coefficient fragments, [head][step][5][2][n_out] records of 16 bytes
   long long cf_head_stride;    // in records
   float* bias_partial;         // [head][ceil(n_in / 32)][n_out]
   long long bp_head_stride;    // in floats
@@ -64,8 +64,8 @@ struct PrepCoefArgs {
 struct MfmaArgs {
   const uint4* cf;
   long long cf_head_stride;
-  const uint32_t* U;           // packed span + local coordinate, [head or 1][n_in][B]
-  long long u_head_stride;     // 0 when all heads share the input
+  const uint2* W;              // packed basis weights + span, [head or 1][n_in][B]
+  long long w_head_stride;     // 0 when all heads share the input
   const float* bias_partial;
   long long bp_head_stride;
   float* dst;
@@ -78,7 +78,7 @@ struct MfmaArgs {
 };
 
 hipError_t launch_prep_coef(const GatherCfg&, const PrepCoefArgs&, int heads, hipStream_t);
-hipError_t launch_prep_basis(const float* x, long long x_head_stride, uint32_t* U, long long u_head_stride,
+hipError_t launch_prep_basis(const float* x, long long x_head_stride, uint2* W, long long w_head_stride,
                              int n_in, int B, int heads, hipStream_t);
 hipError_t launch_mfma(const MfmaArgs&, dim3 grid, hipStream_t);
 

@@ -18,15 +18,20 @@
 //                   it, and write per-32-row partial bias sums.  A random 10-byte
 //                   gather costs the L1 a whole cache line, so it is done once per
 //                   edge here instead of once per edge and batch tile.
-//   kan_prep_basis  every (sample, input) once: exact span (fp64) and local
-//                   coordinate u, packed into one word and stored transposed
+//   kan_prep_basis  every (sample, input) once: exact span (fp64) and the four
+//                   basis weights as fp16, the span hidden in three of their
+//                   (always clear) sign bits; 8 bytes per pair, stored transposed
 //                   ([input][sample]) so that the contraction kernel reads it
 //                   coalesced.
-//   kan_mfma        128 samples x 256 outputs per workgroup, 4 waves side by side
-//                   along the outputs (wave tile 128 x 64).  Per step of 8 inputs:
+//   kan_mfma        64 samples x 256 outputs per workgroup, 4 waves side by side
+//                   along the outputs (wave tile 64 x 64); two workgroups share a
+//                   CU and drift apart, so one's MFMAs overlap the other's tile
+//                   generation and LDS latency.  Per step of 8 inputs:
 //                   the Phi tile is built in LDS (double buffered) from the packed
-//                   basis words, the Chat fragments stream from memory straight
-//                   into registers two steps ahead, 40 MFMAs per wave.
+//                   basis words with byte permutes whose selectors come from a
+//                   7-entry table (one row per span), the Chat fragments stream
+//                   from memory straight into registers one step ahead, 20
+//                   MFMAs per wave.
 // k order inside a step of 8 inputs (80 slots = 5 MFMA k-steps x 2 lane halves x 8):
 // k-step s < 4, half h carries coefficients 0..7 of input 4h+s; k-step 4, half h
 // carries coefficients 8, 9 of inputs 4h..4h+3.
@@ -43,11 +48,12 @@ typedef _Float16 h16x2 __attribute__((ext_vector_type(2)));
 typedef _Float16 h16x8 __attribute__((ext_vector_type(8)));
 typedef float f32x16 __attribute__((ext_vector_type(16)));
 
-constexpr int kThreads = 256;
-constexpr int BM = 128, BN = 256;      // workgroup tile: samples x outputs
+constexpr int kThreads = 256;          // preparation kernels
+constexpr int kMfmaThreads = 256;      // contraction kernel: 4 waves along the outputs
+constexpr int BM = 64, BN = 256;       // workgroup tile: samples x outputs
 constexpr int IT = 8;                  // input rows per step (80 k-slots = 5 MFMA k-steps)
 constexpr int LDK = 88;                // LDS row stride in halves (176 B = 11 x 16 B)
-constexpr int MB = BM / 32;            // MFMA row blocks per wave
+constexpr int MB = 2;                  // MFMA row blocks per wave (64 samples)
 constexpr int NB = 2;                  // MFMA column blocks per wave (64 outputs)
 
 __device__ __forceinline__ uint32_t pack_h2(float a, float b) {
@@ -109,13 +115,17 @@ __device__ __forceinline__ void dequant_row(const RawRow<CbT>& r, float g, uint3
 }
 
 // ---- kan_prep_coef ------------------------------------------------------------------
-// Chat as uint4 records: rec[((step*5 + ks) * n_out + j) * 2 + h], step = i / 8.
-// A thread owns one output column and walks kMfmaPrepRows input rows (4 steps).
+// Chat as uint4 records: rec[((step*5 + ks) * 2 + h) * n_out + j], step = i / 8, so that
+// both the writer and the MFMA B-operand lanes touch 16-byte items contiguous in j.
+// A workgroup covers 64 output columns x 32 input rows: each of its 4 waves takes one
+// step of 8 rows (lanes along the columns), so all loads of an edge's chain
+// (metadata, then codeword) are in flight at once across many small waves.
 template <typename IdxT, typename GbT, typename CbT>
 __global__ __launch_bounds__(kThreads) void kan_prep_coef_kernel(const PrepCoefArgs a) {
+  __shared__ float sb[4][64];
   const int head = blockIdx.z;
-  const int j = blockIdx.x * kThreads + threadIdx.x;
-  if (j >= a.n_out) return;
+  const int lane = threadIdx.x & 63, wave = threadIdx.x >> 6;
+  const int j = blockIdx.x * 64 + lane;
   const LayerPtrs hp = a.h[head];
   const IdxT* idx = (const IdxT*)hp.idx;
   const GbT* gain = (const GbT*)hp.gain;
@@ -124,12 +134,9 @@ __global__ __launch_bounds__(kThreads) void kan_prep_coef_kernel(const PrepCoefA
   uint4* cf = a.cf + (long long)head * a.cf_head_stride;
   float* bp = a.bias_partial + (long long)head * a.bp_head_stride;
   const int n_in = a.n_in, n_out = a.n_out;
-  const int i0 = blockIdx.y * kMfmaPrepRows;
+  const int ib = blockIdx.y * kMfmaPrepRows + wave * IT;
   float bs = 0.f;
-#pragma unroll 1
-  for (int st = 0; st < kMfmaPrepRows / IT; ++st) {
-    const int ib = i0 + st * IT;
-    if (ib >= n_in) break;
+  if (j < n_out && ib < n_in) {
     const long long step = ib / IT;
     uint32_t id[IT];
     float g[IT];
@@ -157,37 +164,48 @@ __global__ __launch_bounds__(kThreads) void kan_prep_coef_kernel(const PrepCoefA
       for (int s = 0; s < 4; ++s) {
         uint32_t w[5];
         dequant_row<CbT>(raw[4 * h + s], g[4 * h + s], w);
-        cf[((step * 5 + s) * n_out + j) * 2 + h] = make_uint4(w[0], w[1], w[2], w[3]);
+        cf[((step * 5 + s) * 2 + h) * n_out + j] = make_uint4(w[0], w[1], w[2], w[3]);
         tail[s] = w[4];
       }
-      cf[((step * 5 + 4) * n_out + j) * 2 + h] = make_uint4(tail[0], tail[1], tail[2], tail[3]);
+      cf[((step * 5 + 4) * 2 + h) * n_out + j] = make_uint4(tail[0], tail[1], tail[2], tail[3]);
     }
   }
-  bp[(long long)blockIdx.y * n_out + j] = bs;
+  sb[wave][lane] = bs;
+  __syncthreads();
+  if (wave == 0 && j < n_out)
+    bp[(long long)blockIdx.y * n_out + j] = (sb[0][lane] + sb[1][lane]) + (sb[2][lane] + sb[3][lane]);
 }
 
 // ---- kan_prep_basis -----------------------------------------------------------------
-// U[i][b] = bits(u) with the low 3 mantissa bits replaced by the span (u loses 2^-21).
+// W[i][b] = { half2(w0, w1), half2(w2, w3) } with span bit 0, 1, 2 in the sign bits of
+// w0, w1, w2 (the weights are never negative).
 __global__ __launch_bounds__(256) void kan_prep_basis_kernel(const float* __restrict__ x, long long x_head_stride,
-                                                             uint32_t* __restrict__ U, long long u_head_stride,
+                                                             uint2* __restrict__ W, long long w_head_stride,
                                                              int n_in, int B) {
-  __shared__ uint32_t tile[32][33];
+  __shared__ uint2 tile[32][33];
   const int head = blockIdx.z;
   const float* xh = x + (long long)head * x_head_stride;
-  uint32_t* uh = U + (long long)head * u_head_stride;
+  uint2* wh = W + (long long)head * w_head_stride;
   const int tx = threadIdx.x & 31, ty = threadIdx.x >> 5;      // 32 x 8
   const int ib = blockIdx.x * 32, bb = blockIdx.y * 32;
 #pragma unroll
   for (int r = 0; r < 4; ++r) {
     const int b = bb + ty + 8 * r, i = ib + tx;
-    uint32_t v = 0u;
+    uint2 v = make_uint2(0u, 0u);
     if (b < B && i < n_in) {
       const float xc = fminf(fmaxf(xh[(long long)b * n_in + i], -1.0f), 1.0f);
-      // exact span: t = (7x + 7) / 2 is exact in fp64; span = min(floor(t), 6)
+      // exact span: t = (7x + 7) / 2 is exact in fp64; span = min(floor(t), 6); the local
+      // coordinate u = t - span is exact too and is rounded once to fp32
       const double t = fma((double)xc, 3.5, 3.5);
-      const int l = min((int)t, kSpans - 1);
+      const uint32_t l = (uint32_t)min((int)t, kSpans - 1);
       const float u = (float)(t - (double)l);
-      v = (__float_as_uint(u) & ~7u) | (uint32_t)l;
+      const float u2 = u * u, u3 = u2 * u, om = 1.0f - u;
+      const float w0 = om * om * om * (1.0f / 6.0f);
+      const float w3 = u3 * (1.0f / 6.0f);
+      const float w1 = fmaf(0.5f, u3, fmaf(-1.0f, u2, 2.0f / 3.0f));
+      const float w2 = fmaf(-0.5f, u3, fmaf(0.5f, u2, fmaf(0.5f, u, 1.0f / 6.0f)));
+      v.x = pack_h2(w0, w1) | ((l & 1u) << 15) | ((l & 2u) << 30);
+      v.y = pack_h2(w2, w3) | ((l & 4u) << 13);
     }
     tile[ty + 8 * r][tx] = v;
   }
@@ -195,17 +213,33 @@ __global__ __launch_bounds__(256) void kan_prep_basis_kernel(const float* __rest
 #pragma unroll
   for (int r = 0; r < 4; ++r) {
     const int i = ib + ty + 8 * r, b = bb + tx;
-    if (i < n_in && b < B) uh[(long long)i * B + b] = tile[tx][ty + 8 * r];
+    if (i < n_in && b < B) wh[(long long)i * B + b] = tile[tx][ty + 8 * r];
   }
 }
 
 // ---- kan_mfma ---------------------------------------------------------------------------
-__global__ __launch_bounds__(kThreads) void kan_mfma_kernel(const MfmaArgs a) {
+__global__ __launch_bounds__(kMfmaThreads, 2) void kan_mfma_kernel(const MfmaArgs a) {
   __shared__ __attribute__((aligned(16))) uint16_t sA[2][BM * LDK];   // Phi tiles [b][k], 2 x 22.5 KB
+  // Byte-permute selectors: row l, word k builds half-word slots 2k, 2k+1 of an input whose
+  // weights w0..w3 (bytes 0..7 of {w23:w01}) sit at slots l..l+3; selector byte 0x0c yields 0.
+  __shared__ __attribute__((aligned(16))) uint32_t sSel[kSpans][8];
+  if (threadIdx.x < kSpans * 8) {   // 56 entries
+    const int l = threadIdx.x >> 3, k = threadIdx.x & 7;
+    uint32_t sel = 0x0c0c0c0cu;
+    if (k < 5) {
+      const int r0 = 2 * k - l, r1 = 2 * k + 1 - l;
+      const uint32_t lo = (r0 >= 0 && r0 <= 3) ? (uint32_t)((2 * r0) | ((2 * r0 + 1) << 8)) : 0x0c0cu;
+      const uint32_t hi = (r1 >= 0 && r1 <= 3) ? (uint32_t)((2 * r1) | ((2 * r1 + 1) << 8)) : 0x0c0cu;
+      sel = lo | (hi << 16);
+    }
+    sSel[l][k] = sel;
+  }
+  __syncthreads();
 
   const int tid = threadIdx.x;
   const int lane = tid & 63, wave = tid >> 6;
   const int ln = lane & 31, lh = lane >> 5;
+  const int wm = 0, wn = wave;
   const int head = blockIdx.z, chunk = blockIdx.y;
   const int jt = blockIdx.x % a.n_jt, bt = blockIdx.x / a.n_jt;
   const int b0 = bt * BM, j0 = jt * BN;
@@ -217,17 +251,17 @@ __global__ __launch_bounds__(kThreads) void kan_mfma_kernel(const MfmaArgs a) {
   const int last_step = (n_in + IT - 1) / IT - 1;
 
   const uint4* cf = a.cf + (long long)head * a.cf_head_stride;
-  const uint32_t* U = a.U + (long long)head * a.u_head_stride;
+  const uint2* W = a.W + (long long)head * a.w_head_stride;
 
-  // Phi generation: this thread owns sample row pb and inputs 4*ph .. 4*ph+3 of every step.
-  const int pb = tid & (BM - 1), ph = tid >> 7;
-  const uint32_t* ucol = U + min(b0 + pb, B - 1);
+  // Phi generation: this thread owns sample row pb and inputs 2*ph, 2*ph+1 of every step.
+  const int pb = tid & (BM - 1), ph = tid >> 6;
+  const uint2* wcol = W + min(b0 + pb, B - 1);
   // B operand: columns jc[nb]
   int jc[NB];
   bool j_ok[NB];
 #pragma unroll
   for (int nb = 0; nb < NB; ++nb) {
-    const int j = j0 + wave * 64 + nb * 32 + ln;
+    const int j = j0 + wn * 64 + nb * 32 + ln;
     j_ok[nb] = j < n_out;
     jc[nb] = min(j, n_out - 1);
   }
@@ -240,38 +274,29 @@ __global__ __launch_bounds__(kThreads) void kan_mfma_kernel(const MfmaArgs a) {
 #pragma unroll
       for (int r = 0; r < 16; ++r) acc[m][n][r] = 0.f;
 
-  auto load_u = [&](int k, uint32_t (&uv)[4]) {       // step index relative to the chunk
-    const int i = i_begin + k * IT + 4 * ph;
+  auto load_u = [&](int k, uint2 (&uv)[2]) {       // step index relative to the chunk
+    const int i = i_begin + k * IT + 2 * ph;
 #pragma unroll
-    for (int s = 0; s < 4; ++s) uv[s] = ucol[(long long)min(i + s, n_in - 1) * B];
+    for (int q = 0; q < 2; ++q) uv[q] = wcol[(long long)min(i + q, n_in - 1) * B];
   };
 
-  auto gen_phi = [&](const uint32_t (&uv)[4], uint16_t* tile) {
+  auto gen_phi = [&](const uint2 (&uv)[2], uint16_t* tile) {
     uint16_t* rowp = tile + pb * LDK;
 #pragma unroll
-    for (int s = 0; s < 4; ++s) {
-      const int l = uv[s] & 7u;
-      const float u = __uint_as_float(uv[s] & ~7u);
-      const float u2 = u * u, u3 = u2 * u, om = 1.0f - u;
-      const float w0 = om * om * om * (1.0f / 6.0f);
-      const float w3 = u3 * (1.0f / 6.0f);
-      const float w1 = fmaf(0.5f, u3, fmaf(-1.0f, u2, 2.0f / 3.0f));
-      const float w2 = fmaf(-0.5f, u3, fmaf(0.5f, u2, fmaf(0.5f, u, 1.0f / 6.0f)));
-      const uint32_t w01 = pack_h2(w0, w1), w23 = pack_h2(w2, w3);
-      // the 4 weights sit at half-word offset l of this input's 10 slots (5 words)
-      const bool odd = l & 1;
-      const uint32_t t0 = odd ? (w01 << 16) : w01;
-      const uint32_t t1 = odd ? ((w01 >> 16) | (w23 << 16)) : w23;
-      const uint32_t t2 = odd ? (w23 >> 16) : 0u;
-      const int q = l >> 1;
+    for (int q = 0; q < 2; ++q) {
+      const int ii = 2 * ph + q, h = ii >> 2, s = ii & 3;     // input ii of the step: k-step s, lane half h
+      const uint32_t l = ((uv[q].x >> 15) & 1u) | ((uv[q].x >> 30) & 2u) | ((uv[q].y >> 13) & 4u);
+      const uint32_t w01 = uv[q].x & 0x7fff7fffu, w23 = uv[q].y & 0x7fff7fffu;
+      const uint4 sl = *(const uint4*)&sSel[l][0];
+      const uint32_t sh = sSel[l][4];
       uint4 lo;
-      lo.x = q == 0 ? t0 : 0u;
-      lo.y = q == 1 ? t0 : (q == 0 ? t1 : 0u);
-      lo.z = q == 2 ? t0 : (q == 1 ? t1 : (q == 0 ? t2 : 0u));
-      lo.w = q == 3 ? t0 : (q == 2 ? t1 : (q == 1 ? t2 : 0u));
-      const uint32_t hi = q == 3 ? t1 : (q == 2 ? t2 : 0u);
-      *(uint4*)(rowp + 16 * s + 8 * ph) = lo;                   // coefficients 0..7: k-step s, half ph
-      *(uint32_t*)(rowp + 64 + 8 * ph + 2 * s) = hi;            // coefficients 8, 9: k-step 4
+      lo.x = __builtin_amdgcn_perm(w23, w01, sl.x);
+      lo.y = __builtin_amdgcn_perm(w23, w01, sl.y);
+      lo.z = __builtin_amdgcn_perm(w23, w01, sl.z);
+      lo.w = __builtin_amdgcn_perm(w23, w01, sl.w);
+      const uint32_t hi = __builtin_amdgcn_perm(w23, w01, sh);
+      *(uint4*)(rowp + 16 * s + 8 * h) = lo;                    // coefficients 0..7
+      *(uint32_t*)(rowp + 64 + 8 * h + 2 * s) = hi;             // coefficients 8, 9: k-step 4
     }
   };
 
@@ -280,7 +305,7 @@ __global__ __launch_bounds__(kThreads) void kan_mfma_kernel(const MfmaArgs a) {
 #pragma unroll
     for (int ks = 0; ks < 5; ++ks)
 #pragma unroll
-      for (int nb = 0; nb < NB; ++nb) bf[nb][ks] = cf[((step * 5 + ks) * n_out + jc[nb]) * 2 + lh];
+      for (int nb = 0; nb < NB; ++nb) bf[nb][ks] = cf[((step * 5 + ks) * 2 + lh) * n_out + jc[nb]];
   };
 
   auto mfma_step = [&](const uint16_t* tile, const uint4 (&bf)[NB][5]) {
@@ -289,7 +314,7 @@ __global__ __launch_bounds__(kThreads) void kan_mfma_kernel(const MfmaArgs a) {
       h16x8 fa[MB];
 #pragma unroll
       for (int m = 0; m < MB; ++m)
-        fa[m] = __builtin_bit_cast(h16x8, *(const uint4*)(tile + (m * 32 + ln) * LDK + ks * 16 + lh * 8));
+        fa[m] = __builtin_bit_cast(h16x8, *(const uint4*)(tile + (wm * 64 + m * 32 + ln) * LDK + ks * 16 + lh * 8));
 #pragma unroll
       for (int n = 0; n < NB; ++n) {
         const h16x8 fb = __builtin_bit_cast(h16x8, bf[n][ks]);
@@ -300,24 +325,28 @@ __global__ __launch_bounds__(kThreads) void kan_mfma_kernel(const MfmaArgs a) {
     }
   };
 
-  // ---- pipeline: rings indexed by compile-time slots (loop unrolled by 6 = lcm(3, 2)) -------
-  // Top of step k: Phi tile k and fragments k are ready, fragments k+1 and basis words k+1
-  // are in flight.  Step k issues fragments k+2 and basis words k+2.
+  // ---- pipeline: three-slot rings indexed by compile-time slots (loop unrolled by 6) --------
+  // Top of step k: Phi tile k and fragments k are ready; fragments and basis words of
+  // steps k+1, k+2 are in flight.  Step k issues those of step k+3 into the slot step k
+  // frees, so every load has two full steps to arrive; the second workgroup on the CU
+  // covers the rest.
   uint4 bfr[3][NB][5];
-  uint32_t uv[2][4];
+  uint2 uv[3][2];
   load_u(0, uv[0]);
   load_b(0, bfr[0]);
   load_u(1, uv[1]);
   load_b(1, bfr[1]);
+  load_u(2, uv[2]);
+  load_b(2, bfr[2]);
   gen_phi(uv[0], sA[0]);
 
   auto step = [&](auto T, int k) {
     constexpr int t = decltype(T)::value;          // k mod 6
     __syncthreads();     // tile k is complete; every wave is done reading tile k-1
-    load_b(k + 2, bfr[(t + 2) % 3]);
     mfma_step(sA[t & 1], bfr[t % 3]);
-    gen_phi(uv[(t + 1) & 1], sA[(t + 1) & 1]);     // step k+1 basis tile
-    load_u(k + 2, uv[t & 1]);
+    gen_phi(uv[(t + 1) % 3], sA[(t + 1) & 1]);     // step k+1 basis tile
+    load_b(k + 3, bfr[t % 3]);                     // fragments of step k have been consumed
+    load_u(k + 3, uv[t % 3]);                      // basis words of step k were consumed a step ago
   };
   for (int k = 0; k < n_steps; k += 6) {
     step(std::integral_constant<int, 0>{}, k);
@@ -343,7 +372,7 @@ __global__ __launch_bounds__(kThreads) void kan_mfma_kernel(const MfmaArgs a) {
       for (int m = 0; m < MB; ++m)
 #pragma unroll
         for (int r = 0; r < 16; ++r) {
-          const int b = b0 + m * 32 + 8 * (r >> 2) + 4 * lh + (r & 3);
+          const int b = b0 + wm * 64 + m * 32 + 8 * (r >> 2) + 4 * lh + (r & 3);
           if (b < B) {
             float v = fmaf(scale, acc[m][n][r], bs);
             if (a.apply_tanh) v = tanhf(v);
@@ -374,19 +403,19 @@ hipError_t prep_types(const GatherCfg& c, const PrepCoefArgs& a, dim3 grid, hipS
 
 hipError_t launch_prep_coef(const GatherCfg& c, const PrepCoefArgs& a, int heads, hipStream_t s) {
   if (c.code == kDense) return hipErrorInvalidValue;
-  dim3 grid((a.n_out + kThreads - 1) / kThreads, (a.n_in + kMfmaPrepRows - 1) / kMfmaPrepRows, heads);
+  dim3 grid((a.n_out + 63) / 64, (a.n_in + kMfmaPrepRows - 1) / kMfmaPrepRows, heads);
   return c.idx_u32 ? prep_types<uint32_t>(c, a, grid, s) : prep_types<uint16_t>(c, a, grid, s);
 }
 
-hipError_t launch_prep_basis(const float* x, long long x_head_stride, uint32_t* U, long long u_head_stride,
+hipError_t launch_prep_basis(const float* x, long long x_head_stride, uint2* W, long long w_head_stride,
                              int n_in, int B, int heads, hipStream_t s) {
   dim3 grid((n_in + 31) / 32, (B + 31) / 32, heads);
-  hipLaunchKernelGGL(kan_prep_basis_kernel, grid, dim3(256), 0, s, x, x_head_stride, U, u_head_stride, n_in, B);
+  hipLaunchKernelGGL(kan_prep_basis_kernel, grid, dim3(256), 0, s, x, x_head_stride, W, w_head_stride, n_in, B);
   return hipGetLastError();
 }
 
 hipError_t launch_mfma(const MfmaArgs& a, dim3 grid, hipStream_t s) {
-  hipLaunchKernelGGL(kan_mfma_kernel, grid, dim3(kThreads), 0, s, a);
+  hipLaunchKernelGGL(kan_mfma_kernel, grid, dim3(kMfmaThreads), 0, s, a);
   return hipGetLastError();
 }
 
