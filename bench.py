@@ -38,7 +38,11 @@ MALL_BYTES = 256 << 20
 # HBM bytes per launch of the dominant kernel measured with rocprofv3 --pmc
 # (FETCH_SIZE / WRITE_SIZE runs scaled by a copy kernel of known size); see the
 # summaries under profiles/.  None until such a run exists for the workload.
-MEASURED_TRAFFIC = {}
+MEASURED_TRAFFIC = {
+    # average over the layer-1 and layer-2 launches of one step, bytes per launch
+    ("kan_mfma", 1024): int((156.77 + 32.00 + 65.09 + 16.00) / 2 * 2**20),
+    ("kan_gather_bt1", 1): int((17.20 + 1.00 + 6.58 + 0.25) / 2 * 2**20),
+}
 
 
 def parse():
@@ -50,6 +54,8 @@ def parse():
     ap.add_argument("--path", default="auto", choices=["auto", "gather", "mfma"])
     ap.add_argument("--no-cpu-baseline", action="store_true")
     ap.add_argument("--copies", type=int, default=0, help="parameter copies to rotate over (0 = enough to exceed the memory-side cache)")
+    ap.add_argument("--probe-copy", action="store_true",
+                    help="also run a 256 MiB device copy three times (known traffic: calibrates rocprofv3 FETCH_SIZE / WRITE_SIZE)")
     return ap.parse_args()
 
 
@@ -125,6 +131,13 @@ def main():
             cp.append(kb.VQLayer(p))
         copies.append(cp)
 
+    if args.probe_copy:
+        src = torch.empty(256 << 20, dtype=torch.uint8, device="cuda").fill_(1)
+        dst = torch.empty_like(src)
+        for _ in range(3):
+            dst.copy_(src)
+        torch.cuda.synchronize()
+
     results = {}
     for B in sorted({1, args.batch}):
         steps = args.steps if B > 1 else max(args.steps, 500)
@@ -132,7 +145,6 @@ def main():
         ee = sum(edges) * B
         dom = max((k for k in kt if k.startswith("kan_gather") or k.startswith("kan_mfma")),
                   key=lambda k: kt[k]["avg_us"] * kt[k]["launches"])
-        # the dominant kernel runs once per layer; split its time by layer using the per-layer work
         results[B] = {
             "batch": B, "steps": steps,
             "ms_per_step": 1e3 * t_cold, "edge_evals_per_s": ee / t_cold,

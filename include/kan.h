@@ -53,10 +53,11 @@ typedef enum kan_dtype { KAN_F32 = 0, KAN_F16 = 1, KAN_I8 = 2, KAN_U16 = 3, KAN_
 /* Which kernels carry the edge evaluation.
  *   KAN_PATH_GATHER  fp32 vector arithmetic, one codeword gather per edge and
  *                    batch tile; matches the float64 definition to ~1e-6.
- *   KAN_PATH_MFMA    coefficient tile dequantised to bf16 in LDS and contracted
- *                    against the bf16 basis tile on the matrix cores, fp32
- *                    accumulation; ~1e-3 relative (bound: 2e-2).
- *   KAN_PATH_AUTO    GATHER below a batch threshold, MFMA above it.           */
+ *   KAN_PATH_MFMA    coefficients dequantised once per call to fp16 in matrix-core
+ *                    operand order (into the workspace), basis weights as fp16
+ *                    tiles in LDS, contraction on the matrix cores with fp32
+ *                    accumulation; ~3e-4 relative per layer (bound: 2e-2).
+ *   KAN_PATH_AUTO    GATHER below batch 32, MFMA from there on (measured crossover).  */
 typedef enum kan_path { KAN_PATH_AUTO = 0, KAN_PATH_GATHER = 1, KAN_PATH_MFMA = 2 } kan_path;
 
 /* One VQ-KAN layer (Eq. (1)): host struct, device pointers. */

@@ -125,7 +125,7 @@ constexpr int kMfmaTileN = 256;
 constexpr int kMfmaRowsStep = kMfmaPrepRows;   // chunk boundaries coincide with partial bias sums
 constexpr int kMfmaTargetWorkgroups = 512;
 constexpr int kMfmaMinRows = 64;
-constexpr int64_t kAutoMfmaBatch = 64;    // KAN_PATH_AUTO switches to the matrix cores from here
+constexpr int64_t kAutoMfmaBatch = 32;    // KAN_PATH_AUTO switches to the matrix cores from here (measured crossover 16-32)
 
 LayerPlan plan_mfma(int n_in, int n_out, int64_t B, int n_heads, int idx_u32, int gb_f16, int code) {
   LayerPlan p;
