@@ -54,6 +54,8 @@ def parse():
     ap.add_argument("--path", default="auto", choices=["auto", "gather", "mfma"])
     ap.add_argument("--no-cpu-baseline", action="store_true")
     ap.add_argument("--copies", type=int, default=0, help="parameter copies to rotate over (0 = enough to exceed the memory-side cache)")
+    ap.add_argument("--sweep", action="store_true",
+                    help="instead of the headline run, time every benchmark configuration (one JSON line each)")
     ap.add_argument("--probe-copy", action="store_true",
                     help="also run a 256 MiB device copy three times (known traffic: calibrates rocprofv3 FETCH_SIZE / WRITE_SIZE)")
     return ap.parse_args()
@@ -103,6 +105,58 @@ def run_batch(kb, torch, synth, copies, B, path, steps, warmup):
     return t_cold, t_warm, kt
 
 
+def sweep(kb, torch, synth):
+    """Wall time per forward of every configuration (cache-warm, single parameter copy)."""
+    def wall(fn, reps):
+        for _ in range(3):
+            fn()
+        torch.cuda.synchronize()
+        t0 = time.perf_counter()
+        for _ in range(reps):
+            fn()
+        torch.cuda.synchronize()
+        return (time.perf_counter() - t0) / reps
+
+    def vq_rows(tag, heads_p, x, paths, reps):
+        heads = [[kb.VQLayer(p) for p in ps] for ps in heads_p]
+        xd = torch.from_numpy(x).cuda()
+        B = x.shape[0]
+        E = sum(p.edges for ps in heads_p for p in ps)
+        meta = sum(p.metadata_bytes for ps in heads_p for p in ps)
+        for name, path in paths:
+            ws = torch.empty(max(kb.kan_vq_workspace_bytes(heads, B, path), 256), dtype=torch.uint8, device="cuda")
+            y = torch.empty((len(heads), B, heads_p[0][-1].n_out), dtype=torch.float32, device="cuda")
+            t = wall(lambda: kb.kan_vq_head_forward(heads, xd, path=path, ws=ws, y=y), reps)
+            print(json.dumps({"workload": tag, "batch": B, "path": name, "us_per_forward": round(t * 1e6, 2),
+                              "edge_evals_per_s": E * B / t, "metadata_GBps": meta / t / 1e9,
+                              "kernel": kb.kan_vq_planned_kernel(heads[0][0], B, len(heads), path)}), flush=True)
+
+    both = [("gather", kb.KAN_PATH_GATHER), ("mfma", kb.KAN_PATH_MFMA)]
+    ps, x = synth.config1()
+    vq_rows("config1 64->32 K=256 fp32", [ps], x, both, 50)
+    from oracle import kan_oracle as ko     # dense twins are reconstructed with the oracle (setup, untimed)
+    for B in (1, 16, 256):
+        ps, x = synth.config2(B)
+        vq_rows("config2 2048->512 K=65536 fp32", [ps], x, both, 30)
+        coef = torch.from_numpy(ko.reconstruct_coefficients(**ps[0].as_dict()).astype("float32")).cuda()
+        xd = torch.from_numpy(x).cuda()
+        ws = torch.empty(max(kb.kan_dense_workspace_bytes(2048, 512, B), 256), dtype=torch.uint8, device="cuda")
+        y = torch.empty((B, 512), dtype=torch.float32, device="cuda")
+        t = wall(lambda: kb.kan_dense_layer_forward(coef, xd, ws=ws, y=y), 30)
+        print(json.dumps({"workload": "config2 dense twin 2048x512x10 fp32", "batch": B, "path": "dense",
+                          "us_per_forward": round(t * 1e6, 2), "edge_evals_per_s": 2048 * 512 * B / t,
+                          "coef_GBps": coef.numel() * 4 / t / 1e9}), flush=True)
+        del coef
+    for B in (1, 16, 256, 1024, 4096):
+        ps, x = synth.config3(B)
+        vq_rows("config3 Int8 head 2048->1024->256", [ps], x, both if B <= 1024 else both[1:], 30 if B <= 256 else 10)
+    heads_p, x = synth.config4(50, 64)
+    vq_rows("config4 50 Int8 heads 2048->256->21", heads_p, x, both, 10)
+    for variant in ("i8", "f32"):
+        ps, x = synth.config5(variant)
+        vq_rows("config5 4096->4096 K=262144 " + variant, [ps], x, both[1:], 3)
+
+
 def main():
     args = parse()
     if args.gpus != 1:
@@ -117,6 +171,10 @@ def main():
     assert torch.cuda.is_available(), "bench.py needs a GPU"
     kb.lib()
     path = {"auto": kb.KAN_PATH_AUTO, "gather": kb.KAN_PATH_GATHER, "mfma": kb.KAN_PATH_MFMA}[args.path]
+
+    if args.sweep:
+        sweep(kb, torch, synth)
+        return
 
     layers = synth.config3_layers()
     edges = [p.edges for p in layers]

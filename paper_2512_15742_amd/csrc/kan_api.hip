@@ -252,7 +252,7 @@ kan_status run_layer_group(const LayerPlan& p, GatherArgs& a, int heads, bool x_
     m.apply_tanh = tanh_in_kernel;
     for (int h = 0; h < heads; ++h) m.scale[h] = p.cfg.code == kCbI8 ? a.h[h].scale : 1.0f;
     dim3 grid((unsigned)(p.n_jt * p.n_bt), (unsigned)p.n_chunks, (unsigned)heads);
-    st = run(p.name, s, [&] { return launch_mfma(m, grid, s); });
+    st = run(p.name, s, [&] { return launch_mfma(m, p.cfg.bt, grid, s); });
   } else {
     a.dst = dst;
     a.dst_head_stride = dst_head_stride;

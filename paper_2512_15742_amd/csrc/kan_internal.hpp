@@ -80,7 +80,7 @@ struct MfmaArgs {
 hipError_t launch_prep_coef(const GatherCfg&, const PrepCoefArgs&, int heads, hipStream_t);
 hipError_t launch_prep_basis(const float* x, long long x_head_stride, uint2* W, long long w_head_stride,
                              int n_in, int B, int heads, hipStream_t);
-hipError_t launch_mfma(const MfmaArgs&, dim3 grid, hipStream_t);
+hipError_t launch_mfma(const MfmaArgs&, int tile_m, dim3 grid, hipStream_t);   // tile_m: samples per tile (64)
 
 // ---- reduction of i-chunk partial sums ------------------------------------------
 // dst[n] = act( sum_c partial[c * chunk_stride + n] ), n < count, for every head.

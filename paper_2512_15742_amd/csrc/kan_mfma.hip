@@ -50,10 +50,9 @@ typedef float f32x16 __attribute__((ext_vector_type(16)));
 
 constexpr int kThreads = 256;          // preparation kernels
 constexpr int kMfmaThreads = 256;      // contraction kernel: 4 waves along the outputs
-constexpr int BM = 64, BN = 256;       // workgroup tile: samples x outputs
+constexpr int BN = 256;                // outputs per workgroup tile (samples per tile: 32 * MB)
 constexpr int IT = 8;                  // input rows per step (80 k-slots = 5 MFMA k-steps)
 constexpr int LDK = 88;                // LDS row stride in halves (176 B = 11 x 16 B)
-constexpr int MB = 2;                  // MFMA row blocks per wave (64 samples)
 constexpr int NB = 2;                  // MFMA column blocks per wave (64 outputs)
 
 __device__ __forceinline__ uint32_t pack_h2(float a, float b) {
@@ -218,7 +217,13 @@ __global__ __launch_bounds__(256) void kan_prep_basis_kernel(const float* __rest
 }
 
 // ---- kan_mfma ---------------------------------------------------------------------------
+// MB = MFMA row blocks per wave: tile of 32*MB samples.  MB = 2 keeps two workgroups on a
+// CU (a 128-sample tile, MB = 4, halves the fragment bytes per MFMA but leaves one wave per
+// SIMD and measured no faster on configurations 3 and 5).
+template <int MB>
 __global__ __launch_bounds__(kMfmaThreads, 2) void kan_mfma_kernel(const MfmaArgs a) {
+  constexpr int BM = 32 * MB;
+  constexpr int NPAIR = MB;            // (sample, input) pairs per thread and step
   __shared__ __attribute__((aligned(16))) uint16_t sA[2][BM * LDK];   // Phi tiles [b][k], 2 x 22.5 KB
   // Byte-permute selectors: row l, word k builds half-word slots 2k, 2k+1 of an input whose
   // weights w0..w3 (bytes 0..7 of {w23:w01}) sit at slots l..l+3; selector byte 0x0c yields 0.
@@ -253,8 +258,8 @@ __global__ __launch_bounds__(kMfmaThreads, 2) void kan_mfma_kernel(const MfmaArg
   const uint4* cf = a.cf + (long long)head * a.cf_head_stride;
   const uint2* W = a.W + (long long)head * a.w_head_stride;
 
-  // Phi generation: this thread owns sample row pb and inputs 2*ph, 2*ph+1 of every step.
-  const int pb = tid & (BM - 1), ph = tid >> 6;
+  // Phi generation: this thread owns sample row pb and inputs NPAIR*ph .. NPAIR*ph+NPAIR-1 of every step.
+  const int pb = tid & (BM - 1), ph = tid / BM;
   const uint2* wcol = W + min(b0 + pb, B - 1);
   // B operand: columns jc[nb]
   int jc[NB];
@@ -274,17 +279,17 @@ __global__ __launch_bounds__(kMfmaThreads, 2) void kan_mfma_kernel(const MfmaArg
 #pragma unroll
       for (int r = 0; r < 16; ++r) acc[m][n][r] = 0.f;
 
-  auto load_u = [&](int k, uint2 (&uv)[2]) {       // step index relative to the chunk
-    const int i = i_begin + k * IT + 2 * ph;
+  auto load_u = [&](int k, uint2 (&uv)[NPAIR]) {       // step index relative to the chunk
+    const int i = i_begin + k * IT + NPAIR * ph;
 #pragma unroll
-    for (int q = 0; q < 2; ++q) uv[q] = wcol[(long long)min(i + q, n_in - 1) * B];
+    for (int q = 0; q < NPAIR; ++q) uv[q] = wcol[(long long)min(i + q, n_in - 1) * B];
   };
 
-  auto gen_phi = [&](const uint2 (&uv)[2], uint16_t* tile) {
+  auto gen_phi = [&](const uint2 (&uv)[NPAIR], uint16_t* tile) {
     uint16_t* rowp = tile + pb * LDK;
 #pragma unroll
-    for (int q = 0; q < 2; ++q) {
-      const int ii = 2 * ph + q, h = ii >> 2, s = ii & 3;     // input ii of the step: k-step s, lane half h
+    for (int q = 0; q < NPAIR; ++q) {
+      const int ii = NPAIR * ph + q, h = ii >> 2, s = ii & 3;     // input ii of the step: k-step s, lane half h
       const uint32_t l = ((uv[q].x >> 15) & 1u) | ((uv[q].x >> 30) & 2u) | ((uv[q].y >> 13) & 4u);
       const uint32_t w01 = uv[q].x & 0x7fff7fffu, w23 = uv[q].y & 0x7fff7fffu;
       const uint4 sl = *(const uint4*)&sSel[l][0];
@@ -331,7 +336,7 @@ __global__ __launch_bounds__(kMfmaThreads, 2) void kan_mfma_kernel(const MfmaArg
   // frees, so every load has two full steps to arrive; the second workgroup on the CU
   // covers the rest.
   uint4 bfr[3][NB][5];
-  uint2 uv[3][2];
+  uint2 uv[3][NPAIR];
   load_u(0, uv[0]);
   load_b(0, bfr[0]);
   load_u(1, uv[1]);
@@ -414,8 +419,9 @@ hipError_t launch_prep_basis(const float* x, long long x_head_stride, uint2* W, 
   return hipGetLastError();
 }
 
-hipError_t launch_mfma(const MfmaArgs& a, dim3 grid, hipStream_t s) {
-  hipLaunchKernelGGL(kan_mfma_kernel, grid, dim3(kMfmaThreads), 0, s, a);
+hipError_t launch_mfma(const MfmaArgs& a, int tile_m, dim3 grid, hipStream_t s) {
+  if (tile_m != 64) return hipErrorInvalidValue;
+  hipLaunchKernelGGL(kan_mfma_kernel<2>, grid, dim3(kMfmaThreads), 0, s, a);
   return hipGetLastError();
 }
 
