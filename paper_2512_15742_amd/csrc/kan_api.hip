@@ -71,21 +71,28 @@ struct LayerPlan {
   const char* name;
 };
 
-constexpr int kTargetWorkgroups = 1024;   // ~4 workgroups of 4 waves per CU
-constexpr int kMinRowsPerWave = 4;
+constexpr int kTargetWorkgroups = 512;    // two workgroups of 4 waves per CU
+constexpr int kEnoughWorkgroups = 384;
 
-// Geometry for one choice of outputs-per-lane.
-void gather_geometry(LayerPlan& p, int n_in, int n_out, int64_t B, int n_heads, int jpl) {
+// Geometry for one choice of outputs-per-lane.  The four waves of a workgroup are
+// interleaved along i whenever the layer has rows for them (their sums meet in LDS), so a
+// workgroup spans 64*jpl outputs and parallelism comes from output tiles first; i is split
+// into chunks only as far as the partial sums stay small next to the parameter stream
+// (n_chunks * B * out * 4 bytes <= a quarter of in * out * bytes_per_edge).
+void gather_geometry(LayerPlan& p, int n_in, int n_out, int64_t B, int n_heads, int jpl, int bytes_per_edge) {
   p.cfg.jpl = jpl;
   const int lanes_j = (n_out + jpl - 1) / jpl;
-  p.cfg.wj = lanes_j > 128 ? 4 : (lanes_j > 64 ? 2 : 1);
+  p.cfg.wj = n_in >= 16 ? 1 : (lanes_j > 128 ? 4 : (lanes_j > 64 ? 2 : 1));
   const int wi = 4 / p.cfg.wj;
   p.n_jt = (lanes_j + 64 * p.cfg.wj - 1) / (64 * p.cfg.wj);
   p.n_bt = (int)((B + p.cfg.bt - 1) / p.cfg.bt);
   const long long base = (long long)n_heads * p.n_jt * p.n_bt;
-  long long chunks = kTargetWorkgroups / (base > 0 ? base : 1);
-  const long long max_chunks = n_in / (wi * kMinRowsPerWave);
-  if (chunks > max_chunks) chunks = max_chunks;
+  long long chunks = (kTargetWorkgroups + base - 1) / (base > 0 ? base : 1);
+  const int rows_per_wave = p.cfg.bt == 1 ? 4 : 2;
+  const long long max_by_rows = n_in / (wi * rows_per_wave);
+  const long long max_by_bytes = (long long)n_in * bytes_per_edge / (16 * (B > 0 ? B : 1));
+  if (chunks > max_by_rows) chunks = max_by_rows;
+  if (chunks > max_by_bytes) chunks = max_by_bytes;
   if (chunks < 1) chunks = 1;
   int rows = (int)((n_in + chunks - 1) / chunks);
   rows = (rows + wi - 1) / wi * wi;
@@ -102,19 +109,20 @@ LayerPlan plan_gather(int n_in, int n_out, int64_t B, int n_heads, int idx_u32, 
   p.cfg.code = code;
   p.cfg.bt = B <= 1 ? 1 : (B <= 4 ? 4 : 16);
   p.name = p.cfg.bt == 1 ? "kan_gather_bt1" : (p.cfg.bt == 4 ? "kan_gather_bt4" : "kan_gather_bt16");
+  const int bytes_per_edge = code == kDense ? 40 : (idx_u32 ? 4 : 2) + 2 * (gb_f16 ? 2 : 4);
   const int jpl_max = p.cfg.bt == 16 ? 4 : 8;
-  // Widest per-lane vector that divides the row and still leaves every CU a workgroup;
-  // narrow layers trade vector width for more workgroups.
+  // Widest per-lane vector that divides the row and still gives the chip enough workgroups;
+  // narrower vectors mean more output tiles (load width does not matter to the stream).
   int best = 1;
   long long best_wgs = -1;
   for (int c = vec_ok ? jpl_max : 1; c >= 1; c >>= 1) {
     if (n_out % c != 0 || (c > 1 && n_out / c < 64)) continue;
-    gather_geometry(p, n_in, n_out, B, n_heads, c);
+    gather_geometry(p, n_in, n_out, B, n_heads, c, bytes_per_edge);
     const long long wgs = (long long)n_heads * p.n_jt * p.n_bt * p.n_chunks;
-    if (wgs >= 256) { best = c; break; }
+    if (wgs >= kEnoughWorkgroups) { best = c; break; }
     if (wgs > best_wgs) { best = c; best_wgs = wgs; }
   }
-  gather_geometry(p, n_in, n_out, B, n_heads, best);
+  gather_geometry(p, n_in, n_out, B, n_heads, best, bytes_per_edge);
   return p;
 }
 
@@ -392,6 +400,7 @@ kan_status kan_vq_head_forward(const kan_vq_layer* layers, int32_t n_layers, int
       a.B = (int)B;
       a.rows_per_chunk = plans[l].rows_per_chunk;
       a.n_jt = plans[l].n_jt;
+      a.cb_bytes = (long long)R.K * 10 * (R.cb_dtype == KAN_I8 ? 1 : 4);
       for (int h = 0; h < heads; ++h) {
         const kan_vq_layer& L = layers[(size_t)(h0 + h) * n_layers + l];
         a.h[h].idx = L.idx;

@@ -72,6 +72,24 @@ __global__ __launch_bounds__(kThreads) void kan_gather_kernel(const GatherArgs a
   const CbT* cb = (const CbT*)hp.cb;
   const float scale = (CODE == kCbI8) ? hp.scale : 1.0f;
 
+  if constexpr (BT == 1 && CODE != kDense) {
+    // Warm this XCD's L2 with the codebook before the random gathers start: the workgroups
+    // that share an XCD (linear id mod 8) each stream one slice of it, coalesced.
+    if (a.cb_bytes > 0) {
+      const long long wg = blockIdx.x + (long long)gridDim.x * (blockIdx.y + (long long)gridDim.y * blockIdx.z);
+      const long long per_xcd = ((long long)gridDim.x * gridDim.y * gridDim.z + 7) / 8;
+      const long long slice = ((a.cb_bytes + per_xcd - 1) / per_xcd + 4095) / 4096 * 4096;
+      const long long lo = (wg >> 3) * slice, hi = min(lo + slice, a.cb_bytes - 16);
+      uint32_t v = 0;
+      for (long long off = lo + tid * 16; off < hi; off += kThreads * 16) {
+        uint4 q;
+        __builtin_memcpy(&q, (const uint8_t*)cb + off, 16);
+        v ^= q.x ^ q.y ^ q.z ^ q.w;
+      }
+      asm volatile("" ::"v"(v));      // keep the loads; the value is not used
+    }
+  }
+
   float acc[BT][JPL];
   float bsum[JPL];
 #pragma unroll

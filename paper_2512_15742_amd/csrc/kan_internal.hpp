@@ -42,6 +42,7 @@ struct GatherArgs {
   int rows_per_chunk;          // i-rows per workgroup (multiple of 4/wj)
   int n_jt;                    // j-tiles; blockIdx.x = bt_index * n_jt + jt
   int apply_tanh;              // only honoured when the kernel writes final values
+  long long cb_bytes;          // codebook bytes per head (0: no L2 warm-up of the codebook)
   LayerPtrs h[kMaxGroup];
 };
 
