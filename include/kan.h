@@ -50,14 +50,17 @@ typedef enum kan_status {
 
 typedef enum kan_dtype { KAN_F32 = 0, KAN_F16 = 1, KAN_I8 = 2, KAN_U16 = 3, KAN_U32 = 4 } kan_dtype;
 
-/* Which kernels carry the edge evaluation.
- *   KAN_PATH_GATHER  fp32 vector arithmetic, one codeword gather per edge and
- *                    batch tile; matches the float64 definition to ~1e-6.
- *   KAN_PATH_MFMA    coefficients dequantised once per call to fp16 in matrix-core
- *                    operand order (into the workspace), basis weights as fp16
- *                    tiles in LDS, contraction on the matrix cores with fp32
- *                    accumulation; ~3e-4 relative per layer (bound: 2e-2).
- *   KAN_PATH_AUTO    GATHER below batch 32, MFMA from there on (measured crossover).  */
+/* Which arithmetic carries the edge evaluation.
+ *   KAN_PATH_GATHER  the precise path: fp32 operands, fp32 accumulation; matches the
+ *                    float64 definition to ~1e-6 (bound 1e-5).  Batch 1: one 4-byte
+ *                    codeword-window gather per edge on the vector ALUs; batch 2..64:
+ *                    fused gather + fp32 matrix-core kernel; above: fp32 FMA kernel.
+ *   KAN_PATH_MFMA    fp16 operands on the matrix cores, fp32 accumulation; ~3e-4
+ *                    relative per layer (bound 2e-2).  Batch <= 64: fused gather +
+ *                    MFMA kernel; above: coefficients dequantised once per call into
+ *                    the workspace in matrix-core operand order, then a streaming
+ *                    contraction.
+ *   KAN_PATH_AUTO    the precise path below batch 32, the fp16 path from there on.   */
 typedef enum kan_path { KAN_PATH_AUTO = 0, KAN_PATH_GATHER = 1, KAN_PATH_MFMA = 2 } kan_path;
 
 /* One VQ-KAN layer (Eq. (1)): host struct, device pointers. */

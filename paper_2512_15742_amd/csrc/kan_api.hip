@@ -64,10 +64,13 @@ kan_status validate_layer(const kan_vq_layer* L) {
 // Everything below is a pure function of shapes, dtypes, batch, head count and
 // pointer alignment, so the workspace query and the forward call always agree.
 
+enum PlanKind { kPlanGather = 0, kPlanMfma = 1, kPlanFused16 = 2, kPlanFused32 = 3 };
+
 struct LayerPlan {
   GatherCfg cfg;
   int n_jt, n_bt, n_chunks, rows_per_chunk;
-  bool mfma;
+  int kind;          // PlanKind
+  bool mfma;         // kind == kPlanMfma (coefficient + basis preparation, streaming contraction)
   const char* name;
 };
 
@@ -104,6 +107,7 @@ LayerPlan plan_gather(int n_in, int n_out, int64_t B, int n_heads, int idx_u32, 
                       bool vec_ok) {
   LayerPlan p;
   p.mfma = false;
+  p.kind = kPlanGather;
   p.cfg.idx_u32 = idx_u32;
   p.cfg.gb_f16 = gb_f16;
   p.cfg.code = code;
@@ -138,6 +142,7 @@ constexpr int64_t kAutoMfmaBatch = 32;    // KAN_PATH_AUTO switches to the matri
 LayerPlan plan_mfma(int n_in, int n_out, int64_t B, int n_heads, int idx_u32, int gb_f16, int code) {
   LayerPlan p;
   p.mfma = true;
+  p.kind = kPlanMfma;
   p.name = "kan_mfma";
   p.cfg.bt = kMfmaTileM;
   p.cfg.jpl = 1;
@@ -159,15 +164,53 @@ LayerPlan plan_mfma(int n_in, int n_out, int64_t B, int n_heads, int idx_u32, in
   return p;
 }
 
-bool use_mfma(int32_t path, int64_t B) {
-  return path == KAN_PATH_MFMA || (path == KAN_PATH_AUTO && B >= kAutoMfmaBatch);
+// Fused matrix-core kernel (one batch tile, 2 <= B <= 64): every edge is gathered once, so
+// the work is bound by the gather rate of the CUs' address units and wants every CU busy.
+// Workgroups tile the outputs by 128; i is split while the partial sums stay below the
+// size of the parameter stream.
+LayerPlan plan_fused(int n_in, int n_out, int64_t B, int n_heads, int idx_u32, int gb_f16, int code, bool f32) {
+  LayerPlan p;
+  p.mfma = false;
+  p.kind = f32 ? kPlanFused32 : kPlanFused16;
+  p.name = f32 ? "kan_fused_f32" : "kan_fused_f16";
+  p.cfg.bt = (int)B;
+  p.cfg.jpl = 1;
+  p.cfg.wj = 4;
+  p.cfg.idx_u32 = idx_u32;
+  p.cfg.gb_f16 = gb_f16;
+  p.cfg.code = code;
+  p.n_jt = (n_out + kFusedTileN - 1) / kFusedTileN;
+  p.n_bt = 1;
+  const int bytes_per_edge = (idx_u32 ? 4 : 2) + 2 * (gb_f16 ? 2 : 4);
+  const long long base = (long long)n_heads * p.n_jt;
+  long long chunks = (kTargetWorkgroups + base - 1) / (base > 0 ? base : 1);
+  const long long max_by_rows = n_in / 16;                                   // at least two steps each
+  const long long max_by_bytes = (long long)n_in * bytes_per_edge / (4 * B);
+  if (chunks > max_by_rows) chunks = max_by_rows;
+  if (chunks > max_by_bytes) chunks = max_by_bytes;
+  if (chunks < 1) chunks = 1;
+  int rows = (int)((n_in + chunks - 1) / chunks);
+  rows = (rows + 7) / 8 * 8;
+  p.rows_per_chunk = rows;
+  p.n_chunks = (n_in + rows - 1) / rows;
+  return p;
 }
 
+// Which kernels serve a layer:
+//   precise path (KAN_PATH_GATHER, and AUTO below batch 32): B = 1 the window-gather kernel,
+//     2 <= B <= 64 the fused kernel with fp32 matrix-core operands, above that the fp32 FMA kernel;
+//   fp16 path (KAN_PATH_MFMA, and AUTO from batch 32): B <= 64 the fused kernel with fp16
+//     operands, above that coefficient/basis preparation + the streaming contraction.
 LayerPlan plan_vq(const kan_vq_layer& L, int64_t B, int n_heads, bool vec_ok, int32_t path) {
   const int code = L.cb_dtype == KAN_I8 ? kCbI8 : kCbF32;
-  if (use_mfma(path, B))
-    return plan_mfma(L.in, L.out, B, n_heads, L.idx_dtype == KAN_U32, L.gb_dtype == KAN_F16, code);
-  return plan_gather(L.in, L.out, B, n_heads, L.idx_dtype == KAN_U32, L.gb_dtype == KAN_F16, code, vec_ok);
+  const int u32 = L.idx_dtype == KAN_U32, f16 = L.gb_dtype == KAN_F16;
+  const bool half_path = path == KAN_PATH_MFMA || (path == KAN_PATH_AUTO && B >= kAutoMfmaBatch);
+  if (half_path) {
+    if (B <= kFusedMaxBatch) return plan_fused(L.in, L.out, B, n_heads, u32, f16, code, false);
+    return plan_mfma(L.in, L.out, B, n_heads, u32, f16, code);
+  }
+  if (B >= 2 && B <= kFusedMaxBatch) return plan_fused(L.in, L.out, B, n_heads, u32, f16, code, true);
+  return plan_gather(L.in, L.out, B, n_heads, u32, f16, code, vec_ok);
 }
 
 bool layer_vec_ok(const kan_vq_layer& L) {
@@ -261,6 +304,23 @@ kan_status run_layer_group(const LayerPlan& p, GatherArgs& a, int heads, bool x_
     for (int h = 0; h < heads; ++h) m.scale[h] = p.cfg.code == kCbI8 ? a.h[h].scale : 1.0f;
     dim3 grid((unsigned)(p.n_jt * p.n_bt), (unsigned)p.n_chunks, (unsigned)heads);
     st = run(p.name, s, [&] { return launch_mfma(m, p.cfg.bt, grid, s); });
+  } else if (p.kind == kPlanFused16 || p.kind == kPlanFused32) {
+    const bool f32 = p.kind == kPlanFused32;
+    FusedArgs f;
+    memset(&f, 0, sizeof(f));
+    f.x = a.x;
+    f.x_head_stride = a.x_head_stride;
+    f.dst = dst;
+    f.dst_head_stride = dst_head_stride;
+    f.dst_chunk_stride = dst_chunk_stride;
+    f.n_in = a.n_in;
+    f.n_out = a.n_out;
+    f.B = a.B;
+    f.rows_per_chunk = p.rows_per_chunk;
+    f.apply_tanh = tanh_in_kernel;
+    memcpy(f.h, a.h, sizeof(f.h));
+    dim3 grid((unsigned)p.n_jt, (unsigned)p.n_chunks, (unsigned)heads);
+    st = run(p.name, s, [&] { return launch_fused(p.cfg, f, f32, grid, s); });
   } else {
     a.dst = dst;
     a.dst_head_stride = dst_head_stride;
@@ -314,8 +374,9 @@ kan_status plan_head(const kan_vq_layer* layers, int32_t n_layers, int32_t n_hea
     if (p.mfma) {
       grow(ws->cf, round_up((size_t)group * mfma_cf_records(R.in, R.out) * sizeof(uint4), 256));
       grow(ws->bp, round_up((size_t)group * mfma_bp_floats(R.in, R.out) * sizeof(float), 256));
-      grow(ws->u, round_up((size_t)(l == 0 ? 1 : group) * (size_t)R.in * (size_t)B * sizeof(uint2), 256));
     }
+    if (p.mfma)
+      grow(ws->u, round_up((size_t)(l == 0 ? 1 : group) * (size_t)R.in * (size_t)B * sizeof(uint2), 256));
     if (l + 1 < n_layers) grow(ws->hidden, round_up((size_t)n_heads * (size_t)B * R.out * sizeof(float), 256));
   }
   return KAN_OK;

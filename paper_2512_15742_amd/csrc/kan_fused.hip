@@ -1,0 +1,292 @@
+// Fused matrix-core kernel of the VQ-KAN forward pass for one batch tile (2 <= B <= 64).
+//
+// Same contraction as kan_mfma.hip, Y = Phi * Chat (+ bias), but with a single batch
+// tile every edge is needed exactly once, so the coefficient operand is not written to
+// memory first: the lane that feeds output column j of the MFMA B operand reads
+// idx/gain/bias of its own edges (coalesced along j), gathers their codewords,
+// dequantises them and keeps the fragments in registers; metadata is prefetched three
+// steps ahead and codewords one step ahead through small register rings.  The work is
+// bound by the rate of random codeword gathers (one per edge), not by arithmetic.
+//
+// Two operand precisions:
+//   F32 = false  fp16 operands, v_mfma_f32_32x32x16_f16, same k order as kan_mfma.hip
+//                (k-step s < 4, lane half h: coefficients 0..7 of input 4h+s; k-step 4:
+//                coefficients 8, 9 of inputs 4h..4h+3); Int8 scale applied at the end.
+//   F32 = true   fp32 operands, v_mfma_f32_32x32x2f32: MFMA t = 10*s + m multiplies, in
+//                lane half h, coefficient m of input 4h+s; products and sums are fp32,
+//                so the result matches the float64 definition to ~1e-6 and this kernel
+//                serves the precise path for 2 <= B <= 64.
+// Workgroup: 256 threads = 4 waves, each 32 output columns; tile of 32*MBLK samples.
+// The basis tile Phi is built in LDS (double buffered) straight from x: with at most 64
+// samples the strided reads of x are few, and no preparation kernel is launched.
+
+#include <type_traits>
+
+#include "kan_device.hpp"
+#include "kan_internal.hpp"
+#include "kan_mfma_common.hpp"
+
+namespace kan {
+namespace {
+
+constexpr int kThreads = 256;
+constexpr int IT = 8;                  // input rows per step
+constexpr int BN = kFusedTileN;        // outputs per workgroup: 4 waves x 32
+constexpr int LDH = 88;                // fp16 tile: row stride in halves (176 B)
+constexpr int LDF = 84;                // fp32 tile: row stride in floats (336 B); row = [h][s][m]
+
+template <typename IdxT, typename GbT, typename CbT, bool F32, int MBLK>
+__global__ __launch_bounds__(kThreads) void kan_fused_kernel(const FusedArgs a) {
+  constexpr int BM = 32 * MBLK;
+  constexpr int NPAIR = MBLK;          // (sample, input) pairs per thread and step
+  constexpr int kTileBytes = F32 ? BM * LDF * 4 : BM * LDH * 2;
+  __shared__ __attribute__((aligned(16))) unsigned char sTile[2][kTileBytes];
+  __shared__ __attribute__((aligned(16))) uint32_t sSel[kSpans][8];
+  if constexpr (!F32) fill_weight_selectors(sSel, threadIdx.x);
+  __syncthreads();
+
+  const int tid = threadIdx.x;
+  const int lane = tid & 63, wave = tid >> 6;
+  const int ln = lane & 31, lh = lane >> 5;
+  const int head = blockIdx.z, chunk = blockIdx.y, jt = blockIdx.x;
+  const int n_in = a.n_in, n_out = a.n_out, B = a.B;
+  const int i_begin = chunk * a.rows_per_chunk;
+  const int i_end = min(n_in, i_begin + a.rows_per_chunk);
+  const int n_steps = (i_end - i_begin + IT - 1) / IT;
+
+  const LayerPtrs hp = a.h[head];
+  const IdxT* idx = (const IdxT*)hp.idx;
+  const GbT* gain = (const GbT*)hp.gain;
+  const GbT* bias = (const GbT*)hp.bias;
+  const CbT* cb = (const CbT*)hp.cb;
+  const float scale = sizeof(CbT) == 1 ? hp.scale : 1.0f;
+  const float gmul = F32 ? scale : 1.0f;        // fp32 operands carry the scale themselves
+  const float* xh = a.x + (long long)head * a.x_head_stride;
+
+  // Phi generation: sample row pb, inputs NPAIR*ph .. of every step
+  const int pb = tid & (BM - 1), ph = tid / BM;
+  const float* xrow = xh + (long long)min(pb, B - 1) * n_in;
+  // coefficient operand: column jc, input rows 4*lh .. 4*lh+3 of every step
+  const int j = jt * BN + wave * 32 + ln;
+  const bool j_ok = j < n_out;
+  const int jc = min(j, n_out - 1);
+
+  f32x16 acc[MBLK];
+#pragma unroll
+  for (int m = 0; m < MBLK; ++m)
+#pragma unroll
+    for (int r = 0; r < 16; ++r) acc[m][r] = 0.f;
+  float bsum = 0.f;
+
+  struct Meta {
+    uint32_t id[4];
+    float g[4], b[4];
+  };
+  struct Frag {                         // B operand of one step
+    uint4 h[F32 ? 1 : 5];               // fp16: 5 k-steps of 8 halves
+    float f[F32 ? 4 : 1][kG];           // fp32: [s][m]
+  };
+
+  auto load_meta = [&](int k, Meta& m) {
+#pragma unroll
+    for (int s = 0; s < 4; ++s) {
+      const int i = i_begin + k * IT + 4 * lh + s;
+      const bool ok = j_ok && i < i_end;
+      const long long e = (long long)min(i, n_in - 1) * n_out + jc;
+      uint32_t id[1];
+      float g[1], bv[1];
+      load_idx<IdxT, 1>(idx + e, id);
+      load_gb<GbT, 1>(gain + e, g);
+      load_gb<GbT, 1>(bias + e, bv);
+      m.id[s] = id[0];
+      m.g[s] = ok ? g[0] * gmul : 0.f;      // out-of-range edges contribute nothing
+      m.b[s] = ok ? bv[0] : 0.f;
+    }
+  };
+  auto gather_rows = [&](const Meta& m, RawRow<CbT> (&rows)[4]) {
+#pragma unroll
+    for (int s = 0; s < 4; ++s) load_row<CbT>(cb, m.id[s], rows[s]);
+  };
+  auto dequant_step = [&](const RawRow<CbT> (&rows)[4], const Meta& m, Frag& out) {
+    if constexpr (F32) {
+#pragma unroll
+      for (int s = 0; s < 4; ++s) dequant_row_f32<CbT>(rows[s], m.g[s], out.f[s]);
+    } else {
+      uint32_t tail[4];
+#pragma unroll
+      for (int s = 0; s < 4; ++s) {
+        uint32_t w[5];
+        dequant_row<CbT>(rows[s], m.g[s], w);
+        out.h[s] = make_uint4(w[0], w[1], w[2], w[3]);
+        tail[s] = w[4];
+      }
+      out.h[4] = make_uint4(tail[0], tail[1], tail[2], tail[3]);
+    }
+#pragma unroll
+    for (int s = 0; s < 4; ++s) bsum += m.b[s];
+  };
+
+  auto load_u = [&](int k, float (&uv)[NPAIR]) {
+    const int i = i_begin + k * IT + NPAIR * ph;
+#pragma unroll
+    for (int q = 0; q < NPAIR; ++q) uv[q] = xrow[min(i + q, n_in - 1)];
+  };
+  auto gen_phi = [&](const float (&uv)[NPAIR], unsigned char* tile) {
+#pragma unroll
+    for (int q = 0; q < NPAIR; ++q) {
+      const int ii = NPAIR * ph + q, h = ii >> 2, s = ii & 3;
+      // exact span: t = (7x + 7) / 2 is exact in fp64; span = min(floor(t), 6); the local
+      // coordinate u = t - span is exact too and is rounded once to fp32
+      const float xc = fminf(fmaxf(uv[q], -1.0f), 1.0f);
+      const double t = fma((double)xc, 3.5, 3.5);
+      const int l = min((int)t, kSpans - 1);
+      const float u = (float)(t - (double)l);
+      const float u2 = u * u, u3 = u2 * u, om = 1.0f - u;
+      const float w0 = om * om * om * (1.0f / 6.0f);
+      const float w3 = u3 * (1.0f / 6.0f);
+      const float w1 = fmaf(0.5f, u3, fmaf(-1.0f, u2, 2.0f / 3.0f));
+      const float w2 = fmaf(-0.5f, u3, fmaf(0.5f, u2, fmaf(0.5f, u, 1.0f / 6.0f)));
+      if constexpr (F32) {
+        float* p = (float*)tile + pb * LDF + h * 40 + s * kG;      // 8-byte aligned
+        const float2 z = make_float2(0.f, 0.f);
+#pragma unroll
+        for (int m = 0; m < kG / 2; ++m) ((float2*)p)[m] = z;
+        p[l] = w0;                  // same thread: LDS keeps the order of its stores
+        p[l + 1] = w1;
+        p[l + 2] = w2;
+        p[l + 3] = w3;
+      } else {
+        const uint32_t w01 = pack_h2(w0, w1), w23 = pack_h2(w2, w3);
+        const uint4 sl = *(const uint4*)&sSel[l][0];
+        const uint32_t sh = sSel[l][4];
+        uint4 lo;
+        lo.x = __builtin_amdgcn_perm(w23, w01, sl.x);
+        lo.y = __builtin_amdgcn_perm(w23, w01, sl.y);
+        lo.z = __builtin_amdgcn_perm(w23, w01, sl.z);
+        lo.w = __builtin_amdgcn_perm(w23, w01, sl.w);
+        const uint32_t hi = __builtin_amdgcn_perm(w23, w01, sh);
+        uint16_t* rowp = (uint16_t*)tile + pb * LDH;
+        *(uint4*)(rowp + 16 * s + 8 * h) = lo;
+        *(uint32_t*)(rowp + 64 + 8 * h + 2 * s) = hi;
+      }
+    }
+  };
+
+  auto mfma_step = [&](const unsigned char* tile, const Frag& bf) {
+    if constexpr (F32) {
+#pragma unroll
+      for (int m = 0; m < MBLK; ++m) {
+        const float* p = (const float*)tile + (m * 32 + ln) * LDF + lh * 40;
+#pragma unroll
+        for (int q = 0; q < 10; ++q) {
+          const float4 av = *(const float4*)(p + 4 * q);       // slots 4q .. 4q+3 of [s][m]
+          const float avs[4] = {av.x, av.y, av.z, av.w};
+#pragma unroll
+          for (int e = 0; e < 4; ++e) {
+            const int t = 4 * q + e;
+            acc[m] = __builtin_amdgcn_mfma_f32_32x32x2f32(avs[e], bf.f[t / kG][t % kG], acc[m], 0, 0, 0);
+          }
+        }
+      }
+    } else {
+#pragma unroll
+      for (int ks = 0; ks < 5; ++ks) {
+        const h16x8 fb = __builtin_bit_cast(h16x8, bf.h[ks]);
+#pragma unroll
+        for (int m = 0; m < MBLK; ++m) {
+          const h16x8 fa = __builtin_bit_cast(
+              h16x8, *(const uint4*)((const uint16_t*)tile + (m * 32 + ln) * LDH + ks * 16 + lh * 8));
+          acc[m] = __builtin_amdgcn_mfma_f32_32x32x16_f16(fa, fb, acc[m], 0, 0, 0);
+        }
+      }
+    }
+  };
+
+  // ---- pipeline (rings indexed by compile-time slots, loop unrolled by 4) ------------------
+  // Top of step k: fragments and Phi tile of step k are ready; codeword rows and basis words
+  // of step k+1 are in flight; metadata of steps k+1 .. k+3 is held or in flight.  Steps past
+  // the end are loaded from clamped addresses with zero gain and never used.
+  Meta meta[4];
+  RawRow<CbT> rows[2][4];
+  float uv[2][NPAIR];
+  Frag frag[2];
+  load_meta(0, meta[0]);
+  load_meta(1, meta[1]);
+  load_u(0, uv[0]);
+  gather_rows(meta[0], rows[0]);
+  load_meta(2, meta[2]);
+  gather_rows(meta[1], rows[1]);
+  load_meta(3, meta[3]);
+  load_u(1, uv[1]);
+  dequant_step(rows[0], meta[0], frag[0]);
+  gen_phi(uv[0], sTile[0]);
+
+  auto step = [&](auto T, int k) {
+    constexpr int t = decltype(T)::value;          // k mod 4
+    __syncthreads();     // tile k is complete; every wave is done reading tile k-1
+    dequant_step(rows[(t + 1) & 1], meta[(t + 1) & 3], frag[(t + 1) & 1]);   // step k+1 fragments
+    gather_rows(meta[(t + 2) & 3], rows[t & 1]);                             // step k+2 codewords
+    load_meta(k + 4, meta[t & 3]);                                           // step k+4 metadata
+    mfma_step(sTile[t & 1], frag[t & 1]);
+    gen_phi(uv[(t + 1) & 1], sTile[(t + 1) & 1]);                            // step k+1 basis tile
+    load_u(k + 2, uv[t & 1]);
+  };
+  for (int k = 0; k < n_steps; k += 4) {
+    step(std::integral_constant<int, 0>{}, k);
+    if (k + 1 < n_steps) step(std::integral_constant<int, 1>{}, k + 1);
+    if (k + 2 < n_steps) step(std::integral_constant<int, 2>{}, k + 2);
+    if (k + 3 < n_steps) step(std::integral_constant<int, 3>{}, k + 3);
+  }
+
+  // ---- epilogue.  D layout of the 32x32 MFMA: lane holds column (lane & 31), rows
+  //      8*(r/4) + 4*(lane/32) + r%4 for r = 0..15 -------------------------------------------
+  // The pipeline dequantised one step beyond the last; its bias entries were zero.
+  const float bs = bsum + __shfl_xor(bsum, 32);      // both lane halves: all 8 input rows
+  const float oscale = F32 ? 1.0f : scale;
+  float* dst = a.dst + (long long)head * a.dst_head_stride + (long long)chunk * a.dst_chunk_stride;
+  if (j_ok) {
+#pragma unroll
+    for (int m = 0; m < MBLK; ++m)
+#pragma unroll
+      for (int r = 0; r < 16; ++r) {
+        const int b = m * 32 + 8 * (r >> 2) + 4 * lh + (r & 3);
+        if (b < B) {
+          float v = fmaf(oscale, acc[m][r], bs);
+          if (a.apply_tanh) v = tanhf(v);
+          dst[(long long)b * n_out + jc] = v;
+        }
+      }
+  }
+}
+
+template <typename IdxT, typename GbT, typename CbT>
+hipError_t launch_variant(const FusedArgs& a, bool f32, int mblk, dim3 grid, hipStream_t s) {
+  if (f32) {
+    if (mblk == 1) hipLaunchKernelGGL((kan_fused_kernel<IdxT, GbT, CbT, true, 1>), grid, dim3(kThreads), 0, s, a);
+    else hipLaunchKernelGGL((kan_fused_kernel<IdxT, GbT, CbT, true, 2>), grid, dim3(kThreads), 0, s, a);
+  } else {
+    if (mblk == 1) hipLaunchKernelGGL((kan_fused_kernel<IdxT, GbT, CbT, false, 1>), grid, dim3(kThreads), 0, s, a);
+    else hipLaunchKernelGGL((kan_fused_kernel<IdxT, GbT, CbT, false, 2>), grid, dim3(kThreads), 0, s, a);
+  }
+  return hipGetLastError();
+}
+
+template <typename IdxT>
+hipError_t launch_types(const GatherCfg& c, const FusedArgs& a, bool f32, int mblk, dim3 grid, hipStream_t s) {
+  if (c.code == kCbI8)
+    return c.gb_f16 ? launch_variant<IdxT, __half, int8_t>(a, f32, mblk, grid, s)
+                    : launch_variant<IdxT, float, int8_t>(a, f32, mblk, grid, s);
+  return c.gb_f16 ? launch_variant<IdxT, __half, float>(a, f32, mblk, grid, s)
+                  : launch_variant<IdxT, float, float>(a, f32, mblk, grid, s);
+}
+
+}  // namespace
+
+hipError_t launch_fused(const GatherCfg& c, const FusedArgs& a, bool f32, dim3 grid, hipStream_t s) {
+  if (c.code == kDense || a.B < 1 || a.B > kFusedMaxBatch) return hipErrorInvalidValue;
+  const int mblk = a.B <= 32 ? 1 : 2;
+  return c.idx_u32 ? launch_types<uint32_t>(c, a, f32, mblk, grid, s)
+                   : launch_types<uint16_t>(c, a, f32, mblk, grid, s);
+}
+
+}  // namespace kan

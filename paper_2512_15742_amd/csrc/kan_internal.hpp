@@ -83,6 +83,23 @@ hipError_t launch_prep_basis(const float* x, long long x_head_stride, uint2* W, 
                              int n_in, int B, int heads, hipStream_t);
 hipError_t launch_mfma(const MfmaArgs&, int tile_m, dim3 grid, hipStream_t);   // tile_m: samples per tile (64)
 
+// ---- fused matrix-core kernel for a single batch tile (2 <= B <= 64) -----------------
+constexpr int kFusedTileN = 128;      // outputs per workgroup
+constexpr int kFusedMaxBatch = 64;
+
+struct FusedArgs {
+  const float* x;              // [head or 1][B][n_in]
+  long long x_head_stride;     // 0 when all heads share the input
+  float* dst;
+  long long dst_head_stride, dst_chunk_stride;
+  int n_in, n_out, B;
+  int rows_per_chunk;          // multiple of 8
+  int apply_tanh;
+  LayerPtrs h[kMaxGroup];
+};
+
+hipError_t launch_fused(const GatherCfg&, const FusedArgs&, bool f32, dim3 grid, hipStream_t);
+
 // ---- reduction of i-chunk partial sums ------------------------------------------
 // dst[n] = act( sum_c partial[c * chunk_stride + n] ), n < count, for every head.
 hipError_t launch_reduce(const float* partial, long long head_stride, long long chunk_stride,

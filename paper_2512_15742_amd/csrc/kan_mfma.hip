@@ -40,13 +40,10 @@
 
 #include "kan_device.hpp"
 #include "kan_internal.hpp"
+#include "kan_mfma_common.hpp"
 
 namespace kan {
 namespace {
-
-typedef _Float16 h16x2 __attribute__((ext_vector_type(2)));
-typedef _Float16 h16x8 __attribute__((ext_vector_type(8)));
-typedef float f32x16 __attribute__((ext_vector_type(16)));
 
 constexpr int kThreads = 256;          // preparation kernels
 constexpr int kMfmaThreads = 256;      // contraction kernel: 4 waves along the outputs
@@ -54,64 +51,6 @@ constexpr int BN = 256;                // outputs per workgroup tile (samples pe
 constexpr int IT = 8;                  // input rows per step (80 k-slots = 5 MFMA k-steps)
 constexpr int LDK = 88;                // LDS row stride in halves (176 B = 11 x 16 B)
 constexpr int NB = 2;                  // MFMA column blocks per wave (64 outputs)
-
-__device__ __forceinline__ uint32_t pack_h2(float a, float b) {
-  h16x2 v = {(_Float16)a, (_Float16)b};
-  return __builtin_bit_cast(uint32_t, v);
-}
-
-// fp16 pair (g*q[p], g*q[p+1]) from bytes p, p+1 of w, where w holds q + 128 as
-// unsigned bytes: 0x6400 | byte is the half 1024 + byte, so subtracting 1152 is
-// exact and leaves q.
-template <int P>
-__device__ __forceinline__ uint32_t dq_pair(uint32_t w, h16x2 g2) {
-  const uint32_t sel = 0x04000400u | ((uint32_t)(P + 1) << 16) | (uint32_t)P;
-  const uint32_t m = __builtin_amdgcn_perm(0x64646464u, w, sel);
-  const h16x2 off = {(_Float16)-1152.0f, (_Float16)-1152.0f};
-  const h16x2 v = (__builtin_bit_cast(h16x2, m) + off) * g2;
-  return __builtin_bit_cast(uint32_t, v);
-}
-
-// Raw codeword of one edge as loaded from the codebook.
-template <typename CbT> struct RawRow;
-template <> struct RawRow<int8_t> { uint32_t a, b, d; };
-template <> struct RawRow<float> { float c[kG]; };
-
-template <typename CbT>
-__device__ __forceinline__ void load_row(const CbT* cb, uint32_t id, RawRow<CbT>& r) {
-  if constexpr (sizeof(CbT) == 1) {
-    const uint8_t* p = (const uint8_t*)cb + (size_t)id * kG;
-    r.a = ld_u32_any(p);
-    r.b = ld_u32_any(p + 4);
-    r.d = ld_u16_any(p + 8);
-  } else {
-    const float2* p = (const float2*)(cb + (size_t)id * kG);
-#pragma unroll
-    for (int m = 0; m < kG / 2; ++m) {
-      const float2 v = p[m];
-      r.c[2 * m] = v.x;
-      r.c[2 * m + 1] = v.y;
-    }
-  }
-}
-
-// w[0..3] = fp16 pairs of g*coef 0..7, w[4] = g*coef 8, 9.
-template <typename CbT>
-__device__ __forceinline__ void dequant_row(const RawRow<CbT>& r, float g, uint32_t (&w)[5]) {
-  if constexpr (sizeof(CbT) == 1) {
-    const _Float16 gh = (_Float16)g;
-    const h16x2 g2 = {gh, gh};
-    const uint32_t a = r.a ^ 0x80808080u, b = r.b ^ 0x80808080u, d = r.d ^ 0x00008080u;
-    w[0] = dq_pair<0>(a, g2);
-    w[1] = dq_pair<2>(a, g2);
-    w[2] = dq_pair<0>(b, g2);
-    w[3] = dq_pair<2>(b, g2);
-    w[4] = dq_pair<0>(d, g2);
-  } else {
-#pragma unroll
-    for (int m = 0; m < 5; ++m) w[m] = pack_h2(g * r.c[2 * m], g * r.c[2 * m + 1]);
-  }
-}
 
 // ---- kan_prep_coef ------------------------------------------------------------------
 // Chat as uint4 records: rec[((step*5 + ks) * 2 + h) * n_out + j], step = i / 8, so that
@@ -228,17 +167,7 @@ __global__ __launch_bounds__(kMfmaThreads, 2) void kan_mfma_kernel(const MfmaArg
   // Byte-permute selectors: row l, word k builds half-word slots 2k, 2k+1 of an input whose
   // weights w0..w3 (bytes 0..7 of {w23:w01}) sit at slots l..l+3; selector byte 0x0c yields 0.
   __shared__ __attribute__((aligned(16))) uint32_t sSel[kSpans][8];
-  if (threadIdx.x < kSpans * 8) {   // 56 entries
-    const int l = threadIdx.x >> 3, k = threadIdx.x & 7;
-    uint32_t sel = 0x0c0c0c0cu;
-    if (k < 5) {
-      const int r0 = 2 * k - l, r1 = 2 * k + 1 - l;
-      const uint32_t lo = (r0 >= 0 && r0 <= 3) ? (uint32_t)((2 * r0) | ((2 * r0 + 1) << 8)) : 0x0c0cu;
-      const uint32_t hi = (r1 >= 0 && r1 <= 3) ? (uint32_t)((2 * r1) | ((2 * r1 + 1) << 8)) : 0x0c0cu;
-      sel = lo | (hi << 16);
-    }
-    sSel[l][k] = sel;
-  }
+  fill_weight_selectors(sSel, threadIdx.x);
   __syncthreads();
 
   const int tid = threadIdx.x;
@@ -290,8 +219,8 @@ __global__ __launch_bounds__(kMfmaThreads, 2) void kan_mfma_kernel(const MfmaArg
 #pragma unroll
     for (int q = 0; q < NPAIR; ++q) {
       const int ii = NPAIR * ph + q, h = ii >> 2, s = ii & 3;     // input ii of the step: k-step s, lane half h
-      const uint32_t l = ((uv[q].x >> 15) & 1u) | ((uv[q].x >> 30) & 2u) | ((uv[q].y >> 13) & 4u);
-      const uint32_t w01 = uv[q].x & 0x7fff7fffu, w23 = uv[q].y & 0x7fff7fffu;
+      uint32_t l, w01, w23;
+      unpack_basis(uv[q], l, w01, w23);
       const uint4 sl = *(const uint4*)&sSel[l][0];
       const uint32_t sh = sSel[l][4];
       uint4 lo;

@@ -1,0 +1,112 @@
+// Pieces shared by the matrix-core kernels: fp16 packing, the raw codeword of an edge and
+// its dequantisation into fp16 pairs (Int8: packed-half arithmetic; fp32: multiply, round).
+#pragma once
+
+#include "kan_device.hpp"
+
+namespace kan {
+
+typedef _Float16 h16x2 __attribute__((ext_vector_type(2)));
+typedef _Float16 h16x8 __attribute__((ext_vector_type(8)));
+typedef float f32x16 __attribute__((ext_vector_type(16)));
+
+__device__ __forceinline__ uint32_t pack_h2(float a, float b) {
+  h16x2 v = {(_Float16)a, (_Float16)b};
+  return __builtin_bit_cast(uint32_t, v);
+}
+
+// fp16 pair (g*q[p], g*q[p+1]) from bytes p, p+1 of w, where w holds q + 128 as
+// unsigned bytes: 0x6400 | byte is the half 1024 + byte, so subtracting 1152 is
+// exact and leaves q.
+template <int P>
+__device__ __forceinline__ uint32_t dq_pair(uint32_t w, h16x2 g2) {
+  const uint32_t sel = 0x04000400u | ((uint32_t)(P + 1) << 16) | (uint32_t)P;
+  const uint32_t m = __builtin_amdgcn_perm(0x64646464u, w, sel);
+  const h16x2 off = {(_Float16)-1152.0f, (_Float16)-1152.0f};
+  const h16x2 v = (__builtin_bit_cast(h16x2, m) + off) * g2;
+  return __builtin_bit_cast(uint32_t, v);
+}
+
+// Raw codeword of one edge as loaded from the codebook.
+template <typename CbT> struct RawRow;
+template <> struct RawRow<int8_t> { uint32_t a, b, d; };
+template <> struct RawRow<float> { float c[kG]; };
+
+template <typename CbT>
+__device__ __forceinline__ void load_row(const CbT* cb, uint32_t id, RawRow<CbT>& r) {
+  if constexpr (sizeof(CbT) == 1) {
+    const uint8_t* p = (const uint8_t*)cb + (size_t)id * kG;
+    r.a = ld_u32_any(p);
+    r.b = ld_u32_any(p + 4);
+    r.d = ld_u16_any(p + 8);
+  } else {
+    const float2* p = (const float2*)(cb + (size_t)id * kG);
+#pragma unroll
+    for (int m = 0; m < kG / 2; ++m) {
+      const float2 v = p[m];
+      r.c[2 * m] = v.x;
+      r.c[2 * m + 1] = v.y;
+    }
+  }
+}
+
+// w[0..3] = fp16 pairs of g*coef 0..7, w[4] = g*coef 8, 9.
+template <typename CbT>
+__device__ __forceinline__ void dequant_row(const RawRow<CbT>& r, float g, uint32_t (&w)[5]) {
+  if constexpr (sizeof(CbT) == 1) {
+    const _Float16 gh = (_Float16)g;
+    const h16x2 g2 = {gh, gh};
+    const uint32_t a = r.a ^ 0x80808080u, b = r.b ^ 0x80808080u, d = r.d ^ 0x00008080u;
+    w[0] = dq_pair<0>(a, g2);
+    w[1] = dq_pair<2>(a, g2);
+    w[2] = dq_pair<0>(b, g2);
+    w[3] = dq_pair<2>(b, g2);
+    w[4] = dq_pair<0>(d, g2);
+  } else {
+#pragma unroll
+    for (int m = 0; m < 5; ++m) w[m] = pack_h2(g * r.c[2 * m], g * r.c[2 * m + 1]);
+  }
+}
+
+// c[m] = g * coef m as fp32 (matrix-core path with fp32 operands).
+template <typename CbT>
+__device__ __forceinline__ void dequant_row_f32(const RawRow<CbT>& r, float g, float (&c)[kG]) {
+  if constexpr (sizeof(CbT) == 1) {
+    const float off = -128.0f * g;
+    float t[4];
+    dequant4(r.a, g, off, &c[0]);
+    dequant4(r.b, g, off, &c[4]);
+    dequant4(r.d, g, off, t);
+    c[8] = t[0];
+    c[9] = t[1];
+  } else {
+#pragma unroll
+    for (int m = 0; m < kG; ++m) c[m] = g * r.c[m];
+  }
+}
+
+// Byte-permute selectors that place the four fp16 weights {w23:w01} of one input at
+// half-word slots l..l+3 of its ten: entry [l][k], k = 0..4, builds slots 2k, 2k+1;
+// selector byte 0x0c yields 0.  56 threads fill the 7 x 8 table.
+__device__ __forceinline__ void fill_weight_selectors(uint32_t (*sel)[8], int tid) {
+  if (tid < kSpans * 8) {
+    const int l = tid >> 3, k = tid & 7;
+    uint32_t v = 0x0c0c0c0cu;
+    if (k < 5) {
+      const int r0 = 2 * k - l, r1 = 2 * k + 1 - l;
+      const uint32_t lo = (r0 >= 0 && r0 <= 3) ? (uint32_t)((2 * r0) | ((2 * r0 + 1) << 8)) : 0x0c0cu;
+      const uint32_t hi = (r1 >= 0 && r1 <= 3) ? (uint32_t)((2 * r1) | ((2 * r1 + 1) << 8)) : 0x0c0cu;
+      v = lo | (hi << 16);
+    }
+    sel[l][k] = v;
+  }
+}
+
+// Span (0..6) and the two weight words from a packed basis word (kan_prep_basis, fp16 form).
+__device__ __forceinline__ void unpack_basis(uint2 u, uint32_t& l, uint32_t& w01, uint32_t& w23) {
+  l = ((u.x >> 15) & 1u) | ((u.x >> 30) & 2u) | ((u.y >> 13) & 4u);
+  w01 = u.x & 0x7fff7fffu;
+  w23 = u.y & 0x7fff7fffu;
+}
+
+}  // namespace kan
