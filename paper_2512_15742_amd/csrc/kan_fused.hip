@@ -204,19 +204,20 @@ __global__ __launch_bounds__(kThreads) void kan_fused_kernel(const FusedArgs a) 
 
   // ---- pipeline (rings indexed by compile-time slots, loop unrolled by 4) ------------------
   // Top of step k: fragments and Phi tile of step k are ready; codeword rows and basis words
-  // of step k+1 are in flight; metadata of steps k+1 .. k+3 is held or in flight.  Steps past
-  // the end are loaded from clamped addresses with zero gain and never used.
+  // of step k+1 are in flight; metadata of steps k+1 .. k+3 is held or in flight.
   Meta meta[4];
   RawRow<CbT> rows[2][4];
   float uv[2][NPAIR];
   Frag frag[2];
+  // Nothing is fetched for steps past the end: the address units that serve the random
+  // codeword gathers are the bottleneck of this kernel, so wasted gathers are not free.
   load_meta(0, meta[0]);
-  load_meta(1, meta[1]);
+  if (1 < n_steps) load_meta(1, meta[1]);
   load_u(0, uv[0]);
   gather_rows(meta[0], rows[0]);
-  load_meta(2, meta[2]);
-  gather_rows(meta[1], rows[1]);
-  load_meta(3, meta[3]);
+  if (2 < n_steps) load_meta(2, meta[2]);
+  if (1 < n_steps) gather_rows(meta[1], rows[1]);
+  if (3 < n_steps) load_meta(3, meta[3]);
   load_u(1, uv[1]);
   dequant_step(rows[0], meta[0], frag[0]);
   gen_phi(uv[0], sTile[0]);
@@ -224,12 +225,12 @@ __global__ __launch_bounds__(kThreads) void kan_fused_kernel(const FusedArgs a) 
   auto step = [&](auto T, int k) {
     constexpr int t = decltype(T)::value;          // k mod 4
     __syncthreads();     // tile k is complete; every wave is done reading tile k-1
-    dequant_step(rows[(t + 1) & 1], meta[(t + 1) & 3], frag[(t + 1) & 1]);   // step k+1 fragments
-    gather_rows(meta[(t + 2) & 3], rows[t & 1]);                             // step k+2 codewords
-    load_meta(k + 4, meta[t & 3]);                                           // step k+4 metadata
+    if (k + 1 < n_steps) dequant_step(rows[(t + 1) & 1], meta[(t + 1) & 3], frag[(t + 1) & 1]);   // step k+1 fragments
+    if (k + 2 < n_steps) gather_rows(meta[(t + 2) & 3], rows[t & 1]);                             // step k+2 codewords
+    if (k + 4 < n_steps) load_meta(k + 4, meta[t & 3]);                                           // step k+4 metadata
     mfma_step(sTile[t & 1], frag[t & 1]);
-    gen_phi(uv[(t + 1) & 1], sTile[(t + 1) & 1]);                            // step k+1 basis tile
-    load_u(k + 2, uv[t & 1]);
+    if (k + 1 < n_steps) gen_phi(uv[(t + 1) & 1], sTile[(t + 1) & 1]);                            // step k+1 basis tile
+    if (k + 2 < n_steps) load_u(k + 2, uv[t & 1]);
   };
   for (int k = 0; k < n_steps; k += 4) {
     step(std::integral_constant<int, 0>{}, k);
@@ -240,7 +241,6 @@ __global__ __launch_bounds__(kThreads) void kan_fused_kernel(const FusedArgs a) 
 
   // ---- epilogue.  D layout of the 32x32 MFMA: lane holds column (lane & 31), rows
   //      8*(r/4) + 4*(lane/32) + r%4 for r = 0..15 -------------------------------------------
-  // The pipeline dequantised one step beyond the last; its bias entries were zero.
   const float bs = bsum + __shfl_xor(bsum, 32);      // both lane halves: all 8 input rows
   const float oscale = F32 ? 1.0f : scale;
   float* dst = a.dst + (long long)head * a.dst_head_stride + (long long)chunk * a.dst_chunk_stride;
