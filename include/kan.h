@@ -53,8 +53,8 @@ typedef enum kan_dtype { KAN_F32 = 0, KAN_F16 = 1, KAN_I8 = 2, KAN_U16 = 3, KAN_
 /* Which arithmetic carries the edge evaluation.
  *   KAN_PATH_GATHER  the precise path: fp32 operands, fp32 accumulation; matches the
  *                    float64 definition to ~1e-6 (bound 1e-5).  Batch 1: one 4-byte
- *                    codeword-window gather per edge on the vector ALUs; batch 2..64:
- *                    fused gather + fp32 matrix-core kernel; above: fp32 FMA kernel.
+ *                    codeword-window gather per edge on the vector ALUs; from batch 2:
+ *                    fused gather + fp32 matrix-core kernel.
  *   KAN_PATH_MFMA    fp16 operands on the matrix cores, fp32 accumulation; ~3e-4
  *                    relative per layer (bound 2e-2).  Batch <= 64: fused gather +
  *                    MFMA kernel; above: coefficients dequantised once per call into

@@ -137,6 +137,7 @@ constexpr int kMfmaTileN = 256;
 constexpr int kMfmaRowsStep = kMfmaPrepRows;   // chunk boundaries coincide with partial bias sums
 constexpr int kMfmaTargetWorkgroups = 512;
 constexpr int kMfmaMinRows = 64;
+constexpr int64_t kHalfFusedMaxBatch = 64;   // fp16 path: fused kernel up to here, streaming contraction above
 constexpr int64_t kAutoMfmaBatch = 32;    // KAN_PATH_AUTO switches to the matrix cores from here (measured crossover 16-32)
 
 LayerPlan plan_mfma(int n_in, int n_out, int64_t B, int n_heads, int idx_u32, int gb_f16, int code) {
@@ -164,25 +165,25 @@ LayerPlan plan_mfma(int n_in, int n_out, int64_t B, int n_heads, int idx_u32, in
   return p;
 }
 
-// Fused matrix-core kernel (one batch tile, 2 <= B <= 64): every edge is gathered once, so
-// the work is bound by the gather rate of the CUs' address units and wants every CU busy.
-// Workgroups tile the outputs by 128; i is split while the partial sums stay below the
-// size of the parameter stream.
+// Fused gather + matrix-core kernel: batch tiles of 32 (B <= 32) or 64 samples, output tiles
+// of 128.  With one batch tile every edge is gathered once and the work is bound by the
+// gather rate of the CUs' address units, so every CU should be busy: i is split while the
+// partial sums stay below the size of the parameter stream.
 LayerPlan plan_fused(int n_in, int n_out, int64_t B, int n_heads, int idx_u32, int gb_f16, int code, bool f32) {
   LayerPlan p;
   p.mfma = false;
   p.kind = f32 ? kPlanFused32 : kPlanFused16;
   p.name = f32 ? "kan_fused_f32" : "kan_fused_f16";
-  p.cfg.bt = (int)B;
+  p.cfg.bt = B <= 32 ? 32 : 64;
   p.cfg.jpl = 1;
   p.cfg.wj = 4;
   p.cfg.idx_u32 = idx_u32;
   p.cfg.gb_f16 = gb_f16;
   p.cfg.code = code;
   p.n_jt = (n_out + kFusedTileN - 1) / kFusedTileN;
-  p.n_bt = 1;
+  p.n_bt = (int)((B + p.cfg.bt - 1) / p.cfg.bt);
   const int bytes_per_edge = (idx_u32 ? 4 : 2) + 2 * (gb_f16 ? 2 : 4);
-  const long long base = (long long)n_heads * p.n_jt;
+  const long long base = (long long)n_heads * p.n_jt * p.n_bt;
   long long chunks = (kTargetWorkgroups + base - 1) / (base > 0 ? base : 1);
   const long long max_by_rows = n_in / 16;                                   // at least two steps each
   const long long max_by_bytes = (long long)n_in * bytes_per_edge / (4 * B);
@@ -198,18 +199,20 @@ LayerPlan plan_fused(int n_in, int n_out, int64_t B, int n_heads, int idx_u32, i
 
 // Which kernels serve a layer:
 //   precise path (KAN_PATH_GATHER, and AUTO below batch 32): B = 1 the window-gather kernel,
-//     2 <= B <= 64 the fused kernel with fp32 matrix-core operands, above that the fp32 FMA kernel;
-//   fp16 path (KAN_PATH_MFMA, and AUTO from batch 32): B <= 64 the fused kernel with fp16
-//     operands, above that coefficient/basis preparation + the streaming contraction.
+//     B >= 2 the fused kernel with fp32 matrix-core operands (the fp32 FMA kernel remains the
+//     dense baseline's);
+//   fp16 path (KAN_PATH_MFMA, and AUTO from batch 32): up to kHalfFusedMaxBatch the fused
+//     kernel with fp16 operands, above that coefficient/basis preparation + the streaming
+//     contraction.
 LayerPlan plan_vq(const kan_vq_layer& L, int64_t B, int n_heads, bool vec_ok, int32_t path) {
   const int code = L.cb_dtype == KAN_I8 ? kCbI8 : kCbF32;
   const int u32 = L.idx_dtype == KAN_U32, f16 = L.gb_dtype == KAN_F16;
   const bool half_path = path == KAN_PATH_MFMA || (path == KAN_PATH_AUTO && B >= kAutoMfmaBatch);
   if (half_path) {
-    if (B <= kFusedMaxBatch) return plan_fused(L.in, L.out, B, n_heads, u32, f16, code, false);
+    if (B <= kHalfFusedMaxBatch) return plan_fused(L.in, L.out, B, n_heads, u32, f16, code, false);
     return plan_mfma(L.in, L.out, B, n_heads, u32, f16, code);
   }
-  if (B >= 2 && B <= kFusedMaxBatch) return plan_fused(L.in, L.out, B, n_heads, u32, f16, code, true);
+  if (B >= 2) return plan_fused(L.in, L.out, B, n_heads, u32, f16, code, true);
   return plan_gather(L.in, L.out, B, n_heads, u32, f16, code, vec_ok);
 }
 
@@ -317,9 +320,10 @@ kan_status run_layer_group(const LayerPlan& p, GatherArgs& a, int heads, bool x_
     f.n_out = a.n_out;
     f.B = a.B;
     f.rows_per_chunk = p.rows_per_chunk;
+    f.n_jt = p.n_jt;
     f.apply_tanh = tanh_in_kernel;
     memcpy(f.h, a.h, sizeof(f.h));
-    dim3 grid((unsigned)p.n_jt, (unsigned)p.n_chunks, (unsigned)heads);
+    dim3 grid((unsigned)(p.n_jt * p.n_bt), (unsigned)p.n_chunks, (unsigned)heads);
     st = run(p.name, s, [&] { return launch_fused(p.cfg, f, f32, grid, s); });
   } else {
     a.dst = dst;

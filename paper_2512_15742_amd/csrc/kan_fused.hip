@@ -1,8 +1,10 @@
-// Fused matrix-core kernel of the VQ-KAN forward pass for one batch tile (2 <= B <= 64).
+// Fused matrix-core kernel of the VQ-KAN forward pass (small and medium batch).
 //
-// Same contraction as kan_mfma.hip, Y = Phi * Chat (+ bias), but with a single batch
-// tile every edge is needed exactly once, so the coefficient operand is not written to
-// memory first: the lane that feeds output column j of the MFMA B operand reads
+// Same contraction as kan_mfma.hip, Y = Phi * Chat (+ bias), but the coefficient operand
+// is not written to memory first; every batch tile of 32 or 64 samples gathers the
+// codewords it needs itself (with one tile every edge is gathered exactly once; with
+// several, the repeated gathers cost less than the fp32 matrix-core time they feed, and
+// for fp16 operands the dispatcher switches to the streaming kernel instead).  The lane that feeds output column j of the MFMA B operand reads
 // idx/gain/bias of its own edges (coalesced along j), gathers their codewords,
 // dequantises them and keeps the fragments in registers; metadata is prefetched three
 // steps ahead and codewords one step ahead through small register rings.  The work is
@@ -15,7 +17,7 @@
 //   F32 = true   fp32 operands, v_mfma_f32_32x32x2f32: MFMA t = 10*s + m multiplies, in
 //                lane half h, coefficient m of input 4h+s; products and sums are fp32,
 //                so the result matches the float64 definition to ~1e-6 and this kernel
-//                serves the precise path for 2 <= B <= 64.
+//                serves the precise path for every batch >= 2.
 // Workgroup: 256 threads = 4 waves, each 32 output columns; tile of 32*MBLK samples.
 // The basis tile Phi is built in LDS (double buffered) straight from x: with at most 64
 // samples the strided reads of x are few, and no preparation kernel is launched.
@@ -48,7 +50,8 @@ __global__ __launch_bounds__(kThreads) void kan_fused_kernel(const FusedArgs a) 
   const int tid = threadIdx.x;
   const int lane = tid & 63, wave = tid >> 6;
   const int ln = lane & 31, lh = lane >> 5;
-  const int head = blockIdx.z, chunk = blockIdx.y, jt = blockIdx.x;
+  const int head = blockIdx.z, chunk = blockIdx.y;
+  const int jt = blockIdx.x % a.n_jt, b0 = (blockIdx.x / a.n_jt) * (32 * MBLK);
   const int n_in = a.n_in, n_out = a.n_out, B = a.B;
   const int i_begin = chunk * a.rows_per_chunk;
   const int i_end = min(n_in, i_begin + a.rows_per_chunk);
@@ -65,7 +68,7 @@ __global__ __launch_bounds__(kThreads) void kan_fused_kernel(const FusedArgs a) 
 
   // Phi generation: sample row pb, inputs NPAIR*ph .. of every step
   const int pb = tid & (BM - 1), ph = tid / BM;
-  const float* xrow = xh + (long long)min(pb, B - 1) * n_in;
+  const float* xrow = xh + (long long)min(b0 + pb, B - 1) * n_in;
   // coefficient operand: column jc, input rows 4*lh .. 4*lh+3 of every step
   const int j = jt * BN + wave * 32 + ln;
   const bool j_ok = j < n_out;
@@ -249,7 +252,7 @@ __global__ __launch_bounds__(kThreads) void kan_fused_kernel(const FusedArgs a) 
     for (int m = 0; m < MBLK; ++m)
 #pragma unroll
       for (int r = 0; r < 16; ++r) {
-        const int b = m * 32 + 8 * (r >> 2) + 4 * lh + (r & 3);
+        const int b = b0 + m * 32 + 8 * (r >> 2) + 4 * lh + (r & 3);
         if (b < B) {
           float v = fmaf(oscale, acc[m][r], bs);
           if (a.apply_tanh) v = tanhf(v);
@@ -283,8 +286,8 @@ hipError_t launch_types(const GatherCfg& c, const FusedArgs& a, bool f32, int mb
 }  // namespace
 
 hipError_t launch_fused(const GatherCfg& c, const FusedArgs& a, bool f32, dim3 grid, hipStream_t s) {
-  if (c.code == kDense || a.B < 1 || a.B > kFusedMaxBatch) return hipErrorInvalidValue;
-  const int mblk = a.B <= 32 ? 1 : 2;
+  if (c.code == kDense || a.B < 1 || (c.bt != 32 && c.bt != 64)) return hipErrorInvalidValue;
+  const int mblk = c.bt / 32;
   return c.idx_u32 ? launch_types<uint32_t>(c, a, f32, mblk, grid, s)
                    : launch_types<uint16_t>(c, a, f32, mblk, grid, s);
 }

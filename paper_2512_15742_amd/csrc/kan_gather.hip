@@ -1,17 +1,18 @@
-// Gather path of the VQ-KAN forward pass for gfx950: fp32 vector arithmetic.
+// Vector-ALU path of the KAN forward pass for gfx950 (fp32): VQ layers at batch 1 and the
+// dense-coefficient baseline at any batch.
 //
 // Mapping.  Lanes own outputs j (JPL consecutive ones each), so the per-edge
 // metadata idx/gain/bias[i][j..] of paper Eq. (1) is one contiguous, coalesced,
 // read-once stream per i-row, and everything that depends on x_bi alone (the
 // interval index and the four basis weights, App. A.1 / section 4.1) is the same
 // for all lanes of a wave: it is computed once per (b, i) into LDS and broadcast.
-// For one sample per tile only the 4 coefficients under the nonzero bases are
-// fetched; for larger tiles the weights are stored as a 10-vector (zeros outside
-// span..span+3) so that the edge evaluation is 10 branch-free fmas against the
-// whole dequantised row, with no register indexing by span.
-// The codeword C[idx] is fetched once per edge and batch tile (from L2), scaled
-// by gain (and the Int8 scale) while it is unpacked, and reused for all BT
-// samples of the tile; bias is summed once per edge because the bases sum to 1.
+// VQ layers, one sample (KAN_BT = 1): only the 4 coefficients under the nonzero
+// bases are gathered (from L2), scaled by gain (and the Int8 scale) while they are
+// unpacked; bias is summed once per edge because the bases sum to 1.
+// Dense baseline (any batch tile): the 10 coefficients of an edge are read straight
+// from coef[in][out][10]; for tiles of 4 or 16 samples the weights are stored as a
+// 10-vector (zeros outside span..span+3) so that the edge evaluation is 10
+// branch-free fmas with no register indexing by span.
 // A workgroup is 4 waves: WJ of them side by side along j, 4/WJ interleaved
 // along i, whose partial sums meet in LDS.  Workgroups split i into chunks; the
 // chunk partial sums are written out and reduced in a fixed order by
@@ -299,6 +300,9 @@ hipError_t launch_jpl(const GatherCfg& c, const GatherArgs& a, dim3 grid, hipStr
   }
 }
 
+// The vector-ALU kernel serves VQ layers at batch 1 only (larger batches go to the fused
+// matrix-core kernel); the batch tiles 4 and 16 exist for the dense baseline.
+#if KAN_BT == 1
 template <typename IdxT>
 hipError_t launch_types(const GatherCfg& c, const GatherArgs& a, dim3 grid, hipStream_t s) {
   if (c.code == kCbI8) {
@@ -308,6 +312,7 @@ hipError_t launch_types(const GatherCfg& c, const GatherArgs& a, dim3 grid, hipS
   return c.gb_f16 ? launch_jpl<IdxT, __half, float, kCbF32>(c, a, grid, s)
                   : launch_jpl<IdxT, float, float, kCbF32>(c, a, grid, s);
 }
+#endif
 
 }  // namespace
 
@@ -318,7 +323,11 @@ hipError_t KAN_CAT(launch_gather_bt, KAN_BT)(const GatherCfg& c, const GatherArg
                                               hipStream_t s) {
   if (c.bt != KAN_BT) return hipErrorInvalidValue;
   if (c.code == kDense) return launch_jpl<uint16_t, float, float, kDense>(c, a, grid, s);
+#if KAN_BT == 1
   return c.idx_u32 ? launch_types<uint32_t>(c, a, grid, s) : launch_types<uint16_t>(c, a, grid, s);
+#else
+  return hipErrorInvalidValue;
+#endif
 }
 
 }  // namespace kan

@@ -83,9 +83,8 @@ hipError_t launch_prep_basis(const float* x, long long x_head_stride, uint2* W, 
                              int n_in, int B, int heads, hipStream_t);
 hipError_t launch_mfma(const MfmaArgs&, int tile_m, dim3 grid, hipStream_t);   // tile_m: samples per tile (64)
 
-// ---- fused matrix-core kernel for a single batch tile (2 <= B <= 64) -----------------
+// ---- fused gather + matrix-core kernel (batch tiles of 32 or 64 samples) --------------
 constexpr int kFusedTileN = 128;      // outputs per workgroup
-constexpr int kFusedMaxBatch = 64;
 
 struct FusedArgs {
   const float* x;              // [head or 1][B][n_in]
@@ -94,6 +93,7 @@ struct FusedArgs {
   long long dst_head_stride, dst_chunk_stride;
   int n_in, n_out, B;
   int rows_per_chunk;          // multiple of 8
+  int n_jt;                    // output tiles; blockIdx.x = batch_tile * n_jt + jt
   int apply_tanh;
   LayerPtrs h[kMaxGroup];
 };
