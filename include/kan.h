@@ -54,7 +54,8 @@ typedef enum kan_dtype { KAN_F32 = 0, KAN_F16 = 1, KAN_I8 = 2, KAN_U16 = 3, KAN_
  *   KAN_PATH_GATHER  the precise path: fp32 operands, fp32 accumulation; matches the
  *                    float64 definition to ~1e-6 (bound 1e-5).  Batch 1: one 4-byte
  *                    codeword-window gather per edge on the vector ALUs; from batch 2:
- *                    fused gather + fp32 matrix-core kernel.
+ *                    fused gather + fp32 matrix-core kernel.  Prepared layers (see
+ *                    kan_vq_prepare), batch <= 4: codebook buckets in LDS.
  *   KAN_PATH_MFMA    fp16 operands on the matrix cores, fp32 accumulation; ~3e-4
  *                    relative per layer (bound 2e-2).  Batch <= 64: fused gather +
  *                    MFMA kernel; above: coefficients dequantised once per call into
@@ -77,6 +78,8 @@ typedef struct kan_vq_layer {
   const void* codebook;  /* [K][10]                                                 */
   float scale;           /* Int8: value = scale * q.  Ignored for KAN_F32 codebooks */
   int32_t reserved;      /* set to 0                                                */
+  const void* prepared;  /* NULL, or the buffer kan_vq_prepare filled for this very
+                            layer (small-batch path, see below)                     */
 } kan_vq_layer;
 
 /* Spans and basis weights of step "index lookup" (section 4.1) for the cubic
@@ -104,6 +107,28 @@ size_t kan_dense_workspace_bytes(int32_t in, int32_t out, int64_t B);
 kan_status kan_dense_layer_forward(const float* coef, int32_t in, int32_t out, int32_t G,
                                    const float* x, int64_t B, float* y,
                                    void* ws, size_t ws_bytes, void* stream);
+
+/* One-time regrouping of a layer for the memory-bound small-batch regime (section 4.2:
+ * batch-1 inference moves the per-edge metadata once; section 4.3: the codebook must be
+ * served from on-chip memory).  The edges are regrouped by codebook bucket (8192 Int8 or
+ * 2048 fp32 consecutive codewords, 80 KB: what one CU's LDS holds beside the basis table),
+ * then by output, then by input; per edge the buffer keeps (input index u16, codeword id
+ * within the bucket u16, gain), and per output the sum of its biases (the bases sum to 1 on
+ * [-1,1], so the bias term does not depend on x).  With L->prepared set, the precise path
+ * serves batches up to 4 from this layout: every workgroup copies one bucket into LDS and
+ * streams that bucket's edges, so no lookup leaves the CU.  Values are unchanged (same
+ * products, different summation order: within the 1e-5 bound).
+ *   kan_vq_prepared_bytes  size of the buffer; 0 if the layer is not eligible (in > 4096),
+ *                          (size_t)-1 if the descriptor is invalid.  L->prepared is ignored.
+ *   kan_vq_prepare         fills `prepared` (device, 256-byte aligned, >= that size) on
+ *                          `stream`.  Requires in <= 4096 (else KAN_ERR_UNSUPPORTED).  The
+ *                          buffer depends on idx, gain, bias (not on the codebook values or
+ *                          scale) and must be rebuilt when they change.  The caller owns it
+ *                          and stores its address in L->prepared for later forward calls;
+ *                          the codebook must then be 16-byte aligned, else the forward call
+ *                          ignores the prepared buffer.                                  */
+size_t kan_vq_prepared_bytes(const kan_vq_layer* L);
+kan_status kan_vq_prepare(const kan_vq_layer* L, void* prepared, size_t prepared_bytes, void* stream);
 
 /* n_heads independent heads of n_layers VQ layers each, applied to the same
  * x[B][in0] (multi-expert deployment, section 5.6); tanh between layers, none

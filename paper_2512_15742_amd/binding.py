@@ -24,7 +24,7 @@ EXPORTS = [
     "kan_bspline_basis", "kan_vq_workspace_bytes", "kan_vq_layer_forward",
     "kan_dense_workspace_bytes", "kan_dense_layer_forward", "kan_vq_head_forward",
     "kan_vq_debug_gather", "kan_vq_count_bad_indices", "kan_prof_begin", "kan_prof_end",
-    "kan_status_string", "kan_vq_planned_kernel",
+    "kan_status_string", "kan_vq_planned_kernel", "kan_vq_prepared_bytes", "kan_vq_prepare",
 ]
 
 
@@ -33,7 +33,7 @@ class kan_vq_layer(C.Structure):
         ("n_in", C.c_int32), ("n_out", C.c_int32), ("G", C.c_int32), ("degree", C.c_int32),
         ("K", C.c_int32), ("idx_dtype", C.c_int32), ("gb_dtype", C.c_int32), ("cb_dtype", C.c_int32),
         ("idx", C.c_void_p), ("gain", C.c_void_p), ("bias", C.c_void_p), ("codebook", C.c_void_p),
-        ("scale", C.c_float), ("reserved", C.c_int32),
+        ("scale", C.c_float), ("reserved", C.c_int32), ("prepared", C.c_void_p),
     ]
 
 
@@ -83,6 +83,10 @@ def lib():
         L.kan_status_string.restype = C.c_char_p
         L.kan_vq_planned_kernel.argtypes = [LP, I64, I32, I32]
         L.kan_vq_planned_kernel.restype = C.c_char_p
+        L.kan_vq_prepared_bytes.argtypes = [LP]
+        L.kan_vq_prepared_bytes.restype = SZ
+        L.kan_vq_prepare.argtypes = [LP, P, SZ, P]
+        L.kan_vq_prepare.restype = I32
         _lib = L
     return _lib
 
@@ -132,7 +136,19 @@ class VQLayer:
             KAN_F16 if params.gain.dtype == np.float16 else KAN_F32,
             KAN_I8 if params.codebook.dtype == np.int8 else KAN_F32,
             self.idx.data_ptr(), self.gain.data_ptr(), self.bias.data_ptr(), self.codebook.data_ptr(),
-            self.scale, 0)
+            self.scale, 0, None)
+        self.prepared = None
+
+    def prepare(self):
+        """Builds the small-batch layout (kan_vq_prepare) and attaches it to the descriptor."""
+        self.prepared = kan_vq_prepare(self)
+        self.desc.prepared = self.prepared.data_ptr()
+        return self
+
+    def unprepare(self):
+        self.prepared = None
+        self.desc.prepared = None
+        return self
 
     @property
     def metadata_bytes(self):
@@ -245,6 +261,23 @@ def kan_vq_count_bad_indices(layer: VQLayer) -> int:
     cnt = torch.zeros(1, dtype=torch.int32, device=layer.idx.device)
     _check(lib().kan_vq_count_bad_indices(C.byref(layer.desc), _ptr(cnt), _stream_ptr()), "kan_vq_count_bad_indices")
     return int(cnt.item())
+
+
+def kan_vq_prepared_bytes(layer: VQLayer) -> int:
+    n = lib().kan_vq_prepared_bytes(C.byref(layer.desc))
+    if n == SIZE_INVALID:
+        raise KanError(KAN_ERR_SHAPE, "kan_vq_prepared_bytes")
+    return n
+
+
+def kan_vq_prepare(layer: VQLayer, out=None):
+    """Returns the uint8 CUDA tensor holding the regrouped layer (caller keeps it alive)."""
+    torch = _torch()
+    n = kan_vq_prepared_bytes(layer)
+    if out is None:
+        out = torch.empty(max(n, 1), dtype=torch.uint8, device=layer.idx.device)
+    _check(lib().kan_vq_prepare(C.byref(layer.desc), _ptr(out), out.numel(), _stream_ptr()), "kan_vq_prepare")
+    return out
 
 
 def kan_vq_planned_kernel(layer: VQLayer, B, n_heads=1, path=KAN_PATH_AUTO) -> str:

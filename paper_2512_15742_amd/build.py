@@ -34,6 +34,7 @@ UNITS = [
     ("kan_misc.hip", "kan_misc.o", []),
     ("kan_mfma.hip", "kan_mfma.o", []),
     ("kan_fused.hip", "kan_fused.o", []),
+    ("kan_bucket.hip", "kan_bucket.o", []),
     ("kan_gather.hip", "kan_gather_bt1.o", ["-DKAN_BT=1"]),
     ("kan_gather.hip", "kan_gather_bt4.o", ["-DKAN_BT=4"]),
     ("kan_gather.hip", "kan_gather_bt16.o", ["-DKAN_BT=16"]),

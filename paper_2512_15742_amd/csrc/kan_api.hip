@@ -64,12 +64,13 @@ kan_status validate_layer(const kan_vq_layer* L) {
 // Everything below is a pure function of shapes, dtypes, batch, head count and
 // pointer alignment, so the workspace query and the forward call always agree.
 
-enum PlanKind { kPlanGather = 0, kPlanMfma = 1, kPlanFused16 = 2, kPlanFused32 = 3 };
+enum PlanKind { kPlanGather = 0, kPlanMfma = 1, kPlanFused16 = 2, kPlanFused32 = 3, kPlanBucket = 4 };
 
 struct LayerPlan {
   GatherCfg cfg;
   int n_jt, n_bt, n_chunks, rows_per_chunk;
   int kind;          // PlanKind
+  int parts = 0, jw = 0;   // bucket path: workgroups per bucket, outputs per workgroup
   bool mfma;         // kind == kPlanMfma (coefficient + basis preparation, streaming contraction)
   const char* name;
 };
@@ -197,14 +198,49 @@ LayerPlan plan_fused(int n_in, int n_out, int64_t B, int n_heads, int idx_u32, i
   return p;
 }
 
+// Bucket path (prepared layers): one workgroup per (bucket, slice of the outputs, sample).
+// A workgroup occupies a whole CU (LDS), so the slices are cut to give every CU one.
+constexpr int64_t kBucketMaxBatch = 4;
+constexpr int kBucketWorkgroups = 256;
+
+LayerPlan plan_bucket(const kan_vq_layer& L, int64_t B, int n_heads) {
+  LayerPlan p;
+  p.mfma = false;
+  p.kind = kPlanBucket;
+  p.name = "kan_bucket";
+  p.cfg.bt = 1;
+  p.cfg.jpl = 1;
+  p.cfg.wj = 1;
+  p.cfg.idx_u32 = L.idx_dtype == KAN_U32;
+  p.cfg.gb_f16 = L.gb_dtype == KAN_F16;
+  p.cfg.code = L.cb_dtype == KAN_I8 ? kCbI8 : kCbF32;
+  const BucketGeom g = bucket_geometry(L.in, L.out, L.K, L.cb_dtype == KAN_I8, L.gb_dtype == KAN_F16);
+  const long long base = (long long)g.n_buckets * B * n_heads;
+  long long parts = (kBucketWorkgroups + base - 1) / base;
+  if (parts > L.out) parts = L.out;
+  if (parts < 1) parts = 1;
+  p.jw = (int)((L.out + parts - 1) / parts);
+  p.parts = (L.out + p.jw - 1) / p.jw;
+  p.n_jt = p.parts;
+  p.n_bt = (int)B;
+  p.n_chunks = g.n_buckets;          // the per-bucket sums are the partial sums
+  p.rows_per_chunk = L.in;
+  return p;
+}
+
+bool layer_prepared_ok(const kan_vq_layer& L) {
+  return L.prepared != nullptr && aligned(L.prepared, 256) && aligned(L.codebook, 16) && L.in <= kBucketMaxIn;
+}
+
 // Which kernels serve a layer:
+//   precise path, prepared layers, B <= kBucketMaxBatch: the bucket kernel (codebook in LDS);
 //   precise path (KAN_PATH_GATHER, and AUTO below batch 32): B = 1 the window-gather kernel,
 //     B >= 2 the fused kernel with fp32 matrix-core operands (the fp32 FMA kernel remains the
 //     dense baseline's);
 //   fp16 path (KAN_PATH_MFMA, and AUTO from batch 32): up to kHalfFusedMaxBatch the fused
 //     kernel with fp16 operands, above that coefficient/basis preparation + the streaming
 //     contraction.
-LayerPlan plan_vq(const kan_vq_layer& L, int64_t B, int n_heads, bool vec_ok, int32_t path) {
+LayerPlan plan_vq(const kan_vq_layer& L, int64_t B, int n_heads, bool vec_ok, bool prepared_ok, int32_t path) {
   const int code = L.cb_dtype == KAN_I8 ? kCbI8 : kCbF32;
   const int u32 = L.idx_dtype == KAN_U32, f16 = L.gb_dtype == KAN_F16;
   const bool half_path = path == KAN_PATH_MFMA || (path == KAN_PATH_AUTO && B >= kAutoMfmaBatch);
@@ -212,6 +248,7 @@ LayerPlan plan_vq(const kan_vq_layer& L, int64_t B, int n_heads, bool vec_ok, in
     if (B <= kHalfFusedMaxBatch) return plan_fused(L.in, L.out, B, n_heads, u32, f16, code, false);
     return plan_mfma(L.in, L.out, B, n_heads, u32, f16, code);
   }
+  if (prepared_ok && B <= kBucketMaxBatch) return plan_bucket(L, B, n_heads);
   if (B >= 2) return plan_fused(L.in, L.out, B, n_heads, u32, f16, code, true);
   return plan_gather(L.in, L.out, B, n_heads, u32, f16, code, vec_ok);
 }
@@ -261,8 +298,9 @@ struct WsPtrs {
 // One layer of a group of heads.  `a` carries x, shapes and the per-head pointers;
 // `final_dst` receives act(y).  Gather path: main kernel, then (if i was split) the
 // fixed-order reduction.  Matrix-core path: coefficient and basis preparation first.
-kan_status run_layer_group(const LayerPlan& p, GatherArgs& a, int heads, bool x_shared, float* final_dst,
-                           long long final_head_stride, const WsPtrs& w, int apply_tanh, hipStream_t s) {
+kan_status run_layer_group(const LayerPlan& p, GatherArgs& a, const void* const* prepared, int heads,
+                           bool x_shared, float* final_dst, long long final_head_stride, const WsPtrs& w,
+                           int apply_tanh, hipStream_t s) {
   const long long count = (long long)a.B * a.n_out;
   const bool split = p.n_chunks > 1;
   float* dst = split ? w.partial : final_dst;
@@ -307,6 +345,35 @@ kan_status run_layer_group(const LayerPlan& p, GatherArgs& a, int heads, bool x_
     for (int h = 0; h < heads; ++h) m.scale[h] = p.cfg.code == kCbI8 ? a.h[h].scale : 1.0f;
     dim3 grid((unsigned)(p.n_jt * p.n_bt), (unsigned)p.n_chunks, (unsigned)heads);
     st = run(p.name, s, [&] { return launch_mfma(m, p.cfg.bt, grid, s); });
+  } else if (p.kind == kPlanBucket) {
+    const bool i8 = p.cfg.code == kCbI8;
+    const BucketGeom g = bucket_geometry(a.n_in, a.n_out, (int)(a.cb_bytes / (i8 ? 10 : 40)), i8, p.cfg.gb_f16 != 0);
+    BucketArgs k;
+    memset(&k, 0, sizeof(k));
+    k.x = a.x;
+    k.x_head_stride = a.x_head_stride;
+    k.dst = dst;
+    k.dst_head_stride = dst_head_stride;
+    k.dst_chunk_stride = dst_chunk_stride;
+    k.n_in = a.n_in;
+    k.n_out = a.n_out;
+    k.B = a.B;
+    k.n_buckets = g.n_buckets;
+    k.jw = p.jw;
+    k.rows_shift = g.rows_shift;
+    k.cb_bytes = a.cb_bytes;
+    k.apply_tanh = tanh_in_kernel;
+    k.off_seg = (long long)g.off_seg;
+    k.off_bias = (long long)g.off_bias;
+    k.off_i = (long long)g.off_i;
+    k.off_q = (long long)g.off_q;
+    k.off_g = (long long)g.off_g;
+    for (int h = 0; h < heads; ++h) {
+      k.h[h].prepared = prepared[h];
+      k.h[h].cb = a.h[h].cb;
+      k.h[h].scale = a.h[h].scale;
+    }
+    st = run(p.name, s, [&] { return launch_bucket(i8, p.cfg.gb_f16 != 0, k, p.parts, heads, s); });
   } else if (p.kind == kPlanFused16 || p.kind == kPlanFused32) {
     const bool f32 = p.kind == kPlanFused32;
     FusedArgs f;
@@ -369,9 +436,12 @@ kan_status plan_head(const kan_vq_layer* layers, int32_t n_layers, int32_t n_hea
   plans->clear();
   for (int l = 0; l < n_layers; ++l) {
     const kan_vq_layer& R = layers[l];
-    bool vec_ok = true;
-    for (int h = 0; h < n_heads; ++h) vec_ok = vec_ok && layer_vec_ok(layers[(size_t)h * n_layers + l]);
-    LayerPlan p = plan_vq(R, B, group, vec_ok, path);
+    bool vec_ok = true, prepared_ok = true;
+    for (int h = 0; h < n_heads; ++h) {
+      vec_ok = vec_ok && layer_vec_ok(layers[(size_t)h * n_layers + l]);
+      prepared_ok = prepared_ok && layer_prepared_ok(layers[(size_t)h * n_layers + l]);
+    }
+    LayerPlan p = plan_vq(R, B, group, vec_ok, prepared_ok, path);
     plans->push_back(p);
     auto grow = [](size_t& dst, size_t v) { if (v > dst) dst = v; };
     grow(ws->partial, partial_bytes(p, R.out, B, group));
@@ -457,6 +527,7 @@ kan_status kan_vq_head_forward(const kan_vq_layer* layers, int32_t n_layers, int
     for (int h0 = 0; h0 < n_heads; h0 += kMaxGroup) {
       const int heads = (n_heads - h0) < kMaxGroup ? (n_heads - h0) : kMaxGroup;
       GatherArgs a;
+      const void* prepared[kMaxGroup];
       memset(&a, 0, sizeof(a));
       a.x = src + (long long)h0 * src_head_stride;
       a.x_head_stride = src_head_stride;
@@ -473,8 +544,9 @@ kan_status kan_vq_head_forward(const kan_vq_layer* layers, int32_t n_layers, int
         a.h[h].bias = L.bias;
         a.h[h].cb = L.codebook;
         a.h[h].scale = L.scale;
+        prepared[h] = L.prepared;
       }
-      st = run_layer_group(plans[l], a, heads, l == 0, dst + (long long)h0 * dst_head_stride, dst_head_stride, w,
+      st = run_layer_group(plans[l], a, prepared, heads, l == 0, dst + (long long)h0 * dst_head_stride, dst_head_stride, w,
                            last ? 0 : 1, s);
       if (st != KAN_OK) return st;
     }
@@ -518,7 +590,26 @@ kan_status kan_dense_layer_forward(const float* coef, int32_t in, int32_t out, i
   WsPtrs w;
   memset(&w, 0, sizeof(w));
   w.partial = (float*)ws;
-  return run_layer_group(p, a, 1, true, y, (long long)B * out, w, 0, (hipStream_t)stream);
+  return run_layer_group(p, a, nullptr, 1, true, y, (long long)B * out, w, 0, (hipStream_t)stream);
+}
+
+size_t kan_vq_prepared_bytes(const kan_vq_layer* L) {
+  if (validate_layer(L) != KAN_OK) return (size_t)-1;
+  if (L->in > kBucketMaxIn) return 0;
+  return bucket_geometry(L->in, L->out, L->K, L->cb_dtype == KAN_I8, L->gb_dtype == KAN_F16).total;
+}
+
+kan_status kan_vq_prepare(const kan_vq_layer* L, void* prepared, size_t prepared_bytes, void* stream) {
+  kan_status st = validate_layer(L);
+  if (st != KAN_OK) return st;
+  if (L->in > kBucketMaxIn) return KAN_ERR_UNSUPPORTED;
+  const BucketGeom g = bucket_geometry(L->in, L->out, L->K, L->cb_dtype == KAN_I8, L->gb_dtype == KAN_F16);
+  if (!prepared || !aligned(prepared, 256) || prepared_bytes < g.total) return KAN_ERR_WORKSPACE;
+  LayerPtrs h = {L->idx, L->gain, L->bias, L->codebook, L->scale, 0};
+  hipStream_t s = (hipStream_t)stream;
+  return run("kan_vq_prepare", s, [&] {
+    return launch_bucket_prepare(h, L->idx_dtype == KAN_U32, L->gb_dtype == KAN_F16, L->in, L->out, g, prepared, s);
+  });
 }
 
 kan_status kan_vq_debug_gather(const kan_vq_layer* L, uint32_t* ids, float* rows, void* stream) {
@@ -546,7 +637,8 @@ kan_status kan_vq_count_bad_indices(const kan_vq_layer* L, uint32_t* count, void
 
 const char* kan_vq_planned_kernel(const kan_vq_layer* L, int64_t B, int32_t n_heads, int32_t path) {
   if (validate_layer(L) != KAN_OK || check_path(path) != KAN_OK || B < 1 || n_heads < 1) return "invalid";
-  return plan_vq(*L, B, n_heads < kMaxGroup ? n_heads : kMaxGroup, layer_vec_ok(*L), path).name;
+  return plan_vq(*L, B, n_heads < kMaxGroup ? n_heads : kMaxGroup, layer_vec_ok(*L), layer_prepared_ok(*L), path)
+      .name;
 }
 
 kan_status kan_prof_begin(int32_t max_launches) {

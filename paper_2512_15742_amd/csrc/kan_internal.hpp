@@ -100,6 +100,68 @@ struct FusedArgs {
 
 hipError_t launch_fused(const GatherCfg&, const FusedArgs&, bool f32, dim3 grid, hipStream_t);
 
+// ---- bucketed small-batch path (prepared layers) ----------------------------------
+// A prepared layer holds its edges regrouped by codebook bucket (a run of consecutive
+// codewords whose rows fit in LDS) and, inside a bucket, by output j then input i; a
+// segment is the run of edges of one (bucket, j).  Per edge it keeps the input index, the
+// codeword id relative to the bucket and the gain; the biases of an output are summed once
+// (the bases sum to 1, so they do not depend on x).
+constexpr int kBucketBytes = 81920;     // codebook bytes per bucket: 8192 Int8 rows or 2048 fp32 rows
+constexpr int kBucketMaxIn = 4096;      // the basis table of all inputs lives in LDS beside the bucket
+constexpr int kBucketThreads = 1024;
+
+struct BucketGeom {
+  int rows_shift;      // log2(codewords per bucket)
+  int n_buckets;
+  size_t off_seg;      // uint32 [n_buckets * n_out + 1] first edge of every segment
+  size_t off_bias;     // float  [n_out]                 sum over i of bias_ij
+  size_t off_i;        // uint16 [E]                     input index
+  size_t off_q;        // uint16 [E]                     codeword id - first id of the bucket
+  size_t off_g;        // gain   [E]                     in the layer's gain dtype
+  size_t total;
+};
+
+inline BucketGeom bucket_geometry(int n_in, int n_out, int K, bool cb_i8, bool gb_f16) {
+  auto up = [](size_t v) { return (v + 255) / 256 * 256; };
+  BucketGeom g;
+  g.rows_shift = cb_i8 ? 13 : 11;
+  g.n_buckets = (K + (1 << g.rows_shift) - 1) >> g.rows_shift;
+  const size_t E = (size_t)n_in * n_out;
+  g.off_seg = 0;
+  g.off_bias = up(((size_t)g.n_buckets * n_out + 1) * 4);
+  g.off_i = g.off_bias + up((size_t)n_out * 4);
+  g.off_q = g.off_i + up(E * 2);
+  g.off_g = g.off_q + up(E * 2);
+  g.total = g.off_g + up(E * (gb_f16 ? 2 : 4));
+  return g;
+}
+
+struct BucketHead {
+  const void* prepared;
+  const void* cb;
+  float scale;
+  int pad;
+};
+
+struct BucketArgs {
+  const float* x;              // [head or 1][B][n_in]
+  long long x_head_stride;     // 0 when all heads share the input
+  float* dst;                  // final values (one bucket) or per-bucket partial sums
+  long long dst_head_stride, dst_chunk_stride;
+  int n_in, n_out, B;
+  int n_buckets, jw;           // jw: outputs per workgroup; blockIdx.x = part * n_buckets + bucket
+  int rows_shift;
+  long long cb_bytes;          // whole codebook, bytes
+  int apply_tanh;              // honoured only when n_buckets == 1
+  long long off_seg, off_bias, off_i, off_q, off_g;
+  BucketHead h[kMaxGroup];
+};
+
+hipError_t launch_bucket(bool cb_i8, bool gb_f16, const BucketArgs&, int parts, int heads, hipStream_t);
+// One-time regrouping of a layer into the layout above (three kernels: count, scan, fill).
+hipError_t launch_bucket_prepare(const LayerPtrs&, int idx_u32, int gb_f16, int n_in, int n_out,
+                                 const BucketGeom&, void* prepared, hipStream_t);
+
 // ---- reduction of i-chunk partial sums ------------------------------------------
 // dst[n] = act( sum_c partial[c * chunk_stride + n] ), n < count, for every head.
 hipError_t launch_reduce(const float* partial, long long head_stride, long long chunk_stride,

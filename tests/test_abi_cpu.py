@@ -29,8 +29,9 @@ def test_exports_match_header():
 
 
 def test_struct_layout_matches_header():
-    # 8 int32, 4 pointers, float, int32 -> 72 bytes on LP64; profile record 56 + 4 + 4
-    assert C.sizeof(kb.kan_vq_layer) == 72
+    # 8 int32, 4 pointers, float, int32, pointer -> 80 bytes on LP64; profile record 56 + 4 + 4
+    assert C.sizeof(kb.kan_vq_layer) == 80
+    assert kb.kan_vq_layer.prepared.offset == 72
     assert C.sizeof(kb.kan_prof_record) == 64
 
 
@@ -43,7 +44,7 @@ def test_status_strings():
 def _desc(**kw):
     base = dict(n_in=8, n_out=8, G=10, degree=3, K=16, idx_dtype=kb.KAN_U16, gb_dtype=kb.KAN_F32,
                 cb_dtype=kb.KAN_F32, idx=0x1000, gain=0x2000, bias=0x3000, codebook=0x4000,
-                scale=1.0, reserved=0)
+                scale=1.0, reserved=0, prepared=None)
     base.update(kw)
     return kb.kan_vq_layer(**base)
 
@@ -106,6 +107,34 @@ def test_workspace_required_and_checked():
     assert L.kan_vq_workspace_bytes(C.byref(d), 1, 1, 0, kb.KAN_PATH_AUTO) == 0
     assert L.kan_dense_workspace_bytes(2048, 512, 1) > 0
     assert L.kan_dense_workspace_bytes(0, 512, 1) == kb.SIZE_INVALID
+
+
+def test_prepare_arguments_and_planning():
+    L = kb.lib()
+    d = _desc(n_in=2048, n_out=1024, K=65536, cb_dtype=kb.KAN_I8, gb_dtype=kb.KAN_F16)
+    need = L.kan_vq_prepared_bytes(C.byref(d))
+    # segment table + bias sums + 6 bytes per edge (u16 input, u16 local id, fp16 gain)
+    E = 2048 * 1024
+    assert need % 256 == 0 and 6 * E < need < 6 * E + (1 << 16)
+    assert L.kan_vq_prepare(C.byref(d), None, need, None) == kb.KAN_ERR_WORKSPACE
+    assert L.kan_vq_prepare(C.byref(d), FAKE, need - 1, None) == kb.KAN_ERR_WORKSPACE
+    assert L.kan_vq_prepare(C.byref(d), C.c_void_p(0x10010), need, None) == kb.KAN_ERR_WORKSPACE
+    assert L.kan_vq_prepare(None, FAKE, need, None) == kb.KAN_ERR_NULL
+    wide = _desc(n_in=4097, n_out=8)
+    assert L.kan_vq_prepared_bytes(C.byref(wide)) == 0
+    assert L.kan_vq_prepare(C.byref(wide), FAKE, 1 << 30, None) == kb.KAN_ERR_UNSUPPORTED
+    assert L.kan_vq_prepared_bytes(C.byref(_desc(G=8))) == kb.SIZE_INVALID
+    # planning: a prepared layer takes the bucket kernel on the precise path up to batch 4
+    assert L.kan_vq_planned_kernel(C.byref(d), 1, 1, kb.KAN_PATH_GATHER) == b"kan_gather_bt1"
+    d.prepared = 0x100000
+    assert L.kan_vq_planned_kernel(C.byref(d), 1, 1, kb.KAN_PATH_GATHER) == b"kan_bucket"
+    assert L.kan_vq_planned_kernel(C.byref(d), 4, 1, kb.KAN_PATH_AUTO) == b"kan_bucket"
+    assert L.kan_vq_planned_kernel(C.byref(d), 5, 1, kb.KAN_PATH_GATHER) == b"kan_fused_f32"
+    assert L.kan_vq_planned_kernel(C.byref(d), 1, 1, kb.KAN_PATH_MFMA) == b"kan_fused_f16"
+    # per-bucket partial sums: 8 buckets x out floats
+    assert L.kan_vq_workspace_bytes(C.byref(d), 1, 1, 1, kb.KAN_PATH_GATHER) == 8 * 1024 * 4
+    d.codebook = 0x4008                                  # bucket copies need 16-byte alignment
+    assert L.kan_vq_planned_kernel(C.byref(d), 1, 1, kb.KAN_PATH_GATHER) == b"kan_gather_bt1"
 
 
 def test_head_table_consistency():

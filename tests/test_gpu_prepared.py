@@ -1,0 +1,196 @@
+"""GPU parity of the small-batch path over prepared layers (codebook buckets in LDS).
+
+The regrouped layout is integer work and must be bit-exact: the expected layout is built
+here with numpy straight from the layer's idx/gain/bias.  The forward results are compared
+with the float64 oracle under the same 1e-5 bound as the other fp32 kernels."""
+import dataclasses
+
+import numpy as np
+import pytest
+
+from oracle import kan_oracle as ko
+from paper_2512_15742_amd import synth
+
+from kan_testlib import TOL_FP32, check_layer_output, gpu_layers, to_dev
+
+pytestmark = pytest.mark.gpu
+
+torch = pytest.importorskip("torch")
+
+
+@pytest.fixture(scope="module")
+def kb():
+    if not torch.cuda.is_available():
+        pytest.skip("no GPU")
+    from paper_2512_15742_amd import binding
+    binding.lib()
+    return binding
+
+
+def _expected_layout(P):
+    """(seg_off, bias_sum, i, q, gain) of the regrouped layer: bucket-major, then j, then i."""
+    rows = 8192 if P.codebook.dtype == np.int8 else 2048
+    n_in, n_out = P.idx.shape
+    nb = (P.K + rows - 1) // rows
+    idx = P.idx.astype(np.int64)
+    bucket = idx // rows
+    ii, jj = np.meshgrid(np.arange(n_in), np.arange(n_out), indexing="ij")
+    order = np.lexsort((ii.ravel(), jj.ravel(), bucket.ravel()))          # last key is primary
+    counts = np.zeros(nb * n_out, dtype=np.int64)
+    np.add.at(counts, (bucket * n_out + jj).ravel(), 1)
+    seg = np.concatenate([[0], np.cumsum(counts)]).astype(np.uint32)
+    bias_sum = np.zeros(n_out, dtype=np.float64)
+    for i in range(n_in):                                                  # same order as the kernel: i upwards
+        bias_sum += P.bias[i].astype(np.float64)
+    return (seg, bias_sum.astype(np.float32), ii.ravel()[order].astype(np.uint16),
+            (idx.ravel()[order] % rows).astype(np.uint16), P.gain.ravel()[order])
+
+
+def _read_layout(buf, P):
+    up = lambda v: (v + 255) // 256 * 256
+    rows = 8192 if P.codebook.dtype == np.int8 else 2048
+    n_in, n_out = P.idx.shape
+    nb = (P.K + rows - 1) // rows
+    E = n_in * n_out
+    raw = buf.cpu().numpy()
+    o = 0
+    seg = raw[o:o + (nb * n_out + 1) * 4].view(np.uint32); o += up((nb * n_out + 1) * 4)
+    bias = raw[o:o + n_out * 4].view(np.float32); o += up(n_out * 4)
+    pi = raw[o:o + 2 * E].view(np.uint16); o += up(2 * E)
+    pq = raw[o:o + 2 * E].view(np.uint16); o += up(2 * E)
+    gsz = P.gain.dtype.itemsize
+    pg = raw[o:o + gsz * E].view(P.gain.dtype); o += up(gsz * E)
+    assert o == raw.size
+    return seg, bias, pi, pq, pg
+
+
+@pytest.mark.parametrize("n_in,n_out,K,cb,gb,idxd", [
+    (37, 29, 20000, "i8", "f16", "u16"),       # 3 buckets, the last one partial
+    (64, 32, 256, "f32", "f32", "u16"),        # one bucket
+    (130, 300, 70000, "f32", "f16", "u32"),    # 35 fp32 buckets
+    (2048, 64, 65536, "i8", "f16", "u16"),
+])
+def test_prepared_layout_bit_exact(kb, n_in, n_out, K, cb, gb, idxd):
+    P = synth.make_layer(n_in + K, n_in, n_out, K, cb_dtype=cb, gb_dtype=gb, idx_dtype=idxd)
+    P.idx.reshape(-1)[:4] = [0, K - 1, min(K - 1, 8191), min(K - 1, 8192)]
+    L = kb.VQLayer(P).prepare()
+    assert L.prepared.numel() == kb.kan_vq_prepared_bytes(L)
+    got = _read_layout(L.prepared, P)
+    exp = _expected_layout(P)
+    for name, g, e in zip(("seg", "bias_sum", "i", "q", "gain"), got, exp):
+        assert np.array_equal(g, e), name
+
+
+def _forward_prepared(kb, P, x, expect_kernel="kan_bucket"):
+    L = kb.VQLayer(P).prepare()
+    assert kb.kan_vq_planned_kernel(L, x.shape[0], 1, kb.KAN_PATH_GATHER) == expect_kernel
+    return kb.kan_vq_layer_forward(L, to_dev(x), path=kb.KAN_PATH_GATHER).cpu().numpy()
+
+
+def test_config1_prepared(kb):
+    (P,), x = synth.config1()
+    for B in (1, 4):
+        y = _forward_prepared(kb, P, x[:B])
+        y_ref, A = ko.vq_layer_forward(x[:B], **P.as_dict(), return_abs=True)
+        rep = ko.error_report(y, y_ref, A)
+        assert rep["headline"] <= TOL_FP32 and rep["strict"] <= TOL_FP32, rep
+
+
+def test_config2_prepared_batch1(kb):
+    (P,), x = synth.config2(1)
+    y = _forward_prepared(kb, P, x)
+    check_layer_output(y, x, P, TOL_FP32)
+
+
+@pytest.mark.parametrize("B", [1, 2, 4])
+def test_config3_head_prepared(kb, B):
+    Ps, x = synth.config3(B)
+    Ls = [L.prepare() for L in gpu_layers(Ps)]
+    xd = to_dev(x)
+    assert kb.kan_vq_planned_kernel(Ls[0], B, 1, kb.KAN_PATH_AUTO) == "kan_bucket"
+    ws = torch.empty(kb.kan_vq_workspace_bytes([Ls], B, kb.KAN_PATH_AUTO), dtype=torch.uint8, device="cuda")
+    y = kb.kan_vq_head_forward([Ls], xd, path=kb.KAN_PATH_AUTO, ws=ws)[0].cpu().numpy()
+    y_ref, hidden_ref = ko.vq_head_forward(x, [p.as_dict() for p in Ps], return_hidden=True)
+    assert ko.error_report(y, y_ref)["headline"] <= TOL_FP32
+    # the hidden activation at the start of the workspace, and layer 2 from exactly those fp32 inputs
+    hid = ws[:B * 1024 * 4].view(torch.float32).reshape(B, 1024).cpu().numpy()
+    assert ko.error_report(hid, hidden_ref[0])["headline"] <= TOL_FP32
+    y2_ref = ko.vq_layer_forward(hid, **Ps[1].as_dict())
+    assert ko.error_report(y, y2_ref)["headline"] <= TOL_FP32
+    # same bits on a second call, and the unprepared kernels agree within the bound
+    y_again = kb.kan_vq_head_forward([Ls], xd, path=kb.KAN_PATH_AUTO, ws=ws)[0].cpu().numpy()
+    assert np.array_equal(y, y_again)
+    y_plain = kb.kan_vq_head_forward([gpu_layers(Ps)], xd, path=kb.KAN_PATH_GATHER)[0].cpu().numpy()
+    assert np.abs(y_plain - y).max() <= 2 * TOL_FP32 * np.abs(y_ref).max()
+    y1 = kb.kan_vq_layer_forward(Ls[0], xd, path=kb.KAN_PATH_GATHER).cpu().numpy()
+    check_layer_output(y1, x, Ps[0], TOL_FP32, full=False, seed=B)
+
+
+@pytest.mark.parametrize("variant", ["i8", "f32"])
+def test_config5_shape_prepared_batch2(kb, variant):
+    """The 4096 x 4096, K = 262,144 layer of configuration 5 (32 Int8 / 128 fp32 buckets) at batch 2."""
+    (P,), x = synth.config5(variant, B=2)
+    y = _forward_prepared(kb, P, x)
+    assert np.isfinite(y).all()
+    check_layer_output(y, x, P, TOL_FP32, n_samples=64, full=False, seed=5)
+
+
+@pytest.mark.parametrize("n_in,n_out,K,B", [(1, 1, 1, 1), (3, 21, 5, 2), (130, 67, 9000, 3), (257, 530, 20000, 1),
+                                            (1000, 264, 8193, 4), (4096, 8, 1000, 1), (40, 1500, 65536, 1)])
+@pytest.mark.parametrize("cb,gb", [("i8", "f16"), ("f32", "f32")])
+def test_ragged_shapes_prepared(kb, n_in, n_out, K, B, cb, gb):
+    P = synth.make_layer(n_in * 7 + n_out, n_in, n_out, K, cb_dtype=cb, gb_dtype=gb)
+    x = synth.make_x(B, B, n_in)
+    x[0, 0] = 1.0
+    x[-1, -1] = -1.0
+    y = _forward_prepared(kb, P, x)
+    y_ref, A = ko.vq_layer_forward(x, **P.as_dict(), return_abs=True)
+    rep = ko.error_report(y, y_ref, A)
+    assert rep["headline"] <= TOL_FP32 and rep["strict"] <= TOL_FP32, rep
+
+
+def test_long_and_empty_segments(kb):
+    """All edges of some outputs in one bucket (segments of 1500 edges: several chunks per
+    wave), none in the others (empty segments)."""
+    P = synth.make_layer(5, 1500, 40, 30000, cb_dtype="i8", gb_dtype="f16")
+    P.idx[:, :20] = P.idx[:, :20] % 8192 + 8192          # outputs 0..19 live in bucket 1 only
+    P.idx[:, 20:] = P.idx[:, 20:] % 100                  # outputs 20..39 in bucket 0 only
+    x = synth.make_x(3, 2, 1500)
+    y = _forward_prepared(kb, P, x)
+    y_ref, A = ko.vq_layer_forward(x, **P.as_dict(), return_abs=True)
+    rep = ko.error_report(y, y_ref, A)
+    assert rep["headline"] <= TOL_FP32 and rep["strict"] <= TOL_FP32, rep
+
+
+def test_grouped_heads_prepared(kb):
+    B = 2
+    heads_p = [[synth.make_layer(500 + h, 96, 48, 20000, cb_dtype="i8", gb_dtype="f16"),
+                synth.make_layer(700 + h, 48, 7, 300, cb_dtype="i8", gb_dtype="f16")] for h in range(5)]
+    x = synth.make_x(1, B, 96)
+    heads = [[L.prepare() for L in gpu_layers(ps)] for ps in heads_p]
+    y = kb.kan_vq_head_forward(heads, to_dev(x), path=kb.KAN_PATH_GATHER).cpu().numpy()
+    for h in range(5):
+        y_ref = ko.vq_head_forward(x, [p.as_dict() for p in heads_p[h]])
+        assert ko.error_report(y[h], y_ref)["headline"] <= TOL_FP32
+    # one head without a prepared buffer sends the whole group to the ordinary kernels
+    heads[3][0].unprepare()
+    assert kb.kan_vq_planned_kernel(heads[3][0], B, 5, kb.KAN_PATH_GATHER) != "kan_bucket"
+    y2 = kb.kan_vq_head_forward(heads, to_dev(x), path=kb.KAN_PATH_GATHER).cpu().numpy()
+    assert np.abs(y2 - y).max() <= 2 * TOL_FP32 * np.abs(y).max()
+
+
+def test_unused_codeword_rows_may_hold_anything(kb):
+    """Rows no edge refers to (here NaN) must not leak into the sums, not even through
+    lanes that run past the end of a segment."""
+    P = synth.make_layer(8, 70, 33, 3000, cb_dtype="f32", gb_dtype="f32")
+    P.idx[P.idx == 0] = 1
+    P.idx[P.idx == 2048] = 2049
+    cb = P.codebook.copy()
+    cb[0] = np.nan                                       # row 0 of buckets 0 and 1
+    cb[2048] = np.nan
+    x = synth.make_x(2, 1, 70)
+    P2 = dataclasses.replace(P, codebook=cb)
+    y = _forward_prepared(kb, P2, x)
+    y_ref = ko.vq_layer_forward(x, **P.as_dict())
+    assert np.isfinite(y).all()
+    assert ko.error_report(y, y_ref)["headline"] <= TOL_FP32
