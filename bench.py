@@ -53,6 +53,8 @@ def parse():
     ap.add_argument("--batch", type=int, default=1024)
     ap.add_argument("--path", default="auto", choices=["auto", "gather", "mfma"])
     ap.add_argument("--no-cpu-baseline", action="store_true")
+    ap.add_argument("--no-prepare", action="store_true",
+                    help="batch <= 4 on the parameters as given (no kan_vq_prepare regrouping)")
     ap.add_argument("--copies", type=int, default=0, help="parameter copies to rotate over (0 = enough to exceed the memory-side cache)")
     ap.add_argument("--sweep", action="store_true",
                     help="instead of the headline run, time every benchmark configuration (one JSON line each)")
@@ -86,7 +88,10 @@ def kernel_times(kb, torch, fn, steps, warmup):
             for k, v in rec.items()}
 
 
-def run_batch(kb, torch, synth, copies, B, path, steps, warmup):
+def run_batch(kb, torch, synth, copies, B, path, steps, warmup, prepared=False):
+    for cp in copies:
+        for L in cp:
+            L.use_prepared(prepared)
     x = torch.from_numpy(synth.make_x(3900 + B, B, 2048, "uniform")).cuda()
     ws_bytes = kb.kan_vq_workspace_bytes([copies[0]], B, path)
     ws = torch.empty(max(ws_bytes, 256), dtype=torch.uint8, device="cuda")
@@ -196,15 +201,30 @@ def main():
             dst.copy_(src)
         torch.cuda.synchronize()
 
+    # one-time regrouping of every copy for the small-batch path (kan_vq_prepare), untimed
+    torch.cuda.synchronize()
+    t0 = time.perf_counter()
+    for cp in copies:
+        for L in cp:
+            L.prepare()
+    torch.cuda.synchronize()
+    prepare_ms_per_head = 1e3 * (time.perf_counter() - t0) / len(copies)
+
+    main_kernels = ("kan_gather", "kan_mfma", "kan_fused", "kan_bucket")
     results = {}
-    for B in sorted({1, args.batch}):
+    for B, prepared in [(b, b <= 4 and not args.no_prepare) for b in sorted({1, args.batch})] + \
+                       ([] if args.no_prepare else [(1, False)]):
         steps = args.steps if B > 1 else max(args.steps, 500)
-        t_cold, t_warm, kt = run_batch(kb, torch, synth, copies, B, path, steps, args.warmup)
+        t_cold, t_warm, kt = run_batch(kb, torch, synth, copies, B, path, steps, args.warmup, prepared)
         ee = sum(edges) * B
-        dom = max((k for k in kt if k.startswith("kan_gather") or k.startswith("kan_mfma")),
+        dom = max((k for k in kt if k.startswith(main_kernels)),
                   key=lambda k: kt[k]["avg_us"] * kt[k]["launches"])
-        results[B] = {
-            "batch": B, "steps": steps,
+        key = B if (prepared or B > 4 or args.no_prepare) else "1_unprepared"
+        for cp in copies:
+            for L in cp:
+                L.use_prepared(prepared)
+        results[key] = {
+            "batch": B, "steps": steps, "prepared_layers": bool(prepared),
             "ms_per_step": 1e3 * t_cold, "edge_evals_per_s": ee / t_cold,
             "metadata_GBps": sum(meta) / t_cold / 1e9,
             "ms_per_step_cache_warm": 1e3 * t_warm, "edge_evals_per_s_cache_warm": ee / t_warm,
@@ -222,11 +242,12 @@ def main():
     launches_per_step = r["kernels_launches_per_step"][dom]
     avg_s = r["kernels_avg_us"][dom] * 1e-6
     edges_per_launch = sum(edges) / launches_per_step
-    is_mfma = dom.startswith("kan_mfma")
+    is_mfma = dom.startswith(("kan_mfma", "kan_fused"))
     if B >= 16:
         # compute-bound regime (the metadata stream stops being the limit near B = 12-20)
         flops = edges_per_launch * (B * FLOP_PER_EDGE_EVAL + FLOP_PER_EDGE_RECON)
-        peak = PEAK_BF16_MFMA_TFLOPS if is_mfma else PEAK_FP32_VECTOR_TFLOPS
+        # fp16 operands price against the fp16/bf16 matrix-core peak, fp32 operands against the fp32 one
+        peak = PEAK_BF16_MFMA_TFLOPS if (is_mfma and dom != "kan_fused_f32") else PEAK_FP32_VECTOR_TFLOPS
         roof = {"bound": "mfma" if is_mfma else "alu", "achieved": flops / avg_s / 1e12, "peak": peak,
                 "unit": "TFLOP/s", "kernel": dom, "avg_launch_us": r["kernels_avg_us"][dom],
                 "traffic": MEASURED_TRAFFIC.get((dom, B))}
@@ -272,7 +293,7 @@ def main():
         "value": r["edge_evals_per_s"], "unit": "edge-evals/s",
         "n_gpus": 1, "steps": r["steps"], "warmup": args.warmup, "ms_per_step": r["ms_per_step"],
         "higher_is_better": True, "scaling": "weak", "vs_baseline": None,
-        "dtype": "bf16" if roof["kernel"].startswith("kan_mfma") else "f32", "data": "synthetic",
+        "dtype": "f16" if roof["kernel"].startswith(("kan_mfma", "kan_fused_f16")) else "f32", "data": "synthetic",
         "config": {"workload": f"config 3: two-layer Int8 VQ-KAN head 2048->1024->256, K=65536 per layer, "
                                f"uint16 idx, fp16 gain/bias, tanh between layers, batch {B}",
                    "batch": B, "path": args.path, "parameter_copies_rotated": n_copies,
@@ -282,7 +303,10 @@ def main():
         "cpu_baseline": cpu,
         "batch1": r1,
         "batch%d" % B: r,
+        "prepare_ms_per_head": prepare_ms_per_head,
     }
+    if "1_unprepared" in results:
+        out["batch1_unprepared"] = results["1_unprepared"]
     print(json.dumps(out))
 
 

@@ -112,6 +112,7 @@ kan_status kan_dense_layer_forward(const float* coef, int32_t in, int32_t out, i
  * batch-1 inference moves the per-edge metadata once; section 4.3: the codebook must be
  * served from on-chip memory).  The edges are regrouped by codebook bucket (8192 Int8 or
  * 2048 fp32 consecutive codewords, 80 KB: what one CU's LDS holds beside the basis table),
+ * (half of that for layers with more than 2048 inputs)
  * then by output, then by input; per edge the buffer keeps (input index u16, codeword id
  * within the bucket u16, gain), and per output the sum of its biases (the bases sum to 1 on
  * [-1,1], so the bias term does not depend on x).  With L->prepared set, the precise path

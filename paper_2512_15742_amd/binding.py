@@ -150,6 +150,11 @@ class VQLayer:
         self.desc.prepared = None
         return self
 
+    def use_prepared(self, on: bool):
+        """Shows or hides an existing prepared buffer to the forward calls."""
+        self.desc.prepared = self.prepared.data_ptr() if (on and self.prepared is not None) else None
+        return self
+
     @property
     def metadata_bytes(self):
         return self.idx.numel() * self.idx.element_size() + 2 * self.gain.numel() * self.gain.element_size()

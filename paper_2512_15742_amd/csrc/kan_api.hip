@@ -216,7 +216,9 @@ LayerPlan plan_bucket(const kan_vq_layer& L, int64_t B, int n_heads) {
   p.cfg.code = L.cb_dtype == KAN_I8 ? kCbI8 : kCbF32;
   const BucketGeom g = bucket_geometry(L.in, L.out, L.K, L.cb_dtype == KAN_I8, L.gb_dtype == KAN_F16);
   const long long base = (long long)g.n_buckets * B * n_heads;
-  long long parts = (kBucketWorkgroups + base - 1) / base;
+  long long parts = kBucketWorkgroups / base;     // rounded down: one round of workgroups, no tail
+  const long long min_parts = (L.out + kBucketMaxJw - 1) / kBucketMaxJw;
+  if (parts < min_parts) parts = min_parts;
   if (parts > L.out) parts = L.out;
   if (parts < 1) parts = 1;
   p.jw = (int)((L.out + parts - 1) / parts);
@@ -229,7 +231,8 @@ LayerPlan plan_bucket(const kan_vq_layer& L, int64_t B, int n_heads) {
 }
 
 bool layer_prepared_ok(const kan_vq_layer& L) {
-  return L.prepared != nullptr && aligned(L.prepared, 256) && aligned(L.codebook, 16) && L.in <= kBucketMaxIn;
+  return L.prepared != nullptr && aligned(L.prepared, 256) && aligned(L.codebook, 16) && L.in <= kBucketMaxIn &&
+         (long long)L.in * L.out <= (1ll << 31);
 }
 
 // Which kernels serve a layer:
@@ -267,11 +270,12 @@ size_t partial_bytes(const LayerPlan& p, int n_out, int64_t B, int heads_in_grou
 struct WsLayout {
   size_t hidden = 0;    // one of two ping-pong hidden-activation buffers, [n_heads][B][out]
   size_t partial = 0;   // i-chunk partial sums
+  size_t partial2 = 0;  // second buffer of per-bucket sums when consecutive bucket layers are chained
   size_t cf = 0;        // matrix-core path: fp16 coefficient fragments
   size_t bp = 0;        // matrix-core path: partial bias sums
   size_t u = 0;         // matrix-core path: packed basis weights + span
   int n_layers = 1;
-  size_t total() const { return (n_layers > 1 ? 2 * hidden : 0) + partial + cf + bp + u; }
+  size_t total() const { return (n_layers > 1 ? 2 * hidden : 0) + partial + partial2 + cf + bp + u; }
 };
 
 size_t mfma_cf_records(int n_in, int n_out) { return (size_t)((n_in + 7) / 8) * 5 * (size_t)n_out * 2; }
@@ -290,6 +294,7 @@ hipError_t launch_gather(const LayerPlan& p, const GatherArgs& a, int heads, hip
 struct WsPtrs {
   float* hid[2];
   float* partial;
+  float* partial2;
   uint4* cf;
   float* bp;
   uint2* u;
@@ -298,12 +303,23 @@ struct WsPtrs {
 // One layer of a group of heads.  `a` carries x, shapes and the per-head pointers;
 // `final_dst` receives act(y).  Gather path: main kernel, then (if i was split) the
 // fixed-order reduction.  Matrix-core path: coefficient and basis preparation first.
+// How a bucket layer receives its input and hands on its output when it is chained to its
+// neighbours: the per-bucket sums of layer l are added (and squashed) by layer l+1 itself.
+struct Chain {
+  int in_parts = 1;              // slices of the input to add (1: plain x)
+  long long in_part_stride = 0;
+  int in_tanh = 0;
+  bool out = false;              // leave the per-bucket sums for the next layer (no reduction pass)
+  float* partial = nullptr;      // where this layer's partial sums go (default: w.partial)
+};
+
 kan_status run_layer_group(const LayerPlan& p, GatherArgs& a, const void* const* prepared, int heads,
                            bool x_shared, float* final_dst, long long final_head_stride, const WsPtrs& w,
-                           int apply_tanh, hipStream_t s) {
+                           int apply_tanh, hipStream_t s, const Chain& chain = Chain()) {
   const long long count = (long long)a.B * a.n_out;
   const bool split = p.n_chunks > 1;
-  float* dst = split ? w.partial : final_dst;
+  float* const partial = chain.partial ? chain.partial : w.partial;
+  float* dst = split ? partial : final_dst;
   const long long dst_head_stride = split ? count * p.n_chunks : final_head_stride;
   const long long dst_chunk_stride = split ? count : 0;
   const int tanh_in_kernel = split ? 0 : apply_tanh;
@@ -352,6 +368,9 @@ kan_status run_layer_group(const LayerPlan& p, GatherArgs& a, const void* const*
     memset(&k, 0, sizeof(k));
     k.x = a.x;
     k.x_head_stride = a.x_head_stride;
+    k.x_parts = chain.in_parts;
+    k.x_part_stride = chain.in_part_stride;
+    k.x_tanh = chain.in_tanh;
     k.dst = dst;
     k.dst_head_stride = dst_head_stride;
     k.dst_chunk_stride = dst_chunk_stride;
@@ -399,9 +418,9 @@ kan_status run_layer_group(const LayerPlan& p, GatherArgs& a, const void* const*
     a.apply_tanh = tanh_in_kernel;
     st = run(p.name, s, [&] { return launch_gather(p, a, heads, s); });
   }
-  if (st != KAN_OK || !split) return st;
+  if (st != KAN_OK || !split || chain.out) return st;
   return run("kan_reduce", s, [&] {
-    return launch_reduce(w.partial, dst_head_stride, count, p.n_chunks, final_dst, final_head_stride, count,
+    return launch_reduce(partial, dst_head_stride, count, p.n_chunks, final_dst, final_head_stride, count,
                          heads, apply_tanh, s);
   });
 }
@@ -409,6 +428,13 @@ kan_status run_layer_group(const LayerPlan& p, GatherArgs& a, const void* const*
 kan_status check_path(int32_t path) {
   if (path == KAN_PATH_AUTO || path == KAN_PATH_GATHER || path == KAN_PATH_MFMA) return KAN_OK;
   return KAN_ERR_UNSUPPORTED;
+}
+
+// Layer l leaves its per-bucket sums to layer l+1 (one group of heads only: the buffers are
+// sized for one group).
+bool chained(const std::vector<LayerPlan>& plans, int l, int n_heads) {
+  return l >= 0 && l + 1 < (int)plans.size() && n_heads <= kMaxGroup && plans[l].kind == kPlanBucket &&
+         plans[l + 1].kind == kPlanBucket && plans[l].n_chunks > 1;
 }
 
 // Validates a [n_heads][n_layers] descriptor table; fills per-layer plans and scratch sizes.
@@ -453,6 +479,9 @@ kan_status plan_head(const kan_vq_layer* layers, int32_t n_layers, int32_t n_hea
       grow(ws->u, round_up((size_t)(l == 0 ? 1 : group) * (size_t)R.in * (size_t)B * sizeof(uint2), 256));
     if (l + 1 < n_layers) grow(ws->hidden, round_up((size_t)n_heads * (size_t)B * R.out * sizeof(float), 256));
   }
+  // consecutive bucket layers hand their per-bucket sums straight on: two buffers, used in turn
+  for (int l = 0; l + 1 < n_layers; ++l)
+    if (chained(*plans, l, n_heads)) ws->partial2 = ws->partial;
   return KAN_OK;
 }
 
@@ -513,15 +542,28 @@ kan_status kan_vq_head_forward(const kan_vq_layer* layers, int32_t n_layers, int
   w.hid[0] = (float*)wsp;
   w.hid[1] = (float*)(wsp + wl.hidden);
   w.partial = (float*)(wsp + hid2);
-  w.cf = (uint4*)(wsp + hid2 + wl.partial);
-  w.bp = (float*)(wsp + hid2 + wl.partial + wl.cf);
-  w.u = (uint2*)(wsp + hid2 + wl.partial + wl.cf + wl.bp);
+  w.partial2 = (float*)(wsp + hid2 + wl.partial);
+  const size_t after_partial = hid2 + wl.partial + wl.partial2;
+  w.cf = (uint4*)(wsp + after_partial);
+  w.bp = (float*)(wsp + after_partial + wl.cf);
+  w.u = (uint2*)(wsp + after_partial + wl.cf + wl.bp);
 
   for (int l = 0; l < n_layers; ++l) {
     const kan_vq_layer& R = layers[l];
     const bool last = (l + 1 == n_layers);
     const float* src = (l == 0) ? x : w.hid[(l - 1) & 1];
-    const long long src_head_stride = (l == 0) ? 0 : (long long)B * R.in;
+    long long src_head_stride = (l == 0) ? 0 : (long long)B * R.in;
+    Chain chain;
+    chain.partial = (l & 1) ? w.partial2 : w.partial;
+    if (!wl.partial2) chain.partial = w.partial;
+    chain.out = chained(plans, l, n_heads);
+    if (chained(plans, l - 1, n_heads)) {
+      src = ((l - 1) & 1) ? w.partial2 : w.partial;
+      chain.in_parts = plans[l - 1].n_chunks;
+      chain.in_part_stride = (long long)B * R.in;
+      chain.in_tanh = 1;
+      src_head_stride = chain.in_part_stride * chain.in_parts;
+    }
     float* dst = last ? y : w.hid[l & 1];
     const long long dst_head_stride = (long long)B * R.out;
     for (int h0 = 0; h0 < n_heads; h0 += kMaxGroup) {
@@ -547,7 +589,7 @@ kan_status kan_vq_head_forward(const kan_vq_layer* layers, int32_t n_layers, int
         prepared[h] = L.prepared;
       }
       st = run_layer_group(plans[l], a, prepared, heads, l == 0, dst + (long long)h0 * dst_head_stride, dst_head_stride, w,
-                           last ? 0 : 1, s);
+                           last ? 0 : 1, s, chain);
       if (st != KAN_OK) return st;
     }
   }
@@ -595,7 +637,7 @@ kan_status kan_dense_layer_forward(const float* coef, int32_t in, int32_t out, i
 
 size_t kan_vq_prepared_bytes(const kan_vq_layer* L) {
   if (validate_layer(L) != KAN_OK) return (size_t)-1;
-  if (L->in > kBucketMaxIn) return 0;
+  if (L->in > kBucketMaxIn || (long long)L->in * L->out > (1ll << 31)) return 0;
   return bucket_geometry(L->in, L->out, L->K, L->cb_dtype == KAN_I8, L->gb_dtype == KAN_F16).total;
 }
 
@@ -603,6 +645,7 @@ kan_status kan_vq_prepare(const kan_vq_layer* L, void* prepared, size_t prepared
   kan_status st = validate_layer(L);
   if (st != KAN_OK) return st;
   if (L->in > kBucketMaxIn) return KAN_ERR_UNSUPPORTED;
+  if ((long long)L->in * L->out > (1ll << 31)) return KAN_ERR_UNSUPPORTED;   // 32-bit segment offsets
   const BucketGeom g = bucket_geometry(L->in, L->out, L->K, L->cb_dtype == KAN_I8, L->gb_dtype == KAN_F16);
   if (!prepared || !aligned(prepared, 256) || prepared_bytes < g.total) return KAN_ERR_WORKSPACE;
   LayerPtrs h = {L->idx, L->gain, L->bias, L->codebook, L->scale, 0};

@@ -5,17 +5,23 @@
 // are limited by the rate at which a CU can issue divergent addresses, far below what the
 // metadata stream could sustain; lookups in LDS are not.  The 655 KB Int8 codebook does not
 // fit the 160 KB LDS of a CU, but an eighth of it does, so the edges are regrouped once
-// (kan_vq_prepare) by bucket = idx / 8192 (fp32 rows: idx / 2048) and every workgroup serves
-// one bucket: it copies the 80 KB of codeword rows into LDS, builds the span/basis table of
-// all inputs of its sample there as well, and then streams its share of the bucket's edges.
+// (kan_vq_prepare) by bucket = idx / 8192 (fp32 rows: idx / 2048; half of that for layers
+// with more than 2048 inputs) and every workgroup serves one bucket: it copies the bucket's
+// codeword rows into LDS, builds the span/basis table of all inputs of its sample there as
+// well, and streams its block of the bucket's edges.
 //
-// Inside a bucket the edges are ordered by output j, then input i, so a segment (the run of
-// edges of one output) is summed by one wave with a fixed-order tree, and the per-bucket
-// sums are added by the fixed-order reduction kernel: no atomics, reproducible bits.
+// Inside a bucket the edges are ordered by output j, then input i.  A workgroup owns the
+// block of edges of a run of outputs, reads it flat (thread t holds 8 consecutive edges per
+// pass: 16-byte loads whose addresses depend on nothing but the block's first edge), puts the
+// per-edge products into LDS and then sums every segment (the edges of one output) with one
+// wave in a fixed order; the per-bucket sums are added by the fixed-order reduction kernel
+// or by the next bucket layer itself: no atomics, reproducible bits.
 // The bias of an edge needs no lookup at all: the four bases sum to 1 on [-1,1], so
 // sum_i bias_ij is a per-output constant computed at preparation time.
 //
 // This file also holds the three preparation kernels (count, scan, fill).
+
+#include <type_traits>
 
 #include "kan_device.hpp"
 #include "kan_internal.hpp"
@@ -23,26 +29,32 @@
 namespace kan {
 namespace {
 
-constexpr int kWaves = kBucketThreads / kWave;   // 16
-constexpr int kUnroll = 4;                       // edges per lane per chunk (256 per wave)
+constexpr int kWaves = kBucketThreads / kWave;     // 16
+constexpr int kEpt = 8;                            // consecutive edges per thread and pass
+constexpr int kPass = kBucketThreads * kEpt;       // 8192 edges per workgroup and pass
 
-// Gains travel as raw bits (uint16_t for fp16, float for fp32).
-template <typename GRaw>
-struct ChunkRegs {
-  uint32_t i[kUnroll], q[kUnroll];
-  GRaw g[kUnroll];
-};
-
-struct ChunkDesc {
-  int n;         // edges in the chunk (0..256)
-  int j;         // output the chunk belongs to
-  bool last;     // chunk ends its segment
-  bool valid;
+// Raw records of one pass: edges e0 .. e0 + 7 of the thread (16-byte loads; fp32 gains: two).
+template <bool GF16>
+struct PassRegs {
+  u32x4 i, q, g0;
+  typename std::conditional<GF16, char, u32x4>::type g1;
 };
 
 __device__ __forceinline__ float gain_to_float(float g) { return g; }
 __device__ __forceinline__ float gain_to_float(__half g) { return __half2float(g); }
-__device__ __forceinline__ float gain_to_float(uint16_t g) { return __half2float(__ushort_as_half(g)); }
+
+__device__ __forceinline__ uint32_t dword_of(const u32x4& v, int n) {
+  return n == 0 ? v.x : (n == 1 ? v.y : (n == 2 ? v.z : v.w));
+}
+__device__ __forceinline__ uint32_t u16_of(const u32x4& v, int u) {   // u = 0..7
+  const uint32_t w = dword_of(v, u >> 1);
+  return (u & 1) ? (w >> 16) : (w & 0xffffu);
+}
+template <bool GF16>
+__device__ __forceinline__ float gain_of(const PassRegs<GF16>& c, int u) {
+  if constexpr (GF16) return __half2float(__ushort_as_half((uint16_t)u16_of(c.g0, u)));
+  else return __uint_as_float(u < 4 ? dword_of(c.g0, u) : dword_of(c.g1, u - 4));
+}
 
 __device__ __forceinline__ float wave_sum(float v) {
 #pragma unroll
@@ -50,10 +62,22 @@ __device__ __forceinline__ float wave_sum(float v) {
   return v;
 }
 
-template <typename GbT, bool I8>
-__global__ __launch_bounds__(kBucketThreads) void kan_bucket_kernel(const BucketArgs a) {   // GbT: uint16_t | float
-  __shared__ __attribute__((aligned(16))) uint32_t cb[kBucketBytes / 4 + 4];
-  __shared__ float4 bas[kBucketMaxIn];
+// Every global load below is unconditional (addresses are clamped into valid memory instead
+// of being predicated): with no branch around a load the compiler counts outstanding loads
+// exactly, so each wait covers only the loads whose data is needed next, and table
+// building, record traffic and arithmetic overlap.
+//
+// MAXIN: inputs the basis table holds (2048 or 4096); the bucket shrinks to make room.
+template <bool GF16, bool I8, int MAXIN>
+__global__ __launch_bounds__(kBucketThreads) void kan_bucket_kernel(const BucketArgs a) {
+  constexpr int kCbBytes = bucket_bytes(MAXIN);
+  constexpr int kXPerThread = MAXIN / kBucketThreads;
+  constexpr int kCbPerThread = (kCbBytes / 16 + kBucketThreads - 1) / kBucketThreads;   // 16-byte units per thread
+  __shared__ __attribute__((aligned(16))) uint32_t cb[kCbBytes / 4 + 8];   // + 16 bytes read-ahead, + 16 spare
+  __shared__ float4 bas[MAXIN];             // {w0, w1, w2, span as integer bits}; w3 = 1 - w0 - w1 - w2
+  __shared__ __attribute__((aligned(16))) float prod[kPass];   // per-edge products of the current pass
+  __shared__ float res[kBucketMaxJw];       // sums of this workgroup's segments
+  __shared__ uint32_t segl[kBucketMaxJw + 1];   // first edge of every segment of the block (+ end)
 
   const int tid = threadIdx.x, lane = tid & (kWave - 1);
   const int wave = __builtin_amdgcn_readfirstlane(tid >> 6);
@@ -64,106 +88,151 @@ __global__ __launch_bounds__(kBucketThreads) void kan_bucket_kernel(const Bucket
   const uint32_t* __restrict__ seg = (const uint32_t*)(prep + a.off_seg) + (size_t)bucket * a.n_out;
   const uint16_t* __restrict__ pi = (const uint16_t*)(prep + a.off_i);
   const uint16_t* __restrict__ pq = (const uint16_t*)(prep + a.off_q);
-  const GbT* __restrict__ pg = (const GbT*)(prep + a.off_g);
+  const char* __restrict__ pg = prep + a.off_g;
+  constexpr int kGainBytes = GF16 ? 2 : 4;
 
   const int j0 = part * a.jw;
   const int j1 = min(j0 + a.jw, a.n_out);
-  const int first_j = j0 + wave;
-  const int n_seg = first_j < j1 ? (j1 - first_j + kWaves - 1) / kWaves : 0;   // segments of this wave
+  const int njw = j1 - j0;
+  // the block of this workgroup: edges [blk_lo, blk_hi)
+  const uint32_t blk_lo = seg[j0], blk_hi = seg[j1];
 
-  // ---- generator over this wave's chunks (all state wave-uniform) ------------------
-  int k = 0;
-  bool have = n_seg > 0;
-  uint32_t pos = 0, end = 0, nxt_pos = 0, nxt_end = 0;
-  if (have) {
-    pos = seg[first_j];
-    end = seg[first_j + 1];
-    if (n_seg > 1) {
-      nxt_pos = seg[first_j + kWaves];
-      nxt_end = seg[first_j + kWaves + 1];
-    }
-  }
-  auto next = [&](ChunkRegs<GbT>& c, ChunkDesc& d) {
-    d.valid = have;
-    if (!have) return;
-    d.j = first_j + k * kWaves;
-    const uint32_t left = end - pos;
-    d.n = (int)(left < (uint32_t)(kWave * kUnroll) ? left : (uint32_t)(kWave * kUnroll));
-#pragma unroll
-    for (int u = 0; u < kUnroll; ++u) {
-      const int o = u * kWave + lane;
-      const size_t e = (size_t)pos + o;
-      const bool v = o < d.n;
-      c.i[u] = v ? (uint32_t)__builtin_nontemporal_load(pi + e) : 0u;
-      c.q[u] = v ? (uint32_t)__builtin_nontemporal_load(pq + e) : 0u;
-      c.g[u] = v ? __builtin_nontemporal_load(pg + e) : GbT(0);
-    }
-    pos += (uint32_t)d.n;
-    d.last = pos == end;
-    if (d.last) {
-      ++k;
-      have = k < n_seg;
-      pos = nxt_pos;
-      end = nxt_end;
-      if (k + 1 < n_seg) {
-        nxt_pos = seg[first_j + (k + 1) * kWaves];
-        nxt_end = seg[first_j + (k + 1) * kWaves + 1];
-      }
-    }
-  };
+  // Loads are issued in the order their data is needed (they return in order): the inputs
+  // of the sample, the codebook bucket, the segment table, then two passes of records.
 
-  ChunkRegs<GbT> A, B;
-  ChunkDesc dA, dB;
-  next(A, dA);   // the first records travel while the tables are built
-
-  // ---- codebook bucket -> LDS ---------------------------------------------------------
-  {
-    const long long start = (long long)bucket * kBucketBytes;
-    const long long rest = a.cb_bytes - start;
-    const int nbytes = (int)(rest < kBucketBytes ? rest : kBucketBytes);
-    const char* src = (const char*)H.cb + start;
-    const int n16 = nbytes >> 4;
-    for (int t = tid; t < n16; t += kBucketThreads) ((uint4*)cb)[t] = ((const uint4*)src)[t];
-    const int tail = nbytes & 15;
-    if (tid < tail) ((uint8_t*)cb)[n16 * 16 + tid] = ((const uint8_t*)src)[n16 * 16 + tid];
-  }
-  // ---- span + weights of every input of sample b -> LDS (span in the sign bits of w0..w2) --
+  // ---- (1) inputs: x itself, or the previous layer's per-bucket sums still to be added
+  //          (fixed order) and squashed ----------------------------------------------------
+  float xv[kXPerThread];
   {
     const float* xr = a.x + (long long)head * a.x_head_stride + (long long)b * a.n_in;
-    for (int i = tid; i < a.n_in; i += kBucketThreads) {
-      const BasisW w = basis_eval(xr[i]);
-      float4 v;
-      v.x = __uint_as_float(__float_as_uint(w.w0) | ((uint32_t)(w.span & 1) << 31));
-      v.y = __uint_as_float(__float_as_uint(w.w1) | ((uint32_t)((w.span >> 1) & 1) << 31));
-      v.z = __uint_as_float(__float_as_uint(w.w2) | ((uint32_t)((w.span >> 2) & 1) << 31));
-      v.w = w.w3;
-      bas[i] = v;
+    int xi[kXPerThread];
+#pragma unroll
+    for (int r = 0; r < kXPerThread; ++r) {
+      xi[r] = min(tid + r * kBucketThreads, a.n_in - 1);
+      xv[r] = xr[xi[r]];
+    }
+    // further slices eight at a time, all their loads in flight together; the additions keep
+    // the order p = 1, 2, ... (slices past the last one are re-reads of it, added as zero)
+    for (int p0 = 1; p0 < a.x_parts; p0 += 8) {
+      float t[8][kXPerThread];
+#pragma unroll
+      for (int pp = 0; pp < 8; ++pp) {
+        const float* xp = xr + (long long)min(p0 + pp, a.x_parts - 1) * a.x_part_stride;
+#pragma unroll
+        for (int r = 0; r < kXPerThread; ++r) t[pp][r] = xp[xi[r]];
+      }
+#pragma unroll
+      for (int pp = 0; pp < 8; ++pp)
+#pragma unroll
+        for (int r = 0; r < kXPerThread; ++r) xv[r] += (p0 + pp < a.x_parts) ? t[pp][r] : 0.f;
     }
   }
+
+  // ---- (4) records.  Pass p covers edges [base + p * 8192, + 8192), base = blk_lo rounded
+  //          down to a multiple of 8, so that every thread's group of 8 is 16-byte aligned.
+  //          Groups past the block re-read its last group; the arrays are padded, so a group
+  //          that straddles the end of the last block stays inside the buffer. -----------------
+  const uint32_t base = blk_lo & ~7u;
+  const uint32_t last_group = blk_hi > 0u ? (blk_hi - 1u) & ~7u : 0u;
+  const int n_pass = blk_hi > blk_lo ? (int)((blk_hi - base + kPass - 1) / kPass) : 0;
+  auto load_pass = [&](PassRegs<GF16>& c, int p) {
+    const uint32_t e0 = min(base + (uint32_t)p * kPass + (uint32_t)tid * kEpt, last_group);
+    c.i = __builtin_nontemporal_load((const u32x4*)(pi + e0));
+    c.q = __builtin_nontemporal_load((const u32x4*)(pq + e0));
+    c.g0 = __builtin_nontemporal_load((const u32x4*)(pg + (size_t)e0 * kGainBytes));
+    if constexpr (!GF16) c.g1 = __builtin_nontemporal_load((const u32x4*)(pg + (size_t)e0 * kGainBytes) + 1);
+  };
+  PassRegs<GF16> A, B;
+  load_pass(A, 0);
+  load_pass(B, 1);
+
+  // ---- (2) codebook bucket, 16 bytes per thread and round.  The workgroups of a bucket
+  //          start at different offsets so that they do not all ask the same L2 channel
+  //          for the same line at the same moment ------------------------------------------
+  const long long cb_start = (long long)bucket * kCbBytes;
+  const long long cb_rest = a.cb_bytes - cb_start;
+  const int cb_nbytes = (int)(cb_rest < kCbBytes ? cb_rest : kCbBytes);
+  const char* cb_src = (const char*)H.cb + cb_start;
+  const int n16 = cb_nbytes >> 4;
+  const int cb_tail = cb_nbytes & 15;
+  const int n_parts = gridDim.x / a.n_buckets;
+  const int rot = (int)((long long)part * n16 / n_parts);
+  // a bucket shorter than 16 bytes, or without tail bytes: the (unused) load goes to the
+  // prepared buffer, which always has that many bytes
+  const u32x4* cb_src16 = n16 > 0 ? (const u32x4*)cb_src : (const u32x4*)prep;
+  const uint8_t* cb_tailp = cb_tail > 0 ? (const uint8_t*)cb_src + n16 * 16 + min(tid, cb_tail - 1)
+                                        : (const uint8_t*)prep;
+  // (plain arrays with compile-time indices only; every element is assigned unconditionally,
+  // so they live in registers)
+  int cbu[kCbPerThread];
+  u32x4 cbv[kCbPerThread];
+#pragma unroll
+  for (int r = 0; r < kCbPerThread; ++r) {
+    const int t = tid + r * kBucketThreads;
+    int u = t + rot;
+    if (u >= n16) u -= n16;
+    cbu[r] = t < n16 ? u : kCbBytes / 16;          // no unit: the spare slot behind the bucket
+    cbv[r] = cb_src16[t < n16 ? u : 0];
+  }
+  const uint8_t cb_tailv = *cb_tailp;
+
+  // ---- (3) segment table of the block ---------------------------------------------------------
+  const uint32_t sv0 = seg[j0 + min(tid, njw)];
+  const uint32_t sv1 = seg[j0 + min(tid + kBucketThreads, njw)];
+
+  __builtin_amdgcn_sched_barrier(0);   // keep the loads above in this order, ahead of their uses
+
+  // ---- span + weights of every input -> LDS ---------------------------------------------------
+  {
+#pragma unroll
+    for (int r = 0; r < kXPerThread; ++r) {
+      if (r * kBucketThreads < a.n_in) {        // uniform: rounds past the last input are skipped
+        const int i = tid + r * kBucketThreads;
+        const float xin = a.x_tanh ? tanhf(xv[r]) : xv[r];
+        const BasisW w = basis_eval(xin);
+        // (threads past the last input of the round write entries nobody reads)
+        bas[i] = make_float4(w.w0, w.w1, w.w2, __uint_as_float((uint32_t)w.span));
+      }
+    }
+  }
+  // ---- codebook rows, segment table -> LDS (unconditional stores: a store inside a branch
+  //      would pull its load into the branch, behind all the others) ------------------------------
+  {
+#pragma unroll
+    for (int r = 0; r < kCbPerThread; ++r) ((u32x4*)cb)[cbu[r]] = cbv[r];
+    ((uint8_t*)cb)[tid < cb_tail ? n16 * 16 + tid : kCbBytes + 16 + (tid & 15)] = cb_tailv;
+  }
+  segl[min(tid, njw)] = sv0;
+  segl[min(tid + kBucketThreads, njw)] = sv1;
+  for (int t = tid; t < njw; t += kBucketThreads) res[t] = 0.f;
   __syncthreads();
 
-  float* dst = a.dst + (long long)head * a.dst_head_stride + (long long)bucket * a.dst_chunk_stride +
-               (long long)b * a.n_out;
-  const float* bias_sum = (const float*)(prep + a.off_bias);
-  const float scale = I8 ? H.scale : 1.0f;
-  float acc = 0.f;
-
-  auto consume = [&](const ChunkRegs<GbT>& c, const ChunkDesc& d) {
+  // products of the thread's 8 edges of pass p -> prod
+  auto products = [&](const PassRegs<GF16>& c, int p) {
+    // edge e belongs to the block iff blk_lo <= e < blk_hi, i.e. (e - blk_lo) < (blk_hi - blk_lo) unsigned
+    const uint32_t rel0 = base + (uint32_t)p * kPass + (uint32_t)tid * kEpt - blk_lo, len = blk_hi - blk_lo;
+    float pr[kEpt];
 #pragma unroll
-    for (int u = 0; u < kUnroll; ++u) {
-      const float4 w = bas[c.i[u]];
-      const uint32_t span = (__float_as_uint(w.x) >> 31) | ((__float_as_uint(w.y) >> 31) << 1) |
-                            ((__float_as_uint(w.z) >> 31) << 2);
-      const uint32_t at = c.q[u] * 10u + span;
+    for (int u = 0; u < kEpt; ++u) pr[u] = 0.f;
+    // Groups wholly outside the block (past its end in the last pass) skip the lookups.  The
+    // group holds an edge of the block iff rel0 + u < len for some u in 0..7; rel0 is "negative"
+    // (wrapped, -7..-1) only for the group that straddles the block's start, and adding 7 to
+    // both sides covers that case as well.
+    if (rel0 + (uint32_t)(kEpt - 1) < len + (uint32_t)(kEpt - 1)) {
+#pragma unroll
+    for (int u = 0; u < kEpt; ++u) {
+      const float4 w = bas[u16_of(c.i, u)];
+      const uint32_t at = u16_of(c.q, u) * 10u + __float_as_uint(w.w);
       float c0, c1, c2, c3;
       if constexpr (I8) {
-        // bytes at .. at+3 of the bucket: two aligned dwords, funnel-shifted
+        // bytes at .. at+3 of the bucket: two aligned dwords, funnel-shifted; q + 128 as
+        // unsigned bytes (the differences below do not see the offset)
         const uint32_t lo = cb[at >> 2], hi = cb[(at >> 2) + 1];
-        const uint32_t win = __builtin_amdgcn_alignbyte(hi, lo, at & 3u);
-        c0 = (float)(int)(int8_t)(win & 0xff);
-        c1 = (float)(int)(int8_t)((win >> 8) & 0xff);
-        c2 = (float)(int)(int8_t)((win >> 16) & 0xff);
-        c3 = (float)(int)(int8_t)(win >> 24);
+        const uint32_t win = __builtin_amdgcn_alignbyte(hi, lo, at & 3u) ^ 0x80808080u;
+        c0 = (float)(win & 0xffu);
+        c1 = (float)((win >> 8) & 0xffu);
+        c2 = (float)((win >> 16) & 0xffu);
+        c3 = (float)(win >> 24);
       } else {
         const float* cf = (const float*)cb;
         c0 = cf[at];
@@ -171,32 +240,61 @@ __global__ __launch_bounds__(kBucketThreads) void kan_bucket_kernel(const Bucket
         c2 = cf[at + 2];
         c3 = cf[at + 3];
       }
-      float s = w.w * c3;
-      s = fmaf(fabsf(w.z), c2, s);
-      s = fmaf(fabsf(w.y), c1, s);
-      s = fmaf(fabsf(w.x), c0, s);
-      // lanes past the end of the chunk looked up row 0 with gain 0; keep even a non-finite
-      // row 0 out of the sum
-      acc = (u * kWave + lane < d.n) ? fmaf(gain_to_float(c.g[u]), s, acc) : acc;
+      // sum_k w_k c_k with w3 = 1 - w0 - w1 - w2 (the bases sum to 1)
+      float s = I8 ? c3 - 128.0f : c3;
+      s = fmaf(w.z, c2 - c3, s);
+      s = fmaf(w.y, c1 - c3, s);
+      s = fmaf(w.x, c0 - c3, s);
+      // Edges outside the block (groups that straddle its ends, re-read groups) contribute
+      // an exact zero rather than gain * s, so that a non-finite codeword which no edge of
+      // the block refers to cannot reach a sum.
+      pr[u] = (rel0 + (uint32_t)u < len) ? gain_of<GF16>(c, u) * s : 0.f;
     }
-    if (d.last) {
-      const float t = wave_sum(acc);
-      if (lane == 0) {
-        float v = scale * t + (bucket == 0 ? bias_sum[d.j] : 0.0f);
-        if (a.apply_tanh && a.n_buckets == 1) v = tanhf(v);
-        dst[d.j] = v;
+    }
+    ((float4*)prod)[tid * 2] = make_float4(pr[0], pr[1], pr[2], pr[3]);
+    ((float4*)prod)[tid * 2 + 1] = make_float4(pr[4], pr[5], pr[6], pr[7]);
+  };
+
+  // segment sums over the products of pass p: wave w takes segments w, w + 16, ...
+  auto segment_sums = [&](int p) {
+    const uint32_t pa = base + (uint32_t)p * kPass;        // prod[n] is edge pa + n
+    for (int jj = wave; jj < njw; jj += kWaves) {
+      const uint32_t s0 = segl[jj], s1 = segl[jj + 1];
+      const uint32_t lo = max(s0, pa), hi = min(s1, pa + (uint32_t)kPass);
+      if (lo < hi) {                                         // uniform
+        float acc = 0.f;
+        for (uint32_t e = lo + (uint32_t)lane; e < hi; e += kWave) acc += prod[e - pa];
+        acc = wave_sum(acc);
+        if (lane == 0) res[jj] += acc;
       }
-      acc = 0.f;
     }
   };
 
-  while (true) {
-    next(B, dB);
-    if (!dA.valid) break;
-    consume(A, dA);
-    next(A, dA);
-    if (!dB.valid) break;
-    consume(B, dB);
+  // two passes are always in flight: a slot is refilled as soon as it has been consumed
+  // (after the last pass the refills are harmless re-reads)
+  for (int p = 0; p < n_pass; p += 2) {
+    products(A, p);
+    __syncthreads();
+    segment_sums(p);
+    __syncthreads();
+    load_pass(A, p + 2);
+    if (p + 1 >= n_pass) break;
+    products(B, p + 1);
+    __syncthreads();
+    segment_sums(p + 1);
+    __syncthreads();
+    load_pass(B, p + 3);
+  }
+
+  // ---- segment sums -> memory (coalesced): scale, bias sum (first bucket only), activation ----
+  float* dst = a.dst + (long long)head * a.dst_head_stride + (long long)bucket * a.dst_chunk_stride +
+               (long long)b * a.n_out;
+  const float* bias_sum = (const float*)(prep + a.off_bias);
+  const float scale = I8 ? H.scale : 1.0f;
+  for (int t = tid; t < njw; t += kBucketThreads) {
+    float v = scale * res[t] + (bucket == 0 ? bias_sum[j0 + t] : 0.0f);
+    if (a.apply_tanh && a.n_buckets == 1) v = tanhf(v);
+    dst[j0 + t] = v;
   }
 }
 
@@ -299,17 +397,25 @@ hipError_t launch_bucket_prepare(const LayerPtrs& h, int idx_u32, int gb_f16, in
 }
 
 hipError_t launch_bucket(bool cb_i8, bool gb_f16, const BucketArgs& a, int parts, int heads, hipStream_t s) {
-  if (a.n_in > kBucketMaxIn || a.n_buckets < 1 || parts < 1 || a.jw < 1 || (long long)parts * a.jw < a.n_out)
+  if (a.n_in > kBucketMaxIn || a.n_buckets < 1 || parts < 1 || a.jw < 1 || a.jw > kBucketMaxJw ||
+      (long long)parts * a.jw < a.n_out)
     return hipErrorInvalidValue;
   dim3 grid((unsigned)(parts * a.n_buckets), (unsigned)a.B, (unsigned)heads);
   dim3 block(kBucketThreads);
+  const bool wide = a.n_in > 2048;
+#define KAN_LAUNCH_BUCKET(GF16, I8)                                                                    \
+  do {                                                                                                 \
+    if (wide) hipLaunchKernelGGL((kan_bucket_kernel<GF16, I8, 4096>), grid, block, 0, s, a);           \
+    else hipLaunchKernelGGL((kan_bucket_kernel<GF16, I8, 2048>), grid, block, 0, s, a);                \
+  } while (0)
   if (cb_i8) {
-    if (gb_f16) hipLaunchKernelGGL((kan_bucket_kernel<uint16_t, true>), grid, block, 0, s, a);
-    else hipLaunchKernelGGL((kan_bucket_kernel<float, true>), grid, block, 0, s, a);
+    if (gb_f16) KAN_LAUNCH_BUCKET(true, true);
+    else KAN_LAUNCH_BUCKET(false, true);
   } else {
-    if (gb_f16) hipLaunchKernelGGL((kan_bucket_kernel<uint16_t, false>), grid, block, 0, s, a);
-    else hipLaunchKernelGGL((kan_bucket_kernel<float, false>), grid, block, 0, s, a);
+    if (gb_f16) KAN_LAUNCH_BUCKET(true, false);
+    else KAN_LAUNCH_BUCKET(false, false);
   }
+#undef KAN_LAUNCH_BUCKET
   return hipGetLastError();
 }
 

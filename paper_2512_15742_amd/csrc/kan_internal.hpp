@@ -106,9 +106,12 @@ hipError_t launch_fused(const GatherCfg&, const FusedArgs&, bool f32, dim3 grid,
 // segment is the run of edges of one (bucket, j).  Per edge it keeps the input index, the
 // codeword id relative to the bucket and the gain; the biases of an output are summed once
 // (the bases sum to 1, so they do not depend on x).
-constexpr int kBucketBytes = 81920;     // codebook bytes per bucket: 8192 Int8 rows or 2048 fp32 rows
 constexpr int kBucketMaxIn = 4096;      // the basis table of all inputs lives in LDS beside the bucket
 constexpr int kBucketThreads = 1024;
+constexpr int kBucketMaxJw = 1024;      // outputs per workgroup (their sums are staged in LDS)
+// Codebook bytes per bucket: 8192 Int8 rows or 2048 fp32 rows for layers of up to 2048
+// inputs, half of that for wider layers (whose basis table takes twice the LDS).
+constexpr int bucket_bytes(int n_in) { return n_in > 2048 ? 40960 : 81920; }
 
 struct BucketGeom {
   int rows_shift;      // log2(codewords per bucket)
@@ -122,9 +125,10 @@ struct BucketGeom {
 };
 
 inline BucketGeom bucket_geometry(int n_in, int n_out, int K, bool cb_i8, bool gb_f16) {
-  auto up = [](size_t v) { return (v + 255) / 256 * 256; };
+  // 32 bytes of slack after every array: threads load aligned groups of eight records
+  auto up = [](size_t v) { return (v + 32 + 255) / 256 * 256; };
   BucketGeom g;
-  g.rows_shift = cb_i8 ? 13 : 11;
+  g.rows_shift = (cb_i8 ? 13 : 11) - (n_in > 2048 ? 1 : 0);
   g.n_buckets = (K + (1 << g.rows_shift) - 1) >> g.rows_shift;
   const size_t E = (size_t)n_in * n_out;
   g.off_seg = 0;
@@ -144,8 +148,10 @@ struct BucketHead {
 };
 
 struct BucketArgs {
-  const float* x;              // [head or 1][B][n_in]
+  const float* x;              // [head or 1][x_parts][B][n_in]
   long long x_head_stride;     // 0 when all heads share the input
+  long long x_part_stride;     // the input of the layer is act(sum over x_parts slices of x): the
+  int x_parts, x_tanh;         //   previous layer's per-bucket sums are consumed without a reduction pass
   float* dst;                  // final values (one bucket) or per-bucket partial sums
   long long dst_head_stride, dst_chunk_stride;
   int n_in, n_out, B;

@@ -27,10 +27,16 @@ def kb():
     return binding
 
 
+def _bucket_rows(P):
+    """Codewords per bucket: 80 KB of rows, 40 KB for layers with more than 2048 inputs."""
+    rows = 8192 if P.codebook.dtype == np.int8 else 2048
+    return rows // 2 if P.idx.shape[0] > 2048 else rows
+
+
 def _expected_layout(P):
     """(seg_off, bias_sum, i, q, gain) of the regrouped layer: bucket-major, then j, then i."""
-    rows = 8192 if P.codebook.dtype == np.int8 else 2048
     n_in, n_out = P.idx.shape
+    rows = _bucket_rows(P)
     nb = (P.K + rows - 1) // rows
     idx = P.idx.astype(np.int64)
     bucket = idx // rows
@@ -47,9 +53,9 @@ def _expected_layout(P):
 
 
 def _read_layout(buf, P):
-    up = lambda v: (v + 255) // 256 * 256
-    rows = 8192 if P.codebook.dtype == np.int8 else 2048
+    up = lambda v: (v + 32 + 255) // 256 * 256       # every array is followed by >= 32 bytes of slack
     n_in, n_out = P.idx.shape
+    rows = _bucket_rows(P)
     nb = (P.K + rows - 1) // rows
     E = n_in * n_out
     raw = buf.cpu().numpy()
@@ -69,6 +75,7 @@ def _read_layout(buf, P):
     (64, 32, 256, "f32", "f32", "u16"),        # one bucket
     (130, 300, 70000, "f32", "f16", "u32"),    # 35 fp32 buckets
     (2048, 64, 65536, "i8", "f16", "u16"),
+    (2100, 9, 30000, "i8", "f32", "u16"),      # more than 2048 inputs: buckets of 4096 rows
 ])
 def test_prepared_layout_bit_exact(kb, n_in, n_out, K, cb, gb, idxd):
     P = synth.make_layer(n_in + K, n_in, n_out, K, cb_dtype=cb, gb_dtype=gb, idx_dtype=idxd)
@@ -112,8 +119,11 @@ def test_config3_head_prepared(kb, B):
     y = kb.kan_vq_head_forward([Ls], xd, path=kb.KAN_PATH_AUTO, ws=ws)[0].cpu().numpy()
     y_ref, hidden_ref = ko.vq_head_forward(x, [p.as_dict() for p in Ps], return_hidden=True)
     assert ko.error_report(y, y_ref)["headline"] <= TOL_FP32
-    # the hidden activation at the start of the workspace, and layer 2 from exactly those fp32 inputs
-    hid = ws[:B * 1024 * 4].view(torch.float32).reshape(B, 1024).cpu().numpy()
+    # chained bucket layers pass per-bucket sums straight on (no hidden tensor is written):
+    # layer 1 alone, squashed, must reproduce the oracle's hidden activation, and layer 2 of
+    # the oracle fed with exactly those fp32 numbers must reproduce y
+    y1 = kb.kan_vq_layer_forward(Ls[0], xd, path=kb.KAN_PATH_GATHER)
+    hid = torch.tanh(y1).cpu().numpy()
     assert ko.error_report(hid, hidden_ref[0])["headline"] <= TOL_FP32
     y2_ref = ko.vq_layer_forward(hid, **Ps[1].as_dict())
     assert ko.error_report(y, y2_ref)["headline"] <= TOL_FP32
@@ -122,8 +132,7 @@ def test_config3_head_prepared(kb, B):
     assert np.array_equal(y, y_again)
     y_plain = kb.kan_vq_head_forward([gpu_layers(Ps)], xd, path=kb.KAN_PATH_GATHER)[0].cpu().numpy()
     assert np.abs(y_plain - y).max() <= 2 * TOL_FP32 * np.abs(y_ref).max()
-    y1 = kb.kan_vq_layer_forward(Ls[0], xd, path=kb.KAN_PATH_GATHER).cpu().numpy()
-    check_layer_output(y1, x, Ps[0], TOL_FP32, full=False, seed=B)
+    check_layer_output(y1.cpu().numpy(), x, Ps[0], TOL_FP32, full=False, seed=B)
 
 
 @pytest.mark.parametrize("variant", ["i8", "f32"])
@@ -147,6 +156,23 @@ def test_ragged_shapes_prepared(kb, n_in, n_out, K, B, cb, gb):
     y_ref, A = ko.vq_layer_forward(x, **P.as_dict(), return_abs=True)
     rep = ko.error_report(y, y_ref, A)
     assert rep["headline"] <= TOL_FP32 and rep["strict"] <= TOL_FP32, rep
+
+
+def test_three_chained_layers_and_mixed_chain(kb):
+    """Three prepared layers in a row (two hand-overs of per-bucket sums, alternating buffers),
+    then the same head with the middle layer unprepared (hand-over only where both sides are
+    bucket layers)."""
+    Ps = [synth.make_layer(31, 200, 300, 30000, cb_dtype="i8", gb_dtype="f16"),
+          synth.make_layer(32, 300, 90, 20000, cb_dtype="i8", gb_dtype="f16"),
+          synth.make_layer(33, 90, 17, 9000, cb_dtype="f32", gb_dtype="f32")]
+    x = synth.make_x(7, 3, 200)
+    y_ref = ko.vq_head_forward(x, [p.as_dict() for p in Ps])
+    Ls = [L.prepare() for L in gpu_layers(Ps)]
+    y = kb.kan_vq_head_forward([Ls], to_dev(x), path=kb.KAN_PATH_GATHER)[0].cpu().numpy()
+    assert ko.error_report(y, y_ref)["headline"] <= TOL_FP32
+    Ls[1].use_prepared(False)
+    y = kb.kan_vq_head_forward([Ls], to_dev(x), path=kb.KAN_PATH_GATHER)[0].cpu().numpy()
+    assert ko.error_report(y, y_ref)["headline"] <= TOL_FP32
 
 
 def test_long_and_empty_segments(kb):
