@@ -64,6 +64,17 @@ typedef enum kan_dtype { KAN_F32 = 0, KAN_F16 = 1, KAN_I8 = 2, KAN_U16 = 3, KAN_
  *   KAN_PATH_AUTO    the precise path below batch 32, the fp16 path from there on.   */
 typedef enum kan_path { KAN_PATH_AUTO = 0, KAN_PATH_GATHER = 1, KAN_PATH_MFMA = 2 } kan_path;
 
+/* How a codeword's G = 10 numbers define the edge function C[k](x) of Eq. (1).
+ *   KAN_RULE_BSPLINE3  coefficients of a cubic B-spline on 7 uniform intervals of [-1,1]
+ *                      (App. A.1: the spline family of the models that are compressed).
+ *   KAN_RULE_PLI2      the rule of the paper's runtime operator (sections 4.1, 4.3): samples at
+ *                      the uniform nodes n_k = -1 + 2k/9; index floor((x+1)/dx) with
+ *                      dx = 2/9, then linear interpolation between entries k and k+1.
+ *                      x = +1 belongs to the last interval (k = 8, u = 1).
+ * In both rules the weights of the entries sum to 1 on [-1,1], so gain * C[k](x) + bias
+ * equals the rule applied to the reconstructed vector gain * C[k] + bias.               */
+typedef enum kan_rule { KAN_RULE_BSPLINE3 = 0, KAN_RULE_PLI2 = 1 } kan_rule;
+
 /* One VQ-KAN layer (Eq. (1)): host struct, device pointers. */
 typedef struct kan_vq_layer {
   int32_t in, out;       /* N_in, N_out, both >= 1                                  */
@@ -77,7 +88,7 @@ typedef struct kan_vq_layer {
   const void* bias;      /* [in][out]                                               */
   const void* codebook;  /* [K][10]                                                 */
   float scale;           /* Int8: value = scale * q.  Ignored for KAN_F32 codebooks */
-  int32_t reserved;      /* set to 0                                                */
+  int32_t rule;          /* KAN_RULE_BSPLINE3 (0) | KAN_RULE_PLI2                   */
   const void* prepared;  /* NULL, or the buffer kan_vq_prepare filled for this very
                             layer (small-batch path, see below)                     */
 } kan_vq_layer;
@@ -89,6 +100,10 @@ typedef struct kan_vq_layer {
  * calls compute the same quantities internally with the same device function.
  * x, span, w: device.  n >= 0 (n == 0 is a no-op).                               */
 kan_status kan_bspline_basis(const float* x, int64_t n, uint8_t* span, float* w, void* stream);
+
+/* The same for KAN_RULE_PLI2: index[n] = k in 0..8 (the interval [n_k, n_k+1) that holds the
+ * clamped x[n]; x = +1 gives 8) and w[n][0..1] = (1 - u, u), the weights of entries k, k+1.   */
+kan_status kan_pli_basis(const float* x, int64_t n, uint8_t* index, float* w, void* stream);
 
 /* Bytes of workspace kan_vq_layer_forward / kan_vq_head_forward need for these
  * descriptors (host array [n_heads][n_layers]), batch B and path.  Returns 0
@@ -134,7 +149,7 @@ kan_status kan_vq_prepare(const kan_vq_layer* L, void* prepared, size_t prepared
 /* n_heads independent heads of n_layers VQ layers each, applied to the same
  * x[B][in0] (multi-expert deployment, section 5.6); tanh between layers, none
  * after the last.  layers: host array [n_heads][n_layers]; layer l of every
- * head must have the same in/out/K/dtypes (else KAN_ERR_UNSUPPORTED) and
+ * head must have the same in/out/K/dtypes/rule (else KAN_ERR_UNSUPPORTED) and
  * out of layer l == in of layer l+1.  y: [n_heads][B][out_last].
  * n_heads <= 64 per call group is handled internally (any n_heads >= 1).        */
 kan_status kan_vq_head_forward(const kan_vq_layer* layers, int32_t n_layers, int32_t n_heads,

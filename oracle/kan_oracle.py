@@ -23,16 +23,27 @@ What it follows
   notes: the paper gives the byte count but not the mapping).
 * Heads: tanh between layers, none after the last (benchmark configuration).
 
+* The runtime operator's own rule (paper §4.1, §4.3), selectable with
+  rule="pli": the G entries of a codeword are samples at G uniform nodes over
+  [-1, 1], the lookup index is floor((x + 1) / dx), dx = 2 / (G - 1), and the
+  value is the linear interpolation between the two neighbouring entries; the
+  last interval is closed at x = +1 (reading stated in the design notes: the
+  paper gives the index expression and "two codebook entries", not dx or the
+  end rule).
+
 Bases are evaluated by the Cox-de Boor recursion, exactly as the textbook
 definition states it; nothing here uses the closed-form uniform cubic weights
-that the GPU kernels use.
+that the GPU kernels use.  The piecewise-linear rule is written out from its
+definition (locate the interval by search over the nodes, interpolate).
 
 Pins (see tests/test_oracle_pins.py): partition of unity, exactly four nonzero
 bases at span..span+3, constant codeword => gain*v+bias, VQ == dense on
 reconstructed coefficients, basis integrals == h, knot/mid-interval closed-form
 weights, linear and quadratic precision (Greville / Marsden coefficients),
 scipy.interpolate.BSpline, scalar brute force vs vectorised form, permutation
-invariance, linearity in gain / additivity in bias, Int8 == fp32 twin.
+invariance, linearity in gain / additivity in bias, Int8 == fp32 twin; for the
+piecewise-linear rule: numpy.interp, reproduction of the node values and of
+every linear function, hat-function integrals, index against brute force.
 """
 from __future__ import annotations
 
@@ -160,6 +171,57 @@ def basis_matrix(x, clamp: bool = True, close_right: bool = True) -> np.ndarray:
     return lvl.reshape(shape + (G,))                             # [..., 10]
 
 
+# --------------------------------------------------------------------------
+# The runtime operator's two-tap rule (paper §4.1 "index lookup [x / dx] followed by a
+# linear interpolation between two codebook entries"; §4.3 LinearInterp(C[k], x))
+# --------------------------------------------------------------------------
+
+def pli_nodes() -> np.ndarray:
+    """The G uniform nodes n_0 = -1 .. n_{G-1} = +1 at which a codeword's entries sit."""
+    return np.array([(2.0 * k - (G - 1)) / (G - 1) for k in range(G)], dtype=np.float64)
+
+
+def pli_index(x) -> np.ndarray:
+    """Lookup index k in 0..G-2 of every (clamped) x: the interval [n_k, n_{k+1}) that holds
+    it, found by search over the interior nodes; x = +1 belongs to the last interval."""
+    n = pli_nodes()
+    return np.searchsorted(n[1:G - 1], clamp_input(x), side="right").astype(np.uint8)
+
+
+def pli_scalar(row, x: float) -> float:
+    """LinearInterp(row, x) for one codeword row (any sequence of G numbers) and one x."""
+    n = pli_nodes()
+    xc = min(max(float(x), X_LO), X_HI)
+    k = 0
+    while k < G - 2 and xc >= n[k + 1]:
+        k += 1
+    u = (xc - n[k]) / (n[k + 1] - n[k])
+    return (1.0 - u) * float(row[k]) + u * float(row[k + 1])
+
+
+def pli_matrix(x) -> np.ndarray:
+    """[..., G] weights of the G entries at every x: (1 - u) on entry k, u on entry k + 1."""
+    n = pli_nodes()
+    x = np.asarray(x, dtype=np.float64)
+    xc = clamp_input(x).reshape(-1)
+    k = pli_index(xc).astype(np.int64)
+    u = (xc - n[k]) / (n[k + 1] - n[k])
+    W = np.zeros((xc.size, G), dtype=np.float64)
+    r = np.arange(xc.size)
+    W[r, k] = 1.0 - u
+    W[r, k + 1] = u
+    return W.reshape(x.shape + (G,))
+
+
+def design_matrix(x, rule: str = "bspline") -> np.ndarray:
+    """Weights of a codeword's G entries at every x under the chosen edge rule."""
+    if rule == "bspline":
+        return basis_matrix(x)
+    if rule == "pli":
+        return pli_matrix(x)
+    raise ValueError(rule)
+
+
 def span_index(x) -> np.ndarray:
     """Interval index l in 0..6 for every (clamped) x, by search over the float64
     interior knots: l = number of interior knots t_4..t_9 that are <= x."""
@@ -186,8 +248,9 @@ def reconstruct_coefficients(codebook, scale, idx, gain, bias) -> np.ndarray:
     return g[..., None] * cb[idx] + b[..., None]
 
 
-def dense_layer_forward(coef, x, return_abs: bool = False):
-    """y[b][j] = sum_i sum_m B_{m,3}(x_bi) * coef[i][j][m]      (paper §3).
+def dense_layer_forward(coef, x, return_abs: bool = False, rule: str = "bspline"):
+    """y[b][j] = sum_i sum_m B_{m,3}(x_bi) * coef[i][j][m]      (paper §3); with rule="pli"
+    the weights B are those of the two-tap interpolation instead.
 
     return_abs additionally gives A[b][j] = sum_i |phi_ij(x_bi)|, the scale
     against which a per-element error is judged.
@@ -197,7 +260,7 @@ def dense_layer_forward(coef, x, return_abs: bool = False):
     assert g == G
     x = np.asarray(x, dtype=np.float64)
     assert x.ndim == 2 and x.shape[1] == n_in
-    Bm = basis_matrix(x)                                         # [B][in][G]
+    Bm = design_matrix(x, rule)                                  # [B][in][G]
     Phi = Bm.reshape(x.shape[0], n_in * G)
     Chat = coef.transpose(0, 2, 1).reshape(n_in * G, n_out)
     y = Phi @ Chat
@@ -210,13 +273,13 @@ def dense_layer_forward(coef, x, return_abs: bool = False):
     return y, A
 
 
-def vq_layer_forward(x, codebook, scale, idx, gain, bias, return_abs: bool = False):
+def vq_layer_forward(x, codebook, scale, idx, gain, bias, return_abs: bool = False, rule: str = "bspline"):
     """Forward pass of one VQ-KAN layer: reconstruct, evaluate, sum over inputs."""
     coef = reconstruct_coefficients(codebook, scale, idx, gain, bias)
-    return dense_layer_forward(coef, x, return_abs=return_abs)
+    return dense_layer_forward(coef, x, return_abs=return_abs, rule=rule)
 
 
-def vq_layer_outputs_at(x, codebook, scale, idx, gain, bias, bs, js, return_abs=False):
+def vq_layer_outputs_at(x, codebook, scale, idx, gain, bias, bs, js, return_abs=False, rule: str = "bspline"):
     """y[b][j] for listed (b, j) pairs only; O(in) work each.  For parity checks
     at sizes where the whole layer is too slow on the CPU."""
     cb = dequantise_codebook(codebook, scale)
@@ -227,7 +290,7 @@ def vq_layer_outputs_at(x, codebook, scale, idx, gain, bias, bs, js, return_abs=
     out = np.empty(len(bs), dtype=np.float64)
     ab = np.empty(len(bs), dtype=np.float64)
     for n, (b, j) in enumerate(zip(bs, js)):
-        Bm = basis_matrix(x[b])                                  # [in][G]
+        Bm = design_matrix(x[b], rule)                           # [in][G]
         c = (gain[:, j].astype(np.float64)[:, None] * cb[idx[:, j].astype(np.int64)]
              + bias[:, j].astype(np.float64)[:, None])           # [in][G]
         phi = (Bm * c).sum(axis=1)
@@ -236,7 +299,7 @@ def vq_layer_outputs_at(x, codebook, scale, idx, gain, bias, bs, js, return_abs=
     return (out, ab) if return_abs else out
 
 
-def vq_head_forward(x, layers, return_hidden: bool = False):
+def vq_head_forward(x, layers, return_hidden: bool = False, rule: str = "bspline"):
     """Multi-layer head: tanh between layers, none after the last.
 
     layers: sequence of dicts with keys codebook, scale, idx, gain, bias.
@@ -244,7 +307,7 @@ def vq_head_forward(x, layers, return_hidden: bool = False):
     a = np.asarray(x, dtype=np.float64)
     hidden = []
     for n, L in enumerate(layers):
-        y = vq_layer_forward(a, L["codebook"], L["scale"], L["idx"], L["gain"], L["bias"])
+        y = vq_layer_forward(a, L["codebook"], L["scale"], L["idx"], L["gain"], L["bias"], rule=rule)
         if n + 1 < len(layers):
             a = np.tanh(y)
             hidden.append(a)

@@ -19,12 +19,13 @@ KAN_OK = 0
 KAN_ERR_NULL, KAN_ERR_SHAPE, KAN_ERR_DTYPE, KAN_ERR_WORKSPACE, KAN_ERR_UNSUPPORTED, KAN_ERR_LAUNCH = 1, 2, 3, 4, 5, 6
 KAN_F32, KAN_F16, KAN_I8, KAN_U16, KAN_U32 = 0, 1, 2, 3, 4
 KAN_PATH_AUTO, KAN_PATH_GATHER, KAN_PATH_MFMA = 0, 1, 2
+KAN_RULE_BSPLINE3, KAN_RULE_PLI2 = 0, 1
 
 EXPORTS = [
     "kan_bspline_basis", "kan_vq_workspace_bytes", "kan_vq_layer_forward",
     "kan_dense_workspace_bytes", "kan_dense_layer_forward", "kan_vq_head_forward",
     "kan_vq_debug_gather", "kan_vq_count_bad_indices", "kan_prof_begin", "kan_prof_end",
-    "kan_status_string", "kan_vq_planned_kernel", "kan_vq_prepared_bytes", "kan_vq_prepare",
+    "kan_status_string", "kan_vq_planned_kernel", "kan_vq_prepared_bytes", "kan_vq_prepare", "kan_pli_basis",
 ]
 
 
@@ -33,7 +34,7 @@ class kan_vq_layer(C.Structure):
         ("n_in", C.c_int32), ("n_out", C.c_int32), ("G", C.c_int32), ("degree", C.c_int32),
         ("K", C.c_int32), ("idx_dtype", C.c_int32), ("gb_dtype", C.c_int32), ("cb_dtype", C.c_int32),
         ("idx", C.c_void_p), ("gain", C.c_void_p), ("bias", C.c_void_p), ("codebook", C.c_void_p),
-        ("scale", C.c_float), ("reserved", C.c_int32), ("prepared", C.c_void_p),
+        ("scale", C.c_float), ("rule", C.c_int32), ("prepared", C.c_void_p),
     ]
 
 
@@ -61,6 +62,8 @@ def lib():
         LP = C.POINTER(kan_vq_layer)
         L.kan_bspline_basis.argtypes = [P, I64, P, P, P]
         L.kan_bspline_basis.restype = I32
+        L.kan_pli_basis.argtypes = [P, I64, P, P, P]
+        L.kan_pli_basis.restype = I32
         L.kan_vq_workspace_bytes.argtypes = [LP, I32, I32, I64, I32]
         L.kan_vq_workspace_bytes.restype = SZ
         L.kan_vq_layer_forward.argtypes = [LP, P, I64, P, P, SZ, I32, P]
@@ -119,7 +122,7 @@ def _ptr(t):
 class VQLayer:
     """Device-resident parameters of one VQ layer plus its C descriptor."""
 
-    def __init__(self, params, device="cuda"):
+    def __init__(self, params, device="cuda", rule=KAN_RULE_BSPLINE3):
         torch = _torch()
         self.n_in, self.n_out, self.K = int(params.n_in), int(params.n_out), int(params.K)
         idx = np.ascontiguousarray(params.idx)
@@ -136,7 +139,7 @@ class VQLayer:
             KAN_F16 if params.gain.dtype == np.float16 else KAN_F32,
             KAN_I8 if params.codebook.dtype == np.int8 else KAN_F32,
             self.idx.data_ptr(), self.gain.data_ptr(), self.bias.data_ptr(), self.codebook.data_ptr(),
-            self.scale, 0, None)
+            self.scale, int(rule), None)
         self.prepared = None
 
     def prepare(self):
@@ -186,6 +189,16 @@ def kan_bspline_basis(x):
     w = torch.empty(tuple(x.shape) + (4,), dtype=torch.float32, device=x.device)
     _check(lib().kan_bspline_basis(_ptr(x), x.numel(), _ptr(span), _ptr(w), _stream_ptr()), "kan_bspline_basis")
     return span, w
+
+
+def kan_pli_basis(x):
+    """x: float32 CUDA tensor (any shape) -> (index uint8 same shape, w float32 [..., 2])."""
+    torch = _torch()
+    x = x.contiguous()
+    index = torch.empty(x.shape, dtype=torch.uint8, device=x.device)
+    w = torch.empty(tuple(x.shape) + (2,), dtype=torch.float32, device=x.device)
+    _check(lib().kan_pli_basis(_ptr(x), x.numel(), _ptr(index), _ptr(w), _stream_ptr()), "kan_pli_basis")
+    return index, w
 
 
 def kan_vq_workspace_bytes(heads, B, path=KAN_PATH_AUTO, strict=True) -> int:

@@ -48,6 +48,7 @@ inline size_t round_up(size_t v, size_t a) { return (v + a - 1) / a * a; }
 kan_status validate_layer(const kan_vq_layer* L) {
   if (!L) return KAN_ERR_NULL;
   if (L->G != 10 || L->degree != 3) return KAN_ERR_UNSUPPORTED;
+  if (L->rule != KAN_RULE_BSPLINE3 && L->rule != KAN_RULE_PLI2) return KAN_ERR_UNSUPPORTED;
   if (L->in < 1 || L->out < 1 || L->in > kMaxDim || L->out > kMaxDim || L->K < 1) return KAN_ERR_SHAPE;
   if (L->idx_dtype != KAN_U16 && L->idx_dtype != KAN_U32) return KAN_ERR_DTYPE;
   if (L->gb_dtype != KAN_F32 && L->gb_dtype != KAN_F16) return KAN_ERR_DTYPE;
@@ -338,7 +339,7 @@ kan_status run_layer_group(const LayerPlan& p, GatherArgs& a, const void* const*
     if (st != KAN_OK) return st;
     const long long u_stride = x_shared ? 0 : (long long)a.n_in * a.B;
     st = run("kan_prep_basis", s, [&] {
-      return launch_prep_basis(a.x, a.x_head_stride, w.u, u_stride, a.n_in, a.B, x_shared ? 1 : heads, s);
+      return launch_prep_basis(a.x, a.x_head_stride, w.u, u_stride, a.n_in, a.B, x_shared ? 1 : heads, a.rule, s);
     });
     if (st != KAN_OK) return st;
     MfmaArgs m;
@@ -382,6 +383,7 @@ kan_status run_layer_group(const LayerPlan& p, GatherArgs& a, const void* const*
     k.rows_shift = g.rows_shift;
     k.cb_bytes = a.cb_bytes;
     k.apply_tanh = tanh_in_kernel;
+    k.rule = a.rule;
     k.off_seg = (long long)g.off_seg;
     k.off_bias = (long long)g.off_bias;
     k.off_i = (long long)g.off_i;
@@ -408,6 +410,7 @@ kan_status run_layer_group(const LayerPlan& p, GatherArgs& a, const void* const*
     f.rows_per_chunk = p.rows_per_chunk;
     f.n_jt = p.n_jt;
     f.apply_tanh = tanh_in_kernel;
+    f.rule = a.rule;
     memcpy(f.h, a.h, sizeof(f.h));
     dim3 grid((unsigned)(p.n_jt * p.n_bt), (unsigned)p.n_chunks, (unsigned)heads);
     st = run(p.name, s, [&] { return launch_fused(p.cfg, f, f32, grid, s); });
@@ -452,7 +455,7 @@ kan_status plan_head(const kan_vq_layer* layers, int32_t n_layers, int32_t n_hea
       if (st != KAN_OK) return st;
       const kan_vq_layer& R = layers[l];
       if (L.in != R.in || L.out != R.out || L.K != R.K || L.idx_dtype != R.idx_dtype ||
-          L.gb_dtype != R.gb_dtype || L.cb_dtype != R.cb_dtype)
+          L.gb_dtype != R.gb_dtype || L.cb_dtype != R.cb_dtype || L.rule != R.rule)
         return KAN_ERR_UNSUPPORTED;
       if (l > 0 && L.in != layers[(size_t)h * n_layers + l - 1].out) return KAN_ERR_SHAPE;
     }
@@ -512,6 +515,15 @@ kan_status kan_bspline_basis(const float* x, int64_t n, uint8_t* span, float* w,
   if (!aligned(w, 16) || !aligned(x, 4)) return KAN_ERR_SHAPE;
   hipStream_t s = (hipStream_t)stream;
   return run("kan_basis", s, [&] { return launch_basis(x, n, span, w, s); });
+}
+
+kan_status kan_pli_basis(const float* x, int64_t n, uint8_t* index, float* w, void* stream) {
+  if (n < 0) return KAN_ERR_SHAPE;
+  if (n == 0) return KAN_OK;
+  if (!x || !index || !w) return KAN_ERR_NULL;
+  if (!aligned(w, 8) || !aligned(x, 4)) return KAN_ERR_SHAPE;
+  hipStream_t s = (hipStream_t)stream;
+  return run("kan_pli_basis", s, [&] { return launch_pli_basis(x, n, index, w, s); });
 }
 
 size_t kan_vq_workspace_bytes(const kan_vq_layer* layers, int32_t n_layers, int32_t n_heads, int64_t B,
@@ -579,6 +591,7 @@ kan_status kan_vq_head_forward(const kan_vq_layer* layers, int32_t n_layers, int
       a.rows_per_chunk = plans[l].rows_per_chunk;
       a.n_jt = plans[l].n_jt;
       a.cb_bytes = (long long)R.K * 10 * (R.cb_dtype == KAN_I8 ? 1 : 4);
+      a.rule = R.rule;
       for (int h = 0; h < heads; ++h) {
         const kan_vq_layer& L = layers[(size_t)(h0 + h) * n_layers + l];
         a.h[h].idx = L.idx;

@@ -189,7 +189,7 @@ __global__ __launch_bounds__(kBucketThreads) void kan_bucket_kernel(const Bucket
       if (r * kBucketThreads < a.n_in) {        // uniform: rounds past the last input are skipped
         const int i = tid + r * kBucketThreads;
         const float xin = a.x_tanh ? tanhf(xv[r]) : xv[r];
-        const BasisW w = basis_eval(xin);
+        const BasisW w = basis_eval_rule(xin, a.rule);
         // (threads past the last input of the round write entries nobody reads)
         bas[i] = make_float4(w.w0, w.w1, w.w2, __uint_as_float((uint32_t)w.span));
       }

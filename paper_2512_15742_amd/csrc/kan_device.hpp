@@ -46,6 +46,73 @@ __device__ __forceinline__ BasisW basis_eval(float xf) {
   return r;
 }
 
+// The runtime rule of the paper's own operator (sections 4.1 and 4.3): the G = 10 entries of a
+// codeword are samples at the uniform nodes n_k = -1 + 2k/9 and the edge function is the
+// linear interpolation between the two neighbours of x, index floor((x + 1) / dx), dx = 2/9.
+// 9x is exact in fp64, so the index is decided exactly by comparing 9x with the odd integers
+// -7..7, and u = (9x + 9 - 2k) / 2 is exact; x = +1 gives k = 8, u = 1 (closed right end).
+// Returned in the same form as the cubic family - a window of four consecutive entries and
+// four weights - so that every kernel serves both rules: the window starts at min(k, 6) and
+// the two weights 1-u, u sit at offset k - min(k, 6) inside it, the others are 0.
+struct PliIndex {
+  int k;        // 0..8
+  double u;     // 0..1
+};
+__device__ __forceinline__ PliIndex pli_index(float xf) {
+  const float xc = fminf(fmaxf(xf, -1.0f), 1.0f);
+  const double x9 = 9.0 * (double)xc;
+  PliIndex r;
+  r.k = (int)(x9 >= -7.0) + (int)(x9 >= -5.0) + (int)(x9 >= -3.0) + (int)(x9 >= -1.0) +
+        (int)(x9 >= 1.0) + (int)(x9 >= 3.0) + (int)(x9 >= 5.0) + (int)(x9 >= 7.0);
+  r.u = (x9 + (double)(9 - 2 * r.k)) * 0.5;
+  return r;
+}
+__device__ __forceinline__ BasisW window_of_pair(int k, float w_lo, float w_hi) {
+  BasisW r;
+  r.span = min(k, kSpans - 1);
+  const int o = k - r.span;                    // 0, 1 or 2
+  r.w0 = o == 0 ? w_lo : 0.f;
+  r.w1 = o == 0 ? w_hi : (o == 1 ? w_lo : 0.f);
+  r.w2 = o == 1 ? w_hi : (o == 2 ? w_lo : 0.f);
+  r.w3 = o == 2 ? w_hi : 0.f;
+  return r;
+}
+__device__ __forceinline__ BasisW basis_eval_pli(float xf) {
+  const PliIndex p = pli_index(xf);
+  return window_of_pair(p.k, (float)(1.0 - p.u), (float)p.u);
+}
+
+enum EdgeRule : int { kRuleBspline3 = 0, kRulePli2 = 1 };
+
+__device__ __forceinline__ BasisW basis_eval_rule(float xf, int rule) {
+  return rule == kRulePli2 ? basis_eval_pli(xf) : basis_eval(xf);
+}
+
+// The same two families with the weights evaluated in fp32 from the exact fp64 index and local
+// coordinate (one fma + truncation instead of the comparisons); used where the weights are
+// about to be rounded to fp16 or feed fp32 matrix-core operands.
+__device__ __forceinline__ BasisW basis_fast(float xf, int rule) {
+  const float xc = fminf(fmaxf(xf, -1.0f), 1.0f);
+  if (rule == kRulePli2) {
+    const double t = fma((double)xc, 4.5, 4.5);          // exact: (9x + 9) / 2
+    const int k = min((int)t, kG - 2);
+    const float u = (float)(t - (double)k);
+    return window_of_pair(k, 1.0f - u, u);
+  }
+  // exact span: t = (7x + 7) / 2 is exact in fp64; span = min(floor(t), 6); the local
+  // coordinate u = t - span is exact too and is rounded once to fp32
+  const double t = fma((double)xc, 3.5, 3.5);
+  BasisW r;
+  r.span = min((int)t, kSpans - 1);
+  const float u = (float)(t - (double)r.span);
+  const float u2 = u * u, u3 = u2 * u, om = 1.0f - u;
+  r.w0 = om * om * om * (1.0f / 6.0f);
+  r.w3 = u3 * (1.0f / 6.0f);
+  r.w1 = fmaf(0.5f, u3, fmaf(-1.0f, u2, 2.0f / 3.0f));
+  r.w2 = fmaf(-0.5f, u3, fmaf(0.5f, u2, fmaf(0.5f, u, 1.0f / 6.0f)));
+  return r;
+}
+
 // ---- streaming loads of N consecutive per-edge values ------------------------
 // The metadata stream is read once per batch tile and never reused, so it is
 // loaded non-temporally to keep it from displacing the codebook in L2.

@@ -138,17 +138,9 @@ __global__ __launch_bounds__(kThreads) void kan_fused_kernel(const FusedArgs a) 
 #pragma unroll
     for (int q = 0; q < NPAIR; ++q) {
       const int ii = NPAIR * ph + q, h = ii >> 2, s = ii & 3;
-      // exact span: t = (7x + 7) / 2 is exact in fp64; span = min(floor(t), 6); the local
-      // coordinate u = t - span is exact too and is rounded once to fp32
-      const float xc = fminf(fmaxf(uv[q], -1.0f), 1.0f);
-      const double t = fma((double)xc, 3.5, 3.5);
-      const int l = min((int)t, kSpans - 1);
-      const float u = (float)(t - (double)l);
-      const float u2 = u * u, u3 = u2 * u, om = 1.0f - u;
-      const float w0 = om * om * om * (1.0f / 6.0f);
-      const float w3 = u3 * (1.0f / 6.0f);
-      const float w1 = fmaf(0.5f, u3, fmaf(-1.0f, u2, 2.0f / 3.0f));
-      const float w2 = fmaf(-0.5f, u3, fmaf(0.5f, u2, fmaf(0.5f, u, 1.0f / 6.0f)));
+      const BasisW bw = basis_fast(uv[q], a.rule);
+      const int l = bw.span;
+      const float w0 = bw.w0, w1 = bw.w1, w2 = bw.w2, w3 = bw.w3;
       if constexpr (F32) {
         float* p = (float*)tile + pb * LDF + h * 40 + s * kG;      // 8-byte aligned
         const float2 z = make_float2(0.f, 0.f);

@@ -107,7 +107,7 @@ __global__ __launch_bounds__(kThreads) void kan_gather_kernel(const GatherArgs a
     for (int t = tid; t < kSub * BT; t += kThreads) {
       const int bb = t / kSub, r = t % kSub;
       BasisW bw = {0.f, 0.f, 0.f, 0.f, 0};
-      if (r < rows && b0 + bb < a.B) bw = basis_eval(xh[(long long)(b0 + bb) * n_in + s0 + r]);
+      if (r < rows && b0 + bb < a.B) bw = basis_eval_rule(xh[(long long)(b0 + bb) * n_in + s0 + r], a.rule);
       if constexpr (kWindow) {
         sw[r] = make_float4(bw.w0, bw.w1, bw.w2, bw.w3);
         ss[r] = bw.span;

@@ -43,6 +43,7 @@ struct GatherArgs {
   int n_jt;                    // j-tiles; blockIdx.x = bt_index * n_jt + jt
   int apply_tanh;              // only honoured when the kernel writes final values
   long long cb_bytes;          // codebook bytes per head (0: no L2 warm-up of the codebook)
+  int rule;                    // edge function: 0 cubic B-spline, 1 two-tap linear interpolation
   LayerPtrs h[kMaxGroup];
 };
 
@@ -80,7 +81,7 @@ struct MfmaArgs {
 
 hipError_t launch_prep_coef(const GatherCfg&, const PrepCoefArgs&, int heads, hipStream_t);
 hipError_t launch_prep_basis(const float* x, long long x_head_stride, uint2* W, long long w_head_stride,
-                             int n_in, int B, int heads, hipStream_t);
+                             int n_in, int B, int heads, int rule, hipStream_t);
 hipError_t launch_mfma(const MfmaArgs&, int tile_m, dim3 grid, hipStream_t);   // tile_m: samples per tile (64)
 
 // ---- fused gather + matrix-core kernel (batch tiles of 32 or 64 samples) --------------
@@ -95,6 +96,7 @@ struct FusedArgs {
   int rows_per_chunk;          // multiple of 8
   int n_jt;                    // output tiles; blockIdx.x = batch_tile * n_jt + jt
   int apply_tanh;
+  int rule;                    // edge function: 0 cubic B-spline, 1 two-tap linear interpolation
   LayerPtrs h[kMaxGroup];
 };
 
@@ -159,6 +161,7 @@ struct BucketArgs {
   int rows_shift;
   long long cb_bytes;          // whole codebook, bytes
   int apply_tanh;              // honoured only when n_buckets == 1
+  int rule;                    // edge function: 0 cubic B-spline, 1 two-tap linear interpolation
   long long off_seg, off_bias, off_i, off_q, off_g;
   BucketHead h[kMaxGroup];
 };
@@ -176,6 +179,7 @@ hipError_t launch_reduce(const float* partial, long long head_stride, long long 
 
 // ---- debug / parity kernels -------------------------------------------------------
 hipError_t launch_basis(const float* x, long long n, uint8_t* span, float* w, hipStream_t);
+hipError_t launch_pli_basis(const float* x, long long n, uint8_t* index, float* w, hipStream_t);
 hipError_t launch_debug_gather(const LayerPtrs&, int idx_u32, int cb_i8, long long edges,
                                uint32_t* ids, float* rows, hipStream_t);
 hipError_t launch_count_bad(const void* idx, int idx_u32, long long edges, uint32_t K,

@@ -119,7 +119,7 @@ __global__ __launch_bounds__(kThreads) void kan_prep_coef_kernel(const PrepCoefA
 // w0, w1, w2 (the weights are never negative).
 __global__ __launch_bounds__(256) void kan_prep_basis_kernel(const float* __restrict__ x, long long x_head_stride,
                                                              uint2* __restrict__ W, long long w_head_stride,
-                                                             int n_in, int B) {
+                                                             int n_in, int B, int rule) {
   __shared__ uint2 tile[32][33];
   const int head = blockIdx.z;
   const float* xh = x + (long long)head * x_head_stride;
@@ -131,17 +131,9 @@ __global__ __launch_bounds__(256) void kan_prep_basis_kernel(const float* __rest
     const int b = bb + ty + 8 * r, i = ib + tx;
     uint2 v = make_uint2(0u, 0u);
     if (b < B && i < n_in) {
-      const float xc = fminf(fmaxf(xh[(long long)b * n_in + i], -1.0f), 1.0f);
-      // exact span: t = (7x + 7) / 2 is exact in fp64; span = min(floor(t), 6); the local
-      // coordinate u = t - span is exact too and is rounded once to fp32
-      const double t = fma((double)xc, 3.5, 3.5);
-      const uint32_t l = (uint32_t)min((int)t, kSpans - 1);
-      const float u = (float)(t - (double)l);
-      const float u2 = u * u, u3 = u2 * u, om = 1.0f - u;
-      const float w0 = om * om * om * (1.0f / 6.0f);
-      const float w3 = u3 * (1.0f / 6.0f);
-      const float w1 = fmaf(0.5f, u3, fmaf(-1.0f, u2, 2.0f / 3.0f));
-      const float w2 = fmaf(-0.5f, u3, fmaf(0.5f, u2, fmaf(0.5f, u, 1.0f / 6.0f)));
+      const BasisW bw = basis_fast(xh[(long long)b * n_in + i], rule);
+      const uint32_t l = (uint32_t)bw.span;
+      const float w0 = bw.w0, w1 = bw.w1, w2 = bw.w2, w3 = bw.w3;
       v.x = pack_h2(w0, w1) | ((l & 1u) << 15) | ((l & 2u) << 30);
       v.y = pack_h2(w2, w3) | ((l & 4u) << 13);
     }
@@ -342,9 +334,9 @@ hipError_t launch_prep_coef(const GatherCfg& c, const PrepCoefArgs& a, int heads
 }
 
 hipError_t launch_prep_basis(const float* x, long long x_head_stride, uint2* W, long long w_head_stride,
-                             int n_in, int B, int heads, hipStream_t s) {
+                             int n_in, int B, int heads, int rule, hipStream_t s) {
   dim3 grid((n_in + 31) / 32, (B + 31) / 32, heads);
-  hipLaunchKernelGGL(kan_prep_basis_kernel, grid, dim3(256), 0, s, x, x_head_stride, W, w_head_stride, n_in, B);
+  hipLaunchKernelGGL(kan_prep_basis_kernel, grid, dim3(256), 0, s, x, x_head_stride, W, w_head_stride, n_in, B, rule);
   return hipGetLastError();
 }
 

@@ -61,6 +61,17 @@ __global__ __launch_bounds__(256) void kan_basis_kernel(const float* __restrict_
   }
 }
 
+// Index k (0..8) and the two weights (1 - u, u) of the two-tap rule, for parity checks.
+__global__ __launch_bounds__(256) void kan_pli_basis_kernel(const float* __restrict__ x, long long n,
+                                                            uint8_t* __restrict__ index, float* __restrict__ w) {
+  for (long long t = (long long)blockIdx.x * blockDim.x + threadIdx.x; t < n;
+       t += (long long)gridDim.x * blockDim.x) {
+    const PliIndex p = pli_index(x[t]);
+    index[t] = (uint8_t)p.k;
+    ((float2*)w)[t] = make_float2((float)(1.0 - p.u), (float)p.u);
+  }
+}
+
 template <typename IdxT, typename CbT>
 __global__ __launch_bounds__(256) void kan_debug_gather_kernel(const IdxT* __restrict__ idx,
                                                                const CbT* __restrict__ cb, float scale,
@@ -125,6 +136,11 @@ hipError_t launch_reduce(const float* partial, long long head_stride, long long 
 
 hipError_t launch_basis(const float* x, long long n, uint8_t* span, float* w, hipStream_t s) {
   hipLaunchKernelGGL(kan_basis_kernel, dim3(blocks_for(n)), dim3(256), 0, s, x, n, span, w);
+  return hipGetLastError();
+}
+
+hipError_t launch_pli_basis(const float* x, long long n, uint8_t* index, float* w, hipStream_t s) {
+  hipLaunchKernelGGL(kan_pli_basis_kernel, dim3(blocks_for(n)), dim3(256), 0, s, x, n, index, w);
   return hipGetLastError();
 }
 

@@ -44,7 +44,7 @@ def test_status_strings():
 def _desc(**kw):
     base = dict(n_in=8, n_out=8, G=10, degree=3, K=16, idx_dtype=kb.KAN_U16, gb_dtype=kb.KAN_F32,
                 cb_dtype=kb.KAN_F32, idx=0x1000, gain=0x2000, bias=0x3000, codebook=0x4000,
-                scale=1.0, reserved=0, prepared=None)
+                scale=1.0, rule=0, prepared=None)
     base.update(kw)
     return kb.kan_vq_layer(**base)
 
@@ -55,6 +55,7 @@ FAKE = C.c_void_p(0x10000)
 @pytest.mark.parametrize("kw,status", [
     (dict(G=8), kb.KAN_ERR_UNSUPPORTED),
     (dict(degree=2), kb.KAN_ERR_UNSUPPORTED),
+    (dict(rule=2), kb.KAN_ERR_UNSUPPORTED),
     (dict(n_in=0), kb.KAN_ERR_SHAPE),
     (dict(n_out=-3), kb.KAN_ERR_SHAPE),
     (dict(K=0), kb.KAN_ERR_SHAPE),
@@ -89,6 +90,9 @@ def test_forward_argument_errors():
     assert L.kan_bspline_basis(None, 0, None, None, None) == kb.KAN_OK
     assert L.kan_bspline_basis(None, 5, FAKE, FAKE, None) == kb.KAN_ERR_NULL
     assert L.kan_bspline_basis(FAKE, -1, FAKE, FAKE, None) == kb.KAN_ERR_SHAPE
+    assert L.kan_pli_basis(None, 0, None, None, None) == kb.KAN_OK
+    assert L.kan_pli_basis(FAKE, 5, None, FAKE, None) == kb.KAN_ERR_NULL
+    assert L.kan_pli_basis(FAKE, -1, FAKE, FAKE, None) == kb.KAN_ERR_SHAPE
     assert L.kan_dense_layer_forward(FAKE, 8, 8, 9, FAKE, 4, FAKE, None, 0, None) == kb.KAN_ERR_UNSUPPORTED
     assert L.kan_dense_layer_forward(FAKE, 0, 8, 10, FAKE, 4, FAKE, None, 0, None) == kb.KAN_ERR_SHAPE
     assert L.kan_dense_layer_forward(None, 8, 8, 10, FAKE, 4, FAKE, None, 0, None) == kb.KAN_ERR_NULL
@@ -145,6 +149,9 @@ def test_head_table_consistency():
     arr[2] = _desc(n_in=32, n_out=16)
     arr[3] = _desc(n_in=16, n_out=4)
     assert L.kan_vq_workspace_bytes(arr, 2, 2, 8, 0) != kb.SIZE_INVALID
+    arr[2] = _desc(n_in=32, n_out=16, rule=kb.KAN_RULE_PLI2)       # heads must share the edge rule
+    assert L.kan_vq_head_forward(arr, 2, 2, FAKE, 8, FAKE, FAKE, 1 << 24, 0, None) == kb.KAN_ERR_UNSUPPORTED
+    arr[2] = _desc(n_in=32, n_out=16)
     arr[3] = _desc(n_in=16, n_out=5)            # heads must share layer shapes
     assert L.kan_vq_head_forward(arr, 2, 2, FAKE, 8, FAKE, FAKE, 1 << 24, 0, None) == kb.KAN_ERR_UNSUPPORTED
     arr[1] = _desc(n_in=15, n_out=4)            # layer chain broken: 16 -> 15

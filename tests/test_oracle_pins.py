@@ -303,3 +303,213 @@ def test_error_report():
     rep = ko.error_report(y + 1e-3, y, np.full_like(y, 10.0))
     assert abs(rep["headline"] - 1e-3 / 4) < 1e-12
     assert abs(rep["strict"] - 1e-4) < 1e-12
+
+
+# ---- the runtime operator's two-tap rule (paper §4.1, §4.3) ---------------------------
+
+def _pli_probe():
+    n = ko.pli_nodes()
+    pts = [np.linspace(-1.0, 1.0, 1801)]
+    for k in n:
+        f = np.float32(k)
+        pts.append(np.array([k, np.nextafter(k, -2), np.nextafter(k, 2), float(f),
+                             float(np.nextafter(f, np.float32(-2))), float(np.nextafter(f, np.float32(2)))]))
+    x = np.concatenate(pts)
+    return x[(x >= -1.0) & (x <= 1.0)]
+
+
+def test_pli_nodes_and_index():
+    """Nodes: G of them, uniform, ends exact.  Index: the interval that holds x, by brute
+    force over all intervals; the last one closed on the right."""
+    n = ko.pli_nodes()
+    assert len(n) == ko.G and n[0] == -1.0 and n[-1] == 1.0
+    assert np.allclose(np.diff(n), 2.0 / 9.0, rtol=0, atol=1e-15)
+    x = _pli_probe()
+    k = ko.pli_index(x)
+    for xv, kv in zip(x, k):
+        inside = [m for m in range(ko.G - 1) if n[m] <= xv < n[m + 1]]
+        assert kv == (inside[0] if inside else ko.G - 2)
+    assert ko.pli_index(np.array([-1.0, 1.0, -5.0, 7.0])).tolist() == [0, 8, 0, 8]
+
+
+def test_pli_is_linear_interpolation_numpy_interp():
+    """The library routine for exactly this operation."""
+    rng = np.random.default_rng(3)
+    x = np.concatenate([_pli_probe(), [-3.0, 2.5]])
+    n = ko.pli_nodes()
+    for _ in range(5):
+        row = rng.standard_normal(ko.G)
+        ref = np.interp(np.clip(x, -1, 1), n, row)
+        got = ko.pli_matrix(x) @ row
+        assert np.abs(got - ref).max() < 1e-14
+        assert abs(ko.pli_scalar(row, 0.3337) - np.interp(0.3337, n, row)) < 1e-15
+
+
+def test_pli_reproduces_node_values_linear_functions_and_unity():
+    n = ko.pli_nodes()
+    W = ko.pli_matrix(_pli_probe())
+    assert np.abs(W.sum(axis=-1) - 1).max() < 1e-15                  # weights sum to 1
+    assert (W >= 0).all() and ((W > 0).sum(axis=-1) <= 2).all()      # at most two taps
+    assert np.abs(ko.pli_matrix(n) - np.eye(ko.G)).max() < 1e-15     # entry k is the value at node k
+    row = 0.75 * n - 0.2                                             # samples of a linear function
+    x = _pli_probe()
+    assert np.abs(W @ row - (0.75 * x - 0.2)).max() < 1e-15
+    # hat functions: integral of an interior one is dx, of an end one dx / 2 (brute force)
+    xs = np.linspace(-1, 1, 180001)
+    area = np.trapezoid(ko.pli_matrix(xs), xs, axis=0) if hasattr(np, "trapezoid") else np.trapz(ko.pli_matrix(xs), xs, axis=0)
+    assert np.abs(area[1:-1] - 2.0 / 9.0).max() < 1e-9
+    assert abs(area[0] - 1.0 / 9.0) < 1e-9 and abs(area[-1] - 1.0 / 9.0) < 1e-9
+
+
+def test_pli_layer_closed_forms_and_scalar_definition():
+    """Layer level: constant codeword => gain*v + bias; linear codeword => a matrix-vector
+    product; vectorised form == scalar definition summed edge by edge."""
+    rng = np.random.default_rng(11)
+    n_in, n_out, K, B = 5, 4, 6, 7
+    cb = rng.standard_normal((K, ko.G))
+    cb[2] = 0.37                                                     # constant codeword
+    cb[4] = ko.pli_nodes()                                           # C[4](x) = x
+    idx = rng.integers(0, K, size=(n_in, n_out))
+    gain = np.abs(rng.normal(0, 0.1, size=(n_in, n_out)))
+    bias = rng.normal(0, 0.01, size=(n_in, n_out))
+    x = rng.uniform(-1.2, 1.2, size=(B, n_in))
+    y = ko.vq_layer_forward(x, cb, 1.0, idx, gain, bias, rule="pli")
+    ref = np.zeros((B, n_out))
+    for b in range(B):
+        for i in range(n_in):
+            for j in range(n_out):
+                ref[b, j] += gain[i, j] * ko.pli_scalar(cb[idx[i, j]], x[b, i]) + bias[i, j]      # Eq. (1)
+    assert np.abs(y - ref).max() < 1e-13
+    idx2 = np.full((n_in, n_out), 2)
+    y2 = ko.vq_layer_forward(x, cb, 1.0, idx2, gain, bias, rule="pli")
+    assert np.abs(y2 - (0.37 * gain + bias).sum(axis=0)[None, :]).max() < 1e-14
+    idx4 = np.full((n_in, n_out), 4)
+    y4 = ko.vq_layer_forward(x, cb, 1.0, idx4, gain, bias, rule="pli")
+    assert np.abs(y4 - (np.clip(x, -1, 1) @ gain + bias.sum(axis=0)[None, :])).max() < 1e-14
+    # the two rules are different functions of the same ten numbers
+    assert np.abs(y - ko.vq_layer_forward(x, cb, 1.0, idx, gain, bias)).max() > 1e-3
+    # sampled form and head chaining use the same rule
+    bs, js = np.array([0, 3, 6]), np.array([1, 0, 3])
+    assert np.abs(ko.vq_layer_outputs_at(x, cb, 1.0, idx, gain, bias, bs, js, rule="pli") - y[bs, js]).max() < 1e-14
+
+
+# ---- the pins bite: a planted mistake in the oracle fails at least one of them ----------
+
+def _pin_suite():
+    """The pins that exercise the oracle's arithmetic, as callables."""
+    return [test_partition_of_unity_and_support, test_span_matches_scalar_search_and_ends,
+            test_closed_form_weights_at_knot_and_midpoint, test_basis_integrals, test_linear_precision_greville,
+            test_quadratic_precision_marsden, test_layer_closed_form_linear_shapes, test_constant_codeword,
+            test_against_scipy_bspline, test_vq_equals_dense_on_reconstructed,
+            test_permutation_linearity_additivity, test_int8_equals_fp32_twin,
+            test_head_is_layers_with_tanh_between, test_pli_nodes_and_index,
+            test_pli_is_linear_interpolation_numpy_interp,
+            test_pli_reproduces_node_values_linear_functions_and_unity,
+            test_pli_layer_closed_forms_and_scalar_definition,
+            lambda: test_scalar_definition_vs_vectorised(False), lambda: test_scalar_definition_vs_vectorised(True)]
+
+
+def _fails_some_pin():
+    for pin in _pin_suite():
+        try:
+            pin()
+        except AssertionError:
+            return True
+        except Exception:
+            return True
+    return False
+
+
+def _mutations():
+    """(name, attribute of the oracle module, replacement) - each a plausible slip."""
+    real = {k: getattr(ko, k) for k in ("knots", "basis_matrix", "reconstruct_coefficients", "dequantise_codebook",
+                                        "dense_layer_forward", "pli_matrix", "pli_nodes", "clamp_input",
+                                        "vq_head_forward")}
+
+    def knots_shifted():                       # knot vector off by one interval
+        return real["knots"]() + 2.0 / 7.0
+
+    def knots_wrong_spacing():                 # 8 intervals instead of 7
+        return np.array([(2.0 * (m - 3) - 8) / 8 for m in range(14)])
+
+    def basis_reversed(x, *a, **k):            # coefficient order reversed
+        return real["basis_matrix"](x, *a, **k)[..., ::-1]
+
+    def basis_dropped_term(x, *a, **k):        # last basis lost
+        Bm = real["basis_matrix"](x, *a, **k).copy()
+        Bm[..., -1] = 0.0
+        return Bm
+
+    def recon_no_bias(cb, scale, idx, gain, bias):
+        return real["reconstruct_coefficients"](cb, scale, idx, gain, np.zeros_like(np.asarray(bias, dtype=np.float64)))
+
+    def recon_transposed_idx(cb, scale, idx, gain, bias):
+        idx = np.asarray(idx)
+        if idx.shape[0] == idx.shape[1]:
+            idx = idx.T
+        else:
+            idx = idx[::-1]
+        return real["reconstruct_coefficients"](cb, scale, idx, gain, bias)
+
+    def recon_gain_on_bias(cb, scale, idx, gain, bias):     # g * (C + b) instead of g * C + b
+        c = real["dequantise_codebook"](cb, scale)
+        g = np.asarray(gain, dtype=np.float64)
+        b = np.asarray(bias, dtype=np.float64)
+        return g[..., None] * (c[np.asarray(idx).astype(np.int64)] + b[..., None])
+
+    def dequant_ignores_scale(cb, scale=1.0):
+        return np.asarray(cb).astype(np.float64)
+
+    def dequant_unsigned(cb, scale=1.0):        # int8 read as uint8
+        cb = np.asarray(cb)
+        if cb.dtype == np.int8:
+            return np.float64(np.float32(scale)) * cb.view(np.uint8).astype(np.float64)
+        return cb.astype(np.float64)
+
+    def dense_sums_wrong_axis(coef, x, return_abs=False, rule="bspline"):
+        coef = np.asarray(coef, dtype=np.float64)
+        y = real["dense_layer_forward"](np.ascontiguousarray(coef[:, ::-1, :]), x, rule=rule)     # outputs reversed
+        return (y, np.abs(y)) if return_abs else y
+
+    def pli_swapped_taps(x):                   # u and 1-u exchanged
+        W = real["pli_matrix"](x)
+        k = ko.pli_index(np.asarray(x, dtype=np.float64).reshape(-1)).astype(np.int64)
+        flat = W.reshape(-1, ko.G)
+        o = np.zeros_like(flat)
+        r = np.arange(flat.shape[0])
+        o[r, k] = flat[r, k + 1]
+        o[r, k + 1] = flat[r, k]
+        return o.reshape(W.shape)
+
+    def pli_nodes_ten_intervals():             # dx = 2/G instead of 2/(G-1)
+        return np.array([-1.0 + 2.0 * k / ko.G for k in range(ko.G)])
+
+    def no_clamp(x):
+        return np.asarray(x, dtype=np.float64)
+
+    def head_tanh_after_last(x, layers, return_hidden=False, rule="bspline"):
+        out = real["vq_head_forward"](x, layers, return_hidden=return_hidden, rule=rule)
+        if return_hidden:
+            return np.tanh(out[0]), out[1]
+        return np.tanh(out)
+
+    return [("knots shifted", "knots", knots_shifted), ("8 intervals", "knots", knots_wrong_spacing),
+            ("bases reversed", "basis_matrix", basis_reversed), ("basis dropped", "basis_matrix", basis_dropped_term),
+            ("bias dropped", "reconstruct_coefficients", recon_no_bias),
+            ("idx transposed", "reconstruct_coefficients", recon_transposed_idx),
+            ("gain applied to bias", "reconstruct_coefficients", recon_gain_on_bias),
+            ("scale ignored", "dequantise_codebook", dequant_ignores_scale),
+            ("int8 read unsigned", "dequantise_codebook", dequant_unsigned),
+            ("outputs reversed", "dense_layer_forward", dense_sums_wrong_axis),
+            ("taps swapped", "pli_matrix", pli_swapped_taps), ("dx = 2/G", "pli_nodes", pli_nodes_ten_intervals),
+            ("no clamp", "clamp_input", no_clamp), ("tanh after last layer", "vq_head_forward", head_tanh_after_last)]
+
+
+def test_pins_pass_unmutated():
+    assert not _fails_some_pin()
+
+
+@pytest.mark.parametrize("name,attr,repl", _mutations(), ids=[m[0] for m in _mutations()])
+def test_planted_mistake_fails_a_pin(monkeypatch, name, attr, repl):
+    monkeypatch.setattr(ko, attr, repl)
+    assert _fails_some_pin(), f"no pin notices: {name}"
