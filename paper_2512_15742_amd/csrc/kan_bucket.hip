@@ -98,7 +98,8 @@ __global__ __launch_bounds__(kBucketThreads) void kan_bucket_kernel(const Bucket
   const uint32_t blk_lo = seg[j0], blk_hi = seg[j1];
 
   // Loads are issued in the order their data is needed (they return in order): the inputs
-  // of the sample, the codebook bucket, the segment table, then two passes of records.
+  // of the sample, the codebook bucket, the segment table; then, after the basis table has
+  // been built from the inputs, two passes of records.
 
   // ---- (1) inputs: x itself, or the previous layer's per-bucket sums still to be added
   //          (fixed order) and squashed ----------------------------------------------------
@@ -127,24 +128,6 @@ __global__ __launch_bounds__(kBucketThreads) void kan_bucket_kernel(const Bucket
         for (int r = 0; r < kXPerThread; ++r) xv[r] += (p0 + pp < a.x_parts) ? t[pp][r] : 0.f;
     }
   }
-
-  // ---- (4) records.  Pass p covers edges [base + p * 8192, + 8192), base = blk_lo rounded
-  //          down to a multiple of 8, so that every thread's group of 8 is 16-byte aligned.
-  //          Groups past the block re-read its last group; the arrays are padded, so a group
-  //          that straddles the end of the last block stays inside the buffer. -----------------
-  const uint32_t base = blk_lo & ~7u;
-  const uint32_t last_group = blk_hi > 0u ? (blk_hi - 1u) & ~7u : 0u;
-  const int n_pass = blk_hi > blk_lo ? (int)((blk_hi - base + kPass - 1) / kPass) : 0;
-  auto load_pass = [&](PassRegs<GF16>& c, int p) {
-    const uint32_t e0 = min(base + (uint32_t)p * kPass + (uint32_t)tid * kEpt, last_group);
-    c.i = __builtin_nontemporal_load((const u32x4*)(pi + e0));
-    c.q = __builtin_nontemporal_load((const u32x4*)(pq + e0));
-    c.g0 = __builtin_nontemporal_load((const u32x4*)(pg + (size_t)e0 * kGainBytes));
-    if constexpr (!GF16) c.g1 = __builtin_nontemporal_load((const u32x4*)(pg + (size_t)e0 * kGainBytes) + 1);
-  };
-  PassRegs<GF16> A, B;
-  load_pass(A, 0);
-  load_pass(B, 1);
 
   // ---- (2) codebook bucket, 16 bytes per thread and round.  The workgroups of a bucket
   //          start at different offsets so that they do not all ask the same L2 channel
@@ -195,6 +178,28 @@ __global__ __launch_bounds__(kBucketThreads) void kan_bucket_kernel(const Bucket
       }
     }
   }
+  // ---- (4) records (their addresses need the block's bounds, two dependent scalar loads that
+  //          have had the basis evaluation above to arrive).  Pass p covers edges
+  //          [base + p * 8192, + 8192), base = blk_lo rounded down to a multiple of 8, so that
+  //          every thread's group of 8 is 16-byte aligned.
+  //          Groups past the block re-read its last group; the arrays are padded, so a group
+  //          that straddles the end of the last block stays inside the buffer. -----------------
+  const uint32_t base = blk_lo & ~7u;
+  const uint32_t last_group = blk_hi > 0u ? (blk_hi - 1u) & ~7u : 0u;
+  const int n_pass = blk_hi > blk_lo ? (int)((blk_hi - base + kPass - 1) / kPass) : 0;
+  auto load_pass = [&](PassRegs<GF16>& c, int p) {
+    const uint32_t e0 = min(base + (uint32_t)p * kPass + (uint32_t)tid * kEpt, last_group);
+    c.i = __builtin_nontemporal_load((const u32x4*)(pi + e0));
+    c.q = __builtin_nontemporal_load((const u32x4*)(pq + e0));
+    c.g0 = __builtin_nontemporal_load((const u32x4*)(pg + (size_t)e0 * kGainBytes));
+    if constexpr (!GF16) c.g1 = __builtin_nontemporal_load((const u32x4*)(pg + (size_t)e0 * kGainBytes) + 1);
+  };
+  PassRegs<GF16> A, B;
+  load_pass(A, 0);
+  load_pass(B, 1);
+
+  __builtin_amdgcn_sched_barrier(0);
+
   // ---- codebook rows, segment table -> LDS (unconditional stores: a store inside a branch
   //      would pull its load into the branch, behind all the others) ------------------------------
   {
