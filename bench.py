@@ -122,8 +122,12 @@ def sweep(kb, torch, synth):
         torch.cuda.synchronize()
         return (time.perf_counter() - t0) / reps
 
-    def vq_rows(tag, heads_p, x, paths, reps):
-        heads = [[kb.VQLayer(p) for p in ps] for ps in heads_p]
+    def vq_rows(tag, heads_p, x, paths, reps, prepared=False, rule=0):
+        heads = [[kb.VQLayer(p, rule=rule) for p in ps] for ps in heads_p]
+        if prepared:
+            for ls in heads:
+                for L in ls:
+                    L.prepare()
         xd = torch.from_numpy(x).cuda()
         B = x.shape[0]
         E = sum(p.edges for ps in heads_p for p in ps)
@@ -132,7 +136,8 @@ def sweep(kb, torch, synth):
             ws = torch.empty(max(kb.kan_vq_workspace_bytes(heads, B, path), 256), dtype=torch.uint8, device="cuda")
             y = torch.empty((len(heads), B, heads_p[0][-1].n_out), dtype=torch.float32, device="cuda")
             t = wall(lambda: kb.kan_vq_head_forward(heads, xd, path=path, ws=ws, y=y), reps)
-            print(json.dumps({"workload": tag, "batch": B, "path": name, "us_per_forward": round(t * 1e6, 2),
+            print(json.dumps({"workload": tag, "batch": B, "path": name, "prepared": bool(prepared),
+                              "rule": "pli2" if rule else "bspline3", "us_per_forward": round(t * 1e6, 2),
                               "edge_evals_per_s": E * B / t, "metadata_GBps": meta / t / 1e9,
                               "kernel": kb.kan_vq_planned_kernel(heads[0][0], B, len(heads), path)}), flush=True)
 
@@ -143,6 +148,8 @@ def sweep(kb, torch, synth):
     for B in (1, 16, 256):
         ps, x = synth.config2(B)
         vq_rows("config2 2048->512 K=65536 fp32", [ps], x, both, 30)
+        if B == 1:
+            vq_rows("config2 2048->512 K=65536 fp32", [ps], x, both[:1], 30, prepared=True)
         coef = torch.from_numpy(ko.reconstruct_coefficients(**ps[0].as_dict()).astype("float32")).cuda()
         xd = torch.from_numpy(x).cuda()
         ws = torch.empty(max(kb.kan_dense_workspace_bytes(2048, 512, B), 256), dtype=torch.uint8, device="cuda")
@@ -152,9 +159,21 @@ def sweep(kb, torch, synth):
                           "us_per_forward": round(t * 1e6, 2), "edge_evals_per_s": 2048 * 512 * B / t,
                           "coef_GBps": coef.numel() * 4 / t / 1e9}), flush=True)
         del coef
-    for B in (1, 16, 256, 1024, 4096):
+    for B in (1, 2, 4, 16, 64, 256, 1024, 4096):
         ps, x = synth.config3(B)
         vq_rows("config3 Int8 head 2048->1024->256", [ps], x, both if B <= 1024 else both[1:], 30 if B <= 256 else 10)
+        if B <= 4:
+            vq_rows("config3 Int8 head 2048->1024->256", [ps], x, both[:1], 30, prepared=True)
+    # the runtime operator's two-tap rule on the same head
+    for B, paths, prepared in ((1, both[:1], True), (16, both, False), (1024, both[1:], False)):
+        ps, x = synth.config3(B)
+        vq_rows("config3 Int8 head 2048->1024->256", [ps], x, paths, 30 if B <= 256 else 10, prepared=prepared,
+                rule=kb.KAN_RULE_PLI2)
+    # the fully quantised 4-bytes-per-edge format (one-byte logarithmic gain, one-byte linear bias)
+    for B, paths, prepared in ((1, both[:1], False), (1, both[:1], True), (16, both, False), (1024, both[1:], False)):
+        ps = synth.config3_layers("q8")
+        vq_rows("config3 shape, 4 B/edge (q8 gain/bias)", [ps], synth.make_x(3900 + B, B, 2048, "uniform"), paths,
+                30 if B <= 256 else 10, prepared=prepared)
     heads_p, x = synth.config4(50, 64)
     vq_rows("config4 50 Int8 heads 2048->256->21", heads_p, x, both, 10)
     for variant in ("i8", "f32"):

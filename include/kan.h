@@ -48,7 +48,10 @@ typedef enum kan_status {
   KAN_ERR_LAUNCH = 6       /* the HIP runtime rejected a launch                   */
 } kan_status;
 
-typedef enum kan_dtype { KAN_F32 = 0, KAN_F16 = 1, KAN_I8 = 2, KAN_U16 = 3, KAN_U32 = 4 } kan_dtype;
+typedef enum kan_dtype {
+  KAN_F32 = 0, KAN_F16 = 1, KAN_I8 = 2, KAN_U16 = 3, KAN_U32 = 4,
+  KAN_Q8 = 5   /* gain and bias as one byte each: logarithmic gain code, linear bias code */
+} kan_dtype;
 
 /* Which arithmetic carries the edge evaluation.
  *   KAN_PATH_GATHER  the precise path: fp32 operands, fp32 accumulation; matches the
@@ -81,7 +84,7 @@ typedef struct kan_vq_layer {
   int32_t G, degree;     /* must be 10 and 3 (App. A.1), else KAN_ERR_UNSUPPORTED   */
   int32_t K;             /* codebook entries, >= 1; <= 65536 when idx is KAN_U16    */
   int32_t idx_dtype;     /* KAN_U16 | KAN_U32                                       */
-  int32_t gb_dtype;      /* KAN_F32 | KAN_F16 (gain and bias share it)              */
+  int32_t gb_dtype;      /* KAN_F32 | KAN_F16 | KAN_Q8 (gain and bias share it)     */
   int32_t cb_dtype;      /* KAN_F32 | KAN_I8                                        */
   const void* idx;       /* [in][out]                                               */
   const void* gain;      /* [in][out]                                               */
@@ -91,6 +94,15 @@ typedef struct kan_vq_layer {
   int32_t rule;          /* KAN_RULE_BSPLINE3 (0) | KAN_RULE_PLI2                   */
   const void* prepared;  /* NULL, or the buffer kan_vq_prepare filled for this very
                             layer (small-batch path, see below)                     */
+  /* KAN_Q8 only (section 4.2: "gains via logarithmic Int8, biases via linear Int8", 16 bits
+   * per edge beside the index; the paper prints no formula, this is the reading used here):
+   *   gain[e] is an unsigned byte: 0 means 0, code c in 1..255 means
+   *           exp2(gain_log2_lo + gain_log2_step * c);
+   *   bias[e] is a signed byte:    bias_scale * c, c in -127..127.
+   * Needs cb_dtype == KAN_I8 (the fully quantised 4-bytes-per-edge format), else
+   * KAN_ERR_UNSUPPORTED.  Ignored for the other gain/bias dtypes.                            */
+  float gain_log2_lo, gain_log2_step, bias_scale;
+  int32_t reserved;      /* set to 0                                                */
 } kan_vq_layer;
 
 /* Spans and basis weights of step "index lookup" (section 4.1) for the cubic

@@ -43,7 +43,9 @@ weights, linear and quadratic precision (Greville / Marsden coefficients),
 scipy.interpolate.BSpline, scalar brute force vs vectorised form, permutation
 invariance, linearity in gain / additivity in bias, Int8 == fp32 twin; for the
 piecewise-linear rule: numpy.interp, reproduction of the node values and of
-every linear function, hat-function integrals, index against brute force.
+every linear function, hat-function integrals, index against brute force; for
+byte-coded gain/bias: exact powers of two at integer exponents, zero code,
+monotonicity, round trip through the encoder within half a step.
 """
 from __future__ import annotations
 
@@ -239,12 +241,31 @@ def dequantise_codebook(codebook, scale=1.0) -> np.ndarray:
     return cb.astype(np.float64)
 
 
-def reconstruct_coefficients(codebook, scale, idx, gain, bias) -> np.ndarray:
+def dequantise_gain_bias(gain, bias, gb_params=None):
+    """Per-edge gain and bias as float64.
+
+    Floating arrays are taken as they are.  With gb_params = (gain_log2_lo, gain_log2_step,
+    bias_scale) the arrays hold one byte per value (paper §4.2: "gains via logarithmic Int8 to
+    retain dynamic range, and biases via linear Int8"; the paper prints no formula - reading
+    stated in the design notes): gain code 0 is a zero gain, code c = 1..255 means
+    2 ** (lo + step * c); bias code c (signed) means bias_scale * c.
+    """
+    if gb_params is None:
+        return np.asarray(gain).astype(np.float64), np.asarray(bias).astype(np.float64)
+    lo, step, bscale = (np.float64(np.float32(v)) for v in gb_params)
+    qg = np.asarray(gain)
+    qb = np.asarray(bias)
+    assert qg.dtype == np.uint8 and qb.dtype == np.int8
+    c = qg.astype(np.float64)
+    g = np.where(qg == 0, 0.0, np.exp2(lo + step * c))
+    return g, bscale * qb.astype(np.float64)
+
+
+def reconstruct_coefficients(codebook, scale, idx, gain, bias, gb_params=None) -> np.ndarray:
     """Dense coefficients c[i][j][m] = g_ij * C[k_ij][m] + b_ij  (paper §4.2)."""
     cb = dequantise_codebook(codebook, scale)
     idx = np.asarray(idx).astype(np.int64)
-    g = np.asarray(gain).astype(np.float64)
-    b = np.asarray(bias).astype(np.float64)
+    g, b = dequantise_gain_bias(gain, bias, gb_params)
     return g[..., None] * cb[idx] + b[..., None]
 
 
@@ -273,19 +294,20 @@ def dense_layer_forward(coef, x, return_abs: bool = False, rule: str = "bspline"
     return y, A
 
 
-def vq_layer_forward(x, codebook, scale, idx, gain, bias, return_abs: bool = False, rule: str = "bspline"):
+def vq_layer_forward(x, codebook, scale, idx, gain, bias, return_abs: bool = False, rule: str = "bspline",
+                     gb_params=None):
     """Forward pass of one VQ-KAN layer: reconstruct, evaluate, sum over inputs."""
-    coef = reconstruct_coefficients(codebook, scale, idx, gain, bias)
+    coef = reconstruct_coefficients(codebook, scale, idx, gain, bias, gb_params)
     return dense_layer_forward(coef, x, return_abs=return_abs, rule=rule)
 
 
-def vq_layer_outputs_at(x, codebook, scale, idx, gain, bias, bs, js, return_abs=False, rule: str = "bspline"):
+def vq_layer_outputs_at(x, codebook, scale, idx, gain, bias, bs, js, return_abs=False, rule: str = "bspline",
+                        gb_params=None):
     """y[b][j] for listed (b, j) pairs only; O(in) work each.  For parity checks
     at sizes where the whole layer is too slow on the CPU."""
     cb = dequantise_codebook(codebook, scale)
     idx = np.asarray(idx)
-    gain = np.asarray(gain)
-    bias = np.asarray(bias)
+    gain, bias = dequantise_gain_bias(gain, bias, gb_params)
     x = np.asarray(x, dtype=np.float64)
     out = np.empty(len(bs), dtype=np.float64)
     ab = np.empty(len(bs), dtype=np.float64)
@@ -307,7 +329,8 @@ def vq_head_forward(x, layers, return_hidden: bool = False, rule: str = "bspline
     a = np.asarray(x, dtype=np.float64)
     hidden = []
     for n, L in enumerate(layers):
-        y = vq_layer_forward(a, L["codebook"], L["scale"], L["idx"], L["gain"], L["bias"], rule=rule)
+        y = vq_layer_forward(a, L["codebook"], L["scale"], L["idx"], L["gain"], L["bias"], rule=rule,
+                             gb_params=L.get("gb_params"))
         if n + 1 < len(layers):
             a = np.tanh(y)
             hidden.append(a)

@@ -17,7 +17,7 @@ LIB_PATH = os.path.join(_HERE, "libkan_mi355x.so")
 
 KAN_OK = 0
 KAN_ERR_NULL, KAN_ERR_SHAPE, KAN_ERR_DTYPE, KAN_ERR_WORKSPACE, KAN_ERR_UNSUPPORTED, KAN_ERR_LAUNCH = 1, 2, 3, 4, 5, 6
-KAN_F32, KAN_F16, KAN_I8, KAN_U16, KAN_U32 = 0, 1, 2, 3, 4
+KAN_F32, KAN_F16, KAN_I8, KAN_U16, KAN_U32, KAN_Q8 = 0, 1, 2, 3, 4, 5
 KAN_PATH_AUTO, KAN_PATH_GATHER, KAN_PATH_MFMA = 0, 1, 2
 KAN_RULE_BSPLINE3, KAN_RULE_PLI2 = 0, 1
 
@@ -35,6 +35,7 @@ class kan_vq_layer(C.Structure):
         ("K", C.c_int32), ("idx_dtype", C.c_int32), ("gb_dtype", C.c_int32), ("cb_dtype", C.c_int32),
         ("idx", C.c_void_p), ("gain", C.c_void_p), ("bias", C.c_void_p), ("codebook", C.c_void_p),
         ("scale", C.c_float), ("rule", C.c_int32), ("prepared", C.c_void_p),
+        ("gain_log2_lo", C.c_float), ("gain_log2_step", C.c_float), ("bias_scale", C.c_float), ("reserved", C.c_int32),
     ]
 
 
@@ -131,15 +132,18 @@ class VQLayer:
         self.idx = torch.from_numpy(idx.view(view)).to(device)
         self.gain = torch.from_numpy(np.ascontiguousarray(params.gain)).to(device)
         self.bias = torch.from_numpy(np.ascontiguousarray(params.bias)).to(device)
+        q8 = params.gain.dtype == np.uint8          # byte-coded gain (uint8) and bias (int8)
+        gb = KAN_Q8 if q8 else (KAN_F16 if params.gain.dtype == np.float16 else KAN_F32)
+        gbp = tuple(float(v) for v in params.gb_params) if q8 else (0.0, 0.0, 0.0)
         self.codebook = torch.from_numpy(np.ascontiguousarray(params.codebook)).to(device)
         self.scale = float(params.scale)
         self.desc = kan_vq_layer(
             self.n_in, self.n_out, 10, 3, self.K,
             KAN_U16 if idx.dtype == np.uint16 else KAN_U32,
-            KAN_F16 if params.gain.dtype == np.float16 else KAN_F32,
+            gb,
             KAN_I8 if params.codebook.dtype == np.int8 else KAN_F32,
             self.idx.data_ptr(), self.gain.data_ptr(), self.bias.data_ptr(), self.codebook.data_ptr(),
-            self.scale, int(rule), None)
+            self.scale, int(rule), None, gbp[0], gbp[1], gbp[2], 0)
         self.prepared = None
 
     def prepare(self):

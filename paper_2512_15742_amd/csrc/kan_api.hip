@@ -45,17 +45,24 @@ constexpr int64_t kMaxBatch = 1 << 24;
 inline bool aligned(const void* p, size_t a) { return ((uintptr_t)p % a) == 0; }
 inline size_t round_up(size_t v, size_t a) { return (v + a - 1) / a * a; }
 
+int gb_kind_of(const kan_vq_layer& L) {
+  return L.gb_dtype == KAN_F32 ? kGbF32 : (L.gb_dtype == KAN_F16 ? kGbF16 : kGbQ8);
+}
+
 kan_status validate_layer(const kan_vq_layer* L) {
   if (!L) return KAN_ERR_NULL;
   if (L->G != 10 || L->degree != 3) return KAN_ERR_UNSUPPORTED;
   if (L->rule != KAN_RULE_BSPLINE3 && L->rule != KAN_RULE_PLI2) return KAN_ERR_UNSUPPORTED;
   if (L->in < 1 || L->out < 1 || L->in > kMaxDim || L->out > kMaxDim || L->K < 1) return KAN_ERR_SHAPE;
   if (L->idx_dtype != KAN_U16 && L->idx_dtype != KAN_U32) return KAN_ERR_DTYPE;
-  if (L->gb_dtype != KAN_F32 && L->gb_dtype != KAN_F16) return KAN_ERR_DTYPE;
+  if (L->gb_dtype != KAN_F32 && L->gb_dtype != KAN_F16 && L->gb_dtype != KAN_Q8) return KAN_ERR_DTYPE;
   if (L->cb_dtype != KAN_F32 && L->cb_dtype != KAN_I8) return KAN_ERR_DTYPE;
   if (L->idx_dtype == KAN_U16 && L->K > 65536) return KAN_ERR_SHAPE;
+  // byte-coded gain/bias belong to the fully quantised format: one-byte codebook entries too
+  if (L->gb_dtype == KAN_Q8 && L->cb_dtype != KAN_I8) return KAN_ERR_UNSUPPORTED;
   if (!L->idx || !L->gain || !L->bias || !L->codebook) return KAN_ERR_NULL;
-  const size_t idx_sz = L->idx_dtype == KAN_U16 ? 2 : 4, gb_sz = L->gb_dtype == KAN_F16 ? 2 : 4;
+  const size_t idx_sz = L->idx_dtype == KAN_U16 ? 2 : 4;
+  const size_t gb_sz = L->gb_dtype == KAN_F32 ? 4 : (L->gb_dtype == KAN_F16 ? 2 : 1);
   if (!aligned(L->idx, idx_sz) || !aligned(L->gain, gb_sz) || !aligned(L->bias, gb_sz)) return KAN_ERR_SHAPE;
   if (!aligned(L->codebook, L->cb_dtype == KAN_F32 ? 8 : 2)) return KAN_ERR_SHAPE;
   return KAN_OK;
@@ -105,17 +112,17 @@ void gather_geometry(LayerPlan& p, int n_in, int n_out, int64_t B, int n_heads, 
   p.n_chunks = (n_in + rows - 1) / rows;
 }
 
-LayerPlan plan_gather(int n_in, int n_out, int64_t B, int n_heads, int idx_u32, int gb_f16, int code,
+LayerPlan plan_gather(int n_in, int n_out, int64_t B, int n_heads, int idx_u32, int gb_kind, int code,
                       bool vec_ok) {
   LayerPlan p;
   p.mfma = false;
   p.kind = kPlanGather;
   p.cfg.idx_u32 = idx_u32;
-  p.cfg.gb_f16 = gb_f16;
+  p.cfg.gb_kind = gb_kind;
   p.cfg.code = code;
   p.cfg.bt = B <= 1 ? 1 : (B <= 4 ? 4 : 16);
   p.name = p.cfg.bt == 1 ? "kan_gather_bt1" : (p.cfg.bt == 4 ? "kan_gather_bt4" : "kan_gather_bt16");
-  const int bytes_per_edge = code == kDense ? 40 : (idx_u32 ? 4 : 2) + 2 * (gb_f16 ? 2 : 4);
+  const int bytes_per_edge = code == kDense ? 40 : (idx_u32 ? 4 : 2) + 2 * gb_bytes(gb_kind);
   const int jpl_max = p.cfg.bt == 16 ? 4 : 8;
   // Widest per-lane vector that divides the row and still gives the chip enough workgroups;
   // narrower vectors mean more output tiles (load width does not matter to the stream).
@@ -140,9 +147,10 @@ constexpr int kMfmaRowsStep = kMfmaPrepRows;   // chunk boundaries coincide with
 constexpr int kMfmaTargetWorkgroups = 512;
 constexpr int kMfmaMinRows = 64;
 constexpr int64_t kHalfFusedMaxBatch = 64;   // fp16 path: fused kernel up to here, streaming contraction above
+constexpr int64_t kHalfFusedMaxSamples = 1024;   // ... and only below this many (sample, head) pairs per group
 constexpr int64_t kAutoMfmaBatch = 32;    // KAN_PATH_AUTO switches to the matrix cores from here (measured crossover 16-32)
 
-LayerPlan plan_mfma(int n_in, int n_out, int64_t B, int n_heads, int idx_u32, int gb_f16, int code) {
+LayerPlan plan_mfma(int n_in, int n_out, int64_t B, int n_heads, int idx_u32, int gb_kind, int code) {
   LayerPlan p;
   p.mfma = true;
   p.kind = kPlanMfma;
@@ -151,7 +159,7 @@ LayerPlan plan_mfma(int n_in, int n_out, int64_t B, int n_heads, int idx_u32, in
   p.cfg.jpl = 1;
   p.cfg.wj = 2;
   p.cfg.idx_u32 = idx_u32;
-  p.cfg.gb_f16 = gb_f16;
+  p.cfg.gb_kind = gb_kind;
   p.cfg.code = code;
   p.n_jt = (n_out + kMfmaTileN - 1) / kMfmaTileN;
   p.n_bt = (int)((B + kMfmaTileM - 1) / kMfmaTileM);
@@ -171,7 +179,7 @@ LayerPlan plan_mfma(int n_in, int n_out, int64_t B, int n_heads, int idx_u32, in
 // of 128.  With one batch tile every edge is gathered once and the work is bound by the
 // gather rate of the CUs' address units, so every CU should be busy: i is split while the
 // partial sums stay below the size of the parameter stream.
-LayerPlan plan_fused(int n_in, int n_out, int64_t B, int n_heads, int idx_u32, int gb_f16, int code, bool f32) {
+LayerPlan plan_fused(int n_in, int n_out, int64_t B, int n_heads, int idx_u32, int gb_kind, int code, bool f32) {
   LayerPlan p;
   p.mfma = false;
   p.kind = f32 ? kPlanFused32 : kPlanFused16;
@@ -180,11 +188,11 @@ LayerPlan plan_fused(int n_in, int n_out, int64_t B, int n_heads, int idx_u32, i
   p.cfg.jpl = 1;
   p.cfg.wj = 4;
   p.cfg.idx_u32 = idx_u32;
-  p.cfg.gb_f16 = gb_f16;
+  p.cfg.gb_kind = gb_kind;
   p.cfg.code = code;
   p.n_jt = (n_out + kFusedTileN - 1) / kFusedTileN;
   p.n_bt = (int)((B + p.cfg.bt - 1) / p.cfg.bt);
-  const int bytes_per_edge = (idx_u32 ? 4 : 2) + 2 * (gb_f16 ? 2 : 4);
+  const int bytes_per_edge = (idx_u32 ? 4 : 2) + 2 * gb_bytes(gb_kind);
   const long long base = (long long)n_heads * p.n_jt * p.n_bt;
   long long chunks = (kTargetWorkgroups + base - 1) / (base > 0 ? base : 1);
   const long long max_by_rows = n_in / 16;                                   // at least two steps each
@@ -213,9 +221,9 @@ LayerPlan plan_bucket(const kan_vq_layer& L, int64_t B, int n_heads) {
   p.cfg.jpl = 1;
   p.cfg.wj = 1;
   p.cfg.idx_u32 = L.idx_dtype == KAN_U32;
-  p.cfg.gb_f16 = L.gb_dtype == KAN_F16;
+  p.cfg.gb_kind = gb_kind_of(L);
   p.cfg.code = L.cb_dtype == KAN_I8 ? kCbI8 : kCbF32;
-  const BucketGeom g = bucket_geometry(L.in, L.out, L.K, L.cb_dtype == KAN_I8, L.gb_dtype == KAN_F16);
+  const BucketGeom g = bucket_geometry(L.in, L.out, L.K, L.cb_dtype == KAN_I8, gb_kind_of(L));
   const long long base = (long long)g.n_buckets * B * n_heads;
   long long parts = kBucketWorkgroups / base;     // rounded down: one round of workgroups, no tail
   const long long min_parts = (L.out + kBucketMaxJw - 1) / kBucketMaxJw;
@@ -246,15 +254,18 @@ bool layer_prepared_ok(const kan_vq_layer& L) {
 //     contraction.
 LayerPlan plan_vq(const kan_vq_layer& L, int64_t B, int n_heads, bool vec_ok, bool prepared_ok, int32_t path) {
   const int code = L.cb_dtype == KAN_I8 ? kCbI8 : kCbF32;
-  const int u32 = L.idx_dtype == KAN_U32, f16 = L.gb_dtype == KAN_F16;
+  const int u32 = L.idx_dtype == KAN_U32, gbk = gb_kind_of(L);
   const bool half_path = path == KAN_PATH_MFMA || (path == KAN_PATH_AUTO && B >= kAutoMfmaBatch);
   if (half_path) {
-    if (B <= kHalfFusedMaxBatch) return plan_fused(L.in, L.out, B, n_heads, u32, f16, code, false);
-    return plan_mfma(L.in, L.out, B, n_heads, u32, f16, code);
+    // the fused kernel gathers every codeword once per batch tile and head; with many heads in
+    // a group the dequantise-once preparation + streaming contraction is ahead already at batch 64
+    if (B <= kHalfFusedMaxBatch && (long long)B * n_heads < kHalfFusedMaxSamples)
+      return plan_fused(L.in, L.out, B, n_heads, u32, gbk, code, false);
+    return plan_mfma(L.in, L.out, B, n_heads, u32, gbk, code);
   }
   if (prepared_ok && B <= kBucketMaxBatch) return plan_bucket(L, B, n_heads);
-  if (B >= 2) return plan_fused(L.in, L.out, B, n_heads, u32, f16, code, true);
-  return plan_gather(L.in, L.out, B, n_heads, u32, f16, code, vec_ok);
+  if (B >= 2) return plan_fused(L.in, L.out, B, n_heads, u32, gbk, code, true);
+  return plan_gather(L.in, L.out, B, n_heads, u32, gbk, code, vec_ok);
 }
 
 bool layer_vec_ok(const kan_vq_layer& L) {
@@ -364,7 +375,7 @@ kan_status run_layer_group(const LayerPlan& p, GatherArgs& a, const void* const*
     st = run(p.name, s, [&] { return launch_mfma(m, p.cfg.bt, grid, s); });
   } else if (p.kind == kPlanBucket) {
     const bool i8 = p.cfg.code == kCbI8;
-    const BucketGeom g = bucket_geometry(a.n_in, a.n_out, (int)(a.cb_bytes / (i8 ? 10 : 40)), i8, p.cfg.gb_f16 != 0);
+    const BucketGeom g = bucket_geometry(a.n_in, a.n_out, (int)(a.cb_bytes / (i8 ? 10 : 40)), i8, p.cfg.gb_kind);
     BucketArgs k;
     memset(&k, 0, sizeof(k));
     k.x = a.x;
@@ -393,8 +404,10 @@ kan_status run_layer_group(const LayerPlan& p, GatherArgs& a, const void* const*
       k.h[h].prepared = prepared[h];
       k.h[h].cb = a.h[h].cb;
       k.h[h].scale = a.h[h].scale;
+      k.h[h].gain_log2_lo = a.h[h].gain_log2_lo;
+      k.h[h].gain_log2_step = a.h[h].gain_log2_step;
     }
-    st = run(p.name, s, [&] { return launch_bucket(i8, p.cfg.gb_f16 != 0, k, p.parts, heads, s); });
+    st = run(p.name, s, [&] { return launch_bucket(i8, p.cfg.gb_kind, k, p.parts, heads, s); });
   } else if (p.kind == kPlanFused16 || p.kind == kPlanFused32) {
     const bool f32 = p.kind == kPlanFused32;
     FusedArgs f;
@@ -599,6 +612,9 @@ kan_status kan_vq_head_forward(const kan_vq_layer* layers, int32_t n_layers, int
         a.h[h].bias = L.bias;
         a.h[h].cb = L.codebook;
         a.h[h].scale = L.scale;
+        a.h[h].gain_log2_lo = L.gain_log2_lo;
+        a.h[h].gain_log2_step = L.gain_log2_step;
+        a.h[h].bias_scale = L.bias_scale;
         prepared[h] = L.prepared;
       }
       st = run_layer_group(plans[l], a, prepared, heads, l == 0, dst + (long long)h0 * dst_head_stride, dst_head_stride, w,
@@ -651,7 +667,7 @@ kan_status kan_dense_layer_forward(const float* coef, int32_t in, int32_t out, i
 size_t kan_vq_prepared_bytes(const kan_vq_layer* L) {
   if (validate_layer(L) != KAN_OK) return (size_t)-1;
   if (L->in > kBucketMaxIn || (long long)L->in * L->out > (1ll << 31)) return 0;
-  return bucket_geometry(L->in, L->out, L->K, L->cb_dtype == KAN_I8, L->gb_dtype == KAN_F16).total;
+  return bucket_geometry(L->in, L->out, L->K, L->cb_dtype == KAN_I8, gb_kind_of(*L)).total;
 }
 
 kan_status kan_vq_prepare(const kan_vq_layer* L, void* prepared, size_t prepared_bytes, void* stream) {
@@ -659,12 +675,12 @@ kan_status kan_vq_prepare(const kan_vq_layer* L, void* prepared, size_t prepared
   if (st != KAN_OK) return st;
   if (L->in > kBucketMaxIn) return KAN_ERR_UNSUPPORTED;
   if ((long long)L->in * L->out > (1ll << 31)) return KAN_ERR_UNSUPPORTED;   // 32-bit segment offsets
-  const BucketGeom g = bucket_geometry(L->in, L->out, L->K, L->cb_dtype == KAN_I8, L->gb_dtype == KAN_F16);
+  const BucketGeom g = bucket_geometry(L->in, L->out, L->K, L->cb_dtype == KAN_I8, gb_kind_of(*L));
   if (!prepared || !aligned(prepared, 256) || prepared_bytes < g.total) return KAN_ERR_WORKSPACE;
-  LayerPtrs h = {L->idx, L->gain, L->bias, L->codebook, L->scale, 0};
+  LayerPtrs h = {L->idx, L->gain, L->bias, L->codebook, L->scale, L->gain_log2_lo, L->gain_log2_step, L->bias_scale};
   hipStream_t s = (hipStream_t)stream;
   return run("kan_vq_prepare", s, [&] {
-    return launch_bucket_prepare(h, L->idx_dtype == KAN_U32, L->gb_dtype == KAN_F16, L->in, L->out, g, prepared, s);
+    return launch_bucket_prepare(h, L->idx_dtype == KAN_U32, gb_kind_of(*L), L->in, L->out, g, prepared, s);
   });
 }
 
@@ -672,7 +688,7 @@ kan_status kan_vq_debug_gather(const kan_vq_layer* L, uint32_t* ids, float* rows
   kan_status st = validate_layer(L);
   if (st != KAN_OK) return st;
   if (!ids && !rows) return KAN_ERR_NULL;
-  LayerPtrs h = {L->idx, L->gain, L->bias, L->codebook, L->scale, 0};
+  LayerPtrs h = {L->idx, L->gain, L->bias, L->codebook, L->scale, 0.f, 0.f, 0.f};
   hipStream_t s = (hipStream_t)stream;
   return run("kan_debug_gather", s, [&] {
     return launch_debug_gather(h, L->idx_dtype == KAN_U32, L->cb_dtype == KAN_I8,

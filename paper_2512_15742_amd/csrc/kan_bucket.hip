@@ -33,15 +33,18 @@ constexpr int kWaves = kBucketThreads / kWave;     // 16
 constexpr int kEpt = 8;                            // consecutive edges per thread and pass
 constexpr int kPass = kBucketThreads * kEpt;       // 8192 edges per workgroup and pass
 
-// Raw records of one pass: edges e0 .. e0 + 7 of the thread (16-byte loads; fp32 gains: two).
-template <bool GF16>
+// Raw records of one pass: edges e0 .. e0 + 7 of the thread (16-byte loads; the eight gains
+// are 32 bytes as fp32 - two loads -, 16 as fp16, 8 as byte codes).  GK is the GbKind.
+template <int GK>
 struct PassRegs {
-  u32x4 i, q, g0;
-  typename std::conditional<GF16, char, u32x4>::type g1;
+  u32x4 i, q;
+  typename std::conditional<GK == kGbQ8, u32x2, u32x4>::type g0;
+  typename std::conditional<GK == kGbF32, u32x4, char>::type g1;
 };
 
-__device__ __forceinline__ float gain_to_float(float g) { return g; }
-__device__ __forceinline__ float gain_to_float(__half g) { return __half2float(g); }
+__device__ __forceinline__ float bias_to_float(float b, const Q8Params&) { return b; }
+__device__ __forceinline__ float bias_to_float(__half b, const Q8Params&) { return __half2float(b); }
+__device__ __forceinline__ float bias_to_float(q8_t b, const Q8Params& qp) { return q8_bias(b.v, qp); }
 
 __device__ __forceinline__ uint32_t dword_of(const u32x4& v, int n) {
   return n == 0 ? v.x : (n == 1 ? v.y : (n == 2 ? v.z : v.w));
@@ -50,10 +53,16 @@ __device__ __forceinline__ uint32_t u16_of(const u32x4& v, int u) {   // u = 0..
   const uint32_t w = dword_of(v, u >> 1);
   return (u & 1) ? (w >> 16) : (w & 0xffffu);
 }
-template <bool GF16>
-__device__ __forceinline__ float gain_of(const PassRegs<GF16>& c, int u) {
-  if constexpr (GF16) return __half2float(__ushort_as_half((uint16_t)u16_of(c.g0, u)));
-  else return __uint_as_float(u < 4 ? dword_of(c.g0, u) : dword_of(c.g1, u - 4));
+template <int GK>
+__device__ __forceinline__ float gain_of(const PassRegs<GK>& c, int u, const Q8Params& qp) {
+  if constexpr (GK == kGbF16) {
+    return __half2float(__ushort_as_half((uint16_t)u16_of(c.g0, u)));
+  } else if constexpr (GK == kGbQ8) {
+    const uint32_t w = u < 4 ? c.g0.x : c.g0.y;
+    return q8_gain((w >> (8 * (u & 3))) & 0xffu, qp);
+  } else {
+    return __uint_as_float(u < 4 ? dword_of(c.g0, u) : dword_of(c.g1, u - 4));
+  }
 }
 
 __device__ __forceinline__ float wave_sum(float v) {
@@ -68,7 +77,7 @@ __device__ __forceinline__ float wave_sum(float v) {
 // building, record traffic and arithmetic overlap.
 //
 // MAXIN: inputs the basis table holds (2048 or 4096); the bucket shrinks to make room.
-template <bool GF16, bool I8, int MAXIN>
+template <int GK, bool I8, int MAXIN>
 __global__ __launch_bounds__(kBucketThreads) void kan_bucket_kernel(const BucketArgs a) {
   constexpr int kCbBytes = bucket_bytes(MAXIN);
   constexpr int kXPerThread = MAXIN / kBucketThreads;
@@ -89,7 +98,8 @@ __global__ __launch_bounds__(kBucketThreads) void kan_bucket_kernel(const Bucket
   const uint16_t* __restrict__ pi = (const uint16_t*)(prep + a.off_i);
   const uint16_t* __restrict__ pq = (const uint16_t*)(prep + a.off_q);
   const char* __restrict__ pg = prep + a.off_g;
-  constexpr int kGainBytes = GF16 ? 2 : 4;
+  constexpr int kGainBytes = gb_bytes(GK);
+  const Q8Params qp = {H.gain_log2_lo, H.gain_log2_step, 0.f};
 
   const int j0 = part * a.jw;
   const int j1 = min(j0 + a.jw, a.n_out);
@@ -187,14 +197,15 @@ __global__ __launch_bounds__(kBucketThreads) void kan_bucket_kernel(const Bucket
   const uint32_t base = blk_lo & ~7u;
   const uint32_t last_group = blk_hi > 0u ? (blk_hi - 1u) & ~7u : 0u;
   const int n_pass = blk_hi > blk_lo ? (int)((blk_hi - base + kPass - 1) / kPass) : 0;
-  auto load_pass = [&](PassRegs<GF16>& c, int p) {
+  auto load_pass = [&](PassRegs<GK>& c, int p) {
     const uint32_t e0 = min(base + (uint32_t)p * kPass + (uint32_t)tid * kEpt, last_group);
     c.i = __builtin_nontemporal_load((const u32x4*)(pi + e0));
     c.q = __builtin_nontemporal_load((const u32x4*)(pq + e0));
-    c.g0 = __builtin_nontemporal_load((const u32x4*)(pg + (size_t)e0 * kGainBytes));
-    if constexpr (!GF16) c.g1 = __builtin_nontemporal_load((const u32x4*)(pg + (size_t)e0 * kGainBytes) + 1);
+    if constexpr (GK == kGbQ8) c.g0 = __builtin_nontemporal_load((const u32x2*)(pg + (size_t)e0 * kGainBytes));
+    else c.g0 = __builtin_nontemporal_load((const u32x4*)(pg + (size_t)e0 * kGainBytes));
+    if constexpr (GK == kGbF32) c.g1 = __builtin_nontemporal_load((const u32x4*)(pg + (size_t)e0 * kGainBytes) + 1);
   };
-  PassRegs<GF16> A, B;
+  PassRegs<GK> A, B;
   load_pass(A, 0);
   load_pass(B, 1);
 
@@ -213,7 +224,7 @@ __global__ __launch_bounds__(kBucketThreads) void kan_bucket_kernel(const Bucket
   __syncthreads();
 
   // products of the thread's 8 edges of pass p -> prod
-  auto products = [&](const PassRegs<GF16>& c, int p) {
+  auto products = [&](const PassRegs<GK>& c, int p) {
     // edge e belongs to the block iff blk_lo <= e < blk_hi, i.e. (e - blk_lo) < (blk_hi - blk_lo) unsigned
     const uint32_t rel0 = base + (uint32_t)p * kPass + (uint32_t)tid * kEpt - blk_lo, len = blk_hi - blk_lo;
     float pr[kEpt];
@@ -253,7 +264,7 @@ __global__ __launch_bounds__(kBucketThreads) void kan_bucket_kernel(const Bucket
       // Edges outside the block (groups that straddle its ends, re-read groups) contribute
       // an exact zero rather than gain * s, so that a non-finite codeword which no edge of
       // the block refers to cannot reach a sum.
-      pr[u] = (rel0 + (uint32_t)u < len) ? gain_of<GF16>(c, u) * s : 0.f;
+      pr[u] = (rel0 + (uint32_t)u < len) ? gain_of<GK>(c, u, qp) * s : 0.f;
     }
     }
     ((float4*)prod)[tid * 2] = make_float4(pr[0], pr[1], pr[2], pr[3]);
@@ -352,7 +363,8 @@ __global__ __launch_bounds__(256) void kan_prepare_fill_kernel(const IdxT* __res
                                                                const GbT* __restrict__ bias, int n_in, int n_out,
                                                                int rows_shift, const uint32_t* __restrict__ seg,
                                                                uint16_t* __restrict__ pi, uint16_t* __restrict__ pq,
-                                                               GbT* __restrict__ pg, float* __restrict__ bias_sum) {
+                                                               GbT* __restrict__ pg, float* __restrict__ bias_sum,
+                                                               Q8Params qp) {
   const int j = blockIdx.x * blockDim.x + threadIdx.x;
   const uint32_t bucket = blockIdx.y;
   if (j >= n_out) return;
@@ -368,7 +380,7 @@ __global__ __launch_bounds__(256) void kan_prepare_fill_kernel(const IdxT* __res
       pg[pos] = gain[e];
       ++pos;
     }
-    if (bucket == 0) bs += (double)gain_to_float(bias[e]);
+    if (bucket == 0) bs += (double)bias_to_float(bias[e], qp);
   }
   if (bucket == 0) bias_sum[j] = (float)bs;
 }
@@ -385,40 +397,44 @@ hipError_t prepare_typed(const LayerPtrs& h, int n_in, int n_out, const BucketGe
   hipLaunchKernelGGL((kan_prepare_fill_kernel<IdxT, GbT>), grid, dim3(256), 0, s, (const IdxT*)h.idx,
                      (const GbT*)h.gain, (const GbT*)h.bias, n_in, n_out, g.rows_shift, (const uint32_t*)seg,
                      (uint16_t*)(p + g.off_i), (uint16_t*)(p + g.off_q), (GbT*)(p + g.off_g),
-                     (float*)(p + g.off_bias));
+                     (float*)(p + g.off_bias), Q8Params{h.gain_log2_lo, h.gain_log2_step, h.bias_scale});
   return hipGetLastError();
 }
 
 }  // namespace
 
-hipError_t launch_bucket_prepare(const LayerPtrs& h, int idx_u32, int gb_f16, int n_in, int n_out,
+hipError_t launch_bucket_prepare(const LayerPtrs& h, int idx_u32, int gb_kind, int n_in, int n_out,
                                  const BucketGeom& g, void* prepared, hipStream_t s) {
   if (idx_u32) {
-    if (gb_f16) return prepare_typed<uint32_t, __half>(h, n_in, n_out, g, prepared, s);
+    if (gb_kind == kGbQ8) return prepare_typed<uint32_t, q8_t>(h, n_in, n_out, g, prepared, s);
+    if (gb_kind == kGbF16) return prepare_typed<uint32_t, __half>(h, n_in, n_out, g, prepared, s);
     return prepare_typed<uint32_t, float>(h, n_in, n_out, g, prepared, s);
   }
-  if (gb_f16) return prepare_typed<uint16_t, __half>(h, n_in, n_out, g, prepared, s);
+  if (gb_kind == kGbQ8) return prepare_typed<uint16_t, q8_t>(h, n_in, n_out, g, prepared, s);
+  if (gb_kind == kGbF16) return prepare_typed<uint16_t, __half>(h, n_in, n_out, g, prepared, s);
   return prepare_typed<uint16_t, float>(h, n_in, n_out, g, prepared, s);
 }
 
-hipError_t launch_bucket(bool cb_i8, bool gb_f16, const BucketArgs& a, int parts, int heads, hipStream_t s) {
+hipError_t launch_bucket(bool cb_i8, int gb_kind, const BucketArgs& a, int parts, int heads, hipStream_t s) {
   if (a.n_in > kBucketMaxIn || a.n_buckets < 1 || parts < 1 || a.jw < 1 || a.jw > kBucketMaxJw ||
       (long long)parts * a.jw < a.n_out)
     return hipErrorInvalidValue;
+  if (gb_kind == kGbQ8 && !cb_i8) return hipErrorInvalidValue;      // byte-coded gains go with Int8 codebooks
   dim3 grid((unsigned)(parts * a.n_buckets), (unsigned)a.B, (unsigned)heads);
   dim3 block(kBucketThreads);
   const bool wide = a.n_in > 2048;
-#define KAN_LAUNCH_BUCKET(GF16, I8)                                                                    \
+#define KAN_LAUNCH_BUCKET(GK, I8)                                                                      \
   do {                                                                                                 \
-    if (wide) hipLaunchKernelGGL((kan_bucket_kernel<GF16, I8, 4096>), grid, block, 0, s, a);           \
-    else hipLaunchKernelGGL((kan_bucket_kernel<GF16, I8, 2048>), grid, block, 0, s, a);                \
+    if (wide) hipLaunchKernelGGL((kan_bucket_kernel<GK, I8, 4096>), grid, block, 0, s, a);             \
+    else hipLaunchKernelGGL((kan_bucket_kernel<GK, I8, 2048>), grid, block, 0, s, a);                  \
   } while (0)
   if (cb_i8) {
-    if (gb_f16) KAN_LAUNCH_BUCKET(true, true);
-    else KAN_LAUNCH_BUCKET(false, true);
+    if (gb_kind == kGbQ8) KAN_LAUNCH_BUCKET(kGbQ8, true);
+    else if (gb_kind == kGbF16) KAN_LAUNCH_BUCKET(kGbF16, true);
+    else KAN_LAUNCH_BUCKET(kGbF32, true);
   } else {
-    if (gb_f16) KAN_LAUNCH_BUCKET(true, false);
-    else KAN_LAUNCH_BUCKET(false, false);
+    if (gb_kind == kGbF16) KAN_LAUNCH_BUCKET(kGbF16, false);
+    else KAN_LAUNCH_BUCKET(kGbF32, false);
   }
 #undef KAN_LAUNCH_BUCKET
   return hipGetLastError();

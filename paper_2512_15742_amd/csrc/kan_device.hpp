@@ -118,6 +118,7 @@ __device__ __forceinline__ BasisW basis_fast(float xf, int rule) {
 // loaded non-temporally to keep it from displacing the codebook in L2.
 
 template <int BYTES> struct RawVec;
+template <> struct RawVec<1> { typedef uint8_t type; };
 template <> struct RawVec<2> { typedef uint16_t type; };
 template <> struct RawVec<4> { typedef uint32_t type; };
 template <> struct RawVec<8> { typedef u32x2 type; };
@@ -147,15 +148,52 @@ __device__ __forceinline__ void load_idx(const IdxT* p, uint32_t (&id)[N]) {
   for (int n = 0; n < N; ++n) id[n] = (uint32_t)raw[n];   // zero-extends
 }
 
-template <typename T, int N>
-__device__ __forceinline__ void load_gb(const T* p, float (&v)[N]) {
-  alignas(16) T raw[N];
-  stream_load<sizeof(T) * N>(p, raw);
+// Per-edge gain and bias come as fp32, fp16, or one byte each (paper section 4.2: gains as
+// logarithmic Int8, biases as linear Int8 - 16 bits per edge beside the index).  The byte
+// codes mean
+//     gain = 0 for code 0, else exp2(gain_log2_lo + gain_log2_step * code)   code = 1..255
+//     bias = bias_scale * code                                               code = -127..127
+// with the three parameters fixed per layer (the paper prints no formula; this is the
+// reading stated in the design notes).
+struct Q8Params {
+  float gain_log2_lo, gain_log2_step, bias_scale;
+};
+struct q8_t {          // element type tag of byte-coded gain/bias arrays
+  uint8_t v;
+};
+
+__device__ __forceinline__ float q8_gain(uint32_t code, const Q8Params& qp) {
+  const float g = exp2f(fmaf(qp.gain_log2_step, (float)code, qp.gain_log2_lo));
+  return code ? g : 0.f;
+}
+__device__ __forceinline__ float q8_bias(uint32_t code, const Q8Params& qp) {
+  return qp.bias_scale * (float)(int)(int8_t)code;
+}
+
+template <typename T, int N, bool GAIN>
+__device__ __forceinline__ void load_gb_any(const T* p, const Q8Params& qp, float (&v)[N]) {
+  if constexpr (sizeof(T) == 1) {
+    alignas(8) uint8_t raw[N];
+    stream_load<N>(p, raw);
 #pragma unroll
-  for (int n = 0; n < N; ++n) {
-    if constexpr (sizeof(T) == 2) v[n] = __half2float(raw[n]);
-    else v[n] = raw[n];
+    for (int n = 0; n < N; ++n) v[n] = GAIN ? q8_gain(raw[n], qp) : q8_bias(raw[n], qp);
+  } else {
+    alignas(16) T raw[N];
+    stream_load<sizeof(T) * N>(p, raw);
+#pragma unroll
+    for (int n = 0; n < N; ++n) {
+      if constexpr (sizeof(T) == 2) v[n] = __half2float(raw[n]);
+      else v[n] = raw[n];
+    }
   }
+}
+template <typename T, int N>
+__device__ __forceinline__ void load_gain(const T* p, const Q8Params& qp, float (&v)[N]) {
+  load_gb_any<T, N, true>(p, qp, v);
+}
+template <typename T, int N>
+__device__ __forceinline__ void load_bias(const T* p, const Q8Params& qp, float (&v)[N]) {
+  load_gb_any<T, N, false>(p, qp, v);
 }
 
 // ---- codeword rows -------------------------------------------------------------

@@ -61,6 +61,7 @@ __global__ __launch_bounds__(kThreads) void kan_fused_kernel(const FusedArgs a) 
   const IdxT* idx = (const IdxT*)hp.idx;
   const GbT* gain = (const GbT*)hp.gain;
   const GbT* bias = (const GbT*)hp.bias;
+  const Q8Params qp = {hp.gain_log2_lo, hp.gain_log2_step, hp.bias_scale};
   const CbT* cb = (const CbT*)hp.cb;
   const float scale = sizeof(CbT) == 1 ? hp.scale : 1.0f;
   const float gmul = F32 ? scale : 1.0f;        // fp32 operands carry the scale themselves
@@ -99,8 +100,8 @@ __global__ __launch_bounds__(kThreads) void kan_fused_kernel(const FusedArgs a) 
       uint32_t id[1];
       float g[1], bv[1];
       load_idx<IdxT, 1>(idx + e, id);
-      load_gb<GbT, 1>(gain + e, g);
-      load_gb<GbT, 1>(bias + e, bv);
+      load_gain<GbT, 1>(gain + e, qp, g);
+      load_bias<GbT, 1>(bias + e, qp, bv);
       m.id[s] = id[0];
       m.g[s] = ok ? g[0] * gmul : 0.f;      // out-of-range edges contribute nothing
       m.b[s] = ok ? bv[0] : 0.f;
@@ -268,11 +269,14 @@ hipError_t launch_variant(const FusedArgs& a, bool f32, int mblk, dim3 grid, hip
 
 template <typename IdxT>
 hipError_t launch_types(const GatherCfg& c, const FusedArgs& a, bool f32, int mblk, dim3 grid, hipStream_t s) {
-  if (c.code == kCbI8)
-    return c.gb_f16 ? launch_variant<IdxT, __half, int8_t>(a, f32, mblk, grid, s)
-                    : launch_variant<IdxT, float, int8_t>(a, f32, mblk, grid, s);
-  return c.gb_f16 ? launch_variant<IdxT, __half, float>(a, f32, mblk, grid, s)
-                  : launch_variant<IdxT, float, float>(a, f32, mblk, grid, s);
+  if (c.code == kCbI8) {
+    if (c.gb_kind == kGbQ8) return launch_variant<IdxT, q8_t, int8_t>(a, f32, mblk, grid, s);
+    return c.gb_kind == kGbF16 ? launch_variant<IdxT, __half, int8_t>(a, f32, mblk, grid, s)
+                               : launch_variant<IdxT, float, int8_t>(a, f32, mblk, grid, s);
+  }
+  if (c.gb_kind == kGbQ8) return hipErrorInvalidValue;      // byte-coded gain/bias go with Int8 codebooks
+  return c.gb_kind == kGbF16 ? launch_variant<IdxT, __half, float>(a, f32, mblk, grid, s)
+                             : launch_variant<IdxT, float, float>(a, f32, mblk, grid, s);
 }
 
 }  // namespace

@@ -70,6 +70,7 @@ __global__ __launch_bounds__(kThreads) void kan_gather_kernel(const GatherArgs a
   const IdxT* idx = (const IdxT*)hp.idx;
   const GbT* gain = (const GbT*)hp.gain;
   const GbT* bias = (const GbT*)hp.bias;
+  const Q8Params qp = {hp.gain_log2_lo, hp.gain_log2_step, hp.bias_scale};
   const CbT* cb = (const CbT*)hp.cb;
   const float scale = (CODE == kCbI8) ? hp.scale : 1.0f;
 
@@ -140,8 +141,8 @@ __global__ __launch_bounds__(kThreads) void kan_gather_kernel(const GatherArgs a
             const int r = min(r0 + q * wi_count, rows - 1);
             const long long e = (long long)(s0 + r) * n_out + j0;
             load_idx<IdxT, JPL>(idx + e, id[q]);
-            load_gb<GbT, JPL>(gain + e, g[q]);
-            load_gb<GbT, JPL>(bias + e, bv[q]);
+            load_gain<GbT, JPL>(gain + e, qp, g[q]);
+            load_bias<GbT, JPL>(bias + e, qp, bv[q]);
           }
           typename WindowRaw<CbT>::type raw[R][JPL];
           int sp[R];
@@ -192,8 +193,8 @@ __global__ __launch_bounds__(kThreads) void kan_gather_kernel(const GatherArgs a
             uint32_t id[JPL];
             float g[JPL], bv[JPL];
             load_idx<IdxT, JPL>(idx + e, id);
-            load_gb<GbT, JPL>(gain + e, g);
-            load_gb<GbT, JPL>(bias + e, bv);
+            load_gain<GbT, JPL>(gain + e, qp, g);
+            load_bias<GbT, JPL>(bias + e, qp, bv);
 #pragma unroll
             for (int p = 0; p < JPL; ++p) {
               fetch_row<CbT>(cb, id[p], g[p] * scale, c[p]);
@@ -306,11 +307,13 @@ hipError_t launch_jpl(const GatherCfg& c, const GatherArgs& a, dim3 grid, hipStr
 template <typename IdxT>
 hipError_t launch_types(const GatherCfg& c, const GatherArgs& a, dim3 grid, hipStream_t s) {
   if (c.code == kCbI8) {
-    return c.gb_f16 ? launch_jpl<IdxT, __half, int8_t, kCbI8>(c, a, grid, s)
-                    : launch_jpl<IdxT, float, int8_t, kCbI8>(c, a, grid, s);
+    if (c.gb_kind == kGbQ8) return launch_jpl<IdxT, q8_t, int8_t, kCbI8>(c, a, grid, s);
+    return c.gb_kind == kGbF16 ? launch_jpl<IdxT, __half, int8_t, kCbI8>(c, a, grid, s)
+                               : launch_jpl<IdxT, float, int8_t, kCbI8>(c, a, grid, s);
   }
-  return c.gb_f16 ? launch_jpl<IdxT, __half, float, kCbF32>(c, a, grid, s)
-                  : launch_jpl<IdxT, float, float, kCbF32>(c, a, grid, s);
+  if (c.gb_kind == kGbQ8) return hipErrorInvalidValue;      // byte-coded gain/bias go with Int8 codebooks
+  return c.gb_kind == kGbF16 ? launch_jpl<IdxT, __half, float, kCbF32>(c, a, grid, s)
+                             : launch_jpl<IdxT, float, float, kCbF32>(c, a, grid, s);
 }
 #endif
 

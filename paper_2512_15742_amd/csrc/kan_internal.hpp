@@ -17,10 +17,12 @@ struct LayerPtrs {
   const void* bias;
   const void* cb;
   float scale;
-  int pad;
+  float gain_log2_lo, gain_log2_step, bias_scale;   // byte-coded gain/bias only
 };
 
 enum CodeKind : int { kCbF32 = 0, kCbI8 = 1, kDense = 2 };
+enum GbKind : int { kGbF32 = 0, kGbF16 = 1, kGbQ8 = 2 };     // fp32, fp16, one byte each (log gain, linear bias)
+constexpr int gb_bytes(int kind) { return kind == kGbF32 ? 4 : (kind == kGbF16 ? 2 : 1); }
 
 // ---- gather path (fp32 vector arithmetic) --------------------------------------
 struct GatherCfg {
@@ -28,7 +30,7 @@ struct GatherCfg {
   int jpl;         // consecutive outputs per lane: 1, 2, 4 or 8
   int wj;          // waves of the 4-wave workgroup laid along j (1, 2 or 4); 4/wj along i
   int idx_u32;     // 0: uint16 indices, 1: uint32
-  int gb_f16;      // 0: fp32 gain/bias, 1: fp16
+  int gb_kind;     // GbKind of gain/bias
   int code;        // CodeKind
 };
 
@@ -126,7 +128,7 @@ struct BucketGeom {
   size_t total;
 };
 
-inline BucketGeom bucket_geometry(int n_in, int n_out, int K, bool cb_i8, bool gb_f16) {
+inline BucketGeom bucket_geometry(int n_in, int n_out, int K, bool cb_i8, int gb_kind) {
   // 32 bytes of slack after every array: threads load aligned groups of eight records
   auto up = [](size_t v) { return (v + 32 + 255) / 256 * 256; };
   BucketGeom g;
@@ -138,7 +140,7 @@ inline BucketGeom bucket_geometry(int n_in, int n_out, int K, bool cb_i8, bool g
   g.off_i = g.off_bias + up((size_t)n_out * 4);
   g.off_q = g.off_i + up(E * 2);
   g.off_g = g.off_q + up(E * 2);
-  g.total = g.off_g + up(E * (gb_f16 ? 2 : 4));
+  g.total = g.off_g + up(E * gb_bytes(gb_kind));
   return g;
 }
 
@@ -146,6 +148,7 @@ struct BucketHead {
   const void* prepared;
   const void* cb;
   float scale;
+  float gain_log2_lo, gain_log2_step;     // byte-coded gains only
   int pad;
 };
 
@@ -166,9 +169,9 @@ struct BucketArgs {
   BucketHead h[kMaxGroup];
 };
 
-hipError_t launch_bucket(bool cb_i8, bool gb_f16, const BucketArgs&, int parts, int heads, hipStream_t);
+hipError_t launch_bucket(bool cb_i8, int gb_kind, const BucketArgs&, int parts, int heads, hipStream_t);
 // One-time regrouping of a layer into the layout above (three kernels: count, scan, fill).
-hipError_t launch_bucket_prepare(const LayerPtrs&, int idx_u32, int gb_f16, int n_in, int n_out,
+hipError_t launch_bucket_prepare(const LayerPtrs&, int idx_u32, int gb_kind, int n_in, int n_out,
                                  const BucketGeom&, void* prepared, hipStream_t);
 
 // ---- reduction of i-chunk partial sums ------------------------------------------

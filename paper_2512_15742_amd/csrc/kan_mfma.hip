@@ -68,6 +68,7 @@ __global__ __launch_bounds__(kThreads) void kan_prep_coef_kernel(const PrepCoefA
   const IdxT* idx = (const IdxT*)hp.idx;
   const GbT* gain = (const GbT*)hp.gain;
   const GbT* bias = (const GbT*)hp.bias;
+  const Q8Params qp = {hp.gain_log2_lo, hp.gain_log2_step, hp.bias_scale};
   const CbT* cb = (const CbT*)hp.cb;
   uint4* cf = a.cf + (long long)head * a.cf_head_stride;
   float* bp = a.bias_partial + (long long)head * a.bp_head_stride;
@@ -86,8 +87,8 @@ __global__ __launch_bounds__(kThreads) void kan_prep_coef_kernel(const PrepCoefA
       uint32_t idv[1];
       float gv[1], bv[1];
       load_idx<IdxT, 1>(idx + e, idv);
-      load_gb<GbT, 1>(gain + e, gv);
-      load_gb<GbT, 1>(bias + e, bv);
+      load_gain<GbT, 1>(gain + e, qp, gv);
+      load_bias<GbT, 1>(bias + e, qp, bv);
       id[r] = idv[0];
       g[r] = ok ? gv[0] : 0.f;          // rows past the end of a ragged last step are zero
       bs += ok ? bv[0] : 0.f;
@@ -312,12 +313,15 @@ __global__ __launch_bounds__(kMfmaThreads, 2) void kan_mfma_kernel(const MfmaArg
 template <typename IdxT>
 hipError_t prep_types(const GatherCfg& c, const PrepCoefArgs& a, dim3 grid, hipStream_t s) {
   if (c.code == kCbI8) {
-    if (c.gb_f16)
+    if (c.gb_kind == kGbQ8)
+      hipLaunchKernelGGL((kan_prep_coef_kernel<IdxT, q8_t, int8_t>), grid, dim3(kThreads), 0, s, a);
+    else if (c.gb_kind == kGbF16)
       hipLaunchKernelGGL((kan_prep_coef_kernel<IdxT, __half, int8_t>), grid, dim3(kThreads), 0, s, a);
     else
       hipLaunchKernelGGL((kan_prep_coef_kernel<IdxT, float, int8_t>), grid, dim3(kThreads), 0, s, a);
   } else {
-    if (c.gb_f16)
+    if (c.gb_kind == kGbQ8) return hipErrorInvalidValue;    // byte-coded gain/bias go with Int8 codebooks
+    if (c.gb_kind == kGbF16)
       hipLaunchKernelGGL((kan_prep_coef_kernel<IdxT, __half, float>), grid, dim3(kThreads), 0, s, a);
     else
       hipLaunchKernelGGL((kan_prep_coef_kernel<IdxT, float, float>), grid, dim3(kThreads), 0, s, a);

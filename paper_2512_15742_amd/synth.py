@@ -31,12 +31,16 @@ class VQLayerParams:
     codebook: np.ndarray      # [K][10] float32 or int8
     scale: np.float32         # Int8: value = scale * q; 1.0 for float codebooks
     idx: np.ndarray           # [in][out] uint16 or uint32
-    gain: np.ndarray          # [in][out] float32 or float16
-    bias: np.ndarray          # [in][out] float32 or float16
+    gain: np.ndarray          # [in][out] float32 or float16, or uint8 codes (byte-coded format)
+    bias: np.ndarray          # [in][out] float32 or float16, or int8 codes
+    gb_params: tuple = None   # byte-coded format only: (gain_log2_lo, gain_log2_step, bias_scale) as float32
 
     def as_dict(self):
-        return {"codebook": self.codebook, "scale": self.scale, "idx": self.idx,
-                "gain": self.gain, "bias": self.bias}
+        d = {"codebook": self.codebook, "scale": self.scale, "idx": self.idx,
+             "gain": self.gain, "bias": self.bias}
+        if self.gb_params is not None:
+            d["gb_params"] = self.gb_params
+        return d
 
     @property
     def metadata_bytes(self) -> int:
@@ -63,6 +67,28 @@ def quantise_shapes(shapes: np.ndarray):
     return q, scale
 
 
+def encode_gain_bias_q8(gain: np.ndarray, bias: np.ndarray):
+    """One byte each (the 16 bits per edge of the fully quantised format): gains on a
+    logarithmic grid, biases on a linear one.  Encoder only - what the codes MEAN is the
+    method's business (oracle and kernels each state it):
+        gain code 0 for a zero gain, else rint((log2 g - lo) / step) in 1..255, where
+        step = (log2 of the largest gain - log2 of the smallest positive one) / 254 and
+        lo = log2 of the smallest positive gain - step (so that it gets code 1);
+        bias code rint(b / bias_scale) in -127..127, bias_scale = max|b| / 127.
+    Returns (gain codes uint8, bias codes int8, (lo, step, bias_scale) as float32)."""
+    g = gain.astype(np.float64)
+    pos = g > 0
+    lg = np.log2(g[pos]) if pos.any() else np.array([0.0])
+    step = np.float32(max((lg.max() - lg.min()) / 254.0, 1e-6))
+    lo = np.float32(lg.min() - float(step))
+    qg = np.zeros(g.shape, dtype=np.uint8)
+    qg[pos] = np.clip(np.rint((np.log2(g[pos]) - float(lo)) / float(step)), 1, 255).astype(np.uint8)
+    b = bias.astype(np.float64)
+    bscale = np.float32(max(np.abs(b).max() / 127.0, 1e-30))
+    qb = np.clip(np.rint(b / float(bscale)), -127, 127).astype(np.int8)
+    return qg, qb, (lo, step, bscale)
+
+
 def make_layer(seed: int, n_in: int, n_out: int, K: int, *, cb_dtype="f32",
                gb_dtype="f32", idx_dtype=None) -> VQLayerParams:
     rng = np.random.default_rng(seed)
@@ -79,9 +105,12 @@ def make_layer(seed: int, n_in: int, n_out: int, K: int, *, cb_dtype="f32",
     if idx_dtype == "u16" and K > 65536:
         raise ValueError("K does not fit a 16-bit index")
     idx = rng.integers(0, K, size=(n_in, n_out), dtype=np.int64).astype(np_idx)
-    np_gb = {"f32": np.float32, "f16": np.float16}[gb_dtype]
+    np_gb = {"f32": np.float32, "f16": np.float16, "q8": np.float64}[gb_dtype]
     gain = np.abs(rng.normal(0.0, 0.1, size=(n_in, n_out))).astype(np_gb)
     bias = rng.normal(0.0, 0.01, size=(n_in, n_out)).astype(np_gb)
+    if gb_dtype == "q8":
+        qg, qb, params = encode_gain_bias_q8(gain, bias)
+        return VQLayerParams(n_in, n_out, K, codebook, scale, idx, qg, qb, params)
     return VQLayerParams(n_in, n_out, K, codebook, scale, idx, gain, bias)
 
 
@@ -112,10 +141,12 @@ def config2(B: int):
     return [make_layer(2000, 2048, 512, 65536)], make_x(2900 + B, B, 2048, "normal")
 
 
-def config3_layers():
-    """Two-layer Int8 head 2048 -> 1024 -> 256, fp16 gain/bias, K = 65,536 each."""
-    return [make_layer(3000, 2048, 1024, 65536, cb_dtype="i8", gb_dtype="f16"),
-            make_layer(3001, 1024, 256, 65536, cb_dtype="i8", gb_dtype="f16")]
+def config3_layers(gb_dtype: str = "f16"):
+    """Two-layer Int8 head 2048 -> 1024 -> 256, fp16 gain/bias, K = 65,536 each.
+    gb_dtype="q8": the same draws with gain and bias encoded in one byte each (the
+    4-bytes-per-edge format of the paper, section 4.2)."""
+    return [make_layer(3000, 2048, 1024, 65536, cb_dtype="i8", gb_dtype=gb_dtype),
+            make_layer(3001, 1024, 256, 65536, cb_dtype="i8", gb_dtype=gb_dtype)]
 
 
 def config3(B: int):

@@ -29,9 +29,11 @@ def test_exports_match_header():
 
 
 def test_struct_layout_matches_header():
-    # 8 int32, 4 pointers, float, int32, pointer -> 80 bytes on LP64; profile record 56 + 4 + 4
-    assert C.sizeof(kb.kan_vq_layer) == 80
+    # 8 int32, 4 pointers, float, int32, pointer, 3 floats, int32 -> 96 bytes on LP64;
+    # profile record 56 + 4 + 4
+    assert C.sizeof(kb.kan_vq_layer) == 96
     assert kb.kan_vq_layer.prepared.offset == 72
+    assert kb.kan_vq_layer.gain_log2_lo.offset == 80 and kb.kan_vq_layer.bias_scale.offset == 88
     assert C.sizeof(kb.kan_prof_record) == 64
 
 
@@ -44,7 +46,8 @@ def test_status_strings():
 def _desc(**kw):
     base = dict(n_in=8, n_out=8, G=10, degree=3, K=16, idx_dtype=kb.KAN_U16, gb_dtype=kb.KAN_F32,
                 cb_dtype=kb.KAN_F32, idx=0x1000, gain=0x2000, bias=0x3000, codebook=0x4000,
-                scale=1.0, rule=0, prepared=None)
+                scale=1.0, rule=0, prepared=None, gain_log2_lo=0.0, gain_log2_step=0.0,
+                bias_scale=0.0, reserved=0)
     base.update(kw)
     return kb.kan_vq_layer(**base)
 
@@ -62,6 +65,7 @@ FAKE = C.c_void_p(0x10000)
     (dict(K=65537), kb.KAN_ERR_SHAPE),                       # does not fit a 16-bit index
     (dict(idx_dtype=kb.KAN_F32), kb.KAN_ERR_DTYPE),
     (dict(gb_dtype=kb.KAN_I8), kb.KAN_ERR_DTYPE),
+    (dict(gb_dtype=kb.KAN_Q8), kb.KAN_ERR_UNSUPPORTED),       # byte-coded gain/bias need an Int8 codebook
     (dict(cb_dtype=kb.KAN_F16), kb.KAN_ERR_DTYPE),
     (dict(idx=0), kb.KAN_ERR_NULL),
     (dict(codebook=0), kb.KAN_ERR_NULL),
@@ -139,6 +143,16 @@ def test_prepare_arguments_and_planning():
     assert L.kan_vq_workspace_bytes(C.byref(d), 1, 1, 1, kb.KAN_PATH_GATHER) == 8 * 1024 * 4
     d.codebook = 0x4008                                  # bucket copies need 16-byte alignment
     assert L.kan_vq_planned_kernel(C.byref(d), 1, 1, kb.KAN_PATH_GATHER) == b"kan_gather_bt1"
+
+
+def test_byte_coded_layers_plan_and_prepare():
+    L = kb.lib()
+    d = _desc(n_in=2048, n_out=1024, K=65536, cb_dtype=kb.KAN_I8, gb_dtype=kb.KAN_Q8, gain=0x2001, bias=0x3003,
+              gain_log2_lo=-12.0, gain_log2_step=0.04, bias_scale=1e-4)
+    assert L.kan_vq_workspace_bytes(C.byref(d), 1, 1, 16, kb.KAN_PATH_AUTO) != kb.SIZE_INVALID   # bytes need no alignment
+    need = L.kan_vq_prepared_bytes(C.byref(d))
+    E = 2048 * 1024
+    assert 5 * E < need < 5 * E + (1 << 16)              # u16 input + u16 local id + 1-byte gain code
 
 
 def test_head_table_consistency():

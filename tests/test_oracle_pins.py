@@ -405,7 +405,8 @@ def _pin_suite():
             test_head_is_layers_with_tanh_between, test_pli_nodes_and_index,
             test_pli_is_linear_interpolation_numpy_interp,
             test_pli_reproduces_node_values_linear_functions_and_unity,
-            test_pli_layer_closed_forms_and_scalar_definition,
+            test_pli_layer_closed_forms_and_scalar_definition, test_q8_gain_bias_meaning,
+            test_q8_round_trip_through_the_encoder,
             lambda: test_scalar_definition_vs_vectorised(False), lambda: test_scalar_definition_vs_vectorised(True)]
 
 
@@ -424,7 +425,7 @@ def _mutations():
     """(name, attribute of the oracle module, replacement) - each a plausible slip."""
     real = {k: getattr(ko, k) for k in ("knots", "basis_matrix", "reconstruct_coefficients", "dequantise_codebook",
                                         "dense_layer_forward", "pli_matrix", "pli_nodes", "clamp_input",
-                                        "vq_head_forward")}
+                                        "vq_head_forward", "dequantise_gain_bias")}
 
     def knots_shifted():                       # knot vector off by one interval
         return real["knots"]() + 2.0 / 7.0
@@ -440,22 +441,42 @@ def _mutations():
         Bm[..., -1] = 0.0
         return Bm
 
-    def recon_no_bias(cb, scale, idx, gain, bias):
-        return real["reconstruct_coefficients"](cb, scale, idx, gain, np.zeros_like(np.asarray(bias, dtype=np.float64)))
+    def recon_no_bias(cb, scale, idx, gain, bias, gb_params=None):
+        g, b = real["dequantise_gain_bias"](gain, bias, gb_params)
+        return real["reconstruct_coefficients"](cb, scale, idx, g, np.zeros_like(b))
 
-    def recon_transposed_idx(cb, scale, idx, gain, bias):
+    def recon_transposed_idx(cb, scale, idx, gain, bias, gb_params=None):
         idx = np.asarray(idx)
         if idx.shape[0] == idx.shape[1]:
             idx = idx.T
         else:
             idx = idx[::-1]
-        return real["reconstruct_coefficients"](cb, scale, idx, gain, bias)
+        return real["reconstruct_coefficients"](cb, scale, idx, gain, bias, gb_params)
 
-    def recon_gain_on_bias(cb, scale, idx, gain, bias):     # g * (C + b) instead of g * C + b
+    def recon_gain_on_bias(cb, scale, idx, gain, bias, gb_params=None):     # g * (C + b) instead of g * C + b
         c = real["dequantise_codebook"](cb, scale)
-        g = np.asarray(gain, dtype=np.float64)
-        b = np.asarray(bias, dtype=np.float64)
+        g, b = real["dequantise_gain_bias"](gain, bias, gb_params)
         return g[..., None] * (c[np.asarray(idx).astype(np.int64)] + b[..., None])
+
+    def q8_zero_code_is_smallest_gain(gain, bias, gb_params=None):       # code 0 not treated as zero
+        if gb_params is None:
+            return real["dequantise_gain_bias"](gain, bias, gb_params)
+        lo, step, bscale = (float(v) for v in gb_params)
+        return np.exp2(lo + step * np.asarray(gain).astype(np.float64)), bscale * np.asarray(bias).astype(np.float64)
+
+    def q8_bias_unsigned(gain, bias, gb_params=None):                    # bias byte read as unsigned
+        if gb_params is None:
+            return real["dequantise_gain_bias"](gain, bias, gb_params)
+        g, _ = real["dequantise_gain_bias"](gain, bias, gb_params)
+        return g, float(gb_params[2]) * np.asarray(bias).view(np.uint8).astype(np.float64)
+
+    def q8_natural_log(gain, bias, gb_params=None):                      # e ** instead of 2 **
+        if gb_params is None:
+            return real["dequantise_gain_bias"](gain, bias, gb_params)
+        g, b = real["dequantise_gain_bias"](gain, bias, gb_params)
+        lo, step = float(gb_params[0]), float(gb_params[1])
+        c = np.asarray(gain).astype(np.float64)
+        return np.where(np.asarray(gain) == 0, 0.0, np.exp(lo + step * c)), b
 
     def dequant_ignores_scale(cb, scale=1.0):
         return np.asarray(cb).astype(np.float64)
@@ -502,7 +523,10 @@ def _mutations():
             ("int8 read unsigned", "dequantise_codebook", dequant_unsigned),
             ("outputs reversed", "dense_layer_forward", dense_sums_wrong_axis),
             ("taps swapped", "pli_matrix", pli_swapped_taps), ("dx = 2/G", "pli_nodes", pli_nodes_ten_intervals),
-            ("no clamp", "clamp_input", no_clamp), ("tanh after last layer", "vq_head_forward", head_tanh_after_last)]
+            ("no clamp", "clamp_input", no_clamp), ("tanh after last layer", "vq_head_forward", head_tanh_after_last),
+            ("gain code 0 not zero", "dequantise_gain_bias", q8_zero_code_is_smallest_gain),
+            ("bias byte unsigned", "dequantise_gain_bias", q8_bias_unsigned),
+            ("natural instead of binary log", "dequantise_gain_bias", q8_natural_log)]
 
 
 def test_pins_pass_unmutated():
@@ -513,3 +537,46 @@ def test_pins_pass_unmutated():
 def test_planted_mistake_fails_a_pin(monkeypatch, name, attr, repl):
     monkeypatch.setattr(ko, attr, repl)
     assert _fails_some_pin(), f"no pin notices: {name}"
+
+
+# ---- byte-coded gain / bias (paper §4.2: logarithmic Int8 gain, linear Int8 bias) --------
+
+def test_q8_gain_bias_meaning():
+    """What the codes mean, pinned by values that need no formula of the oracle's: with
+    lo = -8 and step = 1/16 every 16th code is an exact power of two; code 0 is zero; the
+    grid is strictly increasing; bias codes are a plain multiple."""
+    qg = np.arange(256, dtype=np.uint8)
+    qb = np.arange(-128, 128).astype(np.int8)
+    g, b = ko.dequantise_gain_bias(qg, qb, (np.float32(-8.0), np.float32(1.0 / 16.0), np.float32(0.25)))
+    assert g[0] == 0.0
+    for c in range(16, 256, 16):
+        assert g[c] == 2.0 ** (-8 + c // 16)
+    assert (np.diff(g[1:]) > 0).all()
+    assert np.allclose(g[2:] / g[1:-1], 2.0 ** (1.0 / 16.0), rtol=1e-15)
+    assert np.array_equal(b, 0.25 * np.arange(-128, 128))
+    # floating arrays pass through untouched
+    gf, bf = ko.dequantise_gain_bias(np.float16([0.5, 0.25]), np.float32([1.5, -2.0]))
+    assert gf.tolist() == [0.5, 0.25] and bf.tolist() == [1.5, -2.0]
+
+
+def test_q8_round_trip_through_the_encoder():
+    """Encoder (generator side) and meaning (oracle) fit together: decoded gains are within
+    half a logarithmic step of the originals, biases within half a linear step, zeros stay zero."""
+    rng = np.random.default_rng(4)
+    gain = np.abs(rng.normal(0, 0.1, size=(40, 30)))
+    gain[3, 4] = 0.0
+    bias = rng.normal(0, 0.01, size=(40, 30))
+    qg, qb, params = synth.encode_gain_bias_q8(gain, bias)
+    g, b = ko.dequantise_gain_bias(qg, qb, params)
+    assert g[3, 4] == 0.0 and qg[3, 4] == 0
+    pos = gain > 0
+    assert np.abs(np.log2(g[pos]) - np.log2(gain[pos])).max() <= 0.5 * float(params[1]) * (1 + 1e-6)
+    assert np.abs(b - bias).max() <= 0.5 * float(params[2]) * (1 + 1e-6)
+    # a layer in the byte-coded format equals the floating layer built from the decoded values
+    P = synth.make_layer(9, 12, 7, 50, cb_dtype="i8", gb_dtype="q8")
+    x = synth.make_x(2, 5, 12)
+    gd, bd = ko.dequantise_gain_bias(P.gain, P.bias, P.gb_params)
+    y_codes = ko.vq_layer_forward(x, **P.as_dict())
+    y_float = ko.vq_layer_forward(x, P.codebook, P.scale, P.idx, gd, bd)
+    assert np.array_equal(y_codes, y_float)
+    assert P.metadata_bytes == 4 * P.edges                 # 32 bits per edge at K <= 2^16 (§4.2)
