@@ -177,6 +177,35 @@ kan_status kan_vq_debug_gather(const kan_vq_layer* L, uint32_t* ids, float* rows
 /* Debug: *count (device uint32, overwritten) = number of edges with idx >= K.   */
 kan_status kan_vq_count_bad_indices(const kan_vq_layer* L, uint32_t* count, void* stream);
 
+/* Compression side (section 4.2, steps 1 and 3 of the post-training procedure; learning the
+ * codebook itself, step 2, is not part of this library).  For every edge e = i*out + j of a dense
+ * layer coef[in][out][10]:
+ *   bias[e] = mean of the 10 coefficients, gain[e] = Euclidean norm of the centred grid
+ *             (so that the normalised grid is zero-mean and unit-norm like the codebook shapes;
+ *             the paper says "unit variance": same shapes, gains differ by sqrt(10));
+ *   idx[e]  = index of the codebook row nearest (squared Euclidean distance) to the normalised
+ *             grid; for an all-constant grid (gain 0) the row of smallest norm.
+ * The distance contraction runs on the matrix cores with split fp16 operands (fp32-grade
+ * scores); rows whose scores agree to ~2e-6 relative may resolve to either index.
+ * codebook: fp32 [K][10]; idx: KAN_U16 (K <= 65536) or KAN_U32 array [in][out]; gain, bias:
+ * fp32 [in][out].  ws: kan_vq_assign_workspace_bytes(K) bytes, 256-byte aligned.  All device. */
+size_t kan_vq_assign_workspace_bytes(int32_t K);
+kan_status kan_vq_assign(const float* coef, int32_t in, int32_t out, const float* codebook, int32_t K,
+                         int32_t idx_dtype, void* idx, float* gain, float* bias,
+                         void* ws, size_t ws_bytes, void* stream);
+
+/* Reconstruction quality of an assignment ("R^2 between the original grids and the
+ * reconstructed gain * C[idx] + bias", section 4.2): sums[0] = sum of squared residuals,
+ * sums[1] = sum of all coefficients, sums[2] = sum of their squares (device, 3 doubles,
+ * accumulated in fp64 in a fixed order), from which
+ *   R^2 = 1 - sums[0] / (sums[2] - sums[1]^2 / (10 * in * out)).
+ * ws: kan_vq_reconstruction_workspace_bytes(in, out) bytes, 256-byte aligned.               */
+size_t kan_vq_reconstruction_workspace_bytes(int32_t in, int32_t out);
+kan_status kan_vq_reconstruction_sums(const float* coef, int32_t in, int32_t out, const float* codebook,
+                                      int32_t K, int32_t idx_dtype, const void* idx, const float* gain,
+                                      const float* bias, double* sums, void* ws, size_t ws_bytes,
+                                      void* stream);
+
 /* Per-kernel timing with HIP events on the launch stream, for benchmarks.
  * kan_prof_begin creates up to max_launches event pairs (this is the one place
  * the library creates HIP objects) and brackets every kernel it launches from

@@ -45,7 +45,9 @@ invariance, linearity in gain / additivity in bias, Int8 == fp32 twin; for the
 piecewise-linear rule: numpy.interp, reproduction of the node values and of
 every linear function, hat-function integrals, index against brute force; for
 byte-coded gain/bias: exact powers of two at integer exponents, zero code,
-monotonicity, round trip through the encoder within half a step.
+monotonicity, round trip through the encoder within half a step; for the
+assignment step: brute-force loops, scipy's k-d tree, exact recovery of a layer built
+from the codebook (R^2 = 1), invariance under affine changes of a grid.
 """
 from __future__ import annotations
 
@@ -337,6 +339,59 @@ def vq_head_forward(x, layers, return_hidden: bool = False, rule: str = "bspline
         else:
             a = y
     return (a, hidden) if return_hidden else a
+
+
+# --------------------------------------------------------------------------
+# Compression side: normalise every grid, assign it to the nearest codebook shape
+# (paper §4.2, steps (1) and (3) of the post-training procedure; R^2 of the reconstruction)
+# --------------------------------------------------------------------------
+
+def normalise_grids(coef):
+    """coef [..., G] -> (shape [..., G], gain [...], bias [...]): bias is the mean of the grid,
+    gain the Euclidean norm of the centred grid, shape = centred / gain (zeros where gain is 0).
+    The paper normalises to zero mean and unit variance; the benchmark's codebooks hold
+    zero-mean unit-NORM shapes, so the norm is used here: the same shapes, gains differ by
+    sqrt(G) (reading stated in the design notes)."""
+    c = np.asarray(coef, dtype=np.float64)
+    bias = c.mean(axis=-1)
+    centred = c - bias[..., None]
+    gain = np.sqrt((centred * centred).sum(axis=-1))
+    safe = np.where(gain > 0, gain, 1.0)
+    return centred / safe[..., None], gain, bias
+
+
+def squared_distances(shapes, codebook):
+    """d2[e][k] = sum_m (shapes[e][m] - codebook[k][m])^2, written out as the definition
+    (memory E*K*G doubles: small inputs only)."""
+    n = np.asarray(shapes, dtype=np.float64).reshape(-1, G)
+    C = np.asarray(codebook, dtype=np.float64)
+    diff = n[:, None, :] - C[None, :, :]
+    return (diff * diff).sum(axis=-1)
+
+
+def assign_edges(coef, codebook, chunk: int = 64):
+    """(idx, gain, bias, d2_min) for a dense layer coef [in][out][G]: idx[i][j] is the first
+    codebook row at the smallest squared distance from the normalised grid of edge (i, j)."""
+    c = np.asarray(coef, dtype=np.float64)
+    n, gain, bias = normalise_grids(c)
+    flat = n.reshape(-1, G)
+    idx = np.empty(flat.shape[0], dtype=np.int64)
+    dmin = np.empty(flat.shape[0], dtype=np.float64)
+    for s in range(0, flat.shape[0], chunk):
+        d2 = squared_distances(flat[s:s + chunk], codebook)
+        idx[s:s + chunk] = d2.argmin(axis=1)
+        dmin[s:s + chunk] = d2.min(axis=1)
+    return idx.reshape(c.shape[:-1]), gain, bias, dmin.reshape(c.shape[:-1])
+
+
+def r_squared(coef, codebook, idx, gain, bias) -> float:
+    """R^2 between the original grids and the reconstruction gain * C[idx] + bias (paper §4.2):
+    1 - SS_res / SS_tot over all coefficients, SS_tot about their overall mean."""
+    c = np.asarray(coef, dtype=np.float64)
+    rec = reconstruct_coefficients(np.asarray(codebook, dtype=np.float64), 1.0, idx, gain, bias)
+    ss_res = ((c - rec) ** 2).sum()
+    ss_tot = ((c - c.mean()) ** 2).sum()
+    return float(1.0 - ss_res / ss_tot)
 
 
 def error_report(y_test, y_ref, A_ref=None) -> dict:

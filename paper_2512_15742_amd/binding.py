@@ -26,6 +26,8 @@ EXPORTS = [
     "kan_dense_workspace_bytes", "kan_dense_layer_forward", "kan_vq_head_forward",
     "kan_vq_debug_gather", "kan_vq_count_bad_indices", "kan_prof_begin", "kan_prof_end",
     "kan_status_string", "kan_vq_planned_kernel", "kan_vq_prepared_bytes", "kan_vq_prepare", "kan_pli_basis",
+    "kan_vq_assign_workspace_bytes", "kan_vq_assign", "kan_vq_reconstruction_workspace_bytes",
+    "kan_vq_reconstruction_sums",
 ]
 
 
@@ -91,6 +93,14 @@ def lib():
         L.kan_vq_prepared_bytes.restype = SZ
         L.kan_vq_prepare.argtypes = [LP, P, SZ, P]
         L.kan_vq_prepare.restype = I32
+        L.kan_vq_assign_workspace_bytes.argtypes = [I32]
+        L.kan_vq_assign_workspace_bytes.restype = SZ
+        L.kan_vq_assign.argtypes = [P, I32, I32, P, I32, I32, P, P, P, P, SZ, P]
+        L.kan_vq_assign.restype = I32
+        L.kan_vq_reconstruction_workspace_bytes.argtypes = [I32, I32]
+        L.kan_vq_reconstruction_workspace_bytes.restype = SZ
+        L.kan_vq_reconstruction_sums.argtypes = [P, I32, I32, P, I32, I32, P, P, P, P, P, SZ, P]
+        L.kan_vq_reconstruction_sums.restype = I32
         _lib = L
     return _lib
 
@@ -300,6 +310,42 @@ def kan_vq_prepare(layer: VQLayer, out=None):
         out = torch.empty(max(n, 1), dtype=torch.uint8, device=layer.idx.device)
     _check(lib().kan_vq_prepare(C.byref(layer.desc), _ptr(out), out.numel(), _stream_ptr()), "kan_vq_prepare")
     return out
+
+
+def kan_vq_assign(coef, codebook, ws=None):
+    """coef [in][out][10] float32, codebook [K][10] float32 (CUDA tensors) ->
+    (idx int16/int32 carrying uint16/uint32 bits [in][out], gain float32 [in][out], bias float32 [in][out])."""
+    torch = _torch()
+    assert coef.dtype == torch.float32 and coef.is_contiguous() and coef.shape[2] == 10
+    assert codebook.dtype == torch.float32 and codebook.is_contiguous() and codebook.shape[1] == 10
+    n_in, n_out, _ = coef.shape
+    K = codebook.shape[0]
+    u16 = K <= 65536
+    idx = torch.empty((n_in, n_out), dtype=torch.int16 if u16 else torch.int32, device=coef.device)
+    gain = torch.empty((n_in, n_out), dtype=torch.float32, device=coef.device)
+    bias = torch.empty((n_in, n_out), dtype=torch.float32, device=coef.device)
+    if ws is None:
+        ws = _workspace(lib().kan_vq_assign_workspace_bytes(K), coef.device)
+    st = lib().kan_vq_assign(_ptr(coef), n_in, n_out, _ptr(codebook), K, KAN_U16 if u16 else KAN_U32, _ptr(idx),
+                             _ptr(gain), _ptr(bias), _ptr(ws), ws.numel(), _stream_ptr())
+    _check(st, "kan_vq_assign")
+    return idx, gain, bias
+
+
+def kan_vq_reconstruction_r2(coef, codebook, idx, gain, bias) -> float:
+    """R^2 between the dense grids and gain * C[idx] + bias, from the library's fp64 sums."""
+    torch = _torch()
+    n_in, n_out, _ = coef.shape
+    K = codebook.shape[0]
+    ws = _workspace(lib().kan_vq_reconstruction_workspace_bytes(n_in, n_out), coef.device)
+    sums = torch.empty(3, dtype=torch.float64, device=coef.device)
+    st = lib().kan_vq_reconstruction_sums(_ptr(coef), n_in, n_out, _ptr(codebook), K,
+                                          KAN_U16 if idx.dtype == torch.int16 else KAN_U32, _ptr(idx), _ptr(gain),
+                                          _ptr(bias), _ptr(sums), _ptr(ws), ws.numel(), _stream_ptr())
+    _check(st, "kan_vq_reconstruction_sums")
+    ss_res, s1, s2 = (float(v) for v in sums.cpu())
+    n = 10.0 * n_in * n_out
+    return 1.0 - ss_res / (s2 - s1 * s1 / n)
 
 
 def kan_vq_planned_kernel(layer: VQLayer, B, n_heads=1, path=KAN_PATH_AUTO) -> str:

@@ -35,6 +35,7 @@ UNITS = [
     ("kan_mfma.hip", "kan_mfma.o", []),
     ("kan_fused.hip", "kan_fused.o", []),
     ("kan_bucket.hip", "kan_bucket.o", []),
+    ("kan_assign.hip", "kan_assign.o", []),
     ("kan_gather.hip", "kan_gather_bt1.o", ["-DKAN_BT=1"]),
     ("kan_gather.hip", "kan_gather_bt4.o", ["-DKAN_BT=4"]),
     ("kan_gather.hip", "kan_gather_bt16.o", ["-DKAN_BT=16"]),

@@ -684,6 +684,59 @@ kan_status kan_vq_prepare(const kan_vq_layer* L, void* prepared, size_t prepared
   });
 }
 
+size_t kan_vq_assign_workspace_bytes(int32_t K) {
+  if (K < 1) return (size_t)-1;
+  return round_up(assign_centroid_bytes(K), 256);
+}
+
+namespace {
+kan_status check_assign_shapes(int32_t in, int32_t out, int32_t K, int32_t idx_dtype) {
+  if (in < 1 || out < 1 || in > kMaxDim || out > kMaxDim || K < 1) return KAN_ERR_SHAPE;
+  if ((long long)in * out > (1ll << 31)) return KAN_ERR_SHAPE;
+  if (idx_dtype != KAN_U16 && idx_dtype != KAN_U32) return KAN_ERR_DTYPE;
+  if (idx_dtype == KAN_U16 && K > 65536) return KAN_ERR_SHAPE;
+  return KAN_OK;
+}
+}  // namespace
+
+kan_status kan_vq_assign(const float* coef, int32_t in, int32_t out, const float* codebook, int32_t K,
+                         int32_t idx_dtype, void* idx, float* gain, float* bias, void* ws, size_t ws_bytes,
+                         void* stream) {
+  kan_status st = check_assign_shapes(in, out, K, idx_dtype);
+  if (st != KAN_OK) return st;
+  if (!coef || !codebook || !idx || !gain || !bias) return KAN_ERR_NULL;
+  if (!aligned(coef, 8) || !aligned(codebook, 4) || !aligned(gain, 4) || !aligned(bias, 4) ||
+      !aligned(idx, idx_dtype == KAN_U16 ? 2 : 4))
+    return KAN_ERR_SHAPE;
+  if (!ws || !aligned(ws, 256) || ws_bytes < kan_vq_assign_workspace_bytes(K)) return KAN_ERR_WORKSPACE;
+  hipStream_t s = (hipStream_t)stream;
+  return run("kan_vq_assign", s, [&] {
+    return launch_assign(coef, (long long)in * out, codebook, K, idx_dtype == KAN_U32, idx, gain, bias, ws, s);
+  });
+}
+
+size_t kan_vq_reconstruction_workspace_bytes(int32_t in, int32_t out) {
+  if (in < 1 || out < 1 || in > kMaxDim || out > kMaxDim) return (size_t)-1;
+  return round_up((size_t)recon_blocks((long long)in * out) * 3 * sizeof(double), 256);
+}
+
+kan_status kan_vq_reconstruction_sums(const float* coef, int32_t in, int32_t out, const float* codebook, int32_t K,
+                                      int32_t idx_dtype, const void* idx, const float* gain, const float* bias,
+                                      double* sums, void* ws, size_t ws_bytes, void* stream) {
+  kan_status st = check_assign_shapes(in, out, K, idx_dtype);
+  if (st != KAN_OK) return st;
+  if (!coef || !codebook || !idx || !gain || !bias || !sums) return KAN_ERR_NULL;
+  if (!aligned(coef, 4) || !aligned(codebook, 4) || !aligned(gain, 4) || !aligned(bias, 4) || !aligned(sums, 8) ||
+      !aligned(idx, idx_dtype == KAN_U16 ? 2 : 4))
+    return KAN_ERR_SHAPE;
+  if (!ws || !aligned(ws, 256) || ws_bytes < kan_vq_reconstruction_workspace_bytes(in, out)) return KAN_ERR_WORKSPACE;
+  hipStream_t s = (hipStream_t)stream;
+  return run("kan_vq_reconstruction_sums", s, [&] {
+    return launch_recon_sums(coef, (long long)in * out, codebook, idx_dtype == KAN_U32, idx, gain, bias, (double*)ws,
+                             sums, s);
+  });
+}
+
 kan_status kan_vq_debug_gather(const kan_vq_layer* L, uint32_t* ids, float* rows, void* stream) {
   kan_status st = validate_layer(L);
   if (st != KAN_OK) return st;

@@ -174,6 +174,14 @@ hipError_t launch_bucket(bool cb_i8, int gb_kind, const BucketArgs&, int parts, 
 hipError_t launch_bucket_prepare(const LayerPtrs&, int idx_u32, int gb_kind, int n_in, int n_out,
                                  const BucketGeom&, void* prepared, hipStream_t);
 
+// ---- compression-side assignment (nearest codebook shape per edge) ---------------------------
+size_t assign_centroid_bytes(int K);       // prepared centroid operands (workspace)
+int recon_blocks(long long E);             // workgroups of the reconstruction-sums pass
+hipError_t launch_assign(const float* coef, long long E, const float* cb, int K, int idx_u32, void* idx,
+                         float* gain, float* bias, void* ws, hipStream_t);
+hipError_t launch_recon_sums(const float* coef, long long E, const float* cb, int idx_u32, const void* idx,
+                             const float* gain, const float* bias, double* part, double* sums, hipStream_t);
+
 // ---- reduction of i-chunk partial sums ------------------------------------------
 // dst[n] = act( sum_c partial[c * chunk_stride + n] ), n < count, for every head.
 hipError_t launch_reduce(const float* partial, long long head_stride, long long chunk_stride,

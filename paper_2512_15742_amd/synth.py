@@ -126,6 +126,20 @@ def make_x(seed: int, B: int, n_in: int, dist: str = "uniform") -> np.ndarray:
     return x.astype(np.float32)
 
 
+def make_dense_grids(seed: int, n_in: int, n_out: int, K: int, noise: float = 0.05):
+    """A dense layer to compress, with the codebook to compress it against:
+    coef[i][j] = g * shape[k] + b + noise * g * N(0,1)^10 with the draws of make_layer
+    (shapes zero-mean unit-norm, k uniform, g ~ |N(0,0.1)|, b ~ N(0,0.01)); returns
+    (coef float32 [in][out][10], codebook float32 [K][10], k int64 [in][out])."""
+    rng = np.random.default_rng(seed)
+    shapes = make_shapes(rng, K)
+    k = rng.integers(0, K, size=(n_in, n_out), dtype=np.int64)
+    g = np.abs(rng.normal(0.0, 0.1, size=(n_in, n_out))) + 1e-3
+    b = rng.normal(0.0, 0.01, size=(n_in, n_out))
+    coef = g[..., None] * (shapes[k].astype(np.float64) + noise * rng.standard_normal((n_in, n_out, G))) + b[..., None]
+    return coef.astype(np.float32), shapes, k
+
+
 # ---- the five benchmark configurations ------------------------------------
 # Seeds: configuration n, layer l -> 1000*n + l; x -> 1000*n + 900 + variant.
 # Configuration 4: head h uses seed h for its first layer and h + 100 for its

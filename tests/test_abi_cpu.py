@@ -155,6 +155,19 @@ def test_byte_coded_layers_plan_and_prepare():
     assert 5 * E < need < 5 * E + (1 << 16)              # u16 input + u16 local id + 1-byte gain code
 
 
+def test_assign_argument_errors():
+    L = kb.lib()
+    F = FAKE
+    need = L.kan_vq_assign_workspace_bytes(65536)
+    assert need == 65536 * 64
+    assert L.kan_vq_assign(F, 8, 8, F, 65537, kb.KAN_U16, F, F, F, F, 1 << 30, None) == kb.KAN_ERR_SHAPE
+    assert L.kan_vq_assign(F, 8, 8, F, 100, kb.KAN_F32, F, F, F, F, 1 << 30, None) == kb.KAN_ERR_DTYPE
+    assert L.kan_vq_assign(None, 8, 8, F, 100, kb.KAN_U16, F, F, F, F, 1 << 30, None) == kb.KAN_ERR_NULL
+    assert L.kan_vq_assign(F, 8, 8, F, 100, kb.KAN_U16, F, F, F, F, 100, None) == kb.KAN_ERR_WORKSPACE
+    assert L.kan_vq_assign(F, 0, 8, F, 100, kb.KAN_U16, F, F, F, F, 1 << 30, None) == kb.KAN_ERR_SHAPE
+    assert L.kan_vq_reconstruction_sums(F, 8, 8, F, 100, kb.KAN_U16, F, F, F, None, F, 1 << 20, None) == kb.KAN_ERR_NULL
+
+
 def test_head_table_consistency():
     L = kb.lib()
     arr = (kb.kan_vq_layer * 4)()

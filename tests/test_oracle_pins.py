@@ -406,7 +406,8 @@ def _pin_suite():
             test_pli_is_linear_interpolation_numpy_interp,
             test_pli_reproduces_node_values_linear_functions_and_unity,
             test_pli_layer_closed_forms_and_scalar_definition, test_q8_gain_bias_meaning,
-            test_q8_round_trip_through_the_encoder,
+            test_q8_round_trip_through_the_encoder, test_assignment_brute_force_and_kdtree,
+            test_assignment_recovers_a_layer_built_from_the_codebook,
             lambda: test_scalar_definition_vs_vectorised(False), lambda: test_scalar_definition_vs_vectorised(True)]
 
 
@@ -425,7 +426,8 @@ def _mutations():
     """(name, attribute of the oracle module, replacement) - each a plausible slip."""
     real = {k: getattr(ko, k) for k in ("knots", "basis_matrix", "reconstruct_coefficients", "dequantise_codebook",
                                         "dense_layer_forward", "pli_matrix", "pli_nodes", "clamp_input",
-                                        "vq_head_forward", "dequantise_gain_bias")}
+                                        "vq_head_forward", "dequantise_gain_bias", "normalise_grids",
+                                        "squared_distances")}
 
     def knots_shifted():                       # knot vector off by one interval
         return real["knots"]() + 2.0 / 7.0
@@ -514,6 +516,18 @@ def _mutations():
             return np.tanh(out[0]), out[1]
         return np.tanh(out)
 
+    def normalise_by_std(coef):                                         # unit variance instead of unit norm
+        n, g, b = real["normalise_grids"](coef)
+        return n * math.sqrt(ko.G), g / math.sqrt(ko.G), b
+
+    def normalise_without_centring(coef):
+        c = np.asarray(coef, dtype=np.float64)
+        g = np.sqrt((c * c).sum(axis=-1))
+        return c / np.where(g > 0, g, 1.0)[..., None], g, np.zeros(c.shape[:-1])
+
+    def distances_as_dot_products(shapes, codebook):                     # similarity mistaken for distance
+        return np.asarray(shapes, dtype=np.float64).reshape(-1, ko.G) @ np.asarray(codebook, dtype=np.float64).T
+
     return [("knots shifted", "knots", knots_shifted), ("8 intervals", "knots", knots_wrong_spacing),
             ("bases reversed", "basis_matrix", basis_reversed), ("basis dropped", "basis_matrix", basis_dropped_term),
             ("bias dropped", "reconstruct_coefficients", recon_no_bias),
@@ -526,7 +540,10 @@ def _mutations():
             ("no clamp", "clamp_input", no_clamp), ("tanh after last layer", "vq_head_forward", head_tanh_after_last),
             ("gain code 0 not zero", "dequantise_gain_bias", q8_zero_code_is_smallest_gain),
             ("bias byte unsigned", "dequantise_gain_bias", q8_bias_unsigned),
-            ("natural instead of binary log", "dequantise_gain_bias", q8_natural_log)]
+            ("natural instead of binary log", "dequantise_gain_bias", q8_natural_log),
+            ("unit variance instead of unit norm", "normalise_grids", normalise_by_std),
+            ("grids not centred", "normalise_grids", normalise_without_centring),
+            ("dot product used as a distance", "squared_distances", distances_as_dot_products)]
 
 
 def test_pins_pass_unmutated():
@@ -580,3 +597,57 @@ def test_q8_round_trip_through_the_encoder():
     y_float = ko.vq_layer_forward(x, P.codebook, P.scale, P.idx, gd, bd)
     assert np.array_equal(y_codes, y_float)
     assert P.metadata_bytes == 4 * P.edges                 # 32 bits per edge at K <= 2^16 (§4.2)
+
+
+# ---- compression side: normalise + nearest codebook shape (paper §4.2 steps 1 and 3) ---------
+
+def test_assignment_brute_force_and_kdtree():
+    from scipy.spatial import cKDTree
+    rng = np.random.default_rng(8)
+    coef = rng.standard_normal((6, 5, ko.G)) * rng.uniform(0.1, 3.0, size=(6, 5, 1)) + rng.normal(size=(6, 5, 1))
+    cb = synth.make_shapes(rng, 300).astype(np.float64)
+    idx, gain, bias, dmin = ko.assign_edges(coef, cb)
+    for i in range(6):
+        for j in range(5):
+            grid = coef[i, j]
+            b = sum(grid) / ko.G
+            cen = [v - b for v in grid]
+            g = math.sqrt(sum(v * v for v in cen))
+            shape = [v / g for v in cen]
+            d = [sum((shape[m] - cb[k][m]) ** 2 for m in range(ko.G)) for k in range(300)]
+            k_best = min(range(300), key=lambda k: d[k])
+            assert idx[i, j] == k_best and abs(dmin[i, j] - d[k_best]) < 1e-12
+            assert abs(gain[i, j] - g) < 1e-12 and abs(bias[i, j] - b) < 1e-12
+    shapes, _, _ = ko.normalise_grids(coef)
+    assert np.abs(shapes.sum(axis=-1)).max() < 1e-12 and np.abs((shapes ** 2).sum(axis=-1) - 1).max() < 1e-12
+    dist, nn = cKDTree(cb).query(shapes.reshape(-1, ko.G), k=1)            # library nearest-neighbour search
+    assert np.array_equal(nn, idx.reshape(-1)) and np.abs(dist ** 2 - dmin.reshape(-1)).max() < 1e-12
+
+
+def test_assignment_recovers_a_layer_built_from_the_codebook():
+    """c = g * C[k] + b with zero-mean unit-norm shapes: the assignment returns k, g, b and R^2 = 1;
+    an affine change of a grid changes gain and bias but not its index; a constant grid has gain 0."""
+    rng = np.random.default_rng(9)
+    cb = synth.make_shapes(rng, 500).astype(np.float64)
+    cb -= cb.mean(axis=1, keepdims=True)                  # zero mean and unit norm to float64 accuracy
+    cb /= np.linalg.norm(cb, axis=1, keepdims=True)
+    k = rng.integers(0, 500, size=(7, 9))
+    g = rng.uniform(0.05, 2.0, size=(7, 9))
+    b = rng.normal(size=(7, 9))
+    coef = g[..., None] * cb[k] + b[..., None]
+    idx, gain, bias, dmin = ko.assign_edges(coef, cb)
+    assert np.array_equal(idx, k) and np.abs(gain - g).max() < 1e-12 and np.abs(bias - b).max() < 1e-12
+    assert dmin.max() < 1e-24
+    assert abs(ko.r_squared(coef, cb, idx, gain, bias) - 1.0) < 1e-12
+    noisy = coef + 0.05 * rng.standard_normal(coef.shape)
+    i1, g1, b1, _ = ko.assign_edges(noisy, cb)
+    i2, g2, b2, _ = ko.assign_edges(3.0 * noisy - 1.5, cb)
+    assert np.array_equal(i1, i2) and np.abs(g2 - 3.0 * g1).max() < 1e-12 and np.abs(b2 - (3.0 * b1 - 1.5)).max() < 1e-12
+    r2 = ko.r_squared(noisy, cb, i1, g1, b1)
+    assert 0.5 < r2 < 1.0
+    # R^2 against its definition written with numpy's variance
+    rec = g1[..., None] * cb[i1] + b1[..., None]
+    assert abs(r2 - (1 - ((noisy - rec) ** 2).mean() / noisy.var())) < 1e-12
+    flat = np.full((1, 1, ko.G), 0.7)
+    i0, g0, b0, _ = ko.assign_edges(flat, cb)
+    assert g0[0, 0] == 0.0 and abs(b0[0, 0] - 0.7) < 1e-15
