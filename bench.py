@@ -175,6 +175,25 @@ def sweep(kb, torch, synth):
         ps = synth.config3_layers("q8")
         vq_rows("config3 shape, 4 B/edge (q8 gain/bias)", [ps], synth.make_x(3900 + B, B, 2048, "uniform"), paths,
                 30 if B <= 256 else 10, prepared=prepared)
+    # compression side: assign every grid of a dense layer to its nearest codebook shape
+    for n_in, n_out, K in ((2048, 1024, 65536), (2048, 512, 65536), (1024, 256, 4096)):
+        coef_np, cb_np, _ = synth.make_dense_grids(7000 + K, n_in, n_out, K)
+        coef, cb = torch.from_numpy(coef_np).cuda(), torch.from_numpy(cb_np).cuda()
+        ws = torch.empty(kb.lib().kan_vq_assign_workspace_bytes(K), dtype=torch.uint8, device="cuda")
+        out = kb.kan_vq_assign(coef, cb, ws=ws)
+        reps = 3 if K > 10000 else 10
+        torch.cuda.synchronize()
+        t0 = time.perf_counter()
+        for _ in range(reps):
+            out = kb.kan_vq_assign(coef, cb, ws=ws)
+        torch.cuda.synchronize()
+        t = (time.perf_counter() - t0) / reps
+        E = n_in * n_out
+        print(json.dumps({"workload": f"assign {n_in}x{n_out} grids to K={K} shapes", "ms": round(t * 1e3, 3),
+                          "edges_per_s": E / t, "distances_per_s": E * K / t,
+                          "algorithmic_TFLOPs": E * K * 20 / t / 1e12, "issued_mfma_TFLOPs": E * K * 64 / t / 1e12,
+                          "r2": kb.kan_vq_reconstruction_r2(coef, cb, *out)}), flush=True)
+        del coef, cb
     heads_p, x = synth.config4(50, 64)
     vq_rows("config4 50 Int8 heads 2048->256->21", heads_p, x, both, 10)
     for variant in ("i8", "f32"):

@@ -186,7 +186,7 @@ kan_status kan_vq_count_bad_indices(const kan_vq_layer* L, uint32_t* count, void
  *   idx[e]  = index of the codebook row nearest (squared Euclidean distance) to the normalised
  *             grid; for an all-constant grid (gain 0) the row of smallest norm.
  * The distance contraction runs on the matrix cores with split fp16 operands (fp32-grade
- * scores); rows whose scores agree to ~2e-6 relative may resolve to either index.
+ * scores, ~1e-6 relative): rows that near to a tie may resolve to either index.
  * codebook: fp32 [K][10]; idx: KAN_U16 (K <= 65536) or KAN_U32 array [in][out]; gain, bias:
  * fp32 [in][out].  ws: kan_vq_assign_workspace_bytes(K) bytes, 256-byte aligned.  All device. */
 size_t kan_vq_assign_workspace_bytes(int32_t K);

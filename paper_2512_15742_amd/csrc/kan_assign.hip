@@ -13,12 +13,12 @@
 // the columns, so a lane owns one edge and 16 of the 32 centroids of a tile: the running
 // maximum over centroids never crosses lanes until the very end.
 //
-// The arg-max costs vector instructions per score, which is what bounds the kernel, so it is
-// kept to ~1.6 instructions per score: the row number (4 bits) replaces the four lowest
-// mantissa bits of each score (one v_and_or), the maximum of 16 tagged scores is 8 v_max3,
-// and only the tile number is tracked with a compare + select per tile.  Scores closer than
-// 2^-19 relative are therefore ordered by row, not by value, and exactly equal scores (duplicate
-// shapes) may resolve to either index.
+// The arg-max costs vector instructions per score, which is what would bound the kernel, so the
+// common case is kept to half an instruction per score: the maximum of a lane's 16 scores of a
+// tile is 8 three-input maxima, and only when it beats the lane's running best - the t-th tile
+// does so with probability ~1/t - is the row looked up.  Exactly equal scores (duplicate shapes)
+// resolve to the lower index within a half-wave's rows; which of two half-waves' equal scores
+// wins is decided by index at the end.
 
 #include "kan_device.hpp"
 #include "kan_internal.hpp"
@@ -85,7 +85,7 @@ struct AssignArgs {
 __device__ __forceinline__ float max3(float a, float b, float c) { return fmaxf(fmaxf(a, b), c); }
 
 template <typename IdxT>
-__global__ __launch_bounds__(kAssignThreads, 2) void kan_assign_kernel(const AssignArgs a) {
+__global__ __launch_bounds__(kAssignThreads, 4) void kan_assign_kernel(const AssignArgs a) {
   // edge-side operands of the workgroup's 512 edges: [edge][32 slots] fp16
   __shared__ __attribute__((aligned(16))) _Float16 sB[kEdgesPerWg * kSlots];
   const int tid = threadIdx.x, lane = tid & 63, wave = tid >> 6;
@@ -143,11 +143,12 @@ __global__ __launch_bounds__(kAssignThreads, 2) void kan_assign_kernel(const Ass
     }
 
   float best[kEdgeTilesPerWave];
-  int best_tile[kEdgeTilesPerWave];
+  int best_tile[kEdgeTilesPerWave], best_row[kEdgeTilesPerWave];
 #pragma unroll
   for (int nb = 0; nb < kEdgeTilesPerWave; ++nb) {
     best[nb] = -3.0e38f;
     best_tile[nb] = 0;
+    best_row[nb] = 0;
   }
 
   // ---- step 3: stream the centroid tiles (two tiles in flight) -----------------------------------
@@ -166,15 +167,22 @@ __global__ __launch_bounds__(kAssignThreads, 2) void kan_assign_kernel(const Ass
     for (int nb = 0; nb < kEdgeTilesPerWave; ++nb) {
       f32x16 acc = __builtin_amdgcn_mfma_f32_32x32x16_f16(a0, fb[nb][0], zero, 0, 0, 0);
       acc = __builtin_amdgcn_mfma_f32_32x32x16_f16(a1, fb[nb][1], acc, 0, 0, 0);
-      float s[16];
+      // maximum of the lane's 16 scores: 8 three-input maxima
+      const float m0 = max3(acc[0], acc[1], acc[2]), m1 = max3(acc[3], acc[4], acc[5]);
+      const float m2 = max3(acc[6], acc[7], acc[8]), m3 = max3(acc[9], acc[10], acc[11]);
+      const float m4 = max3(acc[12], acc[13], acc[14]);
+      const float m = max3(max3(m0, m1, m2), m3, max3(m4, acc[15], -3.0e38f));
+      // A new best is rare (the t-th tile improves a lane's running maximum with probability
+      // ~1/t), so the row is looked for only then.  Strictly greater: the earliest tile, and in
+      // it the lowest register, keeps a tie.
+      if (m > best[nb]) {
+        int r_best = 15;
 #pragma unroll
-      for (int r = 0; r < 16; ++r)       // row number into the four lowest mantissa bits
-        s[r] = __uint_as_float((__float_as_uint(acc[r]) & 0xfffffff0u) | (uint32_t)r);
-      const float m0 = max3(s[0], s[1], s[2]), m1 = max3(s[3], s[4], s[5]), m2 = max3(s[6], s[7], s[8]);
-      const float m3 = max3(s[9], s[10], s[11]), m4 = max3(s[12], s[13], s[14]);
-      const float m = max3(max3(m0, m1, m2), max3(m3, m4, s[15]), best[nb]);
-      best_tile[nb] = m > best[nb] ? t : best_tile[nb];     // strictly greater: the earliest tile keeps a tie
-      best[nb] = m;
+        for (int r = 14; r >= 0; --r) r_best = acc[r] == m ? r : r_best;
+        best[nb] = m;
+        best_tile[nb] = t;
+        best_row[nb] = r_best;
+      }
     }
   };
   uint4 fa0[2], fa1[2];
@@ -190,10 +198,10 @@ __global__ __launch_bounds__(kAssignThreads, 2) void kan_assign_kernel(const Ass
   // ---- the two half-waves hold different rows of the same edges: keep the better one ------------
 #pragma unroll
   for (int nb = 0; nb < kEdgeTilesPerWave; ++nb) {
-    const int r = (int)(__float_as_uint(best[nb]) & 15u);
+    const int r = best_row[nb];
     // D layout of the 32x32 MFMA: register r of a lane is row 8*(r/4) + 4*(lane/32) + r%4
     int id = best_tile[nb] * 32 + 8 * (r >> 2) + 4 * (lane >> 5) + (r & 3);
-    float sc = __uint_as_float(__float_as_uint(best[nb]) & 0xfffffff0u);
+    float sc = best[nb];
     const float sc_o = __shfl_xor(sc, 32, kWave);
     const int id_o = __shfl_xor(id, 32, kWave);
     if (sc_o > sc || (sc_o == sc && id_o < id)) id = id_o;
