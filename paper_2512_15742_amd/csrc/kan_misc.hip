@@ -51,6 +51,41 @@ __global__ __launch_bounds__(256) void kan_reduce_kernel(const float* __restrict
   }
 }
 
+// Large tensors: one thread adds four consecutive outputs over all chunks with 16-byte loads,
+// four chunks in flight (fixed order: chunks c, c+4, c+8, ... into accumulator c mod 4, then
+// (s0 + s1) + (s2 + s3)).
+__global__ __launch_bounds__(256) void kan_reduce_vec4_kernel(const float* __restrict__ partial,
+                                                              long long head_stride, long long chunk_stride,
+                                                              int n_chunks, float* __restrict__ dst,
+                                                              long long dst_head_stride, long long count4,
+                                                              int apply_tanh) {
+  typedef float f32x4 __attribute__((ext_vector_type(4)));
+  const int head = blockIdx.y;
+  const f32x4* p = (const f32x4*)(partial + (long long)head * head_stride);
+  f32x4* d = (f32x4*)(dst + (long long)head * dst_head_stride);
+  const long long cs4 = chunk_stride / 4;
+  for (long long n = (long long)blockIdx.x * blockDim.x + threadIdx.x; n < count4;
+       n += (long long)gridDim.x * blockDim.x) {
+    f32x4 s0 = {0.f, 0.f, 0.f, 0.f}, s1 = s0, s2 = s0, s3 = s0;
+    int c = 0;
+    for (; c + 3 < n_chunks; c += 4) {
+      s0 += __builtin_nontemporal_load(p + (long long)c * cs4 + n);
+      s1 += __builtin_nontemporal_load(p + (long long)(c + 1) * cs4 + n);
+      s2 += __builtin_nontemporal_load(p + (long long)(c + 2) * cs4 + n);
+      s3 += __builtin_nontemporal_load(p + (long long)(c + 3) * cs4 + n);
+    }
+    for (; c < n_chunks; ++c) s0 += __builtin_nontemporal_load(p + (long long)c * cs4 + n);
+    f32x4 v = (s0 + s1) + (s2 + s3);
+    if (apply_tanh) {
+      v.x = tanhf(v.x);
+      v.y = tanhf(v.y);
+      v.z = tanhf(v.z);
+      v.w = tanhf(v.w);
+    }
+    d[n] = v;
+  }
+}
+
 __global__ __launch_bounds__(256) void kan_basis_kernel(const float* __restrict__ x, long long n,
                                                         uint8_t* __restrict__ span, float* __restrict__ w) {
   for (long long t = (long long)blockIdx.x * blockDim.x + threadIdx.x; t < n;
@@ -115,8 +150,18 @@ inline int blocks_for(long long n, int cap = 65536) {
 hipError_t launch_reduce(const float* partial, long long head_stride, long long chunk_stride, int n_chunks,
                          float* dst, long long dst_head_stride, long long count, int n_heads,
                          int apply_tanh, hipStream_t s) {
-  // few outputs and many chunks: spread the chunks of one output over several threads
   const long long total = count * n_heads;
+  // large tensors whose rows are 16-byte aligned: vector loads, one thread per four outputs
+  if (total >= (1 << 18) && count % 4 == 0 && head_stride % 4 == 0 && chunk_stride % 4 == 0 &&
+      dst_head_stride % 4 == 0 && ((uintptr_t)partial % 16) == 0 && ((uintptr_t)dst % 16) == 0) {
+    const long long count4 = count / 4;
+    long long blocks = (count4 + 255) / 256;
+    if (blocks > 8192) blocks = 8192;
+    hipLaunchKernelGGL(kan_reduce_vec4_kernel, dim3((unsigned)blocks, n_heads), dim3(256), 0, s, partial, head_stride,
+                       chunk_stride, n_chunks, dst, dst_head_stride, count4, apply_tanh);
+    return hipGetLastError();
+  }
+  // few outputs and many chunks: spread the chunks of one output over several threads
   const int cg = (n_chunks >= 32 && total <= (1 << 16)) ? 16 : ((n_chunks >= 8 && total <= (1 << 20)) ? 4 : 1);
   const int npb = 256 / cg;
   long long blocks = (count + npb - 1) / npb;
