@@ -51,6 +51,10 @@ constexpr int BN = 256;                // outputs per workgroup tile (samples pe
 constexpr int IT = 8;                  // input rows per step (80 k-slots = 5 MFMA k-steps)
 constexpr int LDK = 88;                // LDS row stride in halves (176 B = 11 x 16 B)
 constexpr int NB = 2;                  // MFMA column blocks per wave (64 outputs)
+constexpr int kBufferFlags = 0x00020000;   // buffer resource word 3: raw 32-bit data format, no swizzle
+
+typedef unsigned int u32x4 __attribute__((ext_vector_type(4)));
+typedef unsigned int u32x2 __attribute__((ext_vector_type(2)));
 
 // ---- kan_prep_coef ------------------------------------------------------------------
 // Chat as uint4 records: rec[((step*5 + ks) * 2 + h) * n_out + j], step = i / 8, so that
@@ -182,7 +186,6 @@ __global__ __launch_bounds__(kMfmaThreads, 2) void kan_mfma_kernel(const MfmaArg
 
   // Phi generation: this thread owns sample row pb and inputs NPAIR*ph .. NPAIR*ph+NPAIR-1 of every step.
   const int pb = tid & (BM - 1), ph = tid / BM;
-  const uint2* wcol = W + min(b0 + pb, B - 1);
   // B operand: columns jc[nb]
   int jc[NB];
   bool j_ok[NB];
@@ -201,10 +204,23 @@ __global__ __launch_bounds__(kMfmaThreads, 2) void kan_mfma_kernel(const MfmaArg
 #pragma unroll
       for (int r = 0; r < 16; ++r) acc[m][n][r] = 0.f;
 
+  // Every load of the main loop is a buffer load: the resource (base, size) is rebuilt on the
+  // scalar unit for each step, the lane offsets never change, so a load costs no vector
+  // arithmetic.  Offsets stay below 2^31 because a resource spans one step of one head.
+  static_assert(BM % 64 == 0, "a wave generates the Phi rows of one input group");
+  const int ph_u = __builtin_amdgcn_readfirstlane(ph);
+  const uint32_t u_off = (uint32_t)min(b0 + pb, B - 1) * (uint32_t)sizeof(uint2);
+  const char* w_bytes = (const char*)W;
+  const uint32_t w_row_bytes = (uint32_t)B * (uint32_t)sizeof(uint2);
   auto load_u = [&](int k, uint2 (&uv)[NPAIR]) {       // step index relative to the chunk
-    const int i = i_begin + k * IT + NPAIR * ph;
+    const int i = i_begin + k * IT + NPAIR * ph_u;
 #pragma unroll
-    for (int q = 0; q < NPAIR; ++q) uv[q] = wcol[(long long)min(i + q, n_in - 1) * B];
+    for (int q = 0; q < NPAIR; ++q) {
+      const char* row = w_bytes + (size_t)min(i + q, n_in - 1) * w_row_bytes;
+      const __amdgpu_buffer_rsrc_t r = __builtin_amdgcn_make_buffer_rsrc((void*)row, 0, (int)w_row_bytes, kBufferFlags);
+      const u32x2 v = __builtin_amdgcn_raw_buffer_load_b64(r, (int)u_off, 0, 0);
+      uv[q] = make_uint2(v.x, v.y);
+    }
   };
 
   auto gen_phi = [&](const uint2 (&uv)[NPAIR], uint16_t* tile) {
@@ -227,12 +243,22 @@ __global__ __launch_bounds__(kMfmaThreads, 2) void kan_mfma_kernel(const MfmaArg
     }
   };
 
+  uint32_t b_off[NB];
+#pragma unroll
+  for (int nb = 0; nb < NB; ++nb) b_off[nb] = (uint32_t)(lh * n_out + jc[nb]) * (uint32_t)sizeof(uint4);
+  const char* cf_bytes = (const char*)cf;
+  const uint32_t ks_bytes = 2u * (uint32_t)n_out * (uint32_t)sizeof(uint4);
   auto load_b = [&](int k, uint4 (&bf)[NB][5]) {
-    const long long step = min(step0 + k, last_step);     // past the end: valid memory, never used
+    const int step = min(step0 + k, last_step);           // past the end: valid memory, never used
+    const char* sb = cf_bytes + (size_t)step * (5 * ks_bytes);
+    const __amdgpu_buffer_rsrc_t r = __builtin_amdgcn_make_buffer_rsrc((void*)sb, 0, (int)(5 * ks_bytes), kBufferFlags);
 #pragma unroll
     for (int ks = 0; ks < 5; ++ks)
 #pragma unroll
-      for (int nb = 0; nb < NB; ++nb) bf[nb][ks] = cf[((step * 5 + ks) * 2 + lh) * n_out + jc[nb]];
+      for (int nb = 0; nb < NB; ++nb) {
+        const u32x4 v = __builtin_amdgcn_raw_buffer_load_b128(r, (int)b_off[nb], (int)(ks * ks_bytes), 0);
+        bf[nb][ks] = make_uint4(v.x, v.y, v.z, v.w);
+      }
   };
 
   auto mfma_step = [&](const uint16_t* tile, const uint4 (&bf)[NB][5]) {
@@ -257,6 +283,16 @@ __global__ __launch_bounds__(kMfmaThreads, 2) void kan_mfma_kernel(const MfmaArg
   // steps k+1, k+2 are in flight.  Step k issues those of step k+3 into the slot step k
   // frees, so every load has two full steps to arrive; the second workgroup on the CU
   // covers the rest.
+  // The bias sums of the tile's columns are fetched ahead of everything else (thread t owns
+  // column j0 + t) and parked in LDS until the epilogue, so their latency is never exposed.
+  static_assert(BN == kMfmaThreads, "one bias column per thread");
+  __shared__ float sBias[BN];
+  const float* bp = a.bias_partial + (long long)head * a.bp_head_stride + min(j0 + tid, n_out - 1);
+  const int rb0 = i_begin / kMfmaPrepRows, rb1 = (i_end + kMfmaPrepRows - 1) / kMfmaPrepRows;
+  float bias_v[8];
+#pragma unroll
+  for (int u = 0; u < 8; ++u) bias_v[u] = bp[(long long)min(rb0 + u, rb1 - 1) * n_out];
+
   uint4 bfr[3][NB][5];
   uint2 uv[3][NPAIR];
   load_u(0, uv[0]);
@@ -265,6 +301,13 @@ __global__ __launch_bounds__(kMfmaThreads, 2) void kan_mfma_kernel(const MfmaArg
   load_b(1, bfr[1]);
   load_u(2, uv[2]);
   load_b(2, bfr[2]);
+  {
+    float bs = 0.f;
+#pragma unroll
+    for (int u = 0; u < 8; ++u) bs += rb0 + u < rb1 ? bias_v[u] : 0.f;
+    for (int rb = rb0 + 8; rb < rb1; ++rb) bs += bp[(long long)rb * n_out];
+    sBias[tid] = bs;      // read after the barriers of the main loop
+  }
   gen_phi(uv[0], sA[0]);
 
   auto step = [&](auto T, int k) {
@@ -275,25 +318,30 @@ __global__ __launch_bounds__(kMfmaThreads, 2) void kan_mfma_kernel(const MfmaArg
     load_b(k + 3, bfr[t % 3]);                     // fragments of step k have been consumed
     load_u(k + 3, uv[t % 3]);                      // basis words of step k were consumed a step ago
   };
-  for (int k = 0; k < n_steps; k += 6) {
+  // Whole groups of six steps run without a branch between them: a branch around a step makes
+  // the compiler lose count of the loads in flight and wait for all of them.
+  int k = 0;
+  for (; k + 6 <= n_steps; k += 6) {
     step(std::integral_constant<int, 0>{}, k);
-    if (k + 1 < n_steps) step(std::integral_constant<int, 1>{}, k + 1);
-    if (k + 2 < n_steps) step(std::integral_constant<int, 2>{}, k + 2);
-    if (k + 3 < n_steps) step(std::integral_constant<int, 3>{}, k + 3);
-    if (k + 4 < n_steps) step(std::integral_constant<int, 4>{}, k + 4);
-    if (k + 5 < n_steps) step(std::integral_constant<int, 5>{}, k + 5);
+    step(std::integral_constant<int, 1>{}, k + 1);
+    step(std::integral_constant<int, 2>{}, k + 2);
+    step(std::integral_constant<int, 3>{}, k + 3);
+    step(std::integral_constant<int, 4>{}, k + 4);
+    step(std::integral_constant<int, 5>{}, k + 5);
   }
+  if (k < n_steps) step(std::integral_constant<int, 0>{}, k);
+  if (k + 1 < n_steps) step(std::integral_constant<int, 1>{}, k + 1);
+  if (k + 2 < n_steps) step(std::integral_constant<int, 2>{}, k + 2);
+  if (k + 3 < n_steps) step(std::integral_constant<int, 3>{}, k + 3);
+  if (k + 4 < n_steps) step(std::integral_constant<int, 4>{}, k + 4);
 
   // ---- epilogue.  D layout of the 32x32 MFMA: lane holds column (lane & 31), rows
   //      8*(r/4) + 4*(lane/32) + r%4 for r = 0..15 -------------------------------------------
-  const float* bp = a.bias_partial + (long long)head * a.bp_head_stride;
-  const int rb0 = i_begin / kMfmaPrepRows, rb1 = (i_end + kMfmaPrepRows - 1) / kMfmaPrepRows;
   const float scale = a.scale[head];
   float* dst = a.dst + (long long)head * a.dst_head_stride + (long long)chunk * a.dst_chunk_stride;
 #pragma unroll
   for (int n = 0; n < NB; ++n) {
-    float bs = 0.f;
-    for (int rb = rb0; rb < rb1; ++rb) bs += bp[(long long)rb * n_out + jc[n]];
+    const float bs = sBias[wn * 64 + n * 32 + ln];
     if (j_ok[n]) {
 #pragma unroll
       for (int m = 0; m < MB; ++m)
@@ -346,6 +394,10 @@ hipError_t launch_prep_basis(const float* x, long long x_head_stride, uint2* W, 
 
 hipError_t launch_mfma(const MfmaArgs& a, int tile_m, dim3 grid, hipStream_t s) {
   if (tile_m != 64) return hipErrorInvalidValue;
+  // one step of coefficient records and one row of basis words must fit a buffer resource
+  if ((long long)a.n_out * 10 * (long long)sizeof(uint4) > 0x7fffffffLL ||
+      (long long)a.B * (long long)sizeof(uint2) > 0x7fffffffLL)
+    return hipErrorInvalidValue;
   hipLaunchKernelGGL(kan_mfma_kernel<2>, grid, dim3(kMfmaThreads), 0, s, a);
   return hipGetLastError();
 }
