@@ -315,8 +315,12 @@ struct WsPtrs {
 // One layer of a group of heads.  `a` carries x, shapes and the per-head pointers;
 // `final_dst` receives act(y).  Gather path: main kernel, then (if i was split) the
 // fixed-order reduction.  Matrix-core path: coefficient and basis preparation first.
-// How a bucket layer receives its input and hands on its output when it is chained to its
-// neighbours: the per-bucket sums of layer l are added (and squashed) by layer l+1 itself.
+// How a layer receives its input and hands on its output when it is chained to its
+// neighbours: the partial sums of layer l (per bucket, or per chunk of inputs) are added and
+// squashed by layer l+1 itself: by the bucket kernel while it loads x, or by the basis
+// preparation of the matrix-core path.
+constexpr int kMaxChainedSlices = 16;   // more slices than this go through the reduction pass (more loads in flight per output)
+
 struct Chain {
   int in_parts = 1;              // slices of the input to add (1: plain x)
   long long in_part_stride = 0;
@@ -350,7 +354,8 @@ kan_status run_layer_group(const LayerPlan& p, GatherArgs& a, const void* const*
     if (st != KAN_OK) return st;
     const long long u_stride = x_shared ? 0 : (long long)a.n_in * a.B;
     st = run("kan_prep_basis", s, [&] {
-      return launch_prep_basis(a.x, a.x_head_stride, w.u, u_stride, a.n_in, a.B, x_shared ? 1 : heads, a.rule, s);
+      return launch_prep_basis(a.x, a.x_head_stride, chain.in_parts, chain.in_part_stride, chain.in_tanh, w.u,
+                               u_stride, a.n_in, a.B, x_shared ? 1 : heads, a.rule, s);
     });
     if (st != KAN_OK) return st;
     MfmaArgs m;
@@ -446,11 +451,13 @@ kan_status check_path(int32_t path) {
   return KAN_ERR_UNSUPPORTED;
 }
 
-// Layer l leaves its per-bucket sums to layer l+1 (one group of heads only: the buffers are
-// sized for one group).
+// Layer l leaves its partial sums to layer l+1 (one group of heads only: the buffers are
+// sized for one group).  Consumers: the bucket kernel (after a bucket layer) and the basis
+// preparation of the matrix-core path (after any layer that splits its inputs).
 bool chained(const std::vector<LayerPlan>& plans, int l, int n_heads) {
-  return l >= 0 && l + 1 < (int)plans.size() && n_heads <= kMaxGroup && plans[l].kind == kPlanBucket &&
-         plans[l + 1].kind == kPlanBucket && plans[l].n_chunks > 1;
+  if (l < 0 || l + 1 >= (int)plans.size() || n_heads > kMaxGroup || plans[l].n_chunks <= 1) return false;
+  if (plans[l + 1].kind == kPlanBucket) return plans[l].kind == kPlanBucket;
+  return plans[l + 1].kind == kPlanMfma && plans[l].n_chunks <= kMaxChainedSlices;
 }
 
 // Validates a [n_heads][n_layers] descriptor table; fills per-layer plans and scratch sizes.
@@ -495,7 +502,7 @@ kan_status plan_head(const kan_vq_layer* layers, int32_t n_layers, int32_t n_hea
       grow(ws->u, round_up((size_t)(l == 0 ? 1 : group) * (size_t)R.in * (size_t)B * sizeof(uint2), 256));
     if (l + 1 < n_layers) grow(ws->hidden, round_up((size_t)n_heads * (size_t)B * R.out * sizeof(float), 256));
   }
-  // consecutive bucket layers hand their per-bucket sums straight on: two buffers, used in turn
+  // chained layers hand their partial sums straight on: two buffers, used in turn
   for (int l = 0; l + 1 < n_layers; ++l)
     if (chained(*plans, l, n_heads)) ws->partial2 = ws->partial;
   return KAN_OK;

@@ -82,8 +82,11 @@ struct MfmaArgs {
 };
 
 hipError_t launch_prep_coef(const GatherCfg&, const PrepCoefArgs&, int heads, hipStream_t);
-hipError_t launch_prep_basis(const float* x, long long x_head_stride, uint2* W, long long w_head_stride,
-                             int n_in, int B, int heads, int rule, hipStream_t);
+// The input of the layer is x, or act(sum of x_parts slices of x) when the previous layer left
+// its partial sums (slices x_part_stride elements apart).
+hipError_t launch_prep_basis(const float* x, long long x_head_stride, int x_parts, long long x_part_stride,
+                             int x_tanh, uint2* W, long long w_head_stride, int n_in, int B, int heads, int rule,
+                             hipStream_t);
 hipError_t launch_mfma(const MfmaArgs&, int tile_m, dim3 grid, hipStream_t);   // tile_m: samples per tile (64)
 
 // ---- fused gather + matrix-core kernel (batch tiles of 32 or 64 samples) --------------

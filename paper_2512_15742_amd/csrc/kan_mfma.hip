@@ -122,7 +122,10 @@ __global__ __launch_bounds__(kThreads) void kan_prep_coef_kernel(const PrepCoefA
 // ---- kan_prep_basis -----------------------------------------------------------------
 // W[i][b] = { half2(w0, w1), half2(w2, w3) } with span bit 0, 1, 2 in the sign bits of
 // w0, w1, w2 (the weights are never negative).
+// The input is x itself, or (x_parts > 1) the previous layer's partial sums, added here in
+// the order of the slices and squashed, so that no separate reduction pass runs in between.
 __global__ __launch_bounds__(256) void kan_prep_basis_kernel(const float* __restrict__ x, long long x_head_stride,
+                                                             int x_parts, long long x_part_stride, int x_tanh,
                                                              uint2* __restrict__ W, long long w_head_stride,
                                                              int n_in, int B, int rule) {
   __shared__ uint2 tile[32][33];
@@ -136,7 +139,17 @@ __global__ __launch_bounds__(256) void kan_prep_basis_kernel(const float* __rest
     const int b = bb + ty + 8 * r, i = ib + tx;
     uint2 v = make_uint2(0u, 0u);
     if (b < B && i < n_in) {
-      const BasisW bw = basis_fast(xh[(long long)b * n_in + i], rule);
+      const float* xp = xh + (long long)b * n_in + i;
+      float xv = xp[0];
+      for (int p0 = 1; p0 < x_parts; p0 += 8) {       // eight slices in flight, added in order
+        float t[8];
+#pragma unroll
+        for (int pp = 0; pp < 8; ++pp) t[pp] = xp[(long long)min(p0 + pp, x_parts - 1) * x_part_stride];
+#pragma unroll
+        for (int pp = 0; pp < 8; ++pp) xv += p0 + pp < x_parts ? t[pp] : 0.f;
+      }
+      if (x_tanh) xv = tanhf(xv);
+      const BasisW bw = basis_fast(xv, rule);
       const uint32_t l = (uint32_t)bw.span;
       const float w0 = bw.w0, w1 = bw.w1, w2 = bw.w2, w3 = bw.w3;
       v.x = pack_h2(w0, w1) | ((l & 1u) << 15) | ((l & 2u) << 30);
@@ -385,10 +398,13 @@ hipError_t launch_prep_coef(const GatherCfg& c, const PrepCoefArgs& a, int heads
   return c.idx_u32 ? prep_types<uint32_t>(c, a, grid, s) : prep_types<uint16_t>(c, a, grid, s);
 }
 
-hipError_t launch_prep_basis(const float* x, long long x_head_stride, uint2* W, long long w_head_stride,
-                             int n_in, int B, int heads, int rule, hipStream_t s) {
+hipError_t launch_prep_basis(const float* x, long long x_head_stride, int x_parts, long long x_part_stride,
+                             int x_tanh, uint2* W, long long w_head_stride, int n_in, int B, int heads, int rule,
+                             hipStream_t s) {
+  if (x_parts < 1) return hipErrorInvalidValue;
   dim3 grid((n_in + 31) / 32, (B + 31) / 32, heads);
-  hipLaunchKernelGGL(kan_prep_basis_kernel, grid, dim3(256), 0, s, x, x_head_stride, W, w_head_stride, n_in, B, rule);
+  hipLaunchKernelGGL(kan_prep_basis_kernel, grid, dim3(256), 0, s, x, x_head_stride, x_parts, x_part_stride, x_tanh,
+                     W, w_head_stride, n_in, B, rule);
   return hipGetLastError();
 }
 

@@ -109,3 +109,21 @@ def test_mfma_deterministic(kb):
     y1 = kb.kan_vq_head_forward([Ls], xd, path=kb.KAN_PATH_MFMA).clone()
     y2 = kb.kan_vq_head_forward([Ls], xd, path=kb.KAN_PATH_MFMA)
     assert torch.equal(y1, y2)
+
+
+@pytest.mark.parametrize("B,n_heads", [(150, 1), (40, 3), (700, 2)])
+def test_mfma_three_layer_head_hand_over(kb, B, n_heads):
+    """Hidden activations between matrix-core layers: layers that split their inputs into few
+    chunks leave the partial sums to the next layer's basis preparation (which adds and
+    squashes them), layers with many chunks go through the reduction pass; ragged sizes."""
+    dims = [(520, 264), (264, 130), (130, 21)]
+    heads_p = [[synth.make_layer(100 * h + 7 * l + 1, i, o, 1000, cb_dtype="i8", gb_dtype="f16")
+                for l, (i, o) in enumerate(dims)] for h in range(n_heads)]
+    x = synth.make_x(B + n_heads, B, dims[0][0])
+    heads = [gpu_layers(ps) for ps in heads_p]
+    y = kb.kan_vq_head_forward(heads, to_dev(x), path=kb.KAN_PATH_MFMA).cpu().numpy()
+    assert y.shape == (n_heads, B, 21) and np.isfinite(y).all()
+    for h in range(n_heads):
+        y_ref = ko.vq_head_forward(x, [p.as_dict() for p in heads_p[h]])
+        rep = ko.error_report(y[h], y_ref)
+        assert rep["headline"] <= TOL_MFMA, (h, rep)
