@@ -6,8 +6,9 @@
  *     c_ij   = gain_ij * C[idx_ij] + bias_ij          reconstructed coefficients
  *     phi_ij = sum_m B_{m,3}(x_i) * c_ij[m]            cubic B-spline, G = 10
  *     y_j    = sum_i phi_ij(x_i)
- * with one K x G codebook C per layer (fp32, or Int8 with value = scale * q,
- * the one-byte-per-coefficient codebook of sections 4.3 / 5.4), splines on the
+ * with one K x G codebook C per layer (fp32, fp16, or Int8 with value = scale * q:
+ * the three codebook precisions of Table 1; Int8 is the one-byte-per-coefficient
+ * codebook of sections 4.3 / 5.4), splines on the
  * range [-1, 1] (App. A.1): 7 uniform intervals, 14 knots t_m = -1 + (m-3)*2/7.
  * Inputs are clamped to [-1, 1].  x = +1 belongs to the last interval.
  *
@@ -25,6 +26,8 @@
  *   - Layouts: x[B][in] and y[B][out] row-major fp32; per-edge arrays
  *     idx/gain/bias[in][out] with edge e = i*out + j (j fastest); codebook
  *     [K][10] row-major, unpadded; dense coefficients coef[in][out][10].
+ *   - Every array is aligned to its element size; fp32 codebooks to 8 bytes and fp16
+ *     codebooks to 4 bytes (rows are read in pairs of entries); else KAN_ERR_SHAPE.
  *   - idx values must be < K; they are not checked by the forward calls (use
  *     kan_vq_count_bad_indices).  y must not alias x or the workspace.
  */
@@ -85,12 +88,13 @@ typedef struct kan_vq_layer {
   int32_t K;             /* codebook entries, >= 1; <= 65536 when idx is KAN_U16    */
   int32_t idx_dtype;     /* KAN_U16 | KAN_U32                                       */
   int32_t gb_dtype;      /* KAN_F32 | KAN_F16 | KAN_Q8 (gain and bias share it)     */
-  int32_t cb_dtype;      /* KAN_F32 | KAN_I8                                        */
+  int32_t cb_dtype;      /* KAN_F32 | KAN_F16 | KAN_I8                              */
   const void* idx;       /* [in][out]                                               */
   const void* gain;      /* [in][out]                                               */
   const void* bias;      /* [in][out]                                               */
   const void* codebook;  /* [K][10]                                                 */
-  float scale;           /* Int8: value = scale * q.  Ignored for KAN_F32 codebooks */
+  float scale;           /* Int8: value = scale * q.  Ignored for KAN_F32 and KAN_F16
+                            codebooks (Table 1 lists FP32, FP16 and Int8 codebooks)  */
   int32_t rule;          /* KAN_RULE_BSPLINE3 (0) | KAN_RULE_PLI2                   */
   const void* prepared;  /* NULL, or the buffer kan_vq_prepare filled for this very
                             layer (small-batch path, see below)                     */
@@ -146,10 +150,12 @@ kan_status kan_dense_layer_forward(const float* coef, int32_t in, int32_t out, i
  * serves batches up to 4 from this layout: every workgroup copies one bucket into LDS and
  * streams that bucket's edges, so no lookup leaves the CU.  Values are unchanged (same
  * products, different summation order: within the 1e-5 bound).
- *   kan_vq_prepared_bytes  size of the buffer; 0 if the layer is not eligible (in > 4096),
- *                          (size_t)-1 if the descriptor is invalid.  L->prepared is ignored.
+ *   kan_vq_prepared_bytes  size of the buffer; 0 if the layer is not eligible (in > 4096, or
+ *                          an fp16 codebook), (size_t)-1 if the descriptor is invalid.
+ *                          L->prepared is ignored.
  *   kan_vq_prepare         fills `prepared` (device, 256-byte aligned, >= that size) on
- *                          `stream`.  Requires in <= 4096 (else KAN_ERR_UNSUPPORTED).  The
+ *                          `stream`.  Requires in <= 4096 and an fp32 or Int8 codebook
+ *                          (else KAN_ERR_UNSUPPORTED).  The
  *                          buffer depends on idx, gain, bias (not on the codebook values or
  *                          scale) and must be rebuilt when they change.  The caller owns it
  *                          and stores its address in L->prepared for later forward calls;

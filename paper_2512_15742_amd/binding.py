@@ -151,7 +151,8 @@ class VQLayer:
             self.n_in, self.n_out, 10, 3, self.K,
             KAN_U16 if idx.dtype == np.uint16 else KAN_U32,
             gb,
-            KAN_I8 if params.codebook.dtype == np.int8 else KAN_F32,
+            {np.dtype(np.int8): KAN_I8, np.dtype(np.float16): KAN_F16,
+             np.dtype(np.float32): KAN_F32}[params.codebook.dtype],
             self.idx.data_ptr(), self.gain.data_ptr(), self.bias.data_ptr(), self.codebook.data_ptr(),
             self.scale, int(rule), None, gbp[0], gbp[1], gbp[2], 0)
         self.prepared = None

@@ -49,6 +49,10 @@ int gb_kind_of(const kan_vq_layer& L) {
   return L.gb_dtype == KAN_F32 ? kGbF32 : (L.gb_dtype == KAN_F16 ? kGbF16 : kGbQ8);
 }
 
+int code_of(const kan_vq_layer& L) {
+  return L.cb_dtype == KAN_I8 ? kCbI8 : (L.cb_dtype == KAN_F16 ? kCbF16 : kCbF32);
+}
+
 kan_status validate_layer(const kan_vq_layer* L) {
   if (!L) return KAN_ERR_NULL;
   if (L->G != 10 || L->degree != 3) return KAN_ERR_UNSUPPORTED;
@@ -56,7 +60,7 @@ kan_status validate_layer(const kan_vq_layer* L) {
   if (L->in < 1 || L->out < 1 || L->in > kMaxDim || L->out > kMaxDim || L->K < 1) return KAN_ERR_SHAPE;
   if (L->idx_dtype != KAN_U16 && L->idx_dtype != KAN_U32) return KAN_ERR_DTYPE;
   if (L->gb_dtype != KAN_F32 && L->gb_dtype != KAN_F16 && L->gb_dtype != KAN_Q8) return KAN_ERR_DTYPE;
-  if (L->cb_dtype != KAN_F32 && L->cb_dtype != KAN_I8) return KAN_ERR_DTYPE;
+  if (L->cb_dtype != KAN_F32 && L->cb_dtype != KAN_F16 && L->cb_dtype != KAN_I8) return KAN_ERR_DTYPE;
   if (L->idx_dtype == KAN_U16 && L->K > 65536) return KAN_ERR_SHAPE;
   // byte-coded gain/bias belong to the fully quantised format: one-byte codebook entries too
   if (L->gb_dtype == KAN_Q8 && L->cb_dtype != KAN_I8) return KAN_ERR_UNSUPPORTED;
@@ -64,7 +68,7 @@ kan_status validate_layer(const kan_vq_layer* L) {
   const size_t idx_sz = L->idx_dtype == KAN_U16 ? 2 : 4;
   const size_t gb_sz = L->gb_dtype == KAN_F32 ? 4 : (L->gb_dtype == KAN_F16 ? 2 : 1);
   if (!aligned(L->idx, idx_sz) || !aligned(L->gain, gb_sz) || !aligned(L->bias, gb_sz)) return KAN_ERR_SHAPE;
-  if (!aligned(L->codebook, L->cb_dtype == KAN_F32 ? 8 : 2)) return KAN_ERR_SHAPE;
+  if (!aligned(L->codebook, L->cb_dtype == KAN_F32 ? 8 : (L->cb_dtype == KAN_F16 ? 4 : 2))) return KAN_ERR_SHAPE;
   return KAN_OK;
 }
 
@@ -241,7 +245,7 @@ LayerPlan plan_bucket(const kan_vq_layer& L, int64_t B, int n_heads) {
 
 bool layer_prepared_ok(const kan_vq_layer& L) {
   return L.prepared != nullptr && aligned(L.prepared, 256) && aligned(L.codebook, 16) && L.in <= kBucketMaxIn &&
-         (long long)L.in * L.out <= (1ll << 31);
+         (long long)L.in * L.out <= (1ll << 31) && L.cb_dtype != KAN_F16;     // buckets hold fp32 or Int8 rows
 }
 
 // Which kernels serve a layer:
@@ -253,7 +257,7 @@ bool layer_prepared_ok(const kan_vq_layer& L) {
 //     kernel with fp16 operands, above that coefficient/basis preparation + the streaming
 //     contraction.
 LayerPlan plan_vq(const kan_vq_layer& L, int64_t B, int n_heads, bool vec_ok, bool prepared_ok, int32_t path) {
-  const int code = L.cb_dtype == KAN_I8 ? kCbI8 : kCbF32;
+  const int code = code_of(L);
   const int u32 = L.idx_dtype == KAN_U32, gbk = gb_kind_of(L);
   const bool half_path = path == KAN_PATH_MFMA || (path == KAN_PATH_AUTO && B >= kAutoMfmaBatch);
   if (half_path) {
@@ -610,7 +614,7 @@ kan_status kan_vq_head_forward(const kan_vq_layer* layers, int32_t n_layers, int
       a.B = (int)B;
       a.rows_per_chunk = plans[l].rows_per_chunk;
       a.n_jt = plans[l].n_jt;
-      a.cb_bytes = (long long)R.K * 10 * (R.cb_dtype == KAN_I8 ? 1 : 4);
+      a.cb_bytes = (long long)R.K * cb_row_bytes(code_of(R));
       a.rule = R.rule;
       for (int h = 0; h < heads; ++h) {
         const kan_vq_layer& L = layers[(size_t)(h0 + h) * n_layers + l];
@@ -673,7 +677,7 @@ kan_status kan_dense_layer_forward(const float* coef, int32_t in, int32_t out, i
 
 size_t kan_vq_prepared_bytes(const kan_vq_layer* L) {
   if (validate_layer(L) != KAN_OK) return (size_t)-1;
-  if (L->in > kBucketMaxIn || (long long)L->in * L->out > (1ll << 31)) return 0;
+  if (L->in > kBucketMaxIn || (long long)L->in * L->out > (1ll << 31) || L->cb_dtype == KAN_F16) return 0;
   return bucket_geometry(L->in, L->out, L->K, L->cb_dtype == KAN_I8, gb_kind_of(*L)).total;
 }
 
@@ -681,6 +685,7 @@ kan_status kan_vq_prepare(const kan_vq_layer* L, void* prepared, size_t prepared
   kan_status st = validate_layer(L);
   if (st != KAN_OK) return st;
   if (L->in > kBucketMaxIn) return KAN_ERR_UNSUPPORTED;
+  if (L->cb_dtype == KAN_F16) return KAN_ERR_UNSUPPORTED;                      // buckets hold fp32 or Int8 rows
   if ((long long)L->in * L->out > (1ll << 31)) return KAN_ERR_UNSUPPORTED;   // 32-bit segment offsets
   const BucketGeom g = bucket_geometry(L->in, L->out, L->K, L->cb_dtype == KAN_I8, gb_kind_of(*L));
   if (!prepared || !aligned(prepared, 256) || prepared_bytes < g.total) return KAN_ERR_WORKSPACE;
@@ -751,7 +756,7 @@ kan_status kan_vq_debug_gather(const kan_vq_layer* L, uint32_t* ids, float* rows
   LayerPtrs h = {L->idx, L->gain, L->bias, L->codebook, L->scale, 0.f, 0.f, 0.f};
   hipStream_t s = (hipStream_t)stream;
   return run("kan_debug_gather", s, [&] {
-    return launch_debug_gather(h, L->idx_dtype == KAN_U32, L->cb_dtype == KAN_I8,
+    return launch_debug_gather(h, L->idx_dtype == KAN_U32, code_of(*L),
                                (long long)L->in * L->out, ids, rows, s);
   });
 }

@@ -198,6 +198,10 @@ __device__ __forceinline__ void load_bias(const T* p, const Q8Params& qp, float 
 
 // ---- codeword rows -------------------------------------------------------------
 
+__device__ __forceinline__ float half_bits_to_float(uint32_t bits) {
+  return (float)__builtin_bit_cast(_Float16, (uint16_t)bits);
+}
+
 __device__ __forceinline__ uint32_t ld_u32_any(const uint8_t* p) {
   uint32_t v;
   __builtin_memcpy(&v, p, 4);
@@ -233,6 +237,14 @@ __device__ __forceinline__ void fetch_row(const CbT* cb, uint32_t id, float mul,
     dequant4(d, mul, off, t);
     c[8] = t[0];
     c[9] = t[1];
+  } else if constexpr (sizeof(CbT) == 2) {
+    const uint32_t* p = (const uint32_t*)((const uint16_t*)cb + (size_t)id * kG);   // fp16 rows, 4-byte aligned
+#pragma unroll
+    for (int m = 0; m < kG / 2; ++m) {
+      const uint32_t v = p[m];
+      c[2 * m] = mul * half_bits_to_float(v & 0xffffu);
+      c[2 * m + 1] = mul * half_bits_to_float(v >> 16);
+    }
   } else {
     const float2* p = (const float2*)(cb + (size_t)id * kG);       // 8-byte aligned
 #pragma unroll
@@ -249,12 +261,17 @@ __device__ __forceinline__ void fetch_row(const CbT* cb, uint32_t id, float mul,
 // are separate so that many gathers can be issued before the first one is used.
 template <typename CbT> struct WindowRaw;
 template <> struct WindowRaw<int8_t> { typedef uint32_t type; };
+template <> struct WindowRaw<__half> { typedef uint2 type; };
 template <> struct WindowRaw<float> { typedef float4 type; };
 
 template <typename CbT>
 __device__ __forceinline__ typename WindowRaw<CbT>::type load_window(const CbT* cb, uint32_t id, int span) {
   if constexpr (sizeof(CbT) == 1) {
     return ld_u32_any((const uint8_t*)cb + (size_t)id * kG + span);
+  } else if constexpr (sizeof(CbT) == 2) {
+    uint2 v;                                                       // four halves, 2-byte aligned
+    __builtin_memcpy(&v, (const uint16_t*)cb + (size_t)id * kG + span, 8);
+    return v;
   } else {
     float4 v;
     __builtin_memcpy(&v, cb + (size_t)id * kG + span, 16);
@@ -266,6 +283,11 @@ template <typename CbT>
 __device__ __forceinline__ void dequant_window(typename WindowRaw<CbT>::type raw, float mul, float (&c)[4]) {
   if constexpr (sizeof(CbT) == 1) {
     dequant4(raw, mul, -128.0f * mul, c);
+  } else if constexpr (sizeof(CbT) == 2) {
+    c[0] = mul * half_bits_to_float(raw.x & 0xffffu);
+    c[1] = mul * half_bits_to_float(raw.x >> 16);
+    c[2] = mul * half_bits_to_float(raw.y & 0xffffu);
+    c[3] = mul * half_bits_to_float(raw.y >> 16);
   } else {
     c[0] = mul * raw.x;
     c[1] = mul * raw.y;

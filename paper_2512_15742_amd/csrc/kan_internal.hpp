@@ -20,7 +20,8 @@ struct LayerPtrs {
   float gain_log2_lo, gain_log2_step, bias_scale;   // byte-coded gain/bias only
 };
 
-enum CodeKind : int { kCbF32 = 0, kCbI8 = 1, kDense = 2 };
+enum CodeKind : int { kCbF32 = 0, kCbI8 = 1, kDense = 2, kCbF16 = 3 };
+constexpr int cb_row_bytes(int code) { return code == kCbI8 ? 10 : (code == kCbF16 ? 20 : 40); }
 enum GbKind : int { kGbF32 = 0, kGbF16 = 1, kGbQ8 = 2 };     // fp32, fp16, one byte each (log gain, linear bias)
 constexpr int gb_bytes(int kind) { return kind == kGbF32 ? 4 : (kind == kGbF16 ? 2 : 1); }
 
@@ -194,7 +195,7 @@ hipError_t launch_reduce(const float* partial, long long head_stride, long long 
 // ---- debug / parity kernels -------------------------------------------------------
 hipError_t launch_basis(const float* x, long long n, uint8_t* span, float* w, hipStream_t);
 hipError_t launch_pli_basis(const float* x, long long n, uint8_t* index, float* w, hipStream_t);
-hipError_t launch_debug_gather(const LayerPtrs&, int idx_u32, int cb_i8, long long edges,
+hipError_t launch_debug_gather(const LayerPtrs&, int idx_u32, int code, long long edges,
                                uint32_t* ids, float* rows, hipStream_t);
 hipError_t launch_count_bad(const void* idx, int idx_u32, long long edges, uint32_t K,
                             uint32_t* count, hipStream_t);

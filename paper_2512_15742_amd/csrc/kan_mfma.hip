@@ -382,7 +382,12 @@ hipError_t prep_types(const GatherCfg& c, const PrepCoefArgs& a, dim3 grid, hipS
       hipLaunchKernelGGL((kan_prep_coef_kernel<IdxT, float, int8_t>), grid, dim3(kThreads), 0, s, a);
   } else {
     if (c.gb_kind == kGbQ8) return hipErrorInvalidValue;    // byte-coded gain/bias go with Int8 codebooks
-    if (c.gb_kind == kGbF16)
+    if (c.code == kCbF16) {
+      if (c.gb_kind == kGbF16)
+        hipLaunchKernelGGL((kan_prep_coef_kernel<IdxT, __half, __half>), grid, dim3(kThreads), 0, s, a);
+      else
+        hipLaunchKernelGGL((kan_prep_coef_kernel<IdxT, float, __half>), grid, dim3(kThreads), 0, s, a);
+    } else if (c.gb_kind == kGbF16)
       hipLaunchKernelGGL((kan_prep_coef_kernel<IdxT, __half, float>), grid, dim3(kThreads), 0, s, a);
     else
       hipLaunchKernelGGL((kan_prep_coef_kernel<IdxT, float, float>), grid, dim3(kThreads), 0, s, a);

@@ -30,6 +30,7 @@ __device__ __forceinline__ uint32_t dq_pair(uint32_t w, h16x2 g2) {
 // Raw codeword of one edge as loaded from the codebook.
 template <typename CbT> struct RawRow;
 template <> struct RawRow<int8_t> { uint32_t a, b, d; };
+template <> struct RawRow<__half> { uint32_t w[kG / 2]; };
 template <> struct RawRow<float> { float c[kG]; };
 
 template <typename CbT>
@@ -39,6 +40,10 @@ __device__ __forceinline__ void load_row(const CbT* cb, uint32_t id, RawRow<CbT>
     r.a = ld_u32_any(p);
     r.b = ld_u32_any(p + 4);
     r.d = ld_u16_any(p + 8);
+  } else if constexpr (sizeof(CbT) == 2) {
+    const uint32_t* p = (const uint32_t*)((const uint16_t*)cb + (size_t)id * kG);   // 4-byte aligned
+#pragma unroll
+    for (int m = 0; m < kG / 2; ++m) r.w[m] = p[m];
   } else {
     const float2* p = (const float2*)(cb + (size_t)id * kG);
 #pragma unroll
@@ -62,6 +67,10 @@ __device__ __forceinline__ void dequant_row(const RawRow<CbT>& r, float g, uint3
     w[2] = dq_pair<0>(b, g2);
     w[3] = dq_pair<2>(b, g2);
     w[4] = dq_pair<0>(d, g2);
+  } else if constexpr (sizeof(CbT) == 2) {
+#pragma unroll
+    for (int m = 0; m < 5; ++m)
+      w[m] = pack_h2(g * half_bits_to_float(r.w[m] & 0xffffu), g * half_bits_to_float(r.w[m] >> 16));
   } else {
 #pragma unroll
     for (int m = 0; m < 5; ++m) w[m] = pack_h2(g * r.c[2 * m], g * r.c[2 * m + 1]);
@@ -79,6 +88,12 @@ __device__ __forceinline__ void dequant_row_f32(const RawRow<CbT>& r, float g, f
     dequant4(r.d, g, off, t);
     c[8] = t[0];
     c[9] = t[1];
+  } else if constexpr (sizeof(CbT) == 2) {
+#pragma unroll
+    for (int m = 0; m < kG / 2; ++m) {
+      c[2 * m] = g * half_bits_to_float(r.w[m] & 0xffffu);
+      c[2 * m + 1] = g * half_bits_to_float(r.w[m] >> 16);
+    }
   } else {
 #pragma unroll
     for (int m = 0; m < kG; ++m) c[m] = g * r.c[m];

@@ -189,25 +189,29 @@ hipError_t launch_pli_basis(const float* x, long long n, uint8_t* index, float* 
   return hipGetLastError();
 }
 
-hipError_t launch_debug_gather(const LayerPtrs& h, int idx_u32, int cb_i8, long long edges, uint32_t* ids,
+template <typename IdxT>
+void debug_gather_types(const LayerPtrs& h, int code, long long edges, uint32_t* ids, float* rows, dim3 grid,
+                        hipStream_t s) {
+  const dim3 block(256);
+  if (code == kCbI8)
+    hipLaunchKernelGGL((kan_debug_gather_kernel<IdxT, int8_t>), grid, block, 0, s, (const IdxT*)h.idx,
+                       (const int8_t*)h.cb, h.scale, edges, ids, rows);
+  else if (code == kCbF16)
+    hipLaunchKernelGGL((kan_debug_gather_kernel<IdxT, __half>), grid, block, 0, s, (const IdxT*)h.idx,
+                       (const __half*)h.cb, 1.0f, edges, ids, rows);
+  else
+    hipLaunchKernelGGL((kan_debug_gather_kernel<IdxT, float>), grid, block, 0, s, (const IdxT*)h.idx,
+                       (const float*)h.cb, 1.0f, edges, ids, rows);
+}
+
+hipError_t launch_debug_gather(const LayerPtrs& h, int idx_u32, int code, long long edges, uint32_t* ids,
                                float* rows, hipStream_t s) {
-  dim3 grid(blocks_for(edges)), block(256);
-  const float scale = cb_i8 ? h.scale : 1.0f;
-  if (idx_u32) {
-    if (cb_i8)
-      hipLaunchKernelGGL((kan_debug_gather_kernel<uint32_t, int8_t>), grid, block, 0, s,
-                         (const uint32_t*)h.idx, (const int8_t*)h.cb, scale, edges, ids, rows);
-    else
-      hipLaunchKernelGGL((kan_debug_gather_kernel<uint32_t, float>), grid, block, 0, s,
-                         (const uint32_t*)h.idx, (const float*)h.cb, scale, edges, ids, rows);
-  } else {
-    if (cb_i8)
-      hipLaunchKernelGGL((kan_debug_gather_kernel<uint16_t, int8_t>), grid, block, 0, s,
-                         (const uint16_t*)h.idx, (const int8_t*)h.cb, scale, edges, ids, rows);
-    else
-      hipLaunchKernelGGL((kan_debug_gather_kernel<uint16_t, float>), grid, block, 0, s,
-                         (const uint16_t*)h.idx, (const float*)h.cb, scale, edges, ids, rows);
-  }
+  if (code != kCbI8 && code != kCbF16 && code != kCbF32) return hipErrorInvalidValue;
+  const dim3 grid(blocks_for(edges));
+  if (idx_u32)
+    debug_gather_types<uint32_t>(h, code, edges, ids, rows, grid, s);
+  else
+    debug_gather_types<uint16_t>(h, code, edges, ids, rows, grid, s);
   return hipGetLastError();
 }
 

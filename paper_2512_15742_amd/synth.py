@@ -28,7 +28,7 @@ class VQLayerParams:
     n_in: int
     n_out: int
     K: int
-    codebook: np.ndarray      # [K][10] float32 or int8
+    codebook: np.ndarray      # [K][10] float32, float16 or int8
     scale: np.float32         # Int8: value = scale * q; 1.0 for float codebooks
     idx: np.ndarray           # [in][out] uint16 or uint32
     gain: np.ndarray          # [in][out] float32 or float16, or uint8 codes (byte-coded format)
@@ -97,6 +97,8 @@ def make_layer(seed: int, n_in: int, n_out: int, K: int, *, cb_dtype="f32",
         codebook, scale = quantise_shapes(shapes)
     elif cb_dtype == "f32":
         codebook, scale = shapes, np.float32(1.0)
+    elif cb_dtype == "f16":
+        codebook, scale = shapes.astype(np.float16), np.float32(1.0)
     else:
         raise ValueError(cb_dtype)
     if idx_dtype is None:

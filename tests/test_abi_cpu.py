@@ -66,7 +66,9 @@ FAKE = C.c_void_p(0x10000)
     (dict(idx_dtype=kb.KAN_F32), kb.KAN_ERR_DTYPE),
     (dict(gb_dtype=kb.KAN_I8), kb.KAN_ERR_DTYPE),
     (dict(gb_dtype=kb.KAN_Q8), kb.KAN_ERR_UNSUPPORTED),       # byte-coded gain/bias need an Int8 codebook
-    (dict(cb_dtype=kb.KAN_F16), kb.KAN_ERR_DTYPE),
+    (dict(cb_dtype=kb.KAN_U16), kb.KAN_ERR_DTYPE),
+    (dict(cb_dtype=kb.KAN_F16, codebook=0x4002), kb.KAN_ERR_SHAPE),   # fp16 rows are read in pairs: 4-byte alignment
+    (dict(cb_dtype=kb.KAN_F16, gb_dtype=kb.KAN_Q8), kb.KAN_ERR_UNSUPPORTED),
     (dict(idx=0), kb.KAN_ERR_NULL),
     (dict(codebook=0), kb.KAN_ERR_NULL),
     (dict(gain=0x2001), kb.KAN_ERR_SHAPE),                   # misaligned fp32
@@ -153,6 +155,19 @@ def test_byte_coded_layers_plan_and_prepare():
     need = L.kan_vq_prepared_bytes(C.byref(d))
     E = 2048 * 1024
     assert 5 * E < need < 5 * E + (1 << 16)              # u16 input + u16 local id + 1-byte gain code
+
+
+def test_fp16_codebook_layers_plan_but_do_not_prepare():
+    L = kb.lib()
+    d = _desc(n_in=2048, n_out=1024, K=65536, cb_dtype=kb.KAN_F16, gb_dtype=kb.KAN_F16, codebook=0x4004)
+    for B, path, name in ((1, kb.KAN_PATH_GATHER, b"kan_gather_bt1"), (16, kb.KAN_PATH_GATHER, b"kan_fused_f32"),
+                          (16, kb.KAN_PATH_MFMA, b"kan_fused_f16"), (1024, kb.KAN_PATH_AUTO, b"kan_mfma")):
+        assert L.kan_vq_planned_kernel(C.byref(d), B, 1, path) == name
+        assert L.kan_vq_workspace_bytes(C.byref(d), 1, 1, B, path) != kb.SIZE_INVALID
+    assert L.kan_vq_prepared_bytes(C.byref(d)) == 0
+    assert L.kan_vq_prepare(C.byref(d), FAKE, 1 << 30, None) == kb.KAN_ERR_UNSUPPORTED
+    d.prepared = 0x100000                                # a buffer made for another layer is not used
+    assert L.kan_vq_planned_kernel(C.byref(d), 1, 1, kb.KAN_PATH_GATHER) == b"kan_gather_bt1"
 
 
 def test_assign_argument_errors():

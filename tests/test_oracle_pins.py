@@ -282,6 +282,28 @@ def test_int8_equals_fp32_twin():
     assert np.array_equal(y_f, y_g)
 
 
+def test_fp16_codebook_equals_its_fp32_twin():
+    """An fp16 codebook (Table 1) holds numbers that fp32 and float64 represent exactly: the
+    layer equals, bit for bit, the one built from the converted rows, whatever scale says,
+    and differs from the unrounded fp32 codebook by at most half an fp16 ulp per entry."""
+    P = synth.make_layer(31, 6, 5, 40, cb_dtype="f16", gb_dtype="f16")
+    assert P.codebook.dtype == np.float16 and float(P.scale) == 1.0
+    x = synth.make_x(4, 7, 6)
+    y_h = ko.vq_layer_forward(x, **P.as_dict())
+    y_t = ko.vq_layer_forward(x, P.codebook.astype(np.float32), 77.0, P.idx, P.gain, P.bias)
+    assert np.array_equal(y_h, y_t)
+    y_s = np.array(ko.vq_layer_forward_scalar(x.tolist(), P.codebook.tolist(), 1.0, P.idx.tolist(),
+                                              P.gain.astype(np.float64).tolist(), P.bias.astype(np.float64).tolist()))
+    np.testing.assert_allclose(y_h, y_s, atol=1e-14)
+    F = synth.make_layer(31, 6, 5, 40, cb_dtype="f32", gb_dtype="f16")      # same draws, unrounded rows
+    assert np.array_equal(F.idx, P.idx) and np.array_equal(F.gain, P.gain)
+    err = np.abs(F.codebook.astype(np.float64) - P.codebook.astype(np.float64))
+    assert 0 < err.max() <= 2.0 ** -12                   # |entries| < 1: half an ulp of fp16 is at most 2^-12
+    y_f = ko.vq_layer_forward(x, **F.as_dict())
+    bound = 2.0 ** -12 * np.abs(P.gain.astype(np.float64)).sum(axis=0)      # the basis weights sum to 1
+    assert (np.abs(y_f - y_h) <= bound[None, :] + 1e-15).all()
+
+
 # ---- heads ---------------------------------------------------------------------
 
 def test_head_is_layers_with_tanh_between():
