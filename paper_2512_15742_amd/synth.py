@@ -89,8 +89,26 @@ def encode_gain_bias_q8(gain: np.ndarray, bias: np.ndarray):
     return qg, qb, (lo, step, bscale)
 
 
+def draw_idx(rng: np.random.Generator, K: int, shape, dist: str = "uniform", zipf_s: float = 1.0) -> np.ndarray:
+    """Codeword of every edge, int64.  'uniform': every codeword equally likely (the worst case
+    for gather locality; the draw the configurations name).  'zipf': a trained-like skewed
+    histogram, P(rank r) ~ 1 / r**zipf_s, the ranks scattered over the codebook by a random
+    permutation.  'zipf-sorted': the same histogram with the popular codewords at the low ids
+    (what a compiler that orders the codebook by use would emit)."""
+    if dist == "uniform":
+        return rng.integers(0, K, size=shape, dtype=np.int64)
+    if dist not in ("zipf", "zipf-sorted"):
+        raise ValueError(dist)
+    p = 1.0 / np.arange(1, K + 1, dtype=np.float64) ** zipf_s
+    p /= p.sum()
+    ranks = rng.choice(K, size=shape, p=p)
+    if dist == "zipf-sorted":
+        return ranks.astype(np.int64)
+    return rng.permutation(K)[ranks].astype(np.int64)
+
+
 def make_layer(seed: int, n_in: int, n_out: int, K: int, *, cb_dtype="f32",
-               gb_dtype="f32", idx_dtype=None) -> VQLayerParams:
+               gb_dtype="f32", idx_dtype=None, idx_dist="uniform", zipf_s=1.0) -> VQLayerParams:
     rng = np.random.default_rng(seed)
     shapes = make_shapes(rng, K)
     if cb_dtype == "i8":
@@ -106,7 +124,7 @@ def make_layer(seed: int, n_in: int, n_out: int, K: int, *, cb_dtype="f32",
     np_idx = {"u16": np.uint16, "u32": np.uint32}[idx_dtype]
     if idx_dtype == "u16" and K > 65536:
         raise ValueError("K does not fit a 16-bit index")
-    idx = rng.integers(0, K, size=(n_in, n_out), dtype=np.int64).astype(np_idx)
+    idx = draw_idx(rng, K, (n_in, n_out), idx_dist, zipf_s).astype(np_idx)
     np_gb = {"f32": np.float32, "f16": np.float16, "q8": np.float64}[gb_dtype]
     gain = np.abs(rng.normal(0.0, 0.1, size=(n_in, n_out))).astype(np_gb)
     bias = rng.normal(0.0, 0.01, size=(n_in, n_out)).astype(np_gb)
@@ -157,12 +175,14 @@ def config2(B: int):
     return [make_layer(2000, 2048, 512, 65536)], make_x(2900 + B, B, 2048, "normal")
 
 
-def config3_layers(gb_dtype: str = "f16"):
+def config3_layers(gb_dtype: str = "f16", cb_dtype: str = "i8", idx_dist: str = "uniform"):
     """Two-layer Int8 head 2048 -> 1024 -> 256, fp16 gain/bias, K = 65,536 each.
     gb_dtype="q8": the same draws with gain and bias encoded in one byte each (the
-    4-bytes-per-edge format of the paper, section 4.2)."""
-    return [make_layer(3000, 2048, 1024, 65536, cb_dtype="i8", gb_dtype=gb_dtype),
-            make_layer(3001, 1024, 256, 65536, cb_dtype="i8", gb_dtype=gb_dtype)]
+    4-bytes-per-edge format of the paper, section 4.2).  cb_dtype and idx_dist vary the
+    codebook precision and the assignment histogram on the same shapes (studies, not the
+    configuration itself)."""
+    return [make_layer(3000, 2048, 1024, 65536, cb_dtype=cb_dtype, gb_dtype=gb_dtype, idx_dist=idx_dist),
+            make_layer(3001, 1024, 256, 65536, cb_dtype=cb_dtype, gb_dtype=gb_dtype, idx_dist=idx_dist)]
 
 
 def config3(B: int):
