@@ -82,7 +82,7 @@ struct LayerPlan {
   GatherCfg cfg;
   int n_jt, n_bt, n_chunks, rows_per_chunk;
   int kind;          // PlanKind
-  int parts = 0, jw = 0;   // bucket path: workgroups per bucket, outputs per workgroup
+  int parts = 0, jw = 0;   // bucket path: blocks (workgroups per sample and head) of the launch; jw unused
   bool mfma;         // kind == kPlanMfma (coefficient + basis preparation, streaming contraction)
   const char* name;
 };
@@ -212,9 +212,9 @@ LayerPlan plan_fused(int n_in, int n_out, int64_t B, int n_heads, int idx_u32, i
 }
 
 // Bucket path (prepared layers): one workgroup per (bucket, slice of the outputs, sample).
-// A workgroup occupies a whole CU (LDS), so the slices are cut to give every CU one.
+// A workgroup occupies a whole CU (LDS), so the slices are cut to give every CU one: the
+// cuts come from the block table that the preparation made for this many (samples x heads).
 constexpr int64_t kBucketMaxBatch = 4;
-constexpr int kBucketWorkgroups = 256;
 
 LayerPlan plan_bucket(const kan_vq_layer& L, int64_t B, int n_heads) {
   LayerPlan p;
@@ -228,14 +228,8 @@ LayerPlan plan_bucket(const kan_vq_layer& L, int64_t B, int n_heads) {
   p.cfg.gb_kind = gb_kind_of(L);
   p.cfg.code = L.cb_dtype == KAN_I8 ? kCbI8 : kCbF32;
   const BucketGeom g = bucket_geometry(L.in, L.out, L.K, L.cb_dtype == KAN_I8, gb_kind_of(L));
-  const long long base = (long long)g.n_buckets * B * n_heads;
-  long long parts = kBucketWorkgroups / base;     // rounded down: one round of workgroups, no tail
-  const long long min_parts = (L.out + kBucketMaxJw - 1) / kBucketMaxJw;
-  if (parts < min_parts) parts = min_parts;
-  if (parts > L.out) parts = L.out;
-  if (parts < 1) parts = 1;
-  p.jw = (int)((L.out + parts - 1) / parts);
-  p.parts = (L.out + p.jw - 1) / p.jw;
+  p.parts = g.tab_w[bucket_table_for((long long)B * n_heads)];      // blocks of the table this launch uses
+  p.jw = 0;
   p.n_jt = p.parts;
   p.n_bt = (int)B;
   p.n_chunks = g.n_buckets;          // the per-bucket sums are the partial sums
@@ -399,7 +393,8 @@ kan_status run_layer_group(const LayerPlan& p, GatherArgs& a, const void* const*
     k.n_out = a.n_out;
     k.B = a.B;
     k.n_buckets = g.n_buckets;
-    k.jw = p.jw;
+    const int table = bucket_table_for((long long)a.B * heads);     // by the heads of this very launch
+    k.off_blk = (long long)(g.off_blk + (size_t)g.tab_first[table] * kBucketEntryWords * 4);
     k.rows_shift = g.rows_shift;
     k.cb_bytes = a.cb_bytes;
     k.apply_tanh = tanh_in_kernel;
@@ -416,7 +411,7 @@ kan_status run_layer_group(const LayerPlan& p, GatherArgs& a, const void* const*
       k.h[h].gain_log2_lo = a.h[h].gain_log2_lo;
       k.h[h].gain_log2_step = a.h[h].gain_log2_step;
     }
-    st = run(p.name, s, [&] { return launch_bucket(i8, p.cfg.gb_kind, k, p.parts, heads, s); });
+    st = run(p.name, s, [&] { return launch_bucket(i8, p.cfg.gb_kind, k, g.tab_w[table], heads, s); });
   } else if (p.kind == kPlanFused16 || p.kind == kPlanFused32) {
     const bool f32 = p.kind == kPlanFused32;
     FusedArgs f;

@@ -91,9 +91,14 @@ __global__ __launch_bounds__(kBucketThreads) void kan_bucket_kernel(const Bucket
   const int tid = threadIdx.x, lane = tid & (kWave - 1);
   const int wave = __builtin_amdgcn_readfirstlane(tid >> 6);
   const int head = blockIdx.z, b = blockIdx.y;
-  const int bucket = blockIdx.x % a.n_buckets, part = blockIdx.x / a.n_buckets;
   const BucketHead H = a.h[head];
   const char* prep = (const char*)H.prepared;
+  // the block of this workgroup: outputs [j0, j1) of one bucket, edges [blk_lo, blk_hi)
+  const uint32_t* __restrict__ ent = (const uint32_t*)(prep + a.off_blk) + (size_t)blockIdx.x * kBucketEntryWords;
+  const int bucket = (int)ent[0];
+  const int j0 = (int)ent[1], j1 = (int)ent[2];
+  const uint32_t blk_lo = ent[3], blk_hi = ent[4];
+  const int njw = j1 - j0;
   const uint32_t* __restrict__ seg = (const uint32_t*)(prep + a.off_seg) + (size_t)bucket * a.n_out;
   const uint16_t* __restrict__ pi = (const uint16_t*)(prep + a.off_i);
   const uint16_t* __restrict__ pq = (const uint16_t*)(prep + a.off_q);
@@ -101,11 +106,6 @@ __global__ __launch_bounds__(kBucketThreads) void kan_bucket_kernel(const Bucket
   constexpr int kGainBytes = gb_bytes(GK);
   const Q8Params qp = {H.gain_log2_lo, H.gain_log2_step, 0.f};
 
-  const int j0 = part * a.jw;
-  const int j1 = min(j0 + a.jw, a.n_out);
-  const int njw = j1 - j0;
-  // the block of this workgroup: edges [blk_lo, blk_hi)
-  const uint32_t blk_lo = seg[j0], blk_hi = seg[j1];
 
   // Loads are issued in the order their data is needed (they return in order): the inputs
   // of the sample, the codebook bucket, the segment table; then, after the basis table has
@@ -148,8 +148,7 @@ __global__ __launch_bounds__(kBucketThreads) void kan_bucket_kernel(const Bucket
   const char* cb_src = (const char*)H.cb + cb_start;
   const int n16 = cb_nbytes >> 4;
   const int cb_tail = cb_nbytes & 15;
-  const int n_parts = gridDim.x / a.n_buckets;
-  const int rot = (int)((long long)part * n16 / n_parts);
+  const int rot = (int)((long long)blockIdx.x * n16 / gridDim.x);
   // a bucket shorter than 16 bytes, or without tail bytes: the (unused) load goes to the
   // prepared buffer, which always has that many bytes
   const u32x4* cb_src16 = n16 > 0 ? (const u32x4*)cb_src : (const u32x4*)prep;
@@ -385,6 +384,61 @@ __global__ __launch_bounds__(256) void kan_prepare_fill_kernel(const IdxT* __res
   if (bucket == 0) bias_sum[j] = (float)bs;
 }
 
+// Blocks per bucket for a table of W blocks (prefix sums -> cnt[0 .. n_buckets]): every bucket
+// gets min_blocks, the rest goes in proportion to the edges (cumulative rounding).
+__global__ void kan_prepare_block_counts_kernel(const uint32_t* __restrict__ seg, int n_out, int n_buckets,
+                                                int min_blocks, int W, uint32_t* __restrict__ cnt) {
+  if (blockIdx.x != 0 || threadIdx.x != 0) return;
+  const unsigned long long E = seg[(size_t)n_buckets * n_out];
+  const unsigned long long spare = (unsigned long long)(W - (long long)n_buckets * min_blocks);
+  unsigned long long given = 0;
+  uint32_t run = 0;
+  cnt[0] = 0;
+  for (int b = 0; b < n_buckets; ++b) {
+    const unsigned long long upto = seg[(size_t)(b + 1) * n_out];          // edges of buckets 0..b
+    const unsigned long long target = E > 0 ? (spare * upto + E / 2) / E : 0;
+    run += (uint32_t)min_blocks + (uint32_t)(target - given);
+    given = target;
+    cnt[b + 1] = run;
+  }
+}
+
+// The entries of one bucket (thread = bucket): its outputs are cut into its blocks so that
+// the blocks hold about equal numbers of edges, never more than kBucketMaxJw outputs each
+// (the cuts are made one after the other so that the limit holds for every block).
+__global__ __launch_bounds__(256) void kan_prepare_blocks_kernel(const uint32_t* __restrict__ seg, int n_out,
+                                                                 int n_buckets, const uint32_t* __restrict__ cnt,
+                                                                 uint32_t* __restrict__ table) {
+  const int b = blockIdx.x * blockDim.x + threadIdx.x;
+  if (b >= n_buckets) return;
+  const int first = (int)cnt[b], nb = (int)(cnt[b + 1] - cnt[b]);
+  const uint32_t* sb = seg + (size_t)b * n_out;     // sb[0 .. n_out] are valid (the prefix runs on)
+  const unsigned long long e0 = sb[0], eb = sb[n_out] - sb[0];
+  int j0 = 0;
+  for (int q = 0; q < nb; ++q) {
+    int j1 = n_out;
+    if (q + 1 < nb) {
+      const unsigned long long target = e0 + eb * (unsigned long long)(q + 1) / (unsigned long long)nb;
+      int a = 0, c = n_out;                          // smallest j with sb[j] >= target
+      while (a < c) {
+        const int mid = (a + c) >> 1;
+        if (sb[mid] >= target) c = mid; else a = mid + 1;
+      }
+      const int lo_c = max(j0, n_out - (nb - q - 1) * kBucketMaxJw);   // the blocks after this one can take the rest
+      const int hi_c = min(j0 + kBucketMaxJw, n_out);
+      j1 = min(max(a, lo_c), hi_c);
+    }
+    uint32_t* e = table + (size_t)(first + q) * kBucketEntryWords;
+    e[0] = (uint32_t)b;
+    e[1] = (uint32_t)j0;
+    e[2] = (uint32_t)j1;
+    e[3] = sb[j0];
+    e[4] = sb[j1];
+    e[5] = e[6] = e[7] = 0u;
+    j0 = j1;
+  }
+}
+
 template <typename IdxT, typename GbT>
 hipError_t prepare_typed(const LayerPtrs& h, int n_in, int n_out, const BucketGeom& g, void* prepared,
                          hipStream_t s) {
@@ -398,6 +452,15 @@ hipError_t prepare_typed(const LayerPtrs& h, int n_in, int n_out, const BucketGe
                      (const GbT*)h.gain, (const GbT*)h.bias, n_in, n_out, g.rows_shift, (const uint32_t*)seg,
                      (uint16_t*)(p + g.off_i), (uint16_t*)(p + g.off_q), (GbT*)(p + g.off_g),
                      (float*)(p + g.off_bias), Q8Params{h.gain_log2_lo, h.gain_log2_step, h.bias_scale});
+  const int min_blocks = (n_out + kBucketMaxJw - 1) / kBucketMaxJw;
+  for (int t = 0; t < kBucketTables; ++t) {
+    uint32_t* cnt = (uint32_t*)(p + g.off_cnt) + (size_t)t * (g.n_buckets + 1);
+    uint32_t* table = (uint32_t*)(p + g.off_blk) + (size_t)g.tab_first[t] * kBucketEntryWords;
+    hipLaunchKernelGGL(kan_prepare_block_counts_kernel, dim3(1), dim3(64), 0, s, (const uint32_t*)seg, n_out,
+                       g.n_buckets, min_blocks, g.tab_w[t], cnt);
+    hipLaunchKernelGGL(kan_prepare_blocks_kernel, dim3((unsigned)((g.n_buckets + 255) / 256)), dim3(256), 0, s,
+                       (const uint32_t*)seg, n_out, g.n_buckets, (const uint32_t*)cnt, table);
+  }
   return hipGetLastError();
 }
 
@@ -415,12 +478,10 @@ hipError_t launch_bucket_prepare(const LayerPtrs& h, int idx_u32, int gb_kind, i
   return prepare_typed<uint16_t, float>(h, n_in, n_out, g, prepared, s);
 }
 
-hipError_t launch_bucket(bool cb_i8, int gb_kind, const BucketArgs& a, int parts, int heads, hipStream_t s) {
-  if (a.n_in > kBucketMaxIn || a.n_buckets < 1 || parts < 1 || a.jw < 1 || a.jw > kBucketMaxJw ||
-      (long long)parts * a.jw < a.n_out)
-    return hipErrorInvalidValue;
+hipError_t launch_bucket(bool cb_i8, int gb_kind, const BucketArgs& a, int blocks, int heads, hipStream_t s) {
+  if (a.n_in > kBucketMaxIn || a.n_buckets < 1 || blocks < a.n_buckets) return hipErrorInvalidValue;
   if (gb_kind == kGbQ8 && !cb_i8) return hipErrorInvalidValue;      // byte-coded gains go with Int8 codebooks
-  dim3 grid((unsigned)(parts * a.n_buckets), (unsigned)a.B, (unsigned)heads);
+  dim3 grid((unsigned)blocks, (unsigned)a.B, (unsigned)heads);
   dim3 block(kBucketThreads);
   const bool wide = a.n_in > 2048;
 #define KAN_LAUNCH_BUCKET(GK, I8)                                                                      \

@@ -121,6 +121,16 @@ constexpr int kBucketMaxJw = 1024;      // outputs per workgroup (their sums are
 // inputs, half of that for wider layers (whose basis table takes twice the LDS).
 constexpr int bucket_bytes(int n_in) { return n_in > 2048 ? 40960 : 81920; }
 
+// Workgroups of a launch are laid out by block tables made at preparation time: a block is a
+// run of outputs of one bucket, and the outputs of a bucket are cut so that the blocks of a
+// table hold about the same number of edges whatever the histogram of the codewords is (a
+// bucket gets blocks in proportion to its edges, at least ceil(n_out / kBucketMaxJw), so an
+// empty bucket still writes its zeros).  Table t < 4 serves (samples x heads) = t + 1 with
+// about 256 / (t + 1) blocks, table 4 every larger product with the fewest blocks allowed.
+constexpr int kBucketWorkgroups = 256;  // one workgroup of 1024 threads per CU
+constexpr int kBucketTables = 5;
+constexpr int kBucketEntryWords = 8;    // {bucket, first output, end output, first edge, end edge, 0, 0, 0}
+
 struct BucketGeom {
   int rows_shift;      // log2(codewords per bucket)
   int n_buckets;
@@ -129,8 +139,16 @@ struct BucketGeom {
   size_t off_i;        // uint16 [E]                     input index
   size_t off_q;        // uint16 [E]                     codeword id - first id of the bucket
   size_t off_g;        // gain   [E]                     in the layer's gain dtype
+  size_t off_blk;      // uint32 [sum of tab_w][8]       block tables, one after the other
+  size_t off_cnt;      // uint32 [kBucketTables][n_buckets + 1]  blocks per bucket (prefix sums), scratch of the preparation
+  int tab_w[kBucketTables];        // blocks of every table
+  int tab_first[kBucketTables];    // first entry of every table
   size_t total;
 };
+
+inline int bucket_table_for(long long samples_times_heads) {
+  return samples_times_heads <= 4 ? (int)(samples_times_heads < 1 ? 1 : samples_times_heads) - 1 : kBucketTables - 1;
+}
 
 inline BucketGeom bucket_geometry(int n_in, int n_out, int K, bool cb_i8, int gb_kind) {
   // 32 bytes of slack after every array: threads load aligned groups of eight records
@@ -144,7 +162,18 @@ inline BucketGeom bucket_geometry(int n_in, int n_out, int K, bool cb_i8, int gb
   g.off_i = g.off_bias + up((size_t)n_out * 4);
   g.off_q = g.off_i + up(E * 2);
   g.off_g = g.off_q + up(E * 2);
-  g.total = g.off_g + up(E * gb_bytes(gb_kind));
+  g.off_blk = g.off_g + up(E * gb_bytes(gb_kind));
+  const long long w_min = (long long)g.n_buckets * ((n_out + kBucketMaxJw - 1) / kBucketMaxJw);
+  long long entries = 0;
+  for (int t = 0; t < kBucketTables; ++t) {
+    long long w = t + 1 < kBucketTables ? kBucketWorkgroups / (t + 1) : w_min;
+    if (w < w_min) w = w_min;
+    g.tab_w[t] = (int)w;
+    g.tab_first[t] = (int)entries;
+    entries += w;
+  }
+  g.off_cnt = g.off_blk + up((size_t)entries * kBucketEntryWords * 4);
+  g.total = g.off_cnt + up((size_t)kBucketTables * ((size_t)g.n_buckets + 1) * 4);
   return g;
 }
 
@@ -164,16 +193,17 @@ struct BucketArgs {
   float* dst;                  // final values (one bucket) or per-bucket partial sums
   long long dst_head_stride, dst_chunk_stride;
   int n_in, n_out, B;
-  int n_buckets, jw;           // jw: outputs per workgroup; blockIdx.x = part * n_buckets + bucket
+  int n_buckets;               // blockIdx.x = entry of the block table at off_blk
   int rows_shift;
   long long cb_bytes;          // whole codebook, bytes
   int apply_tanh;              // honoured only when n_buckets == 1
   int rule;                    // edge function: 0 cubic B-spline, 1 two-tap linear interpolation
   long long off_seg, off_bias, off_i, off_q, off_g;
+  long long off_blk;           // byte offset of the block table this launch uses
   BucketHead h[kMaxGroup];
 };
 
-hipError_t launch_bucket(bool cb_i8, int gb_kind, const BucketArgs&, int parts, int heads, hipStream_t);
+hipError_t launch_bucket(bool cb_i8, int gb_kind, const BucketArgs&, int blocks, int heads, hipStream_t);
 // One-time regrouping of a layer into the layout above (three kernels: count, scan, fill).
 hipError_t launch_bucket_prepare(const LayerPtrs&, int idx_u32, int gb_kind, int n_in, int n_out,
                                  const BucketGeom&, void* prepared, hipStream_t);

@@ -125,7 +125,7 @@ def test_prepare_arguments_and_planning():
     need = L.kan_vq_prepared_bytes(C.byref(d))
     # segment table + bias sums + 6 bytes per edge (u16 input, u16 local id, fp16 gain)
     E = 2048 * 1024
-    assert need % 256 == 0 and 6 * E < need < 6 * E + (1 << 16)
+    assert need % 256 == 0 and 6 * E < need < 6 * E + (1 << 17)
     assert L.kan_vq_prepare(C.byref(d), None, need, None) == kb.KAN_ERR_WORKSPACE
     assert L.kan_vq_prepare(C.byref(d), FAKE, need - 1, None) == kb.KAN_ERR_WORKSPACE
     assert L.kan_vq_prepare(C.byref(d), C.c_void_p(0x10010), need, None) == kb.KAN_ERR_WORKSPACE
@@ -154,7 +154,7 @@ def test_byte_coded_layers_plan_and_prepare():
     assert L.kan_vq_workspace_bytes(C.byref(d), 1, 1, 16, kb.KAN_PATH_AUTO) != kb.SIZE_INVALID   # bytes need no alignment
     need = L.kan_vq_prepared_bytes(C.byref(d))
     E = 2048 * 1024
-    assert 5 * E < need < 5 * E + (1 << 16)              # u16 input + u16 local id + 1-byte gain code
+    assert 5 * E < need < 5 * E + (1 << 17)              # u16 input + u16 local id + 1-byte gain code
 
 
 def test_fp16_codebook_layers_plan_but_do_not_prepare():

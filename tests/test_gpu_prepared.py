@@ -66,8 +66,45 @@ def _read_layout(buf, P):
     pq = raw[o:o + 2 * E].view(np.uint16); o += up(2 * E)
     gsz = P.gain.dtype.itemsize
     pg = raw[o:o + gsz * E].view(P.gain.dtype); o += up(gsz * E)
+    # block tables (five, for 1, 2, 3, 4 and more samples x heads) and the per-bucket block counts
+    w_min = nb * ((n_out + 1023) // 1024)
+    tab_w = [max(256 // (t + 1), w_min) for t in range(4)] + [w_min]
+    tables = []
+    for w in tab_w:
+        tables.append(raw[o:o + w * 32].view(np.uint32).reshape(w, 8))
+        o += w * 32
+    o = (o + 32 + 255) // 256 * 256
+    o += up(5 * (nb + 1) * 4)
     assert o == raw.size
+    _read_layout.tables = tables
     return seg, bias, pi, pq, pg
+
+
+def _check_tables(tables, seg, nb, n_in, n_out):
+    """Every table cuts every bucket's outputs into consecutive blocks of at most 1024 outputs,
+    carries the matching edge bounds, and gives the buckets blocks in proportion to their edges."""
+    E = int(seg[-1])
+    m = (n_out + 1023) // 1024
+    for T in tables:
+        W = len(T)
+        assert (T[:, 5:] == 0).all()
+        buckets = T[:, 0].astype(np.int64)
+        assert (np.diff(buckets) >= 0).all() and set(buckets.tolist()) == set(range(nb))
+        for b in range(nb):
+            rows = T[buckets == b]
+            assert len(rows) >= m
+            assert rows[0, 1] == 0 and rows[-1, 2] == n_out
+            assert (rows[1:, 1] == rows[:-1, 2]).all()
+            assert ((rows[:, 2].astype(np.int64) - rows[:, 1]) <= 1024).all() and (rows[:, 2] >= rows[:, 1]).all()
+            assert np.array_equal(rows[:, 3], seg[b * n_out + rows[:, 1].astype(np.int64)])
+            assert np.array_equal(rows[:, 4], seg[b * n_out + rows[:, 2].astype(np.int64)])
+            e_b = int(seg[(b + 1) * n_out]) - int(seg[b * n_out])
+            spare = W - nb * m
+            assert abs(len(rows) - m - spare * e_b / max(E, 1)) <= 1.0 + 1e-9
+        edges = T[:, 4].astype(np.int64) - T[:, 3]
+        assert edges.sum() == E
+        if n_out <= 1024 and W >= 8 * nb * m:      # enough blocks to share out, no output-count limit in the way
+            assert edges.max() <= 2 * (E / W) + 2 * n_in
 
 
 @pytest.mark.parametrize("n_in,n_out,K,cb,gb,idxd", [
@@ -86,6 +123,20 @@ def test_prepared_layout_bit_exact(kb, n_in, n_out, K, cb, gb, idxd):
     exp = _expected_layout(P)
     for name, g, e in zip(("seg", "bias_sum", "i", "q", "gain"), got, exp):
         assert np.array_equal(g, e), name
+    rows = _bucket_rows(P)
+    _check_tables(_read_layout.tables, got[0], (P.K + rows - 1) // rows, n_in, n_out)
+
+
+@pytest.mark.parametrize("dist,n_out", [("zipf-sorted", 300), ("zipf", 300), ("zipf-sorted", 2500), ("uniform", 1024)])
+def test_block_tables_balance_skewed_histograms(kb, dist, n_out):
+    P = synth.make_layer(91, 700, n_out, 40000, cb_dtype="i8", gb_dtype="f16", idx_dist=dist, zipf_s=1.2)
+    L = kb.VQLayer(P).prepare()
+    seg = _read_layout(L.prepared, P)[0]
+    _check_tables(_read_layout.tables, seg, 5, 700, n_out)
+    T = _read_layout.tables[0]
+    edges = T[:, 4].astype(np.int64) - T[:, 3]
+    if n_out <= 1024:
+        assert edges.max() <= 1.6 * edges.mean() + 700, (edges.max(), edges.mean())
 
 
 def _forward_prepared(kb, P, x, expect_kernel="kan_bucket"):
