@@ -146,7 +146,8 @@ kan_status kan_dense_layer_forward(const float* coef, int32_t in, int32_t out, i
  * (half of that for layers with more than 2048 inputs)
  * then by output, then by input; per edge the buffer keeps (input index u16, codeword id
  * within the bucket u16, gain), and per output the sum of its biases (the bases sum to 1 on
- * [-1,1], so the bias term does not depend on x).  With L->prepared set, the precise path
+ * [-1,1], so the bias term does not depend on x), and tables that cut the work into blocks
+ * of about equal edge counts whatever the histogram of the codewords.  With L->prepared set, the precise path
  * serves batches up to 4 from this layout: every workgroup copies one bucket into LDS and
  * streams that bucket's edges, so no lookup leaves the CU.  Values are unchanged (same
  * products, different summation order: within the 1e-5 bound).

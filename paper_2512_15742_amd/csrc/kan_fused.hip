@@ -130,6 +130,54 @@ __global__ __launch_bounds__(kThreads) void kan_fused_kernel(const FusedArgs a) 
     for (int s = 0; s < 4; ++s) bsum += m.b[s];
   };
 
+  // -- the same three pieces for the deep pipeline below (indices apart from gains and biases,
+  //    every load unconditional)
+  struct Ids { uint32_t id[4]; };
+  struct GainBias { float g[4], b[4]; };
+  // Every load of the pipeline is unconditional, so that the compiler counts the loads in
+  // flight exactly and a wait covers only what is needed next.  Steps past the end of the
+  // chunk read the layer's last row (coalesced) and gather codeword 0 with every lane (one
+  // cache line per wave instead of 64), which costs next to nothing; their edges have gain 0.
+  auto load_meta_deep = [&](int k, Ids& ids, GainBias& gb) {
+    const bool live = k < n_steps;
+#pragma unroll
+    for (int s = 0; s < 4; ++s) {
+      const int i = i_begin + k * IT + 4 * lh + s;
+      const bool ok = j_ok && i < i_end;
+      const long long e = (long long)min(i, n_in - 1) * n_out + jc;
+      uint32_t id[1];
+      float g[1], bv[1];
+      load_idx<IdxT, 1>(idx + e, id);
+      load_gain<GbT, 1>(gain + e, qp, g);
+      load_bias<GbT, 1>(bias + e, qp, bv);
+      ids.id[s] = live ? id[0] : 0u;
+      gb.g[s] = ok ? g[0] * gmul : 0.f;      // out-of-range edges contribute nothing
+      gb.b[s] = ok ? bv[0] : 0.f;
+    }
+  };
+  auto gather_ids = [&](const Ids& m, RawRow<CbT> (&rows)[4]) {
+#pragma unroll
+    for (int s = 0; s < 4; ++s) load_row<CbT>(cb, m.id[s], rows[s]);
+  };
+  auto dequant_deep = [&](const RawRow<CbT> (&rows)[4], const GainBias& m, Frag& out) {
+    if constexpr (F32) {
+#pragma unroll
+      for (int s = 0; s < 4; ++s) dequant_row_f32<CbT>(rows[s], m.g[s], out.f[s]);
+    } else {
+      uint32_t tail[4];
+#pragma unroll
+      for (int s = 0; s < 4; ++s) {
+        uint32_t w[5];
+        dequant_row<CbT>(rows[s], m.g[s], w);
+        out.h[s] = make_uint4(w[0], w[1], w[2], w[3]);
+        tail[s] = w[4];
+      }
+      out.h[4] = make_uint4(tail[0], tail[1], tail[2], tail[3]);
+    }
+#pragma unroll
+    for (int s = 0; s < 4; ++s) bsum += m.b[s];
+  };
+
   auto load_u = [&](int k, float (&uv)[NPAIR]) {
     const int i = i_begin + k * IT + NPAIR * ph;
 #pragma unroll
@@ -198,41 +246,117 @@ __global__ __launch_bounds__(kThreads) void kan_fused_kernel(const FusedArgs a) 
     }
   };
 
-  // ---- pipeline (rings indexed by compile-time slots, loop unrolled by 4) ------------------
-  // Top of step k: fragments and Phi tile of step k are ready; codeword rows and basis words
-  // of step k+1 are in flight; metadata of steps k+1 .. k+3 is held or in flight.
-  Meta meta[4];
-  RawRow<CbT> rows[2][4];
-  float uv[2][NPAIR];
-  Frag frag[2];
-  // Nothing is fetched for steps past the end: the address units that serve the random
-  // codeword gathers are the bottleneck of this kernel, so wasted gathers are not free.
-  load_meta(0, meta[0]);
-  if (1 < n_steps) load_meta(1, meta[1]);
-  load_u(0, uv[0]);
-  gather_rows(meta[0], rows[0]);
-  if (2 < n_steps) load_meta(2, meta[2]);
-  if (1 < n_steps) gather_rows(meta[1], rows[1]);
-  if (3 < n_steps) load_meta(3, meta[3]);
-  load_u(1, uv[1]);
-  dequant_step(rows[0], meta[0], frag[0]);
-  gen_phi(uv[0], sTile[0]);
+  // Two pipelines.  The deep one pays off where a step holds enough MFMA work and chunks are
+  // long (fp16 operands, 64-sample tiles: 66.7 -> 57.7 us for configuration 3 at batch 64);
+  // with short chunks its extra prologue loads cost more than they hide (batch 2..16: +2..10 %),
+  // and with fp32 operands the MFMAs of a step already cover the gathers.
+  constexpr bool kDeep = !F32 && MBLK == 2;
+  if constexpr (kDeep) {
+    // ---- pipeline (rings indexed by compile-time slots, loop unrolled by 8) ------------------
+    // With few samples a step is a handful of MFMAs, far shorter than a gather's trip to L2, so
+    // the rings are deep.  Top of step k: fragments and Phi tile of step k are ready; codeword
+    // rows of steps k+1 .. k+RD-1 are held or in flight; so are indices up to step k+RD+1,
+    // gains/biases up to step k+RD+1 and inputs up to step k+3.  Step k dequantises step k+1,
+    // builds tile k+1, multiplies step k and issues the gathers of step k+RD plus the metadata
+    // of step k+RD+2.  RD = 4 for one- and two-byte codebook entries, 2 for fp32 rows (registers).
+    constexpr int RD = sizeof(CbT) == 4 ? 2 : 4;
+    Ids ids[4];
+    GainBias gbr[8];
+    RawRow<CbT> rows[RD][4];
+    float uv[4][NPAIR];
+    Frag frag[2];
+  #pragma unroll
+    for (int q = 0; q < RD; ++q) load_meta_deep(q, ids[q & 3], gbr[q & 7]);
+  #pragma unroll
+    for (int q = 0; q < 4; ++q) load_u(q, uv[q]);
+  #pragma unroll
+    for (int q = 0; q < RD; ++q) gather_ids(ids[q & 3], rows[q]);
+  #pragma unroll
+    for (int q = RD; q < RD + 2; ++q) load_meta_deep(q, ids[q & 3], gbr[q & 7]);     // (the gathers above have read slots 0, 1)
+    dequant_deep(rows[0], gbr[0], frag[0]);
+    gen_phi(uv[0], sTile[0]);
 
-  auto step = [&](auto T, int k) {
-    constexpr int t = decltype(T)::value;          // k mod 4
-    __syncthreads();     // tile k is complete; every wave is done reading tile k-1
-    if (k + 1 < n_steps) dequant_step(rows[(t + 1) & 1], meta[(t + 1) & 3], frag[(t + 1) & 1]);   // step k+1 fragments
-    if (k + 2 < n_steps) gather_rows(meta[(t + 2) & 3], rows[t & 1]);                             // step k+2 codewords
-    if (k + 4 < n_steps) load_meta(k + 4, meta[t & 3]);                                           // step k+4 metadata
-    mfma_step(sTile[t & 1], frag[t & 1]);
-    if (k + 1 < n_steps) gen_phi(uv[(t + 1) & 1], sTile[(t + 1) & 1]);                            // step k+1 basis tile
-    if (k + 2 < n_steps) load_u(k + 2, uv[t & 1]);
-  };
-  for (int k = 0; k < n_steps; k += 4) {
-    step(std::integral_constant<int, 0>{}, k);
-    if (k + 1 < n_steps) step(std::integral_constant<int, 1>{}, k + 1);
-    if (k + 2 < n_steps) step(std::integral_constant<int, 2>{}, k + 2);
-    if (k + 3 < n_steps) step(std::integral_constant<int, 3>{}, k + 3);
+    auto step = [&](auto T, int k) {
+      constexpr int t = decltype(T)::value;          // k mod 8
+      __syncthreads();     // tile k is complete; every wave is done reading tile k-1
+      dequant_deep(rows[(t + 1) % RD], gbr[(t + 1) & 7], frag[(t + 1) & 1]);       // step k+1 fragments
+      gather_ids(ids[(t + RD) & 3], rows[t % RD]);                                 // step k+RD codewords
+      load_meta_deep(k + RD + 2, ids[(t + RD + 2) & 3], gbr[(t + RD + 2) & 7]);          // step k+RD+2 metadata
+      mfma_step(sTile[t & 1], frag[t & 1]);
+      gen_phi(uv[(t + 1) & 3], sTile[(t + 1) & 1]);                                 // step k+1 basis tile
+      load_u(k + 4, uv[t & 3]);
+    };
+    // Branch-free groups of eight steps, then a nested tail: a step that follows a branch
+    // taken or not would make the compiler wait for every load in flight.
+    int k = 0;
+    for (; k + 8 <= n_steps; k += 8) {
+      step(std::integral_constant<int, 0>{}, k);
+      step(std::integral_constant<int, 1>{}, k + 1);
+      step(std::integral_constant<int, 2>{}, k + 2);
+      step(std::integral_constant<int, 3>{}, k + 3);
+      step(std::integral_constant<int, 4>{}, k + 4);
+      step(std::integral_constant<int, 5>{}, k + 5);
+      step(std::integral_constant<int, 6>{}, k + 6);
+      step(std::integral_constant<int, 7>{}, k + 7);
+    }
+    if (k < n_steps) {
+      step(std::integral_constant<int, 0>{}, k);
+      if (k + 1 < n_steps) {
+        step(std::integral_constant<int, 1>{}, k + 1);
+        if (k + 2 < n_steps) {
+          step(std::integral_constant<int, 2>{}, k + 2);
+          if (k + 3 < n_steps) {
+            step(std::integral_constant<int, 3>{}, k + 3);
+            if (k + 4 < n_steps) {
+              step(std::integral_constant<int, 4>{}, k + 4);
+              if (k + 5 < n_steps) {
+                step(std::integral_constant<int, 5>{}, k + 5);
+                if (k + 6 < n_steps) step(std::integral_constant<int, 6>{}, k + 6);
+              }
+            }
+          }
+        }
+      }
+    }
+
+  } else {
+    // ---- pipeline (rings indexed by compile-time slots, loop unrolled by 4) ------------------
+    // Top of step k: fragments and Phi tile of step k are ready; codeword rows and basis words
+    // of step k+1 are in flight; metadata of steps k+1 .. k+3 is held or in flight.
+    Meta meta[4];
+    RawRow<CbT> rows[2][4];
+    float uv[2][NPAIR];
+    Frag frag[2];
+    // Nothing is fetched for steps past the end: the address units that serve the random
+    // codeword gathers are the bottleneck of this kernel, so wasted gathers are not free.
+    load_meta(0, meta[0]);
+    if (1 < n_steps) load_meta(1, meta[1]);
+    load_u(0, uv[0]);
+    gather_rows(meta[0], rows[0]);
+    if (2 < n_steps) load_meta(2, meta[2]);
+    if (1 < n_steps) gather_rows(meta[1], rows[1]);
+    if (3 < n_steps) load_meta(3, meta[3]);
+    load_u(1, uv[1]);
+    dequant_step(rows[0], meta[0], frag[0]);
+    gen_phi(uv[0], sTile[0]);
+
+    auto step = [&](auto T, int k) {
+      constexpr int t = decltype(T)::value;          // k mod 4
+      __syncthreads();     // tile k is complete; every wave is done reading tile k-1
+      if (k + 1 < n_steps) dequant_step(rows[(t + 1) & 1], meta[(t + 1) & 3], frag[(t + 1) & 1]);   // step k+1 fragments
+      if (k + 2 < n_steps) gather_rows(meta[(t + 2) & 3], rows[t & 1]);                             // step k+2 codewords
+      if (k + 4 < n_steps) load_meta(k + 4, meta[t & 3]);                                           // step k+4 metadata
+      mfma_step(sTile[t & 1], frag[t & 1]);
+      if (k + 1 < n_steps) gen_phi(uv[(t + 1) & 1], sTile[(t + 1) & 1]);                            // step k+1 basis tile
+      if (k + 2 < n_steps) load_u(k + 2, uv[t & 1]);
+    };
+    for (int k = 0; k < n_steps; k += 4) {
+      step(std::integral_constant<int, 0>{}, k);
+      if (k + 1 < n_steps) step(std::integral_constant<int, 1>{}, k + 1);
+      if (k + 2 < n_steps) step(std::integral_constant<int, 2>{}, k + 2);
+      if (k + 3 < n_steps) step(std::integral_constant<int, 3>{}, k + 3);
+    }
+
   }
 
   // ---- epilogue.  D layout of the 32x32 MFMA: lane holds column (lane & 31), rows
