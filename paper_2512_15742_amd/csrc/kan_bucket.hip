@@ -406,11 +406,29 @@ __global__ void kan_prepare_block_counts_kernel(const uint32_t* __restrict__ seg
 // The entries of one bucket (thread = bucket): its outputs are cut into its blocks so that
 // the blocks hold about equal numbers of edges, never more than kBucketMaxJw outputs each
 // (the cuts are made one after the other so that the limit holds for every block).
+//
+// Where a block sits in the table decides its XCD (workgroups go to the 8 XCDs in turn): the
+// bucket-sorted list of blocks is dealt out in 8 contiguous runs, run x taking the positions
+// x, x + 8, ..., so that an XCD serves few buckets and its L2 holds only their rows (with 8
+// equal buckets: one bucket per XCD, the codebook crosses the fabric once).
+__device__ __forceinline__ int bucket_table_position(int s, int W) {
+  const int base = W >> 3, rem = W & 7;
+  int x = 0, start = 0;
+  while (x < 7) {
+    const int c = base + (x < rem ? 1 : 0);
+    if (s < start + c) break;
+    start += c;
+    ++x;
+  }
+  return (s - start) * 8 + x;
+}
+
 __global__ __launch_bounds__(256) void kan_prepare_blocks_kernel(const uint32_t* __restrict__ seg, int n_out,
                                                                  int n_buckets, const uint32_t* __restrict__ cnt,
                                                                  uint32_t* __restrict__ table) {
   const int b = blockIdx.x * blockDim.x + threadIdx.x;
   if (b >= n_buckets) return;
+  const int W = (int)cnt[n_buckets];
   const int first = (int)cnt[b], nb = (int)(cnt[b + 1] - cnt[b]);
   const uint32_t* sb = seg + (size_t)b * n_out;     // sb[0 .. n_out] are valid (the prefix runs on)
   const unsigned long long e0 = sb[0], eb = sb[n_out] - sb[0];
@@ -428,7 +446,7 @@ __global__ __launch_bounds__(256) void kan_prepare_blocks_kernel(const uint32_t*
       const int hi_c = min(j0 + kBucketMaxJw, n_out);
       j1 = min(max(a, lo_c), hi_c);
     }
-    uint32_t* e = table + (size_t)(first + q) * kBucketEntryWords;
+    uint32_t* e = table + (size_t)bucket_table_position(first + q, W) * kBucketEntryWords;
     e[0] = (uint32_t)b;
     e[1] = (uint32_t)j0;
     e[2] = (uint32_t)j1;

@@ -80,6 +80,20 @@ def _read_layout(buf, P):
     return seg, bias, pi, pq, pg
 
 
+def _table_position(s, W):
+    """Position of the s-th block of the bucket-sorted list: the list is dealt out in 8 contiguous
+    runs, run x taking positions x, x + 8, ... (workgroups go to the 8 XCDs in turn)."""
+    base, rem = W >> 3, W & 7
+    x = start = 0
+    while x < 7:
+        c = base + (1 if x < rem else 0)
+        if s < start + c:
+            break
+        start += c
+        x += 1
+    return (s - start) * 8 + x
+
+
 def _check_tables(tables, seg, nb, n_in, n_out):
     """Every table cuts every bucket's outputs into consecutive blocks of at most 1024 outputs,
     carries the matching edge bounds, and gives the buckets blocks in proportion to their edges."""
@@ -87,6 +101,7 @@ def _check_tables(tables, seg, nb, n_in, n_out):
     m = (n_out + 1023) // 1024
     for T in tables:
         W = len(T)
+        T = T[[_table_position(q, W) for q in range(W)]]          # back to bucket order
         assert (T[:, 5:] == 0).all()
         buckets = T[:, 0].astype(np.int64)
         assert (np.diff(buckets) >= 0).all() and set(buckets.tolist()) == set(range(nb))
@@ -134,6 +149,9 @@ def test_block_tables_balance_skewed_histograms(kb, dist, n_out):
     seg = _read_layout(L.prepared, P)[0]
     _check_tables(_read_layout.tables, seg, 5, 700, n_out)
     T = _read_layout.tables[0]
+    # an XCD (positions x, x + 8, ...) serves a contiguous run of the bucket-sorted blocks: few buckets
+    per_xcd = [len(set(T[x::8, 0].tolist())) for x in range(8)]
+    assert sum(per_xcd) <= 5 + 7, per_xcd           # a bucket is split over two XCDs only at the 7 run ends
     edges = T[:, 4].astype(np.int64) - T[:, 3]
     if n_out <= 1024:
         assert edges.max() <= 1.6 * edges.mean() + 700, (edges.max(), edges.mean())
