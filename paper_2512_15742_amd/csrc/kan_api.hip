@@ -82,7 +82,6 @@ struct LayerPlan {
   GatherCfg cfg;
   int n_jt, n_bt, n_chunks, rows_per_chunk;
   int kind;          // PlanKind
-  int parts = 0, jw = 0;   // bucket path: blocks (workgroups per sample and head) of the launch; jw unused
   bool mfma;         // kind == kPlanMfma (coefficient + basis preparation, streaming contraction)
   const char* name;
 };
@@ -228,9 +227,7 @@ LayerPlan plan_bucket(const kan_vq_layer& L, int64_t B, int n_heads) {
   p.cfg.gb_kind = gb_kind_of(L);
   p.cfg.code = L.cb_dtype == KAN_I8 ? kCbI8 : kCbF32;
   const BucketGeom g = bucket_geometry(L.in, L.out, L.K, L.cb_dtype == KAN_I8, gb_kind_of(L));
-  p.parts = g.tab_w[bucket_table_for((long long)B * n_heads)];      // blocks of the table this launch uses
-  p.jw = 0;
-  p.n_jt = p.parts;
+  p.n_jt = g.tab_w[bucket_table_for((long long)B * n_heads)];       // blocks of the table a full group of heads uses
   p.n_bt = (int)B;
   p.n_chunks = g.n_buckets;          // the per-bucket sums are the partial sums
   p.rows_per_chunk = L.in;
