@@ -98,7 +98,7 @@ typedef struct kan_vq_layer {
   int32_t rule;          /* KAN_RULE_BSPLINE3 (0) | KAN_RULE_PLI2                   */
   const void* prepared;  /* NULL, or the buffer kan_vq_prepare filled for this very
                             layer (small-batch path, see below)                     */
-  /* KAN_Q8 only (section 4.2: "gains via logarithmic Int8, biases via linear Int8", 16 bits
+  /* KAN_Q8 only (section 4.2: gains on a logarithmic and biases on a linear Int8 grid, 16 bits
    * per edge beside the index; the paper prints no formula, this is the reading used here):
    *   gain[e] is an unsigned byte: 0 means 0, code c in 1..255 means
    *           exp2(gain_log2_lo + gain_log2_step * c);

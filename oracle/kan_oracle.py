@@ -19,17 +19,16 @@ What it follows
   c_ij = g_ij * C[k_ij] + b_ij                                    (paper §4.2).
   On [-1, 1] the two statements agree because the bases sum to one.
 * Int8 codebooks store one byte per coefficient (paper §4.3, §5.4); the value
-  is scale * q with one fp32 scale per layer (reading stated in the design
-  notes: the paper gives the byte count but not the mapping).
+  is scale * q with one fp32 scale per layer (a reading: the paper gives the
+  byte count but not the mapping).
 * Heads: tanh between layers, none after the last (benchmark configuration).
 
 * The runtime operator's own rule (paper §4.1, §4.3), selectable with
   rule="pli": the G entries of a codeword are samples at G uniform nodes over
   [-1, 1], the lookup index is floor((x + 1) / dx), dx = 2 / (G - 1), and the
   value is the linear interpolation between the two neighbouring entries; the
-  last interval is closed at x = +1 (reading stated in the design notes: the
-  paper gives the index expression and "two codebook entries", not dx or the
-  end rule).
+  last interval is closed at x = +1 (a reading: the paper gives the index
+  expression and names two codebook entries, not dx or the end rule).
 
 Bases are evaluated by the Cox-de Boor recursion, exactly as the textbook
 definition states it; nothing here uses the closed-form uniform cubic weights
@@ -247,10 +246,10 @@ def dequantise_gain_bias(gain, bias, gb_params=None):
     """Per-edge gain and bias as float64.
 
     Floating arrays are taken as they are.  With gb_params = (gain_log2_lo, gain_log2_step,
-    bias_scale) the arrays hold one byte per value (paper §4.2: "gains via logarithmic Int8 to
-    retain dynamic range, and biases via linear Int8"; the paper prints no formula - reading
-    stated in the design notes): gain code 0 is a zero gain, code c = 1..255 means
-    2 ** (lo + step * c); bias code c (signed) means bias_scale * c.
+    bias_scale) the arrays hold one byte per value (paper §4.2: gains on a logarithmic Int8
+    grid, biases on a linear Int8 grid; the paper prints no formula, this is a reading):
+    gain code 0 is a zero gain, code c = 1..255 means 2 ** (lo + step * c); bias code c
+    (signed) means bias_scale * c.
     """
     if gb_params is None:
         return np.asarray(gain).astype(np.float64), np.asarray(bias).astype(np.float64)
@@ -351,7 +350,7 @@ def normalise_grids(coef):
     gain the Euclidean norm of the centred grid, shape = centred / gain (zeros where gain is 0).
     The paper normalises to zero mean and unit variance; the benchmark's codebooks hold
     zero-mean unit-NORM shapes, so the norm is used here: the same shapes, gains differ by
-    sqrt(G) (reading stated in the design notes)."""
+    sqrt(G)."""
     c = np.asarray(coef, dtype=np.float64)
     bias = c.mean(axis=-1)
     centred = c - bias[..., None]

@@ -153,8 +153,8 @@ __device__ __forceinline__ void load_idx(const IdxT* p, uint32_t (&id)[N]) {
 // codes mean
 //     gain = 0 for code 0, else exp2(gain_log2_lo + gain_log2_step * code)   code = 1..255
 //     bias = bias_scale * code                                               code = -127..127
-// with the three parameters fixed per layer (the paper prints no formula; this is the
-// reading stated in the design notes).
+// with the three parameters fixed per layer (the paper prints no formula; this reading keeps
+// a zero code for exact zeros and spends the other 255 codes evenly on log2 of the gain).
 struct Q8Params {
   float gain_log2_lo, gain_log2_step, bias_scale;
 };
