@@ -189,7 +189,7 @@ kan_status kan_vq_count_bad_indices(const kan_vq_layer* L, uint32_t* count, void
  * layer coef[in][out][10]:
  *   bias[e] = mean of the 10 coefficients, gain[e] = Euclidean norm of the centred grid
  *             (so that the normalised grid is zero-mean and unit-norm like the codebook shapes;
- *             the paper says "unit variance": same shapes, gains differ by sqrt(10));
+ *             the paper normalises to unit variance: same shapes, gains differ by sqrt(10));
  *   idx[e]  = index of the codebook row nearest (squared Euclidean distance) to the normalised
  *             grid; for an all-constant grid (gain 0) the row of smallest norm.
  * The distance contraction runs on the matrix cores with split fp16 operands (fp32-grade

@@ -24,7 +24,9 @@ def kb():
 
 
 @pytest.mark.parametrize("n_in,n_out,B", [(1, 1, 1), (8, 32, 32), (3, 21, 2), (130, 67, 5), (257, 130, 150),
-                                          (64, 520, 33), (1000, 264, 300), (2048, 8, 129)])
+                                          (64, 520, 33), (1000, 264, 300), (2048, 8, 129),
+                                          # 64-sample tiles of the fused kernel (its deep pipeline): long and short chunks
+                                          (2048, 264, 50), (1000, 130, 64), (300, 21, 40), (4100, 70, 33)])
 def test_mfma_ragged_shapes(kb, n_in, n_out, B):
     P = synth.make_layer(n_in * 7 + n_out, n_in, n_out, 1000, cb_dtype="i8", gb_dtype="f16")
     x = synth.make_x(B, B, n_in)
