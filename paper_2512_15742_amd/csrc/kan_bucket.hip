@@ -87,6 +87,7 @@ __global__ __launch_bounds__(kBucketThreads) void kan_bucket_kernel(const Bucket
   __shared__ __attribute__((aligned(16))) float prod[kPass];   // per-edge products of the current pass
   __shared__ float res[kBucketMaxJw];       // sums of this workgroup's segments
   __shared__ uint32_t segl[kBucketMaxJw + 1];   // first edge of every segment of the block (+ end)
+  __shared__ int seg_first[2];                  // first segment that reaches into the pass (by pass parity)
 
   const int tid = threadIdx.x, lane = tid & (kWave - 1);
   const int wave = __builtin_amdgcn_readfirstlane(tid >> 6);
@@ -268,13 +269,19 @@ __global__ __launch_bounds__(kBucketThreads) void kan_bucket_kernel(const Bucket
     }
     ((float4*)prod)[tid * 2] = make_float4(pr[0], pr[1], pr[2], pr[3]);
     ((float4*)prod)[tid * 2 + 1] = make_float4(pr[4], pr[5], pr[6], pr[7]);
+    // The first segment that ends after the start of the pass: thread t answers for segment t
+    // (exactly one does), so that the sums below visit only the segments of the pass and a
+    // block of 1024 short segments does not walk all of them in every pass.
+    const uint32_t pa = base + (uint32_t)p * kPass;
+    if (tid < njw && segl[tid + 1] > pa && (tid == 0 || segl[tid] <= pa)) seg_first[p & 1] = tid;
   };
 
   // segment sums over the products of pass p: wave w takes segments w, w + 16, ...
   auto segment_sums = [&](int p) {
     const uint32_t pa = base + (uint32_t)p * kPass;        // prod[n] is edge pa + n
-    for (int jj = wave; jj < njw; jj += kWaves) {
+    for (int jj = seg_first[p & 1] + wave; jj < njw; jj += kWaves) {
       const uint32_t s0 = segl[jj], s1 = segl[jj + 1];
+      if (s0 >= pa + (uint32_t)kPass) break;               // the segments are in order: the rest lies behind the pass
       const uint32_t lo = max(s0, pa), hi = min(s1, pa + (uint32_t)kPass);
       if (lo < hi) {                                         // uniform
         float acc = 0.f;
@@ -289,16 +296,16 @@ __global__ __launch_bounds__(kBucketThreads) void kan_bucket_kernel(const Bucket
   // (after the last pass the refills are harmless re-reads)
   for (int p = 0; p < n_pass; p += 2) {
     products(A, p);
+    load_pass(A, p + 2);
     __syncthreads();
     segment_sums(p);
     __syncthreads();
-    load_pass(A, p + 2);
     if (p + 1 >= n_pass) break;
     products(B, p + 1);
+    load_pass(B, p + 3);
     __syncthreads();
     segment_sums(p + 1);
     __syncthreads();
-    load_pass(B, p + 3);
   }
 
   // ---- segment sums -> memory (coalesced): scale, bias sum (first bucket only), activation ----
