@@ -65,9 +65,22 @@ __device__ __forceinline__ float gain_of(const PassRegs<GK>& c, int u, const Q8P
   }
 }
 
-__device__ __forceinline__ float wave_sum(float v) {
-#pragma unroll
-  for (int m = 32; m >= 1; m >>= 1) v += __shfl_xor(v, m, kWave);
+// Sum over the 64 lanes of a wave, delivered in lane 63, with data-parallel-primitive moves
+// (register crossbar: a few clocks each) instead of LDS permutes (a dependent chain of six
+// LDS round trips per segment).  The order of the additions is fixed.
+template <int CTRL, int ROW_MASK>
+__device__ __forceinline__ float dpp_add(float v) {
+  const int moved = __builtin_amdgcn_update_dpp(0, __float_as_int(v), CTRL, ROW_MASK, 0xf, false);
+  return v + __int_as_float(moved);
+}
+
+__device__ __forceinline__ float wave_sum_to_last_lane(float v) {
+  v = dpp_add<0xB1, 0xf>(v);       // quad_perm [1,0,3,2]: neighbours
+  v = dpp_add<0x4E, 0xf>(v);       // quad_perm [2,3,0,1]: every lane holds its quad's sum
+  v = dpp_add<0x141, 0xf>(v);      // row_half_mirror: sums of 8
+  v = dpp_add<0x140, 0xf>(v);      // row_mirror: every lane holds its row's sum (16 lanes)
+  v = dpp_add<0x142, 0xa>(v);      // row_bcast 15 into rows 1 and 3: sums of 32 in rows 1, 3
+  v = dpp_add<0x143, 0xc>(v);      // row_bcast 31 into rows 2 and 3: lane 63 holds the sum of 64
   return v;
 }
 
@@ -286,8 +299,8 @@ __global__ __launch_bounds__(kBucketThreads) void kan_bucket_kernel(const Bucket
       if (lo < hi) {                                         // uniform
         float acc = 0.f;
         for (uint32_t e = lo + (uint32_t)lane; e < hi; e += kWave) acc += prod[e - pa];
-        acc = wave_sum(acc);
-        if (lane == 0) res[jj] += acc;
+        acc = wave_sum_to_last_lane(acc);
+        if (lane == kWave - 1) res[jj] += acc;
       }
     }
   };
