@@ -74,6 +74,15 @@ __device__ __forceinline__ float dpp_add(float v) {
   return v + __int_as_float(moved);
 }
 
+// Sum over a row of 16 lanes, delivered in every lane of the row.
+__device__ __forceinline__ float row_sum(float v) {
+  v = dpp_add<0xB1, 0xf>(v);
+  v = dpp_add<0x4E, 0xf>(v);
+  v = dpp_add<0x141, 0xf>(v);
+  v = dpp_add<0x140, 0xf>(v);
+  return v;
+}
+
 __device__ __forceinline__ float wave_sum_to_last_lane(float v) {
   v = dpp_add<0xB1, 0xf>(v);       // quad_perm [1,0,3,2]: neighbours
   v = dpp_add<0x4E, 0xf>(v);       // quad_perm [2,3,0,1]: every lane holds its quad's sum
@@ -289,9 +298,26 @@ __global__ __launch_bounds__(kBucketThreads) void kan_bucket_kernel(const Bucket
     if (tid < njw && segl[tid + 1] > pa && (tid == 0 || segl[tid] <= pa)) seg_first[p & 1] = tid;
   };
 
-  // segment sums over the products of pass p: wave w takes segments w, w + 16, ...
+  // segment sums over the products of pass p.  Long segments: wave w takes segments w, w + 16, ...
+  // Short segments (128 edges or fewer on average: layers with many buckets or few inputs):
+  // a row of 16 lanes takes a segment, so a wave works on four at a time and the chain of
+  // LDS round trips per segment (bounds, products, running sum) is paid a quarter as often.
+  const bool short_segments = blk_hi - blk_lo <= 128u * (uint32_t)njw;      // uniform
   auto segment_sums = [&](int p) {
     const uint32_t pa = base + (uint32_t)p * kPass;        // prod[n] is edge pa + n
+    if (short_segments) {
+      const int row = lane >> 4, rl = lane & 15;
+      for (int jj = seg_first[p & 1] + wave * 4 + row; jj < njw; jj += kWaves * 4) {
+        const uint32_t s0 = segl[jj], s1 = segl[jj + 1];
+        if (s0 >= pa + (uint32_t)kPass) break;             // (per row: the rows of a wave leave one by one)
+        const uint32_t lo = max(s0, pa), hi = min(s1, pa + (uint32_t)kPass);
+        float acc = 0.f;
+        for (uint32_t e = lo + (uint32_t)rl; e < hi; e += 16u) acc += prod[e - pa];
+        acc = row_sum(acc);
+        if (rl == 0 && lo < hi) res[jj] += acc;
+      }
+      return;
+    }
     for (int jj = seg_first[p & 1] + wave; jj < njw; jj += kWaves) {
       const uint32_t s0 = segl[jj], s1 = segl[jj + 1];
       if (s0 >= pa + (uint32_t)kPass) break;               // the segments are in order: the rest lies behind the pass
