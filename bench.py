@@ -205,6 +205,31 @@ def sweep(kb, torch, synth):
                           "algorithmic_TFLOPs": E * K * 20 / t / 1e12, "issued_mfma_TFLOPs": E * K * 64 / t / 1e12,
                           "r2": kb.kan_vq_reconstruction_r2(coef, cb, *out)}), flush=True)
         del coef, cb
+    # a layer large enough to be bandwidth-bound at batch 1: config 5's Int8 layer (134 MB of metadata),
+    # three copies taken in turn (402 MB: more than the memory-side cache holds)
+    (p5,), x5 = synth.config5("i8", B=16)
+    for prepared in (False, True):
+        copies = [kb.VQLayer(p5) for _ in range(3)]
+        if prepared:
+            for L in copies:
+                L.prepare()
+        for B in (1, 4, 16):
+            xd = torch.from_numpy(x5[:B]).cuda()
+            pth = kb.KAN_PATH_GATHER
+            ws = torch.empty(max(kb.kan_vq_workspace_bytes([[copies[0]]], B, pth), 256), dtype=torch.uint8, device="cuda")
+            y = torch.empty((B, p5.n_out), dtype=torch.float32, device="cuda")
+            turn = [0]
+
+            def fwd():
+                kb.kan_vq_layer_forward(copies[turn[0] % 3], xd, path=pth, ws=ws, y=y)
+                turn[0] += 1
+            t = wall(fwd, 30)
+            print(json.dumps({"workload": "config5 layer 4096->4096 K=262144 i8, 3 copies in turn", "batch": B,
+                              "path": "gather", "prepared": prepared, "rule": "bspline3",
+                              "us_per_forward": round(t * 1e6, 2), "edge_evals_per_s": p5.edges * B / t,
+                              "metadata_GBps": p5.metadata_bytes / t / 1e9,
+                              "kernel": kb.kan_vq_planned_kernel(copies[0], B, 1, pth)}), flush=True)
+        del copies
     heads_p, x = synth.config4(50, 64)
     vq_rows("config4 50 Int8 heads 2048->256->21", heads_p, x, both, 10)
     for variant in ("i8", "f32"):
