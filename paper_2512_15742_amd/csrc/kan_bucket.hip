@@ -298,36 +298,27 @@ __global__ __launch_bounds__(kBucketThreads) void kan_bucket_kernel(const Bucket
     if (tid < njw && segl[tid + 1] > pa && (tid == 0 || segl[tid] <= pa)) seg_first[p & 1] = tid;
   };
 
-  // segment sums over the products of pass p.  Long segments: wave w takes segments w, w + 16, ...
-  // Short segments (128 edges or fewer on average: layers with many buckets or few inputs):
-  // a row of 16 lanes takes a segment, so a wave works on four at a time and the chain of
-  // LDS round trips per segment (bounds, products, running sum) is paid a quarter as often.
-  const bool short_segments = blk_hi - blk_lo <= 128u * (uint32_t)njw;      // uniform
+  // segment sums over the products of pass p.  A group of lanes takes a segment: a whole wave
+  // where segments are long (more than 512 edges on average), half a wave up to 512, a row of 16
+  // lanes up to 128 (layers with many buckets or few inputs): a wave then works on two or four
+  // segments at a time and the chain of LDS round trips per segment (bounds, products, running
+  // sum) is paid that much less often.  Wave w takes the groups w, w + 16, ... of the pass.
+  const uint32_t avg_len_x = blk_hi - blk_lo;                               // compared with len * njw: uniform
+  const int group_shift = avg_len_x <= 128u * (uint32_t)njw ? 4 : (avg_len_x <= 512u * (uint32_t)njw ? 5 : 6);
   auto segment_sums = [&](int p) {
     const uint32_t pa = base + (uint32_t)p * kPass;        // prod[n] is edge pa + n
-    if (short_segments) {
-      const int row = lane >> 4, rl = lane & 15;
-      for (int jj = seg_first[p & 1] + wave * 4 + row; jj < njw; jj += kWaves * 4) {
-        const uint32_t s0 = segl[jj], s1 = segl[jj + 1];
-        if (s0 >= pa + (uint32_t)kPass) break;             // (per row: the rows of a wave leave one by one)
-        const uint32_t lo = max(s0, pa), hi = min(s1, pa + (uint32_t)kPass);
-        float acc = 0.f;
-        for (uint32_t e = lo + (uint32_t)rl; e < hi; e += 16u) acc += prod[e - pa];
-        acc = row_sum(acc);
-        if (rl == 0 && lo < hi) res[jj] += acc;
-      }
-      return;
-    }
-    for (int jj = seg_first[p & 1] + wave; jj < njw; jj += kWaves) {
+    const int glanes = 1 << group_shift, per_wave = kWave >> group_shift;
+    const int grp = lane >> group_shift, gl = lane & (glanes - 1);
+    for (int jj = seg_first[p & 1] + wave * per_wave + grp; jj < njw; jj += kWaves * per_wave) {
       const uint32_t s0 = segl[jj], s1 = segl[jj + 1];
-      if (s0 >= pa + (uint32_t)kPass) break;               // the segments are in order: the rest lies behind the pass
+      if (s0 >= pa + (uint32_t)kPass) break;               // in order: the rest lies behind the pass (the groups of a wave leave one by one)
       const uint32_t lo = max(s0, pa), hi = min(s1, pa + (uint32_t)kPass);
-      if (lo < hi) {                                         // uniform
-        float acc = 0.f;
-        for (uint32_t e = lo + (uint32_t)lane; e < hi; e += kWave) acc += prod[e - pa];
-        acc = wave_sum_to_last_lane(acc);
-        if (lane == kWave - 1) res[jj] += acc;
-      }
+      float acc = 0.f;
+      for (uint32_t e = lo + (uint32_t)gl; e < hi; e += (uint32_t)glanes) acc += prod[e - pa];
+      acc = row_sum(acc);                                   // every lane: the sum of its row of 16
+      if (group_shift >= 5) acc = dpp_add<0x142, 0xa>(acc); // rows 1 and 3: the sum of their half wave
+      if (group_shift == 6) acc = dpp_add<0x143, 0xc>(acc); // row 3: the sum of the wave
+      if (gl == glanes - 1 && lo < hi) res[jj] += acc;
     }
   };
 
