@@ -66,3 +66,39 @@ def test_random_case(kb, case):
         # far below its two terms, and rounding relative to those terms is then large relative to phi.
         if case["n_in"] >= 8:
             assert rep["strict"] <= tol, (path, kb.kan_vq_planned_kernel(L, B, 1, path), rep)
+
+
+def _head_cases(n=30, seed=771):
+    rng = np.random.default_rng(seed)
+    widths = [5, 21, 64, 130, 264, 520]
+    out = []
+    for c in range(n):
+        n_layers = int(rng.integers(2, 5))
+        dims = [int(rng.choice(widths)) for _ in range(n_layers + 1)]
+        out.append(dict(seed=5000 + 10 * c, dims=tuple(dims), heads=int(rng.choice([1, 1, 2, 3])),
+                        B=int(rng.choice([1, 2, 4, 5, 33, 70, 200])), K=int(rng.choice([300, 9000, 20001])),
+                        prep=tuple(bool(v) for v in rng.integers(0, 2, size=n_layers)),
+                        gb=str(rng.choice(["f16", "f32", "q8"]))))
+    return out
+
+
+@pytest.mark.parametrize("case", _head_cases(), ids=lambda c: "-".join(str(v) for v in c.values()))
+def test_random_head(kb, case):
+    """Several layers and heads: hand-overs of partial sums between kernels of every kind (bucket to
+    bucket, split layers to the basis preparation, reductions where neither applies), with
+    prepared and unprepared layers mixed at random."""
+    dims, B = case["dims"], case["B"]
+    heads_p = [[synth.make_layer(case["seed"] + 100 * h + l, dims[l], dims[l + 1], case["K"], cb_dtype="i8",
+                                 gb_dtype=case["gb"]) for l in range(len(dims) - 1)] for h in range(case["heads"])]
+    heads = [[kb.VQLayer(p) for p in ps] for ps in heads_p]
+    for ls in heads:
+        for L, pr in zip(ls, case["prep"]):
+            if pr:
+                L.prepare()
+    x = synth.make_x(case["seed"] + 3, B, dims[0])
+    for path, tol in ((kb.KAN_PATH_GATHER, TOL_FP32), (kb.KAN_PATH_MFMA, TOL_MFMA)):
+        y = kb.kan_vq_head_forward(heads, to_dev(x), path=path).cpu().numpy()
+        assert y.shape == (case["heads"], B, dims[-1]) and np.isfinite(y).all()
+        for h in range(case["heads"]):
+            y_ref = ko.vq_head_forward(x, [p.as_dict() for p in heads_p[h]])
+            assert ko.error_report(y[h], y_ref)["headline"] <= tol * (len(dims) - 1), (path, h)
