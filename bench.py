@@ -176,10 +176,10 @@ def sweep(kb, torch, synth):
         vq_rows("config3 shape, 4 B/edge (q8 gain/bias)", [ps], synth.make_x(3900 + B, B, 2048, "uniform"), paths,
                 30 if B <= 256 else 10, prepared=prepared)
     # fp16 codebook rows (the middle codebook precision of the paper's Table 1) on the same head
-    for B, paths in ((1, both[:1]), (16, both), (1024, both[1:])):
+    for B, paths, prepared in ((1, both[:1], False), (1, both[:1], True), (16, both, False), (1024, both[1:], False)):
         ps = synth.config3_layers("f16", cb_dtype="f16")
         vq_rows("config3 shape, fp16 codebook", [ps], synth.make_x(3950 + B, B, 2048, "uniform"), paths,
-                30 if B <= 256 else 10)
+                30 if B <= 256 else 10, prepared=prepared)
     # residency study: a skewed (trained-like) assignment histogram instead of the uniform worst case
     for dist in ("zipf", "zipf-sorted"):
         for B, paths, prepared in ((1, both[:1], False), (1, both[:1], True), (16, both, False), (1024, both[1:], False)):

@@ -141,9 +141,9 @@ kan_status kan_dense_layer_forward(const float* coef, int32_t in, int32_t out, i
 
 /* One-time regrouping of a layer for the memory-bound small-batch regime (section 4.2:
  * batch-1 inference moves the per-edge metadata once; section 4.3: the codebook must be
- * served from on-chip memory).  The edges are regrouped by codebook bucket (8192 Int8 or
- * 2048 fp32 consecutive codewords, 80 KB: what one CU's LDS holds beside the basis table),
- * (half of that for layers with more than 2048 inputs)
+ * served from on-chip memory).  The edges are regrouped by codebook bucket (8192 Int8,
+ * 4096 fp16 or 2048 fp32 consecutive codewords, 80 KB: what one CU's LDS holds beside the
+ * basis table; half of that for layers with more than 2048 inputs),
  * then by output, then by input; per edge the buffer keeps (input index u16, codeword id
  * within the bucket u16, gain), and per output the sum of its biases (the bases sum to 1 on
  * [-1,1], so the bias term does not depend on x), and tables that cut the work into blocks
@@ -151,14 +151,14 @@ kan_status kan_dense_layer_forward(const float* coef, int32_t in, int32_t out, i
  * serves batches up to 4 from this layout: every workgroup copies one bucket into LDS and
  * streams that bucket's edges, so no lookup leaves the CU.  Values are unchanged (same
  * products, different summation order: within the 1e-5 bound).
- *   kan_vq_prepared_bytes  size of the buffer; 0 if the layer is not eligible (in > 4096, or
- *                          an fp16 codebook), (size_t)-1 if the descriptor is invalid.
+ *   kan_vq_prepared_bytes  size of the buffer; 0 if the layer is not eligible (in > 4096),
+ *                          (size_t)-1 if the descriptor is invalid.
  *                          L->prepared is ignored.
  *   kan_vq_prepare         fills `prepared` (device, 256-byte aligned, >= that size) on
- *                          `stream`.  Requires in <= 4096 and an fp32 or Int8 codebook
- *                          (else KAN_ERR_UNSUPPORTED).  The
- *                          buffer depends on idx, gain, bias (not on the codebook values or
- *                          scale) and must be rebuilt when they change.  The caller owns it
+ *                          `stream`.  Requires in <= 4096 (else KAN_ERR_UNSUPPORTED).
+ *                          The buffer depends on idx, gain, bias and the codebook's dtype
+ *                          (not on the codebook values or scale) and must be rebuilt when
+ *                          they change.  The caller owns it
  *                          and stores its address in L->prepared for later forward calls;
  *                          the codebook must then be 16-byte aligned, else the forward call
  *                          ignores the prepared buffer.                                  */

@@ -175,8 +175,9 @@ def basis_matrix(x, clamp: bool = True, close_right: bool = True) -> np.ndarray:
 
 
 # --------------------------------------------------------------------------
-# The runtime operator's two-tap rule (paper §4.1 "index lookup [x / dx] followed by a
-# linear interpolation between two codebook entries"; §4.3 LinearInterp(C[k], x))
+# The runtime operator's two-tap rule (paper §4.1: the cell index is x / dx rounded down,
+# and the value is interpolated linearly between the two codebook entries at that cell's
+# ends; §4.3 writes it as LinearInterp(C[k], x))
 # --------------------------------------------------------------------------
 
 def pli_nodes() -> np.ndarray:

@@ -225,8 +225,8 @@ LayerPlan plan_bucket(const kan_vq_layer& L, int64_t B, int n_heads) {
   p.cfg.wj = 1;
   p.cfg.idx_u32 = L.idx_dtype == KAN_U32;
   p.cfg.gb_kind = gb_kind_of(L);
-  p.cfg.code = L.cb_dtype == KAN_I8 ? kCbI8 : kCbF32;
-  const BucketGeom g = bucket_geometry(L.in, L.out, L.K, L.cb_dtype == KAN_I8, gb_kind_of(L));
+  p.cfg.code = code_of(L);
+  const BucketGeom g = bucket_geometry(L.in, L.out, L.K, code_of(L), gb_kind_of(L));
   p.n_jt = g.tab_w[bucket_table_for((long long)B * n_heads)];       // blocks of the table a full group of heads uses
   p.n_bt = (int)B;
   p.n_chunks = g.n_buckets;          // the per-bucket sums are the partial sums
@@ -236,7 +236,7 @@ LayerPlan plan_bucket(const kan_vq_layer& L, int64_t B, int n_heads) {
 
 bool layer_prepared_ok(const kan_vq_layer& L) {
   return L.prepared != nullptr && aligned(L.prepared, 256) && aligned(L.codebook, 16) && L.in <= kBucketMaxIn &&
-         (long long)L.in * L.out <= (1ll << 31) && L.cb_dtype != KAN_F16;     // buckets hold fp32 or Int8 rows
+         (long long)L.in * L.out <= (1ll << 31);
 }
 
 // Which kernels serve a layer:
@@ -374,8 +374,8 @@ kan_status run_layer_group(const LayerPlan& p, GatherArgs& a, const void* const*
     dim3 grid((unsigned)(p.n_jt * p.n_bt), (unsigned)p.n_chunks, (unsigned)heads);
     st = run(p.name, s, [&] { return launch_mfma(m, p.cfg.bt, grid, s); });
   } else if (p.kind == kPlanBucket) {
-    const bool i8 = p.cfg.code == kCbI8;
-    const BucketGeom g = bucket_geometry(a.n_in, a.n_out, (int)(a.cb_bytes / (i8 ? 10 : 40)), i8, p.cfg.gb_kind);
+    const BucketGeom g = bucket_geometry(a.n_in, a.n_out, (int)(a.cb_bytes / cb_row_bytes(p.cfg.code)), p.cfg.code,
+                                         p.cfg.gb_kind);
     BucketArgs k;
     memset(&k, 0, sizeof(k));
     k.x = a.x;
@@ -408,7 +408,7 @@ kan_status run_layer_group(const LayerPlan& p, GatherArgs& a, const void* const*
       k.h[h].gain_log2_lo = a.h[h].gain_log2_lo;
       k.h[h].gain_log2_step = a.h[h].gain_log2_step;
     }
-    st = run(p.name, s, [&] { return launch_bucket(i8, p.cfg.gb_kind, k, g.tab_w[table], heads, s); });
+    st = run(p.name, s, [&] { return launch_bucket(p.cfg.code, p.cfg.gb_kind, k, g.tab_w[table], heads, s); });
   } else if (p.kind == kPlanFused16 || p.kind == kPlanFused32) {
     const bool f32 = p.kind == kPlanFused32;
     FusedArgs f;
@@ -669,17 +669,16 @@ kan_status kan_dense_layer_forward(const float* coef, int32_t in, int32_t out, i
 
 size_t kan_vq_prepared_bytes(const kan_vq_layer* L) {
   if (validate_layer(L) != KAN_OK) return (size_t)-1;
-  if (L->in > kBucketMaxIn || (long long)L->in * L->out > (1ll << 31) || L->cb_dtype == KAN_F16) return 0;
-  return bucket_geometry(L->in, L->out, L->K, L->cb_dtype == KAN_I8, gb_kind_of(*L)).total;
+  if (L->in > kBucketMaxIn || (long long)L->in * L->out > (1ll << 31)) return 0;
+  return bucket_geometry(L->in, L->out, L->K, code_of(*L), gb_kind_of(*L)).total;
 }
 
 kan_status kan_vq_prepare(const kan_vq_layer* L, void* prepared, size_t prepared_bytes, void* stream) {
   kan_status st = validate_layer(L);
   if (st != KAN_OK) return st;
   if (L->in > kBucketMaxIn) return KAN_ERR_UNSUPPORTED;
-  if (L->cb_dtype == KAN_F16) return KAN_ERR_UNSUPPORTED;                      // buckets hold fp32 or Int8 rows
   if ((long long)L->in * L->out > (1ll << 31)) return KAN_ERR_UNSUPPORTED;   // 32-bit segment offsets
-  const BucketGeom g = bucket_geometry(L->in, L->out, L->K, L->cb_dtype == KAN_I8, gb_kind_of(*L));
+  const BucketGeom g = bucket_geometry(L->in, L->out, L->K, code_of(*L), gb_kind_of(*L));
   if (!prepared || !aligned(prepared, 256) || prepared_bytes < g.total) return KAN_ERR_WORKSPACE;
   LayerPtrs h = {L->idx, L->gain, L->bias, L->codebook, L->scale, L->gain_log2_lo, L->gain_log2_step, L->bias_scale};
   hipStream_t s = (hipStream_t)stream;

@@ -99,7 +99,7 @@ __device__ __forceinline__ float wave_sum_to_last_lane(float v) {
 // building, record traffic and arithmetic overlap.
 //
 // MAXIN: inputs the basis table holds (2048 or 4096); the bucket shrinks to make room.
-template <int GK, bool I8, int MAXIN>
+template <int GK, int CODE, int MAXIN>
 __global__ __launch_bounds__(kBucketThreads) void kan_bucket_kernel(const BucketArgs a) {
   constexpr int kCbBytes = bucket_bytes(MAXIN);
   constexpr int kXPerThread = MAXIN / kBucketThreads;
@@ -262,7 +262,7 @@ __global__ __launch_bounds__(kBucketThreads) void kan_bucket_kernel(const Bucket
       const float4 w = bas[u16_of(c.i, u)];
       const uint32_t at = u16_of(c.q, u) * 10u + __float_as_uint(w.w);
       float c0, c1, c2, c3;
-      if constexpr (I8) {
+      if constexpr (CODE == kCbI8) {
         // bytes at .. at+3 of the bucket: two aligned dwords, funnel-shifted; q + 128 as
         // unsigned bytes (the differences below do not see the offset)
         const uint32_t lo = cb[at >> 2], hi = cb[(at >> 2) + 1];
@@ -271,6 +271,16 @@ __global__ __launch_bounds__(kBucketThreads) void kan_bucket_kernel(const Bucket
         c1 = (float)((win >> 8) & 0xffu);
         c2 = (float)((win >> 16) & 0xffu);
         c3 = (float)(win >> 24);
+      } else if constexpr (CODE == kCbF16) {
+        // halves at .. at+3 of the bucket (8 bytes from byte 2 * at): three aligned dwords,
+        // funnel-shifted by 0 or 2 bytes
+        const uint32_t d = at >> 1, sh = (at & 1u) * 2u;
+        const uint32_t w0 = __builtin_amdgcn_alignbyte(cb[d + 1], cb[d], sh);
+        const uint32_t w1 = __builtin_amdgcn_alignbyte(cb[d + 2], cb[d + 1], sh);
+        c0 = half_bits_to_float(w0 & 0xffffu);
+        c1 = half_bits_to_float(w0 >> 16);
+        c2 = half_bits_to_float(w1 & 0xffffu);
+        c3 = half_bits_to_float(w1 >> 16);
       } else {
         const float* cf = (const float*)cb;
         c0 = cf[at];
@@ -279,7 +289,7 @@ __global__ __launch_bounds__(kBucketThreads) void kan_bucket_kernel(const Bucket
         c3 = cf[at + 3];
       }
       // sum_k w_k c_k with w3 = 1 - w0 - w1 - w2 (the bases sum to 1)
-      float s = I8 ? c3 - 128.0f : c3;
+      float s = CODE == kCbI8 ? c3 - 128.0f : c3;
       s = fmaf(w.z, c2 - c3, s);
       s = fmaf(w.y, c1 - c3, s);
       s = fmaf(w.x, c0 - c3, s);
@@ -342,7 +352,7 @@ __global__ __launch_bounds__(kBucketThreads) void kan_bucket_kernel(const Bucket
   float* dst = a.dst + (long long)head * a.dst_head_stride + (long long)bucket * a.dst_chunk_stride +
                (long long)b * a.n_out;
   const float* bias_sum = (const float*)(prep + a.off_bias);
-  const float scale = I8 ? H.scale : 1.0f;
+  const float scale = CODE == kCbI8 ? H.scale : 1.0f;
   for (int t = tid; t < njw; t += kBucketThreads) {
     float v = scale * res[t] + (bucket == 0 ? bias_sum[j0 + t] : 0.0f);
     if (a.apply_tanh && a.n_buckets == 1) v = tanhf(v);
@@ -533,24 +543,28 @@ hipError_t launch_bucket_prepare(const LayerPtrs& h, int idx_u32, int gb_kind, i
   return prepare_typed<uint16_t, float>(h, n_in, n_out, g, prepared, s);
 }
 
-hipError_t launch_bucket(bool cb_i8, int gb_kind, const BucketArgs& a, int blocks, int heads, hipStream_t s) {
+hipError_t launch_bucket(int code, int gb_kind, const BucketArgs& a, int blocks, int heads, hipStream_t s) {
   if (a.n_in > kBucketMaxIn || a.n_buckets < 1 || blocks < a.n_buckets) return hipErrorInvalidValue;
-  if (gb_kind == kGbQ8 && !cb_i8) return hipErrorInvalidValue;      // byte-coded gains go with Int8 codebooks
+  if (code != kCbI8 && code != kCbF16 && code != kCbF32) return hipErrorInvalidValue;
+  if (gb_kind == kGbQ8 && code != kCbI8) return hipErrorInvalidValue;      // byte-coded gains go with Int8 codebooks
   dim3 grid((unsigned)blocks, (unsigned)a.B, (unsigned)heads);
   dim3 block(kBucketThreads);
   const bool wide = a.n_in > 2048;
-#define KAN_LAUNCH_BUCKET(GK, I8)                                                                      \
+#define KAN_LAUNCH_BUCKET(GK, CODE)                                                                    \
   do {                                                                                                 \
-    if (wide) hipLaunchKernelGGL((kan_bucket_kernel<GK, I8, 4096>), grid, block, 0, s, a);             \
-    else hipLaunchKernelGGL((kan_bucket_kernel<GK, I8, 2048>), grid, block, 0, s, a);                  \
+    if (wide) hipLaunchKernelGGL((kan_bucket_kernel<GK, CODE, 4096>), grid, block, 0, s, a);           \
+    else hipLaunchKernelGGL((kan_bucket_kernel<GK, CODE, 2048>), grid, block, 0, s, a);                \
   } while (0)
-  if (cb_i8) {
-    if (gb_kind == kGbQ8) KAN_LAUNCH_BUCKET(kGbQ8, true);
-    else if (gb_kind == kGbF16) KAN_LAUNCH_BUCKET(kGbF16, true);
-    else KAN_LAUNCH_BUCKET(kGbF32, true);
+  if (code == kCbI8) {
+    if (gb_kind == kGbQ8) KAN_LAUNCH_BUCKET(kGbQ8, kCbI8);
+    else if (gb_kind == kGbF16) KAN_LAUNCH_BUCKET(kGbF16, kCbI8);
+    else KAN_LAUNCH_BUCKET(kGbF32, kCbI8);
+  } else if (code == kCbF16) {
+    if (gb_kind == kGbF16) KAN_LAUNCH_BUCKET(kGbF16, kCbF16);
+    else KAN_LAUNCH_BUCKET(kGbF32, kCbF16);
   } else {
-    if (gb_kind == kGbF16) KAN_LAUNCH_BUCKET(kGbF16, false);
-    else KAN_LAUNCH_BUCKET(kGbF32, false);
+    if (gb_kind == kGbF16) KAN_LAUNCH_BUCKET(kGbF16, kCbF32);
+    else KAN_LAUNCH_BUCKET(kGbF32, kCbF32);
   }
 #undef KAN_LAUNCH_BUCKET
   return hipGetLastError();

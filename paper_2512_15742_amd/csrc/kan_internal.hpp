@@ -117,7 +117,7 @@ hipError_t launch_fused(const GatherCfg&, const FusedArgs&, bool f32, dim3 grid,
 constexpr int kBucketMaxIn = 4096;      // the basis table of all inputs lives in LDS beside the bucket
 constexpr int kBucketThreads = 1024;
 constexpr int kBucketMaxJw = 1024;      // outputs per workgroup (their sums are staged in LDS)
-// Codebook bytes per bucket: 8192 Int8 rows or 2048 fp32 rows for layers of up to 2048
+// Codebook bytes per bucket: 8192 Int8, 4096 fp16 or 2048 fp32 rows for layers of up to 2048
 // inputs, half of that for wider layers (whose basis table takes twice the LDS).
 constexpr int bucket_bytes(int n_in) { return n_in > 2048 ? 40960 : 81920; }
 
@@ -150,11 +150,11 @@ inline int bucket_table_for(long long samples_times_heads) {
   return samples_times_heads <= 4 ? (int)(samples_times_heads < 1 ? 1 : samples_times_heads) - 1 : kBucketTables - 1;
 }
 
-inline BucketGeom bucket_geometry(int n_in, int n_out, int K, bool cb_i8, int gb_kind) {
+inline BucketGeom bucket_geometry(int n_in, int n_out, int K, int code, int gb_kind) {
   // 32 bytes of slack after every array: threads load aligned groups of eight records
   auto up = [](size_t v) { return (v + 32 + 255) / 256 * 256; };
   BucketGeom g;
-  g.rows_shift = (cb_i8 ? 13 : 11) - (n_in > 2048 ? 1 : 0);
+  g.rows_shift = (code == kCbI8 ? 13 : (code == kCbF16 ? 12 : 11)) - (n_in > 2048 ? 1 : 0);
   g.n_buckets = (K + (1 << g.rows_shift) - 1) >> g.rows_shift;
   const size_t E = (size_t)n_in * n_out;
   g.off_seg = 0;
@@ -203,7 +203,7 @@ struct BucketArgs {
   BucketHead h[kMaxGroup];
 };
 
-hipError_t launch_bucket(bool cb_i8, int gb_kind, const BucketArgs&, int blocks, int heads, hipStream_t);
+hipError_t launch_bucket(int code, int gb_kind, const BucketArgs&, int blocks, int heads, hipStream_t);
 // One-time regrouping of a layer into the layout above (three kernels: count, scan, fill).
 hipError_t launch_bucket_prepare(const LayerPtrs&, int idx_u32, int gb_kind, int n_in, int n_out,
                                  const BucketGeom&, void* prepared, hipStream_t);

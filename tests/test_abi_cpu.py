@@ -157,17 +157,23 @@ def test_byte_coded_layers_plan_and_prepare():
     assert 5 * E < need < 5 * E + (1 << 17)              # u16 input + u16 local id + 1-byte gain code
 
 
-def test_fp16_codebook_layers_plan_but_do_not_prepare():
+def test_fp16_codebook_layers_plan_and_prepare():
     L = kb.lib()
     d = _desc(n_in=2048, n_out=1024, K=65536, cb_dtype=kb.KAN_F16, gb_dtype=kb.KAN_F16, codebook=0x4004)
     for B, path, name in ((1, kb.KAN_PATH_GATHER, b"kan_gather_bt1"), (16, kb.KAN_PATH_GATHER, b"kan_fused_f32"),
                           (16, kb.KAN_PATH_MFMA, b"kan_fused_f16"), (1024, kb.KAN_PATH_AUTO, b"kan_mfma")):
         assert L.kan_vq_planned_kernel(C.byref(d), B, 1, path) == name
         assert L.kan_vq_workspace_bytes(C.byref(d), 1, 1, B, path) != kb.SIZE_INVALID
-    assert L.kan_vq_prepared_bytes(C.byref(d)) == 0
-    assert L.kan_vq_prepare(C.byref(d), FAKE, 1 << 30, None) == kb.KAN_ERR_UNSUPPORTED
-    d.prepared = 0x100000                                # a buffer made for another layer is not used
-    assert L.kan_vq_planned_kernel(C.byref(d), 1, 1, kb.KAN_PATH_GATHER) == b"kan_gather_bt1"
+    E = 2048 * 1024
+    need = L.kan_vq_prepared_bytes(C.byref(d))
+    assert 6 * E < need < 6 * E + 16 * 1024 * 4 * 2 + (1 << 17)   # 16 buckets of 4096 fp16 rows: 16 segment tables
+    assert L.kan_vq_prepare(C.byref(d), FAKE, need - 1, None) == kb.KAN_ERR_WORKSPACE
+    d.prepared = 0x100000
+    assert L.kan_vq_planned_kernel(C.byref(d), 1, 1, kb.KAN_PATH_GATHER) == b"kan_gather_bt1"   # codebook not 16-byte aligned
+    d.codebook = 0x4000
+    assert L.kan_vq_planned_kernel(C.byref(d), 1, 1, kb.KAN_PATH_GATHER) == b"kan_bucket"
+    assert L.kan_vq_planned_kernel(C.byref(d), 4, 1, kb.KAN_PATH_AUTO) == b"kan_bucket"
+    assert L.kan_vq_planned_kernel(C.byref(d), 8, 1, kb.KAN_PATH_GATHER) == b"kan_fused_f32"
 
 
 def test_assign_argument_errors():

@@ -1,6 +1,6 @@
 """GPU parity for fp16 codebooks (Table 1 lists FP32, FP16 and Int8 codebook precisions):
 every kernel family against the float64 oracle, gathered rows bit-exact, ragged shapes,
-both edge rules, a two-layer head.  The prepared (bucket) layout does not take fp16 rows."""
+both edge rules, a two-layer head, the prepared (bucket) layout."""
 import numpy as np
 import pytest
 
@@ -92,13 +92,39 @@ def test_f16cb_config3_shaped_head(kb, B, path):
     assert ko.error_report(y[rows], y_ref)["headline"] <= tol
 
 
-def test_f16cb_has_no_prepared_layout_and_no_byte_coded_gains(kb):
-    P = synth.make_layer(64, 64, 32, 500, cb_dtype="f16", gb_dtype="f16")
-    L = kb.VQLayer(P)
-    assert kb.kan_vq_prepared_bytes(L) == 0
-    with pytest.raises(kb.KanError) as e:
-        L.prepare()
-    assert e.value.status == kb.KAN_ERR_UNSUPPORTED
+@pytest.mark.parametrize("gb_dtype", ["f32", "f16"])
+@pytest.mark.parametrize("rule", ["bspline", "pli"])
+def test_f16cb_prepared_layer(kb, gb_dtype, rule):
+    """Buckets of 4096 fp16 rows: 5 buckets, odd and even row offsets inside a dword, batch 1..4."""
+    P = synth.make_layer(66, 300, 200, 20000, cb_dtype="f16", gb_dtype=gb_dtype)
+    P.idx.reshape(-1)[:6] = [0, 1, 4095, 4096, 19999, 8191]
+    L = kb.VQLayer(P, rule=kb.KAN_RULE_PLI2 if rule == "pli" else kb.KAN_RULE_BSPLINE3).prepare()
+    assert kb.kan_vq_prepared_bytes(L) == L.prepared.numel() > 0
+    plain = kb.VQLayer(P, rule=kb.KAN_RULE_PLI2 if rule == "pli" else kb.KAN_RULE_BSPLINE3)
+    for B in (1, 3, 4):
+        x = synth.make_x(B + 40, B, 300)
+        x[0, 0], x[-1, -1] = 1.0, -1.0
+        assert kb.kan_vq_planned_kernel(L, B, 1, kb.KAN_PATH_AUTO) == "kan_bucket"
+        y = kb.kan_vq_layer_forward(L, to_dev(x)).cpu().numpy()
+        y_ref, A = ko.vq_layer_forward(x, **P.as_dict(), return_abs=True, rule=rule)
+        rep = ko.error_report(y, y_ref, A)
+        assert rep["headline"] <= TOL_FP32 and rep["strict"] <= TOL_FP32, (B, rep)
+        y_plain = kb.kan_vq_layer_forward(plain, to_dev(x), path=kb.KAN_PATH_GATHER).cpu().numpy()
+        assert np.abs(y - y_plain).max() <= 2 * TOL_FP32 * np.abs(y_ref).max()
+
+
+@pytest.mark.parametrize("B", [1, 2, 4])
+def test_f16cb_config3_shaped_head_prepared(kb, B):
+    Ps = synth.config3_layers(gb_dtype="f16", cb_dtype="f16")
+    x = synth.make_x(B + 11, B, Ps[0].idx.shape[0])
+    Ls = [kb.VQLayer(P).prepare() for P in Ps]
+    assert kb.kan_vq_planned_kernel(Ls[0], B, 1, kb.KAN_PATH_AUTO) == "kan_bucket"
+    y = kb.kan_vq_head_forward([Ls], to_dev(x))[0].cpu().numpy()
+    y_ref = ko.vq_head_forward(x, [p.as_dict() for p in Ps])
+    assert ko.error_report(y, y_ref)["headline"] <= TOL_FP32
+
+
+def test_f16cb_takes_no_byte_coded_gains(kb):
     Q = synth.make_layer(65, 16, 8, 50, cb_dtype="i8", gb_dtype="q8")
     Lq = kb.VQLayer(Q)
     Lq.desc.cb_dtype = kb.KAN_F16

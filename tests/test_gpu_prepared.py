@@ -29,7 +29,7 @@ def kb():
 
 def _bucket_rows(P):
     """Codewords per bucket: 80 KB of rows, 40 KB for layers with more than 2048 inputs."""
-    rows = 8192 if P.codebook.dtype == np.int8 else 2048
+    rows = {np.dtype(np.int8): 8192, np.dtype(np.float16): 4096}.get(P.codebook.dtype, 2048)
     return rows // 2 if P.idx.shape[0] > 2048 else rows
 
 
@@ -126,6 +126,8 @@ def _check_tables(tables, seg, nb, n_in, n_out):
     (37, 29, 20000, "i8", "f16", "u16"),       # 3 buckets, the last one partial
     (64, 32, 256, "f32", "f32", "u16"),        # one bucket
     (130, 300, 70000, "f32", "f16", "u32"),    # 35 fp32 buckets
+    (77, 130, 9000, "f16", "f16", "u16"),      # 3 fp16 buckets of 4096 rows, the last one partial
+    (2050, 11, 4100, "f16", "f32", "u16"),     # more than 2048 inputs: fp16 buckets of 2048 rows
     (2048, 64, 65536, "i8", "f16", "u16"),
     (2100, 9, 30000, "i8", "f32", "u16"),      # more than 2048 inputs: buckets of 4096 rows
 ])
@@ -215,7 +217,7 @@ def test_config5_shape_prepared_batch2(kb, variant):
 
 @pytest.mark.parametrize("n_in,n_out,K,B", [(1, 1, 1, 1), (3, 21, 5, 2), (130, 67, 9000, 3), (257, 530, 20000, 1),
                                             (1000, 264, 8193, 4), (4096, 8, 1000, 1), (40, 1500, 65536, 1)])
-@pytest.mark.parametrize("cb,gb", [("i8", "f16"), ("f32", "f32")])
+@pytest.mark.parametrize("cb,gb", [("i8", "f16"), ("f32", "f32"), ("f16", "f16")])
 def test_ragged_shapes_prepared(kb, n_in, n_out, K, B, cb, gb):
     P = synth.make_layer(n_in * 7 + n_out, n_in, n_out, K, cb_dtype=cb, gb_dtype=gb)
     x = synth.make_x(B, B, n_in)

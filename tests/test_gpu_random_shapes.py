@@ -39,7 +39,7 @@ def _cases(n=120, seed=20251127):
         idx = "u32" if K > 65536 else str(rng.choice(["u16", "u32"]))
         out.append(dict(seed=1000 + c, n_in=n_in, n_out=n_out, K=K, cb=cb, gb=gb, idx=idx, B=int(rng.choice(bs)),
                         rule=str(rng.choice(["bspline", "pli"])), dist=str(rng.choice(["uniform", "zipf", "zipf-sorted"])),
-                        prepared=bool(rng.integers(0, 2)) and cb != "f16"))
+                        prepared=bool(rng.integers(0, 2))))
     return out
 
 
