@@ -160,15 +160,21 @@ LayerPlan plan_mfma(int n_in, int n_out, int64_t B, int n_heads, int idx_u32, in
   p.name = "kan_mfma";
   p.cfg.bt = kMfmaTileM;
   p.cfg.jpl = 1;
-  p.cfg.wj = 2;
   p.cfg.idx_u32 = idx_u32;
   p.cfg.gb_kind = gb_kind;
   p.cfg.code = code;
-  p.n_jt = (n_out + kMfmaTileN - 1) / kMfmaTileN;
   p.n_bt = (int)((B + kMfmaTileM - 1) / kMfmaTileM);
+  const long long max_chunks = n_in / kMfmaMinRows;
+  // Column blocks per wave: 256-output tiles, unless they would need more than eight chunks
+  // of inputs to give every CU two workgroups.  128-output tiles then halve the chunks and
+  // with them the partial sums written and read back (the main loop itself is about a
+  // tenth slower with the narrow tile: twice the basis-tile reads per MFMA).
+  const long long wide = (long long)n_heads * ((n_out + kMfmaTileN - 1) / kMfmaTileN) * p.n_bt;
+  p.cfg.wj = (wide * 8 < kMfmaTargetWorkgroups || n_out <= kMfmaTileN / 2) ? 1 : 2;
+  const int tile_n = p.cfg.wj == 1 ? kMfmaTileN / 2 : kMfmaTileN;
+  p.n_jt = (n_out + tile_n - 1) / tile_n;
   const long long base = (long long)n_heads * p.n_jt * p.n_bt;
   long long chunks = kMfmaTargetWorkgroups / (base > 0 ? base : 1);
-  const long long max_chunks = n_in / kMfmaMinRows;
   if (chunks > max_chunks) chunks = max_chunks;
   if (chunks < 1) chunks = 1;
   int rows = (int)((n_in + chunks - 1) / chunks);
@@ -372,7 +378,7 @@ kan_status run_layer_group(const LayerPlan& p, GatherArgs& a, const void* const*
     m.apply_tanh = tanh_in_kernel;
     for (int h = 0; h < heads; ++h) m.scale[h] = p.cfg.code == kCbI8 ? a.h[h].scale : 1.0f;
     dim3 grid((unsigned)(p.n_jt * p.n_bt), (unsigned)p.n_chunks, (unsigned)heads);
-    st = run(p.name, s, [&] { return launch_mfma(m, p.cfg.bt, grid, s); });
+    st = run(p.name, s, [&] { return launch_mfma(m, p.cfg.bt, p.cfg.wj == 1 ? kMfmaTileN / 2 : kMfmaTileN, grid, s); });
   } else if (p.kind == kPlanBucket) {
     const BucketGeom g = bucket_geometry(a.n_in, a.n_out, (int)(a.cb_bytes / cb_row_bytes(p.cfg.code)), p.cfg.code,
                                          p.cfg.gb_kind);

@@ -47,10 +47,8 @@ namespace {
 
 constexpr int kThreads = 256;          // preparation kernels
 constexpr int kMfmaThreads = 256;      // contraction kernel: 4 waves along the outputs
-constexpr int BN = 256;                // outputs per workgroup tile (samples per tile: 32 * MB)
 constexpr int IT = 8;                  // input rows per step (80 k-slots = 5 MFMA k-steps)
 constexpr int LDK = 88;                // LDS row stride in halves (176 B = 11 x 16 B)
-constexpr int NB = 2;                  // MFMA column blocks per wave (64 outputs)
 constexpr int kBufferFlags = 0x00020000;   // buffer resource word 3: raw 32-bit data format, no swizzle
 
 typedef unsigned int u32x4 __attribute__((ext_vector_type(4)));
@@ -169,9 +167,14 @@ __global__ __launch_bounds__(256) void kan_prep_basis_kernel(const float* __rest
 // MB = MFMA row blocks per wave: tile of 32*MB samples.  MB = 2 keeps two workgroups on a
 // CU (a 128-sample tile, MB = 4, halves the fragment bytes per MFMA but leaves one wave per
 // SIMD and measured no faster on configurations 3 and 5).
-template <int MB>
-__global__ __launch_bounds__(kMfmaThreads, 2) void kan_mfma_kernel(const MfmaArgs a) {
+//
+// NB = MFMA column blocks per wave: the four waves cover 128 * NB outputs.  NB = 1 is for
+// layers whose grid of 256-output tiles would leave CUs idle: half the accumulators and
+// fragment registers, three workgroups per CU.
+template <int MB, int NB>
+__global__ __launch_bounds__(kMfmaThreads, NB == 1 ? 3 : 2) void kan_mfma_kernel(const MfmaArgs a) {
   constexpr int BM = 32 * MB;
+  constexpr int BN = 4 * 32 * NB;      // outputs per workgroup tile
   constexpr int NPAIR = MB;            // (sample, input) pairs per thread and step
   __shared__ __attribute__((aligned(16))) uint16_t sA[2][BM * LDK];   // Phi tiles [b][k], 2 x 22.5 KB
   // Byte-permute selectors: row l, word k builds half-word slots 2k, 2k+1 of an input whose
@@ -204,7 +207,7 @@ __global__ __launch_bounds__(kMfmaThreads, 2) void kan_mfma_kernel(const MfmaArg
   bool j_ok[NB];
 #pragma unroll
   for (int nb = 0; nb < NB; ++nb) {
-    const int j = j0 + wn * 64 + nb * 32 + ln;
+    const int j = j0 + wn * (32 * NB) + nb * 32 + ln;
     j_ok[nb] = j < n_out;
     jc[nb] = min(j, n_out - 1);
   }
@@ -298,8 +301,8 @@ __global__ __launch_bounds__(kMfmaThreads, 2) void kan_mfma_kernel(const MfmaArg
   // covers the rest.
   // The bias sums of the tile's columns are fetched ahead of everything else (thread t owns
   // column j0 + t) and parked in LDS until the epilogue, so their latency is never exposed.
-  static_assert(BN == kMfmaThreads, "one bias column per thread");
-  __shared__ float sBias[BN];
+  static_assert(BN <= kMfmaThreads, "one bias column per thread (the others repeat the last column)");
+  __shared__ float sBias[kMfmaThreads];
   const float* bp = a.bias_partial + (long long)head * a.bp_head_stride + min(j0 + tid, n_out - 1);
   const int rb0 = i_begin / kMfmaPrepRows, rb1 = (i_end + kMfmaPrepRows - 1) / kMfmaPrepRows;
   float bias_v[8];
@@ -354,7 +357,7 @@ __global__ __launch_bounds__(kMfmaThreads, 2) void kan_mfma_kernel(const MfmaArg
   float* dst = a.dst + (long long)head * a.dst_head_stride + (long long)chunk * a.dst_chunk_stride;
 #pragma unroll
   for (int n = 0; n < NB; ++n) {
-    const float bs = sBias[wn * 64 + n * 32 + ln];
+    const float bs = sBias[wn * (32 * NB) + n * 32 + ln];
     if (j_ok[n]) {
 #pragma unroll
       for (int m = 0; m < MB; ++m)
@@ -413,13 +416,15 @@ hipError_t launch_prep_basis(const float* x, long long x_head_stride, int x_part
   return hipGetLastError();
 }
 
-hipError_t launch_mfma(const MfmaArgs& a, int tile_m, dim3 grid, hipStream_t s) {
-  if (tile_m != 64) return hipErrorInvalidValue;
+hipError_t launch_mfma(const MfmaArgs& a, int tile_m, int tile_n, dim3 grid, hipStream_t s) {
+  if (tile_m != 64 || (tile_n != 128 && tile_n != 256)) return hipErrorInvalidValue;
+  if ((long long)a.n_jt * tile_n < a.n_out) return hipErrorInvalidValue;
   // one step of coefficient records and one row of basis words must fit a buffer resource
   if ((long long)a.n_out * 10 * (long long)sizeof(uint4) > 0x7fffffffLL ||
       (long long)a.B * (long long)sizeof(uint2) > 0x7fffffffLL)
     return hipErrorInvalidValue;
-  hipLaunchKernelGGL(kan_mfma_kernel<2>, grid, dim3(kMfmaThreads), 0, s, a);
+  if (tile_n == 128) hipLaunchKernelGGL((kan_mfma_kernel<2, 1>), grid, dim3(kMfmaThreads), 0, s, a);
+  else hipLaunchKernelGGL((kan_mfma_kernel<2, 2>), grid, dim3(kMfmaThreads), 0, s, a);
   return hipGetLastError();
 }
 

@@ -94,6 +94,28 @@ def test_mfma_config4_multi_head(kb):
         assert ko.error_report(y[h], y_ref)["headline"] <= TOL_MFMA
 
 
+@pytest.mark.parametrize("n_in,n_out,B", [
+    (70, 1900, 2100),      # 8 x 33 tiles of 256 outputs (ragged in both directions): the wide tile
+    (70, 1900, 300),       # 8 x 5 tiles: the narrow tile, 15 tiles of 128 outputs, the last one ragged
+    (200, 100, 5000),      # at most 128 outputs: always the narrow tile, 79 batch tiles
+    (330, 129, 4100),      # one output past a narrow tile on the wide one
+])
+def test_mfma_both_tile_widths_sampled(kb, n_in, n_out, B):
+    """The contraction kernel has a 256-output and a 128-output tile; which one a layer gets
+    depends on how many tiles its grid has.  Sampled outputs against the oracle, and whole
+    rows (first, last, one per batch tile boundary) so that every column of a row is checked."""
+    P = synth.make_layer(n_in + n_out + B, n_in, n_out, 3000, cb_dtype="i8", gb_dtype="f16")
+    x = synth.make_x(B + 1, B, n_in)
+    (L,) = gpu_layers([P])
+    y = kb.kan_vq_layer_forward(L, to_dev(x), path=kb.KAN_PATH_MFMA).cpu().numpy()
+    assert np.isfinite(y).all()
+    check_layer_output(y, x, P, TOL_MFMA, n_samples=96, full=False, seed=B)
+    rows = np.array([0, 63, 64, B // 2, B - 65, B - 1])
+    y_ref, A = ko.vq_layer_forward(x[rows], **P.as_dict(), return_abs=True)
+    rep = ko.error_report(y[rows], y_ref, A)
+    assert rep["headline"] <= TOL_MFMA and rep["strict"] <= TOL_MFMA, rep
+
+
 @pytest.mark.parametrize("variant", ["i8", "f32"])
 def test_mfma_config5_sampled(kb, variant):
     (P,), x = synth.config5(variant)
