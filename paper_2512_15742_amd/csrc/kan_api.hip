@@ -144,8 +144,7 @@ LayerPlan plan_gather(int n_in, int n_out, int64_t B, int n_heads, int idx_u32, 
 
 // Matrix-core path: 64 x 256 (samples x outputs) tiles, i split so that every CU
 // has two workgroups.
-constexpr int kMfmaTileM = 64;
-constexpr int kMfmaTileN = 256;
+constexpr int kMfmaTileN = 128;
 constexpr int kMfmaRowsStep = kMfmaPrepRows;   // chunk boundaries coincide with partial bias sums
 constexpr int kMfmaTargetWorkgroups = 512;
 constexpr int kMfmaMinRows = 64;
@@ -158,21 +157,20 @@ LayerPlan plan_mfma(int n_in, int n_out, int64_t B, int n_heads, int idx_u32, in
   p.mfma = true;
   p.kind = kPlanMfma;
   p.name = "kan_mfma";
-  p.cfg.bt = kMfmaTileM;
   p.cfg.jpl = 1;
+  p.cfg.wj = 1;
   p.cfg.idx_u32 = idx_u32;
   p.cfg.gb_kind = gb_kind;
   p.cfg.code = code;
-  p.n_bt = (int)((B + kMfmaTileM - 1) / kMfmaTileM);
   const long long max_chunks = n_in / kMfmaMinRows;
-  // Column blocks per wave: 256-output tiles, unless they would need more than eight chunks
-  // of inputs to give every CU two workgroups.  128-output tiles then halve the chunks and
-  // with them the partial sums written and read back (the main loop itself is about a
-  // tenth slower with the narrow tile: twice the basis-tile reads per MFMA).
-  const long long wide = (long long)n_heads * ((n_out + kMfmaTileN - 1) / kMfmaTileN) * p.n_bt;
-  p.cfg.wj = (wide * 8 < kMfmaTargetWorkgroups || n_out <= kMfmaTileN / 2) ? 1 : 2;
-  const int tile_n = p.cfg.wj == 1 ? kMfmaTileN / 2 : kMfmaTileN;
-  p.n_jt = (n_out + tile_n - 1) / tile_n;
+  // Tiles of 128 outputs by 128 samples (half the coefficient bytes per MFMA through the
+  // vector cache), unless their grid would need more than eight chunks of inputs to give
+  // every CU two workgroups: 64-sample tiles then halve the chunks and with them the
+  // partial sums written and read back.
+  p.n_jt = (n_out + kMfmaTileN - 1) / kMfmaTileN;
+  const long long big = (long long)n_heads * p.n_jt * ((B + 127) / 128);
+  p.cfg.bt = big * 8 >= kMfmaTargetWorkgroups ? 128 : 64;
+  p.n_bt = (int)((B + p.cfg.bt - 1) / p.cfg.bt);
   const long long base = (long long)n_heads * p.n_jt * p.n_bt;
   long long chunks = kMfmaTargetWorkgroups / (base > 0 ? base : 1);
   if (chunks > max_chunks) chunks = max_chunks;
@@ -291,7 +289,7 @@ struct WsLayout {
   size_t total() const { return (n_layers > 1 ? 2 * hidden : 0) + partial + partial2 + cf + bp + u; }
 };
 
-size_t mfma_cf_records(int n_in, int n_out) { return (size_t)((n_in + 7) / 8) * 5 * (size_t)n_out * 2; }
+size_t mfma_cf_records(int n_in, int n_out) { return (size_t)((n_in + 15) / 16) * 20 * (size_t)n_out; }
 size_t mfma_bp_floats(int n_in, int n_out) { return (size_t)((n_in + kMfmaPrepRows - 1) / kMfmaPrepRows) * n_out; }
 
 hipError_t launch_gather(const LayerPlan& p, const GatherArgs& a, int heads, hipStream_t s) {
@@ -378,7 +376,7 @@ kan_status run_layer_group(const LayerPlan& p, GatherArgs& a, const void* const*
     m.apply_tanh = tanh_in_kernel;
     for (int h = 0; h < heads; ++h) m.scale[h] = p.cfg.code == kCbI8 ? a.h[h].scale : 1.0f;
     dim3 grid((unsigned)(p.n_jt * p.n_bt), (unsigned)p.n_chunks, (unsigned)heads);
-    st = run(p.name, s, [&] { return launch_mfma(m, p.cfg.bt, p.cfg.wj == 1 ? kMfmaTileN / 2 : kMfmaTileN, grid, s); });
+    st = run(p.name, s, [&] { return launch_mfma(m, p.cfg.bt, kMfmaTileN, grid, s); });
   } else if (p.kind == kPlanBucket) {
     const BucketGeom g = bucket_geometry(a.n_in, a.n_out, (int)(a.cb_bytes / cb_row_bytes(p.cfg.code)), p.cfg.code,
                                          p.cfg.gb_kind);

@@ -23,18 +23,18 @@
 //                   (always clear) sign bits; 8 bytes per pair, stored transposed
 //                   ([input][sample]) so that the contraction kernel reads it
 //                   coalesced.
-//   kan_mfma        64 samples x 256 outputs per workgroup, 4 waves side by side
-//                   along the outputs (wave tile 64 x 64); two workgroups share a
-//                   CU and drift apart, so one's MFMAs overlap the other's tile
-//                   generation and LDS latency.  Per step of 8 inputs:
-//                   the Phi tile is built in LDS (double buffered) from the packed
-//                   basis words with byte permutes whose selectors come from a
-//                   7-entry table (one row per span), the Chat fragments stream
-//                   from memory straight into registers one step ahead, 20
-//                   MFMAs per wave.
-// k order inside a step of 8 inputs (80 slots = 5 MFMA k-steps x 2 lane halves x 8):
-// k-step s < 4, half h carries coefficients 0..7 of input 4h+s; k-step 4, half h
-// carries coefficients 8, 9 of inputs 4h..4h+3.
+//   kan_mfma        64 or 128 samples x 128 outputs per workgroup, 4 waves side by
+//                   side along the outputs; two or three workgroups share a CU and
+//                   drift apart, so one's MFMAs overlap the other's tile generation
+//                   and LDS latency.  Per step of 16 inputs: the Phi tile (the two
+//                   stored values of every group of four k-slots, plus their
+//                   positions) is built in LDS (double buffered) from the packed basis
+//                   words with byte permutes whose selectors come from a 7-entry
+//                   table (one row per span), the Chat fragments stream from memory
+//                   straight into registers a step and a half ahead, and the
+//                   contraction runs on the sparse matrix instruction
+//                   v_smfmac_f32_32x32x32_f16 (5 per row block and step).
+// k order inside a step: see kan_mfma_kernel.
 
 #include <type_traits>
 
@@ -47,19 +47,26 @@ namespace {
 
 constexpr int kThreads = 256;          // preparation kernels
 constexpr int kMfmaThreads = 256;      // contraction kernel: 4 waves along the outputs
-constexpr int IT = 8;                  // input rows per step (80 k-slots = 5 MFMA k-steps)
-constexpr int LDK = 88;                // LDS row stride in halves (176 B = 11 x 16 B)
+constexpr int IT = 16;                 // input rows per step (160 k-slots = 40 groups of four = 5 sparse MFMAs of K = 32)
+constexpr int kRowBytes = 208;         // LDS row of the Phi tile: 160 B of weights, 2 x 16 B of index words, 16 B of
+                                       // padding (52 dwords: sixteen consecutive rows start in sixteen different banks)
+constexpr int kIdxOffset = 160;        // index words of the row: [lane half][S = 0..4] as u16, 16 bytes per lane half
 constexpr int kBufferFlags = 0x00020000;   // buffer resource word 3: raw 32-bit data format, no swizzle
 
 typedef unsigned int u32x4 __attribute__((ext_vector_type(4)));
 typedef unsigned int u32x2 __attribute__((ext_vector_type(2)));
+typedef _Float16 h16x16 __attribute__((ext_vector_type(16)));
 
 // ---- kan_prep_coef ------------------------------------------------------------------
-// Chat as uint4 records: rec[((step*5 + ks) * 2 + h) * n_out + j], step = i / 8, so that
-// both the writer and the MFMA B-operand lanes touch 16-byte items contiguous in j.
-// A workgroup covers 64 output columns x 32 input rows: each of its 4 waves takes one
-// step of 8 rows (lanes along the columns), so all loads of an edge's chain
-// (metadata, then codeword) are in flight at once across many small waves.
+// Chat as uint4 records: rec[(((step*5 + S) * 2 + h) * 2 + a) * n_out + j], step = i / 16: the
+// half a (elements 8a .. 8a+7) of the B operand of lane half h in sparse MFMA S of the step,
+// so that both the writer and the MFMA B-operand lanes touch 16-byte items contiguous in j.
+// Input ii = i % 16 of a step puts its coefficients (0,5,1,6,2,7,3,8) into record
+// (S = ii / 4, h = (ii % 4) / 2, a = ii % 2) and its coefficients (4,9) into word ii % 4 of
+// record (S = 4, h = ii / 8, a = (ii % 8) / 4): see the k order at kan_mfma_kernel.
+// A workgroup covers 64 output columns x 32 input rows: each of its 4 waves takes 8 rows
+// (half a step; lanes along the columns), so all loads of an edge's chain (metadata, then
+// codeword) are in flight at once across many small waves.
 template <typename IdxT, typename GbT, typename CbT>
 __global__ __launch_bounds__(kThreads) void kan_prep_coef_kernel(const PrepCoefArgs a) {
   __shared__ float sb[4][64];
@@ -75,14 +82,15 @@ __global__ __launch_bounds__(kThreads) void kan_prep_coef_kernel(const PrepCoefA
   uint4* cf = a.cf + (long long)head * a.cf_head_stride;
   float* bp = a.bias_partial + (long long)head * a.bp_head_stride;
   const int n_in = a.n_in, n_out = a.n_out;
-  const int ib = blockIdx.y * kMfmaPrepRows + wave * IT;
+  const int ib = blockIdx.y * kMfmaPrepRows + wave * 8;
   float bs = 0.f;
-  if (j < n_out && ib < n_in) {
+  if (j < n_out && ib < (n_in + IT - 1) / IT * IT) {      // rows past the end of a ragged last step are written as zeros
     const long long step = ib / IT;
-    uint32_t id[IT];
-    float g[IT];
+    const int wh = (ib / 8) & 1;                          // which half of the step these 8 rows are
+    uint32_t id[8];
+    float g[8];
 #pragma unroll
-    for (int r = 0; r < IT; ++r) {
+    for (int r = 0; r < 8; ++r) {
       const int i = ib + r;
       const bool ok = i < n_in;
       const long long e = (long long)min(i, n_in - 1) * n_out + j;
@@ -92,23 +100,28 @@ __global__ __launch_bounds__(kThreads) void kan_prep_coef_kernel(const PrepCoefA
       load_gain<GbT, 1>(gain + e, qp, gv);
       load_bias<GbT, 1>(bias + e, qp, bv);
       id[r] = idv[0];
-      g[r] = ok ? gv[0] : 0.f;          // rows past the end of a ragged last step are zero
+      g[r] = ok ? gv[0] : 0.f;
       bs += ok ? bv[0] : 0.f;
     }
-    RawRow<CbT> raw[IT];
+    RawRow<CbT> raw[8];
 #pragma unroll
-    for (int r = 0; r < IT; ++r) load_row<CbT>(cb, id[r], raw[r]);
+    for (int r = 0; r < 8; ++r) load_row<CbT>(cb, id[r], raw[r]);
 #pragma unroll
-    for (int h = 0; h < 2; ++h) {
+    for (int q = 0; q < 2; ++q) {
+      const long long S = 2 * wh + q;
       uint32_t tail[4];
 #pragma unroll
-      for (int s = 0; s < 4; ++s) {
+      for (int t = 0; t < 4; ++t) {                       // ii = 8 wh + 4 q + t: h = t / 2, a = t % 2
         uint32_t w[5];
-        dequant_row<CbT>(raw[4 * h + s], g[4 * h + s], w);
-        cf[((step * 5 + s) * 2 + h) * n_out + j] = make_uint4(w[0], w[1], w[2], w[3]);
-        tail[s] = w[4];
+        dequant_row<CbT>(raw[4 * q + t], g[4 * q + t], w);   // (c0,c1) (c2,c3) (c4,c5) (c6,c7) (c8,c9)
+        const uint32_t p0 = __builtin_amdgcn_perm(w[2], w[0], 0x07060100u);   // (c0, c5)
+        const uint32_t p1 = __builtin_amdgcn_perm(w[3], w[0], 0x05040302u);   // (c1, c6)
+        const uint32_t p2 = __builtin_amdgcn_perm(w[3], w[1], 0x07060100u);   // (c2, c7)
+        const uint32_t p3 = __builtin_amdgcn_perm(w[4], w[1], 0x05040302u);   // (c3, c8)
+        tail[t] = __builtin_amdgcn_perm(w[4], w[2], 0x07060100u);             // (c4, c9)
+        cf[(((step * 5 + S) * 2 + (t >> 1)) * 2 + (t & 1)) * n_out + j] = make_uint4(p0, p1, p2, p3);
       }
-      cf[((step * 5 + 4) * 2 + h) * n_out + j] = make_uint4(tail[0], tail[1], tail[2], tail[3]);
+      cf[(((step * 5 + 4) * 2 + wh) * 2 + q) * n_out + j] = make_uint4(tail[0], tail[1], tail[2], tail[3]);
     }
   }
   sb[wave][lane] = bs;
@@ -164,29 +177,67 @@ __global__ __launch_bounds__(256) void kan_prep_basis_kernel(const float* __rest
 }
 
 // ---- kan_mfma ---------------------------------------------------------------------------
-// MB = MFMA row blocks per wave: tile of 32*MB samples.  MB = 2 keeps two workgroups on a
-// CU (a 128-sample tile, MB = 4, halves the fragment bytes per MFMA but leaves one wave per
-// SIMD and measured no faster on configurations 3 and 5).
+// The Phi operand is 60 % structural zeros: of an input's ten basis values only four
+// consecutive ones (l .. l+3, l = span) are nonzero.  Coefficients m and m+5 are therefore
+// never both under the window, so the k order
+//     group of four k-slots = [m, m+5, m', m'+5]
+// holds at most two nonzeros per group whatever the span: exactly the 2:4 structure of the
+// sparse matrix instruction v_smfmac_f32_32x32x32_f16, which takes the A operand as the two
+// stored values of every group plus two 2-bit positions, and runs K = 32 in the time the
+// dense instruction runs K = 16.  A step of 16 inputs is 40 groups = 5 such MFMAs:
+//   S = 0..3   groups (0,5,1,6) and (2,7,3,8) of inputs 4S .. 4S+3
+//   S = 4      groups (4,9 of input 2g; 4,9 of input 2g+1), g = 0..7
+// Operand layout of the instruction (lane = 32 * half + n): the A lane (row, half a) holds
+// stored values e = 0..7, value pair t = e / 2 belonging to the group at B elements
+// 8a + 4 (t % 2) .. + 3 of B lane half h = t / 2, at the positions given by bits 4t .. 4t+3 of
+// the lane's 16 index bits (ABID picks the low or high half of the index register).
 //
-// NB = MFMA column blocks per wave: the four waves cover 128 * NB outputs.  NB = 1 is for
-// layers whose grid of 256-output tiles would leave CUs idle: half the accumulators and
-// fragment registers, three workgroups per CU.
+// MB = MFMA row blocks per wave (tile of 32 MB samples), NB = column blocks per wave (the
+// four waves cover 128 NB outputs).  MB = 4 reads half the Chat bytes per MFMA; MB = 2 is
+// for layers whose grid of 128-sample tiles would leave CUs idle (three workgroups per CU).
+
+// Per span l: byte-permute selectors that pick, from the four fp16 weights {w23:w01} of an
+// input, the stored values of its pairs (m, m+5): word 0 pairs 0 and 1, word 1 pairs 2 and 3,
+// word 2 pair 4 (high half zero); word 3 the index byte of the input's two full groups
+// (nibble = position of the first value | position of the second << 2), word 4 whether
+// pair 4 takes coefficient 9.  Selector byte 0x0c yields 0.
+__device__ __forceinline__ void fill_sparse_selectors(uint32_t (*sel)[8], int tid) {
+  if (tid < kSpans) {
+    const int l = tid;
+    uint32_t half_sel[5], hi[5];
+#pragma unroll
+    for (int p = 0; p < 5; ++p) {
+      int k = -1;
+      hi[p] = 0;
+      if (p >= l && p <= l + 3) k = p - l;
+      else if (p + 5 >= l && p + 5 <= l + 3) { k = p + 5 - l; hi[p] = 1; }
+      half_sel[p] = k >= 0 ? (uint32_t)((2 * k) | ((2 * k + 1) << 8)) : 0x0c0cu;
+    }
+    sel[l][0] = half_sel[0] | (half_sel[1] << 16);
+    sel[l][1] = half_sel[2] | (half_sel[3] << 16);
+    sel[l][2] = half_sel[4] | 0x0c0c0000u;
+    sel[l][3] = (hi[0] | ((2u + hi[1]) << 2)) | ((hi[2] | ((2u + hi[3]) << 2)) << 4);
+    sel[l][4] = hi[4];
+    sel[l][5] = sel[l][6] = sel[l][7] = 0;
+  }
+}
+
 template <int MB, int NB>
-__global__ __launch_bounds__(kMfmaThreads, NB == 1 ? 3 : 2) void kan_mfma_kernel(const MfmaArgs a) {
-  constexpr int BM = 32 * MB;
+__global__ __launch_bounds__(kMfmaThreads, MB == 2 ? 3 : 2) void kan_mfma_kernel(const MfmaArgs a) {
+  constexpr int BM = 32 * MB;          // samples per workgroup tile (MB = MFMA row blocks per wave)
   constexpr int BN = 4 * 32 * NB;      // outputs per workgroup tile
-  constexpr int NPAIR = MB;            // (sample, input) pairs per thread and step
-  __shared__ __attribute__((aligned(16))) uint16_t sA[2][BM * LDK];   // Phi tiles [b][k], 2 x 22.5 KB
-  // Byte-permute selectors: row l, word k builds half-word slots 2k, 2k+1 of an input whose
-  // weights w0..w3 (bytes 0..7 of {w23:w01}) sit at slots l..l+3; selector byte 0x0c yields 0.
+  constexpr int NSUB = BM / 64;        // quarters of a step (inputs 4 ph .. 4 ph + 3) per thread
+  constexpr int NPAIR = 4 * NSUB;      // (sample, input) pairs per thread and step
+  static_assert(BM * 4 == kMfmaThreads * NSUB && IT == 16, "threads of a sample row share out the four quarters of a step");
+  __shared__ __attribute__((aligned(16))) unsigned char sA[2][BM * kRowBytes];   // Phi tiles, 2 x 13 KB
   __shared__ __attribute__((aligned(16))) uint32_t sSel[kSpans][8];
-  fill_weight_selectors(sSel, threadIdx.x);
+  fill_sparse_selectors(sSel, threadIdx.x);
   __syncthreads();
 
   const int tid = threadIdx.x;
   const int lane = tid & 63, wave = tid >> 6;
   const int ln = lane & 31, lh = lane >> 5;
-  const int wm = 0, wn = wave;
+  const int wn = wave;
   const int head = blockIdx.z, chunk = blockIdx.y;
   const int jt = blockIdx.x % a.n_jt, bt = blockIdx.x / a.n_jt;
   const int b0 = bt * BM, j0 = jt * BN;
@@ -200,8 +251,9 @@ __global__ __launch_bounds__(kMfmaThreads, NB == 1 ? 3 : 2) void kan_mfma_kernel
   const uint4* cf = a.cf + (long long)head * a.cf_head_stride;
   const uint2* W = a.W + (long long)head * a.w_head_stride;
 
-  // Phi generation: this thread owns sample row pb and inputs NPAIR*ph .. NPAIR*ph+NPAIR-1 of every step.
-  const int pb = tid & (BM - 1), ph = tid / BM;
+  // Phi generation: this thread owns sample row pb and inputs 4 ph0 .. 4 ph0 + NPAIR - 1 of every step.
+  const int pb = tid & (BM - 1);
+  const int ph0 = __builtin_amdgcn_readfirstlane(tid / BM) * NSUB;      // first quarter of this thread
   // B operand: columns jc[nb]
   int jc[NB];
   bool j_ok[NB];
@@ -223,13 +275,11 @@ __global__ __launch_bounds__(kMfmaThreads, NB == 1 ? 3 : 2) void kan_mfma_kernel
   // Every load of the main loop is a buffer load: the resource (base, size) is rebuilt on the
   // scalar unit for each step, the lane offsets never change, so a load costs no vector
   // arithmetic.  Offsets stay below 2^31 because a resource spans one step of one head.
-  static_assert(BM % 64 == 0, "a wave generates the Phi rows of one input group");
-  const int ph_u = __builtin_amdgcn_readfirstlane(ph);
   const uint32_t u_off = (uint32_t)min(b0 + pb, B - 1) * (uint32_t)sizeof(uint2);
   const char* w_bytes = (const char*)W;
   const uint32_t w_row_bytes = (uint32_t)B * (uint32_t)sizeof(uint2);
   auto load_u = [&](int k, uint2 (&uv)[NPAIR]) {       // step index relative to the chunk
-    const int i = i_begin + k * IT + NPAIR * ph_u;
+    const int i = i_begin + k * IT + 4 * ph0;
 #pragma unroll
     for (int q = 0; q < NPAIR; ++q) {
       const char* row = w_bytes + (size_t)min(i + q, n_in - 1) * w_row_bytes;
@@ -239,66 +289,125 @@ __global__ __launch_bounds__(kMfmaThreads, NB == 1 ? 3 : 2) void kan_mfma_kernel
     }
   };
 
-  auto gen_phi = [&](const uint2 (&uv)[NPAIR], uint16_t* tile) {
-    uint16_t* rowp = tile + pb * LDK;
+  // Input 4 ph + q = 4 S + 2 x + a with S = ph: its four stored values go to bytes x * 8 of
+  // fragment (S, a); its pair-4 value to half q of the 8 bytes that fragment (4, ph % 2)
+  // keeps for inputs 4 ph .. 4 ph + 3; index bytes likewise.  (Quarter ph of the step.)
+  auto gen_phi = [&](const uint2 (&uv)[NPAIR], unsigned char* tile) {
+    unsigned char* rowp = tile + pb * kRowBytes;
 #pragma unroll
-    for (int q = 0; q < NPAIR; ++q) {
-      const int ii = NPAIR * ph + q, h = ii >> 2, s = ii & 3;     // input ii of the step: k-step s, lane half h
-      uint32_t l, w01, w23;
-      unpack_basis(uv[q], l, w01, w23);
-      const uint4 sl = *(const uint4*)&sSel[l][0];
-      const uint32_t sh = sSel[l][4];
-      uint4 lo;
-      lo.x = __builtin_amdgcn_perm(w23, w01, sl.x);
-      lo.y = __builtin_amdgcn_perm(w23, w01, sl.y);
-      lo.z = __builtin_amdgcn_perm(w23, w01, sl.z);
-      lo.w = __builtin_amdgcn_perm(w23, w01, sl.w);
-      const uint32_t hi = __builtin_amdgcn_perm(w23, w01, sh);
-      *(uint4*)(rowp + 16 * s + 8 * h) = lo;                    // coefficients 0..7
-      *(uint32_t*)(rowp + 64 + 8 * h + 2 * s) = hi;             // coefficients 8, 9: k-step 4
+    for (int sub = 0; sub < NSUB; ++sub) {
+      const int ph = ph0 + sub;
+      uint32_t v4[4], ib[4], h4[4];
+#pragma unroll
+      for (int q = 0; q < 4; ++q) {
+        uint32_t l, w01, w23;
+        unpack_basis(uv[4 * sub + q], l, w01, w23);
+        const uint4 sl = *(const uint4*)&sSel[l][0];
+        uint2 st;
+        st.x = __builtin_amdgcn_perm(w23, w01, sl.x);
+        st.y = __builtin_amdgcn_perm(w23, w01, sl.y);
+        v4[q] = __builtin_amdgcn_perm(w23, w01, sl.z);
+        ib[q] = sl.w;
+        h4[q] = sSel[l][4];
+        *(uint2*)(rowp + (ph * 2 + (q & 1)) * 16 + (q >> 1) * 8) = st;
+      }
+      uint2 t4;
+      t4.x = v4[0] | (v4[1] << 16);
+      t4.y = v4[2] | (v4[3] << 16);
+      *(uint2*)(rowp + 128 + (ph & 1) * 16 + (ph >> 1) * 8) = t4;
+      *(uint16_t*)(rowp + kIdxOffset + 0 * 16 + ph * 2) = (uint16_t)(ib[0] | (ib[2] << 8));
+      *(uint16_t*)(rowp + kIdxOffset + 1 * 16 + ph * 2) = (uint16_t)(ib[1] | (ib[3] << 8));
+      *(uint8_t*)(rowp + kIdxOffset + (ph & 1) * 16 + 8 + (ph >> 1)) =
+          (uint8_t)((h4[0] | ((2u + h4[1]) << 2)) | ((h4[2] | ((2u + h4[3]) << 2)) << 4));
     }
   };
 
+  // Chat fragments of half a step (S = 2 hs, 2 hs + 1 and half hs of S = 4): 5 uint4 per
+  // column block: [0] (S0, a=0) [1] (S0, a=1) [2] (S1, a=0) [3] (S1, a=1) [4] (S = 4, a = hs),
+  // all of B lane half lh.
   uint32_t b_off[NB];
 #pragma unroll
-  for (int nb = 0; nb < NB; ++nb) b_off[nb] = (uint32_t)(lh * n_out + jc[nb]) * (uint32_t)sizeof(uint4);
+  for (int nb = 0; nb < NB; ++nb) b_off[nb] = (uint32_t)(lh * 2 * n_out + jc[nb]) * (uint32_t)sizeof(uint4);
   const char* cf_bytes = (const char*)cf;
-  const uint32_t ks_bytes = 2u * (uint32_t)n_out * (uint32_t)sizeof(uint4);
-  auto load_b = [&](int k, uint4 (&bf)[NB][5]) {
-    const int step = min(step0 + k, last_step);           // past the end: valid memory, never used
-    const char* sb = cf_bytes + (size_t)step * (5 * ks_bytes);
-    const __amdgpu_buffer_rsrc_t r = __builtin_amdgcn_make_buffer_rsrc((void*)sb, 0, (int)(5 * ks_bytes), kBufferFlags);
+  const uint32_t a_bytes = (uint32_t)n_out * (uint32_t)sizeof(uint4);     // from a = 0 to a = 1
+  const uint32_t s_bytes = 4u * a_bytes;                                  // from S to S + 1
+  auto step_rsrc = [&](int k) {                          // step index relative to the chunk
+    const int step = min(step0 + k, last_step);         // past the end: valid memory, never used
+    const char* sb = cf_bytes + (size_t)step * (5 * s_bytes);
+    return __builtin_amdgcn_make_buffer_rsrc((void*)sb, 0, (int)(5 * s_bytes), kBufferFlags);
+  };
+  auto load_b_main = [&](int k, auto HS, uint4 (&bf)[NB][5]) {
+    constexpr int hs = decltype(HS)::value;
+    const __amdgpu_buffer_rsrc_t r = step_rsrc(k);
 #pragma unroll
-    for (int ks = 0; ks < 5; ++ks)
+    for (int u = 0; u < 4; ++u)
 #pragma unroll
       for (int nb = 0; nb < NB; ++nb) {
-        const u32x4 v = __builtin_amdgcn_raw_buffer_load_b128(r, (int)b_off[nb], (int)(ks * ks_bytes), 0);
-        bf[nb][ks] = make_uint4(v.x, v.y, v.z, v.w);
+        const u32x4 v = __builtin_amdgcn_raw_buffer_load_b128(r, (int)b_off[nb],
+                                                              (int)((2 * hs + (u >> 1)) * s_bytes + (u & 1) * a_bytes), 0);
+        bf[nb][u] = make_uint4(v.x, v.y, v.z, v.w);
       }
   };
-
-  auto mfma_step = [&](const uint16_t* tile, const uint4 (&bf)[NB][5]) {
+  auto load_b_tail = [&](int k, auto HS, uint4 (&bf)[NB][5]) {
+    constexpr int hs = decltype(HS)::value;
+    const __amdgpu_buffer_rsrc_t r = step_rsrc(k);
 #pragma unroll
-    for (int ks = 0; ks < 5; ++ks) {
+    for (int nb = 0; nb < NB; ++nb) {
+      const u32x4 v = __builtin_amdgcn_raw_buffer_load_b128(r, (int)b_off[nb], (int)(4 * s_bytes + hs * a_bytes), 0);
+      bf[nb][4] = make_uint4(v.x, v.y, v.z, v.w);
+    }
+  };
+
+  // The index words and stored values of this lane's rows, then the sparse MFMAs S0, S0 + 1
+  // of the step with the fragments of one half step.
+  auto read_idx = [&](const unsigned char* tile, uint4 (&ix)[MB]) {
+#pragma unroll
+    for (int m = 0; m < MB; ++m) ix[m] = *(const uint4*)(tile + (m * 32 + ln) * kRowBytes + kIdxOffset + lh * 16);
+  };
+  auto mfma_pair = [&](const unsigned char* tile, auto HS, const uint4 (&ix)[MB], const uint4 (&bf)[NB][5]) {
+    constexpr int hs = decltype(HS)::value;
+#pragma unroll
+    for (int q = 0; q < 2; ++q) {
       h16x8 fa[MB];
 #pragma unroll
       for (int m = 0; m < MB; ++m)
-        fa[m] = __builtin_bit_cast(h16x8, *(const uint4*)(tile + (wm * 64 + m * 32 + ln) * LDK + ks * 16 + lh * 8));
+        fa[m] = __builtin_bit_cast(h16x8, *(const uint4*)(tile + (m * 32 + ln) * kRowBytes + ((2 * hs + q) * 2 + lh) * 16));
 #pragma unroll
       for (int n = 0; n < NB; ++n) {
-        const h16x8 fb = __builtin_bit_cast(h16x8, bf[n][ks]);
+        const uint4 two[2] = {bf[n][2 * q], bf[n][2 * q + 1]};
+        const h16x16 fb = __builtin_bit_cast(h16x16, two);
 #pragma unroll
-        for (int m = 0; m < MB; ++m)
-          acc[m][n] = __builtin_amdgcn_mfma_f32_32x32x16_f16(fa[m], fb, acc[m][n], 0, 0, 0);
+        for (int m = 0; m < MB; ++m) {
+          const int iw = hs == 0 ? (int)ix[m].x : (int)ix[m].y;       // S = 2 hs + q: word hs, half q
+          if (q == 0) acc[m][n] = __builtin_amdgcn_smfmac_f32_32x32x32_f16(fa[m], fb, acc[m][n], iw, 0, 0);
+          else acc[m][n] = __builtin_amdgcn_smfmac_f32_32x32x32_f16(fa[m], fb, acc[m][n], iw, 0, 1);
+        }
       }
+      if (MB > 2) __builtin_amdgcn_sched_barrier(0);     // keep the fragment reads of the next MFMA group from piling up
     }
   };
+  auto mfma_tail = [&](const unsigned char* tile, const uint4 (&ix)[MB], const uint4 (&bf0)[NB][5], const uint4 (&bf1)[NB][5]) {
+    h16x8 fa[MB];
+#pragma unroll
+    for (int m = 0; m < MB; ++m)
+      fa[m] = __builtin_bit_cast(h16x8, *(const uint4*)(tile + (m * 32 + ln) * kRowBytes + 128 + lh * 16));
+#pragma unroll
+    for (int n = 0; n < NB; ++n) {
+      const uint4 two[2] = {bf0[n][4], bf1[n][4]};
+      const h16x16 fb = __builtin_bit_cast(h16x16, two);
+#pragma unroll
+      for (int m = 0; m < MB; ++m)
+        acc[m][n] = __builtin_amdgcn_smfmac_f32_32x32x32_f16(fa[m], fb, acc[m][n], (int)ix[m].z, 0, 0);
+    }
+    if (MB > 2) __builtin_amdgcn_sched_barrier(0);
+  };
 
-  // ---- pipeline: three-slot rings indexed by compile-time slots (loop unrolled by 6) --------
-  // Top of step k: Phi tile k and fragments k are ready; fragments and basis words of
-  // steps k+1, k+2 are in flight.  Step k issues those of step k+3 into the slot step k
-  // frees, so every load has two full steps to arrive; the second workgroup on the CU
-  // covers the rest.
+  // ---- pipeline.  Fragments travel in half steps through a ring of three register slots
+  // (half step H in slot H mod 3), basis words in whole steps through a ring of three; all
+  // slots are compile-time, so the loop is unrolled by three steps.  Top of step k: Phi tile
+  // k and the fragments of half steps 2k, 2k+1 are ready, those of 2k+2 and the basis words of
+  // steps k+1, k+2 are in flight.  The S = 4 fragment of half step 2k is needed until the end
+  // of the step, so its successor (half step 2k+3) is requested in two parts.
   // The bias sums of the tile's columns are fetched ahead of everything else (thread t owns
   // column j0 + t) and parked in LDS until the epilogue, so their latency is never exposed.
   static_assert(BN <= kMfmaThreads, "one bias column per thread (the others repeat the last column)");
@@ -309,14 +418,19 @@ __global__ __launch_bounds__(kMfmaThreads, NB == 1 ? 3 : 2) void kan_mfma_kernel
 #pragma unroll
   for (int u = 0; u < 8; ++u) bias_v[u] = bp[(long long)min(rb0 + u, rb1 - 1) * n_out];
 
+  using HS0 = std::integral_constant<int, 0>;
+  using HS1 = std::integral_constant<int, 1>;
   uint4 bfr[3][NB][5];
   uint2 uv[3][NPAIR];
   load_u(0, uv[0]);
-  load_b(0, bfr[0]);
+  load_b_main(0, HS0{}, bfr[0]);
+  load_b_tail(0, HS0{}, bfr[0]);
+  load_b_main(0, HS1{}, bfr[1]);
+  load_b_tail(0, HS1{}, bfr[1]);
   load_u(1, uv[1]);
-  load_b(1, bfr[1]);
+  load_b_main(1, HS0{}, bfr[2]);
+  load_b_tail(1, HS0{}, bfr[2]);
   load_u(2, uv[2]);
-  load_b(2, bfr[2]);
   {
     float bs = 0.f;
 #pragma unroll
@@ -327,29 +441,32 @@ __global__ __launch_bounds__(kMfmaThreads, NB == 1 ? 3 : 2) void kan_mfma_kernel
   gen_phi(uv[0], sA[0]);
 
   auto step = [&](auto T, int k) {
-    constexpr int t = decltype(T)::value;          // k mod 6
+    constexpr int t = decltype(T)::value;          // k mod 3
+    constexpr int sa = (2 * t) % 3, sb = (2 * t + 1) % 3;
+    const unsigned char* tile = sA[k & 1];
     __syncthreads();     // tile k is complete; every wave is done reading tile k-1
-    mfma_step(sA[t & 1], bfr[t % 3]);
-    gen_phi(uv[(t + 1) % 3], sA[(t + 1) & 1]);     // step k+1 basis tile
-    load_b(k + 3, bfr[t % 3]);                     // fragments of step k have been consumed
-    load_u(k + 3, uv[t % 3]);                      // basis words of step k were consumed a step ago
+    uint4 ix[MB];
+    read_idx(tile, ix);
+    mfma_pair(tile, HS0{}, ix, bfr[sa]);
+    load_b_main(k + 1, HS1{}, bfr[sa]);            // half step 2k+3; its S = 4 fragment follows below
+    mfma_pair(tile, HS1{}, ix, bfr[sb]);
+    mfma_tail(tile, ix, bfr[sa], bfr[sb]);
+    gen_phi(uv[(t + 1) % 3], sA[(k + 1) & 1]);     // step k+1 basis tile
+    load_b_tail(k + 1, HS1{}, bfr[sa]);
+    load_b_main(k + 2, HS0{}, bfr[sb]);            // half step 2k+4
+    load_b_tail(k + 2, HS0{}, bfr[sb]);
+    load_u(k + 3, uv[t]);                          // basis words of step k were consumed a step ago
   };
-  // Whole groups of six steps run without a branch between them: a branch around a step makes
+  // Whole groups of three steps run without a branch between them: a branch around a step makes
   // the compiler lose count of the loads in flight and wait for all of them.
   int k = 0;
-  for (; k + 6 <= n_steps; k += 6) {
+  for (; k + 3 <= n_steps; k += 3) {
     step(std::integral_constant<int, 0>{}, k);
     step(std::integral_constant<int, 1>{}, k + 1);
     step(std::integral_constant<int, 2>{}, k + 2);
-    step(std::integral_constant<int, 3>{}, k + 3);
-    step(std::integral_constant<int, 4>{}, k + 4);
-    step(std::integral_constant<int, 5>{}, k + 5);
   }
   if (k < n_steps) step(std::integral_constant<int, 0>{}, k);
   if (k + 1 < n_steps) step(std::integral_constant<int, 1>{}, k + 1);
-  if (k + 2 < n_steps) step(std::integral_constant<int, 2>{}, k + 2);
-  if (k + 3 < n_steps) step(std::integral_constant<int, 3>{}, k + 3);
-  if (k + 4 < n_steps) step(std::integral_constant<int, 4>{}, k + 4);
 
   // ---- epilogue.  D layout of the 32x32 MFMA: lane holds column (lane & 31), rows
   //      8*(r/4) + 4*(lane/32) + r%4 for r = 0..15 -------------------------------------------
@@ -363,7 +480,7 @@ __global__ __launch_bounds__(kMfmaThreads, NB == 1 ? 3 : 2) void kan_mfma_kernel
       for (int m = 0; m < MB; ++m)
 #pragma unroll
         for (int r = 0; r < 16; ++r) {
-          const int b = b0 + wm * 64 + m * 32 + 8 * (r >> 2) + 4 * lh + (r & 3);
+          const int b = b0 + m * 32 + 8 * (r >> 2) + 4 * lh + (r & 3);
           if (b < B) {
             float v = fmaf(scale, acc[m][n][r], bs);
             if (a.apply_tanh) v = tanhf(v);
@@ -417,14 +534,14 @@ hipError_t launch_prep_basis(const float* x, long long x_head_stride, int x_part
 }
 
 hipError_t launch_mfma(const MfmaArgs& a, int tile_m, int tile_n, dim3 grid, hipStream_t s) {
-  if (tile_m != 64 || (tile_n != 128 && tile_n != 256)) return hipErrorInvalidValue;
+  if ((tile_m != 64 && tile_m != 128) || tile_n != 128) return hipErrorInvalidValue;
   if ((long long)a.n_jt * tile_n < a.n_out) return hipErrorInvalidValue;
   // one step of coefficient records and one row of basis words must fit a buffer resource
-  if ((long long)a.n_out * 10 * (long long)sizeof(uint4) > 0x7fffffffLL ||
+  if ((long long)a.n_out * 20 * (long long)sizeof(uint4) > 0x7fffffffLL ||
       (long long)a.B * (long long)sizeof(uint2) > 0x7fffffffLL)
     return hipErrorInvalidValue;
-  if (tile_n == 128) hipLaunchKernelGGL((kan_mfma_kernel<2, 1>), grid, dim3(kMfmaThreads), 0, s, a);
-  else hipLaunchKernelGGL((kan_mfma_kernel<2, 2>), grid, dim3(kMfmaThreads), 0, s, a);
+  if (tile_m == 128) hipLaunchKernelGGL((kan_mfma_kernel<4, 1>), grid, dim3(kMfmaThreads), 0, s, a);
+  else hipLaunchKernelGGL((kan_mfma_kernel<2, 1>), grid, dim3(kMfmaThreads), 0, s, a);
   return hipGetLastError();
 }
 

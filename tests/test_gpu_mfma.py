@@ -95,15 +95,15 @@ def test_mfma_config4_multi_head(kb):
 
 
 @pytest.mark.parametrize("n_in,n_out,B", [
-    (70, 1900, 2100),      # 8 x 33 tiles of 256 outputs (ragged in both directions): the wide tile
-    (70, 1900, 300),       # 8 x 5 tiles: the narrow tile, 15 tiles of 128 outputs, the last one ragged
-    (200, 100, 5000),      # at most 128 outputs: always the narrow tile, 79 batch tiles
-    (330, 129, 4100),      # one output past a narrow tile on the wide one
+    (70, 1900, 2100),      # 15 x 17 tiles of 128 samples (ragged in both directions)
+    (70, 1900, 300),       # 15 x 3 tiles of 128 samples would be too few: 64-sample tiles, 15 x 5
+    (200, 100, 5000),      # one column tile: 64-sample tiles, 79 of them
+    (330, 129, 4100),      # one output past a tile; 128-sample tiles, the last one 4 samples
 ])
-def test_mfma_both_tile_widths_sampled(kb, n_in, n_out, B):
-    """The contraction kernel has a 256-output and a 128-output tile; which one a layer gets
+def test_mfma_both_tile_heights_sampled(kb, n_in, n_out, B):
+    """The contraction kernel has a 128-sample and a 64-sample tile; which one a layer gets
     depends on how many tiles its grid has.  Sampled outputs against the oracle, and whole
-    rows (first, last, one per batch tile boundary) so that every column of a row is checked."""
+    rows (first, last, around tile boundaries) so that every column of a row is checked."""
     P = synth.make_layer(n_in + n_out + B, n_in, n_out, 3000, cb_dtype="i8", gb_dtype="f16")
     x = synth.make_x(B + 1, B, n_in)
     (L,) = gpu_layers([P])
