@@ -165,11 +165,12 @@ LayerPlan plan_mfma(int n_in, int n_out, int64_t B, int n_heads, int idx_u32, in
   const long long max_chunks = n_in / kMfmaMinRows;
   // Tiles of 128 outputs by 128 samples (half the coefficient bytes per MFMA through the
   // vector cache), unless their grid would need more than eight chunks of inputs to give
-  // every CU two workgroups: 64-sample tiles then halve the chunks and with them the
-  // partial sums written and read back.
+  // every CU two workgroups (64-sample tiles then halve the chunks and with them the
+  // partial sums written and read back), or would be padded with many more empty rows.
   p.n_jt = (n_out + kMfmaTileN - 1) / kMfmaTileN;
   const long long big = (long long)n_heads * p.n_jt * ((B + 127) / 128);
-  p.cfg.bt = big * 8 >= kMfmaTargetWorkgroups ? 128 : 64;
+  const long long rows128 = (B + 127) / 128 * 128, rows64 = (B + 63) / 64 * 64;     // sample rows the tiles cover
+  p.cfg.bt = (big * 8 >= kMfmaTargetWorkgroups && rows128 * 10 <= rows64 * 11) ? 128 : 64;
   p.n_bt = (int)((B + p.cfg.bt - 1) / p.cfg.bt);
   const long long base = (long long)n_heads * p.n_jt * p.n_bt;
   long long chunks = kMfmaTargetWorkgroups / (base > 0 ? base : 1);

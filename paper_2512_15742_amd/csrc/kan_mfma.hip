@@ -238,8 +238,34 @@ __global__ __launch_bounds__(kMfmaThreads, MB == 2 ? 3 : 2) void kan_mfma_kernel
   const int lane = tid & 63, wave = tid >> 6;
   const int ln = lane & 31, lh = lane >> 5;
   const int wn = wave;
-  const int head = blockIdx.z, chunk = blockIdx.y;
-  const int jt = blockIdx.x % a.n_jt, bt = blockIdx.x / a.n_jt;
+  const int head = blockIdx.z;
+  // Which (tile, chunk of inputs) this workgroup takes.  Workgroups go to the eight XCDs in
+  // turn (linear index mod 8), and each XCD has its own L2: giving an XCD all tiles of the same
+  // chunk(s) makes its L2 hold one slice of the inputs of both operands, each fetched from
+  // memory once, instead of every XCD fetching the whole basis operand.
+  // Within a chunk the tiles are taken in patches of 8 x 8 (sample tiles x output tiles), so that
+  // the 64 workgroups an XCD runs at a time share each fragment eight ways.
+  int chunk = blockIdx.y, seq = blockIdx.x;
+  const int T = gridDim.x, njt = a.n_jt, nbt = T / njt;
+  {
+    const int C = gridDim.y;
+    const int L = blockIdx.x + T * blockIdx.y, xcd = L & 7, m = L >> 3;
+    if ((T * C) % 8 == 0) {
+      if (C % 8 == 0) {
+        chunk = xcd + 8 * (m / T);
+        seq = m % T;
+      } else if (8 % C == 0 && T % (8 / C) == 0) {      // 8 / C XCDs per chunk, a run of tiles each
+        chunk = xcd % C;
+        seq = (xcd / C) * (T / (8 / C)) + m;
+      }
+    }
+  }
+  int jt = seq % njt, bt = seq / njt;
+  if (njt % 8 == 0 && nbt % 8 == 0) {
+    const int patch = seq >> 6, w = seq & 63, per_row = njt >> 3;
+    bt = (patch / per_row) * 8 + (w >> 3);
+    jt = (patch % per_row) * 8 + (w & 7);
+  }
   const int b0 = bt * BM, j0 = jt * BN;
   const int n_in = a.n_in, n_out = a.n_out, B = a.B;
   const int i_begin = chunk * a.rows_per_chunk;
