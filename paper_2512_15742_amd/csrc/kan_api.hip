@@ -352,7 +352,7 @@ kan_status run_layer_group(const LayerPlan& p, GatherArgs& a, const void* const*
     memcpy(pc.h, a.h, sizeof(pc.h));
     st = run("kan_prep_coef", s, [&] { return launch_prep_coef(p.cfg, pc, heads, s); });
     if (st != KAN_OK) return st;
-    const long long u_stride = x_shared ? 0 : (long long)a.n_in * a.B;
+    const long long u_stride = x_shared ? 0 : (long long)((a.n_in + 15) / 16 * 16) * a.B;
     st = run("kan_prep_basis", s, [&] {
       return launch_prep_basis(a.x, a.x_head_stride, chain.in_parts, chain.in_part_stride, chain.in_tanh, w.u,
                                u_stride, a.n_in, a.B, x_shared ? 1 : heads, a.rule, s);
@@ -500,7 +500,7 @@ kan_status plan_head(const kan_vq_layer* layers, int32_t n_layers, int32_t n_hea
       grow(ws->bp, round_up((size_t)group * mfma_bp_floats(R.in, R.out) * sizeof(float), 256));
     }
     if (p.mfma)
-      grow(ws->u, round_up((size_t)(l == 0 ? 1 : group) * (size_t)R.in * (size_t)B * sizeof(uint2), 256));
+      grow(ws->u, round_up((size_t)(l == 0 ? 1 : group) * (size_t)((R.in + 15) / 16 * 16) * (size_t)B * sizeof(uint2), 256));
     if (l + 1 < n_layers) grow(ws->hidden, round_up((size_t)n_heads * (size_t)B * R.out * sizeof(float), 256));
   }
   // chained layers hand their partial sums straight on: two buffers, used in turn

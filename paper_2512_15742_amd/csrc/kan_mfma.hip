@@ -132,7 +132,7 @@ __global__ __launch_bounds__(kThreads) void kan_prep_coef_kernel(const PrepCoefA
 
 // ---- kan_prep_basis -----------------------------------------------------------------
 // W[i][b] = { half2(w0, w1), half2(w2, w3) } with span bit 0, 1, 2 in the sign bits of
-// w0, w1, w2 (the weights are never negative).
+// w0, w1, w2 (the weights are never negative); rows n_in .. next multiple of 16 are zeros.
 // The input is x itself, or (x_parts > 1) the previous layer's partial sums, added here in
 // the order of the slices and squashed, so that no separate reduction pass runs in between.
 __global__ __launch_bounds__(256) void kan_prep_basis_kernel(const float* __restrict__ x, long long x_head_stride,
@@ -172,7 +172,7 @@ __global__ __launch_bounds__(256) void kan_prep_basis_kernel(const float* __rest
 #pragma unroll
   for (int r = 0; r < 4; ++r) {
     const int i = ib + ty + 8 * r, b = bb + tx;
-    if (i < n_in && b < B) wh[(long long)i * B + b] = tile[tx][ty + 8 * r];
+    if (i < (n_in + IT - 1) / IT * IT && b < B) wh[(long long)i * B + b] = tile[tx][ty + 8 * r];   // rows up to a whole step: zeros
   }
 }
 
@@ -305,12 +305,13 @@ __global__ __launch_bounds__(kMfmaThreads, MB == 2 ? 3 : 2) void kan_mfma_kernel
   const char* w_bytes = (const char*)W;
   const uint32_t w_row_bytes = (uint32_t)B * (uint32_t)sizeof(uint2);
   auto load_u = [&](int k, uint2 (&uv)[NPAIR]) {       // step index relative to the chunk
-    const int i = i_begin + k * IT + 4 * ph0;
+    // (the rows of a ragged last step exist and hold zeros; past the chunk: valid memory, never used)
+    const int i = min(step0 + k, last_step) * IT + 4 * ph0;
+    const char* rows = w_bytes + (size_t)i * w_row_bytes;
+    const __amdgpu_buffer_rsrc_t r = __builtin_amdgcn_make_buffer_rsrc((void*)rows, 0, (int)(NPAIR * w_row_bytes), kBufferFlags);
 #pragma unroll
     for (int q = 0; q < NPAIR; ++q) {
-      const char* row = w_bytes + (size_t)min(i + q, n_in - 1) * w_row_bytes;
-      const __amdgpu_buffer_rsrc_t r = __builtin_amdgcn_make_buffer_rsrc((void*)row, 0, (int)w_row_bytes, kBufferFlags);
-      const u32x2 v = __builtin_amdgcn_raw_buffer_load_b64(r, (int)u_off, 0, 0);
+      const u32x2 v = __builtin_amdgcn_raw_buffer_load_b64(r, (int)u_off, (int)(q * w_row_bytes), 0);
       uv[q] = make_uint2(v.x, v.y);
     }
   };
@@ -473,10 +474,12 @@ __global__ __launch_bounds__(kMfmaThreads, MB == 2 ? 3 : 2) void kan_mfma_kernel
     __syncthreads();     // tile k is complete; every wave is done reading tile k-1
     uint4 ix[MB];
     read_idx(tile, ix);
+    __builtin_amdgcn_s_setprio(2);     // the wave that has its operands goes first at the matrix pipe (measured: 1.5-2 %)
     mfma_pair(tile, HS0{}, ix, bfr[sa]);
     load_b_main(k + 1, HS1{}, bfr[sa]);            // half step 2k+3; its S = 4 fragment follows below
     mfma_pair(tile, HS1{}, ix, bfr[sb]);
     mfma_tail(tile, ix, bfr[sa], bfr[sb]);
+    __builtin_amdgcn_s_setprio(0);
     gen_phi(uv[(t + 1) % 3], sA[(k + 1) & 1]);     // step k+1 basis tile
     load_b_tail(k + 1, HS1{}, bfr[sa]);
     load_b_main(k + 2, HS0{}, bfr[sb]);            // half step 2k+4
@@ -564,7 +567,7 @@ hipError_t launch_mfma(const MfmaArgs& a, int tile_m, int tile_n, dim3 grid, hip
   if ((long long)a.n_jt * tile_n < a.n_out) return hipErrorInvalidValue;
   // one step of coefficient records and one row of basis words must fit a buffer resource
   if ((long long)a.n_out * 20 * (long long)sizeof(uint4) > 0x7fffffffLL ||
-      (long long)a.B * (long long)sizeof(uint2) > 0x7fffffffLL)
+      (long long)a.B * 8 * (long long)sizeof(uint2) > 0x7fffffffLL)
     return hipErrorInvalidValue;
   if (tile_m == 128) hipLaunchKernelGGL((kan_mfma_kernel<4, 1>), grid, dim3(kMfmaThreads), 0, s, a);
   else hipLaunchKernelGGL((kan_mfma_kernel<2, 1>), grid, dim3(kMfmaThreads), 0, s, a);
