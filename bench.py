@@ -40,7 +40,7 @@ MALL_BYTES = 256 << 20
 # summaries under profiles/.  None until such a run exists for the workload.
 MEASURED_TRAFFIC = {
     # average over the layer-1 and layer-2 launches of one step, bytes per launch
-    ("kan_mfma", 1024): int((60.74 + 32.00 + 18.26 + 16.00) / 2 * 2**20),
+    ("kan_mfma", 1024): int((60.70 + 32.00 + 18.24 + 16.00) / 2 * 2**20),
     ("kan_gather_bt1", 1): int((17.20 + 0.50 + 6.61 + 0.06) / 2 * 2**20),
     ("kan_bucket", 1): int((7.74 + 0.02) * 2**20),
 }
