@@ -131,8 +131,10 @@ __global__ __launch_bounds__(kThreads) void kan_prep_coef_kernel(const PrepCoefA
 }
 
 // ---- kan_prep_basis -----------------------------------------------------------------
-// W[i][b] = { half2(w0, w1), half2(w2, w3) } with span bit 0, 1, 2 in the sign bits of
-// w0, w1, w2 (the weights are never negative); rows n_in .. next multiple of 16 are zeros.
+// An input's basis word for a sample = { half2(w0, w1), half2(w2, w3) } with span bit 0, 1, 2 in
+// the sign bits of w0, w1, w2 (the weights are never negative); W[i / 2][b][i % 2], so that a
+// lane of the contraction kernel fetches two inputs with one 16-byte load; rows n_in .. next
+// multiple of 16 are zeros.
 // The input is x itself, or (x_parts > 1) the previous layer's partial sums, added here in
 // the order of the slices and squashed, so that no separate reduction pass runs in between.
 __global__ __launch_bounds__(256) void kan_prep_basis_kernel(const float* __restrict__ x, long long x_head_stride,
@@ -172,7 +174,8 @@ __global__ __launch_bounds__(256) void kan_prep_basis_kernel(const float* __rest
 #pragma unroll
   for (int r = 0; r < 4; ++r) {
     const int i = ib + ty + 8 * r, b = bb + tx;
-    if (i < (n_in + IT - 1) / IT * IT && b < B) wh[(long long)i * B + b] = tile[tx][ty + 8 * r];   // rows up to a whole step: zeros
+    if (i < (n_in + IT - 1) / IT * IT && b < B)      // rows up to a whole step: zeros
+      wh[((long long)(i >> 1) * B + b) * 2 + (i & 1)] = tile[tx][ty + 8 * r];
   }
 }
 
@@ -301,18 +304,19 @@ __global__ __launch_bounds__(kMfmaThreads, MB == 2 ? 3 : 2) void kan_mfma_kernel
   // Every load of the main loop is a buffer load: the resource (base, size) is rebuilt on the
   // scalar unit for each step, the lane offsets never change, so a load costs no vector
   // arithmetic.  Offsets stay below 2^31 because a resource spans one step of one head.
-  const uint32_t u_off = (uint32_t)min(b0 + pb, B - 1) * (uint32_t)sizeof(uint2);
+  const uint32_t u_off = (uint32_t)min(b0 + pb, B - 1) * (uint32_t)sizeof(uint4);
   const char* w_bytes = (const char*)W;
-  const uint32_t w_row_bytes = (uint32_t)B * (uint32_t)sizeof(uint2);
+  const uint32_t w_row_bytes = (uint32_t)B * (uint32_t)sizeof(uint4);       // a pair of inputs
   auto load_u = [&](int k, uint2 (&uv)[NPAIR]) {       // step index relative to the chunk
     // (the rows of a ragged last step exist and hold zeros; past the chunk: valid memory, never used)
     const int i = min(step0 + k, last_step) * IT + 4 * ph0;
-    const char* rows = w_bytes + (size_t)i * w_row_bytes;
-    const __amdgpu_buffer_rsrc_t r = __builtin_amdgcn_make_buffer_rsrc((void*)rows, 0, (int)(NPAIR * w_row_bytes), kBufferFlags);
+    const char* rows = w_bytes + (size_t)(i >> 1) * w_row_bytes;
+    const __amdgpu_buffer_rsrc_t r = __builtin_amdgcn_make_buffer_rsrc((void*)rows, 0, (int)(NPAIR / 2 * w_row_bytes), kBufferFlags);
 #pragma unroll
-    for (int q = 0; q < NPAIR; ++q) {
-      const u32x2 v = __builtin_amdgcn_raw_buffer_load_b64(r, (int)u_off, (int)(q * w_row_bytes), 0);
-      uv[q] = make_uint2(v.x, v.y);
+    for (int q = 0; q < NPAIR / 2; ++q) {
+      const u32x4 v = __builtin_amdgcn_raw_buffer_load_b128(r, (int)u_off, (int)(q * w_row_bytes), 0);
+      uv[2 * q] = make_uint2(v.x, v.y);
+      uv[2 * q + 1] = make_uint2(v.z, v.w);
     }
   };
 

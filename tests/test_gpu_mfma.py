@@ -68,12 +68,16 @@ def test_mfma_config2_b256(kb):
     print("config2 B=256 mfma", rep)
 
 
-@pytest.mark.parametrize("B", [256, 1024, 4096])
+@pytest.mark.parametrize("B", [256, 1024, 2048, 4096])
 def test_mfma_config3_head(kb, B):
+    """The batch sizes differ in tile height, number of chunks of inputs and in how the kernel
+    deals its workgroups to the XCDs (8, 4, 2 chunks for layer 1, 16 for layer 2)."""
     Ps, x = synth.config3(B)
     Ls = gpu_layers(Ps)
     y = kb.kan_vq_head_forward([Ls], to_dev(x), path=kb.KAN_PATH_MFMA)[0].cpu().numpy()
-    rows = np.sort(np.random.default_rng(B).choice(B, 64, replace=False))
+    # a row of every 64-sample tile (a tile left out by the workgroup mapping would show), and random ones
+    rows = np.unique(np.concatenate([np.arange(0, B, 64) + (np.arange(0, B, 64) // 64) % 64,
+                                     np.random.default_rng(B).choice(B, 16, replace=False)]))
     y_ref = ko.vq_head_forward(x[rows], [p.as_dict() for p in Ps])
     rep = ko.error_report(y[rows], y_ref)
     print("config3 mfma", B, rep)
