@@ -673,3 +673,21 @@ def test_assignment_recovers_a_layer_built_from_the_codebook():
     flat = np.full((1, 1, ko.G), 0.7)
     i0, g0, b0, _ = ko.assign_edges(flat, cb)
     assert g0[0, 0] == 0.0 and abs(b0[0, 0] - 0.7) < 1e-15
+
+
+@pytest.mark.parametrize("rule", ["bspline", "pli"])
+def test_support_never_holds_both_entries_m_and_m_plus_5(rule):
+    """The streaming matrix-core kernel orders a codeword's ten entries in pairs (m, m + 5) and
+    relies on at most one entry of a pair carrying weight, whatever x: the four nonzero cubic
+    bases (and the two taps of the interpolation rule) are consecutive.  Checked on the
+    oracle's own weights, at random points, at the knots and at both ends."""
+    rng = np.random.default_rng(11)
+    x = np.concatenate([rng.uniform(-1.0, 1.0, 20000), ko.knots()[3:11], ko.pli_nodes(), [-1.0, 1.0, -1.5, 1.5]])
+    W = ko.design_matrix(x, rule)                       # [n][10]
+    assert W.shape == (x.size, 10)
+    nz = W != 0.0
+    assert not (nz[:, :5] & nz[:, 5:]).any()
+    # and the nonzero entries are consecutive: last - first + 1 <= 4
+    first = np.argmax(nz, axis=1)
+    last = 9 - np.argmax(nz[:, ::-1], axis=1)
+    assert (last - first <= 3).all() and (nz.sum(axis=1) >= 1).all()
