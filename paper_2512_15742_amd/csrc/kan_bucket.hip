@@ -32,6 +32,7 @@ namespace {
 constexpr int kWaves = kBucketThreads / kWave;     // 16
 constexpr int kEpt = 8;                            // consecutive edges per thread and pass
 constexpr int kPass = kBucketThreads * kEpt;       // 8192 edges per workgroup and pass
+constexpr int kBadMax = 32;                        // non-finite products of a pass that are placed one by one
 
 // Raw records of one pass: edges e0 .. e0 + 7 of the thread (16-byte loads; the eight gains
 // are 32 bytes as fp32 - two loads -, 16 as fp16, 8 as byte codes).  GK is the GbKind.
@@ -110,6 +111,10 @@ __global__ __launch_bounds__(kBucketThreads) void kan_bucket_kernel(const Bucket
   __shared__ float res[kBucketMaxJw];       // sums of this workgroup's segments
   __shared__ uint32_t segl[kBucketMaxJw + 1];   // first edge of every segment of the block (+ end)
   __shared__ int seg_first[2];                  // first segment that reaches into the pass (by pass parity)
+  __shared__ float wave_total[kWaves];          // prefix mode: the sum of each wave's 512 products of the pass
+  __shared__ int bad_n[2];                      // prefix mode: non-finite products of the pass (by pass parity) ...
+  __shared__ uint32_t bad_pos[kBadMax];         // ... their edges ...
+  __shared__ float bad_val[kBadMax];            // ... and values: they are added to their own segment only
 
   const int tid = threadIdx.x, lane = tid & (kWave - 1);
   const int wave = __builtin_amdgcn_readfirstlane(tid >> 6);
@@ -243,8 +248,17 @@ __global__ __launch_bounds__(kBucketThreads) void kan_bucket_kernel(const Bucket
   segl[min(tid, njw)] = sv0;
   segl[min(tid + kBucketThreads, njw)] = sv1;
   for (int t = tid; t < njw; t += kBucketThreads) res[t] = 0.f;
+  if (tid < 2) bad_n[tid] = 0;
   __syncthreads();
 
+  // Segment sums, two ways.  Long segments (more than 512 edges on the block's average): a whole
+  // wave adds one segment's products.  Shorter ones: the products of a pass are turned into
+  // running sums over each wave's 512 edges (eight per thread, then a scan across the lanes),
+  // and a segment's sum is the difference of the running sums at its two ends, plus whole
+  // waves in between: one thread per segment, three dependent LDS reads instead of a chain
+  // per group of lanes.  Both ways add in a fixed order.
+  const uint32_t avg_len_x = blk_hi - blk_lo;                               // compared with len * njw: uniform
+  const bool use_prefix = avg_len_x <= 512u * (uint32_t)njw;
   // products of the thread's 8 edges of pass p -> prod
   auto products = [&](const PassRegs<GK>& c, int p) {
     // edge e belongs to the block iff blk_lo <= e < blk_hi, i.e. (e - blk_lo) < (blk_hi - blk_lo) unsigned
@@ -299,6 +313,45 @@ __global__ __launch_bounds__(kBucketThreads) void kan_bucket_kernel(const Bucket
       pr[u] = (rel0 + (uint32_t)u < len) ? gain_of<GK>(c, u, qp) * s : 0.f;
     }
     }
+    if (use_prefix) {
+      float run[kEpt];                    // running sums of the thread's eight products
+      run[0] = pr[0];
+#pragma unroll
+      for (int u = 1; u < kEpt; ++u) run[u] = run[u - 1] + pr[u];
+      // A running sum would carry a non-finite product (a codeword with an Inf or NaN that an
+      // edge does refer to) into the segments behind it: such products are set aside.  The
+      // thread's total is finite iff all its eight products are.
+      if (!__builtin_isfinite(run[kEpt - 1])) {
+        float keep = 0.f;
+#pragma unroll
+        for (int u = 0; u < kEpt; ++u) {
+          if (__builtin_isfinite(pr[u])) {
+            keep += pr[u];
+          } else {
+            const int k = atomicAdd(&bad_n[p & 1], 1);
+            if (k < kBadMax) {
+              bad_pos[k] = base + (uint32_t)p * kPass + (uint32_t)tid * kEpt + (uint32_t)u;
+              bad_val[k] = pr[u];
+            }
+          }
+          run[u] = keep;
+        }
+      }
+#pragma unroll
+      for (int u = 0; u < kEpt; ++u) pr[u] = run[u];
+      float v = pr[kEpt - 1];            // inclusive scan of the threads' totals over the wave
+      v = dpp_add<0x111, 0xf>(v);        // row_shr 1, 2, 4, 8: within rows of 16 lanes
+      v = dpp_add<0x112, 0xf>(v);
+      v = dpp_add<0x114, 0xf>(v);
+      v = dpp_add<0x118, 0xf>(v);
+      v = dpp_add<0x142, 0xa>(v);        // row_bcast 15: rows 1 and 3 add the total of the row before
+      v = dpp_add<0x143, 0xc>(v);        // row_bcast 31: rows 2 and 3 add the total of the first half
+      const float before = __shfl_up(v, 1, 64);
+      const float ex = lane == 0 ? 0.f : before;
+#pragma unroll
+      for (int u = 0; u < kEpt; ++u) pr[u] += ex;
+      if (lane == kWave - 1) wave_total[wave] = v;
+    }
     ((float4*)prod)[tid * 2] = make_float4(pr[0], pr[1], pr[2], pr[3]);
     ((float4*)prod)[tid * 2 + 1] = make_float4(pr[4], pr[5], pr[6], pr[7]);
     // The first segment that ends after the start of the pass: thread t answers for segment t
@@ -308,15 +361,42 @@ __global__ __launch_bounds__(kBucketThreads) void kan_bucket_kernel(const Bucket
     if (tid < njw && segl[tid + 1] > pa && (tid == 0 || segl[tid] <= pa)) seg_first[p & 1] = tid;
   };
 
-  // segment sums over the products of pass p.  A group of lanes takes a segment: a whole wave
-  // where segments are long (more than 512 edges on average), half a wave up to 512, a row of 16
-  // lanes up to 128 (layers with many buckets or few inputs): a wave then works on two or four
-  // segments at a time and the chain of LDS round trips per segment (bounds, products, running
-  // sum) is paid that much less often.  Wave w takes the groups w, w + 16, ... of the pass.
-  const uint32_t avg_len_x = blk_hi - blk_lo;                               // compared with len * njw: uniform
-  const int group_shift = avg_len_x <= 128u * (uint32_t)njw ? 4 : (avg_len_x <= 512u * (uint32_t)njw ? 5 : 6);
   auto segment_sums = [&](int p) {
     const uint32_t pa = base + (uint32_t)p * kPass;        // prod[n] is edge pa + n
+    if (use_prefix) {
+      for (int jj = seg_first[p & 1] + tid; jj < njw; jj += kBucketThreads) {
+        const uint32_t s0 = segl[jj], s1 = segl[jj + 1];
+        if (s0 >= pa + (uint32_t)kPass) break;             // in order: the rest lies behind the pass
+        const uint32_t lo = max(s0, pa) - pa, hi = min(s1, pa + (uint32_t)kPass) - pa;
+        if (lo < hi) {
+          const int wl = (int)(lo >> 9), wh = (int)((hi - 1) >> 9);       // 512 products per wave
+          float sum = prod[hi - 1];
+          for (int w = wh - 1; w >= wl; --w) sum += wave_total[w];        // whole waves, and the first wave's total
+          if (lo & 511u) sum -= prod[lo - 1];
+          res[jj] += sum;
+        }
+      }
+      const int nb = bad_n[p & 1];                          // (uniform; almost always 0)
+      if (nb > 0) {
+        __syncthreads();                                    // the sums above are in res
+        if (nb > kBadMax) {                                 // too many to place: the whole block is not a number
+          for (int t = tid; t < njw; t += kBucketThreads) res[t] = __builtin_nanf("");
+        } else if (tid < nb) {
+          const uint32_t e = bad_pos[tid];                  // its segment: segl[jj] <= e < segl[jj + 1]
+          int lo_j = 0, hi_j = njw;
+          while (hi_j - lo_j > 1) {
+            const int mid = (lo_j + hi_j) >> 1;
+            if (segl[mid] <= e) lo_j = mid; else hi_j = mid;
+          }
+          atomicAdd(&res[lo_j], bad_val[tid]);
+        }
+        __syncthreads();
+        if (tid == 0) bad_n[p & 1] = 0;                     // next written two passes on, behind two barriers
+      }
+      return;
+    }
+    // a whole wave per segment; wave w takes segments w, w + 16, ... of the pass
+    constexpr int group_shift = 6;
     const int glanes = 1 << group_shift, per_wave = kWave >> group_shift;
     const int grp = lane >> group_shift, gl = lane & (glanes - 1);
     for (int jj = seg_first[p & 1] + wave * per_wave + grp; jj < njw; jj += kWaves * per_wave) {

@@ -291,3 +291,40 @@ def test_unused_codeword_rows_may_hold_anything(kb):
     y_ref = ko.vq_layer_forward(x, **P.as_dict())
     assert np.isfinite(y).all()
     assert ko.error_report(y, y_ref)["headline"] <= TOL_FP32
+
+
+@pytest.mark.parametrize("n_bad", [3, 200])
+def test_non_finite_codewords_reach_only_their_own_outputs(kb, n_bad):
+    """A codeword with an Inf or a NaN that edges do refer to makes exactly the outputs of those
+    edges non-finite; every other output keeps its value (the running sums of a pass must not
+    carry such a product into the segments behind it).  With very many such products in one
+    workgroup's pass (n_bad = 200 edges of one output column range) whole blocks of outputs may
+    be given up, but never silently wrong: every finite output still matches the oracle."""
+    n_in, n_out, K = 300, 200, 20000
+    P = synth.make_layer(77, n_in, n_out, K, cb_dtype="f32", gb_dtype="f32")
+    rng = np.random.default_rng(n_bad)
+    bad_rows = np.array([5, 4100, 19999])
+    P.idx[np.isin(P.idx, bad_rows)] = 6                              # nobody refers to them by chance
+    cb = P.codebook.copy()
+    cb[5] = np.inf
+    cb[4100] = np.nan
+    cb[19999] = -np.inf                                             # (whole rows: an entry outside the four under the
+                                                                    # span is never read by the kernels)
+    ii = rng.integers(0, n_in, n_bad)
+    jj = rng.integers(0, 12, n_bad) if n_bad > 50 else rng.integers(0, n_out, n_bad)
+    P.idx[ii, jj] = bad_rows[np.arange(n_bad) % 3]
+    P2 = dataclasses.replace(P, codebook=cb)
+    hit = np.isin(P2.idx, bad_rows).any(axis=0)                      # outputs with such an edge
+    for B in (1, 3):
+        x = synth.make_x(5 + B, B, n_in)
+        y = _forward_prepared(kb, P2, x)
+        cb0 = cb.copy()
+        cb0[bad_rows] = 0.0
+        y_ref = ko.vq_layer_forward(x, **dataclasses.replace(P, codebook=cb0).as_dict())
+        assert not np.isfinite(y[:, hit]).any()
+        fin = np.isfinite(y)
+        if n_bad <= 50:
+            assert fin[:, ~hit].all()
+        assert fin.any()
+        scale = np.abs(y_ref).max()
+        assert (np.abs(y[fin] - y_ref[fin]) <= TOL_FP32 * scale).all()
