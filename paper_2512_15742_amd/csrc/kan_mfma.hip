@@ -7,7 +7,7 @@
 //     Phi[b][(i,m)]  = B_m(x_bi)            (4 nonzeros per 10, App. A.1 family)
 //     Chat[(i,m)][j] = gain_ij * q_ij[m]    (q = Int8 codeword, or the fp32 row)
 // Both operands are fp16 (11-bit significand, same matrix-core rate as bf16, all
-// values lie in [-2, 2]); products accumulate in fp32 in v_mfma_f32_32x32x16_f16.
+// values lie in [-2, 2]); products accumulate in fp32 in v_smfmac_f32_32x32x32_f16.
 // The per-layer Int8 scale and the bias sum (the bases sum to one) stay in fp32
 // and are applied to the accumulators at the end.
 //
@@ -21,8 +21,8 @@
 //   kan_prep_basis  every (sample, input) once: exact span (fp64) and the four
 //                   basis weights as fp16, the span hidden in three of their
 //                   (always clear) sign bits; 8 bytes per pair, stored transposed
-//                   ([input][sample]) so that the contraction kernel reads it
-//                   coalesced.
+//                   and in pairs of inputs ([input / 2][sample][input % 2]) so that
+//                   the contraction kernel reads it coalesced, 16 bytes per lane.
 //   kan_mfma        64 or 128 samples x 128 outputs per workgroup, 4 waves side by
 //                   side along the outputs; two or three workgroups share a CU and
 //                   drift apart, so one's MFMAs overlap the other's tile generation
