@@ -60,8 +60,10 @@ typedef enum kan_dtype {
  *   KAN_PATH_GATHER  the precise path: fp32 operands, fp32 accumulation; matches the
  *                    float64 definition to ~1e-6 (bound 1e-5).  Batch 1: one 4-byte
  *                    codeword-window gather per edge on the vector ALUs; from batch 2:
- *                    fused gather + fp32 matrix-core kernel.  Prepared layers (see
- *                    kan_vq_prepare), batch <= 4: codebook buckets in LDS.
+ *                    fused gather + fp32 matrix-core kernel; from batch 112: the kernels
+ *                    of the fp16 path run on coefficients and basis weights split into
+ *                    high and low fp16 parts (three products, fp32-grade sums).  Prepared
+ *                    layers (see kan_vq_prepare), batch <= 4: codebook buckets in LDS.
  *   KAN_PATH_MFMA    fp16 operands on the matrix cores, fp32 accumulation; ~3e-4
  *                    relative per layer (bound 2e-2).  Batch <= 64: fused gather +
  *                    MFMA kernel; above: coefficients dequantised once per call into

@@ -83,6 +83,7 @@ struct LayerPlan {
   int n_jt, n_bt, n_chunks, rows_per_chunk;
   int kind;          // PlanKind
   bool mfma;         // kind == kPlanMfma (coefficient + basis preparation, streaming contraction)
+  int products = 1;  // 3: both operands in high and low fp16 parts, hi*hi + hi*lo + lo*hi (n_chunks counts all slices)
   const char* name;
 };
 
@@ -150,9 +151,10 @@ constexpr int kMfmaTargetWorkgroups = 512;
 constexpr int kMfmaMinRows = 64;
 constexpr int64_t kHalfFusedMaxBatch = 64;   // fp16 path: fused kernel up to here, streaming contraction above
 constexpr int64_t kHalfFusedMaxSamples = 1024;   // ... and only below this many (sample, head) pairs per group
+constexpr int64_t kSplitMinBatch = 112;    // precise path: from here the split-operand matrix-core form (measured crossover 96-128)
 constexpr int64_t kAutoMfmaBatch = 32;    // KAN_PATH_AUTO switches to the matrix cores from here (measured crossover 16-32)
 
-LayerPlan plan_mfma(int n_in, int n_out, int64_t B, int n_heads, int idx_u32, int gb_kind, int code) {
+LayerPlan plan_mfma(int n_in, int n_out, int64_t B, int n_heads, int idx_u32, int gb_kind, int code, bool split3 = false) {
   LayerPlan p;
   p.mfma = true;
   p.kind = kPlanMfma;
@@ -180,6 +182,11 @@ LayerPlan plan_mfma(int n_in, int n_out, int64_t B, int n_heads, int idx_u32, in
   rows = (rows + kMfmaRowsStep - 1) / kMfmaRowsStep * kMfmaRowsStep;
   p.rows_per_chunk = rows;
   p.n_chunks = (n_in + rows - 1) / rows;
+  if (split3) {
+    p.products = 3;
+    p.n_chunks *= 3;
+    p.name = "kan_mfma_split";
+  }
   return p;
 }
 
@@ -248,7 +255,9 @@ bool layer_prepared_ok(const kan_vq_layer& L) {
 //   precise path, prepared layers, B <= kBucketMaxBatch: the bucket kernel (codebook in LDS);
 //   precise path (KAN_PATH_GATHER, and AUTO below batch 32): B = 1 the window-gather kernel,
 //     B >= 2 the fused kernel with fp32 matrix-core operands (the fp32 FMA kernel remains the
-//     dense baseline's);
+//     dense baseline's), from kSplitMinBatch the preparation + streaming contraction of the
+//     fp16 path run three times over operands split into high and low fp16 parts
+//     (hi*hi + hi*lo + lo*hi: fp32-grade sums at matrix-core speed);
 //   fp16 path (KAN_PATH_MFMA, and AUTO from batch 32): up to kHalfFusedMaxBatch the fused
 //     kernel with fp16 operands, above that coefficient/basis preparation + the streaming
 //     contraction.
@@ -264,6 +273,8 @@ LayerPlan plan_vq(const kan_vq_layer& L, int64_t B, int n_heads, bool vec_ok, bo
     return plan_mfma(L.in, L.out, B, n_heads, u32, gbk, code);
   }
   if (prepared_ok && B <= kBucketMaxBatch) return plan_bucket(L, B, n_heads);
+  // large batches: the fp16 machinery with both operands split into high and low parts
+  if (B >= kSplitMinBatch) return plan_mfma(L.in, L.out, B, n_heads, u32, gbk, code, true);
   if (B >= 2) return plan_fused(L.in, L.out, B, n_heads, u32, gbk, code, true);
   return plan_gather(L.in, L.out, B, n_heads, u32, gbk, code, vec_ok);
 }
@@ -343,8 +354,10 @@ kan_status run_layer_group(const LayerPlan& p, GatherArgs& a, const void* const*
   if (p.mfma) {
     PrepCoefArgs pc;
     memset(&pc, 0, sizeof(pc));
+    const bool split3 = p.products == 3;
     pc.cf = w.cf;
     pc.cf_head_stride = (long long)mfma_cf_records(a.n_in, a.n_out);
+    pc.cf_lo = split3 ? w.cf + (long long)heads * pc.cf_head_stride : nullptr;
     pc.bias_partial = w.bp;
     pc.bp_head_stride = (long long)mfma_bp_floats(a.n_in, a.n_out);
     pc.n_in = a.n_in;
@@ -352,9 +365,11 @@ kan_status run_layer_group(const LayerPlan& p, GatherArgs& a, const void* const*
     memcpy(pc.h, a.h, sizeof(pc.h));
     st = run("kan_prep_coef", s, [&] { return launch_prep_coef(p.cfg, pc, heads, s); });
     if (st != KAN_OK) return st;
-    const long long u_stride = x_shared ? 0 : (long long)((a.n_in + 15) / 16 * 16) * a.B;
+    const long long u_elems = (long long)((a.n_in + 15) / 16 * 16) * a.B;
+    const long long u_stride = x_shared ? 0 : u_elems;
+    uint2* const u_lo = split3 ? w.u + (x_shared ? 1 : heads) * u_elems : nullptr;
     st = run("kan_prep_basis", s, [&] {
-      return launch_prep_basis(a.x, a.x_head_stride, chain.in_parts, chain.in_part_stride, chain.in_tanh, w.u,
+      return launch_prep_basis(a.x, a.x_head_stride, chain.in_parts, chain.in_part_stride, chain.in_tanh, w.u, u_lo,
                                u_stride, a.n_in, a.B, x_shared ? 1 : heads, a.rule, s);
     });
     if (st != KAN_OK) return st;
@@ -375,9 +390,25 @@ kan_status run_layer_group(const LayerPlan& p, GatherArgs& a, const void* const*
     m.rows_per_chunk = p.rows_per_chunk;
     m.n_jt = p.n_jt;
     m.apply_tanh = tanh_in_kernel;
+    m.bias_on = 1;
     for (int h = 0; h < heads; ++h) m.scale[h] = p.cfg.code == kCbI8 ? a.h[h].scale : 1.0f;
-    dim3 grid((unsigned)(p.n_jt * p.n_bt), (unsigned)p.n_chunks, (unsigned)heads);
+    const int chunks = p.n_chunks / p.products;          // chunks of inputs per product
+    dim3 grid((unsigned)(p.n_jt * p.n_bt), (unsigned)chunks, (unsigned)heads);
     st = run(p.name, s, [&] { return launch_mfma(m, p.cfg.bt, kMfmaTileN, grid, s); });
+    if (split3 && st == KAN_OK) {
+      // the two cross products (their low operands carry a factor 2048) into the slices behind
+      m.bias_on = 0;
+      for (int h = 0; h < heads; ++h) m.scale[h] *= 1.0f / 2048.0f;
+      m.cf = pc.cf_lo;                                    // high weights x low coefficients
+      m.dst = dst + (long long)chunks * count;
+      st = run(p.name, s, [&] { return launch_mfma(m, p.cfg.bt, kMfmaTileN, grid, s); });
+      if (st == KAN_OK) {
+        m.cf = w.cf;                                      // low weights x high coefficients
+        m.W = u_lo;
+        m.dst = dst + 2ll * chunks * count;
+        st = run(p.name, s, [&] { return launch_mfma(m, p.cfg.bt, kMfmaTileN, grid, s); });
+      }
+    }
   } else if (p.kind == kPlanBucket) {
     const BucketGeom g = bucket_geometry(a.n_in, a.n_out, (int)(a.cb_bytes / cb_row_bytes(p.cfg.code)), p.cfg.code,
                                          p.cfg.gb_kind);
@@ -496,11 +527,11 @@ kan_status plan_head(const kan_vq_layer* layers, int32_t n_layers, int32_t n_hea
     auto grow = [](size_t& dst, size_t v) { if (v > dst) dst = v; };
     grow(ws->partial, partial_bytes(p, R.out, B, group));
     if (p.mfma) {
-      grow(ws->cf, round_up((size_t)group * mfma_cf_records(R.in, R.out) * sizeof(uint4), 256));
+      grow(ws->cf, round_up((size_t)(p.products == 3 ? 2 : 1) * group * mfma_cf_records(R.in, R.out) * sizeof(uint4), 256));
       grow(ws->bp, round_up((size_t)group * mfma_bp_floats(R.in, R.out) * sizeof(float), 256));
     }
     if (p.mfma)
-      grow(ws->u, round_up((size_t)(l == 0 ? 1 : group) * (size_t)((R.in + 15) / 16 * 16) * (size_t)B * sizeof(uint2), 256));
+      grow(ws->u, round_up((size_t)(p.products == 3 ? 2 : 1) * (size_t)(l == 0 ? 1 : group) * (size_t)((R.in + 15) / 16 * 16) * (size_t)B * sizeof(uint2), 256));
     if (l + 1 < n_layers) grow(ws->hidden, round_up((size_t)n_heads * (size_t)B * R.out * sizeof(float), 256));
   }
   // chained layers hand their partial sums straight on: two buffers, used in turn

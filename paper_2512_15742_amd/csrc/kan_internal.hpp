@@ -58,7 +58,8 @@ hipError_t launch_gather_bt16(const GatherCfg&, const GatherArgs&, dim3 grid, hi
 constexpr int kMfmaPrepRows = 32;   // input rows per partial bias sum (and per prep workgroup)
 
 struct PrepCoefArgs {
-  uint4* cf;                   // coefficient fragments, [head][step][5][2][n_out] records of 16 bytes
+  uint4* cf;                   // coefficient fragments, [head][step][5][2][2][n_out] records of 16 bytes
+  uint4* cf_lo;                // split form: the low parts (c - fp16(c)) * 2048 in the same layout; null otherwise
   long long cf_head_stride;    // in records
   float* bias_partial;         // [head][ceil(n_in / 32)][n_out]
   long long bp_head_stride;    // in floats
@@ -73,6 +74,7 @@ struct MfmaArgs {
   long long w_head_stride;     // 0 when all heads share the input
   const float* bias_partial;
   long long bp_head_stride;
+  int bias_on;                 // 0: this launch adds no bias sums (a cross product of the split form)
   float* dst;
   long long dst_head_stride, dst_chunk_stride;
   int n_in, n_out, B;
@@ -85,9 +87,10 @@ struct MfmaArgs {
 hipError_t launch_prep_coef(const GatherCfg&, const PrepCoefArgs&, int heads, hipStream_t);
 // The input of the layer is x, or act(sum of x_parts slices of x) when the previous layer left
 // its partial sums (slices x_part_stride elements apart).
+// W_lo (split form, else null): the low parts (w - hi) * 2048 of the weights, hi = w cut to fp16 towards zero.
 hipError_t launch_prep_basis(const float* x, long long x_head_stride, int x_parts, long long x_part_stride,
-                             int x_tanh, uint2* W, long long w_head_stride, int n_in, int B, int heads, int rule,
-                             hipStream_t);
+                             int x_tanh, uint2* W, uint2* W_lo, long long w_head_stride, int n_in, int B, int heads,
+                             int rule, hipStream_t);
 hipError_t launch_mfma(const MfmaArgs&, int tile_m, int tile_n, dim3 grid, hipStream_t);   // samples (64 | 128) x outputs (128) per tile
 
 // ---- fused gather + matrix-core kernel (batch tiles of 32 or 64 samples) --------------

@@ -57,6 +57,15 @@ typedef unsigned int u32x4 __attribute__((ext_vector_type(4)));
 typedef unsigned int u32x2 __attribute__((ext_vector_type(2)));
 typedef _Float16 h16x16 __attribute__((ext_vector_type(16)));
 
+// Both halves of a packed fp16 pair with subnormals set to zero.  The split form does this to
+// its high parts itself, before it forms the low parts from what is left, so that the sum of
+// the parts does not depend on how conversions and matrix instructions treat subnormals.
+__device__ __forceinline__ uint32_t flush_h2(uint32_t v) {
+  if ((v & 0x7c00u) == 0u) v &= 0xffff8000u;
+  if ((v & 0x7c000000u) == 0u) v &= 0x8000ffffu;
+  return v;
+}
+
 // ---- kan_prep_coef ------------------------------------------------------------------
 // Chat as uint4 records: rec[(((step*5 + S) * 2 + h) * 2 + a) * n_out + j], step = i / 16: the
 // half a (elements 8a .. 8a+7) of the B operand of lane half h in sparse MFMA S of the step,
@@ -67,7 +76,10 @@ typedef _Float16 h16x16 __attribute__((ext_vector_type(16)));
 // A workgroup covers 64 output columns x 32 input rows: each of its 4 waves takes 8 rows
 // (half a step; lanes along the columns), so all loads of an edge's chain (metadata, then
 // codeword) are in flight at once across many small waves.
-template <typename IdxT, typename GbT, typename CbT>
+// SPLIT: fp32-grade operands for the precise path at large batch: every coefficient c (fp32) is
+// written as hi = fp16(c) into cf and as lo = fp16((c - hi) * 2048) into cf_lo (hi + lo / 2048
+// carries 22 bits of c; the factor keeps the low parts out of the fp16 subnormals).
+template <typename IdxT, typename GbT, typename CbT, bool SPLIT>
 __global__ __launch_bounds__(kThreads) void kan_prep_coef_kernel(const PrepCoefArgs a) {
   __shared__ float sb[4][64];
   const int head = blockIdx.z;
@@ -80,6 +92,7 @@ __global__ __launch_bounds__(kThreads) void kan_prep_coef_kernel(const PrepCoefA
   const Q8Params qp = {hp.gain_log2_lo, hp.gain_log2_step, hp.bias_scale};
   const CbT* cb = (const CbT*)hp.cb;
   uint4* cf = a.cf + (long long)head * a.cf_head_stride;
+  uint4* cf_lo = SPLIT ? a.cf_lo + (long long)head * a.cf_head_stride : nullptr;
   float* bp = a.bias_partial + (long long)head * a.bp_head_stride;
   const int n_in = a.n_in, n_out = a.n_out;
   const int ib = blockIdx.y * kMfmaPrepRows + wave * 8;
@@ -109,19 +122,38 @@ __global__ __launch_bounds__(kThreads) void kan_prep_coef_kernel(const PrepCoefA
 #pragma unroll
     for (int q = 0; q < 2; ++q) {
       const long long S = 2 * wh + q;
-      uint32_t tail[4];
+      uint32_t tail[4], tail_lo[4];
 #pragma unroll
       for (int t = 0; t < 4; ++t) {                       // ii = 8 wh + 4 q + t: h = t / 2, a = t % 2
-        uint32_t w[5];
-        dequant_row<CbT>(raw[4 * q + t], g[4 * q + t], w);   // (c0,c1) (c2,c3) (c4,c5) (c6,c7) (c8,c9)
-        const uint32_t p0 = __builtin_amdgcn_perm(w[2], w[0], 0x07060100u);   // (c0, c5)
-        const uint32_t p1 = __builtin_amdgcn_perm(w[3], w[0], 0x05040302u);   // (c1, c6)
-        const uint32_t p2 = __builtin_amdgcn_perm(w[3], w[1], 0x07060100u);   // (c2, c7)
-        const uint32_t p3 = __builtin_amdgcn_perm(w[4], w[1], 0x05040302u);   // (c3, c8)
-        tail[t] = __builtin_amdgcn_perm(w[4], w[2], 0x07060100u);             // (c4, c9)
-        cf[(((step * 5 + S) * 2 + (t >> 1)) * 2 + (t & 1)) * n_out + j] = make_uint4(p0, p1, p2, p3);
+        const long long rec = (((step * 5 + S) * 2 + (t >> 1)) * 2 + (t & 1)) * n_out + j;
+        if constexpr (SPLIT) {
+          float c[kG];
+          dequant_row_f32<CbT>(raw[4 * q + t], g[4 * q + t], c);
+          uint32_t hi[5], lo[5];
+#pragma unroll
+          for (int m = 0; m < 5; ++m) {                   // pair (m, m + 5)
+            hi[m] = flush_h2(pack_h2(c[m], c[m + 5]));
+            lo[m] = flush_h2(pack_h2((c[m] - half_bits_to_float(hi[m] & 0xffffu)) * 2048.0f,
+                                     (c[m + 5] - half_bits_to_float(hi[m] >> 16)) * 2048.0f));
+          }
+          cf[rec] = make_uint4(hi[0], hi[1], hi[2], hi[3]);
+          cf_lo[rec] = make_uint4(lo[0], lo[1], lo[2], lo[3]);
+          tail[t] = hi[4];
+          tail_lo[t] = lo[4];
+        } else {
+          uint32_t w[5];
+          dequant_row<CbT>(raw[4 * q + t], g[4 * q + t], w);   // (c0,c1) (c2,c3) (c4,c5) (c6,c7) (c8,c9)
+          const uint32_t p0 = __builtin_amdgcn_perm(w[2], w[0], 0x07060100u);   // (c0, c5)
+          const uint32_t p1 = __builtin_amdgcn_perm(w[3], w[0], 0x05040302u);   // (c1, c6)
+          const uint32_t p2 = __builtin_amdgcn_perm(w[3], w[1], 0x07060100u);   // (c2, c7)
+          const uint32_t p3 = __builtin_amdgcn_perm(w[4], w[1], 0x05040302u);   // (c3, c8)
+          tail[t] = __builtin_amdgcn_perm(w[4], w[2], 0x07060100u);             // (c4, c9)
+          cf[rec] = make_uint4(p0, p1, p2, p3);
+        }
       }
-      cf[(((step * 5 + 4) * 2 + wh) * 2 + q) * n_out + j] = make_uint4(tail[0], tail[1], tail[2], tail[3]);
+      const long long trec = (((step * 5 + 4) * 2 + wh) * 2 + q) * n_out + j;
+      cf[trec] = make_uint4(tail[0], tail[1], tail[2], tail[3]);
+      if constexpr (SPLIT) cf_lo[trec] = make_uint4(tail_lo[0], tail_lo[1], tail_lo[2], tail_lo[3]);
     }
   }
   sb[wave][lane] = bs;
@@ -139,18 +171,20 @@ __global__ __launch_bounds__(kThreads) void kan_prep_coef_kernel(const PrepCoefA
 // the order of the slices and squashed, so that no separate reduction pass runs in between.
 __global__ __launch_bounds__(256) void kan_prep_basis_kernel(const float* __restrict__ x, long long x_head_stride,
                                                              int x_parts, long long x_part_stride, int x_tanh,
-                                                             uint2* __restrict__ W, long long w_head_stride,
-                                                             int n_in, int B, int rule) {
+                                                             uint2* __restrict__ W, uint2* __restrict__ W_lo,
+                                                             long long w_head_stride, int n_in, int B, int rule) {
   __shared__ uint2 tile[32][33];
+  __shared__ uint2 tile_lo[32][33];
   const int head = blockIdx.z;
   const float* xh = x + (long long)head * x_head_stride;
   uint2* wh = W + (long long)head * w_head_stride;
+  uint2* wl = W_lo ? W_lo + (long long)head * w_head_stride : nullptr;
   const int tx = threadIdx.x & 31, ty = threadIdx.x >> 5;      // 32 x 8
   const int ib = blockIdx.x * 32, bb = blockIdx.y * 32;
 #pragma unroll
   for (int r = 0; r < 4; ++r) {
     const int b = bb + ty + 8 * r, i = ib + tx;
-    uint2 v = make_uint2(0u, 0u);
+    uint2 v = make_uint2(0u, 0u), vlo = make_uint2(0u, 0u);
     if (b < B && i < n_in) {
       const float* xp = xh + (long long)b * n_in + i;
       float xv = xp[0];
@@ -165,17 +199,40 @@ __global__ __launch_bounds__(256) void kan_prep_basis_kernel(const float* __rest
       const BasisW bw = basis_fast(xv, rule);
       const uint32_t l = (uint32_t)bw.span;
       const float w0 = bw.w0, w1 = bw.w1, w2 = bw.w2, w3 = bw.w3;
-      v.x = pack_h2(w0, w1) | ((l & 1u) << 15) | ((l & 2u) << 30);
-      v.y = pack_h2(w2, w3) | ((l & 4u) << 13);
+      const uint32_t sx = ((l & 1u) << 15) | ((l & 2u) << 30), sy = (l & 4u) << 13;
+      uint32_t hx = pack_h2(w0, w1), hy = pack_h2(w2, w3);
+      if (wl) {
+        // split form: the high part is the weight cut to fp16 towards zero, so that the low
+        // part (w - hi) * 2048 is never negative and its sign bits are free for the span too
+        const float w[4] = {w0, w1, w2, w3};
+        uint32_t hb[4];
+        float rest[4];
+#pragma unroll
+        for (int k = 0; k < 4; ++k) {
+          hb[k] = ((k & 1) ? ((k < 2 ? hx : hy) >> 16) : ((k < 2 ? hx : hy) & 0xffffu));
+          if (half_bits_to_float(hb[k]) > w[k]) hb[k] -= 1u;       // one fp16 step down (w > 0 there)
+          if ((hb[k] & 0x7c00u) == 0u) hb[k] = 0u;                 // no subnormal high parts (and no -0)
+          rest[k] = (w[k] - half_bits_to_float(hb[k])) * 2048.0f;
+        }
+        hx = hb[0] | (hb[1] << 16);
+        hy = hb[2] | (hb[3] << 16);
+        vlo.x = (flush_h2(pack_h2(rest[0], rest[1])) & 0x7fff7fffu) | sx;
+        vlo.y = (flush_h2(pack_h2(rest[2], rest[3])) & 0x7fff7fffu) | sy;
+      }
+      v.x = hx | sx;
+      v.y = hy | sy;
     }
     tile[ty + 8 * r][tx] = v;
+    if (wl) tile_lo[ty + 8 * r][tx] = vlo;
   }
   __syncthreads();
 #pragma unroll
   for (int r = 0; r < 4; ++r) {
     const int i = ib + ty + 8 * r, b = bb + tx;
-    if (i < (n_in + IT - 1) / IT * IT && b < B)      // rows up to a whole step: zeros
+    if (i < (n_in + IT - 1) / IT * IT && b < B) {    // rows up to a whole step: zeros
       wh[((long long)(i >> 1) * B + b) * 2 + (i & 1)] = tile[tx][ty + 8 * r];
+      if (wl) wl[((long long)(i >> 1) * B + b) * 2 + (i & 1)] = tile_lo[tx][ty + 8 * r];
+    }
   }
 }
 
@@ -467,7 +524,7 @@ __global__ __launch_bounds__(kMfmaThreads, MB == 2 ? 3 : 2) void kan_mfma_kernel
 #pragma unroll
     for (int u = 0; u < 8; ++u) bs += rb0 + u < rb1 ? bias_v[u] : 0.f;
     for (int rb = rb0 + 8; rb < rb1; ++rb) bs += bp[(long long)rb * n_out];
-    sBias[tid] = bs;      // read after the barriers of the main loop
+    sBias[tid] = a.bias_on ? bs : 0.f;      // read after the barriers of the main loop
   }
   gen_phi(uv[0], sA[0]);
 
@@ -524,26 +581,26 @@ __global__ __launch_bounds__(kMfmaThreads, MB == 2 ? 3 : 2) void kan_mfma_kernel
   }
 }
 
-template <typename IdxT>
+template <typename IdxT, bool SPLIT>
 hipError_t prep_types(const GatherCfg& c, const PrepCoefArgs& a, dim3 grid, hipStream_t s) {
   if (c.code == kCbI8) {
     if (c.gb_kind == kGbQ8)
-      hipLaunchKernelGGL((kan_prep_coef_kernel<IdxT, q8_t, int8_t>), grid, dim3(kThreads), 0, s, a);
+      hipLaunchKernelGGL((kan_prep_coef_kernel<IdxT, q8_t, int8_t, SPLIT>), grid, dim3(kThreads), 0, s, a);
     else if (c.gb_kind == kGbF16)
-      hipLaunchKernelGGL((kan_prep_coef_kernel<IdxT, __half, int8_t>), grid, dim3(kThreads), 0, s, a);
+      hipLaunchKernelGGL((kan_prep_coef_kernel<IdxT, __half, int8_t, SPLIT>), grid, dim3(kThreads), 0, s, a);
     else
-      hipLaunchKernelGGL((kan_prep_coef_kernel<IdxT, float, int8_t>), grid, dim3(kThreads), 0, s, a);
+      hipLaunchKernelGGL((kan_prep_coef_kernel<IdxT, float, int8_t, SPLIT>), grid, dim3(kThreads), 0, s, a);
   } else {
     if (c.gb_kind == kGbQ8) return hipErrorInvalidValue;    // byte-coded gain/bias go with Int8 codebooks
     if (c.code == kCbF16) {
       if (c.gb_kind == kGbF16)
-        hipLaunchKernelGGL((kan_prep_coef_kernel<IdxT, __half, __half>), grid, dim3(kThreads), 0, s, a);
+        hipLaunchKernelGGL((kan_prep_coef_kernel<IdxT, __half, __half, SPLIT>), grid, dim3(kThreads), 0, s, a);
       else
-        hipLaunchKernelGGL((kan_prep_coef_kernel<IdxT, float, __half>), grid, dim3(kThreads), 0, s, a);
+        hipLaunchKernelGGL((kan_prep_coef_kernel<IdxT, float, __half, SPLIT>), grid, dim3(kThreads), 0, s, a);
     } else if (c.gb_kind == kGbF16)
-      hipLaunchKernelGGL((kan_prep_coef_kernel<IdxT, __half, float>), grid, dim3(kThreads), 0, s, a);
+      hipLaunchKernelGGL((kan_prep_coef_kernel<IdxT, __half, float, SPLIT>), grid, dim3(kThreads), 0, s, a);
     else
-      hipLaunchKernelGGL((kan_prep_coef_kernel<IdxT, float, float>), grid, dim3(kThreads), 0, s, a);
+      hipLaunchKernelGGL((kan_prep_coef_kernel<IdxT, float, float, SPLIT>), grid, dim3(kThreads), 0, s, a);
   }
   return hipGetLastError();
 }
@@ -553,16 +610,17 @@ hipError_t prep_types(const GatherCfg& c, const PrepCoefArgs& a, dim3 grid, hipS
 hipError_t launch_prep_coef(const GatherCfg& c, const PrepCoefArgs& a, int heads, hipStream_t s) {
   if (c.code == kDense) return hipErrorInvalidValue;
   dim3 grid((a.n_out + 63) / 64, (a.n_in + kMfmaPrepRows - 1) / kMfmaPrepRows, heads);
-  return c.idx_u32 ? prep_types<uint32_t>(c, a, grid, s) : prep_types<uint16_t>(c, a, grid, s);
+  if (a.cf_lo) return c.idx_u32 ? prep_types<uint32_t, true>(c, a, grid, s) : prep_types<uint16_t, true>(c, a, grid, s);
+  return c.idx_u32 ? prep_types<uint32_t, false>(c, a, grid, s) : prep_types<uint16_t, false>(c, a, grid, s);
 }
 
 hipError_t launch_prep_basis(const float* x, long long x_head_stride, int x_parts, long long x_part_stride,
-                             int x_tanh, uint2* W, long long w_head_stride, int n_in, int B, int heads, int rule,
-                             hipStream_t s) {
+                             int x_tanh, uint2* W, uint2* W_lo, long long w_head_stride, int n_in, int B, int heads,
+                             int rule, hipStream_t s) {
   if (x_parts < 1) return hipErrorInvalidValue;
   dim3 grid((n_in + 31) / 32, (B + 31) / 32, heads);
   hipLaunchKernelGGL(kan_prep_basis_kernel, grid, dim3(256), 0, s, x, x_head_stride, x_parts, x_part_stride, x_tanh,
-                     W, w_head_stride, n_in, B, rule);
+                     W, W_lo, w_head_stride, n_in, B, rule);
   return hipGetLastError();
 }
 
