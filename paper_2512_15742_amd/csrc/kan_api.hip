@@ -363,7 +363,10 @@ kan_status run_layer_group(const LayerPlan& p, GatherArgs& a, const void* const*
     pc.n_in = a.n_in;
     pc.n_out = a.n_out;
     memcpy(pc.h, a.h, sizeof(pc.h));
-    st = run("kan_prep_coef", s, [&] { return launch_prep_coef(p.cfg, pc, heads, s); });
+    if (p.cfg.code == kDense)
+      st = run("kan_prep_dense", s, [&] { return launch_prep_dense((const float*)a.h[0].cb, pc.cf, pc.cf_lo, a.n_in, a.n_out, s); });
+    else
+      st = run("kan_prep_coef", s, [&] { return launch_prep_coef(p.cfg, pc, heads, s); });
     if (st != KAN_OK) return st;
     const long long u_elems = (long long)((a.n_in + 15) / 16 * 16) * a.B;
     const long long u_stride = x_shared ? 0 : u_elems;
@@ -379,7 +382,9 @@ kan_status run_layer_group(const LayerPlan& p, GatherArgs& a, const void* const*
     m.cf_head_stride = pc.cf_head_stride;
     m.W = w.u;
     m.w_head_stride = u_stride;
-    m.bias_partial = w.bp;
+    // (the dense form has no bias sums: the kernel still reads the rows it would add, so it is
+    // given valid memory - the coefficient records, which are larger - and told not to add them)
+    m.bias_partial = p.cfg.code == kDense ? (const float*)w.cf : w.bp;
     m.bp_head_stride = pc.bp_head_stride;
     m.dst = dst;
     m.dst_head_stride = dst_head_stride;
@@ -390,7 +395,7 @@ kan_status run_layer_group(const LayerPlan& p, GatherArgs& a, const void* const*
     m.rows_per_chunk = p.rows_per_chunk;
     m.n_jt = p.n_jt;
     m.apply_tanh = tanh_in_kernel;
-    m.bias_on = 1;
+    m.bias_on = p.cfg.code == kDense ? 0 : 1;            // the dense form has no bias
     for (int h = 0; h < heads; ++h) m.scale[h] = p.cfg.code == kCbI8 ? a.h[h].scale : 1.0f;
     const int chunks = p.n_chunks / p.products;          // chunks of inputs per product
     dim3 grid((unsigned)(p.n_jt * p.n_bt), (unsigned)chunks, (unsigned)heads);
@@ -669,11 +674,31 @@ kan_status kan_vq_layer_forward(const kan_vq_layer* L, const float* x, int64_t B
   return kan_vq_head_forward(L, 1, 1, x, B, y, ws, ws_bytes, path, stream);
 }
 
+// The dense baseline: the fp32 FMA kernel, and from kSplitMinBatch the split-operand matrix-core
+// form the precise VQ path uses (a converter of the coefficients in place of gather + dequantise).
+static LayerPlan plan_dense(int32_t in, int32_t out, int64_t B) {
+  if (B >= kSplitMinBatch) {
+    LayerPlan p = plan_mfma(in, out, B, 1, 0, 0, kDense, true);
+    p.name = "kan_dense_split";
+    return p;
+  }
+  LayerPlan p = plan_gather(in, out, B, 1, 0, 0, kDense, true);
+  p.name = "kan_dense";
+  return p;
+}
+
+static void dense_ws(const LayerPlan& p, int32_t in, int32_t out, int64_t B, size_t* partial, size_t* cf, size_t* u) {
+  *partial = partial_bytes(p, out, B, 1);
+  *cf = p.mfma ? round_up(2 * mfma_cf_records(in, out) * sizeof(uint4), 256) : 0;
+  *u = p.mfma ? round_up(2 * (size_t)((in + 15) / 16 * 16) * (size_t)B * sizeof(uint2), 256) : 0;
+}
+
 size_t kan_dense_workspace_bytes(int32_t in, int32_t out, int64_t B) {
   if (in < 1 || out < 1 || in > kMaxDim || out > kMaxDim || B < 0 || B > kMaxBatch) return (size_t)-1;
   if (B == 0) return 0;
-  const LayerPlan p = plan_gather(in, out, B, 1, 0, 0, kDense, true);
-  return partial_bytes(p, out, B, 1);
+  size_t partial, cf, u;
+  dense_ws(plan_dense(in, out, B), in, out, B, &partial, &cf, &u);
+  return partial + cf + u;
 }
 
 kan_status kan_dense_layer_forward(const float* coef, int32_t in, int32_t out, int32_t G, const float* x,
@@ -683,9 +708,10 @@ kan_status kan_dense_layer_forward(const float* coef, int32_t in, int32_t out, i
   if (B == 0) return KAN_OK;
   if (!coef || !x || !y) return KAN_ERR_NULL;
   if (!aligned(coef, 8) || !aligned(x, 4) || !aligned(y, 4)) return KAN_ERR_SHAPE;
-  LayerPlan p = plan_gather(in, out, B, 1, 0, 0, kDense, true);
-  p.name = "kan_dense";
-  const size_t need = partial_bytes(p, out, B, 1);
+  const LayerPlan p = plan_dense(in, out, B);
+  size_t partial, cf, u;
+  dense_ws(p, in, out, B, &partial, &cf, &u);
+  const size_t need = partial + cf + u;
   if (need > 0 && (!ws || !aligned(ws, 256) || ws_bytes < need)) return KAN_ERR_WORKSPACE;
   GatherArgs a;
   memset(&a, 0, sizeof(a));
@@ -700,6 +726,8 @@ kan_status kan_dense_layer_forward(const float* coef, int32_t in, int32_t out, i
   WsPtrs w;
   memset(&w, 0, sizeof(w));
   w.partial = (float*)ws;
+  w.cf = (uint4*)((char*)ws + partial);
+  w.u = (uint2*)((char*)ws + partial + cf);
   return run_layer_group(p, a, nullptr, 1, true, y, (long long)B * out, w, 0, (hipStream_t)stream);
 }
 

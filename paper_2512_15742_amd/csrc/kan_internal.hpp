@@ -85,6 +85,8 @@ struct MfmaArgs {
 };
 
 hipError_t launch_prep_coef(const GatherCfg&, const PrepCoefArgs&, int heads, hipStream_t);
+// Dense fp32 coefficients coef[n_in][n_out][10] into the split form (high and low fp16 records).
+hipError_t launch_prep_dense(const float* coef, uint4* cf, uint4* cf_lo, int n_in, int n_out, hipStream_t);
 // The input of the layer is x, or act(sum of x_parts slices of x) when the previous layer left
 // its partial sums (slices x_part_stride elements apart).
 // W_lo (split form, else null): the low parts (w - hi) * 2048 of the weights, hi = w cut to fp16 towards zero.

@@ -66,6 +66,16 @@ __device__ __forceinline__ uint32_t flush_h2(uint32_t v) {
   return v;
 }
 
+// Ten fp32 coefficients as high and low fp16 parts, in pairs (m, m + 5): c = hi + lo / 2048.
+__device__ __forceinline__ void split_pairs(const float (&c)[kG], uint32_t (&hi)[5], uint32_t (&lo)[5]) {
+#pragma unroll
+  for (int m = 0; m < 5; ++m) {
+    hi[m] = flush_h2(pack_h2(c[m], c[m + 5]));
+    lo[m] = flush_h2(pack_h2((c[m] - half_bits_to_float(hi[m] & 0xffffu)) * 2048.0f,
+                             (c[m + 5] - half_bits_to_float(hi[m] >> 16)) * 2048.0f));
+  }
+}
+
 // ---- kan_prep_coef ------------------------------------------------------------------
 // Chat as uint4 records: rec[(((step*5 + S) * 2 + h) * 2 + a) * n_out + j], step = i / 16: the
 // half a (elements 8a .. 8a+7) of the B operand of lane half h in sparse MFMA S of the step,
@@ -130,12 +140,7 @@ __global__ __launch_bounds__(kThreads) void kan_prep_coef_kernel(const PrepCoefA
           float c[kG];
           dequant_row_f32<CbT>(raw[4 * q + t], g[4 * q + t], c);
           uint32_t hi[5], lo[5];
-#pragma unroll
-          for (int m = 0; m < 5; ++m) {                   // pair (m, m + 5)
-            hi[m] = flush_h2(pack_h2(c[m], c[m + 5]));
-            lo[m] = flush_h2(pack_h2((c[m] - half_bits_to_float(hi[m] & 0xffffu)) * 2048.0f,
-                                     (c[m + 5] - half_bits_to_float(hi[m] >> 16)) * 2048.0f));
-          }
+          split_pairs(c, hi, lo);
           cf[rec] = make_uint4(hi[0], hi[1], hi[2], hi[3]);
           cf_lo[rec] = make_uint4(lo[0], lo[1], lo[2], lo[3]);
           tail[t] = hi[4];
@@ -160,6 +165,52 @@ __global__ __launch_bounds__(kThreads) void kan_prep_coef_kernel(const PrepCoefA
   __syncthreads();
   if (wave == 0 && j < n_out)
     bp[(long long)blockIdx.y * n_out + j] = (sb[0][lane] + sb[1][lane]) + (sb[2][lane] + sb[3][lane]);
+}
+
+// ---- kan_prep_dense -----------------------------------------------------------------
+// The dense baseline at large batch: its fp32 coefficients coef[i][j][10] in the split form,
+// in the record order of kan_prep_coef (same grid: 64 columns x 32 rows per workgroup, a wave
+// takes 8 rows).  No bias sums: the contraction is launched without them.
+__global__ __launch_bounds__(kThreads) void kan_prep_dense_kernel(const float* __restrict__ coef, uint4* __restrict__ cf,
+                                                                  uint4* __restrict__ cf_lo, int n_in, int n_out) {
+  const int lane = threadIdx.x & 63, wave = threadIdx.x >> 6;
+  const int j = blockIdx.x * 64 + lane;
+  const int ib = blockIdx.y * kMfmaPrepRows + wave * 8;
+  if (j >= n_out || ib >= (n_in + IT - 1) / IT * IT) return;
+  const long long step = ib / IT;
+  const int wh = (ib / 8) & 1;
+  float2 raw[8][5];
+#pragma unroll
+  for (int r = 0; r < 8; ++r) {
+    const float2* p = (const float2*)(coef + ((long long)min(ib + r, n_in - 1) * n_out + j) * kG);
+#pragma unroll
+    for (int m = 0; m < 5; ++m) raw[r][m] = p[m];
+  }
+#pragma unroll
+  for (int q = 0; q < 2; ++q) {
+    const long long S = 2 * wh + q;
+    uint32_t tail[4], tail_lo[4];
+#pragma unroll
+    for (int t = 0; t < 4; ++t) {
+      const bool ok = ib + 4 * q + t < n_in;              // rows past the end of a ragged last step are zeros
+      float c[kG];
+#pragma unroll
+      for (int m = 0; m < 5; ++m) {
+        c[2 * m] = ok ? raw[4 * q + t][m].x : 0.f;
+        c[2 * m + 1] = ok ? raw[4 * q + t][m].y : 0.f;
+      }
+      uint32_t hi[5], lo[5];
+      split_pairs(c, hi, lo);
+      const long long rec = (((step * 5 + S) * 2 + (t >> 1)) * 2 + (t & 1)) * n_out + j;
+      cf[rec] = make_uint4(hi[0], hi[1], hi[2], hi[3]);
+      cf_lo[rec] = make_uint4(lo[0], lo[1], lo[2], lo[3]);
+      tail[t] = hi[4];
+      tail_lo[t] = lo[4];
+    }
+    const long long trec = (((step * 5 + 4) * 2 + wh) * 2 + q) * n_out + j;
+    cf[trec] = make_uint4(tail[0], tail[1], tail[2], tail[3]);
+    cf_lo[trec] = make_uint4(tail_lo[0], tail_lo[1], tail_lo[2], tail_lo[3]);
+  }
 }
 
 // ---- kan_prep_basis -----------------------------------------------------------------
@@ -612,6 +663,13 @@ hipError_t launch_prep_coef(const GatherCfg& c, const PrepCoefArgs& a, int heads
   dim3 grid((a.n_out + 63) / 64, (a.n_in + kMfmaPrepRows - 1) / kMfmaPrepRows, heads);
   if (a.cf_lo) return c.idx_u32 ? prep_types<uint32_t, true>(c, a, grid, s) : prep_types<uint16_t, true>(c, a, grid, s);
   return c.idx_u32 ? prep_types<uint32_t, false>(c, a, grid, s) : prep_types<uint16_t, false>(c, a, grid, s);
+}
+
+hipError_t launch_prep_dense(const float* coef, uint4* cf, uint4* cf_lo, int n_in, int n_out, hipStream_t s) {
+  if (!coef || !cf || !cf_lo) return hipErrorInvalidValue;
+  dim3 grid((n_out + 63) / 64, (n_in + kMfmaPrepRows - 1) / kMfmaPrepRows, 1);
+  hipLaunchKernelGGL(kan_prep_dense_kernel, grid, dim3(kThreads), 0, s, coef, cf, cf_lo, n_in, n_out);
+  return hipGetLastError();
 }
 
 hipError_t launch_prep_basis(const float* x, long long x_head_stride, int x_parts, long long x_part_stride,

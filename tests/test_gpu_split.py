@@ -126,3 +126,37 @@ def test_split_config2_and_config3(kb, B):
     rows = np.unique(np.concatenate([np.arange(0, B, 64), np.random.default_rng(B).choice(B, 16, replace=False)]))
     y_ref = ko.vq_head_forward(x3[rows], [p.as_dict() for p in Ps])
     assert ko.error_report(y3[rows], y_ref)["headline"] <= TOL_FP32
+
+
+# ---- the dense baseline on the same split operands -----------------------------------
+
+@pytest.mark.parametrize("n_in,n_out,B", [(8, 32, 129), (130, 67, 200), (257, 130, 150), (64, 520, 133),
+                                          (1000, 264, 300), (2052, 70, 112), (33, 1, 500)])
+def test_dense_baseline_split_form(kb, n_in, n_out, B):
+    """The dense layer at batch >= 112 runs the same three contractions on coefficients it
+    splits itself; below that it stays on the fp32 FMA kernel.  Both against the oracle's
+    dense layer, and against each other across the switch (batch 111 / 112 share rows)."""
+    rng = np.random.default_rng(n_in * 13 + n_out)
+    coef = (rng.standard_normal((n_in, n_out, 10)) * rng.uniform(1e-3, 2.0, (n_in, n_out, 1))).astype(np.float32)
+    coef[0, 0, :] = 1e-6                      # below fp16's normal range
+    x = synth.make_x(B + 5, B, n_in)
+    x[0, 0] = 1.0
+    x[-1, -1] = -1.0
+    cd = to_dev(coef)
+    y = kb.kan_dense_layer_forward(cd, to_dev(x)).cpu().numpy()
+    y_ref, A = ko.dense_layer_forward(coef, x, return_abs=True)
+    rep = ko.error_report(y, y_ref, A)
+    assert rep["headline"] <= TOL_FP32 and rep["strict"] <= TOL_FP32, rep
+    y_small = kb.kan_dense_layer_forward(cd, to_dev(x[:111])).cpu().numpy()
+    assert np.abs(y_small - y[:111]).max() <= 2 * TOL_FP32 * np.abs(y_ref).max()
+
+
+def test_dense_baseline_split_config2_twin(kb):
+    (P,), x = synth.config2(256)
+    coef = ko.reconstruct_coefficients(**P.as_dict()).astype(np.float32)
+    xd = to_dev(x)
+    yd = kb.kan_dense_layer_forward(to_dev(coef), xd).cpu().numpy()
+    y = kb.kan_vq_layer_forward(kb.VQLayer(P), xd, path=kb.KAN_PATH_GATHER).cpu().numpy()
+    y_ref = ko.dense_layer_forward(coef, x)
+    assert ko.error_report(yd, y_ref)["headline"] <= TOL_FP32
+    assert np.abs(yd - y).max() <= 2 * TOL_FP32 * np.abs(y_ref).max()
