@@ -146,7 +146,7 @@ def sweep(kb, torch, synth):
     ps, x = synth.config1()
     vq_rows("config1 64->32 K=256 fp32", [ps], x, both, 50)
     from oracle import kan_oracle as ko     # dense twins are reconstructed with the oracle (setup, untimed)
-    for B in (1, 16, 256):
+    for B in (1, 16, 256, 1024):
         ps, x = synth.config2(B)
         vq_rows("config2 2048->512 K=65536 fp32", [ps], x, both, 30)
         if B == 1:
@@ -158,7 +158,8 @@ def sweep(kb, torch, synth):
         t = wall(lambda: kb.kan_dense_layer_forward(coef, xd, ws=ws, y=y), 30)
         print(json.dumps({"workload": "config2 dense twin 2048x512x10 fp32", "batch": B, "path": "dense",
                           "us_per_forward": round(t * 1e6, 2), "edge_evals_per_s": 2048 * 512 * B / t,
-                          "coef_GBps": coef.numel() * 4 / t / 1e9}), flush=True)
+                          "coef_GBps": coef.numel() * 4 / t / 1e9,
+                          "kernel": kb.kan_dense_planned_kernel(2048, 512, B)}), flush=True)
         del coef
     for B in (1, 2, 4, 16, 64, 256, 1024, 4096):
         ps, x = synth.config3(B)

@@ -137,8 +137,8 @@ kan_status kan_vq_layer_forward(const kan_vq_layer* L, const float* x, int64_t B
 /* Dense-coefficient KAN layer (the uncompressed 40-bytes-per-edge form of
  * section 4.2): y[b][j] = sum_i sum_m B_m(x_bi) * coef[i][j][m].  G must be 10.
  * coef, x, y and ws are device pointers (ws 256-byte aligned, at least
- * kan_dense_workspace_bytes(in, out, B), which is never 0; contents need not survive
- * between calls).  Result within 1e-5 relative at every batch size: below batch 112 an
+ * kan_dense_workspace_bytes(in, out, B) bytes, (size_t)-1 for invalid sizes; contents need
+ * not survive between calls).  Result within 1e-5 relative at every batch size: below batch 112 an
  * fp32 FMA kernel, from 112 on the matrix cores on coefficients and basis weights split
  * into high and low fp16 parts (hi*hi + hi*lo + lo*hi), as the precise VQ path does.  */
 size_t kan_dense_workspace_bytes(int32_t in, int32_t out, int64_t B);
@@ -237,6 +237,7 @@ kan_status kan_prof_end(kan_prof_record* out, int32_t cap, int32_t* n_out);
 const char* kan_status_string(int32_t status);
 /* Name of the kernel family the dispatcher would pick (for reports). */
 const char* kan_vq_planned_kernel(const kan_vq_layer* L, int64_t B, int32_t n_heads, int32_t path);
+const char* kan_dense_planned_kernel(int32_t in, int32_t out, int64_t B);
 
 #ifdef __cplusplus
 }

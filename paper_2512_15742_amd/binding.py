@@ -25,7 +25,7 @@ EXPORTS = [
     "kan_bspline_basis", "kan_vq_workspace_bytes", "kan_vq_layer_forward",
     "kan_dense_workspace_bytes", "kan_dense_layer_forward", "kan_vq_head_forward",
     "kan_vq_debug_gather", "kan_vq_count_bad_indices", "kan_prof_begin", "kan_prof_end",
-    "kan_status_string", "kan_vq_planned_kernel", "kan_vq_prepared_bytes", "kan_vq_prepare", "kan_pli_basis",
+    "kan_status_string", "kan_vq_planned_kernel", "kan_dense_planned_kernel", "kan_vq_prepared_bytes", "kan_vq_prepare", "kan_pli_basis",
     "kan_vq_assign_workspace_bytes", "kan_vq_assign", "kan_vq_reconstruction_workspace_bytes",
     "kan_vq_reconstruction_sums",
 ]
@@ -89,6 +89,8 @@ def lib():
         L.kan_status_string.restype = C.c_char_p
         L.kan_vq_planned_kernel.argtypes = [LP, I64, I32, I32]
         L.kan_vq_planned_kernel.restype = C.c_char_p
+        L.kan_dense_planned_kernel.argtypes = [I32, I32, I64]
+        L.kan_dense_planned_kernel.restype = C.c_char_p
         L.kan_vq_prepared_bytes.argtypes = [LP]
         L.kan_vq_prepared_bytes.restype = SZ
         L.kan_vq_prepare.argtypes = [LP, P, SZ, P]
@@ -351,6 +353,10 @@ def kan_vq_reconstruction_r2(coef, codebook, idx, gain, bias) -> float:
 
 def kan_vq_planned_kernel(layer: VQLayer, B, n_heads=1, path=KAN_PATH_AUTO) -> str:
     return lib().kan_vq_planned_kernel(C.byref(layer.desc), int(B), int(n_heads), int(path)).decode()
+
+
+def kan_dense_planned_kernel(n_in, n_out, B) -> str:
+    return lib().kan_dense_planned_kernel(int(n_in), int(n_out), int(B)).decode()
 
 
 def kan_prof_begin(max_launches=4096):

@@ -833,6 +833,11 @@ const char* kan_vq_planned_kernel(const kan_vq_layer* L, int64_t B, int32_t n_he
       .name;
 }
 
+const char* kan_dense_planned_kernel(int32_t in, int32_t out, int64_t B) {
+  if (in < 1 || out < 1 || in > kMaxDim || out > kMaxDim || B < 1 || B > kMaxBatch) return "invalid";
+  return plan_dense(in, out, B).name;
+}
+
 kan_status kan_prof_begin(int32_t max_launches) {
   if (max_launches < 1 || max_launches > (1 << 20)) return KAN_ERR_SHAPE;
   if (g_prof.on) return KAN_ERR_UNSUPPORTED;

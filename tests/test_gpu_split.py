@@ -160,3 +160,9 @@ def test_dense_baseline_split_config2_twin(kb):
     y_ref = ko.dense_layer_forward(coef, x)
     assert ko.error_report(yd, y_ref)["headline"] <= TOL_FP32
     assert np.abs(yd - y).max() <= 2 * TOL_FP32 * np.abs(y_ref).max()
+
+
+def test_dense_planned_kernel(kb):
+    assert kb.kan_dense_planned_kernel(2048, 512, 111) == "kan_dense"
+    assert kb.kan_dense_planned_kernel(2048, 512, 112) == "kan_dense_split"
+    assert kb.kan_dense_planned_kernel(0, 512, 112) == "invalid"
