@@ -294,8 +294,9 @@ struct WsLayout {
   size_t hidden = 0;    // one of two ping-pong hidden-activation buffers, [n_heads][B][out]
   size_t partial = 0;   // i-chunk partial sums
   size_t partial2 = 0;  // second buffer of per-bucket sums when consecutive bucket layers are chained
-  size_t cf = 0;        // matrix-core path: fp16 coefficient fragments
-  size_t bp = 0;        // matrix-core path: partial bias sums
+  size_t cf = 0;        // matrix-core path: fp16 coefficient fragments, a region per layer (layers after the
+  size_t bp = 0;        //   first are prepared beside the first one's work) / partial bias sums, likewise
+  std::vector<size_t> cf_off, bp_off;   // start of each layer's region within cf / bp
   size_t u = 0;         // matrix-core path: packed basis weights + span
   int n_layers = 1;
   size_t total() const { return (n_layers > 1 ? 2 * hidden : 0) + partial + partial2 + cf + bp + u; }
@@ -338,7 +339,48 @@ struct Chain {
   int in_tanh = 0;
   bool out = false;              // leave the per-bucket sums for the next layer (no reduction pass)
   float* partial = nullptr;      // where this layer's partial sums go (default: w.partial)
+  // matrix-core path: stages the head's first launch has already covered
+  bool coef_done = false;
+  bool basis_done = false;
 };
+
+// Matrix-core path, stage 1: coefficient records (and bias sums) of one layer of a group of heads.
+// Depends on the layer's parameters only, not on x.
+kan_status run_prep_coef(const LayerPlan& p, const GatherArgs& a, int heads, const WsPtrs& w, PrepCoefArgs* out,
+                         bool launch, hipStream_t s) {
+  PrepCoefArgs& pc = *out;
+  memset(&pc, 0, sizeof(pc));
+  pc.cf = w.cf;
+  pc.cf_head_stride = (long long)mfma_cf_records(a.n_in, a.n_out);
+  pc.cf_lo = p.products == 3 ? w.cf + (long long)heads * pc.cf_head_stride : nullptr;
+  pc.bias_partial = w.bp;
+  pc.bp_head_stride = (long long)mfma_bp_floats(a.n_in, a.n_out);
+  pc.n_in = a.n_in;
+  pc.n_out = a.n_out;
+  memcpy(pc.h, a.h, sizeof(pc.h));
+  if (!launch) return KAN_OK;
+  if (p.cfg.code == kDense)
+    return run("kan_prep_dense", s, [&] { return launch_prep_dense((const float*)a.h[0].cb, pc.cf, pc.cf_lo, a.n_in, a.n_out, s); });
+  return run("kan_prep_coef", s, [&] { return launch_prep_coef(p.cfg, pc, heads, s); });
+}
+
+// Stage 2: packed basis weights and spans of the layer's input (x, or the previous layer's
+// partial sums added and squashed).
+struct BasisBufs {
+  uint2* u_lo;
+  long long u_stride;
+};
+kan_status run_prep_basis(const LayerPlan& p, const GatherArgs& a, int heads, bool x_shared, const WsPtrs& w,
+                          const Chain& chain, BasisBufs* out, bool launch, hipStream_t s) {
+  const long long u_elems = (long long)((a.n_in + 15) / 16 * 16) * a.B;
+  out->u_stride = x_shared ? 0 : u_elems;
+  out->u_lo = p.products == 3 ? w.u + (x_shared ? 1 : heads) * u_elems : nullptr;
+  if (!launch) return KAN_OK;
+  return run("kan_prep_basis", s, [&] {
+    return launch_prep_basis(a.x, a.x_head_stride, chain.in_parts, chain.in_part_stride, chain.in_tanh, w.u, out->u_lo,
+                             out->u_stride, a.n_in, a.B, x_shared ? 1 : heads, a.rule, s);
+  });
+}
 
 kan_status run_layer_group(const LayerPlan& p, GatherArgs& a, const void* const* prepared, int heads,
                            bool x_shared, float* final_dst, long long final_head_stride, const WsPtrs& w,
@@ -353,29 +395,14 @@ kan_status run_layer_group(const LayerPlan& p, GatherArgs& a, const void* const*
   kan_status st;
   if (p.mfma) {
     PrepCoefArgs pc;
-    memset(&pc, 0, sizeof(pc));
     const bool split3 = p.products == 3;
-    pc.cf = w.cf;
-    pc.cf_head_stride = (long long)mfma_cf_records(a.n_in, a.n_out);
-    pc.cf_lo = split3 ? w.cf + (long long)heads * pc.cf_head_stride : nullptr;
-    pc.bias_partial = w.bp;
-    pc.bp_head_stride = (long long)mfma_bp_floats(a.n_in, a.n_out);
-    pc.n_in = a.n_in;
-    pc.n_out = a.n_out;
-    memcpy(pc.h, a.h, sizeof(pc.h));
-    if (p.cfg.code == kDense)
-      st = run("kan_prep_dense", s, [&] { return launch_prep_dense((const float*)a.h[0].cb, pc.cf, pc.cf_lo, a.n_in, a.n_out, s); });
-    else
-      st = run("kan_prep_coef", s, [&] { return launch_prep_coef(p.cfg, pc, heads, s); });
+    st = run_prep_coef(p, a, heads, w, &pc, !chain.coef_done, s);
     if (st != KAN_OK) return st;
-    const long long u_elems = (long long)((a.n_in + 15) / 16 * 16) * a.B;
-    const long long u_stride = x_shared ? 0 : u_elems;
-    uint2* const u_lo = split3 ? w.u + (x_shared ? 1 : heads) * u_elems : nullptr;
-    st = run("kan_prep_basis", s, [&] {
-      return launch_prep_basis(a.x, a.x_head_stride, chain.in_parts, chain.in_part_stride, chain.in_tanh, w.u, u_lo,
-                               u_stride, a.n_in, a.B, x_shared ? 1 : heads, a.rule, s);
-    });
+    BasisBufs bb;
+    st = run_prep_basis(p, a, heads, x_shared, w, chain, &bb, !chain.basis_done, s);
     if (st != KAN_OK) return st;
+    uint2* const u_lo = bb.u_lo;
+    const long long u_stride = bb.u_stride;
     MfmaArgs m;
     memset(&m, 0, sizeof(m));
     m.cf = w.cf;
@@ -531,9 +558,11 @@ kan_status plan_head(const kan_vq_layer* layers, int32_t n_layers, int32_t n_hea
     plans->push_back(p);
     auto grow = [](size_t& dst, size_t v) { if (v > dst) dst = v; };
     grow(ws->partial, partial_bytes(p, R.out, B, group));
+    ws->cf_off.push_back(ws->cf);
+    ws->bp_off.push_back(ws->bp);
     if (p.mfma) {
-      grow(ws->cf, round_up((size_t)(p.products == 3 ? 2 : 1) * group * mfma_cf_records(R.in, R.out) * sizeof(uint4), 256));
-      grow(ws->bp, round_up((size_t)group * mfma_bp_floats(R.in, R.out) * sizeof(float), 256));
+      ws->cf += round_up((size_t)(p.products == 3 ? 2 : 1) * group * mfma_cf_records(R.in, R.out) * sizeof(uint4), 256);
+      ws->bp += round_up((size_t)group * mfma_bp_floats(R.in, R.out) * sizeof(float), 256);
     }
     if (p.mfma)
       grow(ws->u, round_up((size_t)(p.products == 3 ? 2 : 1) * (size_t)(l == 0 ? 1 : group) * (size_t)((R.in + 15) / 16 * 16) * (size_t)B * sizeof(uint2), 256));
@@ -613,13 +642,90 @@ kan_status kan_vq_head_forward(const kan_vq_layer* layers, int32_t n_layers, int
   w.partial = (float*)(wsp + hid2);
   w.partial2 = (float*)(wsp + hid2 + wl.partial);
   const size_t after_partial = hid2 + wl.partial + wl.partial2;
-  w.cf = (uint4*)(wsp + after_partial);
-  w.bp = (float*)(wsp + after_partial + wl.cf);
+  uint4* const cf_base = (uint4*)(wsp + after_partial);
+  float* const bp_base = (float*)(wsp + after_partial + wl.cf);
+  w.cf = cf_base;
+  w.bp = bp_base;
   w.u = (uint2*)(wsp + after_partial + wl.cf + wl.bp);
+
+  auto layer_args = [&](int l, int h0, int heads, const float* src, long long src_head_stride, GatherArgs* out,
+                        const void** prepared) {
+    const kan_vq_layer& R = layers[l];
+    GatherArgs& a = *out;
+    memset(&a, 0, sizeof(a));
+    a.x = src + (long long)h0 * src_head_stride;
+    a.x_head_stride = src_head_stride;
+    a.n_in = R.in;
+    a.n_out = R.out;
+    a.B = (int)B;
+    a.rows_per_chunk = plans[l].rows_per_chunk;
+    a.n_jt = plans[l].n_jt;
+    a.cb_bytes = (long long)R.K * cb_row_bytes(code_of(R));
+    a.rule = R.rule;
+    for (int h = 0; h < heads; ++h) {
+      const kan_vq_layer& L = layers[(size_t)(h0 + h) * n_layers + l];
+      a.h[h].idx = L.idx;
+      a.h[h].gain = L.gain;
+      a.h[h].bias = L.bias;
+      a.h[h].cb = L.codebook;
+      a.h[h].scale = L.scale;
+      a.h[h].gain_log2_lo = L.gain_log2_lo;
+      a.h[h].gain_log2_step = L.gain_log2_step;
+      a.h[h].bias_scale = L.bias_scale;
+      if (prepared) prepared[h] = L.prepared;
+    }
+  };
+
+  // A single head on the matrix cores: one launch prepares the coefficient records of its
+  // matrix-core layers (those stored like the first one, up to kStartJobs) and the first layer's
+  // basis words; the layers below then skip these stages.
+  std::vector<char> coef_done(n_layers, 0);
+  bool basis0_done = false;
+  if (n_heads == 1 && plans[0].mfma) {
+    PrepStartArgs ps;
+    memset(&ps, 0, sizeof(ps));
+    const LayerPlan& p0 = plans[0];
+    for (int l = 0; l < n_layers && ps.n_jobs < kStartJobs; ++l) {
+      const LayerPlan& p = plans[l];
+      if (!p.mfma || p.products != p0.products || p.cfg.code != p0.cfg.code || p.cfg.gb_kind != p0.cfg.gb_kind ||
+          p.cfg.idx_u32 != p0.cfg.idx_u32)
+        continue;
+      GatherArgs a;
+      layer_args(l, 0, 1, x, 0, &a, nullptr);
+      WsPtrs wl_ptrs = w;
+      wl_ptrs.cf = cf_base + wl.cf_off[l] / sizeof(uint4);
+      wl_ptrs.bp = bp_base + wl.bp_off[l] / sizeof(float);
+      PrepCoefArgs pc;
+      (void)run_prep_coef(p, a, 1, wl_ptrs, &pc, false, s);
+      PrepStartArgs::Job& job = ps.job[ps.n_jobs++];
+      job.cf = pc.cf;
+      job.cf_lo = pc.cf_lo;
+      job.bp = pc.bias_partial;
+      job.n_in = pc.n_in;
+      job.n_out = pc.n_out;
+      job.h = pc.h[0];
+      coef_done[l] = 1;
+    }
+    GatherArgs a0;
+    layer_args(0, 0, 1, x, 0, &a0, nullptr);
+    BasisBufs bb;
+    (void)run_prep_basis(p0, a0, 1, true, w, Chain(), &bb, false, s);
+    ps.x = x;
+    ps.W = w.u;
+    ps.W_lo = bb.u_lo;
+    ps.n_in = a0.n_in;
+    ps.B = a0.B;
+    ps.rule = a0.rule;
+    st = run("kan_prep_start", s, [&] { return launch_prep_start(p0.cfg, ps, p0.products == 3, s); });
+    if (st != KAN_OK) return st;
+    basis0_done = true;
+  }
 
   for (int l = 0; l < n_layers; ++l) {
     const kan_vq_layer& R = layers[l];
     const bool last = (l + 1 == n_layers);
+    w.cf = cf_base + wl.cf_off[l] / sizeof(uint4);
+    w.bp = bp_base + wl.bp_off[l] / sizeof(float);
     const float* src = (l == 0) ? x : w.hid[(l - 1) & 1];
     long long src_head_stride = (l == 0) ? 0 : (long long)B * R.in;
     Chain chain;
@@ -639,28 +745,9 @@ kan_status kan_vq_head_forward(const kan_vq_layer* layers, int32_t n_layers, int
       const int heads = (n_heads - h0) < kMaxGroup ? (n_heads - h0) : kMaxGroup;
       GatherArgs a;
       const void* prepared[kMaxGroup];
-      memset(&a, 0, sizeof(a));
-      a.x = src + (long long)h0 * src_head_stride;
-      a.x_head_stride = src_head_stride;
-      a.n_in = R.in;
-      a.n_out = R.out;
-      a.B = (int)B;
-      a.rows_per_chunk = plans[l].rows_per_chunk;
-      a.n_jt = plans[l].n_jt;
-      a.cb_bytes = (long long)R.K * cb_row_bytes(code_of(R));
-      a.rule = R.rule;
-      for (int h = 0; h < heads; ++h) {
-        const kan_vq_layer& L = layers[(size_t)(h0 + h) * n_layers + l];
-        a.h[h].idx = L.idx;
-        a.h[h].gain = L.gain;
-        a.h[h].bias = L.bias;
-        a.h[h].cb = L.codebook;
-        a.h[h].scale = L.scale;
-        a.h[h].gain_log2_lo = L.gain_log2_lo;
-        a.h[h].gain_log2_step = L.gain_log2_step;
-        a.h[h].bias_scale = L.bias_scale;
-        prepared[h] = L.prepared;
-      }
+      layer_args(l, h0, heads, src, src_head_stride, &a, prepared);
+      chain.coef_done = coef_done[l] != 0;
+      chain.basis_done = l == 0 && basis0_done;
       st = run_layer_group(plans[l], a, prepared, heads, l == 0, dst + (long long)h0 * dst_head_stride, dst_head_stride, w,
                            last ? 0 : 1, s, chain);
       if (st != KAN_OK) return st;

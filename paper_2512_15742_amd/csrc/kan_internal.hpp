@@ -67,6 +67,29 @@ struct PrepCoefArgs {
   LayerPtrs h[kMaxGroup];
 };
 
+// One launch for all a single head's call can prepare before its first contraction: the
+// coefficient records of up to kStartJobs matrix-core layers of the same storage types, and
+// the basis words of the first layer's input.
+constexpr int kStartJobs = 4;
+struct PrepStartArgs {
+  int n_jobs;
+  int first_block[kStartJobs + 1];   // filled by the launcher: job k takes blocks first_block[k] .. first_block[k+1]-1,
+                                     // the basis job those from first_block[n_jobs] on
+  struct Job {
+    uint4* cf;
+    uint4* cf_lo;                    // split form only
+    float* bp;
+    int n_in, n_out;
+    int nx;                          // filled by the launcher: blocks along the outputs
+    LayerPtrs h;
+  } job[kStartJobs];
+  const float* x;                    // [B][n_in] of the first layer
+  uint2* W;
+  uint2* W_lo;                       // split form only
+  int n_in, B, rule;
+  int basis_nx;                      // filled by the launcher
+};
+
 struct MfmaArgs {
   const uint4* cf;
   long long cf_head_stride;
@@ -84,6 +107,7 @@ struct MfmaArgs {
   float scale[kMaxGroup];      // Int8 scale per head (1 for fp32 codebooks)
 };
 
+hipError_t launch_prep_start(const GatherCfg&, PrepStartArgs&, bool split, hipStream_t);
 hipError_t launch_prep_coef(const GatherCfg&, const PrepCoefArgs&, int heads, hipStream_t);
 // Dense fp32 coefficients coef[n_in][n_out][10] into the split form (high and low fp16 records).
 hipError_t launch_prep_dense(const float* coef, uint4* cf, uint4* cf_lo, int n_in, int n_out, hipStream_t);

@@ -90,22 +90,17 @@ __device__ __forceinline__ void split_pairs(const float (&c)[kG], uint32_t (&hi)
 // written as hi = fp16(c) into cf and as lo = fp16((c - hi) * 2048) into cf_lo (hi + lo / 2048
 // carries 22 bits of c; the factor keeps the low parts out of the fp16 subnormals).
 template <typename IdxT, typename GbT, typename CbT, bool SPLIT>
-__global__ __launch_bounds__(kThreads) void kan_prep_coef_kernel(const PrepCoefArgs a) {
-  __shared__ float sb[4][64];
-  const int head = blockIdx.z;
+__device__ __forceinline__ void prep_coef_block(const LayerPtrs& hp, uint4* __restrict__ cf, uint4* __restrict__ cf_lo,
+                                                float* __restrict__ bp, const int n_in, const int n_out, const int bx,
+                                                const int by, float (*sb)[64]) {
   const int lane = threadIdx.x & 63, wave = threadIdx.x >> 6;
-  const int j = blockIdx.x * 64 + lane;
-  const LayerPtrs hp = a.h[head];
+  const int j = bx * 64 + lane;
   const IdxT* idx = (const IdxT*)hp.idx;
   const GbT* gain = (const GbT*)hp.gain;
   const GbT* bias = (const GbT*)hp.bias;
   const Q8Params qp = {hp.gain_log2_lo, hp.gain_log2_step, hp.bias_scale};
   const CbT* cb = (const CbT*)hp.cb;
-  uint4* cf = a.cf + (long long)head * a.cf_head_stride;
-  uint4* cf_lo = SPLIT ? a.cf_lo + (long long)head * a.cf_head_stride : nullptr;
-  float* bp = a.bias_partial + (long long)head * a.bp_head_stride;
-  const int n_in = a.n_in, n_out = a.n_out;
-  const int ib = blockIdx.y * kMfmaPrepRows + wave * 8;
+  const int ib = by * kMfmaPrepRows + wave * 8;
   float bs = 0.f;
   if (j < n_out && ib < (n_in + IT - 1) / IT * IT) {      // rows past the end of a ragged last step are written as zeros
     const long long step = ib / IT;
@@ -164,7 +159,17 @@ __global__ __launch_bounds__(kThreads) void kan_prep_coef_kernel(const PrepCoefA
   sb[wave][lane] = bs;
   __syncthreads();
   if (wave == 0 && j < n_out)
-    bp[(long long)blockIdx.y * n_out + j] = (sb[0][lane] + sb[1][lane]) + (sb[2][lane] + sb[3][lane]);
+    bp[(long long)by * n_out + j] = (sb[0][lane] + sb[1][lane]) + (sb[2][lane] + sb[3][lane]);
+}
+
+template <typename IdxT, typename GbT, typename CbT, bool SPLIT>
+__global__ __launch_bounds__(kThreads) void kan_prep_coef_kernel(const PrepCoefArgs a) {
+  __shared__ float sb[4][64];
+  const int head = blockIdx.z;
+  prep_coef_block<IdxT, GbT, CbT, SPLIT>(a.h[head], a.cf + (long long)head * a.cf_head_stride,
+                                         SPLIT ? a.cf_lo + (long long)head * a.cf_head_stride : nullptr,
+                                         a.bias_partial + (long long)head * a.bp_head_stride, a.n_in, a.n_out,
+                                         blockIdx.x, blockIdx.y, sb);
 }
 
 // ---- kan_prep_dense -----------------------------------------------------------------
@@ -220,18 +225,13 @@ __global__ __launch_bounds__(kThreads) void kan_prep_dense_kernel(const float* _
 // multiple of 16 are zeros.
 // The input is x itself, or (x_parts > 1) the previous layer's partial sums, added here in
 // the order of the slices and squashed, so that no separate reduction pass runs in between.
-__global__ __launch_bounds__(256) void kan_prep_basis_kernel(const float* __restrict__ x, long long x_head_stride,
-                                                             int x_parts, long long x_part_stride, int x_tanh,
-                                                             uint2* __restrict__ W, uint2* __restrict__ W_lo,
-                                                             long long w_head_stride, int n_in, int B, int rule) {
-  __shared__ uint2 tile[32][33];
-  __shared__ uint2 tile_lo[32][33];
-  const int head = blockIdx.z;
-  const float* xh = x + (long long)head * x_head_stride;
-  uint2* wh = W + (long long)head * w_head_stride;
-  uint2* wl = W_lo ? W_lo + (long long)head * w_head_stride : nullptr;
+__device__ __forceinline__ void prep_basis_block(const float* __restrict__ xh, const int x_parts,
+                                                 const long long x_part_stride, const int x_tanh,
+                                                 uint2* __restrict__ wh, uint2* __restrict__ wl, const int n_in,
+                                                 const int B, const int rule, const int bx, const int by,
+                                                 uint2 (*tile)[33], uint2 (*tile_lo)[33]) {
   const int tx = threadIdx.x & 31, ty = threadIdx.x >> 5;      // 32 x 8
-  const int ib = blockIdx.x * 32, bb = blockIdx.y * 32;
+  const int ib = bx * 32, bb = by * 32;
 #pragma unroll
   for (int r = 0; r < 4; ++r) {
     const int b = bb + ty + 8 * r, i = ib + tx;
@@ -284,6 +284,43 @@ __global__ __launch_bounds__(256) void kan_prep_basis_kernel(const float* __rest
       wh[((long long)(i >> 1) * B + b) * 2 + (i & 1)] = tile[tx][ty + 8 * r];
       if (wl) wl[((long long)(i >> 1) * B + b) * 2 + (i & 1)] = tile_lo[tx][ty + 8 * r];
     }
+  }
+}
+
+__global__ __launch_bounds__(256) void kan_prep_basis_kernel(const float* __restrict__ x, long long x_head_stride,
+                                                             int x_parts, long long x_part_stride, int x_tanh,
+                                                             uint2* __restrict__ W, uint2* __restrict__ W_lo,
+                                                             long long w_head_stride, int n_in, int B, int rule) {
+  __shared__ uint2 tile[32][33];
+  __shared__ uint2 tile_lo[32][33];
+  const int head = blockIdx.z;
+  prep_basis_block(x + (long long)head * x_head_stride, x_parts, x_part_stride, x_tanh,
+                   W + (long long)head * w_head_stride, W_lo ? W_lo + (long long)head * w_head_stride : nullptr, n_in, B,
+                   rule, blockIdx.x, blockIdx.y, tile, tile_lo);
+}
+
+// ---- kan_prep_start -----------------------------------------------------------------
+// Everything a single head's call can prepare before its first contraction, in one launch:
+// the coefficient records of its matrix-core layers (they depend on the parameters only) and
+// the basis words of the first layer's input.  The small grids of the later layers and the
+// basis pass fill the tail of the first layer's coefficient pass instead of running as
+// launches of their own behind it.  Blocks are numbered job after job, the largest first.
+template <typename IdxT, typename GbT, typename CbT, bool SPLIT>
+__global__ __launch_bounds__(kThreads) void kan_prep_start_kernel(const PrepStartArgs a) {
+  __shared__ float sb[4][64];
+  __shared__ uint2 tile[32][33];
+  __shared__ uint2 tile_lo[SPLIT ? 32 : 1][33];
+  const int blk = blockIdx.x;
+  int k = 0;
+  while (k < a.n_jobs && blk >= a.first_block[k + 1]) ++k;
+  const int rel = blk - a.first_block[k];
+  if (k < a.n_jobs) {
+    const PrepStartArgs::Job& job = a.job[k];
+    prep_coef_block<IdxT, GbT, CbT, SPLIT>(job.h, job.cf, SPLIT ? job.cf_lo : nullptr, job.bp, job.n_in, job.n_out,
+                                           rel % job.nx, rel / job.nx, sb);
+  } else {
+    prep_basis_block(a.x, 1, 0, 0, a.W, SPLIT ? a.W_lo : nullptr, a.n_in, a.B, a.rule, rel % a.basis_nx,
+                     rel / a.basis_nx, tile, SPLIT ? tile_lo : tile);
   }
 }
 
@@ -632,28 +669,43 @@ __global__ __launch_bounds__(kMfmaThreads, MB == 2 ? 3 : 2) void kan_mfma_kernel
   }
 }
 
-template <typename IdxT, bool SPLIT>
-hipError_t prep_types(const GatherCfg& c, const PrepCoefArgs& a, dim3 grid, hipStream_t s) {
+template <typename T>
+struct TypeTag {
+  using type = T;
+};
+
+// Calls launch(gain/bias type, codebook type) for the layer's storage types.
+template <typename F>
+hipError_t prep_types(const GatherCfg& c, F&& launch) {
   if (c.code == kCbI8) {
-    if (c.gb_kind == kGbQ8)
-      hipLaunchKernelGGL((kan_prep_coef_kernel<IdxT, q8_t, int8_t, SPLIT>), grid, dim3(kThreads), 0, s, a);
-    else if (c.gb_kind == kGbF16)
-      hipLaunchKernelGGL((kan_prep_coef_kernel<IdxT, __half, int8_t, SPLIT>), grid, dim3(kThreads), 0, s, a);
-    else
-      hipLaunchKernelGGL((kan_prep_coef_kernel<IdxT, float, int8_t, SPLIT>), grid, dim3(kThreads), 0, s, a);
+    if (c.gb_kind == kGbQ8) launch(TypeTag<q8_t>(), TypeTag<int8_t>());
+    else if (c.gb_kind == kGbF16) launch(TypeTag<__half>(), TypeTag<int8_t>());
+    else launch(TypeTag<float>(), TypeTag<int8_t>());
   } else {
     if (c.gb_kind == kGbQ8) return hipErrorInvalidValue;    // byte-coded gain/bias go with Int8 codebooks
     if (c.code == kCbF16) {
-      if (c.gb_kind == kGbF16)
-        hipLaunchKernelGGL((kan_prep_coef_kernel<IdxT, __half, __half, SPLIT>), grid, dim3(kThreads), 0, s, a);
-      else
-        hipLaunchKernelGGL((kan_prep_coef_kernel<IdxT, float, __half, SPLIT>), grid, dim3(kThreads), 0, s, a);
-    } else if (c.gb_kind == kGbF16)
-      hipLaunchKernelGGL((kan_prep_coef_kernel<IdxT, __half, float, SPLIT>), grid, dim3(kThreads), 0, s, a);
-    else
-      hipLaunchKernelGGL((kan_prep_coef_kernel<IdxT, float, float, SPLIT>), grid, dim3(kThreads), 0, s, a);
+      if (c.gb_kind == kGbF16) launch(TypeTag<__half>(), TypeTag<__half>());
+      else launch(TypeTag<float>(), TypeTag<__half>());
+    } else if (c.gb_kind == kGbF16) launch(TypeTag<__half>(), TypeTag<float>());
+    else launch(TypeTag<float>(), TypeTag<float>());
   }
   return hipGetLastError();
+}
+
+template <typename IdxT, bool SPLIT>
+hipError_t prep_coef_types(const GatherCfg& c, const PrepCoefArgs& a, dim3 grid, hipStream_t s) {
+  return prep_types(c, [&](auto gb, auto cb) {
+    hipLaunchKernelGGL((kan_prep_coef_kernel<IdxT, typename decltype(gb)::type, typename decltype(cb)::type, SPLIT>), grid,
+                       dim3(kThreads), 0, s, a);
+  });
+}
+
+template <typename IdxT, bool SPLIT>
+hipError_t prep_start_types(const GatherCfg& c, const PrepStartArgs& a, dim3 grid, hipStream_t s) {
+  return prep_types(c, [&](auto gb, auto cb) {
+    hipLaunchKernelGGL((kan_prep_start_kernel<IdxT, typename decltype(gb)::type, typename decltype(cb)::type, SPLIT>), grid,
+                       dim3(kThreads), 0, s, a);
+  });
 }
 
 }  // namespace
@@ -661,8 +713,27 @@ hipError_t prep_types(const GatherCfg& c, const PrepCoefArgs& a, dim3 grid, hipS
 hipError_t launch_prep_coef(const GatherCfg& c, const PrepCoefArgs& a, int heads, hipStream_t s) {
   if (c.code == kDense) return hipErrorInvalidValue;
   dim3 grid((a.n_out + 63) / 64, (a.n_in + kMfmaPrepRows - 1) / kMfmaPrepRows, heads);
-  if (a.cf_lo) return c.idx_u32 ? prep_types<uint32_t, true>(c, a, grid, s) : prep_types<uint16_t, true>(c, a, grid, s);
-  return c.idx_u32 ? prep_types<uint32_t, false>(c, a, grid, s) : prep_types<uint16_t, false>(c, a, grid, s);
+  if (a.cf_lo) return c.idx_u32 ? prep_coef_types<uint32_t, true>(c, a, grid, s) : prep_coef_types<uint16_t, true>(c, a, grid, s);
+  return c.idx_u32 ? prep_coef_types<uint32_t, false>(c, a, grid, s) : prep_coef_types<uint16_t, false>(c, a, grid, s);
+}
+
+hipError_t launch_prep_start(const GatherCfg& c, PrepStartArgs& a, bool split, hipStream_t s) {
+  if (c.code == kDense || a.n_jobs < 1 || a.n_jobs > kStartJobs || !a.x || !a.W || (split && !a.W_lo)) return hipErrorInvalidValue;
+  long long blocks = 0;
+  for (int k = 0; k < a.n_jobs; ++k) {
+    PrepStartArgs::Job& job = a.job[k];
+    if (!job.cf || !job.bp || (split && !job.cf_lo)) return hipErrorInvalidValue;
+    job.nx = (job.n_out + 63) / 64;
+    a.first_block[k] = (int)blocks;
+    blocks += (long long)job.nx * ((job.n_in + kMfmaPrepRows - 1) / kMfmaPrepRows);
+  }
+  a.first_block[a.n_jobs] = (int)blocks;
+  a.basis_nx = (a.n_in + 31) / 32;
+  blocks += (long long)a.basis_nx * ((a.B + 31) / 32);
+  if (blocks > 0x7fffffffLL) return hipErrorInvalidValue;
+  dim3 grid((unsigned)blocks, 1, 1);
+  if (split) return c.idx_u32 ? prep_start_types<uint32_t, true>(c, a, grid, s) : prep_start_types<uint16_t, true>(c, a, grid, s);
+  return c.idx_u32 ? prep_start_types<uint32_t, false>(c, a, grid, s) : prep_start_types<uint16_t, false>(c, a, grid, s);
 }
 
 hipError_t launch_prep_dense(const float* coef, uint4* cf, uint4* cf_lo, int n_in, int n_out, hipStream_t s) {
