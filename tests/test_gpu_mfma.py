@@ -155,3 +155,30 @@ def test_mfma_three_layer_head_hand_over(kb, B, n_heads):
         y_ref = ko.vq_head_forward(x, [p.as_dict() for p in heads_p[h]])
         rep = ko.error_report(y[h], y_ref)
         assert rep["headline"] <= TOL_MFMA, (h, rep)
+
+
+@pytest.mark.parametrize("path_name", ["mfma", "gather"])
+def test_single_head_start_launch_mixed_types_and_many_layers(kb, path_name):
+    """A single head's call prepares the coefficient records of its layers in one launch, but only
+    those stored like the first layer and only the first four: a six-layer head whose third and
+    fifth layers use other storage types takes both ways in one call (fp16 path, and the split
+    precise path from batch 112)."""
+    path = kb.KAN_PATH_MFMA if path_name == "mfma" else kb.KAN_PATH_GATHER
+    tol = TOL_MFMA if path_name == "mfma" else 1e-5
+    dims = [(70, 96), (96, 130), (130, 64), (64, 80), (80, 33), (33, 21)]
+    kinds = [("i8", "f16", "u16"), ("i8", "f16", "u16"), ("f32", "f32", "u32"), ("i8", "f16", "u16"),
+             ("f16", "f16", "u16"), ("i8", "f16", "u16")]
+    Ps = [synth.make_layer(31 + l, i, o, 70000 if idx == "u32" else 1000, cb_dtype=cb, gb_dtype=gb, idx_dtype=idx)
+          for l, ((i, o), (cb, gb, idx)) in enumerate(zip(dims, kinds))]
+    B = 150
+    x = synth.make_x(77, B, dims[0][0])
+    Ls = gpu_layers(Ps)
+    y = kb.kan_vq_head_forward([Ls], to_dev(x), path=path)[0].cpu().numpy()
+    y_ref = ko.vq_head_forward(x, [p.as_dict() for p in Ps])
+    rep = ko.error_report(y, y_ref)
+    assert np.isfinite(y).all() and rep["headline"] <= tol * (1 if path_name == "mfma" else 6), rep
+    # the same head through the grouped launches (two identical heads; the planner may cut the
+    # inputs into other chunks there, so the sums agree to rounding only)
+    y2 = kb.kan_vq_head_forward([Ls, Ls], to_dev(x), path=path).cpu().numpy()
+    assert np.array_equal(y2[0], y2[1])
+    assert ko.error_report(y2[0], y_ref)["headline"] <= tol * (1 if path_name == "mfma" else 6)
