@@ -39,11 +39,22 @@ MALL_BYTES = 256 << 20
 # (FETCH_SIZE / WRITE_SIZE runs scaled by a copy kernel of known size); see the
 # summaries under profiles/.  None until such a run exists for the workload.
 MEASURED_TRAFFIC = {
-    # average over the layer-1 and layer-2 launches of one step, bytes per launch
-    ("kan_mfma", 1024): int((60.70 + 32.00 + 18.24 + 16.00) / 2 * 2**20),
-    ("kan_gather_bt1", 1): int((17.20 + 0.50 + 6.61 + 0.06) / 2 * 2**20),
-    ("kan_bucket", 1): int((7.74 + 0.02) * 2**20),
+    # bytes per launch (fetched + written) of the layer-1 launch, the dominant one of a step
+    ("kan_mfma@L1", 1024): int((60.70 + 32.00) * 2**20),
+    ("kan_gather_bt1@L1", 1): int((17.20 + 0.50) * 2**20),
+    ("kan_bucket@L1", 1): int((12.93 + 0.03) * 2**20),
 }
+
+
+def layer_of(kernel_key):
+    """Timed launches inside a head call are keyed "family@L<layer>" (1-based)."""
+    return int(kernel_key.split("@L")[1]) - 1 if "@L" in kernel_key else None
+
+
+def per_launch(values, kernel_key, launches_per_step):
+    """Share of a per-layer quantity (edges, metadata bytes) that one launch of this kernel covers."""
+    l = layer_of(kernel_key)
+    return (values[l] if l is not None else sum(values)) / launches_per_step
 
 
 def parse():
@@ -314,22 +325,23 @@ def main():
     B = args.batch
     r = results[B]
     dom = r["dominant"]
-    # Layer 1 and layer 2 launch the same kernel family; its average launch moves
-    # (edges_l1 + edges_l2) / 2 edges, which is what `achieved` is priced on.
+    # The dominant kernel is one layer's launch (layer 1 here): `achieved` is priced on that
+    # layer's edges and on that launch's event-timed duration.
     launches_per_step = r["kernels_launches_per_step"][dom]
     avg_s = r["kernels_avg_us"][dom] * 1e-6
-    edges_per_launch = sum(edges) / launches_per_step
-    is_mfma = dom.startswith(("kan_mfma", "kan_fused"))
+    edges_per_launch = per_launch(edges, dom, launches_per_step)
+    family = dom.split("@")[0]
+    is_mfma = family.startswith(("kan_mfma", "kan_fused"))
     if B >= 16:
         # compute-bound regime (the metadata stream stops being the limit near B = 12-20)
         flops = edges_per_launch * (B * FLOP_PER_EDGE_EVAL + FLOP_PER_EDGE_RECON)
         # fp16 operands price against the fp16/bf16 matrix-core peak, fp32 operands against the fp32 one
-        peak = PEAK_BF16_MFMA_TFLOPS if (is_mfma and dom != "kan_fused_f32") else PEAK_FP32_VECTOR_TFLOPS
+        peak = PEAK_BF16_MFMA_TFLOPS if (is_mfma and family != "kan_fused_f32") else PEAK_FP32_VECTOR_TFLOPS
         roof = {"bound": "mfma" if is_mfma else "alu", "achieved": flops / avg_s / 1e12, "peak": peak,
                 "unit": "TFLOP/s", "kernel": dom, "avg_launch_us": r["kernels_avg_us"][dom],
                 "traffic": MEASURED_TRAFFIC.get((dom, B))}
     else:
-        nbytes = sum(meta) / launches_per_step
+        nbytes = per_launch(meta, dom, launches_per_step)
         roof = {"bound": "hbm", "achieved": nbytes / avg_s / 1e9, "peak": PEAK_HBM_GBPS, "unit": "GB/s",
                 "kernel": dom, "avg_launch_us": r["kernels_avg_us"][dom],
                 "traffic": MEASURED_TRAFFIC.get((dom, B))}
@@ -338,7 +350,7 @@ def main():
     r1 = results[1]
     dom1 = r1["dominant"]
     l1 = r1["kernels_launches_per_step"][dom1]
-    roof1 = {"bound": "hbm", "achieved": (sum(meta) / l1) / (r1["kernels_avg_us"][dom1] * 1e-6) / 1e9,
+    roof1 = {"bound": "hbm", "achieved": per_launch(meta, dom1, l1) / (r1["kernels_avg_us"][dom1] * 1e-6) / 1e9,
              "peak": PEAK_HBM_GBPS, "unit": "GB/s", "kernel": dom1, "avg_launch_us": r1["kernels_avg_us"][dom1],
              "traffic": MEASURED_TRAFFIC.get((dom1, 1))}
     roof1["frac"] = roof1["achieved"] / roof1["peak"]

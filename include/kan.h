@@ -224,6 +224,7 @@ kan_status kan_vq_reconstruction_sums(const float* coef, int32_t in, int32_t out
  * kan_prof_begin creates up to max_launches event pairs (this is the one place
  * the library creates HIP objects) and brackets every kernel it launches from
  * then on.  kan_prof_end synchronises those events, aggregates by kernel name
+ * (launches that belong to layer l = 1, 2, ... of a head call as "name@Ll")
  * into out[0..cap) (host), stores the number of distinct kernels in *n_out,
  * destroys the events and stops recording.  Not thread-safe.                     */
 typedef struct kan_prof_record {

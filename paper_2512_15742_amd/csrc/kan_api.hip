@@ -6,6 +6,7 @@
 #include "../../include/kan.h"
 
 #include <hip/hip_runtime.h>
+#include <stdio.h>
 #include <string.h>
 
 #include <vector>
@@ -21,6 +22,8 @@ struct Prof {
   int cap = 0, n = 0;
   std::vector<hipEvent_t> ev;
   std::vector<const char*> names;
+  std::vector<int> layer;     // 1-based layer of a head call the launch belongs to, 0: none
+  int cur_layer = 0;
 } g_prof;
 
 template <typename F>
@@ -29,6 +32,7 @@ kan_status run(const char* name, hipStream_t s, F&& f) {
   if (g_prof.on && g_prof.n < g_prof.cap) {
     const int n = g_prof.n++;
     g_prof.names[n] = name;
+    g_prof.layer[n] = g_prof.cur_layer;
     (void)hipEventRecord(g_prof.ev[2 * n], s);
     err = f();
     (void)hipEventRecord(g_prof.ev[2 * n + 1], s);
@@ -721,7 +725,11 @@ kan_status kan_vq_head_forward(const kan_vq_layer* layers, int32_t n_layers, int
     basis0_done = true;
   }
 
+  struct LayerScope {      // launches of the loop below are timed per layer
+    ~LayerScope() { g_prof.cur_layer = 0; }
+  } layer_scope;
   for (int l = 0; l < n_layers; ++l) {
+    g_prof.cur_layer = l + 1;
     const kan_vq_layer& R = layers[l];
     const bool last = (l + 1 == n_layers);
     w.cf = cf_base + wl.cf_off[l] / sizeof(uint4);
@@ -930,6 +938,7 @@ kan_status kan_prof_begin(int32_t max_launches) {
   if (g_prof.on) return KAN_ERR_UNSUPPORTED;
   g_prof.ev.assign(2 * (size_t)max_launches, nullptr);
   g_prof.names.assign(max_launches, nullptr);
+  g_prof.layer.assign(max_launches, 0);
   for (auto& e : g_prof.ev)
     if (hipEventCreate(&e) != hipSuccess) return KAN_ERR_LAUNCH;
   g_prof.cap = max_launches;
@@ -950,13 +959,16 @@ kan_status kan_prof_end(kan_prof_record* out, int32_t cap, int32_t* n_out) {
       st = KAN_ERR_LAUNCH;
       break;
     }
+    char key[sizeof(out[0].name)];
+    if (g_prof.layer[n] > 0) snprintf(key, sizeof(key), "%s@L%d", g_prof.names[n], g_prof.layer[n]);
+    else snprintf(key, sizeof(key), "%s", g_prof.names[n]);
     int r = 0;
     for (; r < n_rec; ++r)
-      if (strcmp(out[r].name, g_prof.names[n]) == 0) break;
+      if (strcmp(out[r].name, key) == 0) break;
     if (r == n_rec) {
       if (!out || n_rec >= cap) continue;
       memset(&out[r], 0, sizeof(out[r]));
-      strncpy(out[r].name, g_prof.names[n], sizeof(out[r].name) - 1);
+      memcpy(out[r].name, key, sizeof(key));
       ++n_rec;
     }
     out[r].launches += 1;
@@ -966,6 +978,8 @@ kan_status kan_prof_end(kan_prof_record* out, int32_t cap, int32_t* n_out) {
     if (e) (void)hipEventDestroy(e);
   g_prof.ev.clear();
   g_prof.names.clear();
+  g_prof.layer.clear();
+  g_prof.cur_layer = 0;
   if (n_out) *n_out = n_rec;
   return st;
 }

@@ -182,3 +182,23 @@ def test_single_head_start_launch_mixed_types_and_many_layers(kb, path_name):
     y2 = kb.kan_vq_head_forward([Ls, Ls], to_dev(x), path=path).cpu().numpy()
     assert np.array_equal(y2[0], y2[1])
     assert ko.error_report(y2[0], y_ref)["headline"] <= tol * (1 if path_name == "mfma" else 6)
+
+
+def test_profiled_launches_are_keyed_by_layer(kb):
+    """The library's event timing names the launches of a head call by layer; a single head on
+    the matrix cores starts with the merged preparation launch."""
+    Ps, x = synth.config3(256)
+    Ls = gpu_layers(Ps)
+    xd = to_dev(x)
+    kb.kan_vq_head_forward([Ls], xd, path=kb.KAN_PATH_MFMA)
+    torch.cuda.synchronize()
+    kb.kan_prof_begin(64)
+    for _ in range(3):
+        kb.kan_vq_head_forward([Ls], xd, path=kb.KAN_PATH_MFMA)
+    rec = kb.kan_prof_end()
+    assert set(rec) == {"kan_prep_start", "kan_mfma@L1", "kan_prep_basis@L2", "kan_mfma@L2", "kan_reduce@L2"}, rec
+    assert all(v["launches"] == 3 and v["total_ms"] > 0 for v in rec.values()), rec
+    # outside a head call nothing carries a layer
+    kb.kan_prof_begin(8)
+    kb.kan_bspline_basis(xd[0])
+    assert set(kb.kan_prof_end()) == {"kan_basis"}
