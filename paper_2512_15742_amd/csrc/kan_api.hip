@@ -720,9 +720,13 @@ kan_status kan_vq_head_forward(const kan_vq_layer* layers, int32_t n_layers, int
     ps.n_in = a0.n_in;
     ps.B = a0.B;
     ps.rule = a0.rule;
-    st = run("kan_prep_start", s, [&] { return launch_prep_start(p0.cfg, ps, p0.products == 3, s); });
-    if (st != KAN_OK) return st;
-    basis0_done = true;
+    if (prep_start_blocks(ps) <= kPrepStartMaxBlocks) {
+      st = run("kan_prep_start", s, [&] { return launch_prep_start(p0.cfg, ps, p0.products == 3, s); });
+      if (st != KAN_OK) return st;
+      basis0_done = true;
+    } else {                                   // too many workgroups for one grid: the layers launch their own
+      coef_done.assign(n_layers, 0);
+    }
   }
 
   struct LayerScope {      // launches of the loop below are timed per layer

@@ -107,6 +107,14 @@ struct MfmaArgs {
   float scale[kMaxGroup];      // Int8 scale per head (1 for fp32 codebooks)
 };
 
+// Workgroups of that launch (its grid is one-dimensional: at most 2^24 - 1 workgroups of 256 threads).
+inline long long prep_start_blocks(const PrepStartArgs& a) {
+  long long blocks = (long long)((a.n_in + 31) / 32) * ((a.B + 31) / 32);
+  for (int k = 0; k < a.n_jobs; ++k)
+    blocks += (long long)((a.job[k].n_out + 63) / 64) * ((a.job[k].n_in + kMfmaPrepRows - 1) / kMfmaPrepRows);
+  return blocks;
+}
+constexpr long long kPrepStartMaxBlocks = (1ll << 24) - 1;
 hipError_t launch_prep_start(const GatherCfg&, PrepStartArgs&, bool split, hipStream_t);
 hipError_t launch_prep_coef(const GatherCfg&, const PrepCoefArgs&, int heads, hipStream_t);
 // Dense fp32 coefficients coef[n_in][n_out][10] into the split form (high and low fp16 records).

@@ -730,7 +730,7 @@ hipError_t launch_prep_start(const GatherCfg& c, PrepStartArgs& a, bool split, h
   a.first_block[a.n_jobs] = (int)blocks;
   a.basis_nx = (a.n_in + 31) / 32;
   blocks += (long long)a.basis_nx * ((a.B + 31) / 32);
-  if (blocks > 0x7fffffffLL) return hipErrorInvalidValue;
+  if (blocks != prep_start_blocks(a) || blocks > kPrepStartMaxBlocks) return hipErrorInvalidValue;
   dim3 grid((unsigned)blocks, 1, 1);
   if (split) return c.idx_u32 ? prep_start_types<uint32_t, true>(c, a, grid, s) : prep_start_types<uint16_t, true>(c, a, grid, s);
   return c.idx_u32 ? prep_start_types<uint32_t, false>(c, a, grid, s) : prep_start_types<uint16_t, false>(c, a, grid, s);
