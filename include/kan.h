@@ -60,7 +60,7 @@ typedef enum kan_dtype {
  *   KAN_PATH_GATHER  the precise path: fp32 operands, fp32 accumulation; matches the
  *                    float64 definition to ~1e-6 (bound 1e-5).  Batch 1: one 4-byte
  *                    codeword-window gather per edge on the vector ALUs; from batch 2:
- *                    fused gather + fp32 matrix-core kernel; from batch 112: the kernels
+ *                    fused gather + fp32 matrix-core kernel; from batch 65: the kernels
  *                    of the fp16 path run on coefficients and basis weights split into
  *                    high and low fp16 parts (three products, fp32-grade sums).  Prepared
  *                    layers (see kan_vq_prepare), batch <= 4: codebook buckets in LDS.
@@ -138,8 +138,8 @@ kan_status kan_vq_layer_forward(const kan_vq_layer* L, const float* x, int64_t B
  * section 4.2): y[b][j] = sum_i sum_m B_m(x_bi) * coef[i][j][m].  G must be 10.
  * coef, x, y and ws are device pointers (ws 256-byte aligned, at least
  * kan_dense_workspace_bytes(in, out, B) bytes, (size_t)-1 for invalid sizes; contents need
- * not survive between calls).  Result within 1e-5 relative at every batch size: below batch 112 an
- * fp32 FMA kernel, from 112 on the matrix cores on coefficients and basis weights split
+ * not survive between calls).  Result within 1e-5 relative at every batch size: up to batch 16 an
+ * fp32 FMA kernel, from 17 on the matrix cores on coefficients and basis weights split
  * into high and low fp16 parts (hi*hi + hi*lo + lo*hi), as the precise VQ path does.  */
 size_t kan_dense_workspace_bytes(int32_t in, int32_t out, int64_t B);
 kan_status kan_dense_layer_forward(const float* coef, int32_t in, int32_t out, int32_t G,

@@ -87,7 +87,7 @@ struct LayerPlan {
   int n_jt, n_bt, n_chunks, rows_per_chunk;
   int kind;          // PlanKind
   bool mfma;         // kind == kPlanMfma (coefficient + basis preparation, streaming contraction)
-  int products = 1;  // 3: both operands in high and low fp16 parts, hi*hi + hi*lo + lo*hi (n_chunks counts all slices)
+  int products = 1;  // 3: both operands in high and low fp16 parts, hi*hi + hi*lo + lo*hi (three passes inside the kernel)
   const char* name;
 };
 
@@ -155,7 +155,13 @@ constexpr int kMfmaTargetWorkgroups = 512;
 constexpr int kMfmaMinRows = 64;
 constexpr int64_t kHalfFusedMaxBatch = 64;   // fp16 path: fused kernel up to here, streaming contraction above
 constexpr int64_t kHalfFusedMaxSamples = 1024;   // ... and only below this many (sample, head) pairs per group
-constexpr int64_t kSplitMinBatch = 112;    // precise path: from here the split-operand matrix-core form (measured crossover 96-128)
+// Precise path: from this batch on the split-operand matrix-core form.  Its time hardly depends on
+// the batch below 128 (config 3: 96 us, config 2: 44 us) while the fused fp32 kernel's doubles with
+// its second tile of 64 samples (config 3: 97 us at 64, 113 at 80; config 2: 33 and 57).
+constexpr int64_t kSplitMinBatch = 65;
+// The dense baseline's switch from its fp32 FMA kernel (config 2's twin: 35 us at batch 16, 54 at 24;
+// the split form 35-37 us anywhere below batch 64).
+constexpr int64_t kDenseSplitMinBatch = 17;
 constexpr int64_t kAutoMfmaBatch = 32;    // KAN_PATH_AUTO switches to the matrix cores from here (measured crossover 16-32)
 
 LayerPlan plan_mfma(int n_in, int n_out, int64_t B, int n_heads, int idx_u32, int gb_kind, int code, bool split3 = false) {
@@ -188,7 +194,6 @@ LayerPlan plan_mfma(int n_in, int n_out, int64_t B, int n_heads, int idx_u32, in
   p.n_chunks = (n_in + rows - 1) / rows;
   if (split3) {
     p.products = 3;
-    p.n_chunks *= 3;
     p.name = "kan_mfma_split";
   }
   return p;
@@ -428,23 +433,16 @@ kan_status run_layer_group(const LayerPlan& p, GatherArgs& a, const void* const*
     m.apply_tanh = tanh_in_kernel;
     m.bias_on = p.cfg.code == kDense ? 0 : 1;            // the dense form has no bias
     for (int h = 0; h < heads; ++h) m.scale[h] = p.cfg.code == kCbI8 ? a.h[h].scale : 1.0f;
-    const int chunks = p.n_chunks / p.products;          // chunks of inputs per product
-    dim3 grid((unsigned)(p.n_jt * p.n_bt), (unsigned)chunks, (unsigned)heads);
-    st = run(p.name, s, [&] { return launch_mfma(m, p.cfg.bt, kMfmaTileN, grid, s); });
-    if (split3 && st == KAN_OK) {
-      // the two cross products (their low operands carry a factor 2048) into the slices behind
-      m.bias_on = 0;
-      for (int h = 0; h < heads; ++h) m.scale[h] *= 1.0f / 2048.0f;
-      m.cf = pc.cf_lo;                                    // high weights x low coefficients
-      m.dst = dst + (long long)chunks * count;
-      st = run(p.name, s, [&] { return launch_mfma(m, p.cfg.bt, kMfmaTileN, grid, s); });
-      if (st == KAN_OK) {
-        m.cf = w.cf;                                      // low weights x high coefficients
-        m.W = u_lo;
-        m.dst = dst + 2ll * chunks * count;
-        st = run(p.name, s, [&] { return launch_mfma(m, p.cfg.bt, kMfmaTileN, grid, s); });
-      }
+    if (split3) {                                        // hi*lo and lo*hi first, scaled by 1/2048, then hi*hi on top
+      m.passes = 3;
+      m.cf_lo = pc.cf_lo;
+      m.W_lo = u_lo;
+      m.lo_scale = 1.0f / 2048.0f;
+    } else {
+      m.passes = 1;
     }
+    dim3 grid((unsigned)(p.n_jt * p.n_bt), (unsigned)p.n_chunks, (unsigned)heads);
+    st = run(p.name, s, [&] { return launch_mfma(m, p.cfg.bt, kMfmaTileN, grid, s); });
   } else if (p.kind == kPlanBucket) {
     const BucketGeom g = bucket_geometry(a.n_in, a.n_out, (int)(a.cb_bytes / cb_row_bytes(p.cfg.code)), p.cfg.code,
                                          p.cfg.gb_kind);
@@ -773,10 +771,10 @@ kan_status kan_vq_layer_forward(const kan_vq_layer* L, const float* x, int64_t B
   return kan_vq_head_forward(L, 1, 1, x, B, y, ws, ws_bytes, path, stream);
 }
 
-// The dense baseline: the fp32 FMA kernel, and from kSplitMinBatch the split-operand matrix-core
+// The dense baseline: the fp32 FMA kernel, and from kDenseSplitMinBatch the split-operand matrix-core
 // form the precise VQ path uses (a converter of the coefficients in place of gather + dequantise).
 static LayerPlan plan_dense(int32_t in, int32_t out, int64_t B) {
-  if (B >= kSplitMinBatch) {
+  if (B >= kDenseSplitMinBatch) {
     LayerPlan p = plan_mfma(in, out, B, 1, 0, 0, kDense, true);
     p.name = "kan_dense_split";
     return p;

@@ -97,7 +97,13 @@ struct MfmaArgs {
   long long w_head_stride;     // 0 when all heads share the input
   const float* bias_partial;
   long long bp_head_stride;
-  int bias_on;                 // 0: this launch adds no bias sums (a cross product of the split form)
+  int bias_on;                 // 0: this launch adds no bias sums (the dense baseline has none)
+  // Split form (passes == 3): the low parts of both operands; the kernel runs its steps three
+  // times, (W, cf_lo), (W_lo, cf), then scales the sums by lo_scale and goes on with (W, cf).
+  int passes;                  // 1 or 3
+  const uint4* cf_lo;
+  const uint2* W_lo;
+  float lo_scale;              // 1 / 2048: the factor the low parts carry
   float* dst;
   long long dst_head_stride, dst_chunk_stride;
   int n_in, n_out, B;

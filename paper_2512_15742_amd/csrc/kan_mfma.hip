@@ -34,6 +34,12 @@
 //                   straight into registers a step and a half ahead, and the
 //                   contraction runs on the sparse matrix instruction
 //                   v_smfmac_f32_32x32x32_f16 (5 per row block and step).
+//   kan_prep_start  the first two for a single head's call in one launch: the coefficient
+//                   records of all its layers and the first layer's basis words.
+// The precise path at batch > 64 runs the same kernels on operands split into high
+// and low fp16 parts (c = hi + lo / 2048): the preparation kernels write both parts,
+// the contraction kernel makes three passes over its steps (hi*lo, lo*hi, scale by
+// 1/2048, hi*hi on top) and keeps fp32-grade sums.
 // k order inside a step: see kan_mfma_kernel.
 
 #include <type_traits>
@@ -370,7 +376,7 @@ __device__ __forceinline__ void fill_sparse_selectors(uint32_t (*sel)[8], int ti
   }
 }
 
-template <int MB, int NB>
+template <int MB, int NB, bool THREE>
 __global__ __launch_bounds__(kMfmaThreads, MB == 2 ? 3 : 2) void kan_mfma_kernel(const MfmaArgs a) {
   constexpr int BM = 32 * MB;          // samples per workgroup tile (MB = MFMA row blocks per wave)
   constexpr int BN = 4 * 32 * NB;      // outputs per workgroup tile
@@ -422,8 +428,17 @@ __global__ __launch_bounds__(kMfmaThreads, MB == 2 ? 3 : 2) void kan_mfma_kernel
   const int step0 = i_begin / IT;
   const int last_step = (n_in + IT - 1) / IT - 1;
 
-  const uint4* cf = a.cf + (long long)head * a.cf_head_stride;
-  const uint2* W = a.W + (long long)head * a.w_head_stride;
+  // Passes over the chunk's steps.  One pass: operands (W, cf).  Three (split form): first the
+  // cross products (W, cf_lo) and (W_lo, cf), whose low operands carry a factor 2048, then the
+  // accumulators are scaled by 1 / 2048 (exact) and the main product (W, cf) is added on top.
+  // Virtual step k = pass * n_steps + step; n1, n2 are the first steps of passes 1 and 2.
+  constexpr bool three = THREE;       // (a.passes == 3; a template parameter so that the one-pass form carries none of it)
+  const int total_steps = three ? 3 * n_steps : n_steps;
+  const int n1 = three ? n_steps : 0x3fffffff, n2 = three ? 2 * n_steps : 0x3fffffff;
+  const uint4* cf_main = a.cf + (long long)head * a.cf_head_stride;
+  const uint2* W_main = a.W + (long long)head * a.w_head_stride;
+  const uint4* cf_low = three ? a.cf_lo + (long long)head * a.cf_head_stride : cf_main;
+  const uint2* W_low = three ? a.W_lo + (long long)head * a.w_head_stride : W_main;
 
   // Phi generation: this thread owns sample row pb and inputs 4 ph0 .. 4 ph0 + NPAIR - 1 of every step.
   const int pb = tid & (BM - 1);
@@ -450,10 +465,11 @@ __global__ __launch_bounds__(kMfmaThreads, MB == 2 ? 3 : 2) void kan_mfma_kernel
   // scalar unit for each step, the lane offsets never change, so a load costs no vector
   // arithmetic.  Offsets stay below 2^31 because a resource spans one step of one head.
   const uint32_t u_off = (uint32_t)min(b0 + pb, B - 1) * (uint32_t)sizeof(uint4);
-  const char* w_bytes = (const char*)W;
   const uint32_t w_row_bytes = (uint32_t)B * (uint32_t)sizeof(uint4);       // a pair of inputs
-  auto load_u = [&](int k, uint2 (&uv)[NPAIR]) {       // step index relative to the chunk
+  auto load_u = [&](int kv, uint2 (&uv)[NPAIR]) {      // virtual step index
     // (the rows of a ragged last step exist and hold zeros; past the chunk: valid memory, never used)
+    const int k = kv - (kv >= n2 ? n2 : (kv >= n1 ? n1 : 0));
+    const char* w_bytes = (const char*)((three && kv >= n1 && kv < n2) ? W_low : W_main);
     const int i = min(step0 + k, last_step) * IT + 4 * ph0;
     const char* rows = w_bytes + (size_t)(i >> 1) * w_row_bytes;
     const __amdgpu_buffer_rsrc_t r = __builtin_amdgcn_make_buffer_rsrc((void*)rows, 0, (int)(NPAIR / 2 * w_row_bytes), kBufferFlags);
@@ -504,10 +520,11 @@ __global__ __launch_bounds__(kMfmaThreads, MB == 2 ? 3 : 2) void kan_mfma_kernel
   uint32_t b_off[NB];
 #pragma unroll
   for (int nb = 0; nb < NB; ++nb) b_off[nb] = (uint32_t)(lh * 2 * n_out + jc[nb]) * (uint32_t)sizeof(uint4);
-  const char* cf_bytes = (const char*)cf;
   const uint32_t a_bytes = (uint32_t)n_out * (uint32_t)sizeof(uint4);     // from a = 0 to a = 1
   const uint32_t s_bytes = 4u * a_bytes;                                  // from S to S + 1
-  auto step_rsrc = [&](int k) {                          // step index relative to the chunk
+  auto step_rsrc = [&](int kv) {                         // virtual step index
+    const int k = kv - (kv >= n2 ? n2 : (kv >= n1 ? n1 : 0));
+    const char* cf_bytes = (const char*)((three && kv < n1) ? cf_low : cf_main);
     const int step = min(step0 + k, last_step);         // past the end: valid memory, never used
     const char* sb = cf_bytes + (size_t)step * (5 * s_bytes);
     return __builtin_amdgcn_make_buffer_rsrc((void*)sb, 0, (int)(5 * s_bytes), kBufferFlags);
@@ -621,6 +638,15 @@ __global__ __launch_bounds__(kMfmaThreads, MB == 2 ? 3 : 2) void kan_mfma_kernel
     constexpr int sa = (2 * t) % 3, sb = (2 * t + 1) % 3;
     const unsigned char* tile = sA[k & 1];
     __syncthreads();     // tile k is complete; every wave is done reading tile k-1
+    if (three && k == n2) {       // split form: the cross products are complete
+      const float f = a.lo_scale;
+#pragma unroll
+      for (int m = 0; m < MB; ++m)
+#pragma unroll
+        for (int n = 0; n < NB; ++n)
+#pragma unroll
+          for (int r = 0; r < 16; ++r) acc[m][n][r] *= f;
+    }
     uint4 ix[MB];
     read_idx(tile, ix);
     __builtin_amdgcn_s_setprio(2);     // the wave that has its operands goes first at the matrix pipe (measured: 1.5-2 %)
@@ -638,13 +664,13 @@ __global__ __launch_bounds__(kMfmaThreads, MB == 2 ? 3 : 2) void kan_mfma_kernel
   // Whole groups of three steps run without a branch between them: a branch around a step makes
   // the compiler lose count of the loads in flight and wait for all of them.
   int k = 0;
-  for (; k + 3 <= n_steps; k += 3) {
+  for (; k + 3 <= total_steps; k += 3) {
     step(std::integral_constant<int, 0>{}, k);
     step(std::integral_constant<int, 1>{}, k + 1);
     step(std::integral_constant<int, 2>{}, k + 2);
   }
-  if (k < n_steps) step(std::integral_constant<int, 0>{}, k);
-  if (k + 1 < n_steps) step(std::integral_constant<int, 1>{}, k + 1);
+  if (k < total_steps) step(std::integral_constant<int, 0>{}, k);
+  if (k + 1 < total_steps) step(std::integral_constant<int, 1>{}, k + 1);
 
   // ---- epilogue.  D layout of the 32x32 MFMA: lane holds column (lane & 31), rows
   //      8*(r/4) + 4*(lane/32) + r%4 for r = 0..15 -------------------------------------------
@@ -755,13 +781,19 @@ hipError_t launch_prep_basis(const float* x, long long x_head_stride, int x_part
 
 hipError_t launch_mfma(const MfmaArgs& a, int tile_m, int tile_n, dim3 grid, hipStream_t s) {
   if ((tile_m != 64 && tile_m != 128) || tile_n != 128) return hipErrorInvalidValue;
+  if (a.passes != 1 && (a.passes != 3 || !a.cf_lo || !a.W_lo)) return hipErrorInvalidValue;
   if ((long long)a.n_jt * tile_n < a.n_out) return hipErrorInvalidValue;
   // one step of coefficient records and one row of basis words must fit a buffer resource
   if ((long long)a.n_out * 20 * (long long)sizeof(uint4) > 0x7fffffffLL ||
       (long long)a.B * 8 * (long long)sizeof(uint2) > 0x7fffffffLL)
     return hipErrorInvalidValue;
-  if (tile_m == 128) hipLaunchKernelGGL((kan_mfma_kernel<4, 1>), grid, dim3(kMfmaThreads), 0, s, a);
-  else hipLaunchKernelGGL((kan_mfma_kernel<2, 1>), grid, dim3(kMfmaThreads), 0, s, a);
+  if (a.passes == 3) {
+    if (tile_m == 128) hipLaunchKernelGGL((kan_mfma_kernel<4, 1, true>), grid, dim3(kMfmaThreads), 0, s, a);
+    else hipLaunchKernelGGL((kan_mfma_kernel<2, 1, true>), grid, dim3(kMfmaThreads), 0, s, a);
+  } else {
+    if (tile_m == 128) hipLaunchKernelGGL((kan_mfma_kernel<4, 1, false>), grid, dim3(kMfmaThreads), 0, s, a);
+    else hipLaunchKernelGGL((kan_mfma_kernel<2, 1, false>), grid, dim3(kMfmaThreads), 0, s, a);
+  }
   return hipGetLastError();
 }
 

@@ -40,7 +40,8 @@ def test_f16cb_every_kernel_family(kb, gb_dtype):
     rng = np.random.default_rng(8)
     seen = set()
     for B, path, tol in [(1, kb.KAN_PATH_GATHER, TOL_FP32), (9, kb.KAN_PATH_GATHER, TOL_FP32),
-                         (70, kb.KAN_PATH_GATHER, TOL_FP32), (20, kb.KAN_PATH_MFMA, TOL_MFMA),
+                         (50, kb.KAN_PATH_GATHER, TOL_FP32), (70, kb.KAN_PATH_GATHER, TOL_FP32),
+                             (20, kb.KAN_PATH_MFMA, TOL_MFMA),
                          (150, kb.KAN_PATH_MFMA, TOL_MFMA)]:
         x = rng.uniform(-1.1, 1.1, size=(B, 300)).astype(np.float32)
         L = kb.VQLayer(P)
@@ -49,7 +50,7 @@ def test_f16cb_every_kernel_family(kb, gb_dtype):
         y_ref, A = ko.vq_layer_forward(x, **P.as_dict(), return_abs=True)
         rep = ko.error_report(y, y_ref, A)
         assert rep["headline"] <= tol and rep["strict"] <= tol, (B, path, rep)
-    assert seen == {"kan_gather_bt1", "kan_fused_f32", "kan_fused_f16", "kan_mfma"}
+    assert seen == {"kan_gather_bt1", "kan_fused_f32", "kan_mfma_split", "kan_fused_f16", "kan_mfma"}
 
 
 @pytest.mark.parametrize("n_in,n_out,K,B", [(1, 1, 2, 1), (3, 21, 5, 2), (130, 67, 9000, 5), (257, 530, 20000, 1),

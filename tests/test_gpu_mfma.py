@@ -162,7 +162,7 @@ def test_single_head_start_launch_mixed_types_and_many_layers(kb, path_name):
     """A single head's call prepares the coefficient records of its layers in one launch, but only
     those stored like the first layer and only the first four: a six-layer head whose third and
     fifth layers use other storage types takes both ways in one call (fp16 path, and the split
-    precise path from batch 112)."""
+    precise path from batch 65)."""
     path = kb.KAN_PATH_MFMA if path_name == "mfma" else kb.KAN_PATH_GATHER
     tol = TOL_MFMA if path_name == "mfma" else 1e-5
     dims = [(70, 96), (96, 130), (130, 64), (64, 80), (80, 33), (33, 21)]

@@ -75,12 +75,13 @@ def test_pli_every_kernel_family(kb, cb, gb):
     seen = set()
     for B, path, tol, prepared in [(1, kb.KAN_PATH_GATHER, TOL_FP32, False), (1, kb.KAN_PATH_GATHER, TOL_FP32, True),
                                    (3, kb.KAN_PATH_GATHER, TOL_FP32, True), (9, kb.KAN_PATH_GATHER, TOL_FP32, False),
-                                   (70, kb.KAN_PATH_GATHER, TOL_FP32, False), (20, kb.KAN_PATH_MFMA, TOL_MFMA, False),
+                                   (50, kb.KAN_PATH_GATHER, TOL_FP32, False), (70, kb.KAN_PATH_GATHER, TOL_FP32, False),
+                                   (20, kb.KAN_PATH_MFMA, TOL_MFMA, False),
                                    (150, kb.KAN_PATH_MFMA, TOL_MFMA, False)]:
         x = rng.uniform(-1.1, 1.1, size=(B, 300)).astype(np.float32)
         x[0, :4] = [1.0, -1.0, np.float32(7.0 / 9.0), np.float32(-1.0 / 9.0)]
         seen.add(_check(kb, P, x, path, tol, prepared))
-    assert seen == {"kan_gather_bt1", "kan_bucket", "kan_fused_f32", "kan_fused_f16", "kan_mfma"}
+    assert seen == {"kan_gather_bt1", "kan_bucket", "kan_fused_f32", "kan_mfma_split", "kan_fused_f16", "kan_mfma"}
 
 
 @pytest.mark.parametrize("B,path,prepared", [(1, "gather", True), (1, "gather", False), (16, "gather", False),

@@ -30,7 +30,7 @@ def test_split_takes_over_the_precise_path_at_large_batch(kb):
     P = synth.make_layer(1, 256, 128, 4096, cb_dtype="i8", gb_dtype="f16")
     L = kb.VQLayer(P)
     assert kb.kan_vq_planned_kernel(L, 64, 1, kb.KAN_PATH_GATHER) == "kan_fused_f32"
-    assert kb.kan_vq_planned_kernel(L, 112, 1, kb.KAN_PATH_GATHER) == "kan_mfma_split"
+    assert kb.kan_vq_planned_kernel(L, 65, 1, kb.KAN_PATH_GATHER) == "kan_mfma_split"
     assert kb.kan_vq_planned_kernel(L, 4096, 1, kb.KAN_PATH_GATHER) == "kan_mfma_split"
     assert kb.kan_vq_planned_kernel(L, 4096, 1, kb.KAN_PATH_MFMA) == "kan_mfma"
     assert kb.kan_vq_planned_kernel(L, 4096, 1, kb.KAN_PATH_AUTO) == "kan_mfma"
@@ -131,11 +131,11 @@ def test_split_config2_and_config3(kb, B):
 # ---- the dense baseline on the same split operands -----------------------------------
 
 @pytest.mark.parametrize("n_in,n_out,B", [(8, 32, 129), (130, 67, 200), (257, 130, 150), (64, 520, 133),
-                                          (1000, 264, 300), (2052, 70, 112), (33, 1, 500)])
+                                          (1000, 264, 300), (2052, 70, 112), (33, 1, 500), (300, 40, 17)])
 def test_dense_baseline_split_form(kb, n_in, n_out, B):
-    """The dense layer at batch >= 112 runs the same three contractions on coefficients it
+    """The dense layer at batch >= 17 runs the same three-pass contraction on coefficients it
     splits itself; below that it stays on the fp32 FMA kernel.  Both against the oracle's
-    dense layer, and against each other across the switch (batch 111 / 112 share rows)."""
+    dense layer, and against each other across the switch (the first 16 rows again)."""
     rng = np.random.default_rng(n_in * 13 + n_out)
     coef = (rng.standard_normal((n_in, n_out, 10)) * rng.uniform(1e-3, 2.0, (n_in, n_out, 1))).astype(np.float32)
     coef[0, 0, :] = 1e-6                      # below fp16's normal range
@@ -147,8 +147,8 @@ def test_dense_baseline_split_form(kb, n_in, n_out, B):
     y_ref, A = ko.dense_layer_forward(coef, x, return_abs=True)
     rep = ko.error_report(y, y_ref, A)
     assert rep["headline"] <= TOL_FP32 and rep["strict"] <= TOL_FP32, rep
-    y_small = kb.kan_dense_layer_forward(cd, to_dev(x[:111])).cpu().numpy()
-    assert np.abs(y_small - y[:111]).max() <= 2 * TOL_FP32 * np.abs(y_ref).max()
+    y_small = kb.kan_dense_layer_forward(cd, to_dev(x[:16])).cpu().numpy()
+    assert np.abs(y_small - y[:16]).max() <= 2 * TOL_FP32 * np.abs(y_ref).max()
 
 
 def test_dense_baseline_split_config2_twin(kb):
@@ -163,6 +163,6 @@ def test_dense_baseline_split_config2_twin(kb):
 
 
 def test_dense_planned_kernel(kb):
-    assert kb.kan_dense_planned_kernel(2048, 512, 111) == "kan_dense"
-    assert kb.kan_dense_planned_kernel(2048, 512, 112) == "kan_dense_split"
+    assert kb.kan_dense_planned_kernel(2048, 512, 16) == "kan_dense"
+    assert kb.kan_dense_planned_kernel(2048, 512, 17) == "kan_dense_split"
     assert kb.kan_dense_planned_kernel(0, 512, 112) == "invalid"
