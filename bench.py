@@ -125,14 +125,18 @@ def run_batch(kb, torch, synth, copies, B, path, steps, warmup, prepared=False):
 def sweep(kb, torch, synth):
     """Wall time per forward of every configuration (cache-warm, single parameter copy)."""
     def wall(fn, reps):
+        # median of three timed blocks of `reps` calls (a single block now and then catches a stall)
         for _ in range(3):
             fn()
-        torch.cuda.synchronize()
-        t0 = time.perf_counter()
-        for _ in range(reps):
-            fn()
-        torch.cuda.synchronize()
-        return (time.perf_counter() - t0) / reps
+        blocks = []
+        for _ in range(3):
+            torch.cuda.synchronize()
+            t0 = time.perf_counter()
+            for _ in range(reps):
+                fn()
+            torch.cuda.synchronize()
+            blocks.append((time.perf_counter() - t0) / reps)
+        return sorted(blocks)[1]
 
     def vq_rows(tag, heads_p, x, paths, reps, prepared=False, rule=0):
         heads = [[kb.VQLayer(p, rule=rule) for p in ps] for ps in heads_p]
