@@ -176,6 +176,28 @@ def test_fp16_codebook_layers_plan_and_prepare():
     assert L.kan_vq_planned_kernel(C.byref(d), 8, 1, kb.KAN_PATH_GATHER) == b"kan_fused_f32"
 
 
+def test_precise_path_switches_and_workspace_sizes():
+    """Host logic only: where the precise path and the dense baseline change kernels, and that
+    the workspace of the split form holds both parts of both operands and one set of partial
+    sums (its three products are passes of one launch)."""
+    L = kb.lib()
+    d = _desc(n_in=2048, n_out=1024, K=65536)
+    assert L.kan_vq_planned_kernel(C.byref(d), 64, 1, kb.KAN_PATH_GATHER) == b"kan_fused_f32"
+    assert L.kan_vq_planned_kernel(C.byref(d), 65, 1, kb.KAN_PATH_GATHER) == b"kan_mfma_split"
+    assert L.kan_vq_planned_kernel(C.byref(d), 65, 1, kb.KAN_PATH_MFMA) == b"kan_mfma"
+    assert L.kan_dense_planned_kernel(2048, 1024, 16) == b"kan_dense"
+    assert L.kan_dense_planned_kernel(2048, 1024, 17) == b"kan_dense_split"
+    assert L.kan_dense_planned_kernel(2048, 1024, 0) == b"invalid"
+    B = 1024
+    one = L.kan_vq_workspace_bytes(C.byref(d), 1, 1, B, kb.KAN_PATH_MFMA)
+    three = L.kan_vq_workspace_bytes(C.byref(d), 1, 1, B, kb.KAN_PATH_GATHER)
+    records = (2048 // 16) * 20 * 1024 * 16              # coefficient records of one part
+    words = 2048 * B * 8                                 # basis words of one part
+    assert three - one == records + words, (one, three)  # same chunks, same partial sums
+    dense = L.kan_dense_workspace_bytes(2048, 1024, B)
+    assert dense >= 2 * (records + words) and dense < three
+
+
 def test_assign_argument_errors():
     L = kb.lib()
     F = FAKE
