@@ -166,3 +166,19 @@ def test_dense_planned_kernel(kb):
     assert kb.kan_dense_planned_kernel(2048, 512, 16) == "kan_dense"
     assert kb.kan_dense_planned_kernel(2048, 512, 17) == "kan_dense_split"
     assert kb.kan_dense_planned_kernel(0, 512, 112) == "invalid"
+
+
+def test_split_config5_sampled(kb):
+    """The largest configured layer (4096 -> 4096, K = 262,144, batch 8192) through the
+    three-pass form: sampled outputs and whole rows against the oracle at the fp32 bound."""
+    (P,), x = synth.config5("i8")
+    L = kb.VQLayer(P)
+    assert kb.kan_vq_planned_kernel(L, x.shape[0], 1, kb.KAN_PATH_GATHER) == "kan_mfma_split"
+    y = kb.kan_vq_layer_forward(L, to_dev(x), path=kb.KAN_PATH_GATHER).cpu().numpy()
+    assert np.isfinite(y).all()
+    rep = check_layer_output(y, x, P, TOL_FP32, n_samples=64, full=False, seed=55)
+    rows = np.array([0, 127, 128, 4095, 8191])
+    y_ref, A = ko.vq_layer_forward(x[rows], **P.as_dict(), return_abs=True)
+    rep_rows = ko.error_report(y[rows], y_ref, A)
+    print("config5 precise", rep, rep_rows)
+    assert rep_rows["headline"] <= TOL_FP32 and rep_rows["strict"] <= TOL_FP32, rep_rows
