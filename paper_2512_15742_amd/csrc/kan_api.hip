@@ -265,8 +265,8 @@ bool layer_prepared_ok(const kan_vq_layer& L) {
 //   precise path (KAN_PATH_GATHER, and AUTO below batch 32): B = 1 the window-gather kernel,
 //     B >= 2 the fused kernel with fp32 matrix-core operands (the fp32 FMA kernel remains the
 //     dense baseline's), from kSplitMinBatch the preparation + streaming contraction of the
-//     fp16 path run three times over operands split into high and low fp16 parts
-//     (hi*hi + hi*lo + lo*hi: fp32-grade sums at matrix-core speed);
+//     fp16 path on operands split into high and low fp16 parts, the contraction making
+//     three passes (hi*lo, lo*hi, hi*hi: fp32-grade sums at matrix-core speed);
 //   fp16 path (KAN_PATH_MFMA, and AUTO from batch 32): up to kHalfFusedMaxBatch the fused
 //     kernel with fp16 operands, above that coefficient/basis preparation + the streaming
 //     contraction.
