@@ -353,8 +353,8 @@ __global__ __launch_bounds__(kThreads) void kan_prep_start_kernel(const PrepStar
 // Per span l: byte-permute selectors that pick, from the four fp16 weights {w23:w01} of an
 // input, the stored values of its pairs (m, m+5): word 0 pairs 0 and 1, word 1 pairs 2 and 3,
 // word 2 pair 4 (high half zero); word 3 the index byte of the input's two full groups
-// (nibble = position of the first value | position of the second << 2), word 4 whether
-// pair 4 takes coefficient 9.  Selector byte 0x0c yields 0.
+// (nibble = position of the first value | position of the second << 2) and, in bit 8, whether
+// pair 4 takes coefficient 9: one 16-byte table read per input.  Selector byte 0x0c yields 0.
 __device__ __forceinline__ void fill_sparse_selectors(uint32_t (*sel)[8], int tid) {
   if (tid < kSpans) {
     const int l = tid;
@@ -370,9 +370,8 @@ __device__ __forceinline__ void fill_sparse_selectors(uint32_t (*sel)[8], int ti
     sel[l][0] = half_sel[0] | (half_sel[1] << 16);
     sel[l][1] = half_sel[2] | (half_sel[3] << 16);
     sel[l][2] = half_sel[4] | 0x0c0c0000u;
-    sel[l][3] = (hi[0] | ((2u + hi[1]) << 2)) | ((hi[2] | ((2u + hi[3]) << 2)) << 4);
-    sel[l][4] = hi[4];
-    sel[l][5] = sel[l][6] = sel[l][7] = 0;
+    sel[l][3] = (hi[0] | ((2u + hi[1]) << 2)) | ((hi[2] | ((2u + hi[3]) << 2)) << 4) | (hi[4] << 8);
+    sel[l][4] = sel[l][5] = sel[l][6] = sel[l][7] = 0;
   }
 }
 
@@ -499,8 +498,8 @@ __global__ __launch_bounds__(kMfmaThreads, MB == 2 ? 3 : 2) void kan_mfma_kernel
         st.x = __builtin_amdgcn_perm(w23, w01, sl.x);
         st.y = __builtin_amdgcn_perm(w23, w01, sl.y);
         v4[q] = __builtin_amdgcn_perm(w23, w01, sl.z);
-        ib[q] = sl.w;
-        h4[q] = sSel[l][4];
+        ib[q] = sl.w & 0xffu;
+        h4[q] = sl.w >> 8;            // (word 3 carries both: one table read per input)
         *(uint2*)(rowp + (ph * 2 + (q & 1)) * 16 + (q >> 1) * 8) = st;
       }
       uint2 t4;
