@@ -236,3 +236,35 @@ def test_prof_state_machine_without_gpu_work():
     n = C.c_int32(-1)
     assert L.kan_prof_end(None, 0, C.byref(n)) == kb.KAN_ERR_UNSUPPORTED      # not begun
     assert L.kan_prof_begin(0) == kb.KAN_ERR_SHAPE
+
+
+def test_planner_accepts_every_shape_and_names_a_known_kernel():
+    """Host logic over a seeded sweep of shapes, batches, head counts, storage types and paths:
+    the workspace query succeeds, is a multiple of 256 bytes, and the kernel the dispatcher
+    names is one of the families the library has."""
+    import numpy as np
+    L = kb.lib()
+    rng = np.random.default_rng(20251127)
+    known = {b"kan_gather_bt1", b"kan_gather_bt4", b"kan_gather_bt16", b"kan_fused_f32", b"kan_fused_f16",
+             b"kan_mfma", b"kan_mfma_split", b"kan_bucket"}
+    kinds = [(kb.KAN_F32, kb.KAN_F32), (kb.KAN_I8, kb.KAN_F16), (kb.KAN_I8, kb.KAN_F32), (kb.KAN_F16, kb.KAN_F16),
+             (kb.KAN_I8, kb.KAN_Q8)]
+    seen = set()
+    for _ in range(400):
+        n_in = int(rng.choice([1, 3, 8, 64, 130, 1000, 2048, 4100, 8192]))
+        n_out = int(rng.choice([1, 8, 21, 128, 264, 1024, 4096]))
+        B = int(rng.choice([1, 2, 4, 5, 16, 33, 64, 65, 111, 200, 1024, 5000]))
+        heads = int(rng.choice([1, 1, 2, 50, 70]))
+        cb, gb = kinds[int(rng.integers(len(kinds)))]
+        u32 = bool(rng.integers(2))
+        d = _desc(n_in=n_in, n_out=n_out, K=70000 if u32 else 4096, cb_dtype=cb, gb_dtype=gb,
+                  idx_dtype=kb.KAN_U32 if u32 else kb.KAN_U16, scale=0.01, gain_log2_lo=-8.0, gain_log2_step=0.05,
+                  bias_scale=1e-3)
+        for path in (kb.KAN_PATH_AUTO, kb.KAN_PATH_GATHER, kb.KAN_PATH_MFMA):
+            name = L.kan_vq_planned_kernel(C.byref(d), B, heads, path)
+            assert name in known, (n_in, n_out, B, heads, cb, gb, path, name)
+            seen.add(name)
+            arr = (kb.kan_vq_layer * heads)(*([d] * heads))
+            ws = L.kan_vq_workspace_bytes(arr, 1, heads, B, path)
+            assert ws != kb.SIZE_INVALID and ws % 256 == 0, (n_in, n_out, B, heads, path, ws)
+    assert {b"kan_gather_bt1", b"kan_fused_f32", b"kan_fused_f16", b"kan_mfma", b"kan_mfma_split"} <= seen
