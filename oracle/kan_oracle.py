@@ -46,7 +46,9 @@ every linear function, hat-function integrals, index against brute force; for
 byte-coded gain/bias: exact powers of two at integer exponents, zero code,
 monotonicity, round trip through the encoder within half a step; for the
 assignment step: brute-force loops, scipy's k-d tree, exact recovery of a layer built
-from the codebook (R^2 = 1), invariance under affine changes of a grid.
+from the codebook (R^2 = 1), invariance under affine changes of a grid; for the error
+scale A = sum_i |phi_ij|: the scalar definition summed edge by edge, constant and linear
+codewords (closed forms), in both vectorised forms.
 """
 from __future__ import annotations
 

@@ -415,6 +415,62 @@ def test_pli_layer_closed_forms_and_scalar_definition():
     assert np.abs(ko.vq_layer_outputs_at(x, cb, 1.0, idx, gain, bias, bs, js, rule="pli") - y[bs, js]).max() < 1e-14
 
 
+# ---- the error scale A = sum_i |phi_ij| (the denominator of every strict per-element gate) ----
+
+def test_abs_sum_A_against_the_scalar_definition_and_closed_forms():
+    """A[b][j] = sum_i |phi_ij(x_bi)| from both vectorised forms against (a) the scalar Cox-de Boor
+    definition summed edge by edge, (b) a constant codeword, where every edge is the constant
+    gain * v + bias, and (c) a Greville (linear) codeword, where phi_ij(x) = gain * a * x + bias.
+    A mistake such as sum_i sum_m |B_m c_m| (larger: it would loosen every strict gate) fails all three."""
+    for int8 in (False, True):
+        x, cb, scale, idx, gain, bias = _tiny(seed=12, n_in=6, n_out=4, B=5, K=7, int8=int8)
+        A_def = np.zeros((x.shape[0], idx.shape[1]))
+        for b in range(x.shape[0]):
+            for j in range(idx.shape[1]):
+                A_def[b, j] = math.fsum(
+                    abs(ko.edge_phi_scalar(ko.reconstruct_scalar(cb.tolist(), float(scale), idx.tolist(), gain.tolist(),
+                                                                 bias.tolist(), i, j), float(x[b, i])))
+                    for i in range(x.shape[1]))
+        _, A = ko.vq_layer_forward(x, cb, scale, idx, gain, bias, return_abs=True)
+        np.testing.assert_allclose(A, A_def, rtol=0, atol=1e-15)
+        bs, js = [0, 4, 2, 1], [3, 0, 1, 2]
+        _, As = ko.vq_layer_outputs_at(x, cb, scale, idx, gain, bias, bs, js, return_abs=True)
+        np.testing.assert_allclose(As, A_def[bs, js], rtol=0, atol=1e-15)
+    rng = np.random.default_rng(13)
+    K, n_in, n_out, B = 5, 7, 3, 6
+    idx = rng.integers(0, K, size=(n_in, n_out)).astype(np.uint16)
+    gain = rng.normal(size=(n_in, n_out))               # mixed signs: |sum| and sum of |.| differ
+    bias = rng.normal(size=(n_in, n_out))
+    x = rng.uniform(-1.3, 1.3, size=(B, n_in))
+    # (b) constant codewords
+    v = rng.normal(size=K)
+    cb = np.repeat(v[:, None], 10, axis=1)
+    y, A = ko.vq_layer_forward(x, cb, 1.0, idx, gain, bias, return_abs=True)
+    expect = np.abs(gain * v[idx] + bias).sum(axis=0)
+    np.testing.assert_allclose(A, np.broadcast_to(expect, (B, n_out)), atol=1e-13)
+    assert (A > np.abs(y) + 1e-3).any()                 # the case tells A from |y|
+    _, As = ko.vq_layer_outputs_at(x, cb, 1.0, idx, gain, bias, [1, 5], [2, 0], return_abs=True)
+    np.testing.assert_allclose(As, expect[[2, 0]], atol=1e-13)
+    # (c) linear codewords: rows a_k * (Greville abscissae)
+    t = ko.knots()
+    grev = np.array([(t[m + 1] + t[m + 2] + t[m + 3]) / 3 for m in range(10)])
+    a = rng.normal(size=K)
+    cbl = a[:, None] * grev[None, :]
+    xc = np.clip(x, -1, 1)
+    expect = np.abs(gain[None] * a[idx][None] * xc[:, :, None] + bias[None]).sum(axis=1)       # [B][out]
+    for rule_cb, rule in ((cbl, "bspline"), (a[:, None] * ko.pli_nodes()[None, :], "pli")):
+        _, A = ko.vq_layer_forward(x, rule_cb, 1.0, idx, gain, bias, return_abs=True, rule=rule)
+        np.testing.assert_allclose(A, expect, atol=1e-13)
+        _, As = ko.vq_layer_outputs_at(x, rule_cb, 1.0, idx, gain, bias, [0, 3], [1, 2], return_abs=True, rule=rule)
+        np.testing.assert_allclose(As, expect[[0, 3], [1, 2]], atol=1e-13)
+    # dense form on its own (the dense baseline's gate)
+    coef = rng.normal(size=(n_in, n_out, 10))
+    _, Ad = ko.dense_layer_forward(coef, x, return_abs=True)
+    ref = np.array([[math.fsum(abs(ko.edge_phi_scalar(coef[i, j], x[b, i])) for i in range(n_in))
+                     for j in range(n_out)] for b in range(B)])
+    np.testing.assert_allclose(Ad, ref, atol=1e-14)
+
+
 # ---- the pins bite: a planted mistake in the oracle fails at least one of them ----------
 
 def _pin_suite():
@@ -430,6 +486,7 @@ def _pin_suite():
             test_pli_layer_closed_forms_and_scalar_definition, test_q8_gain_bias_meaning,
             test_q8_round_trip_through_the_encoder, test_assignment_brute_force_and_kdtree,
             test_assignment_recovers_a_layer_built_from_the_codebook,
+            test_abs_sum_A_against_the_scalar_definition_and_closed_forms,
             lambda: test_scalar_definition_vs_vectorised(False), lambda: test_scalar_definition_vs_vectorised(True)]
 
 
@@ -449,7 +506,7 @@ def _mutations():
     real = {k: getattr(ko, k) for k in ("knots", "basis_matrix", "reconstruct_coefficients", "dequantise_codebook",
                                         "dense_layer_forward", "pli_matrix", "pli_nodes", "clamp_input",
                                         "vq_head_forward", "dequantise_gain_bias", "normalise_grids",
-                                        "squared_distances")}
+                                        "squared_distances", "vq_layer_outputs_at")}
 
     def knots_shifted():                       # knot vector off by one interval
         return real["knots"]() + 2.0 / 7.0
@@ -516,6 +573,25 @@ def _mutations():
         y = real["dense_layer_forward"](np.ascontiguousarray(coef[:, ::-1, :]), x, rule=rule)     # outputs reversed
         return (y, np.abs(y)) if return_abs else y
 
+    def dense_abs_per_coefficient(coef, x, return_abs=False, rule="bspline"):       # A = sum_i sum_m |B_m c_m|: too large
+        y = real["dense_layer_forward"](coef, x, rule=rule)
+        if not return_abs:
+            return y
+        Bm = ko.design_matrix(np.asarray(x, dtype=np.float64), rule)
+        return y, np.einsum("bim,ijm->bj", np.abs(Bm), np.abs(np.asarray(coef, dtype=np.float64)))
+
+    def outputs_at_abs_of_the_sum(x, cb, scale, idx, gain, bias, bs, js, return_abs=False, rule="bspline", gb_params=None):
+        out = real["vq_layer_outputs_at"](x, cb, scale, idx, gain, bias, bs, js, rule=rule, gb_params=gb_params)
+        return (out, np.abs(out)) if return_abs else out      # A = |sum_i phi|: too small
+
+    def outputs_at_abs_per_coefficient(x, cb, scale, idx, gain, bias, bs, js, return_abs=False, rule="bspline", gb_params=None):
+        out = real["vq_layer_outputs_at"](x, cb, scale, idx, gain, bias, bs, js, rule=rule, gb_params=gb_params)
+        if not return_abs:
+            return out
+        coef = real["reconstruct_coefficients"](cb, scale, idx, gain, bias, gb_params)
+        Bm = ko.design_matrix(np.asarray(x, dtype=np.float64), rule)
+        return out, np.array([(np.abs(Bm[b]) * np.abs(coef[:, j])).sum() for b, j in zip(bs, js)])
+
     def pli_swapped_taps(x):                   # u and 1-u exchanged
         W = real["pli_matrix"](x)
         k = ko.pli_index(np.asarray(x, dtype=np.float64).reshape(-1)).astype(np.int64)
@@ -565,7 +641,10 @@ def _mutations():
             ("natural instead of binary log", "dequantise_gain_bias", q8_natural_log),
             ("unit variance instead of unit norm", "normalise_grids", normalise_by_std),
             ("grids not centred", "normalise_grids", normalise_without_centring),
-            ("dot product used as a distance", "squared_distances", distances_as_dot_products)]
+            ("dot product used as a distance", "squared_distances", distances_as_dot_products),
+            ("A summed per coefficient (dense form)", "dense_layer_forward", dense_abs_per_coefficient),
+            ("A taken as |sum| (sampled form)", "vq_layer_outputs_at", outputs_at_abs_of_the_sum),
+            ("A summed per coefficient (sampled form)", "vq_layer_outputs_at", outputs_at_abs_per_coefficient)]
 
 
 def test_pins_pass_unmutated():
