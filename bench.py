@@ -30,7 +30,7 @@ if ROOT not in sys.path:
 
 PEAK_HBM_GBPS = 8000.0          # MI355X HBM3E
 PEAK_FP32_VECTOR_TFLOPS = 157.3
-PEAK_BF16_MFMA_TFLOPS = 2500.0
+PEAK_F16_MFMA_TFLOPS = 2500.0
 FLOP_PER_EDGE_EVAL = 8.0        # 4 multiply-adds under the nonzero cubic bases
 FLOP_PER_EDGE_RECON = 20.0      # gain * C[idx] + bias over G = 10, once per launch
 MALL_BYTES = 256 << 20
@@ -340,7 +340,7 @@ def main():
         # compute-bound regime (the metadata stream stops being the limit near B = 12-20)
         flops = edges_per_launch * (B * FLOP_PER_EDGE_EVAL + FLOP_PER_EDGE_RECON)
         # fp16 operands price against the fp16/bf16 matrix-core peak, fp32 operands against the fp32 one
-        peak = PEAK_BF16_MFMA_TFLOPS if (is_mfma and family != "kan_fused_f32") else PEAK_FP32_VECTOR_TFLOPS
+        peak = PEAK_F16_MFMA_TFLOPS if (is_mfma and family != "kan_fused_f32") else PEAK_FP32_VECTOR_TFLOPS
         roof = {"bound": "mfma" if is_mfma else "alu", "achieved": flops / avg_s / 1e12, "peak": peak,
                 "unit": "TFLOP/s", "kernel": dom, "avg_launch_us": r["kernels_avg_us"][dom],
                 "traffic": MEASURED_TRAFFIC.get((dom, B))}

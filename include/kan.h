@@ -21,8 +21,10 @@
  *     runtime malloc: paper section 4.3).  ws must be 256-byte aligned.
  *   - Work is enqueued on `stream` (a hipStream_t passed as void*; NULL is the
  *     default stream).  No call synchronises the device or reads results back.
- *   - Arguments are validated on the host first; on any error a status other
- *     than KAN_OK is returned and NOTHING has been enqueued.
+ *   - Arguments are validated on the host first: every status but KAN_OK and
+ *     KAN_ERR_LAUNCH means that nothing has been enqueued.  KAN_ERR_LAUNCH (the HIP
+ *     runtime rejected a kernel launch) can come after earlier kernels of the same
+ *     call are already on the stream; outputs and workspace are then undefined.
  *   - Layouts: x[B][in] and y[B][out] row-major fp32; per-edge arrays
  *     idx/gain/bias[in][out] with edge e = i*out + j (j fastest); codebook
  *     [K][10] row-major, unpadded; dense coefficients coef[in][out][10].
@@ -30,6 +32,16 @@
  *     codebooks to 4 bytes (rows are read in pairs of entries); else KAN_ERR_SHAPE.
  *   - idx values must be < K; they are not checked by the forward calls (use
  *     kan_vq_count_bad_indices).  y must not alias x or the workspace.
+ *   - Value range on the matrix cores (KAN_PATH_MFMA at any batch; KAN_PATH_GATHER from
+ *     batch 65, the dense baseline from batch 17): the coefficient operand is carried as
+ *     fp16 numbers gain * q (Int8 codebooks, q the byte code) or gain * C (floating
+ *     codebooks, dense coefficients), so these products must stay below 65504 in magnitude
+ *     (gains up to about 515 with Int8 codes) or the result is infinite; products below
+ *     6.1e-5 in magnitude keep fewer bits (the split form of the precise path: the 11 bits
+ *     of its low part).  The stated bounds hold for layers whose |gain * q| or |gain * C| lie
+ *     in [6.1e-5, 65504] or are 0; kan_vq_coef_range reports the range of a layer.  The
+ *     vector-ALU, bucket and fused fp32 kernels (KAN_PATH_GATHER up to batch 64) have no
+ *     such limit.
  */
 #ifndef KAN_MI355X_H
 #define KAN_MI355X_H
@@ -114,14 +126,27 @@ typedef struct kan_vq_layer {
 /* Spans and basis weights of step "index lookup" (section 4.1) for the cubic
  * family of App. A.1: for every x[n] (clamped to [-1,1]) the interval index
  * span[n] in 0..6 and the four nonzero Cox-de Boor weights w[n][0..3], which
- * multiply coefficients span..span+3.  Parity/debug entry point; the forward
- * calls compute the same quantities internally with the same device function.
- * x, span, w: device.  n >= 0 (n == 0 is a no-op).                               */
+ * multiply coefficients span..span+3.  Parity/debug entry point: it runs the device
+ * routine of the vector-ALU and bucket kernels (exact comparisons of 7x with the
+ * knots' numerators in fp64, weights in fp64 rounded once); the fused kernel and the
+ * basis preparation of the streaming contraction use a second routine, which
+ * kan_basis_window exposes.  x, span, w: device.  n >= 0 (n == 0 is a no-op).     */
 kan_status kan_bspline_basis(const float* x, int64_t n, uint8_t* span, float* w, void* stream);
 
 /* The same for KAN_RULE_PLI2: index[n] = k in 0..8 (the interval [n_k, n_k+1) that holds the
  * clamped x[n]; x = +1 gives 8) and w[n][0..1] = (1 - u, u), the weights of entries k, k+1.   */
 kan_status kan_pli_basis(const float* x, int64_t n, uint8_t* index, float* w, void* stream);
+
+/* The window of four consecutive codeword entries and their four weights, as the forward kernels
+ * form it for either rule (sections 4.1 / 4.3 and App. A.1): start[n] = first entry (cubic rule:
+ * the interval index 0..6; two-tap rule: min(k, 6), the taps 1 - u, u sitting at offset k - start,
+ * the other two weights 0) and w[n][0..3].  variant 0: the routine of the vector-ALU and bucket
+ * kernels (what kan_bspline_basis / kan_pli_basis run); variant 1: the routine of the fused kernel
+ * and of the basis preparation (index by one fp64 fma and truncation, which is exact, weights in
+ * fp32).  Both must give the same start for every fp32 x; parity/debug entry point.
+ * x, start, w: device; w 16-byte aligned.                                                        */
+kan_status kan_basis_window(const float* x, int64_t n, int32_t rule, int32_t variant, uint8_t* start, float* w,
+                            void* stream);
 
 /* Bytes of workspace kan_vq_layer_forward / kan_vq_head_forward need for these
  * descriptors (host array [n_heads][n_layers]), batch B and path.  Returns 0
@@ -191,6 +216,14 @@ kan_status kan_vq_debug_gather(const kan_vq_layer* L, uint32_t* ids, float* rows
 /* Debug: *count (device uint32, overwritten) = number of edges with idx >= K.   */
 kan_status kan_vq_count_bad_indices(const kan_vq_layer* L, uint32_t* count, void* stream);
 
+/* Debug: the range of the fp16 coefficient operand of the matrix-core kernels for this layer
+ * (the reconstructed coefficients of section 4.2 without bias and Int8 scale, which stay fp32):
+ * range[0] = smallest nonzero and range[1] = largest magnitude of gain * q (Int8 codebooks, q the
+ * byte code) or gain * C (floating codebooks) over all edges and their ten entries; +inf and 0
+ * when every product is 0.  The matrix-core paths keep their bounds for ranges inside
+ * [6.1e-5, 65504] (see the conventions above).  range: device, 2 floats, overwritten.            */
+kan_status kan_vq_coef_range(const kan_vq_layer* L, float* range, void* stream);
+
 /* Compression side (section 4.2, steps 1 and 3 of the post-training procedure; learning the
  * codebook itself, step 2, is not part of this library).  For every edge e = i*out + j of a dense
  * layer coef[in][out][10]:
@@ -210,9 +243,9 @@ kan_status kan_vq_assign(const float* coef, int32_t in, int32_t out, const float
 
 /* Reconstruction quality of an assignment ("R^2 between the original grids and the
  * reconstructed gain * C[idx] + bias", section 4.2): sums[0] = sum of squared residuals,
- * sums[1] = sum of all coefficients, sums[2] = sum of their squares (device, 3 doubles,
- * accumulated in fp64 in a fixed order), from which
- *   R^2 = 1 - sums[0] / (sums[2] - sums[1]^2 / (10 * in * out)).
+ * sums[1] = sum of all coefficients, sums[2] = sum of their squares (accumulated in fp64 in a
+ * fixed order), and sums[3] = R^2 = 1 - sums[0] / (sums[2] - sums[1]^2 / (10 * in * out)),
+ * the total sum of squares taken about the overall mean.  sums: device, 4 doubles.
  * ws: kan_vq_reconstruction_workspace_bytes(in, out) bytes, 256-byte aligned.               */
 size_t kan_vq_reconstruction_workspace_bytes(int32_t in, int32_t out);
 kan_status kan_vq_reconstruction_sums(const float* coef, int32_t in, int32_t out, const float* codebook,

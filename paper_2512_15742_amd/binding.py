@@ -27,7 +27,7 @@ EXPORTS = [
     "kan_vq_debug_gather", "kan_vq_count_bad_indices", "kan_prof_begin", "kan_prof_end",
     "kan_status_string", "kan_vq_planned_kernel", "kan_dense_planned_kernel", "kan_vq_prepared_bytes", "kan_vq_prepare", "kan_pli_basis",
     "kan_vq_assign_workspace_bytes", "kan_vq_assign", "kan_vq_reconstruction_workspace_bytes",
-    "kan_vq_reconstruction_sums",
+    "kan_vq_reconstruction_sums", "kan_basis_window", "kan_vq_coef_range",
 ]
 
 
@@ -67,6 +67,8 @@ def lib():
         L.kan_bspline_basis.restype = I32
         L.kan_pli_basis.argtypes = [P, I64, P, P, P]
         L.kan_pli_basis.restype = I32
+        L.kan_basis_window.argtypes = [P, I64, I32, I32, P, P, P]
+        L.kan_basis_window.restype = I32
         L.kan_vq_workspace_bytes.argtypes = [LP, I32, I32, I64, I32]
         L.kan_vq_workspace_bytes.restype = SZ
         L.kan_vq_layer_forward.argtypes = [LP, P, I64, P, P, SZ, I32, P]
@@ -81,6 +83,8 @@ def lib():
         L.kan_vq_debug_gather.restype = I32
         L.kan_vq_count_bad_indices.argtypes = [LP, P, P]
         L.kan_vq_count_bad_indices.restype = I32
+        L.kan_vq_coef_range.argtypes = [LP, P, P]
+        L.kan_vq_coef_range.restype = I32
         L.kan_prof_begin.argtypes = [I32]
         L.kan_prof_begin.restype = I32
         L.kan_prof_end.argtypes = [C.POINTER(kan_prof_record), I32, C.POINTER(I32)]
@@ -191,6 +195,13 @@ def _desc_array(heads):
     return arr, n_layers, n_heads
 
 
+def _new_output(shape, device):
+    """An output tensor the binding allocates itself starts as NaN, so that an element no kernel
+    wrote cannot pass for a result (callers that time a call pass their own y)."""
+    torch = _torch()
+    return torch.full(shape, float("nan"), dtype=torch.float32, device=device)
+
+
 def _workspace(nbytes, device):
     torch = _torch()
     if nbytes == 0:
@@ -218,6 +229,18 @@ def kan_pli_basis(x):
     return index, w
 
 
+def kan_basis_window(x, rule=KAN_RULE_BSPLINE3, variant=0):
+    """x: float32 CUDA tensor -> (start uint8 same shape, w float32 [..., 4]): the four-entry window
+    of either rule as the kernels form it (variant 1: the routine of the matrix-core kernels)."""
+    torch = _torch()
+    x = x.contiguous()
+    start = torch.empty(x.shape, dtype=torch.uint8, device=x.device)
+    w = torch.empty(tuple(x.shape) + (4,), dtype=torch.float32, device=x.device)
+    _check(lib().kan_basis_window(_ptr(x), x.numel(), int(rule), int(variant), _ptr(start), _ptr(w), _stream_ptr()),
+           "kan_basis_window")
+    return start, w
+
+
 def kan_vq_workspace_bytes(heads, B, path=KAN_PATH_AUTO, strict=True) -> int:
     arr, n_layers, n_heads = _desc_array(heads)
     n = lib().kan_vq_workspace_bytes(arr, n_layers, n_heads, int(B), int(path))
@@ -235,7 +258,7 @@ def kan_vq_layer_forward(layer: VQLayer, x, path=KAN_PATH_AUTO, ws=None, y=None)
     if ws is None:
         ws = _workspace(kan_vq_workspace_bytes([[layer]], B, path, strict=False), x.device)
     if y is None:
-        y = torch.empty((B, layer.n_out), dtype=torch.float32, device=x.device)
+        y = _new_output((B, layer.n_out), x.device)
     st = lib().kan_vq_layer_forward(C.byref(layer.desc), _ptr(x), B, _ptr(y), _ptr(ws),
                                     0 if ws is None else ws.numel(), int(path), _stream_ptr())
     _check(st, "kan_vq_layer_forward")
@@ -251,7 +274,7 @@ def kan_vq_head_forward(heads, x, path=KAN_PATH_AUTO, ws=None, y=None):
     if ws is None:
         ws = _workspace(kan_vq_workspace_bytes(heads, B, path, strict=False), x.device)
     if y is None:
-        y = torch.empty((n_heads, B, heads[0][-1].n_out), dtype=torch.float32, device=x.device)
+        y = _new_output((n_heads, B, heads[0][-1].n_out), x.device)
     st = lib().kan_vq_head_forward(arr, n_layers, n_heads, _ptr(x), B, _ptr(y), _ptr(ws),
                                    0 if ws is None else ws.numel(), int(path), _stream_ptr())
     _check(st, "kan_vq_head_forward")
@@ -274,7 +297,7 @@ def kan_dense_layer_forward(coef, x, ws=None, y=None):
     if ws is None:
         ws = _workspace(kan_dense_workspace_bytes(n_in, n_out, B), x.device)
     if y is None:
-        y = torch.empty((B, n_out), dtype=torch.float32, device=x.device)
+        y = _new_output((B, n_out), x.device)
     st = lib().kan_dense_layer_forward(_ptr(coef), n_in, n_out, g, _ptr(x), B, _ptr(y), _ptr(ws),
                                        0 if ws is None else ws.numel(), _stream_ptr())
     _check(st, "kan_dense_layer_forward")
@@ -296,6 +319,15 @@ def kan_vq_count_bad_indices(layer: VQLayer) -> int:
     cnt = torch.zeros(1, dtype=torch.int32, device=layer.idx.device)
     _check(lib().kan_vq_count_bad_indices(C.byref(layer.desc), _ptr(cnt), _stream_ptr()), "kan_vq_count_bad_indices")
     return int(cnt.item())
+
+
+def kan_vq_coef_range(layer: VQLayer):
+    """(smallest nonzero, largest) magnitude of the fp16 coefficient operand gain * q / gain * C."""
+    torch = _torch()
+    r = torch.empty(2, dtype=torch.float32, device=layer.idx.device)
+    _check(lib().kan_vq_coef_range(C.byref(layer.desc), _ptr(r), _stream_ptr()), "kan_vq_coef_range")
+    lo, hi = (float(v) for v in r.cpu())
+    return lo, hi
 
 
 def kan_vq_prepared_bytes(layer: VQLayer) -> int:
@@ -336,19 +368,17 @@ def kan_vq_assign(coef, codebook, ws=None):
 
 
 def kan_vq_reconstruction_r2(coef, codebook, idx, gain, bias) -> float:
-    """R^2 between the dense grids and gain * C[idx] + bias, from the library's fp64 sums."""
+    """R^2 between the dense grids and gain * C[idx] + bias, as the library computes it (fp64)."""
     torch = _torch()
     n_in, n_out, _ = coef.shape
     K = codebook.shape[0]
     ws = _workspace(lib().kan_vq_reconstruction_workspace_bytes(n_in, n_out), coef.device)
-    sums = torch.empty(3, dtype=torch.float64, device=coef.device)
+    sums = torch.empty(4, dtype=torch.float64, device=coef.device)
     st = lib().kan_vq_reconstruction_sums(_ptr(coef), n_in, n_out, _ptr(codebook), K,
                                           KAN_U16 if idx.dtype == torch.int16 else KAN_U32, _ptr(idx), _ptr(gain),
                                           _ptr(bias), _ptr(sums), _ptr(ws), ws.numel(), _stream_ptr())
     _check(st, "kan_vq_reconstruction_sums")
-    ss_res, s1, s2 = (float(v) for v in sums.cpu())
-    n = 10.0 * n_in * n_out
-    return 1.0 - ss_res / (s2 - s1 * s1 / n)
+    return float(sums[3].item())
 
 
 def kan_vq_planned_kernel(layer: VQLayer, B, n_heads=1, path=KAN_PATH_AUTO) -> str:

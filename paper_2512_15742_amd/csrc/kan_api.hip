@@ -618,6 +618,18 @@ kan_status kan_pli_basis(const float* x, int64_t n, uint8_t* index, float* w, vo
   return run("kan_pli_basis", s, [&] { return launch_pli_basis(x, n, index, w, s); });
 }
 
+kan_status kan_basis_window(const float* x, int64_t n, int32_t rule, int32_t variant, uint8_t* start, float* w,
+                            void* stream) {
+  if (n < 0) return KAN_ERR_SHAPE;
+  if (rule != KAN_RULE_BSPLINE3 && rule != KAN_RULE_PLI2) return KAN_ERR_UNSUPPORTED;
+  if (variant != 0 && variant != 1) return KAN_ERR_UNSUPPORTED;
+  if (n == 0) return KAN_OK;
+  if (!x || !start || !w) return KAN_ERR_NULL;
+  if (!aligned(w, 16) || !aligned(x, 4)) return KAN_ERR_SHAPE;
+  hipStream_t s = (hipStream_t)stream;
+  return run("kan_basis_window", s, [&] { return launch_basis_window(x, n, rule, variant, start, w, s); });
+}
+
 size_t kan_vq_workspace_bytes(const kan_vq_layer* layers, int32_t n_layers, int32_t n_heads, int64_t B,
                               int32_t path) {
   std::vector<LayerPlan> plans;
@@ -925,6 +937,18 @@ kan_status kan_vq_count_bad_indices(const kan_vq_layer* L, uint32_t* count, void
   return run("kan_count_bad", s, [&] {
     return launch_count_bad(L->idx, L->idx_dtype == KAN_U32, (long long)L->in * L->out, (uint32_t)L->K,
                             count, s);
+  });
+}
+
+kan_status kan_vq_coef_range(const kan_vq_layer* L, float* range, void* stream) {
+  kan_status st = validate_layer(L);
+  if (st != KAN_OK) return st;
+  if (!range) return KAN_ERR_NULL;
+  if (!aligned(range, 4)) return KAN_ERR_SHAPE;
+  LayerPtrs h = {L->idx, L->gain, L->bias, L->codebook, L->scale, L->gain_log2_lo, L->gain_log2_step, L->bias_scale};
+  hipStream_t s = (hipStream_t)stream;
+  return run("kan_coef_range", s, [&] {
+    return launch_coef_range(h, L->idx_dtype == KAN_U32, gb_kind_of(*L), code_of(*L), (long long)L->in * L->out, range, s);
   });
 }
 

@@ -246,12 +246,19 @@ __global__ __launch_bounds__(256) void kan_recon_partial_kernel(const float* __r
   }
 }
 
-__global__ void kan_recon_final_kernel(const double* __restrict__ part, int n_blocks, double* __restrict__ sums) {
+// sums[0..2] = the three totals; sums[3] = R^2 = 1 - SS_res / SS_tot with SS_tot taken about the
+// overall mean of the n_coef coefficients (section 4.2).
+__global__ void kan_recon_final_kernel(const double* __restrict__ part, int n_blocks, double n_coef,
+                                       double* __restrict__ sums) {
+  __shared__ double tot[3];
   if (threadIdx.x < 3) {
     double t = 0.0;
     for (int q = 0; q < n_blocks; ++q) t += part[(long long)q * 3 + threadIdx.x];
     sums[threadIdx.x] = t;
+    tot[threadIdx.x] = t;
   }
+  __syncthreads();
+  if (threadIdx.x == 0) sums[3] = 1.0 - tot[0] / (tot[2] - tot[1] * tot[1] / n_coef);
 }
 
 }  // namespace
@@ -291,7 +298,7 @@ hipError_t launch_recon_sums(const float* coef, long long E, const float* cb, in
   else
     hipLaunchKernelGGL(kan_recon_partial_kernel<uint16_t>, dim3(nb), dim3(256), 0, s, coef, cb, (const uint16_t*)idx,
                        gain, bias, E, part);
-  hipLaunchKernelGGL(kan_recon_final_kernel, dim3(1), dim3(64), 0, s, (const double*)part, nb, sums);
+  hipLaunchKernelGGL(kan_recon_final_kernel, dim3(1), dim3(64), 0, s, (const double*)part, nb, (double)E * kG, sums);
   return hipGetLastError();
 }
 

@@ -15,7 +15,10 @@
 // pass: 16-byte loads whose addresses depend on nothing but the block's first edge), puts the
 // per-edge products into LDS and then sums every segment (the edges of one output) with one
 // wave in a fixed order; the per-bucket sums are added by the fixed-order reduction kernel
-// or by the next bucket layer itself: no atomics, reproducible bits.
+// or by the next bucket layer itself: no atomics on this path, reproducible bits.  (The one
+// exception is the side path for non-finite products - a codeword holding Inf or NaN that an
+// edge refers to - which counts and places such products with LDS atomics; finite data never
+// takes it, and its results are non-finite whatever the order.)
 // The bias of an edge needs no lookup at all: the four bases sum to 1 on [-1,1], so
 // sum_i bias_ij is a per-output constant computed at preparation time.
 //

@@ -268,9 +268,13 @@ hipError_t launch_reduce(const float* partial, long long head_stride, long long 
 // ---- debug / parity kernels -------------------------------------------------------
 hipError_t launch_basis(const float* x, long long n, uint8_t* span, float* w, hipStream_t);
 hipError_t launch_pli_basis(const float* x, long long n, uint8_t* index, float* w, hipStream_t);
+hipError_t launch_basis_window(const float* x, long long n, int rule, int fast, uint8_t* start, float* w, hipStream_t);
 hipError_t launch_debug_gather(const LayerPtrs&, int idx_u32, int code, long long edges,
                                uint32_t* ids, float* rows, hipStream_t);
 hipError_t launch_count_bad(const void* idx, int idx_u32, long long edges, uint32_t K,
                             uint32_t* count, hipStream_t);
+// range[0], range[1] = smallest nonzero and largest |gain * codeword entry| over the layer
+hipError_t launch_coef_range(const LayerPtrs&, int idx_u32, int gb_kind, int code, long long edges, float* range,
+                             hipStream_t);
 
 }  // namespace kan

@@ -6,8 +6,12 @@
 //     Y[b][j] = scale * sum_k Phi[b][k] * Chat[k][j] + sum_i bias_ij
 //     Phi[b][(i,m)]  = B_m(x_bi)            (4 nonzeros per 10, App. A.1 family)
 //     Chat[(i,m)][j] = gain_ij * q_ij[m]    (q = Int8 codeword, or the fp32 row)
-// Both operands are fp16 (11-bit significand, same matrix-core rate as bf16, all
-// values lie in [-2, 2]); products accumulate in fp32 in v_smfmac_f32_32x32x32_f16.
+// Both operands are fp16 (11-bit significand, same matrix-core rate as bf16); products
+// accumulate in fp32 in v_smfmac_f32_32x32x32_f16.  The basis operand lies in [0, 1]; the
+// coefficient operand is gain * q with q the Int8 code (|q| <= 127) or gain * C for floating
+// codebooks, so |gain * q| (resp. |gain * C|) must stay below the fp16 maximum 65504, and
+// magnitudes below 6.1e-5 (the fp16 normal range) lose precision: one-pass form to fp16
+// subnormal spacing, split form to the 11 bits of its low part.
 // The per-layer Int8 scale and the bias sum (the bases sum to one) stay in fp32
 // and are applied to the accumulators at the end.
 //

@@ -107,6 +107,20 @@ __global__ __launch_bounds__(256) void kan_pli_basis_kernel(const float* __restr
   }
 }
 
+// The four-entry window (first entry, four weights) of either rule as the forward kernels form
+// it: FAST = false through basis_eval / basis_eval_pli (vector-ALU and bucket kernels), FAST =
+// true through basis_fast (fused kernel, basis preparation of the streaming contraction).
+template <bool FAST>
+__global__ __launch_bounds__(256) void kan_basis_window_kernel(const float* __restrict__ x, long long n, int rule,
+                                                               uint8_t* __restrict__ start, float* __restrict__ w) {
+  for (long long t = (long long)blockIdx.x * blockDim.x + threadIdx.x; t < n;
+       t += (long long)gridDim.x * blockDim.x) {
+    const BasisW b = FAST ? basis_fast(x[t], rule) : basis_eval_rule(x[t], rule);
+    start[t] = (uint8_t)b.span;
+    ((float4*)w)[t] = make_float4(b.w0, b.w1, b.w2, b.w3);
+  }
+}
+
 template <typename IdxT, typename CbT>
 __global__ __launch_bounds__(256) void kan_debug_gather_kernel(const IdxT* __restrict__ idx,
                                                                const CbT* __restrict__ cb, float scale,
@@ -137,6 +151,37 @@ __global__ __launch_bounds__(256) void kan_count_bad_kernel(const IdxT* __restri
 }
 
 __global__ void kan_zero_u32_kernel(uint32_t* p) { *p = 0u; }
+
+// Smallest nonzero and largest magnitude of the fp16 coefficient operand of the matrix-core
+// kernels, gain * q (Int8 codes) or gain * C (floating codebooks), over all edges and entries.
+// Magnitudes are non-negative floats, whose order is that of their bit patterns.
+__global__ void kan_range_init_kernel(uint32_t* r) {
+  r[0] = 0x7f800000u;      // +inf: no nonzero product seen
+  r[1] = 0u;
+}
+template <typename IdxT, typename GbT, typename CbT>
+__global__ __launch_bounds__(256) void kan_coef_range_kernel(const IdxT* __restrict__ idx, const GbT* __restrict__ gain,
+                                                             const CbT* __restrict__ cb, Q8Params qp, long long edges,
+                                                             uint32_t* __restrict__ r) {
+  float lo = __uint_as_float(0x7f800000u), hi = 0.f;
+  for (long long e = (long long)blockIdx.x * blockDim.x + threadIdx.x; e < edges;
+       e += (long long)gridDim.x * blockDim.x) {
+    uint32_t id[1];
+    float g[1];
+    load_idx<IdxT, 1>(idx + e, id);
+    load_gain<GbT, 1>(gain + e, qp, g);
+    float c[kG];
+    fetch_row<CbT>(cb, id[0], g[0], c);
+#pragma unroll
+    for (int m = 0; m < kG; ++m) {
+      const float v = fabsf(c[m]);
+      hi = fmaxf(hi, v);
+      if (v > 0.f) lo = fminf(lo, v);
+    }
+  }
+  atomicMin(r, __float_as_uint(lo));
+  atomicMax(r + 1, __float_as_uint(hi));
+}
 
 inline int blocks_for(long long n, int cap = 65536) {
   long long b = (n + 255) / 256;
@@ -189,6 +234,13 @@ hipError_t launch_pli_basis(const float* x, long long n, uint8_t* index, float* 
   return hipGetLastError();
 }
 
+hipError_t launch_basis_window(const float* x, long long n, int rule, int fast, uint8_t* start, float* w,
+                               hipStream_t s) {
+  if (fast) hipLaunchKernelGGL(kan_basis_window_kernel<true>, dim3(blocks_for(n)), dim3(256), 0, s, x, n, rule, start, w);
+  else hipLaunchKernelGGL(kan_basis_window_kernel<false>, dim3(blocks_for(n)), dim3(256), 0, s, x, n, rule, start, w);
+  return hipGetLastError();
+}
+
 template <typename IdxT>
 void debug_gather_types(const LayerPtrs& h, int code, long long edges, uint32_t* ids, float* rows, dim3 grid,
                         hipStream_t s) {
@@ -213,6 +265,41 @@ hipError_t launch_debug_gather(const LayerPtrs& h, int idx_u32, int code, long l
   else
     debug_gather_types<uint16_t>(h, code, edges, ids, rows, grid, s);
   return hipGetLastError();
+}
+
+namespace {
+template <typename IdxT, typename GbT, typename CbT>
+void coef_range_launch(const LayerPtrs& h, long long edges, float* range, hipStream_t s) {
+  hipLaunchKernelGGL((kan_coef_range_kernel<IdxT, GbT, CbT>), dim3(blocks_for(edges, 2048)), dim3(256), 0, s,
+                     (const IdxT*)h.idx, (const GbT*)h.gain, (const CbT*)h.cb,
+                     Q8Params{h.gain_log2_lo, h.gain_log2_step, h.bias_scale}, edges, (uint32_t*)range);
+}
+template <typename IdxT>
+hipError_t coef_range_types(const LayerPtrs& h, int gb_kind, int code, long long edges, float* range, hipStream_t s) {
+  if (code == kCbI8) {
+    if (gb_kind == kGbQ8) coef_range_launch<IdxT, q8_t, int8_t>(h, edges, range, s);
+    else if (gb_kind == kGbF16) coef_range_launch<IdxT, __half, int8_t>(h, edges, range, s);
+    else coef_range_launch<IdxT, float, int8_t>(h, edges, range, s);
+  } else if (gb_kind == kGbQ8) {
+    return hipErrorInvalidValue;
+  } else if (code == kCbF16) {
+    if (gb_kind == kGbF16) coef_range_launch<IdxT, __half, __half>(h, edges, range, s);
+    else coef_range_launch<IdxT, float, __half>(h, edges, range, s);
+  } else if (code == kCbF32) {
+    if (gb_kind == kGbF16) coef_range_launch<IdxT, __half, float>(h, edges, range, s);
+    else coef_range_launch<IdxT, float, float>(h, edges, range, s);
+  } else {
+    return hipErrorInvalidValue;
+  }
+  return hipGetLastError();
+}
+}  // namespace
+
+hipError_t launch_coef_range(const LayerPtrs& h, int idx_u32, int gb_kind, int code, long long edges, float* range,
+                             hipStream_t s) {
+  hipLaunchKernelGGL(kan_range_init_kernel, dim3(1), dim3(1), 0, s, (uint32_t*)range);
+  return idx_u32 ? coef_range_types<uint32_t>(h, gb_kind, code, edges, range, s)
+                 : coef_range_types<uint16_t>(h, gb_kind, code, edges, range, s);
 }
 
 hipError_t launch_count_bad(const void* idx, int idx_u32, long long edges, uint32_t K, uint32_t* count,

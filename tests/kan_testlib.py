@@ -4,7 +4,7 @@ import numpy as np
 from oracle import kan_oracle as ko
 
 TOL_FP32 = 1e-5     # gather path: relative bound stated for the fp32 kernels
-TOL_MFMA = 2e-2     # bf16 matrix-core path
+TOL_MFMA = 2e-2     # matrix-core path with fp16 operands (the bound stated for 16-bit operands)
 
 
 def gpu_layers(param_list):
@@ -50,3 +50,26 @@ def check_dense_output(y_gpu, x, coef, tol):
     rep = ko.error_report(y_gpu, y_ref, A)
     assert rep["headline"] <= tol and rep["strict"] <= tol, rep
     return rep
+
+
+def check_head_layer_by_layer(kb, Ls, Ps, x, path, tol, rows=None, rule="bspline"):
+    """Every layer of a head at `tol` on identical fp32 inputs: layer l runs through the single-layer
+    entry point on the activation the GPU itself produced for layers 1..l-1 (tanh of its own fp32
+    output), and the oracle evaluates layer l on exactly those fp32 numbers.  Errors of earlier
+    layers therefore do not enter a later layer's figure and no factor for depth is needed.
+    Returns the GPU's final output [B][out] (numpy) of that chain and the worst figure."""
+    import torch
+    a = to_dev(x)
+    worst = 0.0
+    y = None
+    for l, (L, P) in enumerate(zip(Ls, Ps)):
+        y_t = kb.kan_vq_layer_forward(L, a, path=path)
+        y = y_t.cpu().numpy()
+        a_np = a.cpu().numpy()
+        sel = np.arange(a_np.shape[0]) if rows is None else rows
+        y_ref = ko.vq_layer_forward(a_np[sel], **P.as_dict(), rule=rule)
+        rep = ko.error_report(y[sel], y_ref)
+        assert np.isfinite(y).all() and rep["headline"] <= tol, (l, rep)
+        worst = max(worst, rep["headline"])
+        a = torch.tanh(y_t)
+    return y, worst

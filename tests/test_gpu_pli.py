@@ -53,6 +53,25 @@ def test_pli_index_bit_exact_and_weights(kb):
     assert e.numel() == 0 and w2.shape == (0, 2)
 
 
+@pytest.mark.parametrize("variant", [0, 1])
+def test_pli_window_routines_index_bit_exact(kb, variant):
+    """The two-tap rule as the kernels carry it - a window of four entries starting at min(k, 6)
+    with the taps 1 - u, u at offset k - start - from both device routines (variant 1: the one of
+    the fused kernel and of the basis preparation), index bit for bit against the oracle's search."""
+    x = _probe()
+    start, w = kb.kan_basis_window(to_dev(x), rule=kb.KAN_RULE_PLI2, variant=variant)
+    start, w = start.cpu().numpy().astype(np.int64), w.cpu().numpy().astype(np.float64)
+    ref_k = ko.pli_index(x.astype(np.float64)).astype(np.int64)
+    assert np.array_equal(start, np.minimum(ref_k, 6))
+    W = ko.pli_matrix(x.astype(np.float64))                    # [n][10]: weights of all ten entries
+    ref_w = np.take_along_axis(W, start[:, None] + np.arange(4)[None, :], axis=1)
+    assert np.abs(w - ref_w).max() <= (6e-8 if variant == 0 else 1.2e-7)
+    # exactly the two taps are set: the weights outside offsets k - start, k - start + 1 are zero
+    off = ref_k - start
+    mask = (np.arange(4)[None, :] == off[:, None]) | (np.arange(4)[None, :] == off[:, None] + 1)
+    assert (w[~mask] == 0).all()
+
+
 def _check(kb, P, x, path, tol, prepared=False):
     L = kb.VQLayer(P, rule=kb.KAN_RULE_PLI2)
     if prepared:

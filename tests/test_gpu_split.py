@@ -81,6 +81,36 @@ def test_split_keeps_coefficients_and_weights_below_the_fp16_normal_range(kb):
     assert rep["headline"] <= TOL_FP32 and rep["strict"] <= TOL_FP32, rep
 
 
+def test_large_gains_up_to_the_fp16_range_and_the_range_report(kb):
+    """The coefficient operand of the matrix-core kernels is gain * q in fp16: gains of a few
+    hundred with Int8 codes reach the tens of thousands, still below 65504.  kan_vq_coef_range
+    reports the smallest nonzero and the largest such product bit for bit; inside the supported
+    range the split form keeps the fp32 bound and the one-pass form the fp16 bound."""
+    n_in, n_out, B = 200, 130, 150
+    P = synth.make_layer(43, n_in, n_out, 700, cb_dtype="i8", gb_dtype="f32")
+    rng = np.random.default_rng(5)
+    gain = (400.0 * rng.uniform(0.01, 1.0, size=P.gain.shape)).astype(np.float32)
+    gain[3, 5] = 0.0
+    P2 = dataclasses.replace(P, gain=gain)
+    L = kb.VQLayer(P2)
+    lo, hi = kb.kan_vq_coef_range(L)
+    prod = np.abs(gain.astype(np.float32)[:, :, None] * P2.codebook[P2.idx.astype(np.int64)].astype(np.float32))
+    assert hi == float(prod.max()) and lo == float(prod[prod > 0].min())
+    assert 6.1e-5 <= lo and hi < 65504 and hi > 4e4
+    x = synth.make_x(9, B, n_in)
+    y_ref, A = ko.vq_layer_forward(x, **P2.as_dict(), return_abs=True)
+    y = kb.kan_vq_layer_forward(L, to_dev(x), path=kb.KAN_PATH_GATHER).cpu().numpy()
+    rep = ko.error_report(y, y_ref, A)
+    assert rep["headline"] <= TOL_FP32 and rep["strict"] <= TOL_FP32, rep
+    y16 = kb.kan_vq_layer_forward(L, to_dev(x), path=kb.KAN_PATH_MFMA).cpu().numpy()
+    rep16 = ko.error_report(y16, y_ref, A)
+    assert rep16["headline"] <= 2e-2 and rep16["strict"] <= 2e-2, rep16
+    # all-zero gains: nothing nonzero to report
+    Z = kb.VQLayer(dataclasses.replace(P, gain=np.zeros_like(P.gain)))
+    lo0, hi0 = kb.kan_vq_coef_range(Z)
+    assert lo0 == float("inf") and hi0 == 0.0
+
+
 @pytest.mark.parametrize("B", [130, 700])
 def test_split_pli_rule(kb, B):
     P = synth.make_layer(63, 130, 70, 4000, cb_dtype="f16", gb_dtype="f16")
