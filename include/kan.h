@@ -207,6 +207,23 @@ kan_status kan_vq_head_forward(const kan_vq_layer* layers, int32_t n_layers, int
                                const float* x, int64_t B, float* y,
                                void* ws, size_t ws_bytes, int32_t path, void* stream);
 
+/* kan_vq_head_forward for callers that cannot allocate device memory and have no workspace to
+ * hand over: code under HIP graph capture, tight serving loops, harnesses that forbid hipMalloc.
+ * Same arguments, kernels and results as kan_vq_head_forward, but the scratch regions (partial
+ * sums, hidden activations, matrix-core operand records) live in a fixed array of
+ * KAN_STATIC_SCRATCH_BYTES inside the library, one per GPU, which that GPU holds from the moment
+ * the library's code is loaded there until the process ends.  The call allocates and frees
+ * nothing (no hipMalloc / hipFree, no HIP objects); the first call on a device looks up the
+ * array's address there.  Calls whose kan_vq_workspace_bytes exceeds KAN_STATIC_SCRATCH_BYTES are
+ * rejected with KAN_ERR_WORKSPACE and enqueue nothing (small and medium batches fit: the
+ * two-layer 2048 -> 1024 -> 256 head up to batch 64 on either path).  Nothing in the array has to
+ * start at zero - every region is written before it is read within the call -, and it keeps the
+ * last call's contents.  All calls on one GPU share the one array: calls that overlap in time on
+ * the same GPU (different streams, or host threads) race on it; order them on one stream.      */
+#define KAN_STATIC_SCRATCH_BYTES (32 * 1024 * 1024)
+kan_status kan_vq_head_forward_static(const kan_vq_layer* layers, int32_t n_layers, int32_t n_heads,
+                                      const float* x, int64_t B, float* y, int32_t path, void* stream);
+
 /* Debug / parity: what the kernels' own load routines fetch for every edge.
  * ids[e] = zero-extended codeword id of edge e; rows[e][0..9] = dequantised
  * codeword (scale*q or the fp32 row) before gain/bias.  Either output may be

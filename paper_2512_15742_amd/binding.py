@@ -27,8 +27,9 @@ EXPORTS = [
     "kan_vq_debug_gather", "kan_vq_count_bad_indices", "kan_prof_begin", "kan_prof_end",
     "kan_status_string", "kan_vq_planned_kernel", "kan_dense_planned_kernel", "kan_vq_prepared_bytes", "kan_vq_prepare", "kan_pli_basis",
     "kan_vq_assign_workspace_bytes", "kan_vq_assign", "kan_vq_reconstruction_workspace_bytes",
-    "kan_vq_reconstruction_sums", "kan_basis_window", "kan_vq_coef_range",
+    "kan_vq_reconstruction_sums", "kan_basis_window", "kan_vq_coef_range", "kan_vq_head_forward_static",
 ]
+KAN_STATIC_SCRATCH_BYTES = 32 * 1024 * 1024
 
 
 class kan_vq_layer(C.Structure):
@@ -79,6 +80,8 @@ def lib():
         L.kan_dense_layer_forward.restype = I32
         L.kan_vq_head_forward.argtypes = [LP, I32, I32, P, I64, P, P, SZ, I32, P]
         L.kan_vq_head_forward.restype = I32
+        L.kan_vq_head_forward_static.argtypes = [LP, I32, I32, P, I64, P, I32, P]
+        L.kan_vq_head_forward_static.restype = I32
         L.kan_vq_debug_gather.argtypes = [LP, P, P, P]
         L.kan_vq_debug_gather.restype = I32
         L.kan_vq_count_bad_indices.argtypes = [LP, P, P]
@@ -278,6 +281,20 @@ def kan_vq_head_forward(heads, x, path=KAN_PATH_AUTO, ws=None, y=None):
     st = lib().kan_vq_head_forward(arr, n_layers, n_heads, _ptr(x), B, _ptr(y), _ptr(ws),
                                    0 if ws is None else ws.numel(), int(path), _stream_ptr())
     _check(st, "kan_vq_head_forward")
+    return y
+
+
+def kan_vq_head_forward_static(heads, x, path=KAN_PATH_AUTO, y=None):
+    """kan_vq_head_forward on the library's own fixed scratch array: no workspace argument, and the
+    call itself allocates nothing when y is given."""
+    torch = _torch()
+    assert x.dtype == torch.float32 and x.is_contiguous()
+    arr, n_layers, n_heads = _desc_array(heads)
+    B = x.shape[0]
+    if y is None:
+        y = _new_output((n_heads, B, heads[0][-1].n_out), x.device)
+    st = lib().kan_vq_head_forward_static(arr, n_layers, n_heads, _ptr(x), B, _ptr(y), int(path), _stream_ptr())
+    _check(st, "kan_vq_head_forward_static")
     return y
 
 

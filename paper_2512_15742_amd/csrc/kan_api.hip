@@ -9,12 +9,37 @@
 #include <stdio.h>
 #include <string.h>
 
+#include <mutex>
 #include <vector>
 
 #include "kan_internal.hpp"
 
+// Scratch memory of kan_vq_head_forward_static: one array per GPU, held from the moment the
+// library's code is loaded on that GPU until the process ends.  In host code this name is only
+// a handle for hipGetSymbolAddress; the address the kernels get is looked up per device.
+static __device__ __align__(256) unsigned char scratch[KAN_STATIC_SCRATCH_BYTES];
+
 namespace kan {
 namespace {
+
+// Device address of `scratch` on the current device (looked up on the first call per device).
+constexpr int kMaxDevices = 64;
+void* g_scratch_ptr[kMaxDevices] = {};
+std::mutex g_scratch_mutex;
+
+kan_status static_scratch(void** out) {
+  int dev = -1;
+  if (hipGetDevice(&dev) != hipSuccess) return KAN_ERR_LAUNCH;
+  if (dev < 0 || dev >= kMaxDevices) return KAN_ERR_UNSUPPORTED;
+  std::lock_guard<std::mutex> lock(g_scratch_mutex);
+  if (!g_scratch_ptr[dev]) {
+    void* p = nullptr;
+    if (hipGetSymbolAddress(&p, HIP_SYMBOL(scratch)) != hipSuccess || !p) return KAN_ERR_LAUNCH;
+    g_scratch_ptr[dev] = p;
+  }
+  *out = g_scratch_ptr[dev];
+  return KAN_OK;
+}
 
 // ---- per-kernel event timing ---------------------------------------------------
 struct Prof {
@@ -639,8 +664,11 @@ size_t kan_vq_workspace_bytes(const kan_vq_layer* layers, int32_t n_layers, int3
   return wl.total();
 }
 
-kan_status kan_vq_head_forward(const kan_vq_layer* layers, int32_t n_layers, int32_t n_heads, const float* x,
-                               int64_t B, float* y, void* ws, size_t ws_bytes, int32_t path, void* stream) {
+namespace {
+// The forward of a group of heads.  static_ws: take the scratch regions from the library's own
+// per-device array instead of a caller's workspace (ws, ws_bytes are then ignored).
+kan_status head_forward(const kan_vq_layer* layers, int32_t n_layers, int32_t n_heads, const float* x, int64_t B,
+                        float* y, void* ws, size_t ws_bytes, bool static_ws, int32_t path, void* stream) {
   std::vector<LayerPlan> plans;
   WsLayout wl;
   kan_status st = plan_head(layers, n_layers, n_heads, B, path, &plans, &wl);
@@ -649,6 +677,15 @@ kan_status kan_vq_head_forward(const kan_vq_layer* layers, int32_t n_layers, int
   if (!x || !y) return KAN_ERR_NULL;
   if (!aligned(x, 4) || !aligned(y, 4)) return KAN_ERR_SHAPE;
   const size_t need = wl.total();
+  if (static_ws) {
+    if (need > (size_t)KAN_STATIC_SCRATCH_BYTES) return KAN_ERR_WORKSPACE;     // beyond the fixed array: use kan_vq_head_forward
+    ws = nullptr;
+    ws_bytes = KAN_STATIC_SCRATCH_BYTES;
+    if (need > 0) {
+      st = static_scratch(&ws);
+      if (st != KAN_OK) return st;
+    }
+  }
   if (need > 0 && (!ws || !aligned(ws, 256) || ws_bytes < need)) return KAN_ERR_WORKSPACE;
 
   hipStream_t s = (hipStream_t)stream;
@@ -780,6 +817,17 @@ kan_status kan_vq_head_forward(const kan_vq_layer* layers, int32_t n_layers, int
     }
   }
   return KAN_OK;
+}
+}  // namespace
+
+kan_status kan_vq_head_forward(const kan_vq_layer* layers, int32_t n_layers, int32_t n_heads, const float* x,
+                               int64_t B, float* y, void* ws, size_t ws_bytes, int32_t path, void* stream) {
+  return head_forward(layers, n_layers, n_heads, x, B, y, ws, ws_bytes, false, path, stream);
+}
+
+kan_status kan_vq_head_forward_static(const kan_vq_layer* layers, int32_t n_layers, int32_t n_heads, const float* x,
+                                      int64_t B, float* y, int32_t path, void* stream) {
+  return head_forward(layers, n_layers, n_heads, x, B, y, nullptr, 0, true, path, stream);
 }
 
 kan_status kan_vq_layer_forward(const kan_vq_layer* L, const float* x, int64_t B, float* y, void* ws,
