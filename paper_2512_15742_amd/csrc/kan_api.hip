@@ -179,7 +179,7 @@ constexpr int kMfmaRowsStep = kMfmaPrepRows;   // chunk boundaries coincide with
 constexpr int kMfmaTargetWorkgroups = 512;
 constexpr int kMfmaMinRows = 64;
 constexpr int64_t kHalfFusedMaxBatch = 64;   // fp16 path: fused kernel up to here, streaming contraction above
-constexpr int64_t kHalfFusedMaxSamples = 1024;   // ... and only below this many (sample, head) pairs per group
+constexpr int kFusedMinWgsPerHead = 24;      // fused kernel, several heads: workgroups per head (L2 residency of the codebooks)
 // Precise path: from this batch on the split-operand matrix-core form.  Its time hardly depends on
 // the batch below 128 (config 3: 96 us, config 2: 44 us) while the fused fp32 kernel's doubles with
 // its second tile of 64 samples (config 3: 97 us at 64, 113 at 80; config 2: 33 and 57).
@@ -248,6 +248,14 @@ LayerPlan plan_fused(int n_in, int n_out, int64_t B, int n_heads, int idx_u32, i
   // on the fp16 path, 96.7 -> 82.9 us on the precise path; 32-sample tiles are better off with two)
   const long long target = p.cfg.bt == 64 ? kTargetWorkgroups / 2 : kTargetWorkgroups;
   long long chunks = (target + base - 1) / (base > 0 ? base : 1);
+  // Several heads in one launch: the kernel gives every XCD a contiguous run of heads, and an XCD
+  // (64 resident workgroups) should work on at most two or three heads at a time so that their
+  // codebooks stay in its L2: at least kFusedMinWgsPerHead workgroups per head.
+  if (n_heads > 1) {
+    const long long per_head = (long long)p.n_jt * p.n_bt;
+    const long long want = (kFusedMinWgsPerHead + per_head - 1) / per_head;
+    if (chunks < want) chunks = want;
+  }
   const long long max_by_rows = n_in / 16;                                   // at least two steps each
   const long long max_by_bytes = (long long)n_in * bytes_per_edge / (4 * B);
   if (chunks > max_by_rows) chunks = max_by_rows;
@@ -304,10 +312,9 @@ LayerPlan plan_vq(const kan_vq_layer& L, int64_t B, int n_heads, bool vec_ok, bo
   const int u32 = L.idx_dtype == KAN_U32, gbk = gb_kind_of(L);
   const bool half_path = path == KAN_PATH_MFMA || (path == KAN_PATH_AUTO && B >= kAutoMfmaBatch);
   if (half_path) {
-    // the fused kernel gathers every codeword once per batch tile and head; with many heads in
-    // a group the dequantise-once preparation + streaming contraction is ahead already at batch 64
-    if (B <= kHalfFusedMaxBatch && (long long)B * n_heads < kHalfFusedMaxSamples)
-      return plan_fused(L.in, L.out, B, n_heads, u32, gbk, code, false);
+    // one batch tile: every edge is needed once, so nothing is staged in memory (the streaming
+    // path would write 20 bytes per edge and read them back for no reuse)
+    if (B <= kHalfFusedMaxBatch) return plan_fused(L.in, L.out, B, n_heads, u32, gbk, code, false);
     return plan_mfma(L.in, L.out, B, n_heads, u32, gbk, code);
   }
   if (prepared_ok && B <= kBucketMaxBatch) return plan_bucket(L, B, n_heads);

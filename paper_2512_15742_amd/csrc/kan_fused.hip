@@ -38,7 +38,7 @@ constexpr int LDH = 88;                // fp16 tile: row stride in halves (176 B
 constexpr int LDF = 84;                // fp32 tile: row stride in floats (336 B); row = [h][s][m]
 
 template <typename IdxT, typename GbT, typename CbT, bool F32, int MBLK>
-__global__ __launch_bounds__(kThreads) void kan_fused_kernel(const FusedArgs a) {
+__global__ __launch_bounds__(kThreads, 2) void kan_fused_kernel(const FusedArgs a) {
   constexpr int BM = 32 * MBLK;
   constexpr int NPAIR = MBLK;          // (sample, input) pairs per thread and step
   constexpr int kTileBytes = F32 ? BM * LDF * 4 : BM * LDH * 2;
@@ -50,8 +50,24 @@ __global__ __launch_bounds__(kThreads) void kan_fused_kernel(const FusedArgs a) 
   const int tid = threadIdx.x;
   const int lane = tid & 63, wave = tid >> 6;
   const int ln = lane & 31, lh = lane >> 5;
-  const int head = blockIdx.z, chunk = blockIdx.y;
-  const int jt = blockIdx.x % a.n_jt, b0 = (blockIdx.x / a.n_jt) * (32 * MBLK);
+  // Which (head, chunk of inputs, tile) this workgroup takes.  Workgroups go to the eight XCDs in
+  // turn (linear index mod 8) and every XCD has its own 4 MB L2.  With several heads in a launch
+  // the plain order would put workgroups of every resident head on every XCD, and the codebooks
+  // of all of them (655 KB each as Int8) would compete for each L2.  Instead the list of work
+  // items, sorted by head, is cut into eight contiguous runs, one per XCD, taken in order: an XCD
+  // then works on two or three heads at a time and a codebook enters one L2 only.
+  int head = blockIdx.z, chunk = blockIdx.y, tile = blockIdx.x;
+  if (gridDim.z > 1) {
+    const unsigned T = gridDim.x, C = gridDim.y, W = T * C * gridDim.z;
+    const unsigned L = blockIdx.x + T * (blockIdx.y + C * blockIdx.z);
+    const unsigned xcd = L & 7u, m = L >> 3, q = W >> 3, r = W & 7u;
+    const unsigned item = xcd * q + min(xcd, r) + m;          // XCD x owns q + (x < r) items
+    head = (int)(item / (T * C));
+    const unsigned rem = item % (T * C);
+    chunk = (int)(rem / T);
+    tile = (int)(rem % T);
+  }
+  const int jt = tile % a.n_jt, b0 = (tile / a.n_jt) * (32 * MBLK);
   const int n_in = a.n_in, n_out = a.n_out, B = a.B;
   const int i_begin = chunk * a.rows_per_chunk;
   const int i_end = min(n_in, i_begin + a.rows_per_chunk);
@@ -111,7 +127,9 @@ __global__ __launch_bounds__(kThreads) void kan_fused_kernel(const FusedArgs a) 
 #pragma unroll
     for (int s = 0; s < 4; ++s) load_row<CbT>(cb, m.id[s], rows[s]);
   };
-  auto dequant_step = [&](const RawRow<CbT> (&rows)[4], const Meta& m, Frag& out) {
+  auto dequant_step = [&](RawRow<CbT> (&rows)[4], const Meta& m, Frag& out) {
+#pragma unroll
+    for (int s = 0; s < 4; ++s) align_row<CbT>(rows[s], row_odd<CbT>(cb, m.id[s]));
     if constexpr (F32) {
 #pragma unroll
       for (int s = 0; s < 4; ++s) dequant_row_f32<CbT>(rows[s], m.g[s], out.f[s]);
@@ -155,11 +173,18 @@ __global__ __launch_bounds__(kThreads) void kan_fused_kernel(const FusedArgs a) 
       gb.b[s] = ok ? bv[0] : 0.f;
     }
   };
-  auto gather_ids = [&](const Ids& m, RawRow<CbT> (&rows)[4]) {
+  // (the alignment bits of a step's four rows travel in one word beside the rows)
+  auto gather_ids = [&](const Ids& m, RawRow<CbT> (&rows)[4], uint32_t& odd) {
+    odd = 0u;
 #pragma unroll
-    for (int s = 0; s < 4; ++s) load_row<CbT>(cb, m.id[s], rows[s]);
+    for (int s = 0; s < 4; ++s) {
+      load_row<CbT>(cb, m.id[s], rows[s]);
+      odd |= row_odd<CbT>(cb, m.id[s]) << s;
+    }
   };
-  auto dequant_deep = [&](const RawRow<CbT> (&rows)[4], const GainBias& m, Frag& out) {
+  auto dequant_deep = [&](RawRow<CbT> (&rows)[4], const uint32_t odd, const GainBias& m, Frag& out) {
+#pragma unroll
+    for (int s = 0; s < 4; ++s) align_row<CbT>(rows[s], (odd >> s) & 1u);
     if constexpr (F32) {
 #pragma unroll
       for (int s = 0; s < 4; ++s) dequant_row_f32<CbT>(rows[s], m.g[s], out.f[s]);
@@ -263,6 +288,7 @@ __global__ __launch_bounds__(kThreads) void kan_fused_kernel(const FusedArgs a) 
     Ids ids[4];
     GainBias gbr[8];
     RawRow<CbT> rows[RD][4];
+    uint32_t odd[RD];
     float uv[4][NPAIR];
     Frag frag[2];
   #pragma unroll
@@ -270,17 +296,17 @@ __global__ __launch_bounds__(kThreads) void kan_fused_kernel(const FusedArgs a) 
   #pragma unroll
     for (int q = 0; q < 4; ++q) load_u(q, uv[q]);
   #pragma unroll
-    for (int q = 0; q < RD; ++q) gather_ids(ids[q & 3], rows[q]);
+    for (int q = 0; q < RD; ++q) gather_ids(ids[q & 3], rows[q], odd[q]);
   #pragma unroll
     for (int q = RD; q < RD + 2; ++q) load_meta_deep(q, ids[q & 3], gbr[q & 7]);     // (the gathers above have read slots 0, 1)
-    dequant_deep(rows[0], gbr[0], frag[0]);
+    dequant_deep(rows[0], odd[0], gbr[0], frag[0]);
     gen_phi(uv[0], sTile[0]);
 
     auto step = [&](auto T, int k) {
       constexpr int t = decltype(T)::value;          // k mod 8
       __syncthreads();     // tile k is complete; every wave is done reading tile k-1
-      dequant_deep(rows[(t + 1) % RD], gbr[(t + 1) & 7], frag[(t + 1) & 1]);       // step k+1 fragments
-      gather_ids(ids[(t + RD) & 3], rows[t % RD]);                                 // step k+RD codewords
+      dequant_deep(rows[(t + 1) % RD], odd[(t + 1) % RD], gbr[(t + 1) & 7], frag[(t + 1) & 1]);   // step k+1 fragments
+      gather_ids(ids[(t + RD) & 3], rows[t % RD], odd[t % RD]);                    // step k+RD codewords
       load_meta_deep(k + RD + 2, ids[(t + RD + 2) & 3], gbr[(t + RD + 2) & 7]);          // step k+RD+2 metadata
       mfma_step(sTile[t & 1], frag[t & 1]);
       gen_phi(uv[(t + 1) & 3], sTile[(t + 1) & 1]);                                 // step k+1 basis tile

@@ -135,6 +135,8 @@ __device__ __forceinline__ void prep_coef_block(const LayerPtrs& hp, uint4* __re
 #pragma unroll
     for (int r = 0; r < 8; ++r) load_row<CbT>(cb, id[r], raw[r]);
 #pragma unroll
+    for (int r = 0; r < 8; ++r) align_row<CbT>(raw[r], row_odd<CbT>(cb, id[r]));
+#pragma unroll
     for (int q = 0; q < 2; ++q) {
       const long long S = 2 * wh + q;
       uint32_t tail[4], tail_lo[4];

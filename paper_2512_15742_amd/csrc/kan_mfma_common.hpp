@@ -33,25 +33,73 @@ template <> struct RawRow<int8_t> { uint32_t a, b, d; };
 template <> struct RawRow<__half> { uint32_t w[kG / 2]; };
 template <> struct RawRow<float> { float c[kG]; };
 
+// One row = one to three load instructions per lane, as wide as they come: every vector-memory
+// instruction of a divergent gather costs the CU's address and tag pipeline a slot per lane,
+// whether it brings 2 bytes or 16.  The loads are raw buffer loads (exact widths whatever the
+// alignment of the row; the resource spans the address space from the codebook's base, so no
+// range check cuts a row short):
+//   Int8 (10 bytes, 2-byte aligned): the three aligned dwords that hold the row, shifted into
+//     place (0 or 2 bytes).  Every dword touched holds at least one byte of the row, so the load
+//     never leaves the pages of the codebook, whatever its size.
+//   fp16 (20 bytes, 4-byte aligned): 16 + 4.   fp32 (40 bytes, 8-byte aligned): 16 + 16 + 8.
+constexpr int kRowBufferFlags = 0x00020000;       // buffer resource word 3: raw 32-bit data, no swizzle
+
+// For Int8 rows the shift is applied when the row is used (align_row), so that a row in flight
+// costs three registers and one bit: row_odd() is that bit, and callers keep the bits of the
+// rows of a step in one word.
+template <typename CbT>
+__device__ __forceinline__ uint32_t row_odd(const CbT* cb, uint32_t id) {
+  if constexpr (sizeof(CbT) == 1) return ((uint32_t)((uintptr_t)cb >> 1) + id) & 1u;    // (base + 10 id) / 2 mod 2
+  else return 0u;
+}
+
 template <typename CbT>
 __device__ __forceinline__ void load_row(const CbT* cb, uint32_t id, RawRow<CbT>& r) {
+  typedef unsigned int bu32x2 __attribute__((ext_vector_type(2)));
+  typedef unsigned int bu32x3 __attribute__((ext_vector_type(3)));
+  typedef unsigned int bu32x4 __attribute__((ext_vector_type(4)));
   if constexpr (sizeof(CbT) == 1) {
-    const uint8_t* p = (const uint8_t*)cb + (size_t)id * kG;
-    r.a = ld_u32_any(p);
-    r.b = ld_u32_any(p + 4);
-    r.d = ld_u16_any(p + 8);
+    const uint32_t mis = (uint32_t)(uintptr_t)cb & 3u;           // 0 or 2: the base within its dword
+    const __amdgpu_buffer_rsrc_t rs =
+        __builtin_amdgcn_make_buffer_rsrc((void*)((uintptr_t)cb - mis), 0, 0x7fffffff, kRowBufferFlags);
+    const uint32_t at = id * (uint32_t)kG + mis;                 // byte offset of the row from the aligned base
+    const bu32x3 v = __builtin_amdgcn_raw_buffer_load_b96(rs, (int)(at & ~3u), 0, 0);
+    r.a = v.x;                                                   // still to be shifted: align_row
+    r.b = v.y;
+    r.d = v.z;
   } else if constexpr (sizeof(CbT) == 2) {
-    const uint32_t* p = (const uint32_t*)((const uint16_t*)cb + (size_t)id * kG);   // 4-byte aligned
-#pragma unroll
-    for (int m = 0; m < kG / 2; ++m) r.w[m] = p[m];
+    const __amdgpu_buffer_rsrc_t rs = __builtin_amdgcn_make_buffer_rsrc((void*)cb, 0, 0x7fffffff, kRowBufferFlags);
+    const int at = (int)(id * (uint32_t)(kG * 2));
+    const bu32x4 v = __builtin_amdgcn_raw_buffer_load_b128(rs, at, 0, 0);
+    r.w[0] = v.x;
+    r.w[1] = v.y;
+    r.w[2] = v.z;
+    r.w[3] = v.w;
+    r.w[4] = __builtin_amdgcn_raw_buffer_load_b32(rs, at, 16, 0);
   } else {
-    const float2* p = (const float2*)(cb + (size_t)id * kG);
-#pragma unroll
-    for (int m = 0; m < kG / 2; ++m) {
-      const float2 v = p[m];
-      r.c[2 * m] = v.x;
-      r.c[2 * m + 1] = v.y;
-    }
+    const __amdgpu_buffer_rsrc_t rs = __builtin_amdgcn_make_buffer_rsrc((void*)cb, 0, 0x7fffffff, kRowBufferFlags);
+    const int at = (int)(id * (uint32_t)(kG * 4));
+    const bu32x4 v0 = __builtin_amdgcn_raw_buffer_load_b128(rs, at, 0, 0);
+    const bu32x4 v1 = __builtin_amdgcn_raw_buffer_load_b128(rs, at, 16, 0);
+    const bu32x2 v2 = __builtin_amdgcn_raw_buffer_load_b64(rs, at, 32, 0);
+    r.c[0] = __uint_as_float(v0.x); r.c[1] = __uint_as_float(v0.y); r.c[2] = __uint_as_float(v0.z); r.c[3] = __uint_as_float(v0.w);
+    r.c[4] = __uint_as_float(v1.x); r.c[5] = __uint_as_float(v1.y); r.c[6] = __uint_as_float(v1.z); r.c[7] = __uint_as_float(v1.w);
+    r.c[8] = __uint_as_float(v2.x); r.c[9] = __uint_as_float(v2.y);
+  }
+}
+
+// The row as it lies in memory: bytes 0..3 in a, 4..7 in b, 8..9 in the low half of d (odd: the
+// row starts in the upper half of its first dword).  No-op for the other row types.
+template <typename CbT>
+__device__ __forceinline__ void align_row(RawRow<CbT>& r, uint32_t odd) {
+  if constexpr (sizeof(CbT) == 1) {
+    const uint32_t sh = odd * 2u;
+    const uint32_t a = __builtin_amdgcn_alignbyte(r.b, r.a, sh);
+    const uint32_t b = __builtin_amdgcn_alignbyte(r.d, r.b, sh);
+    const uint32_t d = __builtin_amdgcn_alignbyte(0u, r.d, sh) & 0xffffu;
+    r.a = a;
+    r.b = b;
+    r.d = d;
   }
 }
 
