@@ -2,14 +2,20 @@
 """Benchmark of the VQ-KAN forward pass on one MI355X.
 
     python bench.py [--gpus 1] [--steps K] [--warmup W] [--batch 1024] [--path auto|gather|mfma]
+    python bench.py --config {2,4,5} ...      one of the other configurations as the headline of the line
+    python bench.py --sweep                   every configuration, one JSON line each
 
-Workload: the two-layer Int8 VQ-KAN head 2048 -> 1024 -> 256 (K = 65,536 per
+Headline workload: the two-layer Int8 VQ-KAN head 2048 -> 1024 -> 256 (K = 65,536 per
 layer, uint16 idx, fp16 gain/bias, tanh between layers), synthetic seeded
 parameters and inputs resident in HBM before the timed region.  A step is one
 forward of the whole head over one batch.  The headline `value` is edge
 evaluations per second at --batch (default 1024); the same line also carries
 the batch-1 figures (edge-evals/s and metadata-stream GB/s), the roofline of
-the dominant kernel, and the CPU oracle timed on a bounded sample.
+the dominant kernel, the L2 hit rate of that kernel's launch (from the counter
+summaries under profiles/), the same head through the dense-coefficient
+baseline, the CPU oracle timed on a bounded sample, and a short leg for each of
+the other configurations (2, 4 cold and warm, 5) with its own roofline, dense
+twin and CPU-oracle figure.  Times are medians over five blocks of --steps steps.
 
 To keep the metadata stream coming from HBM rather than from the 256 MB
 memory-side cache, the steps rotate over enough independent parameter copies
@@ -35,15 +41,46 @@ FLOP_PER_EDGE_EVAL = 8.0        # 4 multiply-adds under the nonzero cubic bases
 FLOP_PER_EDGE_RECON = 20.0      # gain * C[idx] + bias over G = 10, once per launch
 MALL_BYTES = 256 << 20
 
-# HBM bytes per launch of the dominant kernel measured with rocprofv3 --pmc
-# (FETCH_SIZE / WRITE_SIZE runs scaled by a copy kernel of known size); see the
-# summaries under profiles/.  None until such a run exists for the workload.
-MEASURED_TRAFFIC = {
-    # bytes per launch (fetched + written) of the layer-1 launch, the dominant one of a step
-    ("kan_mfma@L1", 1024): int((60.70 + 32.00) * 2**20),
-    ("kan_gather_bt1@L1", 1): int((17.20 + 0.50) * 2**20),
-    ("kan_bucket@L1", 1): int((12.93 + 0.03) * 2**20),
-}
+
+
+def load_profile_facts():
+    """Counter figures stored by earlier rocprofv3 runs of this file: every line "@kv key=value ..."
+    of the summaries under profiles/.  kind=traffic rows carry fetch_bytes / write_bytes per launch
+    (FETCH_SIZE and WRITE_SIZE scaled by a copy of known size), kind=l2 rows tcc_hit / tcc_req.
+    They describe the kernels as they were when the summary was written; the summary names its
+    command, and a row is only used for the very workload, batch and kernel it was taken on."""
+    facts = {}
+    pdir = os.path.join(ROOT, "profiles")
+    for name in sorted(os.listdir(pdir)) if os.path.isdir(pdir) else []:
+        if not name.endswith((".txt", ".md")):
+            continue
+        for line in open(os.path.join(pdir, name), errors="replace"):
+            line = line.strip()
+            if not line.startswith("@kv "):
+                continue
+            kv = dict(tok.split("=", 1) for tok in line[4:].split() if "=" in tok)
+            try:
+                key = (kv["kind"], kv["workload"], int(kv["batch"]), kv["kernel"])
+            except (KeyError, ValueError):
+                continue
+            kv["source"] = "profiles/" + name
+            facts[key] = kv
+    return facts
+
+
+def traffic_of(facts, workload, batch, kernel):
+    kv = facts.get(("traffic", workload, int(batch), kernel))
+    if not kv:
+        return None, None
+    return int(float(kv["fetch_bytes"]) + float(kv["write_bytes"])), kv["source"]
+
+
+def l2_of(facts, workload, batch, kernel):
+    kv = facts.get(("l2", workload, int(batch), kernel))
+    if not kv:
+        return None
+    hit, req = float(kv["tcc_hit"]), float(kv["tcc_req"])
+    return {"kernel": kernel, "tcc_hit": hit, "tcc_req": req, "hit_rate": hit / max(req, 1.0), "source": kv["source"]}
 
 
 def layer_of(kernel_key):
@@ -68,6 +105,10 @@ def parse():
     ap.add_argument("--no-prepare", action="store_true",
                     help="batch <= 4 on the parameters as given (no kan_vq_prepare regrouping)")
     ap.add_argument("--copies", type=int, default=0, help="parameter copies to rotate over (0 = enough to exceed the memory-side cache)")
+    ap.add_argument("--config", type=int, default=3, choices=[2, 3, 4, 5],
+                    help="configuration whose leg is the headline of the line (default 3: the metric's own)")
+    ap.add_argument("--only", action="store_true", help="run the --config leg alone (short runs under a profiler)")
+    ap.add_argument("--variant", default="", help="leg variant: config 4 cold|warm, config 5 i8|f32")
     ap.add_argument("--sweep", action="store_true",
                     help="instead of the headline run, time every benchmark configuration (one JSON line each)")
     ap.add_argument("--probe-copy", action="store_true",
@@ -75,15 +116,22 @@ def parse():
     return ap.parse_args()
 
 
-def time_steps(torch, fn, steps, warmup):
+def time_steps(torch, fn, steps, warmup, blocks=5):
+    """Seconds per step: the median over `blocks` timed blocks of `steps` steps each, every block
+    bracketed by a device synchronisation (a single short block now and then catches a stall)."""
     for s in range(warmup):
         fn(s)
-    torch.cuda.synchronize()
-    t0 = time.perf_counter()
-    for s in range(steps):
-        fn(warmup + s)
-    torch.cuda.synchronize()
-    return (time.perf_counter() - t0) / steps
+    per = []
+    n = warmup
+    for _ in range(blocks):
+        torch.cuda.synchronize()
+        t0 = time.perf_counter()
+        for s in range(steps):
+            fn(n + s)
+        torch.cuda.synchronize()
+        per.append((time.perf_counter() - t0) / steps)
+        n += steps
+    return sorted(per)[len(per) // 2]
 
 
 def kernel_times(kb, torch, fn, steps, warmup):
@@ -98,28 +146,6 @@ def kernel_times(kb, torch, fn, steps, warmup):
     rec = kb.kan_prof_end()
     return {k: {"launches": v["launches"], "avg_us": 1e3 * v["total_ms"] / max(v["launches"], 1)}
             for k, v in rec.items()}
-
-
-def run_batch(kb, torch, synth, copies, B, path, steps, warmup, prepared=False):
-    for cp in copies:
-        for L in cp:
-            L.use_prepared(prepared)
-    x = torch.from_numpy(synth.make_x(3900 + B, B, 2048, "uniform")).cuda()
-    ws_bytes = kb.kan_vq_workspace_bytes([copies[0]], B, path)
-    ws = torch.empty(max(ws_bytes, 256), dtype=torch.uint8, device="cuda")
-    y = torch.empty((1, B, 256), dtype=torch.float32, device="cuda")
-    n = len(copies)
-
-    def cold(s):
-        kb.kan_vq_head_forward([copies[s % n]], x, path=path, ws=ws, y=y)
-
-    def warm(s):
-        kb.kan_vq_head_forward([copies[0]], x, path=path, ws=ws, y=y)
-
-    t_cold = time_steps(torch, cold, steps, warmup)
-    t_warm = time_steps(torch, warm, steps, warmup)
-    kt = kernel_times(kb, torch, cold, min(steps, 100), warmup)
-    return t_cold, t_warm, kt
 
 
 def sweep(kb, torch, synth):
@@ -254,12 +280,232 @@ def sweep(kb, torch, synth):
         vq_rows("config5 4096->4096 K=262144 " + variant, [ps], x, both[1:], 3)
 
 
+MAIN_KERNELS = ("kan_gather", "kan_mfma", "kan_fused", "kan_bucket")
+
+
+def roofline_of(kt, lps, layer_edges, layer_meta, B, facts, workload, extra_param_bytes=0):
+    """Roofline object of the dominant kernel of a step.  One batch tile (B <= 64): every parameter
+    byte is used once, the launch is a stream over its metadata -> HBM.  Above: the contraction
+    dominates -> matrix cores (fp16 operands against the fp16 peak, fp32 operands against the fp32
+    one) or, for the vector-ALU kernels, the fp32 vector peak."""
+    dom = max((k for k in kt if k.startswith(MAIN_KERNELS)), key=lambda k: kt[k]["avg_us"] * kt[k]["launches"])
+    avg_s = kt[dom]["avg_us"] * 1e-6
+    edges = per_launch(layer_edges, dom, lps[dom])
+    family = dom.split("@")[0]
+    is_mfma = family.startswith(("kan_mfma", "kan_fused"))
+    traffic, tsrc = traffic_of(facts, workload, B, dom)
+    if B > 64:
+        flops = edges * (B * FLOP_PER_EDGE_EVAL + FLOP_PER_EDGE_RECON)
+        peak = PEAK_F16_MFMA_TFLOPS if (is_mfma and family != "kan_fused_f32") else PEAK_FP32_VECTOR_TFLOPS
+        roof = {"bound": "mfma" if is_mfma else "alu", "achieved": flops / avg_s / 1e12, "peak": peak, "unit": "TFLOP/s"}
+    else:
+        nbytes = per_launch(layer_meta, dom, lps[dom])
+        roof = {"bound": "hbm", "achieved": nbytes / avg_s / 1e9, "peak": PEAK_HBM_GBPS, "unit": "GB/s"}
+    roof.update({"frac": roof["achieved"] / roof["peak"], "kernel": dom, "avg_launch_us": kt[dom]["avg_us"],
+                 "traffic": traffic, "traffic_source": tsrc})
+    return roof
+
+
+def run_leg(kb, torch, sets, x, path, steps, warmup, layer_edges, layer_meta, facts, workload, cold=True):
+    """Times head calls over `sets` (parameter sets taken in turn: set s % n at step s).
+    layer_edges / layer_meta: per layer, summed over the heads of a call."""
+    B = x.shape[0]
+    heads0 = sets[0]
+    ws_bytes = kb.kan_vq_workspace_bytes(heads0, B, path)
+    ws = torch.empty(max(ws_bytes, 256), dtype=torch.uint8, device="cuda")
+    y = torch.empty((len(heads0), B, heads0[0][-1].n_out), dtype=torch.float32, device="cuda")
+    n = len(sets) if cold else 1
+
+    def step(s):
+        kb.kan_vq_head_forward(sets[s % n], x, path=path, ws=ws, y=y)
+
+    t = time_steps(torch, step, steps, warmup)
+    kt = kernel_times(kb, torch, step, min(steps, 50), warmup)
+    n_prof = min(steps, 50)
+    lps = {k: v["launches"] / n_prof for k, v in kt.items()}
+    ee = sum(layer_edges) * B
+    roof = roofline_of(kt, lps, layer_edges, layer_meta, B, facts, workload)
+    return {"batch": B, "steps": steps, "ms_per_step": 1e3 * t, "edge_evals_per_s": ee / t,
+            "metadata_GBps": sum(layer_meta) / t / 1e9, "parameter_sets_rotated": n,
+            "kernels_avg_us": {k: round(v["avg_us"], 3) for k, v in kt.items()},
+            "kernels_launches_per_step": lps, "kernel_sequence": list(kt.keys()),
+            "planned_kernel_layer1": kb.kan_vq_planned_kernel(heads0[0][0], B, len(heads0), path),
+            "dominant": roof["kernel"], "roofline": roof, "l2_hit_rate": l2_of(facts, workload, B, roof["kernel"]),
+            "workspace_bytes": ws_bytes}
+
+
+def dense_leg(kb, torch, dims, n_heads, x, steps, warmup):
+    """The same shapes through the dense-coefficient baseline (40 bytes per edge): one
+    kan_dense_layer_forward per head and layer, tanh (torch) between the layers.  The time does not
+    depend on the coefficient values: seeded normal draws of the reconstructed coefficients' scale."""
+    B = x.shape[0]
+    gen = torch.Generator(device="cuda").manual_seed(1234)
+    coefs = [[torch.randn((i, o, 10), generator=gen, dtype=torch.float32, device="cuda") * 0.03 for (i, o) in dims]
+             for _ in range(n_heads)]
+    wss = [torch.empty(max(kb.kan_dense_workspace_bytes(i, o, B), 256), dtype=torch.uint8, device="cuda") for (i, o) in dims]
+    ys = [torch.empty((B, o), dtype=torch.float32, device="cuda") for (_, o) in dims]
+
+    def step(s):
+        for h in range(n_heads):
+            a = x
+            for l in range(len(dims)):
+                kb.kan_dense_layer_forward(coefs[h][l], a, ws=wss[l], y=ys[l])
+                a = torch.tanh(ys[l]) if l + 1 < len(dims) else ys[l]
+
+    t = time_steps(torch, step, steps, warmup)
+    edges = n_heads * sum(i * o for i, o in dims)
+    out = {"ms_per_step": 1e3 * t, "edge_evals_per_s": edges * B / t, "coef_bytes": edges * 40,
+           "coef_GBps": edges * 40 / t / 1e9, "kernel_layer1": kb.kan_dense_planned_kernel(dims[0][0], dims[0][1], B),
+           "calls_per_step": n_heads * len(dims)}
+    del coefs
+    torch.cuda.empty_cache()
+    return out
+
+
+def cpu_leg(fn, edge_evals, what, reps=5, budget_s=25.0):
+    """The float64 numpy oracle as it stands, timed on the host: median of up to `reps` runs of a
+    bounded sample (fewer when the budget of CPU seconds is used up)."""
+    try:
+        from threadpoolctl import threadpool_info
+        threads = max([p.get("num_threads", 1) for p in threadpool_info()] or [1])
+    except Exception:
+        threads = os.cpu_count()
+    ts = []
+    t_all = time.perf_counter()
+    for _ in range(reps):
+        t0 = time.perf_counter()
+        fn()
+        ts.append(time.perf_counter() - t0)
+        if time.perf_counter() - t_all > budget_s:
+            break
+    t = sorted(ts)[len(ts) // 2]
+    return {"value": edge_evals / t, "unit": "edge-evals/s", "cores": int(threads), "kind": "oracle",
+            "sample": f"float64 numpy oracle, {what}, median of {len(ts)} ({t:.2f} s each)"}
+
+
+def leg_config2(kb, torch, synth, args, path, facts, with_cpu, B=16):
+    (P,), x = synth.config2(B)
+    n_sets = (MALL_BYTES * 5 // 4) // (P.metadata_bytes + P.codebook.nbytes) + 1
+    sets = [[[kb.VQLayer(P)]] for _ in range(n_sets)]
+    xd = torch.from_numpy(x).cuda()
+    r = run_leg(kb, torch, sets, xd, path, args.steps, args.warmup, [P.edges], [P.metadata_bytes], facts, "config2")
+    r["workload"] = f"config 2: layer 2048->512, fp32 codebook K=65536, uint16 idx, fp32 gain/bias, batch {B}"
+    if not args.only:
+        r["dense_baseline"] = dense_leg(kb, torch, [(2048, 512)], 1, xd, args.steps, args.warmup)
+    if with_cpu:
+        from oracle import kan_oracle as ko
+        r["cpu_baseline"] = cpu_leg(lambda: ko.vq_layer_forward(x, **P.as_dict()), P.edges * B, f"the whole layer, batch {B}")
+    return r
+
+
+def leg_config4(kb, torch, synth, args, path, facts, with_cpu, cold=True, n_heads=50, B=64):
+    heads_p, x = synth.config4(n_heads, B)
+    # cold: two full parameter sets taken in turn (2 x 224 MB, more than the memory-side cache holds)
+    sets = [[[kb.VQLayer(p) for p in ps] for ps in heads_p] for _ in range(2 if cold else 1)]
+    xd = torch.from_numpy(x).cuda()
+    edges = [sum(ps[l].edges for ps in heads_p) for l in range(2)]
+    meta = [sum(ps[l].metadata_bytes for ps in heads_p) for l in range(2)]
+    r = run_leg(kb, torch, sets, xd, path, args.steps, args.warmup, edges, meta, facts, "config4", cold=cold)
+    r["workload"] = (f"config 4: {n_heads} Int8 heads 2048->256->21 on one shared batch of {B}, one grouped launch per layer, "
+                     + ("two parameter sets in turn (cold)" if cold else "one parameter set (cache-warm)"))
+    r["codebook_bytes"] = sum(p.codebook.nbytes for ps in heads_p for p in ps)
+    if not args.only and cold:
+        r["dense_baseline"] = dense_leg(kb, torch, [(2048, 256), (256, 21)], n_heads, xd, max(args.steps // 4, 3), 2)
+    if with_cpu and cold:
+        from oracle import kan_oracle as ko
+        hs = heads_p[:8]
+        r["cpu_baseline"] = cpu_leg(lambda: [ko.vq_head_forward(x, [p.as_dict() for p in ps]) for ps in hs],
+                                    sum(p.edges for ps in hs for p in ps) * B, f"8 of the {n_heads} heads, whole batch of {B}")
+    return r
+
+
+def leg_config5(kb, torch, synth, args, path, facts, with_cpu, variant="i8", B=8192):
+    (P,), x = synth.config5(variant, B=B)
+    sets = [[[kb.VQLayer(P)]]]
+    xd = torch.from_numpy(x).cuda()
+    steps = max(args.steps // 10, 5)
+    r = run_leg(kb, torch, sets, xd, path, steps, min(args.warmup, 3), [P.edges], [P.metadata_bytes], facts, "config5_" + variant)
+    r["workload"] = (f"config 5: layer 4096->4096, K=262144 {'Int8' if variant == 'i8' else 'fp32'} codebook, uint32 idx, "
+                     f"{'fp16' if variant == 'i8' else 'fp32'} gain/bias, batch {B}")
+    if not args.only:
+        r["dense_baseline"] = dense_leg(kb, torch, [(4096, 4096)], 1, xd, steps, 2)
+    if with_cpu:
+        from oracle import kan_oracle as ko
+        rows = 64
+        r["cpu_baseline"] = cpu_leg(lambda: ko.vq_layer_forward(x[:rows], **P.as_dict()), P.edges * rows,
+                                    f"the layer on {rows} of the {B} batch rows", reps=3)
+    return r
+
+
+def config3_legs(kb, torch, synth, args, path, facts, with_cpu):
+    """The metric's own configuration: batch args.batch and batch 1 (prepared and as given), parameters
+    rotated over enough copies to exceed the memory-side cache."""
+    layers = synth.config3_layers()
+    edges = [p.edges for p in layers]
+    meta = [p.metadata_bytes for p in layers]
+    param_bytes = sum(meta) + sum(p.codebook.nbytes for p in layers)
+    n_copies = args.copies or (MALL_BYTES * 5 // 4 + param_bytes - 1) // param_bytes
+    copies = [[kb.VQLayer(p) for p in layers] for _ in range(n_copies)]
+    sets = [[cp] for cp in copies]
+    torch.cuda.synchronize()
+    t0 = time.perf_counter()
+    for cp in copies:
+        for L in cp:
+            L.prepare()
+    torch.cuda.synchronize()
+    prepare_ms_per_head = 1e3 * (time.perf_counter() - t0) / len(copies)
+
+    results = {}
+    batches = sorted({1, args.batch}) if not args.only else [args.batch]
+    legs = [(b, b <= 4 and not args.no_prepare) for b in batches]
+    if not args.no_prepare and not args.only:
+        legs.append((1, False))
+    for B, prepared in legs:
+        for cp in copies:
+            for L in cp:
+                L.use_prepared(prepared)
+        steps = args.steps if B > 1 else max(args.steps, 200)
+        x = torch.from_numpy(synth.make_x(3900 + B, B, 2048, "uniform")).cuda()
+        r = run_leg(kb, torch, sets, x, path, steps, args.warmup, edges, meta, facts, "config3")
+        warm = run_leg(kb, torch, sets, x, path, steps, args.warmup, edges, meta, facts, "config3", cold=False) \
+            if not args.only else None
+        r["prepared_layers"] = bool(prepared)
+        if warm:
+            r["ms_per_step_cache_warm"] = warm["ms_per_step"]
+            r["edge_evals_per_s_cache_warm"] = warm["edge_evals_per_s"]
+        key = B if (prepared or B > 4 or args.no_prepare) else "1_unprepared"
+        results[key] = r
+    for cp in copies:
+        for L in cp:
+            L.use_prepared(False)
+    B = args.batch
+    r = results[B]
+    r["workload"] = (f"config 3: two-layer Int8 VQ-KAN head 2048->1024->256, K=65536 per layer, uint16 idx, "
+                     f"fp16 gain/bias, tanh between layers, batch {B}")
+    if not args.only:
+        x = torch.from_numpy(synth.make_x(3900 + B, B, 2048, "uniform")).cuda()
+        r["dense_baseline"] = dense_leg(kb, torch, [(2048, 1024), (1024, 256)], 1, x, max(args.steps // 2, 5), 3)
+    if with_cpu:
+        from oracle import kan_oracle as ko
+        rows = min(B, 1024)
+        xs = synth.make_x(3900 + B, B, 2048, "uniform")[:rows]
+        dl = [p.as_dict() for p in layers]
+        ko.vq_head_forward(xs[:8], dl)                       # warm-up (untimed)
+        r["cpu_baseline"] = cpu_leg(lambda: ko.vq_head_forward(xs, dl), sum(edges) * rows,
+                                    f"whole head on {rows} of the {B} batch rows", reps=11, budget_s=15.0)
+    return results, {"parameter_copies_rotated": n_copies, "edges": sum(edges), "metadata_bytes": sum(meta),
+                     "prepare_ms_per_head": prepare_ms_per_head}
+
+
+def dtype_of(r):
+    return "f16" if r["roofline"]["kernel"].startswith(("kan_mfma@", "kan_fused_f16")) else "f32"
+
+
 def main():
     args = parse()
     if args.gpus != 1:
         print("bench.py measures one MI355X; runs with --gpus above 1 are not part of this build", file=sys.stderr)
         sys.exit(2)
-    import numpy as np
     import torch
 
     from paper_2512_15742_amd import binding as kb
@@ -272,19 +518,8 @@ def main():
     if args.sweep:
         sweep(kb, torch, synth)
         return
-
-    layers = synth.config3_layers()
-    edges = [p.edges for p in layers]
-    meta = [p.metadata_bytes for p in layers]
-    param_bytes = sum(meta) + sum(p.codebook.nbytes for p in layers)
-    n_copies = args.copies or (MALL_BYTES * 5 // 4 + param_bytes - 1) // param_bytes
-    base = [kb.VQLayer(p) for p in layers]
-    copies = [base]
-    for _ in range(n_copies - 1):           # independent device copies of the same parameters
-        cp = []
-        for p in layers:
-            cp.append(kb.VQLayer(p))
-        copies.append(cp)
+    facts = load_profile_facts()
+    with_cpu = not args.no_cpu_baseline
 
     if args.probe_copy:
         src = torch.empty(256 << 20, dtype=torch.uint8, device="cuda").fill_(1)
@@ -292,116 +527,62 @@ def main():
         for _ in range(3):
             dst.copy_(src)
         torch.cuda.synchronize()
+        del src, dst
 
-    # one-time regrouping of every copy for the small-batch path (kan_vq_prepare), untimed
-    torch.cuda.synchronize()
-    t0 = time.perf_counter()
-    for cp in copies:
-        for L in cp:
-            L.prepare()
-    torch.cuda.synchronize()
-    prepare_ms_per_head = 1e3 * (time.perf_counter() - t0) / len(copies)
+    legs = {}
+    extra = {}
 
-    main_kernels = ("kan_gather", "kan_mfma", "kan_fused", "kan_bucket")
-    results = {}
-    for B, prepared in [(b, b <= 4 and not args.no_prepare) for b in sorted({1, args.batch})] + \
-                       ([] if args.no_prepare else [(1, False)]):
-        steps = args.steps if B > 1 else max(args.steps, 500)
-        t_cold, t_warm, kt = run_batch(kb, torch, synth, copies, B, path, steps, args.warmup, prepared)
-        ee = sum(edges) * B
-        dom = max((k for k in kt if k.startswith(main_kernels)),
-                  key=lambda k: kt[k]["avg_us"] * kt[k]["launches"])
-        key = B if (prepared or B > 4 or args.no_prepare) else "1_unprepared"
-        for cp in copies:
-            for L in cp:
-                L.use_prepared(prepared)
-        results[key] = {
-            "batch": B, "steps": steps, "prepared_layers": bool(prepared),
-            "ms_per_step": 1e3 * t_cold, "edge_evals_per_s": ee / t_cold,
-            "metadata_GBps": sum(meta) / t_cold / 1e9,
-            "ms_per_step_cache_warm": 1e3 * t_warm, "edge_evals_per_s_cache_warm": ee / t_warm,
-            "kernels_avg_us": {k: round(v["avg_us"], 3) for k, v in kt.items()},
-            "kernels_launches_per_step": {k: v["launches"] / min(steps, 100) for k, v in kt.items()},
-            "planned_kernel_layer1": kb.kan_vq_planned_kernel(base[0], B, 1, path),
-            "dominant": dom,
-        }
+    def other(n):          # the legs of the other configurations
+        if n == 2:
+            return leg_config2(kb, torch, synth, args, path, facts, with_cpu)
+        if n == 4:
+            cold = args.variant != "warm"
+            r = leg_config4(kb, torch, synth, args, path, facts, with_cpu, cold=cold)
+            if not args.only and cold:
+                w = leg_config4(kb, torch, synth, args, path, facts, False, cold=False)
+                r["cache_warm"] = {k: w[k] for k in ("ms_per_step", "edge_evals_per_s", "metadata_GBps", "kernels_avg_us", "roofline")}
+            return r
+        return leg_config5(kb, torch, synth, args, path, facts, with_cpu, variant=args.variant or "i8")
 
-    B = args.batch
-    r = results[B]
-    dom = r["dominant"]
-    # The dominant kernel is one layer's launch (layer 1 here): `achieved` is priced on that
-    # layer's edges and on that launch's event-timed duration.
-    launches_per_step = r["kernels_launches_per_step"][dom]
-    avg_s = r["kernels_avg_us"][dom] * 1e-6
-    edges_per_launch = per_launch(edges, dom, launches_per_step)
-    family = dom.split("@")[0]
-    is_mfma = family.startswith(("kan_mfma", "kan_fused"))
-    if B >= 16:
-        # compute-bound regime (the metadata stream stops being the limit near B = 12-20)
-        flops = edges_per_launch * (B * FLOP_PER_EDGE_EVAL + FLOP_PER_EDGE_RECON)
-        # fp16 operands price against the fp16/bf16 matrix-core peak, fp32 operands against the fp32 one
-        peak = PEAK_F16_MFMA_TFLOPS if (is_mfma and family != "kan_fused_f32") else PEAK_FP32_VECTOR_TFLOPS
-        roof = {"bound": "mfma" if is_mfma else "alu", "achieved": flops / avg_s / 1e12, "peak": peak,
-                "unit": "TFLOP/s", "kernel": dom, "avg_launch_us": r["kernels_avg_us"][dom],
-                "traffic": MEASURED_TRAFFIC.get((dom, B))}
+    if args.config == 3 or not args.only:
+        res3, extra = config3_legs(kb, torch, synth, args, path, facts, with_cpu)
+        legs[3] = res3[args.batch]
     else:
-        nbytes = per_launch(meta, dom, launches_per_step)
-        roof = {"bound": "hbm", "achieved": nbytes / avg_s / 1e9, "peak": PEAK_HBM_GBPS, "unit": "GB/s",
-                "kernel": dom, "avg_launch_us": r["kernels_avg_us"][dom],
-                "traffic": MEASURED_TRAFFIC.get((dom, B))}
-    roof["frac"] = roof["achieved"] / roof["peak"]
+        res3 = {}
+    if args.only:
+        if args.config != 3:
+            legs[args.config] = other(args.config)
+    else:
+        for n in (2, 4, 5):
+            torch.cuda.empty_cache()
+            legs[n] = other(n)
 
-    r1 = results[1]
-    dom1 = r1["dominant"]
-    l1 = r1["kernels_launches_per_step"][dom1]
-    roof1 = {"bound": "hbm", "achieved": per_launch(meta, dom1, l1) / (r1["kernels_avg_us"][dom1] * 1e-6) / 1e9,
-             "peak": PEAK_HBM_GBPS, "unit": "GB/s", "kernel": dom1, "avg_launch_us": r1["kernels_avg_us"][dom1],
-             "traffic": MEASURED_TRAFFIC.get((dom1, 1))}
-    roof1["frac"] = roof1["achieved"] / roof1["peak"]
-    r1["roofline"] = roof1
-
-    cpu = None
-    if not args.no_cpu_baseline:
-        from oracle import kan_oracle as ko
-        try:
-            from threadpoolctl import threadpool_info
-            threads = max([p.get("num_threads", 1) for p in threadpool_info()] or [1])
-        except Exception:
-            threads = os.cpu_count()
-        # a bounded sample: the whole head on the first 1024 rows of the batch (the whole batch of
-        # the default run), eleven times: about 10 s of CPU work on a 16-thread host
-        rows = min(B, 1024)
-        xs = synth.make_x(3900 + B, B, 2048, "uniform")[:rows]
-        dl = [p.as_dict() for p in layers]
-        ko.vq_head_forward(xs[:8], dl)                       # warm-up (untimed)
-        ts = []
-        for _ in range(11):
-            t0 = time.perf_counter()
-            ko.vq_head_forward(xs, dl)
-            ts.append(time.perf_counter() - t0)
-        t = sorted(ts)[5]
-        cpu = {"value": sum(edges) * rows / t, "unit": "edge-evals/s", "cores": int(threads), "kind": "oracle",
-               "sample": f"float64 numpy oracle, whole head on {rows} of the {B} batch rows, median of 11 ({t:.2f} s each)"}
-
+    r = legs[args.config]
     out = {
-        "metric": "VQ-KAN edge-evals/sec (Int8 K=65536 head 2048->1024->256)",
+        "metric": "VQ-KAN edge-evals/sec (Int8 K=65536 head 2048->1024->256)" if args.config == 3
+                  else f"VQ-KAN edge-evals/sec (configuration {args.config})",
         "value": r["edge_evals_per_s"], "unit": "edge-evals/s",
         "n_gpus": 1, "steps": r["steps"], "warmup": args.warmup, "ms_per_step": r["ms_per_step"],
         "higher_is_better": True, "scaling": "weak", "vs_baseline": None,
-        "dtype": "f16" if roof["kernel"].startswith(("kan_mfma", "kan_fused_f16")) else "f32", "data": "synthetic",
-        "config": {"workload": f"config 3: two-layer Int8 VQ-KAN head 2048->1024->256, K=65536 per layer, "
-                               f"uint16 idx, fp16 gain/bias, tanh between layers, batch {B}",
-                   "batch": B, "path": args.path, "parameter_copies_rotated": n_copies,
-                   "edges": sum(edges), "metadata_bytes": sum(meta)},
+        "dtype": dtype_of(r), "data": "synthetic",
+        "config": dict({"workload": r["workload"], "batch": r["batch"], "path": args.path}, **extra),
         "metadata_GBps": r["metadata_GBps"],
-        "roofline": roof,
-        "cpu_baseline": cpu,
-        "batch1": r1,
-        "batch%d" % B: r,
-        "prepare_ms_per_head": prepare_ms_per_head,
+        "roofline": r["roofline"],
+        "l2_hit_rate": r.get("l2_hit_rate"),
+        "cpu_baseline": r.get("cpu_baseline"),
+        "dense_baseline": r.get("dense_baseline"),
+        "timing": "median of 5 blocks of `steps` steps, each block bracketed by a device synchronisation",
     }
-    if "1_unprepared" in results:
-        out["batch1_unprepared"] = results["1_unprepared"]
+    if 3 in legs:
+        out["batch%d" % args.batch] = legs[3]
+        if 1 in res3:
+            out["batch1"] = res3[1]
+        if "1_unprepared" in res3:
+            out["batch1_unprepared"] = res3["1_unprepared"]
+        out["prepare_ms_per_head"] = extra.get("prepare_ms_per_head")
+    for n in (2, 4, 5):
+        if n in legs:
+            out["config%d" % n] = legs[n]
     print(json.dumps(out))
 
 

@@ -179,6 +179,7 @@ constexpr int kMfmaRowsStep = kMfmaPrepRows;   // chunk boundaries coincide with
 constexpr int kMfmaTargetWorkgroups = 512;
 constexpr int kMfmaMinRows = 64;
 constexpr int64_t kHalfFusedMaxBatch = 64;   // fp16 path: fused kernel up to here, streaming contraction above
+constexpr long long kFusedMinEdgesForResidency = 1 << 17;   // ... for layers of at least this many edges per head
 constexpr int kFusedMinWgsPerHead = 24;      // fused kernel, several heads: workgroups per head (L2 residency of the codebooks)
 // Precise path: from this batch on the split-operand matrix-core form.  Its time hardly depends on
 // the batch below 128 (config 3: 96 us, config 2: 44 us) while the fused fp32 kernel's doubles with
@@ -251,7 +252,9 @@ LayerPlan plan_fused(int n_in, int n_out, int64_t B, int n_heads, int idx_u32, i
   // Several heads in one launch: the kernel gives every XCD a contiguous run of heads, and an XCD
   // (64 resident workgroups) should work on at most two or three heads at a time so that their
   // codebooks stay in its L2: at least kFusedMinWgsPerHead workgroups per head.
-  if (n_heads > 1) {
+  // (layers whose whole codebook traffic is small gain nothing from it: their workgroups would
+  // only get shorter)
+  if (n_heads > 1 && (long long)n_in * n_out >= kFusedMinEdgesForResidency) {
     const long long per_head = (long long)p.n_jt * p.n_bt;
     const long long want = (kFusedMinWgsPerHead + per_head - 1) / per_head;
     if (chunks < want) chunks = want;
