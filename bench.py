@@ -405,7 +405,7 @@ def leg_config4(kb, torch, synth, args, path, facts, with_cpu, cold=True, n_head
     xd = torch.from_numpy(x).cuda()
     edges = [sum(ps[l].edges for ps in heads_p) for l in range(2)]
     meta = [sum(ps[l].metadata_bytes for ps in heads_p) for l in range(2)]
-    r = run_leg(kb, torch, sets, xd, path, args.steps, args.warmup, edges, meta, facts, "config4", cold=cold)
+    r = run_leg(kb, torch, sets, xd, path, args.steps, args.warmup, edges, meta, facts, "config4" if cold else "config4warm", cold=cold)
     r["workload"] = (f"config 4: {n_heads} Int8 heads 2048->256->21 on one shared batch of {B}, one grouped launch per layer, "
                      + ("two parameter sets in turn (cold)" if cold else "one parameter set (cache-warm)"))
     r["codebook_bytes"] = sum(p.codebook.nbytes for ps in heads_p for p in ps)
