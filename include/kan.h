@@ -6,8 +6,8 @@
  *     c_ij   = gain_ij * C[idx_ij] + bias_ij          reconstructed coefficients
  *     phi_ij = sum_m B_{m,3}(x_i) * c_ij[m]            cubic B-spline, G = 10
  *     y_j    = sum_i phi_ij(x_i)
- * with one K x G codebook C per layer (fp32, fp16, or Int8 with value = scale * q:
- * the three codebook precisions of Table 1; Int8 is the one-byte-per-coefficient
+ * with one K x G codebook C per layer (fp32, fp16, block floating point with 8-bit
+ * mantissas, or Int8 with value = scale * q: the codebook precisions of Table 1; Int8 is the one-byte-per-coefficient
  * codebook of sections 4.3 / 5.4), splines on the
  * range [-1, 1] (App. A.1): 7 uniform intervals, 14 knots t_m = -1 + (m-3)*2/7.
  * Inputs are clamped to [-1, 1].  x = +1 belongs to the last interval.
@@ -28,8 +28,8 @@
  *   - Layouts: x[B][in] and y[B][out] row-major fp32; per-edge arrays
  *     idx/gain/bias[in][out] with edge e = i*out + j (j fastest); codebook
  *     [K][10] row-major, unpadded; dense coefficients coef[in][out][10].
- *   - Every array is aligned to its element size; fp32 codebooks to 8 bytes and fp16
- *     codebooks to 4 bytes (rows are read in pairs of entries); else KAN_ERR_SHAPE.
+ *   - Every array is aligned to its element size; fp32 codebooks to 8 bytes, fp16 and
+ *     block-floating-point codebooks to 4 bytes; else KAN_ERR_SHAPE.
  *   - idx values must be < K; they are not checked by the forward calls (use
  *     kan_vq_count_bad_indices).  y must not alias x or the workspace.
  *   - Value range on the matrix cores (KAN_PATH_MFMA at any batch; KAN_PATH_GATHER from
@@ -65,7 +65,8 @@ typedef enum kan_status {
 
 typedef enum kan_dtype {
   KAN_F32 = 0, KAN_F16 = 1, KAN_I8 = 2, KAN_U16 = 3, KAN_U32 = 4,
-  KAN_Q8 = 5   /* gain and bias as one byte each: logarithmic gain code, linear bias code */
+  KAN_Q8 = 5,  /* gain and bias as one byte each: logarithmic gain code, linear bias code */
+  KAN_BFP8 = 6 /* codebook rows in block floating point, 8-bit mantissas: see kan_vq_layer  */
 } kan_dtype;
 
 /* Which arithmetic carries the edge evaluation.
@@ -102,11 +103,11 @@ typedef struct kan_vq_layer {
   int32_t K;             /* codebook entries, >= 1; <= 65536 when idx is KAN_U16    */
   int32_t idx_dtype;     /* KAN_U16 | KAN_U32                                       */
   int32_t gb_dtype;      /* KAN_F32 | KAN_F16 | KAN_Q8 (gain and bias share it)     */
-  int32_t cb_dtype;      /* KAN_F32 | KAN_F16 | KAN_I8                              */
+  int32_t cb_dtype;      /* KAN_F32 | KAN_F16 | KAN_I8 | KAN_BFP8                   */
   const void* idx;       /* [in][out]                                               */
   const void* gain;      /* [in][out]                                               */
   const void* bias;      /* [in][out]                                               */
-  const void* codebook;  /* [K][10]                                                 */
+  const void* codebook;  /* [K][10]; KAN_BFP8: [K] rows of 12 bytes (below)         */
   float scale;           /* Int8: value = scale * q.  Ignored for KAN_F32 and KAN_F16
                             codebooks (Table 1 lists FP32, FP16 and Int8 codebooks)  */
   int32_t rule;          /* KAN_RULE_BSPLINE3 (0) | KAN_RULE_PLI2                   */
@@ -121,6 +122,12 @@ typedef struct kan_vq_layer {
    * KAN_ERR_UNSUPPORTED.  Ignored for the other gain/bias dtypes.                            */
   float gain_log2_lo, gain_log2_step, bias_scale;
   int32_t reserved;      /* set to 0                                                */
+  /* KAN_BFP8 codebooks (Table 1 lists a block-floating-point row between FP16 and Int8; the
+   * paper defines no format, this is the one used here): a codeword row is one block of 12
+   * bytes, 4-byte aligned: ten signed mantissa bytes q[0..9] in -127..127, one signed exponent
+   * byte e in -126..127 shared by the row, one zero byte; entry m means q[m] * 2^e.  `scale` is
+   * ignored.  Served by the vector-ALU, fused and streaming kernels; kan_vq_prepare does not
+   * take such layers (kan_vq_prepared_bytes returns 0).                                     */
 } kan_vq_layer;
 
 /* Spans and basis weights of step "index lookup" (section 4.1) for the cubic

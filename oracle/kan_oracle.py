@@ -21,6 +21,10 @@ What it follows
 * Int8 codebooks store one byte per coefficient (paper §4.3, §5.4); the value
   is scale * q with one fp32 scale per layer (a reading: the paper gives the
   byte count but not the mapping).
+* Block-floating-point codebooks (the BFP8 row of the paper's Table 1): one shared
+  exponent byte per codeword row and ten signed mantissa bytes (a reading: the
+  paper names the precision only; PARITY WITH THE PAPER'S OWN ENCODING IS UNPINNED,
+  the decoder is pinned against what fixes this reading's meaning).
 * Heads: tanh between layers, none after the last (benchmark configuration).
 
 * The runtime operator's own rule (paper §4.1, §4.3), selectable with
@@ -48,7 +52,10 @@ monotonicity, round trip through the encoder within half a step; for the
 assignment step: brute-force loops, scipy's k-d tree, exact recovery of a layer built
 from the codebook (R^2 = 1), invariance under affine changes of a grid; for the error
 scale A = sum_i |phi_ij|: the scalar definition summed edge by edge, constant and linear
-codewords (closed forms), in both vectorised forms.
+codewords (closed forms), in both vectorised forms; for block-floating-point codebooks:
+rows of exact powers of two, negative exponents, the ignored twelfth byte, round trip
+through the generator's encoder within half a mantissa step, equality with the layer built
+from the decoded fp64 rows.
 """
 from __future__ import annotations
 
@@ -236,10 +243,22 @@ def span_index(x) -> np.ndarray:
     return np.searchsorted(t[DEGREE + 1:G], xc, side="right").astype(np.uint8)
 
 
+BFP8_ROW_BYTES = G + 2       # ten mantissa bytes, the row's exponent byte, one zero byte
+
+
 def dequantise_codebook(codebook, scale=1.0) -> np.ndarray:
-    """Codebook as float64 [K][G].  Int8 codebooks: value = scale * q; floating
-    codebooks are taken as they are (scale ignored)."""
+    """Codebook as float64 [K][G].  Int8 codebooks [K][G]: value = scale * q; floating
+    codebooks are taken as they are (scale ignored).
+
+    Block floating point with 8-bit mantissas (the BFP8 row of the paper's Table 1; the paper
+    names the precision, not the format - this reading: one block per codeword row): an int8
+    array [K][12] whose row k holds ten signed mantissas q[k][0..9], then the signed exponent
+    e[k] shared by the row, then a zero byte; entry m is q[k][m] * 2 ** e[k] (scale ignored)."""
     cb = np.asarray(codebook)
+    if cb.dtype == np.int8 and cb.shape[-1] == BFP8_ROW_BYTES:
+        q = cb[..., :G].astype(np.float64)
+        e = cb[..., G].astype(np.float64)
+        return q * np.exp2(e)[..., None]
     if cb.dtype == np.int8:
         return np.float64(np.float32(scale)) * cb.astype(np.float64)
     return cb.astype(np.float64)

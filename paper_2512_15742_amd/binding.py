@@ -17,7 +17,7 @@ LIB_PATH = os.path.join(_HERE, "libkan_mi355x.so")
 
 KAN_OK = 0
 KAN_ERR_NULL, KAN_ERR_SHAPE, KAN_ERR_DTYPE, KAN_ERR_WORKSPACE, KAN_ERR_UNSUPPORTED, KAN_ERR_LAUNCH = 1, 2, 3, 4, 5, 6
-KAN_F32, KAN_F16, KAN_I8, KAN_U16, KAN_U32, KAN_Q8 = 0, 1, 2, 3, 4, 5
+KAN_F32, KAN_F16, KAN_I8, KAN_U16, KAN_U32, KAN_Q8, KAN_BFP8 = 0, 1, 2, 3, 4, 5, 6
 KAN_PATH_AUTO, KAN_PATH_GATHER, KAN_PATH_MFMA = 0, 1, 2
 KAN_RULE_BSPLINE3, KAN_RULE_PLI2 = 0, 1
 
@@ -160,6 +160,8 @@ class VQLayer:
             self.n_in, self.n_out, 10, 3, self.K,
             KAN_U16 if idx.dtype == np.uint16 else KAN_U32,
             gb,
+            # (an int8 array of 12-byte rows is a block-floating-point codebook: 10 mantissas, exponent, zero)
+            KAN_BFP8 if (params.codebook.dtype == np.int8 and params.codebook.shape[1] == 12) else
             {np.dtype(np.int8): KAN_I8, np.dtype(np.float16): KAN_F16,
              np.dtype(np.float32): KAN_F32}[params.codebook.dtype],
             self.idx.data_ptr(), self.gain.data_ptr(), self.bias.data_ptr(), self.codebook.data_ptr(),

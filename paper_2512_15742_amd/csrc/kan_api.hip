@@ -79,7 +79,7 @@ int gb_kind_of(const kan_vq_layer& L) {
 }
 
 int code_of(const kan_vq_layer& L) {
-  return L.cb_dtype == KAN_I8 ? kCbI8 : (L.cb_dtype == KAN_F16 ? kCbF16 : kCbF32);
+  return L.cb_dtype == KAN_I8 ? kCbI8 : (L.cb_dtype == KAN_F16 ? kCbF16 : (L.cb_dtype == KAN_BFP8 ? kCbBfp8 : kCbF32));
 }
 
 kan_status validate_layer(const kan_vq_layer* L) {
@@ -89,7 +89,7 @@ kan_status validate_layer(const kan_vq_layer* L) {
   if (L->in < 1 || L->out < 1 || L->in > kMaxDim || L->out > kMaxDim || L->K < 1) return KAN_ERR_SHAPE;
   if (L->idx_dtype != KAN_U16 && L->idx_dtype != KAN_U32) return KAN_ERR_DTYPE;
   if (L->gb_dtype != KAN_F32 && L->gb_dtype != KAN_F16 && L->gb_dtype != KAN_Q8) return KAN_ERR_DTYPE;
-  if (L->cb_dtype != KAN_F32 && L->cb_dtype != KAN_F16 && L->cb_dtype != KAN_I8) return KAN_ERR_DTYPE;
+  if (L->cb_dtype != KAN_F32 && L->cb_dtype != KAN_F16 && L->cb_dtype != KAN_I8 && L->cb_dtype != KAN_BFP8) return KAN_ERR_DTYPE;
   if (L->idx_dtype == KAN_U16 && L->K > 65536) return KAN_ERR_SHAPE;
   // byte-coded gain/bias belong to the fully quantised format: one-byte codebook entries too
   if (L->gb_dtype == KAN_Q8 && L->cb_dtype != KAN_I8) return KAN_ERR_UNSUPPORTED;
@@ -97,7 +97,7 @@ kan_status validate_layer(const kan_vq_layer* L) {
   const size_t idx_sz = L->idx_dtype == KAN_U16 ? 2 : 4;
   const size_t gb_sz = L->gb_dtype == KAN_F32 ? 4 : (L->gb_dtype == KAN_F16 ? 2 : 1);
   if (!aligned(L->idx, idx_sz) || !aligned(L->gain, gb_sz) || !aligned(L->bias, gb_sz)) return KAN_ERR_SHAPE;
-  if (!aligned(L->codebook, L->cb_dtype == KAN_F32 ? 8 : (L->cb_dtype == KAN_F16 ? 4 : 2))) return KAN_ERR_SHAPE;
+  if (!aligned(L->codebook, L->cb_dtype == KAN_F32 ? 8 : (L->cb_dtype == KAN_I8 ? 2 : 4))) return KAN_ERR_SHAPE;
   return KAN_OK;
 }
 
@@ -296,7 +296,7 @@ LayerPlan plan_bucket(const kan_vq_layer& L, int64_t B, int n_heads) {
 }
 
 bool layer_prepared_ok(const kan_vq_layer& L) {
-  return L.prepared != nullptr && aligned(L.prepared, 256) && aligned(L.codebook, 16) && L.in <= kBucketMaxIn &&
+  return L.prepared != nullptr && L.cb_dtype != KAN_BFP8 && aligned(L.prepared, 256) && aligned(L.codebook, 16) && L.in <= kBucketMaxIn &&
          (long long)L.in * L.out <= (1ll << 31);
 }
 
@@ -904,14 +904,14 @@ kan_status kan_dense_layer_forward(const float* coef, int32_t in, int32_t out, i
 
 size_t kan_vq_prepared_bytes(const kan_vq_layer* L) {
   if (validate_layer(L) != KAN_OK) return (size_t)-1;
-  if (L->in > kBucketMaxIn || (long long)L->in * L->out > (1ll << 31)) return 0;
+  if (L->in > kBucketMaxIn || (long long)L->in * L->out > (1ll << 31) || L->cb_dtype == KAN_BFP8) return 0;
   return bucket_geometry(L->in, L->out, L->K, code_of(*L), gb_kind_of(*L)).total;
 }
 
 kan_status kan_vq_prepare(const kan_vq_layer* L, void* prepared, size_t prepared_bytes, void* stream) {
   kan_status st = validate_layer(L);
   if (st != KAN_OK) return st;
-  if (L->in > kBucketMaxIn) return KAN_ERR_UNSUPPORTED;
+  if (L->in > kBucketMaxIn || L->cb_dtype == KAN_BFP8) return KAN_ERR_UNSUPPORTED;   // (no bucket layout for 12-byte rows)
   if ((long long)L->in * L->out > (1ll << 31)) return KAN_ERR_UNSUPPORTED;   // 32-bit segment offsets
   const BucketGeom g = bucket_geometry(L->in, L->out, L->K, code_of(*L), gb_kind_of(*L));
   if (!prepared || !aligned(prepared, 256) || prepared_bytes < g.total) return KAN_ERR_WORKSPACE;

@@ -198,6 +198,25 @@ __device__ __forceinline__ void load_bias(const T* p, const Q8Params& qp, float 
 
 // ---- codeword rows -------------------------------------------------------------
 
+// Block floating point with 8-bit mantissas (the BFP8 codebook row of the paper's Table 1; the
+// paper names the precision but not the format, so the format is this library's): a codeword
+// row is one block of twelve bytes - ten signed mantissa bytes q[0..9] in -127..127, one signed
+// exponent byte e shared by the row, one zero byte - and entry m means q[m] * 2^e.
+struct bfp8_t {
+  int8_t q[10];
+  int8_t e;
+  int8_t zero;
+};
+static_assert(sizeof(bfp8_t) == 12, "a block-floating-point row is twelve bytes");
+
+template <typename CbT> constexpr bool kIsBfp8 = sizeof(CbT) == 12;
+
+// 2^e for the exponent byte held in bits 16..23 of the row's third dword.
+__device__ __forceinline__ float bfp8_row_scale(uint32_t third_dword) {
+  const int e = (int)(int8_t)(third_dword >> 16);
+  return __uint_as_float((uint32_t)(e + 127) << 23);      // e in -126..127: a normal fp32 power of two
+}
+
 __device__ __forceinline__ float half_bits_to_float(uint32_t bits) {
   return (float)__builtin_bit_cast(_Float16, (uint16_t)bits);
 }
@@ -227,7 +246,17 @@ __device__ __forceinline__ void dequant4(uint32_t w, float mul, float off, float
 // Whole row: c[m] = mul * C[id][m], m = 0..9.
 template <typename CbT>
 __device__ __forceinline__ void fetch_row(const CbT* cb, uint32_t id, float mul, float (&c)[kG]) {
-  if constexpr (sizeof(CbT) == 1) {
+  if constexpr (kIsBfp8<CbT>) {
+    const uint32_t* p = (const uint32_t*)(cb + id);                // 4-byte aligned rows
+    const uint32_t a = p[0], b = p[1], d = p[2];
+    const float m2 = mul * bfp8_row_scale(d), off = -128.0f * m2;
+    float t[4];
+    dequant4(a, m2, off, &c[0]);
+    dequant4(b, m2, off, &c[4]);
+    dequant4(d, m2, off, t);
+    c[8] = t[0];
+    c[9] = t[1];
+  } else if constexpr (sizeof(CbT) == 1) {
     const uint8_t* p = (const uint8_t*)cb + (size_t)id * kG;       // 2-byte aligned
     const uint32_t a = ld_u32_any(p), b = ld_u32_any(p + 4), d = ld_u16_any(p + 8);
     const float off = -128.0f * mul;
@@ -263,10 +292,14 @@ template <typename CbT> struct WindowRaw;
 template <> struct WindowRaw<int8_t> { typedef uint32_t type; };
 template <> struct WindowRaw<__half> { typedef uint2 type; };
 template <> struct WindowRaw<float> { typedef float4 type; };
+template <> struct WindowRaw<bfp8_t> { typedef uint2 type; };      // four mantissa bytes, the row's third dword
 
 template <typename CbT>
 __device__ __forceinline__ typename WindowRaw<CbT>::type load_window(const CbT* cb, uint32_t id, int span) {
-  if constexpr (sizeof(CbT) == 1) {
+  if constexpr (kIsBfp8<CbT>) {
+    const uint8_t* p = (const uint8_t*)(cb + id);
+    return make_uint2(ld_u32_any(p + span), ((const uint32_t*)p)[2]);
+  } else if constexpr (sizeof(CbT) == 1) {
     return ld_u32_any((const uint8_t*)cb + (size_t)id * kG + span);
   } else if constexpr (sizeof(CbT) == 2) {
     uint2 v;                                                       // four halves, 2-byte aligned
@@ -281,7 +314,10 @@ __device__ __forceinline__ typename WindowRaw<CbT>::type load_window(const CbT* 
 
 template <typename CbT>
 __device__ __forceinline__ void dequant_window(typename WindowRaw<CbT>::type raw, float mul, float (&c)[4]) {
-  if constexpr (sizeof(CbT) == 1) {
+  if constexpr (kIsBfp8<CbT>) {
+    const float m2 = mul * bfp8_row_scale(raw.y);
+    dequant4(raw.x, m2, -128.0f * m2, c);
+  } else if constexpr (sizeof(CbT) == 1) {
     dequant4(raw, mul, -128.0f * mul, c);
   } else if constexpr (sizeof(CbT) == 2) {
     c[0] = mul * half_bits_to_float(raw.x & 0xffffu);

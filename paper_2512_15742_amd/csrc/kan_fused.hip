@@ -425,6 +425,9 @@ hipError_t launch_types(const GatherCfg& c, const FusedArgs& a, bool f32, int mb
                                : launch_variant<IdxT, float, int8_t>(a, f32, mblk, grid, s);
   }
   if (c.gb_kind == kGbQ8) return hipErrorInvalidValue;      // byte-coded gain/bias go with Int8 codebooks
+  if (c.code == kCbBfp8)
+    return c.gb_kind == kGbF16 ? launch_variant<IdxT, __half, bfp8_t>(a, f32, mblk, grid, s)
+                               : launch_variant<IdxT, float, bfp8_t>(a, f32, mblk, grid, s);
   if (c.code == kCbF16)
     return c.gb_kind == kGbF16 ? launch_variant<IdxT, __half, __half>(a, f32, mblk, grid, s)
                                : launch_variant<IdxT, float, __half>(a, f32, mblk, grid, s);

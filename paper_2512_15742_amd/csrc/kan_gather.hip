@@ -312,6 +312,9 @@ hipError_t launch_types(const GatherCfg& c, const GatherArgs& a, dim3 grid, hipS
                                : launch_jpl<IdxT, float, int8_t, kCbI8>(c, a, grid, s);
   }
   if (c.gb_kind == kGbQ8) return hipErrorInvalidValue;      // byte-coded gain/bias go with Int8 codebooks
+  if (c.code == kCbBfp8)
+    return c.gb_kind == kGbF16 ? launch_jpl<IdxT, __half, bfp8_t, kCbBfp8>(c, a, grid, s)
+                               : launch_jpl<IdxT, float, bfp8_t, kCbBfp8>(c, a, grid, s);
   if (c.code == kCbF16)
     return c.gb_kind == kGbF16 ? launch_jpl<IdxT, __half, __half, kCbF16>(c, a, grid, s)
                                : launch_jpl<IdxT, float, __half, kCbF16>(c, a, grid, s);

@@ -20,8 +20,8 @@ struct LayerPtrs {
   float gain_log2_lo, gain_log2_step, bias_scale;   // byte-coded gain/bias only
 };
 
-enum CodeKind : int { kCbF32 = 0, kCbI8 = 1, kDense = 2, kCbF16 = 3 };
-constexpr int cb_row_bytes(int code) { return code == kCbI8 ? 10 : (code == kCbF16 ? 20 : 40); }
+enum CodeKind : int { kCbF32 = 0, kCbI8 = 1, kDense = 2, kCbF16 = 3, kCbBfp8 = 4 };
+constexpr int cb_row_bytes(int code) { return code == kCbI8 ? 10 : (code == kCbF16 ? 20 : (code == kCbBfp8 ? 12 : 40)); }
 enum GbKind : int { kGbF32 = 0, kGbF16 = 1, kGbQ8 = 2 };     // fp32, fp16, one byte each (log gain, linear bias)
 constexpr int gb_bytes(int kind) { return kind == kGbF32 ? 4 : (kind == kGbF16 ? 2 : 1); }
 

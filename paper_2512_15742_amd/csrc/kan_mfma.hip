@@ -714,7 +714,10 @@ hipError_t prep_types(const GatherCfg& c, F&& launch) {
     else launch(TypeTag<float>(), TypeTag<int8_t>());
   } else {
     if (c.gb_kind == kGbQ8) return hipErrorInvalidValue;    // byte-coded gain/bias go with Int8 codebooks
-    if (c.code == kCbF16) {
+    if (c.code == kCbBfp8) {
+      if (c.gb_kind == kGbF16) launch(TypeTag<__half>(), TypeTag<bfp8_t>());
+      else launch(TypeTag<float>(), TypeTag<bfp8_t>());
+    } else if (c.code == kCbF16) {
       if (c.gb_kind == kGbF16) launch(TypeTag<__half>(), TypeTag<__half>());
       else launch(TypeTag<float>(), TypeTag<__half>());
     } else if (c.gb_kind == kGbF16) launch(TypeTag<__half>(), TypeTag<float>());

@@ -32,6 +32,7 @@ template <typename CbT> struct RawRow;
 template <> struct RawRow<int8_t> { uint32_t a, b, d; };
 template <> struct RawRow<__half> { uint32_t w[kG / 2]; };
 template <> struct RawRow<float> { float c[kG]; };
+template <> struct RawRow<bfp8_t> { uint32_t a, b, d; };           // d: mantissas 8, 9, exponent byte, zero
 
 // One row = one to three load instructions per lane, as wide as they come: every vector-memory
 // instruction of a divergent gather costs the CU's address and tag pipeline a slot per lane,
@@ -58,7 +59,13 @@ __device__ __forceinline__ void load_row(const CbT* cb, uint32_t id, RawRow<CbT>
   typedef unsigned int bu32x2 __attribute__((ext_vector_type(2)));
   typedef unsigned int bu32x3 __attribute__((ext_vector_type(3)));
   typedef unsigned int bu32x4 __attribute__((ext_vector_type(4)));
-  if constexpr (sizeof(CbT) == 1) {
+  if constexpr (kIsBfp8<CbT>) {                                   // twelve bytes, 4-byte aligned: one load
+    const __amdgpu_buffer_rsrc_t rs = __builtin_amdgcn_make_buffer_rsrc((void*)cb, 0, 0x7fffffff, kRowBufferFlags);
+    const bu32x3 v = __builtin_amdgcn_raw_buffer_load_b96(rs, (int)(id * 12u), 0, 0);
+    r.a = v.x;
+    r.b = v.y;
+    r.d = v.z;
+  } else if constexpr (sizeof(CbT) == 1) {
     const uint32_t mis = (uint32_t)(uintptr_t)cb & 3u;           // 0 or 2: the base within its dword
     const __amdgpu_buffer_rsrc_t rs =
         __builtin_amdgcn_make_buffer_rsrc((void*)((uintptr_t)cb - mis), 0, 0x7fffffff, kRowBufferFlags);
@@ -106,8 +113,10 @@ __device__ __forceinline__ void align_row(RawRow<CbT>& r, uint32_t odd) {
 // w[0..3] = fp16 pairs of g*coef 0..7, w[4] = g*coef 8, 9.
 template <typename CbT>
 __device__ __forceinline__ void dequant_row(const RawRow<CbT>& r, float g, uint32_t (&w)[5]) {
-  if constexpr (sizeof(CbT) == 1) {
-    const _Float16 gh = (_Float16)g;
+  if constexpr (sizeof(CbT) == 1 || kIsBfp8<CbT>) {
+    float gs = g;
+    if constexpr (kIsBfp8<CbT>) gs = g * bfp8_row_scale(r.d);      // the row's own power of two goes with the gain
+    const _Float16 gh = (_Float16)gs;
     const h16x2 g2 = {gh, gh};
     const uint32_t a = r.a ^ 0x80808080u, b = r.b ^ 0x80808080u, d = r.d ^ 0x00008080u;
     w[0] = dq_pair<0>(a, g2);
@@ -128,7 +137,8 @@ __device__ __forceinline__ void dequant_row(const RawRow<CbT>& r, float g, uint3
 // c[m] = g * coef m as fp32 (matrix-core path with fp32 operands).
 template <typename CbT>
 __device__ __forceinline__ void dequant_row_f32(const RawRow<CbT>& r, float g, float (&c)[kG]) {
-  if constexpr (sizeof(CbT) == 1) {
+  if constexpr (sizeof(CbT) == 1 || kIsBfp8<CbT>) {
+    if constexpr (kIsBfp8<CbT>) g *= bfp8_row_scale(r.d);          // the row's own power of two goes with the gain
     const float off = -128.0f * g;
     float t[4];
     dequant4(r.a, g, off, &c[0]);

@@ -248,6 +248,9 @@ void debug_gather_types(const LayerPtrs& h, int code, long long edges, uint32_t*
   if (code == kCbI8)
     hipLaunchKernelGGL((kan_debug_gather_kernel<IdxT, int8_t>), grid, block, 0, s, (const IdxT*)h.idx,
                        (const int8_t*)h.cb, h.scale, edges, ids, rows);
+  else if (code == kCbBfp8)
+    hipLaunchKernelGGL((kan_debug_gather_kernel<IdxT, bfp8_t>), grid, block, 0, s, (const IdxT*)h.idx,
+                       (const bfp8_t*)h.cb, 1.0f, edges, ids, rows);
   else if (code == kCbF16)
     hipLaunchKernelGGL((kan_debug_gather_kernel<IdxT, __half>), grid, block, 0, s, (const IdxT*)h.idx,
                        (const __half*)h.cb, 1.0f, edges, ids, rows);
@@ -258,7 +261,7 @@ void debug_gather_types(const LayerPtrs& h, int code, long long edges, uint32_t*
 
 hipError_t launch_debug_gather(const LayerPtrs& h, int idx_u32, int code, long long edges, uint32_t* ids,
                                float* rows, hipStream_t s) {
-  if (code != kCbI8 && code != kCbF16 && code != kCbF32) return hipErrorInvalidValue;
+  if (code != kCbI8 && code != kCbF16 && code != kCbF32 && code != kCbBfp8) return hipErrorInvalidValue;
   const dim3 grid(blocks_for(edges));
   if (idx_u32)
     debug_gather_types<uint32_t>(h, code, edges, ids, rows, grid, s);
@@ -282,6 +285,9 @@ hipError_t coef_range_types(const LayerPtrs& h, int gb_kind, int code, long long
     else coef_range_launch<IdxT, float, int8_t>(h, edges, range, s);
   } else if (gb_kind == kGbQ8) {
     return hipErrorInvalidValue;
+  } else if (code == kCbBfp8) {
+    if (gb_kind == kGbF16) coef_range_launch<IdxT, __half, bfp8_t>(h, edges, range, s);
+    else coef_range_launch<IdxT, float, bfp8_t>(h, edges, range, s);
   } else if (code == kCbF16) {
     if (gb_kind == kGbF16) coef_range_launch<IdxT, __half, __half>(h, edges, range, s);
     else coef_range_launch<IdxT, float, __half>(h, edges, range, s);

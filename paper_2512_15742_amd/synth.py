@@ -67,6 +67,22 @@ def quantise_shapes(shapes: np.ndarray):
     return q, scale
 
 
+def quantise_shapes_bfp8(shapes: np.ndarray) -> np.ndarray:
+    """Block-floating-point codebook, one block per row: int8 [K][12] = ten mantissas, the row's
+    exponent, a zero byte.  Encoder only: exponent e = the smallest integer with
+    max|row| <= 127 * 2**e (clamped to -126..127; an all-zero row gets -126),
+    mantissas rint(row / 2**e) in -127..127."""
+    s = shapes.astype(np.float64)
+    m = np.abs(s).max(axis=1)
+    e = np.where(m > 0, np.ceil(np.log2(np.maximum(m, 1e-300) / 127.0)), -126.0)
+    e = np.clip(e, -126, 127)
+    q = np.clip(np.rint(s / np.exp2(e)[:, None]), -127, 127)
+    out = np.zeros((s.shape[0], G + 2), dtype=np.int8)
+    out[:, :G] = q.astype(np.int8)
+    out[:, G] = e.astype(np.int8)
+    return out
+
+
 def encode_gain_bias_q8(gain: np.ndarray, bias: np.ndarray):
     """One byte each (the 16 bits per edge of the fully quantised format): gains on a
     logarithmic grid, biases on a linear one.  Encoder only - what the codes MEAN is the
@@ -117,6 +133,8 @@ def make_layer(seed: int, n_in: int, n_out: int, K: int, *, cb_dtype="f32",
         codebook, scale = shapes, np.float32(1.0)
     elif cb_dtype == "f16":
         codebook, scale = shapes.astype(np.float16), np.float32(1.0)
+    elif cb_dtype == "bfp8":
+        codebook, scale = quantise_shapes_bfp8(shapes), np.float32(1.0)
     else:
         raise ValueError(cb_dtype)
     if idx_dtype is None:

@@ -471,6 +471,61 @@ def test_abs_sum_A_against_the_scalar_definition_and_closed_forms():
     np.testing.assert_allclose(Ad, ref, atol=1e-14)
 
 
+# ---- block-floating-point codebooks (the BFP8 row of Table 1; the format is a reading) ----------
+
+def test_bfp8_codebook_meaning_and_round_trip():
+    """What the twelve bytes of a row mean, by values that need no formula of the oracle's:
+    mantissa 1 with exponent e is exactly 2**e (negative exponents included: the byte is signed),
+    mantissas scale linearly, the twelfth byte is ignored, `scale` is ignored; decoded rows of the
+    generator's encoder lie within half a mantissa step of the shapes they encode; a layer over a
+    block-floating-point codebook equals the layer over its decoded rows."""
+    rows = np.zeros((6, 12), dtype=np.int8)
+    rows[0, :10], rows[0, 10] = 1, 0                       # all ones
+    rows[1, :10], rows[1, 10] = np.arange(-5, 5), -3       # q / 8
+    rows[2, :10], rows[2, 10] = 127, -126                  # smallest exponent
+    rows[3, :10], rows[3, 10] = -127, 5                    # -127 * 32
+    rows[4, :10], rows[4, 10], rows[4, 11] = 64, -7, 99    # the last byte carries nothing
+    rows[5, 10] = 17                                       # zero mantissas
+    C = ko.dequantise_codebook(rows, 123.0)
+    assert C.shape == (6, 10) and C.dtype == np.float64
+    assert (C[0] == 1.0).all()
+    assert np.array_equal(C[1], np.arange(-5, 5) / 8.0)
+    assert (C[2] == 127.0 * 2.0 ** -126).all()
+    assert (C[3] == -127.0 * 32.0).all()
+    assert (C[4] == 0.5).all() and (C[5] == 0.0).all()
+    # an Int8 codebook [K][10] keeps its own meaning
+    q = np.arange(-5, 5, dtype=np.int8)[None, :]
+    assert np.array_equal(ko.dequantise_codebook(q, 0.5), 0.5 * q.astype(np.float64))
+    # round trip through the encoder
+    rng = np.random.default_rng(17)
+    shapes = synth.make_shapes(rng, 400)
+    shapes[7] *= 1e-3                                      # a row far smaller than the others keeps its own exponent
+    shapes[9] = 0.0
+    enc = synth.quantise_shapes_bfp8(shapes)
+    assert enc.dtype == np.int8 and enc.shape == (400, 12) and (enc[:, 11] == 0).all()
+    dec = ko.dequantise_codebook(enc)
+    step = np.exp2(enc[:, 10].astype(np.float64))
+    assert (np.abs(dec - shapes.astype(np.float64)) <= 0.5 * step[:, None] * (1 + 1e-12)).all()
+    assert (dec[9] == 0).all() and np.abs(dec[7]).max() < 2e-3 and np.abs(dec[7] - shapes[7]).max() < 1e-5
+    assert np.abs(enc[:, :10]).max(axis=1).min() >= 0 and (np.abs(enc[np.abs(shapes).max(axis=1) > 0, :10]).max(axis=1) >= 64).all()
+    # layer level: equal to the layer over the decoded rows, whatever `scale` says
+    P = synth.make_layer(51, 9, 6, 30, cb_dtype="bfp8", gb_dtype="f16")
+    assert P.codebook.shape == (30, 12)
+    x = synth.make_x(5, 7, 9)
+    y_b = ko.vq_layer_forward(x, P.codebook, 55.0, P.idx, P.gain, P.bias)
+    y_d = ko.vq_layer_forward(x, ko.dequantise_codebook(P.codebook), 1.0, P.idx, P.gain, P.bias)
+    assert np.array_equal(y_b, y_d)
+    y_s = ko.vq_layer_forward_scalar(x.tolist(), ko.dequantise_codebook(P.codebook).tolist(), 1.0, P.idx.tolist(),
+                                     P.gain.astype(np.float64).tolist(), P.bias.astype(np.float64).tolist())
+    np.testing.assert_allclose(y_b, y_s, atol=1e-14)
+    # and close to the fp32 layer it was encoded from: |dC| <= step / 2 per entry, weights sum to 1
+    F = synth.make_layer(51, 9, 6, 30, cb_dtype="f32", gb_dtype="f16")
+    y_f = ko.vq_layer_forward(x, **F.as_dict())
+    stepP = np.exp2(P.codebook[:, 10].astype(np.float64))
+    bound = (np.abs(P.gain.astype(np.float64)) * 0.5 * stepP[P.idx.astype(np.int64)]).sum(axis=0)
+    assert (np.abs(y_b - y_f) <= bound[None, :] + 1e-12).all() and np.abs(y_b - y_f).max() > 0
+
+
 # ---- the pins bite: a planted mistake in the oracle fails at least one of them ----------
 
 def _pin_suite():
@@ -487,6 +542,7 @@ def _pin_suite():
             test_q8_round_trip_through_the_encoder, test_assignment_brute_force_and_kdtree,
             test_assignment_recovers_a_layer_built_from_the_codebook,
             test_abs_sum_A_against_the_scalar_definition_and_closed_forms,
+            test_bfp8_codebook_meaning_and_round_trip,
             lambda: test_scalar_definition_vs_vectorised(False), lambda: test_scalar_definition_vs_vectorised(True)]
 
 
@@ -592,6 +648,29 @@ def _mutations():
         Bm = ko.design_matrix(np.asarray(x, dtype=np.float64), rule)
         return out, np.array([(np.abs(Bm[b]) * np.abs(coef[:, j])).sum() for b, j in zip(bs, js)])
 
+    def bfp8_exponent_unsigned(cb, scale=1.0):           # exponent byte read as unsigned
+        cb = np.asarray(cb)
+        if cb.dtype == np.int8 and cb.shape[-1] == 12:
+            return cb[..., :10].astype(np.float64) * np.exp2(cb[..., 10].view(np.uint8).astype(np.float64))[..., None]
+        return real["dequantise_codebook"](cb, scale)
+
+    def bfp8_exponent_negated(cb, scale=1.0):            # q / 2**e instead of q * 2**e
+        cb = np.asarray(cb)
+        if cb.dtype == np.int8 and cb.shape[-1] == 12:
+            return cb[..., :10].astype(np.float64) * np.exp2(-cb[..., 10].astype(np.float64))[..., None]
+        return real["dequantise_codebook"](cb, scale)
+
+    def bfp8_scale_applied(cb, scale=1.0):               # the layer scale wrongly applied on top
+        cb = np.asarray(cb)
+        out = real["dequantise_codebook"](cb, scale)
+        return out * float(scale) if (cb.dtype == np.int8 and cb.shape[-1] == 12) else out
+
+    def bfp8_exponent_from_last_byte(cb, scale=1.0):     # exponent taken from byte 11 instead of byte 10
+        cb = np.asarray(cb)
+        if cb.dtype == np.int8 and cb.shape[-1] == 12:
+            return cb[..., :10].astype(np.float64) * np.exp2(cb[..., 11].astype(np.float64))[..., None]
+        return real["dequantise_codebook"](cb, scale)
+
     def pli_swapped_taps(x):                   # u and 1-u exchanged
         W = real["pli_matrix"](x)
         k = ko.pli_index(np.asarray(x, dtype=np.float64).reshape(-1)).astype(np.int64)
@@ -642,6 +721,10 @@ def _mutations():
             ("unit variance instead of unit norm", "normalise_grids", normalise_by_std),
             ("grids not centred", "normalise_grids", normalise_without_centring),
             ("dot product used as a distance", "squared_distances", distances_as_dot_products),
+            ("block exponent read unsigned", "dequantise_codebook", bfp8_exponent_unsigned),
+            ("block exponent negated", "dequantise_codebook", bfp8_exponent_negated),
+            ("layer scale applied to a block codebook", "dequantise_codebook", bfp8_scale_applied),
+            ("block exponent taken from the wrong byte", "dequantise_codebook", bfp8_exponent_from_last_byte),
             ("A summed per coefficient (dense form)", "dense_layer_forward", dense_abs_per_coefficient),
             ("A taken as |sum| (sampled form)", "vq_layer_outputs_at", outputs_at_abs_of_the_sum),
             ("A summed per coefficient (sampled form)", "vq_layer_outputs_at", outputs_at_abs_per_coefficient)]
