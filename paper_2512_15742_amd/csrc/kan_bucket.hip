@@ -22,7 +22,7 @@
 // The bias of an edge needs no lookup at all: the four bases sum to 1 on [-1,1], so
 // sum_i bias_ij is a per-output constant computed at preparation time.
 //
-// This file also holds the three preparation kernels (count, scan, fill).
+// This file also holds the preparation kernels (count, scan, fill, bias sums, block tables).
 
 #include <type_traits>
 
@@ -444,16 +444,68 @@ __global__ __launch_bounds__(kBucketThreads) void kan_bucket_kernel(const Bucket
 }
 
 // ---- preparation ------------------------------------------------------------------------
-// Thread (j, bucket) counts the edges of its segment, walking i upwards.
-template <typename IdxT>
-__global__ __launch_bounds__(256) void kan_prepare_count_kernel(const IdxT* __restrict__ idx, int n_in, int n_out,
-                                                                int rows_shift, uint32_t* __restrict__ seg) {
+// The regrouping is a counting sort of the edges by (bucket, output j), input i ascending
+// inside a run, and at the same time a transposition: the layer stores consecutive outputs side
+// by side, the prepared layout consecutive inputs.  It is done tile by tile (kPrepareRows inputs x
+// kPrepareCols outputs per workgroup), so that both the reads (rows of the tile) and the writes
+// (runs of one (bucket, output) within the tile's row block) move whole runs of bytes:
+//   count   per tile: edges per (bucket, output) -> tcnt[row block][bucket][output] and, added
+//           up over the row blocks with integer atomics, the segment lengths; bias sums per
+//           (row block, output) in fp64
+//   scan    exclusive prefix over the segment lengths (bucket-major) -> segment table
+//   fill    per tile: the tile's idx and gain staged in LDS; a wave takes a column, and for
+//           every 64 rows ranks its lanes within their bucket (ballots) behind the edges of the
+//           earlier row blocks and rows
+//   bias    per output: the row blocks' sums added in order, rounded once to fp32
+
+template <typename IdxT, typename GbT>
+__global__ __launch_bounds__(256) void kan_prepare_count_kernel(const IdxT* __restrict__ idx,
+                                                                const GbT* __restrict__ bias, int n_in, int n_out,
+                                                                int rows_shift, int n_buckets,
+                                                                uint32_t* __restrict__ seg, uint16_t* __restrict__ tcnt,
+                                                                double* __restrict__ tbias, Q8Params qp) {
+  extern __shared__ uint32_t cnt[];                 // [n_buckets][kPrepareCols]
+  __shared__ double bsum[4][kPrepareCols];
+  const int lane = threadIdx.x & 63, wave = threadIdx.x >> 6;
+  const int j = blockIdx.x * kPrepareCols + lane;
+  const int i0 = blockIdx.y * kPrepareRows + wave * (kPrepareRows / 4);
+  for (int t = threadIdx.x; t < n_buckets * kPrepareCols; t += 256) cnt[t] = 0u;
+  __syncthreads();
+  double bs = 0.0;
+  if (j < n_out) {
+    const int i1 = min(i0 + kPrepareRows / 4, n_in);
+    for (int i = i0; i < i1; ++i) {
+      const size_t e = (size_t)i * n_out + j;
+      const uint32_t b = min((uint32_t)idx[e] >> rows_shift, (uint32_t)(n_buckets - 1));
+      atomicAdd(&cnt[b * kPrepareCols + lane], 1u);            // (waves share a column: integer, order-free)
+      bs += (double)bias_to_float(bias[e], qp);
+    }
+  }
+  bsum[wave][lane] = bs;
+  __syncthreads();
+  for (int t = threadIdx.x; t < n_buckets * kPrepareCols; t += 256) {
+    const int b = t / kPrepareCols, jj = blockIdx.x * kPrepareCols + (t % kPrepareCols);
+    if (jj < n_out) {
+      const uint32_t c = cnt[t];
+      tcnt[((size_t)blockIdx.y * n_buckets + b) * n_out + jj] = (uint16_t)c;
+      if (c) atomicAdd(&seg[(size_t)b * n_out + jj], c);
+    }
+  }
+  if (wave == 0 && j < n_out)
+    tbias[(size_t)blockIdx.y * n_out + j] = ((bsum[0][lane] + bsum[1][lane]) + bsum[2][lane]) + bsum[3][lane];
+}
+
+__global__ __launch_bounds__(256) void kan_prepare_zero_kernel(uint32_t* __restrict__ p, long long n) {
+  for (long long t = (long long)blockIdx.x * blockDim.x + threadIdx.x; t < n; t += (long long)gridDim.x * blockDim.x) p[t] = 0u;
+}
+
+__global__ __launch_bounds__(256) void kan_prepare_bias_kernel(const double* __restrict__ tbias, int n_row_blocks, int n_out,
+                                                               float* __restrict__ bias_sum) {
   const int j = blockIdx.x * blockDim.x + threadIdx.x;
-  const uint32_t bucket = blockIdx.y;
   if (j >= n_out) return;
-  uint32_t c = 0;
-  for (int i = 0; i < n_in; ++i) c += ((uint32_t)idx[(size_t)i * n_out + j] >> rows_shift) == bucket;
-  seg[(size_t)bucket * n_out + j] = c;
+  double s = 0.0;
+  for (int r = 0; r < n_row_blocks; ++r) s += tbias[(size_t)r * n_out + j];
+  bias_sum[j] = (float)s;
 }
 
 // In-place exclusive scan of n counts by one workgroup; seg[n] = total.
@@ -484,34 +536,67 @@ __global__ __launch_bounds__(1024) void kan_prepare_scan_kernel(uint32_t* __rest
   }
 }
 
-// Thread (j, bucket) writes the records of its segment in order of i; bucket 0 also sums
-// the biases of output j (in fp64, rounded once).
 template <typename IdxT, typename GbT>
-__global__ __launch_bounds__(256) void kan_prepare_fill_kernel(const IdxT* __restrict__ idx,
-                                                               const GbT* __restrict__ gain,
-                                                               const GbT* __restrict__ bias, int n_in, int n_out,
-                                                               int rows_shift, const uint32_t* __restrict__ seg,
+__global__ __launch_bounds__(256) void kan_prepare_fill_kernel(const IdxT* __restrict__ idx, const GbT* __restrict__ gain,
+                                                               int n_in, int n_out, int rows_shift, int n_buckets,
+                                                               const uint32_t* __restrict__ seg,
+                                                               const uint16_t* __restrict__ tcnt,
                                                                uint16_t* __restrict__ pi, uint16_t* __restrict__ pq,
-                                                               GbT* __restrict__ pg, float* __restrict__ bias_sum,
-                                                               Q8Params qp) {
-  const int j = blockIdx.x * blockDim.x + threadIdx.x;
-  const uint32_t bucket = blockIdx.y;
-  if (j >= n_out) return;
-  size_t pos = seg[(size_t)bucket * n_out + j];
-  const uint32_t mask = (1u << rows_shift) - 1u;
-  double bs = 0.0;
-  for (int i = 0; i < n_in; ++i) {
-    const size_t e = (size_t)i * n_out + j;
-    const uint32_t id = (uint32_t)idx[e];
-    if ((id >> rows_shift) == bucket) {
-      pi[pos] = (uint16_t)i;
-      pq[pos] = (uint16_t)(id & mask);
-      pg[pos] = gain[e];
-      ++pos;
+                                                               GbT* __restrict__ pg) {
+  extern __shared__ __attribute__((aligned(16))) unsigned char lds_raw[];
+  // tile of ids and gains, [row][column], then the running position of every bucket, one table per wave
+  IdxT* tid_ = (IdxT*)lds_raw;
+  GbT* tg = (GbT*)(lds_raw + (size_t)kPrepareRows * kPrepareCols * sizeof(IdxT));
+  uint32_t* base = (uint32_t*)(lds_raw + (size_t)kPrepareRows * kPrepareCols * (sizeof(IdxT) + sizeof(GbT)));
+  const int lane = threadIdx.x & 63, wave = threadIdx.x >> 6;
+  const int j0 = blockIdx.x * kPrepareCols, i0 = blockIdx.y * kPrepareRows;
+  const int rows = min(kPrepareRows, n_in - i0), cols = min(kPrepareCols, n_out - j0);
+  for (int r = wave; r < rows; r += 4) {                     // a wave reads a row of the tile
+    if (lane < cols) {
+      const size_t e = (size_t)(i0 + r) * n_out + j0 + lane;
+      tid_[r * kPrepareCols + lane] = idx[e];
+      tg[r * kPrepareCols + lane] = gain[e];
     }
-    if (bucket == 0) bs += (double)bias_to_float(bias[e], qp);
   }
-  if (bucket == 0) bias_sum[j] = (float)bs;
+  __syncthreads();
+  uint32_t* wbase = base + (size_t)wave * n_buckets;
+  const uint32_t mask = (1u << rows_shift) - 1u;
+  const unsigned long long lt = (1ull << lane) - 1ull;
+  for (int c = wave; c < cols; c += 4) {                     // a wave takes a column
+    const int j = j0 + c;
+    // where this row block's edges of (bucket, j) start: the segment's start plus the earlier row blocks
+    for (int b = lane; b < n_buckets; b += 64) {
+      uint32_t at = seg[(size_t)b * n_out + j];
+      for (int rb = 0; rb < (int)blockIdx.y; ++rb) at += tcnt[((size_t)rb * n_buckets + b) * n_out + j];
+      wbase[b] = at;
+    }
+    __builtin_amdgcn_wave_barrier();
+    for (int r0 = 0; r0 < rows; r0 += 64) {
+      const int r = r0 + lane;
+      const bool live = r < rows;
+      const uint32_t id = live ? (uint32_t)tid_[r * kPrepareCols + c] : 0u;
+      const uint32_t b = min(id >> rows_shift, (uint32_t)(n_buckets - 1));
+      unsigned long long todo = __ballot(live);
+      uint32_t pos = 0;
+      while (todo) {                                         // one round per bucket present among the 64 rows
+        const int first = __ffsll((long long)todo) - 1;
+        const uint32_t kb = __shfl(b, first);
+        const unsigned long long same = __ballot(live && b == kb) & todo;
+        const uint32_t start = wbase[kb];
+        if (live && b == kb) pos = start + (uint32_t)__popcll(same & lt);
+        __builtin_amdgcn_wave_barrier();
+        if (lane == first) wbase[kb] = start + (uint32_t)__popcll(same);
+        __builtin_amdgcn_wave_barrier();
+        todo &= ~same;
+      }
+      if (live) {
+        pi[pos] = (uint16_t)(i0 + r);
+        pq[pos] = (uint16_t)(id & mask);
+        pg[pos] = tg[r * kPrepareCols + c];
+      }
+    }
+    __builtin_amdgcn_wave_barrier();
+  }
 }
 
 // Blocks per bucket for a table of W blocks (prefix sums -> cnt[0 .. n_buckets]): every bucket
@@ -592,14 +677,28 @@ hipError_t prepare_typed(const LayerPtrs& h, int n_in, int n_out, const BucketGe
                          hipStream_t s) {
   char* p = (char*)prepared;
   uint32_t* seg = (uint32_t*)(p + g.off_seg);
-  dim3 grid((unsigned)((n_out + 255) / 256), (unsigned)g.n_buckets);
-  hipLaunchKernelGGL((kan_prepare_count_kernel<IdxT>), grid, dim3(256), 0, s, (const IdxT*)h.idx, n_in, n_out,
-                     g.rows_shift, seg);
-  hipLaunchKernelGGL(kan_prepare_scan_kernel, dim3(1), dim3(1024), 0, s, seg, (long long)g.n_buckets * n_out);
-  hipLaunchKernelGGL((kan_prepare_fill_kernel<IdxT, GbT>), grid, dim3(256), 0, s, (const IdxT*)h.idx,
-                     (const GbT*)h.gain, (const GbT*)h.bias, n_in, n_out, g.rows_shift, (const uint32_t*)seg,
-                     (uint16_t*)(p + g.off_i), (uint16_t*)(p + g.off_q), (GbT*)(p + g.off_g),
-                     (float*)(p + g.off_bias), Q8Params{h.gain_log2_lo, h.gain_log2_step, h.bias_scale});
+  uint16_t* tcnt = (uint16_t*)(p + g.off_tcnt);
+  double* tbias = (double*)(p + g.off_tbias);
+  const long long n_seg = (long long)g.n_buckets * n_out;
+  const Q8Params qp = {h.gain_log2_lo, h.gain_log2_step, h.bias_scale};
+  dim3 grid((unsigned)((n_out + kPrepareCols - 1) / kPrepareCols), (unsigned)g.n_row_blocks);
+  const size_t lds_count = (size_t)g.n_buckets * kPrepareCols * sizeof(uint32_t);
+  const size_t lds_fill = (size_t)kPrepareRows * kPrepareCols * (sizeof(IdxT) + sizeof(GbT)) + (size_t)4 * g.n_buckets * sizeof(uint32_t);
+  if (lds_count > 64 * 1024 || lds_fill > 150 * 1024) return hipErrorInvalidValue;     // (n_buckets <= 256 fits)
+  // (dynamic LDS beyond 64 KB has to be asked for; the tile of 4-byte ids and 4-byte gains takes 128 KB)
+  hipError_t err = hipFuncSetAttribute((const void*)kan_prepare_fill_kernel<IdxT, GbT>,
+                                       hipFuncAttributeMaxDynamicSharedMemorySize, (int)lds_fill);
+  if (err != hipSuccess) return err;
+  hipLaunchKernelGGL(kan_prepare_zero_kernel, dim3((unsigned)((n_seg + 1 + 255) / 256 > 1024 ? 1024 : (n_seg + 1 + 255) / 256)),
+                     dim3(256), 0, s, seg, n_seg + 1);
+  hipLaunchKernelGGL((kan_prepare_count_kernel<IdxT, GbT>), grid, dim3(256), lds_count, s, (const IdxT*)h.idx,
+                     (const GbT*)h.bias, n_in, n_out, g.rows_shift, g.n_buckets, seg, tcnt, tbias, qp);
+  hipLaunchKernelGGL(kan_prepare_scan_kernel, dim3(1), dim3(1024), 0, s, seg, n_seg);
+  hipLaunchKernelGGL((kan_prepare_fill_kernel<IdxT, GbT>), grid, dim3(256), lds_fill, s, (const IdxT*)h.idx,
+                     (const GbT*)h.gain, n_in, n_out, g.rows_shift, g.n_buckets, (const uint32_t*)seg,
+                     (const uint16_t*)tcnt, (uint16_t*)(p + g.off_i), (uint16_t*)(p + g.off_q), (GbT*)(p + g.off_g));
+  hipLaunchKernelGGL(kan_prepare_bias_kernel, dim3((unsigned)((n_out + 255) / 256)), dim3(256), 0, s, (const double*)tbias,
+                     g.n_row_blocks, n_out, (float*)(p + g.off_bias));
   const int min_blocks = (n_out + kBucketMaxJw - 1) / kBucketMaxJw;
   for (int t = 0; t < kBucketTables; ++t) {
     uint32_t* cnt = (uint32_t*)(p + g.off_cnt) + (size_t)t * (g.n_buckets + 1);

@@ -163,6 +163,9 @@ constexpr int kBucketMaxJw = 1024;      // outputs per workgroup (their sums are
 // Codebook bytes per bucket: 8192 Int8, 4096 fp16 or 2048 fp32 rows for layers of up to 2048
 // inputs, half of that for wider layers (whose basis table takes twice the LDS).
 constexpr int bucket_bytes(int n_in) { return n_in > 2048 ? 40960 : 81920; }
+// The preparation regroups a layer tile by tile: kPrepareRows inputs x kPrepareCols outputs per workgroup.
+constexpr int kPrepareRows = 256;
+constexpr int kPrepareCols = 64;
 
 // Workgroups of a launch are laid out by block tables made at preparation time: a block is a
 // run of outputs of one bucket, and the outputs of a bucket are cut so that the blocks of a
@@ -184,6 +187,9 @@ struct BucketGeom {
   size_t off_g;        // gain   [E]                     in the layer's gain dtype
   size_t off_blk;      // uint32 [sum of tab_w][8]       block tables, one after the other
   size_t off_cnt;      // uint32 [kBucketTables][n_buckets + 1]  blocks per bucket (prefix sums), scratch of the preparation
+  size_t off_tcnt;     // uint16 [row blocks][n_buckets][n_out]  edges per (row block, bucket, output), scratch of the preparation
+  size_t off_tbias;    // double [row blocks][n_out]             bias sums per row block, scratch of the preparation
+  int n_row_blocks;    // row blocks of kPrepareRows inputs
   int tab_w[kBucketTables];        // blocks of every table
   int tab_first[kBucketTables];    // first entry of every table
   size_t total;
@@ -216,7 +222,10 @@ inline BucketGeom bucket_geometry(int n_in, int n_out, int K, int code, int gb_k
     entries += w;
   }
   g.off_cnt = g.off_blk + up((size_t)entries * kBucketEntryWords * 4);
-  g.total = g.off_cnt + up((size_t)kBucketTables * ((size_t)g.n_buckets + 1) * 4);
+  g.n_row_blocks = (n_in + kPrepareRows - 1) / kPrepareRows;
+  g.off_tcnt = g.off_cnt + up((size_t)kBucketTables * ((size_t)g.n_buckets + 1) * 4);
+  g.off_tbias = g.off_tcnt + up((size_t)g.n_row_blocks * g.n_buckets * n_out * 2);
+  g.total = g.off_tbias + up((size_t)g.n_row_blocks * n_out * 8);
   return g;
 }
 

@@ -125,7 +125,9 @@ def test_prepare_arguments_and_planning():
     need = L.kan_vq_prepared_bytes(C.byref(d))
     # segment table + bias sums + 6 bytes per edge (u16 input, u16 local id, fp16 gain)
     E = 2048 * 1024
-    assert need % 256 == 0 and 6 * E < need < 6 * E + (1 << 17)
+    # (+ the preparation's scratch: a u16 count per (block of 256 inputs, bucket, output), a bias sum per (block, output))
+    scratch = 8 * 8 * 1024 * 2 + 8 * 1024 * 8
+    assert need % 256 == 0 and 6 * E + scratch < need < 6 * E + scratch + (1 << 17)
     assert L.kan_vq_prepare(C.byref(d), None, need, None) == kb.KAN_ERR_WORKSPACE
     assert L.kan_vq_prepare(C.byref(d), FAKE, need - 1, None) == kb.KAN_ERR_WORKSPACE
     assert L.kan_vq_prepare(C.byref(d), C.c_void_p(0x10010), need, None) == kb.KAN_ERR_WORKSPACE
@@ -154,7 +156,8 @@ def test_byte_coded_layers_plan_and_prepare():
     assert L.kan_vq_workspace_bytes(C.byref(d), 1, 1, 16, kb.KAN_PATH_AUTO) != kb.SIZE_INVALID   # bytes need no alignment
     need = L.kan_vq_prepared_bytes(C.byref(d))
     E = 2048 * 1024
-    assert 5 * E < need < 5 * E + (1 << 17)              # u16 input + u16 local id + 1-byte gain code
+    scratch = 8 * 8 * 1024 * 2 + 8 * 1024 * 8            # the preparation's scratch (counts per row block, bias sums)
+    assert 5 * E + scratch < need < 5 * E + scratch + (1 << 17)      # u16 input + u16 local id + 1-byte gain code
 
 
 def test_fp16_codebook_layers_plan_and_prepare():
@@ -166,7 +169,8 @@ def test_fp16_codebook_layers_plan_and_prepare():
         assert L.kan_vq_workspace_bytes(C.byref(d), 1, 1, B, path) != kb.SIZE_INVALID
     E = 2048 * 1024
     need = L.kan_vq_prepared_bytes(C.byref(d))
-    assert 6 * E < need < 6 * E + 16 * 1024 * 4 * 2 + (1 << 17)   # 16 buckets of 4096 fp16 rows: 16 segment tables
+    scratch = 8 * 16 * 1024 * 2 + 8 * 1024 * 8                    # the preparation's scratch (counts per row block, bias sums)
+    assert 6 * E + scratch < need < 6 * E + scratch + 16 * 1024 * 4 * 2 + (1 << 17)   # 16 buckets of 4096 fp16 rows: 16 segment tables
     assert L.kan_vq_prepare(C.byref(d), FAKE, need - 1, None) == kb.KAN_ERR_WORKSPACE
     d.prepared = 0x100000
     assert L.kan_vq_planned_kernel(C.byref(d), 1, 1, kb.KAN_PATH_GATHER) == b"kan_gather_bt1"   # codebook not 16-byte aligned

@@ -33,6 +33,11 @@ def _bucket_rows(P):
     return rows // 2 if P.idx.shape[0] > 2048 else rows
 
 
+def _bias_f64(P):
+    """Per-edge biases as float64 (the prepared layout is not used with byte-coded biases here)."""
+    return P.bias.astype(np.float64)
+
+
 def _expected_layout(P):
     """(seg_off, bias_sum, i, q, gain) of the regrouped layer: bucket-major, then j, then i."""
     n_in, n_out = P.idx.shape
@@ -45,9 +50,18 @@ def _expected_layout(P):
     counts = np.zeros(nb * n_out, dtype=np.int64)
     np.add.at(counts, (bucket * n_out + jj).ravel(), 1)
     seg = np.concatenate([[0], np.cumsum(counts)]).astype(np.uint32)
+    # same order as the kernel: fp64 sums over quarters of 64 inputs, ((q0 + q1) + q2) + q3 per block of
+    # 256 inputs, the blocks added in order, rounded once to fp32
     bias_sum = np.zeros(n_out, dtype=np.float64)
-    for i in range(n_in):                                                  # same order as the kernel: i upwards
-        bias_sum += P.bias[i].astype(np.float64)
+    b64 = _bias_f64(P)
+    for r0 in range(0, n_in, 256):
+        quarters = []
+        for q0 in range(r0, r0 + 256, 64):
+            acc = np.zeros(n_out, dtype=np.float64)
+            for i in range(q0, min(q0 + 64, n_in)):
+                acc += b64[i]
+            quarters.append(acc)
+        bias_sum += ((quarters[0] + quarters[1]) + quarters[2]) + quarters[3]
     return (seg, bias_sum.astype(np.float32), ii.ravel()[order].astype(np.uint16),
             (idx.ravel()[order] % rows).astype(np.uint16), P.gain.ravel()[order])
 
@@ -75,6 +89,9 @@ def _read_layout(buf, P):
         o += w * 32
     o = (o + 32 + 255) // 256 * 256
     o += up(5 * (nb + 1) * 4)
+    # scratch of the preparation: edges per (row block of 256 inputs, bucket, output) as u16, bias sums per row block as fp64
+    n_rb = (n_in + 255) // 256
+    o += up(n_rb * nb * n_out * 2) + up(n_rb * n_out * 8)
     assert o == raw.size
     _read_layout.tables = tables
     return seg, bias, pi, pq, pg

@@ -80,6 +80,7 @@ def test_q8_prepared_layout_and_bias_sums(kb):
     pg = raw[o:o + E]; o += up(E)
     tab_w = [max(256 // (t + 1), nb) for t in range(4)] + [nb]          # block tables, then per-bucket block counts
     o += up(sum(tab_w) * 32) + up(5 * (nb + 1) * 4)
+    o += up(1 * nb * 40 * 2) + up(1 * 40 * 8)          # the preparation's scratch: counts and bias sums per block of 256 inputs
     assert o == raw.size
     bucket = P.idx.astype(np.int64) // 8192
     ii, jj = np.meshgrid(np.arange(130), np.arange(40), indexing="ij")
