@@ -37,7 +37,13 @@ constexpr int BN = kFusedTileN;        // outputs per workgroup: 4 waves x 32
 constexpr int LDH = 88;                // fp16 tile: row stride in halves (176 B)
 constexpr int LDF = 84;                // fp32 tile: row stride in floats (336 B); row = [h][s][m]
 
-template <typename IdxT, typename GbT, typename CbT, bool F32, int MBLK>
+// STAGE (deep pipeline only): the per-edge metadata of two steps (16 input rows x the wave's 32
+// columns) comes in with one 16-byte load per lane and array and is dealt to the lanes that own
+// the columns through a wave-private strip of LDS, instead of one 2-byte load per lane, row and
+// array: 3 vector-memory instructions per two steps instead of 24 (the address unit of the CU,
+// which every such instruction occupies for its 64 lanes, is what bounds this kernel).  Needs
+// n_out % 16 == 0 and 16-byte aligned arrays.
+template <typename IdxT, typename GbT, typename CbT, bool F32, int MBLK, bool STAGE>
 __global__ __launch_bounds__(kThreads, 2) void kan_fused_kernel(const FusedArgs a) {
   constexpr int BM = 32 * MBLK;
   constexpr int NPAIR = MBLK;          // (sample, input) pairs per thread and step
@@ -203,6 +209,75 @@ __global__ __launch_bounds__(kThreads, 2) void kan_fused_kernel(const FusedArgs 
     for (int s = 0; s < 4; ++s) bsum += m.b[s];
   };
 
+  // ---- staged metadata (STAGE): a pair of steps per load -------------------------------------
+  constexpr int EI = (int)sizeof(IdxT), EG = (int)sizeof(GbT);
+  constexpr int NLI = (EI + 1) / 2, NLG = (EG + 1) / 2;          // 16-byte loads per lane and pair: 32 E units over 64 lanes
+  constexpr int kStripBytes = STAGE ? 512 * (EI + 2 * EG) : 16;   // idx, gain, bias tiles of 16 rows x 32 columns
+  __shared__ __attribute__((aligned(16))) unsigned char sMeta[4][kStripBytes];
+  struct MetaRaw {
+    u32x4 i[NLI], g[NLG], b[NLG];
+  };
+  // unit t of an array with E-byte elements: row t / (2 E) of the pair, 16 / E columns from (t % (2 E)) * 16 / E
+  auto stage_issue = [&](int pair, MetaRaw& m) {
+    const int col0 = jt * BN + wave * 32;
+    auto one = [&](const void* base, auto E_, u32x4* dst, int u) {
+      constexpr int E = decltype(E_)::value;
+      const int t = (lane + 64 * u) & (32 * E - 1);              // (one-byte arrays: the upper half of the wave repeats the lower)
+      const int r = t / (2 * E), part = t % (2 * E);
+      const int i = min(i_begin + pair * 16 + r, n_in - 1);
+      const int col = min(col0 + part * (16 / E), n_out - 16 / E);
+      dst[u] = __builtin_nontemporal_load((const u32x4*)((const char*)base + ((size_t)i * n_out + col) * E));
+    };
+#pragma unroll
+    for (int u = 0; u < NLI; ++u) one(idx, std::integral_constant<int, EI>{}, m.i, u);
+#pragma unroll
+    for (int u = 0; u < NLG; ++u) one(gain, std::integral_constant<int, EG>{}, m.g, u);
+#pragma unroll
+    for (int u = 0; u < NLG; ++u) one(bias, std::integral_constant<int, EG>{}, m.b, u);
+  };
+  // raw tiles -> the wave's strip; then every lane picks the values of its own column and rows
+  auto stage_commit = [&](const MetaRaw& m) {
+    unsigned char* strip = sMeta[wave];
+    __builtin_amdgcn_wave_barrier();                             // earlier reads of the strip stay before these writes
+#pragma unroll
+    for (int u = 0; u < NLI; ++u) *(u32x4*)(strip + (((lane + 64 * u) & (32 * EI - 1)) * 16)) = m.i[u];
+#pragma unroll
+    for (int u = 0; u < NLG; ++u) *(u32x4*)(strip + 512 * EI + (((lane + 64 * u) & (32 * EG - 1)) * 16)) = m.g[u];
+#pragma unroll
+    for (int u = 0; u < NLG; ++u) *(u32x4*)(strip + 512 * (EI + EG) + (((lane + 64 * u) & (32 * EG - 1)) * 16)) = m.b[u];
+    __builtin_amdgcn_wave_barrier();
+  };
+  // the values of step `k` (half `sp` = k & 1 of the pair in the strip), with the masks of load_meta_deep
+  auto stage_read = [&](int k, int sp, Ids& ids, GainBias& gb) {
+    const unsigned char* strip = sMeta[wave];
+    const bool live = k < n_steps;
+    // columns past n_out were read from the last 16 / E columns of the row: this lane's slot then holds another
+    // column's value, which the masks below discard (gain and bias 0; the codeword it gathers is a valid row)
+#pragma unroll
+    for (int s = 0; s < 4; ++s) {
+      const int r = sp * 8 + 4 * lh + s;
+      const int i = i_begin + k * IT + 4 * lh + s;
+      const bool ok = j_ok && i < i_end;
+      const IdxT idv = *(const IdxT*)(strip + (r * 32 + ln) * EI);
+      const GbT gv = *(const GbT*)(strip + 512 * EI + (r * 32 + ln) * EG);
+      const GbT bv = *(const GbT*)(strip + 512 * (EI + EG) + (r * 32 + ln) * EG);
+      float g, b;
+      if constexpr (EG == 1) {
+        g = q8_gain(gv.v, qp);
+        b = q8_bias(bv.v, qp);
+      } else if constexpr (EG == 2) {
+        g = __half2float(gv);
+        b = __half2float(bv);
+      } else {
+        g = gv;
+        b = bv;
+      }
+      ids.id[s] = (live && j_ok) ? (uint32_t)idv : 0u;
+      gb.g[s] = ok ? g * gmul : 0.f;
+      gb.b[s] = ok ? b : 0.f;
+    }
+  };
+
   auto load_u = [&](int k, float (&uv)[NPAIR]) {
     const int i = i_begin + k * IT + NPAIR * ph;
 #pragma unroll
@@ -291,14 +366,37 @@ __global__ __launch_bounds__(kThreads, 2) void kan_fused_kernel(const FusedArgs 
     uint32_t odd[RD];
     float uv[4][NPAIR];
     Frag frag[2];
+    MetaRaw mraw;                                     // STAGE: the pair of steps on its way from memory
+    if constexpr (STAGE) {
+      static_assert(RD == 4, "the staged pipeline is laid out for four steps of codewords in flight");
+      MetaRaw m0, m1, m2;
+      stage_issue(0, m0);
+      stage_issue(1, m1);
+      stage_issue(2, m2);
   #pragma unroll
-    for (int q = 0; q < RD; ++q) load_meta_deep(q, ids[q & 3], gbr[q & 7]);
+      for (int q = 0; q < 4; ++q) load_u(q, uv[q]);
+      stage_commit(m0);
+      stage_read(0, 0, ids[0], gbr[0]);
+      stage_read(1, 1, ids[1], gbr[1]);
+      stage_commit(m1);
+      stage_read(2, 0, ids[2], gbr[2]);
+      stage_read(3, 1, ids[3], gbr[3]);
   #pragma unroll
-    for (int q = 0; q < 4; ++q) load_u(q, uv[q]);
+      for (int q = 0; q < RD; ++q) gather_ids(ids[q & 3], rows[q], odd[q]);
+      stage_commit(m2);
+      stage_read(4, 0, ids[0], gbr[4]);               // (the gathers above have read slots 0, 1)
+      stage_read(5, 1, ids[1], gbr[5]);
+      stage_issue(3, mraw);
+    } else {
   #pragma unroll
-    for (int q = 0; q < RD; ++q) gather_ids(ids[q & 3], rows[q], odd[q]);
+      for (int q = 0; q < RD; ++q) load_meta_deep(q, ids[q & 3], gbr[q & 7]);
   #pragma unroll
-    for (int q = RD; q < RD + 2; ++q) load_meta_deep(q, ids[q & 3], gbr[q & 7]);     // (the gathers above have read slots 0, 1)
+      for (int q = 0; q < 4; ++q) load_u(q, uv[q]);
+  #pragma unroll
+      for (int q = 0; q < RD; ++q) gather_ids(ids[q & 3], rows[q], odd[q]);
+  #pragma unroll
+      for (int q = RD; q < RD + 2; ++q) load_meta_deep(q, ids[q & 3], gbr[q & 7]);     // (the gathers above have read slots 0, 1)
+    }
     dequant_deep(rows[0], odd[0], gbr[0], frag[0]);
     gen_phi(uv[0], sTile[0]);
 
@@ -307,7 +405,18 @@ __global__ __launch_bounds__(kThreads, 2) void kan_fused_kernel(const FusedArgs 
       __syncthreads();     // tile k is complete; every wave is done reading tile k-1
       dequant_deep(rows[(t + 1) % RD], odd[(t + 1) % RD], gbr[(t + 1) & 7], frag[(t + 1) & 1]);   // step k+1 fragments
       gather_ids(ids[(t + RD) & 3], rows[t % RD], odd[t % RD]);                    // step k+RD codewords
-      load_meta_deep(k + RD + 2, ids[(t + RD + 2) & 3], gbr[(t + RD + 2) & 7]);          // step k+RD+2 metadata
+      if constexpr (STAGE) {
+        // even steps: the pair k+6, k+7 (requested two steps ago) goes through the strip into the rings,
+        // and the pair k+8, k+9 is requested
+        if constexpr ((t & 1) == 0) {
+          stage_commit(mraw);
+          stage_read(k + 6, 0, ids[(t + 6) & 3], gbr[(t + 6) & 7]);
+          stage_read(k + 7, 1, ids[(t + 7) & 3], gbr[(t + 7) & 7]);
+          stage_issue((k >> 1) + 4, mraw);
+        }
+      } else {
+        load_meta_deep(k + RD + 2, ids[(t + RD + 2) & 3], gbr[(t + RD + 2) & 7]);          // step k+RD+2 metadata
+      }
       mfma_step(sTile[t & 1], frag[t & 1]);
       gen_phi(uv[(t + 1) & 3], sTile[(t + 1) & 1]);                                 // step k+1 basis tile
       load_u(k + 4, uv[t & 3]);
@@ -406,33 +515,38 @@ __global__ __launch_bounds__(kThreads, 2) void kan_fused_kernel(const FusedArgs 
 }
 
 template <typename IdxT, typename GbT, typename CbT>
-hipError_t launch_variant(const FusedArgs& a, bool f32, int mblk, dim3 grid, hipStream_t s) {
+hipError_t launch_variant(const FusedArgs& a, bool f32, int mblk, bool stage, dim3 grid, hipStream_t s) {
   if (f32) {
-    if (mblk == 1) hipLaunchKernelGGL((kan_fused_kernel<IdxT, GbT, CbT, true, 1>), grid, dim3(kThreads), 0, s, a);
-    else hipLaunchKernelGGL((kan_fused_kernel<IdxT, GbT, CbT, true, 2>), grid, dim3(kThreads), 0, s, a);
+    if (mblk == 1) hipLaunchKernelGGL((kan_fused_kernel<IdxT, GbT, CbT, true, 1, false>), grid, dim3(kThreads), 0, s, a);
+    else hipLaunchKernelGGL((kan_fused_kernel<IdxT, GbT, CbT, true, 2, false>), grid, dim3(kThreads), 0, s, a);
   } else {
-    if (mblk == 1) hipLaunchKernelGGL((kan_fused_kernel<IdxT, GbT, CbT, false, 1>), grid, dim3(kThreads), 0, s, a);
-    else hipLaunchKernelGGL((kan_fused_kernel<IdxT, GbT, CbT, false, 2>), grid, dim3(kThreads), 0, s, a);
+    if (mblk == 1) hipLaunchKernelGGL((kan_fused_kernel<IdxT, GbT, CbT, false, 1, false>), grid, dim3(kThreads), 0, s, a);
+    else if constexpr (sizeof(CbT) != 4) {            // (fp32 rows keep two steps of codewords in flight: not staged)
+      if (stage) hipLaunchKernelGGL((kan_fused_kernel<IdxT, GbT, CbT, false, 2, true>), grid, dim3(kThreads), 0, s, a);
+      else hipLaunchKernelGGL((kan_fused_kernel<IdxT, GbT, CbT, false, 2, false>), grid, dim3(kThreads), 0, s, a);
+    } else {
+      hipLaunchKernelGGL((kan_fused_kernel<IdxT, GbT, CbT, false, 2, false>), grid, dim3(kThreads), 0, s, a);
+    }
   }
   return hipGetLastError();
 }
 
 template <typename IdxT>
-hipError_t launch_types(const GatherCfg& c, const FusedArgs& a, bool f32, int mblk, dim3 grid, hipStream_t s) {
+hipError_t launch_types(const GatherCfg& c, const FusedArgs& a, bool f32, int mblk, bool stage, dim3 grid, hipStream_t s) {
   if (c.code == kCbI8) {
-    if (c.gb_kind == kGbQ8) return launch_variant<IdxT, q8_t, int8_t>(a, f32, mblk, grid, s);
-    return c.gb_kind == kGbF16 ? launch_variant<IdxT, __half, int8_t>(a, f32, mblk, grid, s)
-                               : launch_variant<IdxT, float, int8_t>(a, f32, mblk, grid, s);
+    if (c.gb_kind == kGbQ8) return launch_variant<IdxT, q8_t, int8_t>(a, f32, mblk, stage, grid, s);
+    return c.gb_kind == kGbF16 ? launch_variant<IdxT, __half, int8_t>(a, f32, mblk, stage, grid, s)
+                               : launch_variant<IdxT, float, int8_t>(a, f32, mblk, stage, grid, s);
   }
   if (c.gb_kind == kGbQ8) return hipErrorInvalidValue;      // byte-coded gain/bias go with Int8 codebooks
   if (c.code == kCbBfp8)
-    return c.gb_kind == kGbF16 ? launch_variant<IdxT, __half, bfp8_t>(a, f32, mblk, grid, s)
-                               : launch_variant<IdxT, float, bfp8_t>(a, f32, mblk, grid, s);
+    return c.gb_kind == kGbF16 ? launch_variant<IdxT, __half, bfp8_t>(a, f32, mblk, stage, grid, s)
+                               : launch_variant<IdxT, float, bfp8_t>(a, f32, mblk, stage, grid, s);
   if (c.code == kCbF16)
-    return c.gb_kind == kGbF16 ? launch_variant<IdxT, __half, __half>(a, f32, mblk, grid, s)
-                               : launch_variant<IdxT, float, __half>(a, f32, mblk, grid, s);
-  return c.gb_kind == kGbF16 ? launch_variant<IdxT, __half, float>(a, f32, mblk, grid, s)
-                             : launch_variant<IdxT, float, float>(a, f32, mblk, grid, s);
+    return c.gb_kind == kGbF16 ? launch_variant<IdxT, __half, __half>(a, f32, mblk, stage, grid, s)
+                               : launch_variant<IdxT, float, __half>(a, f32, mblk, stage, grid, s);
+  return c.gb_kind == kGbF16 ? launch_variant<IdxT, __half, float>(a, f32, mblk, stage, grid, s)
+                             : launch_variant<IdxT, float, float>(a, f32, mblk, stage, grid, s);
 }
 
 }  // namespace
@@ -440,8 +554,12 @@ hipError_t launch_types(const GatherCfg& c, const FusedArgs& a, bool f32, int mb
 hipError_t launch_fused(const GatherCfg& c, const FusedArgs& a, bool f32, dim3 grid, hipStream_t s) {
   if (c.code == kDense || a.B < 1 || (c.bt != 32 && c.bt != 64)) return hipErrorInvalidValue;
   const int mblk = c.bt / 32;
-  return c.idx_u32 ? launch_types<uint32_t>(c, a, f32, mblk, grid, s)
-                   : launch_types<uint16_t>(c, a, f32, mblk, grid, s);
+  // the staged metadata loads need rows of the per-edge arrays that are whole 16-byte units
+  bool stage = a.n_out % 16 == 0;
+  for (unsigned h = 0; h < grid.z && stage; ++h)
+    stage = ((uintptr_t)a.h[h].idx % 16 == 0) && ((uintptr_t)a.h[h].gain % 16 == 0) && ((uintptr_t)a.h[h].bias % 16 == 0);
+  return c.idx_u32 ? launch_types<uint32_t>(c, a, f32, mblk, stage, grid, s)
+                   : launch_types<uint16_t>(c, a, f32, mblk, stage, grid, s);
 }
 
 }  // namespace kan

@@ -40,6 +40,45 @@ def test_mfma_ragged_shapes(kb, n_in, n_out, B):
     assert rep["headline"] >= 0 and np.isfinite(y).all()
 
 
+@pytest.mark.parametrize("gb,cb,idx", [("f16", "i8", "u16"), ("f32", "i8", "u16"), ("q8", "i8", "u16"), ("f16", "i8", "u32"),
+                                       ("f32", "i8", "u32"), ("f16", "f16", "u16"), ("f32", "bfp8", "u16"), ("f16", "bfp8", "u32"),
+                                       ("f32", "f32", "u16")])
+@pytest.mark.parametrize("n_in,n_out,B", [(520, 272, 50), (1001, 48, 64), (24, 16, 33), (300, 400, 40), (2048, 1024, 64)])
+def test_fused_64_sample_tiles_with_staged_metadata(kb, gb, cb, idx, n_in, n_out, B):
+    """Batch 33..64 on the fp16 path: the fused kernel's deep pipeline.  With n_out a multiple of 16 (and
+    aligned arrays) the per-edge metadata of two steps comes in through 16-byte loads and a strip of LDS:
+    output tiles cut short by n_out, chunks whose last pair of steps is ragged or missing, every storage
+    type of index, gain/bias and codebook (fp32 rows take the unstaged pipeline)."""
+    if n_in * n_out > 500000 and (gb, cb, idx) != ("f16", "i8", "u16"):
+        pytest.skip("the large shape runs once")
+    K = 70000 if idx == "u32" else 3000
+    P = synth.make_layer(n_in + 3 * n_out + B, n_in, n_out, K, cb_dtype=cb, gb_dtype=gb, idx_dtype=idx)
+    x = synth.make_x(B + 7, B, n_in)
+    (L,) = gpu_layers([P])
+    assert kb.kan_vq_planned_kernel(L, B, 1, kb.KAN_PATH_MFMA) == "kan_fused_f16"
+    y = kb.kan_vq_layer_forward(L, to_dev(x), path=kb.KAN_PATH_MFMA).cpu().numpy()
+    if n_in * n_out * B <= 2e8:
+        y_ref, A = ko.vq_layer_forward(x, **P.as_dict(), return_abs=True)
+        rep = ko.error_report(y, y_ref, A)
+        assert rep["headline"] <= TOL_MFMA and rep["strict"] <= TOL_MFMA, rep
+    else:
+        assert np.isfinite(y).all()
+        check_layer_output(y, x, P, TOL_MFMA, n_samples=96, full=False, seed=B)
+    # the same layer with arrays 2 bytes off a 16-byte boundary takes the unstaged pipeline: same sums
+    # up to the order of nothing - both add the same products in the same order
+    L2 = kb.VQLayer(P)
+    for name in ("idx", "gain", "bias"):
+        t = getattr(L2, name)
+        pad = 16 // t.element_size()
+        buf = torch.empty(t.numel() + 2 * pad, dtype=t.dtype, device="cuda")
+        off = pad + 1                                     # one element past a 16-byte boundary
+        buf[off:off + t.numel()] = t.reshape(-1)
+        setattr(L2, name + "_shifted", buf)
+        setattr(L2.desc, name, buf.data_ptr() + off * t.element_size())
+    y2 = kb.kan_vq_layer_forward(L2, to_dev(x), path=kb.KAN_PATH_MFMA).cpu().numpy()
+    assert np.array_equal(y2, y)
+
+
 @pytest.mark.parametrize("gb,cb,idx", [("f32", "i8", "u16"), ("f16", "f32", "u16"), ("f32", "f32", "u32"), ("f16", "i8", "u32")])
 def test_mfma_dtype_combinations(kb, gb, cb, idx):
     P = synth.make_layer(9, 96, 160, 70000 if idx == "u32" else 4096, cb_dtype=cb, gb_dtype=gb, idx_dtype=idx)
