@@ -10,14 +10,17 @@
 // steps ahead and codewords one step ahead through small register rings.  The work is
 // bound by the rate of random codeword gathers (one per edge), not by arithmetic.
 //
-// Two operand precisions:
-//   F32 = false  fp16 operands, v_mfma_f32_32x32x16_f16, same k order as kan_mfma.hip
-//                (k-step s < 4, lane half h: coefficients 0..7 of input 4h+s; k-step 4:
-//                coefficients 8, 9 of inputs 4h..4h+3); Int8 scale applied at the end.
-//   F32 = true   fp32 operands, v_mfma_f32_32x32x2f32: MFMA t = 10*s + m multiplies, in
-//                lane half h, coefficient m of input 4h+s; products and sums are fp32,
-//                so the result matches the float64 definition to ~1e-6 and this kernel
-//                serves the precise path for every batch >= 2.
+// Operand precisions (fp16 forms: v_mfma_f32_32x32x16_f16 with k-step s < 4, lane half h:
+// coefficients 0..7 of input 4h+s; k-step 4: coefficients 8, 9 of inputs 4h..4h+3):
+//   F32 = false  fp16 operands; the Int8 scale is applied at the end.
+//   F32 = true   the precise path (sums match the float64 definition to ~1e-6), in two forms:
+//     32-sample tiles: fp32 operands, v_mfma_f32_32x32x2f32: MFMA t = 10*s + m multiplies, in
+//                lane half h, coefficient m of input 4h+s.  With one row block the 40 MFMAs of a
+//                step take about as long as its gathers.
+//     64-sample tiles: both operands split into high and low fp16 parts (v = hi + lo / 2048,
+//                22 significant bits), three fp16 products per k-step (hi*lo and lo*hi into one
+//                set of accumulators, hi*hi into another); every fp16 x fp16 product is exact in
+//                the fp32 accumulators: a fifth of the matrix-pipe time of fp32 operands.
 // Workgroup: 256 threads = 4 waves, each 32 output columns; tile of 32*MBLK samples.
 // The basis tile Phi is built in LDS (double buffered) straight from x: with at most 64
 // samples the strided reads of x are few, and no preparation kernel is launched.
@@ -47,10 +50,16 @@ template <typename IdxT, typename GbT, typename CbT, bool F32, int MBLK, bool ST
 __global__ __launch_bounds__(kThreads, 2) void kan_fused_kernel(const FusedArgs a) {
   constexpr int BM = 32 * MBLK;
   constexpr int NPAIR = MBLK;          // (sample, input) pairs per thread and step
-  constexpr int kTileBytes = F32 ? BM * LDF * 4 : BM * LDH * 2;
+  // The precise path comes in two forms: fp32 operands for 32-sample tiles (one row block: the 40 fp32
+  // MFMAs of a step take about as long as its gathers, and nothing has to be split), split fp16 operands
+  // for 64-sample tiles (two row blocks: a fifth of the matrix-pipe time).
+  constexpr bool kFp32Ops = F32 && MBLK == 1;
+  constexpr bool kSplit = F32 && MBLK == 2;
+  constexpr int kHalfTile = BM * LDH * 2;                       // one fp16 tile
+  constexpr int kTileBytes = kFp32Ops ? BM * LDF * 4 : (kSplit ? 2 * kHalfTile : kHalfTile);   // split form: high parts, then low parts
   __shared__ __attribute__((aligned(16))) unsigned char sTile[2][kTileBytes];
   __shared__ __attribute__((aligned(16))) uint32_t sSel[kSpans][8];
-  if constexpr (!F32) fill_weight_selectors(sSel, threadIdx.x);
+  if constexpr (!kFp32Ops) fill_weight_selectors(sSel, threadIdx.x);
   __syncthreads();
 
   const int tid = threadIdx.x;
@@ -86,7 +95,7 @@ __global__ __launch_bounds__(kThreads, 2) void kan_fused_kernel(const FusedArgs 
   const Q8Params qp = {hp.gain_log2_lo, hp.gain_log2_step, hp.bias_scale};
   const CbT* cb = (const CbT*)hp.cb;
   const float scale = sizeof(CbT) == 1 ? hp.scale : 1.0f;
-  const float gmul = F32 ? scale : 1.0f;        // fp32 operands carry the scale themselves
+  const float gmul = F32 ? scale : 1.0f;        // the precise form's coefficients carry the scale themselves
   const float* xh = a.x + (long long)head * a.x_head_stride;
 
   // Phi generation: sample row pb, inputs NPAIR*ph .. of every step
@@ -97,11 +106,14 @@ __global__ __launch_bounds__(kThreads, 2) void kan_fused_kernel(const FusedArgs 
   const bool j_ok = j < n_out;
   const int jc = min(j, n_out - 1);
 
-  f32x16 acc[MBLK];
+  f32x16 acc[MBLK], acc_x[MBLK];       // (acc_x: the cross products of the split form)
 #pragma unroll
   for (int m = 0; m < MBLK; ++m)
 #pragma unroll
-    for (int r = 0; r < 16; ++r) acc[m][r] = 0.f;
+    for (int r = 0; r < 16; ++r) {
+      acc[m][r] = 0.f;
+      acc_x[m][r] = 0.f;
+    }
   float bsum = 0.f;
 
   struct Meta {
@@ -109,8 +121,24 @@ __global__ __launch_bounds__(kThreads, 2) void kan_fused_kernel(const FusedArgs 
     float g[4], b[4];
   };
   struct Frag {                         // B operand of one step
-    uint4 h[F32 ? 1 : 5];               // fp16: 5 k-steps of 8 halves
-    float f[F32 ? 4 : 1][kG];           // fp32: [s][m]
+    uint4 h[kFp32Ops ? 1 : 5];          // 5 k-steps of 8 halves (split form: the high parts)
+    uint4 l[kSplit ? 5 : 1];            // split form: the low parts
+    float f[kFp32Ops ? 4 : 1][kG];      // fp32 operands: [s][m]
+  };
+  // fp32 coefficients of the four rows of a step -> high and low fragments
+  auto split_step = [&](const float (&c)[4][kG], Frag& out) {
+    uint32_t th[4], tl[4];
+#pragma unroll
+    for (int s = 0; s < 4; ++s) {
+      uint32_t hi[5], lo[5];
+      split_consecutive(c[s], hi, lo);
+      out.h[kSplit ? s : 0] = make_uint4(hi[0], hi[1], hi[2], hi[3]);
+      out.l[kSplit ? s : 0] = make_uint4(lo[0], lo[1], lo[2], lo[3]);
+      th[s] = hi[4];
+      tl[s] = lo[4];
+    }
+    out.h[kSplit ? 4 : 0] = make_uint4(th[0], th[1], th[2], th[3]);
+    out.l[kSplit ? 4 : 0] = make_uint4(tl[0], tl[1], tl[2], tl[3]);
   };
 
   auto load_meta = [&](int k, Meta& m) {
@@ -136,9 +164,14 @@ __global__ __launch_bounds__(kThreads, 2) void kan_fused_kernel(const FusedArgs 
   auto dequant_step = [&](RawRow<CbT> (&rows)[4], const Meta& m, Frag& out) {
 #pragma unroll
     for (int s = 0; s < 4; ++s) align_row<CbT>(rows[s], row_odd<CbT>(cb, m.id[s]));
-    if constexpr (F32) {
+    if constexpr (kFp32Ops) {
 #pragma unroll
       for (int s = 0; s < 4; ++s) dequant_row_f32<CbT>(rows[s], m.g[s], out.f[s]);
+    } else if constexpr (kSplit) {
+      float c[4][kG];
+#pragma unroll
+      for (int s = 0; s < 4; ++s) dequant_row_f32<CbT>(rows[s], m.g[s], c[s]);
+      split_step(c, out);
     } else {
       uint32_t tail[4];
 #pragma unroll
@@ -191,9 +224,14 @@ __global__ __launch_bounds__(kThreads, 2) void kan_fused_kernel(const FusedArgs 
   auto dequant_deep = [&](RawRow<CbT> (&rows)[4], const uint32_t odd, const GainBias& m, Frag& out) {
 #pragma unroll
     for (int s = 0; s < 4; ++s) align_row<CbT>(rows[s], (odd >> s) & 1u);
-    if constexpr (F32) {
+    if constexpr (kFp32Ops) {
 #pragma unroll
       for (int s = 0; s < 4; ++s) dequant_row_f32<CbT>(rows[s], m.g[s], out.f[s]);
+    } else if constexpr (kSplit) {
+      float c[4][kG];
+#pragma unroll
+      for (int s = 0; s < 4; ++s) dequant_row_f32<CbT>(rows[s], m.g[s], c[s]);
+      split_step(c, out);
     } else {
       uint32_t tail[4];
 #pragma unroll
@@ -290,7 +328,7 @@ __global__ __launch_bounds__(kThreads, 2) void kan_fused_kernel(const FusedArgs 
       const BasisW bw = basis_fast(uv[q], a.rule);
       const int l = bw.span;
       const float w0 = bw.w0, w1 = bw.w1, w2 = bw.w2, w3 = bw.w3;
-      if constexpr (F32) {
+      if constexpr (kFp32Ops) {
         float* p = (float*)tile + pb * LDF + h * 40 + s * kG;      // 8-byte aligned
         const float2 z = make_float2(0.f, 0.f);
 #pragma unroll
@@ -299,49 +337,65 @@ __global__ __launch_bounds__(kThreads, 2) void kan_fused_kernel(const FusedArgs 
         p[l + 1] = w1;
         p[l + 2] = w2;
         p[l + 3] = w3;
+        continue;
+      }
+      uint32_t w01, w23, l01 = 0u, l23 = 0u;
+      if constexpr (kSplit) {
+        split_weights(w0, w1, w01, l01);
+        split_weights(w2, w3, w23, l23);
       } else {
-        const uint32_t w01 = pack_h2(w0, w1), w23 = pack_h2(w2, w3);
-        const uint4 sl = *(const uint4*)&sSel[l][0];
-        const uint32_t sh = sSel[l][4];
+        w01 = pack_h2(w0, w1);
+        w23 = pack_h2(w2, w3);
+      }
+      const uint4 sl = *(const uint4*)&sSel[l][0];
+      const uint32_t sh = sSel[l][4];
+      auto place = [&](uint32_t a01, uint32_t a23, unsigned char* t) {
         uint4 lo;
-        lo.x = __builtin_amdgcn_perm(w23, w01, sl.x);
-        lo.y = __builtin_amdgcn_perm(w23, w01, sl.y);
-        lo.z = __builtin_amdgcn_perm(w23, w01, sl.z);
-        lo.w = __builtin_amdgcn_perm(w23, w01, sl.w);
-        const uint32_t hi = __builtin_amdgcn_perm(w23, w01, sh);
-        uint16_t* rowp = (uint16_t*)tile + pb * LDH;
+        lo.x = __builtin_amdgcn_perm(a23, a01, sl.x);
+        lo.y = __builtin_amdgcn_perm(a23, a01, sl.y);
+        lo.z = __builtin_amdgcn_perm(a23, a01, sl.z);
+        lo.w = __builtin_amdgcn_perm(a23, a01, sl.w);
+        const uint32_t hi = __builtin_amdgcn_perm(a23, a01, sh);
+        uint16_t* rowp = (uint16_t*)t + pb * LDH;
         *(uint4*)(rowp + 16 * s + 8 * h) = lo;
         *(uint32_t*)(rowp + 64 + 8 * h + 2 * s) = hi;
-      }
+      };
+      place(w01, w23, tile);
+      if constexpr (kSplit) place(l01, l23, tile + kHalfTile);
     }
   };
 
+  // Precise form: cross products (high x low, low x high; they carry a factor 2048) into acc_x,
+  // the main product into acc; every fp16 x fp16 product is exact in the fp32 accumulators.
   auto mfma_step = [&](const unsigned char* tile, const Frag& bf) {
-    if constexpr (F32) {
+    if constexpr (kFp32Ops) {       // MFMA t = 10 s + m multiplies, in lane half h, coefficient m of input 4h + s
+      const float* p = (const float*)tile + ln * LDF + lh * 40;
 #pragma unroll
-      for (int m = 0; m < MBLK; ++m) {
-        const float* p = (const float*)tile + (m * 32 + ln) * LDF + lh * 40;
+      for (int q = 0; q < 10; ++q) {
+        const float4 av = *(const float4*)(p + 4 * q);       // slots 4q .. 4q+3 of [s][m]
+        const float avs[4] = {av.x, av.y, av.z, av.w};
 #pragma unroll
-        for (int q = 0; q < 10; ++q) {
-          const float4 av = *(const float4*)(p + 4 * q);       // slots 4q .. 4q+3 of [s][m]
-          const float avs[4] = {av.x, av.y, av.z, av.w};
-#pragma unroll
-          for (int e = 0; e < 4; ++e) {
-            const int t = 4 * q + e;
-            acc[m] = __builtin_amdgcn_mfma_f32_32x32x2f32(avs[e], bf.f[t / kG][t % kG], acc[m], 0, 0, 0);
-          }
+        for (int e = 0; e < 4; ++e) {
+          const int t = 4 * q + e;
+          acc[0] = __builtin_amdgcn_mfma_f32_32x32x2f32(avs[e], bf.f[kFp32Ops ? t / kG : 0][t % kG], acc[0], 0, 0, 0);
         }
       }
-    } else {
+      return;
+    }
 #pragma unroll
-      for (int ks = 0; ks < 5; ++ks) {
-        const h16x8 fb = __builtin_bit_cast(h16x8, bf.h[ks]);
+    for (int ks = 0; ks < 5; ++ks) {
+      const h16x8 fb = __builtin_bit_cast(h16x8, bf.h[kFp32Ops ? 0 : ks]);
 #pragma unroll
-        for (int m = 0; m < MBLK; ++m) {
-          const h16x8 fa = __builtin_bit_cast(
-              h16x8, *(const uint4*)((const uint16_t*)tile + (m * 32 + ln) * LDH + ks * 16 + lh * 8));
-          acc[m] = __builtin_amdgcn_mfma_f32_32x32x16_f16(fa, fb, acc[m], 0, 0, 0);
+      for (int m = 0; m < MBLK; ++m) {
+        const uint16_t* ap = (const uint16_t*)tile + (m * 32 + ln) * LDH + ks * 16 + lh * 8;
+        const h16x8 fa = __builtin_bit_cast(h16x8, *(const uint4*)ap);
+        if constexpr (kSplit) {
+          const h16x8 fbl = __builtin_bit_cast(h16x8, bf.l[kSplit ? ks : 0]);
+          const h16x8 fal = __builtin_bit_cast(h16x8, *(const uint4*)(ap + kHalfTile / 2));
+          acc_x[m] = __builtin_amdgcn_mfma_f32_32x32x16_f16(fa, fbl, acc_x[m], 0, 0, 0);
+          acc_x[m] = __builtin_amdgcn_mfma_f32_32x32x16_f16(fal, fb, acc_x[m], 0, 0, 0);
         }
+        acc[m] = __builtin_amdgcn_mfma_f32_32x32x16_f16(fa, fb, acc[m], 0, 0, 0);
       }
     }
   };
@@ -349,7 +403,7 @@ __global__ __launch_bounds__(kThreads, 2) void kan_fused_kernel(const FusedArgs 
   // Two pipelines.  The deep one pays off where a step holds enough MFMA work and chunks are
   // long (fp16 operands, 64-sample tiles: 66.7 -> 57.7 us for configuration 3 at batch 64);
   // with short chunks its extra prologue loads cost more than they hide (batch 2..16: +2..10 %),
-  // and with fp32 operands the MFMAs of a step already cover the gathers.
+  // and the precise form's three products per k-step already cover the gathers.
   constexpr bool kDeep = !F32 && MBLK == 2;
   if constexpr (kDeep) {
     // ---- pipeline (rings indexed by compile-time slots, loop unrolled by 8) ------------------
@@ -506,7 +560,9 @@ __global__ __launch_bounds__(kThreads, 2) void kan_fused_kernel(const FusedArgs 
       for (int r = 0; r < 16; ++r) {
         const int b = b0 + m * 32 + 8 * (r >> 2) + 4 * lh + (r & 3);
         if (b < B) {
-          float v = fmaf(oscale, acc[m][r], bs);
+          float v;
+          if constexpr (kSplit) v = fmaf(1.0f / 2048.0f, acc_x[m][r], acc[m][r]) + bs;   // (the scale went in with the gains)
+          else v = fmaf(oscale, acc[m][r], bs);
           if (a.apply_tanh) v = tanhf(v);
           dst[(long long)b * n_out + jc] = v;
         }

@@ -67,15 +67,6 @@ typedef unsigned int u32x4 __attribute__((ext_vector_type(4)));
 typedef unsigned int u32x2 __attribute__((ext_vector_type(2)));
 typedef _Float16 h16x16 __attribute__((ext_vector_type(16)));
 
-// Both halves of a packed fp16 pair with subnormals set to zero.  The split form does this to
-// its high parts itself, before it forms the low parts from what is left, so that the sum of
-// the parts does not depend on how conversions and matrix instructions treat subnormals.
-__device__ __forceinline__ uint32_t flush_h2(uint32_t v) {
-  if ((v & 0x7c00u) == 0u) v &= 0xffff8000u;
-  if ((v & 0x7c000000u) == 0u) v &= 0x8000ffffu;
-  return v;
-}
-
 // Ten fp32 coefficients as high and low fp16 parts, in pairs (m, m + 5): c = hi + lo / 2048.
 __device__ __forceinline__ void split_pairs(const float (&c)[kG], uint32_t (&hi)[5], uint32_t (&lo)[5]) {
 #pragma unroll

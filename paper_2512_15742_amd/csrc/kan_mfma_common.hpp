@@ -27,6 +27,40 @@ __device__ __forceinline__ uint32_t dq_pair(uint32_t w, h16x2 g2) {
   return __builtin_bit_cast(uint32_t, v);
 }
 
+// Both halves of a packed fp16 pair with subnormals set to zero.  The split form does this to
+// its high parts itself, before it forms the low parts from what is left, so that the sum of
+// the parts does not depend on how conversions and matrix instructions treat subnormals.
+__device__ __forceinline__ uint32_t flush_h2(uint32_t v) {
+  if ((v & 0x7c00u) == 0u) v &= 0xffff8000u;
+  if ((v & 0x7c000000u) == 0u) v &= 0x8000ffffu;
+  return v;
+}
+
+// Split form of the precise path: a number v travels as two fp16 parts, v = hi + lo / 2048 with
+// hi = fp16(v) and lo = fp16((v - hi) * 2048): 22 significant bits; the factor keeps the low
+// parts out of the fp16 subnormals.  Ten coefficients in consecutive pairs (2m, 2m + 1).
+__device__ __forceinline__ void split_consecutive(const float (&c)[kG], uint32_t (&hi)[5], uint32_t (&lo)[5]) {
+#pragma unroll
+  for (int m = 0; m < 5; ++m) {
+    hi[m] = flush_h2(pack_h2(c[2 * m], c[2 * m + 1]));
+    lo[m] = flush_h2(pack_h2((c[2 * m] - half_bits_to_float(hi[m] & 0xffffu)) * 2048.0f,
+                             (c[2 * m + 1] - half_bits_to_float(hi[m] >> 16)) * 2048.0f));
+  }
+}
+
+// A pair of basis weights (never negative) in split form: the high parts cut to fp16 towards zero
+// (so that the low parts are never negative either), no subnormal high parts.
+__device__ __forceinline__ void split_weights(float wa, float wb, uint32_t& hi, uint32_t& lo) {
+  const uint32_t h = pack_h2(wa, wb);
+  uint32_t ha = h & 0xffffu, hb = h >> 16;
+  if (half_bits_to_float(ha) > wa) ha -= 1u;                   // one fp16 step down (w > 0 there)
+  if (half_bits_to_float(hb) > wb) hb -= 1u;
+  if ((ha & 0x7c00u) == 0u) ha = 0u;
+  if ((hb & 0x7c00u) == 0u) hb = 0u;
+  hi = ha | (hb << 16);
+  lo = flush_h2(pack_h2((wa - half_bits_to_float(ha)) * 2048.0f, (wb - half_bits_to_float(hb)) * 2048.0f)) & 0x7fff7fffu;
+}
+
 // Raw codeword of one edge as loaded from the codebook.
 template <typename CbT> struct RawRow;
 template <> struct RawRow<int8_t> { uint32_t a, b, d; };
