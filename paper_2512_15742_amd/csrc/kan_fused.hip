@@ -146,7 +146,7 @@ __global__ __launch_bounds__(kThreads, 2) void kan_fused_kernel(const FusedArgs 
     for (int s = 0; s < 4; ++s) {
       const int i = i_begin + k * IT + 4 * lh + s;
       const bool ok = j_ok && i < i_end;
-      const long long e = (long long)min(i, n_in - 1) * n_out + jc;
+      const long long e = (long long)min(i, i_end - 1) * n_out + jc;
       uint32_t id[1];
       float g[1], bv[1];
       load_idx<IdxT, 1>(idx + e, id);
@@ -193,7 +193,7 @@ __global__ __launch_bounds__(kThreads, 2) void kan_fused_kernel(const FusedArgs 
   struct GainBias { float g[4], b[4]; };
   // Every load of the pipeline is unconditional, so that the compiler counts the loads in
   // flight exactly and a wait covers only what is needed next.  Steps past the end of the
-  // chunk read the layer's last row (coalesced) and gather codeword 0 with every lane (one
+  // chunk read the chunk's last row again (coalesced) and gather codeword 0 with every lane (one
   // cache line per wave instead of 64), which costs next to nothing; their edges have gain 0.
   auto load_meta_deep = [&](int k, Ids& ids, GainBias& gb) {
     const bool live = k < n_steps;
@@ -201,7 +201,7 @@ __global__ __launch_bounds__(kThreads, 2) void kan_fused_kernel(const FusedArgs 
     for (int s = 0; s < 4; ++s) {
       const int i = i_begin + k * IT + 4 * lh + s;
       const bool ok = j_ok && i < i_end;
-      const long long e = (long long)min(i, n_in - 1) * n_out + jc;
+      const long long e = (long long)min(i, i_end - 1) * n_out + jc;
       uint32_t id[1];
       float g[1], bv[1];
       load_idx<IdxT, 1>(idx + e, id);
@@ -262,7 +262,7 @@ __global__ __launch_bounds__(kThreads, 2) void kan_fused_kernel(const FusedArgs 
       constexpr int E = decltype(E_)::value;
       const int t = (lane + 64 * u) & (32 * E - 1);              // (one-byte arrays: the upper half of the wave repeats the lower)
       const int r = t / (2 * E), part = t % (2 * E);
-      const int i = min(i_begin + pair * 16 + r, n_in - 1);
+      const int i = min(i_begin + pair * 16 + r, i_end - 1);      // rows past the chunk re-read its last row
       const int col = min(col0 + part * (16 / E), n_out - 16 / E);
       dst[u] = __builtin_nontemporal_load((const u32x4*)((const char*)base + ((size_t)i * n_out + col) * E));
     };
