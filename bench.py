@@ -461,7 +461,7 @@ def config3_legs(kb, torch, synth, args, path, facts, with_cpu):
     prepare_ms_per_head = 1e3 * (time.perf_counter() - t0) / len(copies)
 
     results = {}
-    batches = sorted({1, args.batch}) if not args.only else [args.batch]
+    batches = sorted({1, 4, 16, args.batch}) if not args.only else [args.batch]
     legs = [(b, b <= 4 and not args.no_prepare) for b in batches]
     if not args.no_prepare and not args.only:
         legs.append((1, False))
@@ -580,8 +580,9 @@ def main():
     }
     if 3 in legs:
         out["batch%d" % args.batch] = legs[3]
-        if 1 in res3:
-            out["batch1"] = res3[1]
+        for b in (1, 4, 16):
+            if b in res3 and b != args.batch:
+                out["batch%d" % b] = res3[b]
         if "1_unprepared" in res3:
             out["batch1_unprepared"] = res3["1_unprepared"]
         out["prepare_ms_per_head"] = extra.get("prepare_ms_per_head")
