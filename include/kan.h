@@ -121,7 +121,7 @@ typedef struct kan_vq_layer {
    * Needs cb_dtype == KAN_I8 (the fully quantised 4-bytes-per-edge format), else
    * KAN_ERR_UNSUPPORTED.  Ignored for the other gain/bias dtypes.                            */
   float gain_log2_lo, gain_log2_step, bias_scale;
-  int32_t reserved;      /* set to 0                                                */
+  int32_t flags;         /* 0, or KAN_LAYER_NO_COLUMN (below, with kan_vq_prepare)    */
   /* KAN_BFP8 codebooks (Table 1 lists a block-floating-point row between FP16 and Int8; the
    * paper defines no format, this is the one used here): a codeword row is one block of 12
    * bytes, 4-byte aligned: ten signed mantissa bytes q[0..9] in -127..127, one signed exponent
@@ -190,6 +190,12 @@ kan_status kan_dense_layer_forward(const float* coef, int32_t in, int32_t out, i
  * serves batches up to 4 from this layout: every workgroup copies one bucket into LDS and
  * streams that bucket's edges, so no lookup leaves the CU.  Values are unchanged (same
  * products, different summation order: within the 1e-5 bound).
+ * A small prepared layer (edges x samples at most 2^20) would leave such a workgroup with little
+ * more than the wait for its bucket; it is served by one workgroup per output and sample instead,
+ * which reads the output's ids and gains from a transposed copy that the buffer of a small layer
+ * also holds, fetches the codeword windows from the L2-resident codebook and writes the finished
+ * output (no partial sums).  KAN_LAYER_NO_COLUMN in L->flags keeps such a layer on the bucket kernel; the flags
+ * of all heads of a layer must agree.
  *   kan_vq_prepared_bytes  size of the buffer; 0 if the layer is not eligible (in > 4096),
  *                          (size_t)-1 if the descriptor is invalid.
  *                          L->prepared is ignored.
@@ -201,6 +207,7 @@ kan_status kan_dense_layer_forward(const float* coef, int32_t in, int32_t out, i
  *                          and stores its address in L->prepared for later forward calls;
  *                          the codebook must then be 16-byte aligned, else the forward call
  *                          ignores the prepared buffer.                                  */
+#define KAN_LAYER_NO_COLUMN 1
 size_t kan_vq_prepared_bytes(const kan_vq_layer* L);
 kan_status kan_vq_prepare(const kan_vq_layer* L, void* prepared, size_t prepared_bytes, void* stream);
 

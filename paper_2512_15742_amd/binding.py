@@ -29,6 +29,7 @@ EXPORTS = [
     "kan_vq_assign_workspace_bytes", "kan_vq_assign", "kan_vq_reconstruction_workspace_bytes",
     "kan_vq_reconstruction_sums", "kan_basis_window", "kan_vq_coef_range", "kan_vq_head_forward_static",
 ]
+KAN_LAYER_NO_COLUMN = 1
 KAN_STATIC_SCRATCH_BYTES = 32 * 1024 * 1024
 
 
@@ -38,7 +39,7 @@ class kan_vq_layer(C.Structure):
         ("K", C.c_int32), ("idx_dtype", C.c_int32), ("gb_dtype", C.c_int32), ("cb_dtype", C.c_int32),
         ("idx", C.c_void_p), ("gain", C.c_void_p), ("bias", C.c_void_p), ("codebook", C.c_void_p),
         ("scale", C.c_float), ("rule", C.c_int32), ("prepared", C.c_void_p),
-        ("gain_log2_lo", C.c_float), ("gain_log2_step", C.c_float), ("bias_scale", C.c_float), ("reserved", C.c_int32),
+        ("gain_log2_lo", C.c_float), ("gain_log2_step", C.c_float), ("bias_scale", C.c_float), ("flags", C.c_int32),
     ]
 
 
@@ -178,6 +179,10 @@ class VQLayer:
         self.prepared = None
         self.desc.prepared = None
         return self
+
+    def keep_on_bucket_kernel(self, on: bool = True):
+        """KAN_LAYER_NO_COLUMN: a small prepared layer stays on the bucket kernel."""
+        self.desc.flags = KAN_LAYER_NO_COLUMN if on else 0
 
     def use_prepared(self, on: bool):
         """Shows or hides an existing prepared buffer to the forward calls."""

@@ -93,6 +93,7 @@ kan_status validate_layer(const kan_vq_layer* L) {
   if (L->idx_dtype == KAN_U16 && L->K > 65536) return KAN_ERR_SHAPE;
   // byte-coded gain/bias belong to the fully quantised format: one-byte codebook entries too
   if (L->gb_dtype == KAN_Q8 && L->cb_dtype != KAN_I8) return KAN_ERR_UNSUPPORTED;
+  if (L->flags & ~KAN_LAYER_NO_COLUMN) return KAN_ERR_UNSUPPORTED;
   if (!L->idx || !L->gain || !L->bias || !L->codebook) return KAN_ERR_NULL;
   const size_t idx_sz = L->idx_dtype == KAN_U16 ? 2 : 4;
   const size_t gb_sz = L->gb_dtype == KAN_F32 ? 4 : (L->gb_dtype == KAN_F16 ? 2 : 1);
@@ -105,7 +106,7 @@ kan_status validate_layer(const kan_vq_layer* L) {
 // Everything below is a pure function of shapes, dtypes, batch, head count and
 // pointer alignment, so the workspace query and the forward call always agree.
 
-enum PlanKind { kPlanGather = 0, kPlanMfma = 1, kPlanFused16 = 2, kPlanFused32 = 3, kPlanBucket = 4 };
+enum PlanKind { kPlanGather = 0, kPlanMfma = 1, kPlanFused16 = 2, kPlanFused32 = 3, kPlanBucket = 4, kPlanColumn = 5 };
 
 struct LayerPlan {
   GatherCfg cfg;
@@ -303,6 +304,39 @@ LayerPlan plan_bucket(const kan_vq_layer& L, int64_t B, int n_heads) {
   return p;
 }
 
+// Small prepared layers: one workgroup per (output, sample) reads the output's ids and gains from the
+// transposed copy in the prepared buffer, gathers from L2 and writes finished outputs (no bucket
+// copies, no partial sums, no reduction launch).  It is ahead of the bucket kernel while the layer's
+// edges x samples stay within about 2^20 (measured, a layer alone, cold, column against bucket kernel:
+// 1024 x 256 at batch 1 / 2 / 4: 11.0 / 9.6 / 9.6 against 14.7 / 13.3 / 13.2 us; 1024 x 512: 10.9 / 9.7 /
+// 13.1 against 14.9 / 13.5 / 13.1; 1024 x 1024: 10.8 / 13.3 / 22.2 against 14.5 / 12.9 / 15.0; 2048 x 1024:
+// 14.0 / 21.6 / 38.3 against 14.4 / 15.6 / 20.0); config 3's head with it on the second layer: 21.8 -> 15.8 us
+// at batch 1, 24.2 -> 20.9 at batch 2.
+constexpr long long kColumnMaxWork = 1ll << 20;     // edges x samples
+
+bool layer_column_ok(const kan_vq_layer& L) {
+  if (L.flags & KAN_LAYER_NO_COLUMN) return false;
+  return (long long)L.in * L.out <= kColumnMaxEdges;
+}
+
+LayerPlan plan_column(const kan_vq_layer& L, int64_t B) {
+  LayerPlan p;
+  p.mfma = false;
+  p.kind = kPlanColumn;
+  p.name = "kan_column";
+  p.cfg.bt = 1;
+  p.cfg.jpl = 1;
+  p.cfg.wj = 1;
+  p.cfg.idx_u32 = L.idx_dtype == KAN_U32;
+  p.cfg.gb_kind = gb_kind_of(L);
+  p.cfg.code = code_of(L);
+  p.n_jt = L.out;
+  p.n_bt = (int)B;
+  p.n_chunks = 1;
+  p.rows_per_chunk = L.in;
+  return p;
+}
+
 bool layer_prepared_ok(const kan_vq_layer& L) {
   return L.prepared != nullptr && L.cb_dtype != KAN_BFP8 && aligned(L.prepared, 256) && aligned(L.codebook, 16) && L.in <= kBucketMaxIn &&
          (long long)L.in * L.out <= (1ll << 31);
@@ -318,7 +352,8 @@ bool layer_prepared_ok(const kan_vq_layer& L) {
 //   fp16 path (KAN_PATH_MFMA, and AUTO from batch 32): up to kHalfFusedMaxBatch the fused
 //     kernel with fp16 operands, above that coefficient/basis preparation + the streaming
 //     contraction.
-LayerPlan plan_vq(const kan_vq_layer& L, int64_t B, int n_heads, bool vec_ok, bool prepared_ok, int32_t path) {
+LayerPlan plan_vq(const kan_vq_layer& L, int64_t B, int n_heads, bool vec_ok, bool prepared_ok, int32_t path,
+                  bool column_ok) {
   const int code = code_of(L);
   const int u32 = L.idx_dtype == KAN_U32, gbk = gb_kind_of(L);
   const bool half_path = path == KAN_PATH_MFMA || (path == KAN_PATH_AUTO && B >= kAutoMfmaBatch);
@@ -328,7 +363,8 @@ LayerPlan plan_vq(const kan_vq_layer& L, int64_t B, int n_heads, bool vec_ok, bo
     if (B <= kHalfFusedMaxBatch) return plan_fused(L.in, L.out, B, n_heads, u32, gbk, code, false);
     return plan_mfma(L.in, L.out, B, n_heads, u32, gbk, code);
   }
-  if (prepared_ok && B <= kBucketMaxBatch) return plan_bucket(L, B, n_heads);
+  if (prepared_ok && B <= kBucketMaxBatch)
+    return column_ok && (long long)L.in * L.out * B <= kColumnMaxWork ? plan_column(L, B) : plan_bucket(L, B, n_heads);
   // large batches: the fp16 machinery with both operands split into high and low parts
   if (B >= kSplitMinBatch) return plan_mfma(L.in, L.out, B, n_heads, u32, gbk, code, true);
   if (B >= 2) return plan_fused(L.in, L.out, B, n_heads, u32, gbk, code, true);
@@ -490,7 +526,7 @@ kan_status run_layer_group(const LayerPlan& p, GatherArgs& a, const void* const*
     }
     dim3 grid((unsigned)(p.n_jt * p.n_bt), (unsigned)p.n_chunks, (unsigned)heads);
     st = run(p.name, s, [&] { return launch_mfma(m, p.cfg.bt, kMfmaTileN, grid, s); });
-  } else if (p.kind == kPlanBucket) {
+  } else if (p.kind == kPlanBucket || p.kind == kPlanColumn) {
     const BucketGeom g = bucket_geometry(a.n_in, a.n_out, (int)(a.cb_bytes / cb_row_bytes(p.cfg.code)), p.cfg.code,
                                          p.cfg.gb_kind);
     BucketArgs k;
@@ -518,6 +554,8 @@ kan_status run_layer_group(const LayerPlan& p, GatherArgs& a, const void* const*
     k.off_i = (long long)g.off_i;
     k.off_q = (long long)g.off_q;
     k.off_g = (long long)g.off_g;
+    k.off_ti = (long long)g.off_ti;
+    k.off_tg = (long long)g.off_tg;
     for (int h = 0; h < heads; ++h) {
       k.h[h].prepared = prepared[h];
       k.h[h].cb = a.h[h].cb;
@@ -525,7 +563,8 @@ kan_status run_layer_group(const LayerPlan& p, GatherArgs& a, const void* const*
       k.h[h].gain_log2_lo = a.h[h].gain_log2_lo;
       k.h[h].gain_log2_step = a.h[h].gain_log2_step;
     }
-    st = run(p.name, s, [&] { return launch_bucket(p.cfg.code, p.cfg.gb_kind, k, g.tab_w[table], heads, s); });
+    if (p.kind == kPlanColumn) st = run(p.name, s, [&] { return launch_column(p.cfg.code, p.cfg.gb_kind, k, heads, s); });
+    else st = run(p.name, s, [&] { return launch_bucket(p.cfg.code, p.cfg.gb_kind, k, g.tab_w[table], heads, s); });
   } else if (p.kind == kPlanFused16 || p.kind == kPlanFused32) {
     const bool f32 = p.kind == kPlanFused32;
     FusedArgs f;
@@ -569,7 +608,7 @@ kan_status check_path(int32_t path) {
 // preparation of the matrix-core path (after any layer that splits its inputs).
 bool chained(const std::vector<LayerPlan>& plans, int l, int n_heads) {
   if (l < 0 || l + 1 >= (int)plans.size() || n_heads > kMaxGroup || plans[l].n_chunks <= 1) return false;
-  if (plans[l + 1].kind == kPlanBucket) return plans[l].kind == kPlanBucket;
+  if (plans[l + 1].kind == kPlanBucket || plans[l + 1].kind == kPlanColumn) return plans[l].kind == kPlanBucket;
   return plans[l + 1].kind == kPlanMfma && plans[l].n_chunks <= kMaxChainedSlices;
 }
 
@@ -598,12 +637,13 @@ kan_status plan_head(const kan_vq_layer* layers, int32_t n_layers, int32_t n_hea
   plans->clear();
   for (int l = 0; l < n_layers; ++l) {
     const kan_vq_layer& R = layers[l];
-    bool vec_ok = true, prepared_ok = true;
+    bool vec_ok = true, prepared_ok = true, column_ok = true;
     for (int h = 0; h < n_heads; ++h) {
       vec_ok = vec_ok && layer_vec_ok(layers[(size_t)h * n_layers + l]);
       prepared_ok = prepared_ok && layer_prepared_ok(layers[(size_t)h * n_layers + l]);
+      column_ok = column_ok && layer_column_ok(layers[(size_t)h * n_layers + l]);
     }
-    LayerPlan p = plan_vq(R, B, group, vec_ok, prepared_ok, path);
+    LayerPlan p = plan_vq(R, B, group, vec_ok, prepared_ok, path, column_ok);
     plans->push_back(p);
     auto grow = [](size_t& dst, size_t v) { if (v > dst) dst = v; };
     grow(ws->partial, partial_bytes(p, R.out, B, group));
@@ -1020,7 +1060,7 @@ kan_status kan_vq_coef_range(const kan_vq_layer* L, float* range, void* stream) 
 
 const char* kan_vq_planned_kernel(const kan_vq_layer* L, int64_t B, int32_t n_heads, int32_t path) {
   if (validate_layer(L) != KAN_OK || check_path(path) != KAN_OK || B < 1 || n_heads < 1) return "invalid";
-  return plan_vq(*L, B, n_heads < kMaxGroup ? n_heads : kMaxGroup, layer_vec_ok(*L), layer_prepared_ok(*L), path)
+  return plan_vq(*L, B, n_heads < kMaxGroup ? n_heads : kMaxGroup, layer_vec_ok(*L), layer_prepared_ok(*L), path, layer_column_ok(*L))
       .name;
 }
 

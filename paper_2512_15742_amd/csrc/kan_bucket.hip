@@ -443,6 +443,95 @@ __global__ __launch_bounds__(kBucketThreads) void kan_bucket_kernel(const Bucket
   }
 }
 
+// ---- column kernel: small prepared layers ------------------------------------------------
+// A layer of a few hundred thousand edges gives a bucket workgroup a thousand edges or fewer:
+// what it does then is wait - for 80 KB of codeword rows to reach its LDS, for its block
+// bounds, for a reduction launch behind it.  Such a layer is served by one workgroup per
+// (output j, sample) instead.  The prepared buffer of a small layer also holds ids and gains
+// transposed ([output][input]), so thread t owns inputs t, t + 256, ... of the sample: it loads
+// x, id and gain of its edges at once (coalesced, nothing depends on anything), evaluates the
+// basis of its own inputs, fetches each edge's four-coefficient window straight from the
+// codebook in L2 (Eq. (1); a thousand gathers per CU are a microsecond) and adds the products
+// in a fixed order: per thread by ascending input, then across the lanes, then the waves.
+// It writes the finished output - bias sum, activation - so no reduction pass follows.
+constexpr int kColumnPer = 8;          // edges per thread and round (2048 inputs per round)
+
+template <int GK, typename CbT>
+__global__ __launch_bounds__(kColumnThreads) void kan_column_kernel(const BucketArgs a) {
+  __shared__ float wave_sum[kColumnThreads / kWave];
+  const int tid = threadIdx.x, lane = tid & (kWave - 1), wave = tid >> 6;
+  const int j = blockIdx.x, b = blockIdx.y, head = blockIdx.z;
+  const BucketHead H = a.h[head];
+  const char* prep = (const char*)H.prepared;
+  constexpr int kGainBytes = gb_bytes(GK);
+  const uint32_t* __restrict__ ti = (const uint32_t*)(prep + a.off_ti) + (size_t)j * a.n_in;
+  const char* __restrict__ tg = prep + a.off_tg + (size_t)j * a.n_in * kGainBytes;
+  const Q8Params qp = {H.gain_log2_lo, H.gain_log2_step, 0.f};
+  const CbT* __restrict__ cbk = (const CbT*)H.cb;
+  const float* xr = a.x + (long long)head * a.x_head_stride + (long long)b * a.n_in;
+  const float bias_sum = ((const float*)(prep + a.off_bias))[j];
+
+  float acc = 0.f;
+  for (int i0 = 0; i0 < a.n_in; i0 += kColumnThreads * kColumnPer) {       // one round for up to 2048 inputs
+    // ---- everything the round needs from memory except the windows: unconditional loads,
+    //      clamped addresses (inputs past the end re-read the last one and count as zero) ----
+    int xi[kColumnPer];
+    float xv[kColumnPer], gain[kColumnPer];
+    uint32_t row[kColumnPer];
+#pragma unroll
+    for (int r = 0; r < kColumnPer; ++r) {
+      xi[r] = min(i0 + tid + r * kColumnThreads, a.n_in - 1);
+      xv[r] = xr[xi[r]];
+      row[r] = ti[xi[r]];
+      if constexpr (GK == kGbF16) gain[r] = __half2float(((const __half*)tg)[xi[r]]);
+      else if constexpr (GK == kGbQ8) gain[r] = q8_gain(((const uint8_t*)tg)[xi[r]], qp);
+      else gain[r] = ((const float*)tg)[xi[r]];
+    }
+    // the input is x itself, or the previous layer's per-bucket sums still to be added (in order) and squashed
+    for (int p0 = 1; p0 < a.x_parts; p0 += 8) {
+      float t[8][kColumnPer];
+#pragma unroll
+      for (int pp = 0; pp < 8; ++pp) {
+        const float* xp = xr + (long long)min(p0 + pp, a.x_parts - 1) * a.x_part_stride;
+#pragma unroll
+        for (int r = 0; r < kColumnPer; ++r) t[pp][r] = xp[xi[r]];
+      }
+#pragma unroll
+      for (int pp = 0; pp < 8; ++pp)
+#pragma unroll
+        for (int r = 0; r < kColumnPer; ++r) xv[r] += (p0 + pp < a.x_parts) ? t[pp][r] : 0.f;
+    }
+    // ---- basis of the thread's own inputs, then the windows of its edges ----------------------
+    BasisW w[kColumnPer];
+    typename WindowRaw<CbT>::type raw[kColumnPer];
+#pragma unroll
+    for (int r = 0; r < kColumnPer; ++r) {
+      w[r] = basis_eval_rule(a.x_tanh ? tanhf(xv[r]) : xv[r], a.rule);
+      raw[r] = load_window<CbT>(cbk, row[r], w[r].span);
+    }
+#pragma unroll
+    for (int r = 0; r < kColumnPer; ++r) {
+      float c[4];
+      dequant_window<CbT>(raw[r], 1.0f, c);
+      // sum_k w_k c_k with w3 = 1 - w0 - w1 - w2 (the bases sum to 1)
+      float sv = c[3];
+      sv = fmaf(w[r].w2, c[2] - c[3], sv);
+      sv = fmaf(w[r].w1, c[1] - c[3], sv);
+      sv = fmaf(w[r].w0, c[0] - c[3], sv);
+      acc += (i0 + tid + r * kColumnThreads < a.n_in) ? gain[r] * sv : 0.f;
+    }
+  }
+  acc = wave_sum_to_last_lane(acc);
+  if (lane == kWave - 1) wave_sum[wave] = acc;
+  __syncthreads();
+  if (tid == 0) {
+    const float scale = sizeof(CbT) == 1 ? H.scale : 1.0f;
+    float v = scale * ((wave_sum[0] + wave_sum[1]) + (wave_sum[2] + wave_sum[3])) + bias_sum;
+    if (a.apply_tanh) v = tanhf(v);
+    a.dst[(long long)head * a.dst_head_stride + (long long)b * a.n_out + j] = v;
+  }
+}
+
 // ---- preparation ------------------------------------------------------------------------
 // The regrouping is a counting sort of the edges by (bucket, output j), input i ascending
 // inside a run, and at the same time a transposition: the layer stores consecutive outputs side
@@ -542,7 +631,8 @@ __global__ __launch_bounds__(256) void kan_prepare_fill_kernel(const IdxT* __res
                                                                const uint32_t* __restrict__ seg,
                                                                const uint16_t* __restrict__ tcnt,
                                                                uint16_t* __restrict__ pi, uint16_t* __restrict__ pq,
-                                                               GbT* __restrict__ pg) {
+                                                               GbT* __restrict__ pg, uint32_t* __restrict__ ti,
+                                                               GbT* __restrict__ tgo) {
   extern __shared__ __attribute__((aligned(16))) unsigned char lds_raw[];
   // tile of ids and gains, [row][column], then the running position of every bucket, one table per wave
   IdxT* tid_ = (IdxT*)lds_raw;
@@ -575,6 +665,10 @@ __global__ __launch_bounds__(256) void kan_prepare_fill_kernel(const IdxT* __res
       const int r = r0 + lane;
       const bool live = r < rows;
       const uint32_t id = live ? (uint32_t)tid_[r * kPrepareCols + c] : 0u;
+      if (ti && live) {        // small layers: ids and gains once more, the inputs of an output side by side
+        ti[(size_t)j * n_in + i0 + r] = id;
+        tgo[(size_t)j * n_in + i0 + r] = tg[r * kPrepareCols + c];
+      }
       const uint32_t b = min(id >> rows_shift, (uint32_t)(n_buckets - 1));
       unsigned long long todo = __ballot(live);
       uint32_t pos = 0;
@@ -696,7 +790,8 @@ hipError_t prepare_typed(const LayerPtrs& h, int n_in, int n_out, const BucketGe
   hipLaunchKernelGGL(kan_prepare_scan_kernel, dim3(1), dim3(1024), 0, s, seg, n_seg);
   hipLaunchKernelGGL((kan_prepare_fill_kernel<IdxT, GbT>), grid, dim3(256), lds_fill, s, (const IdxT*)h.idx,
                      (const GbT*)h.gain, n_in, n_out, g.rows_shift, g.n_buckets, (const uint32_t*)seg,
-                     (const uint16_t*)tcnt, (uint16_t*)(p + g.off_i), (uint16_t*)(p + g.off_q), (GbT*)(p + g.off_g));
+                     (const uint16_t*)tcnt, (uint16_t*)(p + g.off_i), (uint16_t*)(p + g.off_q), (GbT*)(p + g.off_g),
+                     g.off_ti ? (uint32_t*)(p + g.off_ti) : nullptr, g.off_tg ? (GbT*)(p + g.off_tg) : nullptr);
   hipLaunchKernelGGL(kan_prepare_bias_kernel, dim3((unsigned)((n_out + 255) / 256)), dim3(256), 0, s, (const double*)tbias,
                      g.n_row_blocks, n_out, (float*)(p + g.off_bias));
   const int min_blocks = (n_out + kBucketMaxJw - 1) / kBucketMaxJw;
@@ -749,6 +844,26 @@ hipError_t launch_bucket(int code, int gb_kind, const BucketArgs& a, int blocks,
     else KAN_LAUNCH_BUCKET(kGbF32, kCbF32);
   }
 #undef KAN_LAUNCH_BUCKET
+  return hipGetLastError();
+}
+
+hipError_t launch_column(int code, int gb_kind, const BucketArgs& a, int heads, hipStream_t s) {
+  if ((long long)a.n_in * a.n_out > kColumnMaxEdges || a.off_ti <= 0 || a.off_tg <= 0) return hipErrorInvalidValue;
+  if (code != kCbI8 && code != kCbF16 && code != kCbF32) return hipErrorInvalidValue;
+  if (gb_kind == kGbQ8 && code != kCbI8) return hipErrorInvalidValue;
+  dim3 grid((unsigned)a.n_out, (unsigned)a.B, (unsigned)heads);
+  dim3 block(kColumnThreads);
+  if (code == kCbI8) {
+    if (gb_kind == kGbQ8) hipLaunchKernelGGL((kan_column_kernel<kGbQ8, int8_t>), grid, block, 0, s, a);
+    else if (gb_kind == kGbF16) hipLaunchKernelGGL((kan_column_kernel<kGbF16, int8_t>), grid, block, 0, s, a);
+    else hipLaunchKernelGGL((kan_column_kernel<kGbF32, int8_t>), grid, block, 0, s, a);
+  } else if (code == kCbF16) {
+    if (gb_kind == kGbF16) hipLaunchKernelGGL((kan_column_kernel<kGbF16, __half>), grid, block, 0, s, a);
+    else hipLaunchKernelGGL((kan_column_kernel<kGbF32, __half>), grid, block, 0, s, a);
+  } else {
+    if (gb_kind == kGbF16) hipLaunchKernelGGL((kan_column_kernel<kGbF16, float>), grid, block, 0, s, a);
+    else hipLaunchKernelGGL((kan_column_kernel<kGbF32, float>), grid, block, 0, s, a);
+  }
   return hipGetLastError();
 }
 

@@ -177,6 +177,12 @@ constexpr int kBucketWorkgroups = 256;  // one workgroup of 1024 threads per CU
 constexpr int kBucketTables = 5;
 constexpr int kBucketEntryWords = 8;    // {bucket, first output, end output, first edge, end edge, 0, 0, 0}
 
+// Small prepared layers: one workgroup per (output, sample) reads the output's inputs side by side from a
+// transposed copy of ids and gains in the prepared buffer, gathers the windows from L2 and writes the
+// finished output (no bucket copies, no partial sums, no reduction launch).
+constexpr long long kColumnMaxEdges = 1ll << 20;
+constexpr int kColumnThreads = 256;
+
 struct BucketGeom {
   int rows_shift;      // log2(codewords per bucket)
   int n_buckets;
@@ -189,6 +195,8 @@ struct BucketGeom {
   size_t off_cnt;      // uint32 [kBucketTables][n_buckets + 1]  blocks per bucket (prefix sums), scratch of the preparation
   size_t off_tcnt;     // uint16 [row blocks][n_buckets][n_out]  edges per (row block, bucket, output), scratch of the preparation
   size_t off_tbias;    // double [row blocks][n_out]             bias sums per row block, scratch of the preparation
+  size_t off_ti;       // uint32 [n_out][n_in]   small layers only (at most kColumnMaxEdges edges, else 0): codeword ids ...
+  size_t off_tg;       // gain   [n_out][n_in]   ... and gains with the inputs of an output side by side (column kernel)
   int n_row_blocks;    // row blocks of kPrepareRows inputs
   int tab_w[kBucketTables];        // blocks of every table
   int tab_first[kBucketTables];    // first entry of every table
@@ -226,6 +234,12 @@ inline BucketGeom bucket_geometry(int n_in, int n_out, int K, int code, int gb_k
   g.off_tcnt = g.off_cnt + up((size_t)kBucketTables * ((size_t)g.n_buckets + 1) * 4);
   g.off_tbias = g.off_tcnt + up((size_t)g.n_row_blocks * g.n_buckets * n_out * 2);
   g.total = g.off_tbias + up((size_t)g.n_row_blocks * n_out * 8);
+  g.off_ti = g.off_tg = 0;
+  if ((long long)E <= kColumnMaxEdges) {
+    g.off_ti = g.total;
+    g.off_tg = g.off_ti + up(E * 4);
+    g.total = g.off_tg + up(E * gb_bytes(gb_kind));
+  }
   return g;
 }
 
@@ -251,11 +265,13 @@ struct BucketArgs {
   int apply_tanh;              // honoured only when n_buckets == 1
   int rule;                    // edge function: 0 cubic B-spline, 1 two-tap linear interpolation
   long long off_seg, off_bias, off_i, off_q, off_g;
+  long long off_ti, off_tg;    // column kernel: transposed ids and gains
   long long off_blk;           // byte offset of the block table this launch uses
   BucketHead h[kMaxGroup];
 };
 
 hipError_t launch_bucket(int code, int gb_kind, const BucketArgs&, int blocks, int heads, hipStream_t);
+hipError_t launch_column(int code, int gb_kind, const BucketArgs&, int heads, hipStream_t);
 // One-time regrouping of a layer into the layout above (three kernels: count, scan, fill).
 hipError_t launch_bucket_prepare(const LayerPtrs&, int idx_u32, int gb_kind, int n_in, int n_out,
                                  const BucketGeom&, void* prepared, hipStream_t);

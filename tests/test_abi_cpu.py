@@ -47,7 +47,7 @@ def _desc(**kw):
     base = dict(n_in=8, n_out=8, G=10, degree=3, K=16, idx_dtype=kb.KAN_U16, gb_dtype=kb.KAN_F32,
                 cb_dtype=kb.KAN_F32, idx=0x1000, gain=0x2000, bias=0x3000, codebook=0x4000,
                 scale=1.0, rule=0, prepared=None, gain_log2_lo=0.0, gain_log2_step=0.0,
-                bias_scale=0.0, reserved=0)
+                bias_scale=0.0, flags=0)
     base.update(kw)
     return kb.kan_vq_layer(**base)
 

@@ -100,6 +100,7 @@ def test_f16cb_prepared_layer(kb, gb_dtype, rule):
     P = synth.make_layer(66, 300, 200, 20000, cb_dtype="f16", gb_dtype=gb_dtype)
     P.idx.reshape(-1)[:6] = [0, 1, 4095, 4096, 19999, 8191]
     L = kb.VQLayer(P, rule=kb.KAN_RULE_PLI2 if rule == "pli" else kb.KAN_RULE_BSPLINE3).prepare()
+    L.keep_on_bucket_kernel()                    # (this small layer would take the column kernel otherwise)
     assert kb.kan_vq_prepared_bytes(L) == L.prepared.numel() > 0
     plain = kb.VQLayer(P, rule=kb.KAN_RULE_PLI2 if rule == "pli" else kb.KAN_RULE_BSPLINE3)
     for B in (1, 3, 4):

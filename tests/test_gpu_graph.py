@@ -22,6 +22,7 @@ def kb():
 
 @pytest.mark.parametrize("B,path,prepared,kernel", [
     (1, "gather", True, "kan_bucket"), (1, "gather", False, "kan_gather_bt1"), (3, "gather", True, "kan_bucket"),
+    (2, "gather", True, "kan_column"),
     (16, "gather", False, "kan_fused_f32"), (48, "mfma", False, "kan_fused_f16"), (300, "mfma", False, "kan_mfma")])
 def test_head_forward_replays_from_a_graph(kb, B, path, prepared, kernel):
     dims = [(520, 264), (264, 130), (130, 21)]
@@ -30,6 +31,7 @@ def test_head_forward_replays_from_a_graph(kb, B, path, prepared, kernel):
     if prepared:
         for L in Ls:
             L.prepare()
+            L.keep_on_bucket_kernel(kernel == "kan_bucket")     # (small layers: the column kernel otherwise)
     pth = kb.KAN_PATH_GATHER if path == "gather" else kb.KAN_PATH_MFMA
     assert kb.kan_vq_planned_kernel(Ls[0], B, 1, pth) == kernel
     xs = [torch.from_numpy(synth.make_x(70 + r, B, 520)).cuda() for r in range(4)]

@@ -32,13 +32,16 @@ def test_skewed_histograms_every_kernel_family(kb, dist, zipf_s, n_in, n_out, K)
     assert counts.max() > 20 * counts.mean()                   # really skewed
     rng = np.random.default_rng(9)
     for B, path, tol, prepared in [(1, kb.KAN_PATH_GATHER, TOL_FP32, False), (1, kb.KAN_PATH_GATHER, TOL_FP32, True),
-                                   (3, kb.KAN_PATH_GATHER, TOL_FP32, True), (9, kb.KAN_PATH_GATHER, TOL_FP32, False),
+                                   (3, kb.KAN_PATH_GATHER, TOL_FP32, True), (2, kb.KAN_PATH_GATHER, TOL_FP32, "column"),
+                                   (9, kb.KAN_PATH_GATHER, TOL_FP32, False),
                                    (20, kb.KAN_PATH_MFMA, TOL_MFMA, False), (150, kb.KAN_PATH_MFMA, TOL_MFMA, False)]:
         x = rng.uniform(-1.0, 1.0, size=(B, n_in)).astype(np.float32)
         L = kb.VQLayer(P)
         if prepared:
             L.prepare()
-            assert kb.kan_vq_planned_kernel(L, B, 1, path) == "kan_bucket"
+            L.keep_on_bucket_kernel(prepared is True)
+            small = prepared == "column"
+            assert kb.kan_vq_planned_kernel(L, B, 1, path) == ("kan_column" if small else "kan_bucket")
         y = kb.kan_vq_layer_forward(L, to_dev(x), path=path).cpu().numpy()
         y_ref, A = ko.vq_layer_forward(x, **P.as_dict(), return_abs=True)
         rep = ko.error_report(y, y_ref, A)

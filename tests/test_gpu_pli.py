@@ -76,6 +76,7 @@ def _check(kb, P, x, path, tol, prepared=False):
     L = kb.VQLayer(P, rule=kb.KAN_RULE_PLI2)
     if prepared:
         L.prepare()
+        L.keep_on_bucket_kernel(prepared is True)       # prepared == "column": the small-layer kernel
     kern = kb.kan_vq_planned_kernel(L, x.shape[0], 1, path)
     y = kb.kan_vq_layer_forward(L, to_dev(x), path=path).cpu().numpy()
     y_ref, A = ko.vq_layer_forward(x, **P.as_dict(), return_abs=True, rule="pli")
@@ -93,14 +94,15 @@ def test_pli_every_kernel_family(kb, cb, gb):
     rng = np.random.default_rng(5)
     seen = set()
     for B, path, tol, prepared in [(1, kb.KAN_PATH_GATHER, TOL_FP32, False), (1, kb.KAN_PATH_GATHER, TOL_FP32, True),
-                                   (3, kb.KAN_PATH_GATHER, TOL_FP32, True), (9, kb.KAN_PATH_GATHER, TOL_FP32, False),
+                                   (3, kb.KAN_PATH_GATHER, TOL_FP32, True), (2, kb.KAN_PATH_GATHER, TOL_FP32, "column"),
+                                   (9, kb.KAN_PATH_GATHER, TOL_FP32, False),
                                    (50, kb.KAN_PATH_GATHER, TOL_FP32, False), (70, kb.KAN_PATH_GATHER, TOL_FP32, False),
                                    (20, kb.KAN_PATH_MFMA, TOL_MFMA, False),
                                    (150, kb.KAN_PATH_MFMA, TOL_MFMA, False)]:
         x = rng.uniform(-1.1, 1.1, size=(B, 300)).astype(np.float32)
         x[0, :4] = [1.0, -1.0, np.float32(7.0 / 9.0), np.float32(-1.0 / 9.0)]
         seen.add(_check(kb, P, x, path, tol, prepared))
-    assert seen == {"kan_gather_bt1", "kan_bucket", "kan_fused_f32", "kan_mfma_split", "kan_fused_f16", "kan_mfma"}
+    assert seen == {"kan_gather_bt1", "kan_bucket", "kan_column", "kan_fused_f32", "kan_mfma_split", "kan_fused_f16", "kan_mfma"}
 
 
 @pytest.mark.parametrize("B,path,prepared", [(1, "gather", True), (1, "gather", False), (16, "gather", False),

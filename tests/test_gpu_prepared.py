@@ -92,6 +92,12 @@ def _read_layout(buf, P):
     # scratch of the preparation: edges per (row block of 256 inputs, bucket, output) as u16, bias sums per row block as fp64
     n_rb = (n_in + 255) // 256
     o += up(n_rb * nb * n_out * 2) + up(n_rb * n_out * 8)
+    if E <= 2 ** 20:
+        # small layers: ids (as u32) and gains once more, transposed (the inputs of an output side by side)
+        ti = raw[o:o + 4 * E].view(np.uint32).reshape(n_out, n_in); o += up(4 * E)
+        tgn = raw[o:o + gsz * E].view(P.gain.dtype).reshape(n_out, n_in); o += up(gsz * E)
+        assert np.array_equal(ti, P.idx.T.astype(np.uint32))
+        assert np.array_equal(tgn.view(np.uint8), np.ascontiguousarray(P.gain.T).view(np.uint8))
     assert o == raw.size
     _read_layout.tables = tables
     return seg, bias, pi, pq, pg
@@ -177,9 +183,21 @@ def test_block_tables_balance_skewed_histograms(kb, dist, n_out):
 
 
 def _forward_prepared(kb, P, x, expect_kernel="kan_bucket"):
+    """The bucket kernel's result (small layers are kept on it by their flag).  Where the layer is small
+    enough for the column kernel, that kernel runs on the same buffer too and must agree: the same
+    finite outputs of the bucket kernel finite here too and equal within the fp32 bound."""
     L = kb.VQLayer(P).prepare()
+    L.keep_on_bucket_kernel()
     assert kb.kan_vq_planned_kernel(L, x.shape[0], 1, kb.KAN_PATH_GATHER) == expect_kernel
-    return kb.kan_vq_layer_forward(L, to_dev(x), path=kb.KAN_PATH_GATHER).cpu().numpy()
+    y = kb.kan_vq_layer_forward(L, to_dev(x), path=kb.KAN_PATH_GATHER).cpu().numpy()
+    L.keep_on_bucket_kernel(False)
+    if kb.kan_vq_planned_kernel(L, x.shape[0], 1, kb.KAN_PATH_GATHER) == "kan_column":
+        yc = kb.kan_vq_layer_forward(L, to_dev(x), path=kb.KAN_PATH_GATHER).cpu().numpy()
+        fin = np.isfinite(y)
+        assert np.isfinite(yc[fin]).all()       # (the bucket kernel may give up more outputs than the edges make non-finite)
+        if fin.any():
+            assert np.abs(yc[fin] - y[fin]).max() <= TOL_FP32 * max(float(np.abs(y[fin]).max()), 1e-30)
+    return y
 
 
 def test_config1_prepared(kb):
@@ -253,12 +271,23 @@ def test_three_chained_layers_and_mixed_chain(kb):
     Ps = [synth.make_layer(31, 200, 300, 30000, cb_dtype="i8", gb_dtype="f16"),
           synth.make_layer(32, 300, 90, 20000, cb_dtype="i8", gb_dtype="f16"),
           synth.make_layer(33, 90, 17, 9000, cb_dtype="f32", gb_dtype="f32")]
-    x = synth.make_x(7, 3, 200)
+    x = synth.make_x(7, 2, 200)
     y_ref = ko.vq_head_forward(x, [p.as_dict() for p in Ps])
     Ls = [L.prepare() for L in gpu_layers(Ps)]
-    y = kb.kan_vq_head_forward([Ls], to_dev(x), path=kb.KAN_PATH_GATHER)[0].cpu().numpy()
-    assert ko.error_report(y, y_ref)["headline"] <= TOL_FP32
-    Ls[1].use_prepared(False)
+    for bucket_only in (True, False):             # small layers: kept on the bucket kernel, then on the column kernel
+        for L in Ls:
+            L.use_prepared(True)
+            L.keep_on_bucket_kernel(bucket_only)
+        assert kb.kan_vq_planned_kernel(Ls[1], 2, 1, kb.KAN_PATH_GATHER) == ("kan_bucket" if bucket_only else "kan_column")
+        y = kb.kan_vq_head_forward([Ls], to_dev(x), path=kb.KAN_PATH_GATHER)[0].cpu().numpy()
+        assert ko.error_report(y, y_ref)["headline"] <= TOL_FP32
+        Ls[1].use_prepared(False)
+        y = kb.kan_vq_head_forward([Ls], to_dev(x), path=kb.KAN_PATH_GATHER)[0].cpu().numpy()
+        assert ko.error_report(y, y_ref)["headline"] <= TOL_FP32
+    # a bucket layer hands its per-bucket sums to a column layer behind it
+    for L, bucket_only in zip(Ls, (True, False, True)):
+        L.use_prepared(True)
+        L.keep_on_bucket_kernel(bucket_only)
     y = kb.kan_vq_head_forward([Ls], to_dev(x), path=kb.KAN_PATH_GATHER)[0].cpu().numpy()
     assert ko.error_report(y, y_ref)["headline"] <= TOL_FP32
 
@@ -282,10 +311,19 @@ def test_grouped_heads_prepared(kb):
                 synth.make_layer(700 + h, 48, 7, 300, cb_dtype="i8", gb_dtype="f16")] for h in range(5)]
     x = synth.make_x(1, B, 96)
     heads = [[L.prepare() for L in gpu_layers(ps)] for ps in heads_p]
+    for ls in heads:
+        for L in ls:
+            L.keep_on_bucket_kernel()             # (these small layers would take the column kernel otherwise)
+    assert kb.kan_vq_planned_kernel(heads[0][0], B, 5, kb.KAN_PATH_GATHER) == "kan_bucket"
     y = kb.kan_vq_head_forward(heads, to_dev(x), path=kb.KAN_PATH_GATHER).cpu().numpy()
     for h in range(5):
         y_ref = ko.vq_head_forward(x, [p.as_dict() for p in heads_p[h]])
         assert ko.error_report(y[h], y_ref)["headline"] <= TOL_FP32
+    # heads whose flags differ: the whole group stays on the bucket kernel
+    heads[2][0].keep_on_bucket_kernel(False)
+    y3 = kb.kan_vq_head_forward(heads, to_dev(x), path=kb.KAN_PATH_GATHER).cpu().numpy()
+    assert np.array_equal(y3, y)
+    heads[2][0].keep_on_bucket_kernel()
     # one head without a prepared buffer sends the whole group to the ordinary kernels
     heads[3][0].unprepare()
     assert kb.kan_vq_planned_kernel(heads[3][0], B, 5, kb.KAN_PATH_GATHER) != "kan_bucket"

@@ -34,7 +34,8 @@ def test_q8_every_kernel_family(kb):
     rng = np.random.default_rng(6)
     seen = set()
     for B, path, tol, prepared in [(1, kb.KAN_PATH_GATHER, TOL_FP32, False), (1, kb.KAN_PATH_GATHER, TOL_FP32, True),
-                                   (3, kb.KAN_PATH_GATHER, TOL_FP32, True), (9, kb.KAN_PATH_GATHER, TOL_FP32, False),
+                                   (3, kb.KAN_PATH_GATHER, TOL_FP32, True), (2, kb.KAN_PATH_GATHER, TOL_FP32, "column"),
+                                   (9, kb.KAN_PATH_GATHER, TOL_FP32, False),
                                    (50, kb.KAN_PATH_GATHER, TOL_FP32, False), (70, kb.KAN_PATH_GATHER, TOL_FP32, False),
                                    (20, kb.KAN_PATH_MFMA, TOL_MFMA, False),
                                    (150, kb.KAN_PATH_MFMA, TOL_MFMA, False)]:
@@ -42,12 +43,13 @@ def test_q8_every_kernel_family(kb):
         L = kb.VQLayer(P)
         if prepared:
             L.prepare()
+            L.keep_on_bucket_kernel(prepared is True)       # prepared == "column": the small-layer kernel
         seen.add(kb.kan_vq_planned_kernel(L, B, 1, path))
         y = kb.kan_vq_layer_forward(L, to_dev(x), path=path).cpu().numpy()
         y_ref, A = ko.vq_layer_forward(x, **P.as_dict(), return_abs=True)
         rep = ko.error_report(y, y_ref, A)
         assert rep["headline"] <= tol and rep["strict"] <= tol, (B, path, prepared, rep)
-    assert seen == {"kan_gather_bt1", "kan_bucket", "kan_fused_f32", "kan_mfma_split", "kan_fused_f16", "kan_mfma"}
+    assert seen == {"kan_gather_bt1", "kan_bucket", "kan_column", "kan_fused_f32", "kan_mfma_split", "kan_fused_f16", "kan_mfma"}
 
 
 @pytest.mark.parametrize("n_in,n_out,K,B", [(1, 1, 2, 1), (3, 21, 5, 2), (130, 67, 9000, 5), (257, 530, 20000, 1),
@@ -81,7 +83,10 @@ def test_q8_prepared_layout_and_bias_sums(kb):
     tab_w = [max(256 // (t + 1), nb) for t in range(4)] + [nb]          # block tables, then per-bucket block counts
     o += up(sum(tab_w) * 32) + up(5 * (nb + 1) * 4)
     o += up(1 * nb * 40 * 2) + up(1 * 40 * 8)          # the preparation's scratch: counts and bias sums per block of 256 inputs
+    ti = raw[o:o + 4 * E].view(np.uint32).reshape(40, 130); o += up(4 * E)      # small layer: ids and gain codes transposed
+    tgc = raw[o:o + E].reshape(40, 130); o += up(E)
     assert o == raw.size
+    assert np.array_equal(ti, P.idx.T.astype(np.uint32)) and np.array_equal(tgc, P.gain.T)
     bucket = P.idx.astype(np.int64) // 8192
     ii, jj = np.meshgrid(np.arange(130), np.arange(40), indexing="ij")
     order = np.lexsort((ii.ravel(), jj.ravel(), bucket.ravel()))

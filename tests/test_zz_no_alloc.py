@@ -68,9 +68,11 @@ def test_static_scratch_prepared_layers_and_single_layer(kb):
     Ps = [synth.make_layer(1, 256, 128, 4096, cb_dtype="i8", gb_dtype="f16"),
           synth.make_layer(2, 128, 32, 4096, cb_dtype="i8", gb_dtype="f16")]
     Ls = [kb.VQLayer(p).prepare() for p in Ps]
+    Ls[0].keep_on_bucket_kernel()                 # (small layers: the first stays on the bucket kernel, the second takes the column kernel)
     x = synth.make_x(3, 1, 256)
     xd = to_dev(x)
     assert kb.kan_vq_planned_kernel(Ls[0], 1, 1, kb.KAN_PATH_GATHER) == "kan_bucket"
+    assert kb.kan_vq_planned_kernel(Ls[1], 1, 1, kb.KAN_PATH_GATHER) == "kan_column"
     y_st = kb.kan_vq_head_forward_static([Ls], xd, path=kb.KAN_PATH_GATHER)
     y_ws = kb.kan_vq_head_forward([Ls], xd, path=kb.KAN_PATH_GATHER)
     assert torch.equal(y_st, y_ws)
