@@ -285,7 +285,7 @@ def sweep(kb, torch, synth):
         vq_rows("config5 4096->4096 K=262144 " + variant, [ps], x, both[1:], 3)
 
 
-MAIN_KERNELS = ("kan_gather", "kan_mfma", "kan_fused", "kan_bucket")
+MAIN_KERNELS = ("kan_gather", "kan_mfma", "kan_fused", "kan_bucket", "kan_column")
 
 
 def roofline_of(kt, lps, layer_edges, layer_meta, B, facts, workload, extra_param_bytes=0):

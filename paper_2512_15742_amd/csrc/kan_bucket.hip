@@ -22,7 +22,9 @@
 // The bias of an edge needs no lookup at all: the four bases sum to 1 on [-1,1], so
 // sum_i bias_ij is a per-output constant computed at preparation time.
 //
-// This file also holds the preparation kernels (count, scan, fill, bias sums, block tables).
+// This file also holds the column kernel for small prepared layers (one workgroup per output and
+// sample, windows gathered from L2, no partial sums) and the preparation kernels (count, scan,
+// fill, bias sums, block tables).
 
 #include <type_traits>
 
