@@ -90,10 +90,16 @@ __device__ __forceinline__ void split_pairs(const float (&c)[kG], uint32_t (&hi)
 // SPLIT: fp32-grade operands for the precise path at large batch: every coefficient c (fp32) is
 // written as hi = fp16(c) into cf and as lo = fp16((c - hi) * 2048) into cf_lo (hi + lo / 2048
 // carries 22 bits of c; the factor keeps the low parts out of the fp16 subnormals).
+// Two-byte ids, gains and biases (the usual storage) of whole tiles are fetched with one 16-byte
+// load per array and wave - a wave's 8 rows x 64 columns of an array are 1 KB: lane l takes the 8
+// columns from 8 (l % 8) of row l / 8 - and dealt out through a strip of LDS that only this wave
+// touches: 3 vector-memory instructions in place of 24 (the kernel is bound by its address units).
+constexpr int kPrepStripBytes = 3 * 1024;
+
 template <typename IdxT, typename GbT, typename CbT, bool SPLIT>
 __device__ __forceinline__ void prep_coef_block(const LayerPtrs& hp, uint4* __restrict__ cf, uint4* __restrict__ cf_lo,
                                                 float* __restrict__ bp, const int n_in, const int n_out, const int bx,
-                                                const int by, float (*sb)[64]) {
+                                                const int by, float (*sb)[64], unsigned char (*strips)[kPrepStripBytes]) {
   const int lane = threadIdx.x & 63, wave = threadIdx.x >> 6;
   const int j = bx * 64 + lane;
   const IdxT* idx = (const IdxT*)hp.idx;
@@ -108,19 +114,47 @@ __device__ __forceinline__ void prep_coef_block(const LayerPtrs& hp, uint4* __re
     const int wh = (ib / 8) & 1;                          // which half of the step these 8 rows are
     uint32_t id[8];
     float g[8];
+    bool wide = false;
+    if constexpr (sizeof(IdxT) == 2 && sizeof(GbT) == 2) {
+      // (uniform: a whole tile of columns, rows 16-byte aligned)
+      wide = (n_out & 7) == 0 && bx * 64 + 64 <= n_out &&
+             ((((size_t)hp.idx) | ((size_t)hp.gain) | ((size_t)hp.bias)) & 15) == 0;
+      if (wide) {
+        unsigned char* strip = strips[wave];
+        const long long e16 = (long long)min(ib + (lane >> 3), n_in - 1) * n_out + bx * 64 + (lane & 7) * 8;
+        const u32x4 vi = __builtin_nontemporal_load((const u32x4*)(idx + e16));
+        const u32x4 vg = __builtin_nontemporal_load((const u32x4*)(gain + e16));
+        const u32x4 vb = __builtin_nontemporal_load((const u32x4*)(bias + e16));
+        *(u32x4*)(strip + lane * 16) = vi;                  // [row][column], 128 bytes per row
+        *(u32x4*)(strip + 1024 + lane * 16) = vg;
+        *(u32x4*)(strip + 2048 + lane * 16) = vb;
+        __builtin_amdgcn_wave_barrier();
 #pragma unroll
-    for (int r = 0; r < 8; ++r) {
-      const int i = ib + r;
-      const bool ok = i < n_in;
-      const long long e = (long long)min(i, n_in - 1) * n_out + j;
-      uint32_t idv[1];
-      float gv[1], bv[1];
-      load_idx<IdxT, 1>(idx + e, idv);
-      load_gain<GbT, 1>(gain + e, qp, gv);
-      load_bias<GbT, 1>(bias + e, qp, bv);
-      id[r] = idv[0];
-      g[r] = ok ? gv[0] : 0.f;
-      bs += ok ? bv[0] : 0.f;
+        for (int r = 0; r < 8; ++r) {
+          const bool ok = ib + r < n_in;
+          id[r] = *(const uint16_t*)(strip + (r * 64 + lane) * 2);
+          const float gv = __half2float(*(const __half*)(strip + 1024 + (r * 64 + lane) * 2));
+          const float bv = __half2float(*(const __half*)(strip + 2048 + (r * 64 + lane) * 2));
+          g[r] = ok ? gv : 0.f;
+          bs += ok ? bv : 0.f;
+        }
+      }
+    }
+    if (!wide) {
+#pragma unroll
+      for (int r = 0; r < 8; ++r) {
+        const int i = ib + r;
+        const bool ok = i < n_in;
+        const long long e = (long long)min(i, n_in - 1) * n_out + j;
+        uint32_t idv[1];
+        float gv[1], bv[1];
+        load_idx<IdxT, 1>(idx + e, idv);
+        load_gain<GbT, 1>(gain + e, qp, gv);
+        load_bias<GbT, 1>(bias + e, qp, bv);
+        id[r] = idv[0];
+        g[r] = ok ? gv[0] : 0.f;
+        bs += ok ? bv[0] : 0.f;
+      }
     }
     RawRow<CbT> raw[8];
 #pragma unroll
@@ -168,11 +202,12 @@ __device__ __forceinline__ void prep_coef_block(const LayerPtrs& hp, uint4* __re
 template <typename IdxT, typename GbT, typename CbT, bool SPLIT>
 __global__ __launch_bounds__(kThreads) void kan_prep_coef_kernel(const PrepCoefArgs a) {
   __shared__ float sb[4][64];
+  __shared__ __attribute__((aligned(16))) unsigned char strips[4][kPrepStripBytes];
   const int head = blockIdx.z;
   prep_coef_block<IdxT, GbT, CbT, SPLIT>(a.h[head], a.cf + (long long)head * a.cf_head_stride,
                                          SPLIT ? a.cf_lo + (long long)head * a.cf_head_stride : nullptr,
                                          a.bias_partial + (long long)head * a.bp_head_stride, a.n_in, a.n_out,
-                                         blockIdx.x, blockIdx.y, sb);
+                                         blockIdx.x, blockIdx.y, sb, strips);
 }
 
 // ---- kan_prep_dense -----------------------------------------------------------------
@@ -311,6 +346,7 @@ __global__ __launch_bounds__(256) void kan_prep_basis_kernel(const float* __rest
 template <typename IdxT, typename GbT, typename CbT, bool SPLIT>
 __global__ __launch_bounds__(kThreads) void kan_prep_start_kernel(const PrepStartArgs a) {
   __shared__ float sb[4][64];
+  __shared__ __attribute__((aligned(16))) unsigned char strips[4][kPrepStripBytes];
   __shared__ uint2 tile[32][33];
   __shared__ uint2 tile_lo[SPLIT ? 32 : 1][33];
   const int blk = blockIdx.x;
@@ -320,7 +356,7 @@ __global__ __launch_bounds__(kThreads) void kan_prep_start_kernel(const PrepStar
   if (k < a.n_jobs) {
     const PrepStartArgs::Job& job = a.job[k];
     prep_coef_block<IdxT, GbT, CbT, SPLIT>(job.h, job.cf, SPLIT ? job.cf_lo : nullptr, job.bp, job.n_in, job.n_out,
-                                           rel % job.nx, rel / job.nx, sb);
+                                           rel % job.nx, rel / job.nx, sb, strips);
   } else {
     prep_basis_block(a.x, 1, 0, 0, a.W, SPLIT ? a.W_lo : nullptr, a.n_in, a.B, a.rule, rel % a.basis_nx,
                      rel / a.basis_nx, tile, SPLIT ? tile_lo : tile);
