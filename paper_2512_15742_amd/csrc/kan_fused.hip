@@ -40,7 +40,7 @@ constexpr int BN = kFusedTileN;        // outputs per workgroup: 4 waves x 32
 constexpr int LDH = 88;                // fp16 tile: row stride in halves (176 B)
 constexpr int LDF = 84;                // fp32 tile: row stride in floats (336 B); row = [h][s][m]
 
-// STAGE (deep pipeline only): the per-edge metadata of two steps (16 input rows x the wave's 32
+// STAGE: the per-edge metadata of two steps (16 input rows x the wave's 32
 // columns) comes in with one 16-byte load per lane and array and is dealt to the lanes that own
 // the columns through a wave-private strip of LDS, instead of one 2-byte load per lane, row and
 // array: 3 vector-memory instructions per two steps instead of 24 (the address unit of the CU,
@@ -286,7 +286,7 @@ __global__ __launch_bounds__(kThreads, 2) void kan_fused_kernel(const FusedArgs 
     __builtin_amdgcn_wave_barrier();
   };
   // the values of step `k` (half `sp` = k & 1 of the pair in the strip), with the masks of load_meta_deep
-  auto stage_read = [&](int k, int sp, Ids& ids, GainBias& gb) {
+  auto stage_read_into = [&](int k, int sp, uint32_t (&out_id)[4], float (&out_g)[4], float (&out_b)[4]) {
     const unsigned char* strip = sMeta[wave];
     const bool live = k < n_steps;
     // columns past n_out were read from the last 16 / E columns of the row: this lane's slot then holds another
@@ -310,11 +310,12 @@ __global__ __launch_bounds__(kThreads, 2) void kan_fused_kernel(const FusedArgs 
         g = gv;
         b = bv;
       }
-      ids.id[s] = (live && j_ok) ? (uint32_t)idv : 0u;
-      gb.g[s] = ok ? g * gmul : 0.f;
-      gb.b[s] = ok ? b : 0.f;
+      out_id[s] = (live && j_ok) ? (uint32_t)idv : 0u;
+      out_g[s] = ok ? g * gmul : 0.f;
+      out_b[s] = ok ? b : 0.f;
     }
   };
+  auto stage_read = [&](int k, int sp, Ids& ids, GainBias& gb) { stage_read_into(k, sp, ids.id, gb.g, gb.b); };
 
   auto load_u = [&](int k, float (&uv)[NPAIR]) {
     const int i = i_begin + k * IT + NPAIR * ph;
@@ -518,13 +519,25 @@ __global__ __launch_bounds__(kThreads, 2) void kan_fused_kernel(const FusedArgs 
     Frag frag[2];
     // Nothing is fetched for steps past the end: the address units that serve the random
     // codeword gathers are the bottleneck of this kernel, so wasted gathers are not free.
-    load_meta(0, meta[0]);
-    if (1 < n_steps) load_meta(1, meta[1]);
-    load_u(0, uv[0]);
-    gather_rows(meta[0], rows[0]);
-    if (2 < n_steps) load_meta(2, meta[2]);
-    if (1 < n_steps) gather_rows(meta[1], rows[1]);
-    if (3 < n_steps) load_meta(3, meta[3]);
+    MetaRaw mraw;                                     // STAGE: the pair of steps on its way from memory
+    if constexpr (STAGE) {
+      stage_issue(0, mraw);
+      stage_commit(mraw);
+      stage_read_into(0, 0, meta[0].id, meta[0].g, meta[0].b);
+      stage_read_into(1, 1, meta[1].id, meta[1].g, meta[1].b);
+      if (2 < n_steps) stage_issue(1, mraw);
+      load_u(0, uv[0]);
+      gather_rows(meta[0], rows[0]);
+      if (1 < n_steps) gather_rows(meta[1], rows[1]);
+    } else {
+      load_meta(0, meta[0]);
+      if (1 < n_steps) load_meta(1, meta[1]);
+      load_u(0, uv[0]);
+      gather_rows(meta[0], rows[0]);
+      if (2 < n_steps) load_meta(2, meta[2]);
+      if (1 < n_steps) gather_rows(meta[1], rows[1]);
+      if (3 < n_steps) load_meta(3, meta[3]);
+    }
     load_u(1, uv[1]);
     dequant_step(rows[0], meta[0], frag[0]);
     gen_phi(uv[0], sTile[0]);
@@ -533,8 +546,19 @@ __global__ __launch_bounds__(kThreads, 2) void kan_fused_kernel(const FusedArgs 
       constexpr int t = decltype(T)::value;          // k mod 4
       __syncthreads();     // tile k is complete; every wave is done reading tile k-1
       if (k + 1 < n_steps) dequant_step(rows[(t + 1) & 1], meta[(t + 1) & 3], frag[(t + 1) & 1]);   // step k+1 fragments
+      if constexpr (STAGE && (t & 1) == 0) {
+        // the pair of steps k+2, k+3 arrived behind the codewords that the fragments above waited for
+        if (k + 2 < n_steps) {
+          stage_commit(mraw);
+          stage_read_into(k + 2, 0, meta[(t + 2) & 3].id, meta[(t + 2) & 3].g, meta[(t + 2) & 3].b);
+          stage_read_into(k + 3, 1, meta[(t + 3) & 3].id, meta[(t + 3) & 3].g, meta[(t + 3) & 3].b);
+          if (k + 4 < n_steps) stage_issue((k >> 1) + 2, mraw);                                     // steps k+4, k+5
+        }
+      }
       if (k + 2 < n_steps) gather_rows(meta[(t + 2) & 3], rows[t & 1]);                             // step k+2 codewords
-      if (k + 4 < n_steps) load_meta(k + 4, meta[t & 3]);                                           // step k+4 metadata
+      if constexpr (!STAGE) {
+        if (k + 4 < n_steps) load_meta(k + 4, meta[t & 3]);                                         // step k+4 metadata
+      }
       mfma_step(sTile[t & 1], frag[t & 1]);
       if (k + 1 < n_steps) gen_phi(uv[(t + 1) & 1], sTile[(t + 1) & 1]);                            // step k+1 basis tile
       if (k + 2 < n_steps) load_u(k + 2, uv[t & 1]);
@@ -573,10 +597,13 @@ __global__ __launch_bounds__(kThreads, 2) void kan_fused_kernel(const FusedArgs 
 template <typename IdxT, typename GbT, typename CbT>
 hipError_t launch_variant(const FusedArgs& a, bool f32, int mblk, bool stage, dim3 grid, hipStream_t s) {
   if (f32) {
-    if (mblk == 1) hipLaunchKernelGGL((kan_fused_kernel<IdxT, GbT, CbT, true, 1, false>), grid, dim3(kThreads), 0, s, a);
+    if (mblk == 1 && stage) hipLaunchKernelGGL((kan_fused_kernel<IdxT, GbT, CbT, true, 1, true>), grid, dim3(kThreads), 0, s, a);
+    else if (mblk == 1) hipLaunchKernelGGL((kan_fused_kernel<IdxT, GbT, CbT, true, 1, false>), grid, dim3(kThreads), 0, s, a);
+    else if (stage) hipLaunchKernelGGL((kan_fused_kernel<IdxT, GbT, CbT, true, 2, true>), grid, dim3(kThreads), 0, s, a);
     else hipLaunchKernelGGL((kan_fused_kernel<IdxT, GbT, CbT, true, 2, false>), grid, dim3(kThreads), 0, s, a);
   } else {
-    if (mblk == 1) hipLaunchKernelGGL((kan_fused_kernel<IdxT, GbT, CbT, false, 1, false>), grid, dim3(kThreads), 0, s, a);
+    if (mblk == 1 && stage) hipLaunchKernelGGL((kan_fused_kernel<IdxT, GbT, CbT, false, 1, true>), grid, dim3(kThreads), 0, s, a);
+    else if (mblk == 1) hipLaunchKernelGGL((kan_fused_kernel<IdxT, GbT, CbT, false, 1, false>), grid, dim3(kThreads), 0, s, a);
     else if constexpr (sizeof(CbT) != 4) {            // (fp32 rows keep two steps of codewords in flight: not staged)
       if (stage) hipLaunchKernelGGL((kan_fused_kernel<IdxT, GbT, CbT, false, 2, true>), grid, dim3(kThreads), 0, s, a);
       else hipLaunchKernelGGL((kan_fused_kernel<IdxT, GbT, CbT, false, 2, false>), grid, dim3(kThreads), 0, s, a);
