@@ -315,12 +315,17 @@ __device__ __forceinline__ void prep_basis_block(const float* __restrict__ xh, c
     if (wl) tile_lo[ty + 8 * r][tx] = vlo;
   }
   __syncthreads();
+  // the words of a pair of inputs lie side by side: one 16-byte store per thread and pair
 #pragma unroll
-  for (int r = 0; r < 4; ++r) {
-    const int i = ib + ty + 8 * r, b = bb + tx;
+  for (int r = 0; r < 2; ++r) {
+    const int p = ty + 8 * r, i = ib + 2 * p, b = bb + tx;
     if (i < (n_in + IT - 1) / IT * IT && b < B) {    // rows up to a whole step: zeros
-      wh[((long long)(i >> 1) * B + b) * 2 + (i & 1)] = tile[tx][ty + 8 * r];
-      if (wl) wl[((long long)(i >> 1) * B + b) * 2 + (i & 1)] = tile_lo[tx][ty + 8 * r];
+      const uint2 e0 = tile[tx][2 * p], e1 = tile[tx][2 * p + 1];
+      ((uint4*)wh)[(long long)(i >> 1) * B + b] = make_uint4(e0.x, e0.y, e1.x, e1.y);
+      if (wl) {
+        const uint2 l0 = tile_lo[tx][2 * p], l1 = tile_lo[tx][2 * p + 1];
+        ((uint4*)wl)[(long long)(i >> 1) * B + b] = make_uint4(l0.x, l0.y, l1.x, l1.y);
+      }
     }
   }
 }
