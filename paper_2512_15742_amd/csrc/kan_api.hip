@@ -179,7 +179,7 @@ constexpr int kMfmaTileN = 128;
 constexpr int kMfmaRowsStep = kMfmaPrepRows;   // chunk boundaries coincide with partial bias sums
 constexpr int kMfmaTargetWorkgroups = 512;
 constexpr int kMfmaMinRows = 64;
-constexpr int kMfmaMaxSteps = 128;            // steps of 16 inputs per workgroup of the streaming contraction
+constexpr int kMfmaMaxSteps = 256;            // steps of 16 inputs per workgroup of the streaming contraction
 constexpr int64_t kHalfFusedMaxBatch = 64;   // fp16 path: fused kernel up to here, streaming contraction above
 constexpr long long kFusedMinEdgesForResidency = 1 << 17;   // ... for layers of at least this many edges per head
 constexpr int kFusedMinWgsPerHead = 24;      // fused kernel, several heads: workgroups per head (L2 residency of the codebooks)
@@ -215,10 +215,12 @@ LayerPlan plan_mfma(int n_in, int n_out, int64_t B, int n_heads, int idx_u32, in
   const long long base = (long long)n_heads * p.n_jt * p.n_bt;
   long long chunks = kMfmaTargetWorkgroups / (base > 0 ? base : 1);
   // A workgroup that lives for hundreds of steps drifts away from the others of its XCD, which work on
-  // the same rows and columns of the operands, by more steps than that XCD's L2 holds (about nine of a
-  // patch of 8 x 8 tiles): operands are then fetched again and again (config 5, 256 steps: 15 GB for
-  // 0.6 GB of operands, L2 hit rate 46 %).  At most kMfmaMaxSteps steps per workgroup; the partial sums
-  // this costs (one slice of the output per chunk) are the smaller price: 2.56 -> 2.27 ms + 65 us.
+  // the same rows and columns of the operands, by more steps than that XCD's L2 holds: operands are then
+  // fetched again and again (config 5 with patches of 8 x 8 tiles and 256 steps: 15 GB for 0.6 GB of
+  // operands, L2 hit rate 46 %, 2.56 ms; capped at 128 steps 2.27 ms + 65 us for the reduction).  With the
+  // patches of 32 sample tiles x 2 output tiles the kernel uses now (64 workgroups share two slices of the
+  // coefficient records, the larger operand) the uncapped form is the faster one: 2.50 against 2.62 ms per
+  // step, no partial sums, no reduction.  The cap remains for layers of more than 4096 inputs.
   const long long by_steps = ((n_in + 15) / 16 + kMfmaMaxSteps - 1) / kMfmaMaxSteps;
   if (chunks < by_steps) chunks = by_steps;
   if (chunks > max_chunks) chunks = max_chunks;
