@@ -90,11 +90,29 @@ __device__ __forceinline__ void split_pairs(const float (&c)[kG], uint32_t (&hi)
 // SPLIT: fp32-grade operands for the precise path at large batch: every coefficient c (fp32) is
 // written as hi = fp16(c) into cf and as lo = fp16((c - hi) * 2048) into cf_lo (hi + lo / 2048
 // carries 22 bits of c; the factor keeps the low parts out of the fp16 subnormals).
-// Two-byte ids, gains and biases (the usual storage) of whole tiles are fetched with one 16-byte
-// load per array and wave - a wave's 8 rows x 64 columns of an array are 1 KB: lane l takes the 8
-// columns from 8 (l % 8) of row l / 8 - and dealt out through a strip of LDS that only this wave
-// touches: 3 vector-memory instructions in place of 24 (the kernel is bound by its address units).
-constexpr int kPrepStripBytes = 3 * 1024;
+// The ids, gains and biases of whole tiles are fetched with 16-byte loads - a wave's 8 rows x 64
+// columns of an array of E-byte elements are 512 E bytes, E / 2 loads per lane (unit t = row
+// t / (4 E), 16 / E columns from (t % (4 E)) * 16 / E) - and dealt out to the lanes that own the
+// columns through a strip of LDS that only this wave touches: with two-byte elements 3
+// vector-memory instructions in place of 24 (the kernel is bound by its address units).
+constexpr int kPrepStripBytes = 3 * 2048;      // three arrays of at most 4-byte elements
+
+template <int E>
+__device__ __forceinline__ void prep_wide_load(const void* base, int ib, int n_in, int n_out, int col0, int lane,
+                                               u32x4 (&v)[(E + 1) / 2]) {
+#pragma unroll
+  for (int u = 0; u < (E + 1) / 2; ++u) {
+    const int t = (lane + 64 * u) & (32 * E - 1);          // (one-byte arrays: the upper half of the wave repeats the lower)
+    const int r = t / (4 * E), part = t % (4 * E);
+    v[u] = __builtin_nontemporal_load(
+        (const u32x4*)((const char*)base + ((size_t)min(ib + r, n_in - 1) * n_out + col0) * E + part * 16));
+  }
+}
+template <int E>
+__device__ __forceinline__ void prep_wide_store(unsigned char* strip, int lane, const u32x4 (&v)[(E + 1) / 2]) {
+#pragma unroll
+  for (int u = 0; u < (E + 1) / 2; ++u) *(u32x4*)(strip + ((lane + 64 * u) & (32 * E - 1)) * 16) = v[u];
+}
 
 template <typename IdxT, typename GbT, typename CbT, bool SPLIT>
 __device__ __forceinline__ void prep_coef_block(const LayerPtrs& hp, uint4* __restrict__ cf, uint4* __restrict__ cf_lo,
@@ -114,30 +132,41 @@ __device__ __forceinline__ void prep_coef_block(const LayerPtrs& hp, uint4* __re
     const int wh = (ib / 8) & 1;                          // which half of the step these 8 rows are
     uint32_t id[8];
     float g[8];
-    bool wide = false;
-    if constexpr (sizeof(IdxT) == 2 && sizeof(GbT) == 2) {
-      // (uniform: a whole tile of columns, rows 16-byte aligned)
-      wide = (n_out & 7) == 0 && bx * 64 + 64 <= n_out &&
-             ((((size_t)hp.idx) | ((size_t)hp.gain) | ((size_t)hp.bias)) & 15) == 0;
-      if (wide) {
-        unsigned char* strip = strips[wave];
-        const long long e16 = (long long)min(ib + (lane >> 3), n_in - 1) * n_out + bx * 64 + (lane & 7) * 8;
-        const u32x4 vi = __builtin_nontemporal_load((const u32x4*)(idx + e16));
-        const u32x4 vg = __builtin_nontemporal_load((const u32x4*)(gain + e16));
-        const u32x4 vb = __builtin_nontemporal_load((const u32x4*)(bias + e16));
-        *(u32x4*)(strip + lane * 16) = vi;                  // [row][column], 128 bytes per row
-        *(u32x4*)(strip + 1024 + lane * 16) = vg;
-        *(u32x4*)(strip + 2048 + lane * 16) = vb;
-        __builtin_amdgcn_wave_barrier();
+    // (uniform: a whole tile of columns, rows that are whole 16-byte units)
+    // (with 32-bit ids - large codebooks, whose gathers miss in L2 - the narrow loads were the faster ones:
+    // config 5's preparation 276 against 305 us)
+    const bool wide = sizeof(IdxT) == 2 && (n_out & 15) == 0 && bx * 64 + 64 <= n_out &&
+                      ((((size_t)hp.idx) | ((size_t)hp.gain) | ((size_t)hp.bias)) & 15) == 0;
+    if (wide) {
+      constexpr int EI = (int)sizeof(IdxT), EG = (int)sizeof(GbT);
+      unsigned char* strip = strips[wave];
+      u32x4 vi[(EI + 1) / 2], vg[(EG + 1) / 2], vb[(EG + 1) / 2];
+      prep_wide_load<EI>(idx, ib, n_in, n_out, bx * 64, lane, vi);
+      prep_wide_load<EG>(gain, ib, n_in, n_out, bx * 64, lane, vg);
+      prep_wide_load<EG>(bias, ib, n_in, n_out, bx * 64, lane, vb);
+      prep_wide_store<EI>(strip, lane, vi);                       // [row][column] per array
+      prep_wide_store<EG>(strip + 2048, lane, vg);
+      prep_wide_store<EG>(strip + 4096, lane, vb);
+      __builtin_amdgcn_wave_barrier();
 #pragma unroll
-        for (int r = 0; r < 8; ++r) {
-          const bool ok = ib + r < n_in;
-          id[r] = *(const uint16_t*)(strip + (r * 64 + lane) * 2);
-          const float gv = __half2float(*(const __half*)(strip + 1024 + (r * 64 + lane) * 2));
-          const float bv = __half2float(*(const __half*)(strip + 2048 + (r * 64 + lane) * 2));
-          g[r] = ok ? gv : 0.f;
-          bs += ok ? bv : 0.f;
+      for (int r = 0; r < 8; ++r) {
+        const bool ok = ib + r < n_in;
+        id[r] = (uint32_t)*(const IdxT*)(strip + (r * 64 + lane) * EI);
+        const GbT gr = *(const GbT*)(strip + 2048 + (r * 64 + lane) * EG);
+        const GbT br = *(const GbT*)(strip + 4096 + (r * 64 + lane) * EG);
+        float gv, bv;
+        if constexpr (EG == 1) {
+          gv = q8_gain(gr.v, qp);
+          bv = q8_bias(br.v, qp);
+        } else if constexpr (EG == 2) {
+          gv = __half2float(gr);
+          bv = __half2float(br);
+        } else {
+          gv = gr;
+          bv = br;
         }
+        g[r] = ok ? gv : 0.f;
+        bs += ok ? bv : 0.f;
       }
     }
     if (!wide) {
