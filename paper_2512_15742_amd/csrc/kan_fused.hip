@@ -98,9 +98,14 @@ __global__ __launch_bounds__(kThreads, 2) void kan_fused_kernel(const FusedArgs 
   const float gmul = F32 ? scale : 1.0f;        // the precise form's coefficients carry the scale themselves
   const float* xh = a.x + (long long)head * a.x_head_stride;
 
-  // Phi generation: sample row pb, inputs NPAIR*ph .. of every step
-  const int pb = tid & (BM - 1), ph = tid / BM;
-  const float* xrow = xh + (long long)min(b0 + pb, B - 1) * n_in;
+  // Phi generation: input pin of every step for the sample rows psm, psm + 32, ...  Eight neighbouring lanes
+  // read eight consecutive inputs of one sample, so a load of x touches 8 cache lines, not 64 (lanes along
+  // the samples made every such load as dear to the address unit as a codeword gather).
+  static_assert(IT == 8, "eight inputs per step: one per lane of a group of eight");
+  const int pin = tid & 7, psm = tid >> 3;
+  const float* xrow[NPAIR];
+#pragma unroll
+  for (int q = 0; q < NPAIR; ++q) xrow[q] = xh + (long long)min(b0 + psm + 32 * q, B - 1) * n_in;
   // coefficient operand: column jc, input rows 4*lh .. 4*lh+3 of every step
   const int j = jt * BN + wave * 32 + ln;
   const bool j_ok = j < n_out;
@@ -318,14 +323,14 @@ __global__ __launch_bounds__(kThreads, 2) void kan_fused_kernel(const FusedArgs 
   auto stage_read = [&](int k, int sp, Ids& ids, GainBias& gb) { stage_read_into(k, sp, ids.id, gb.g, gb.b); };
 
   auto load_u = [&](int k, float (&uv)[NPAIR]) {
-    const int i = i_begin + k * IT + NPAIR * ph;
+    const int i = min(i_begin + k * IT + pin, n_in - 1);
 #pragma unroll
-    for (int q = 0; q < NPAIR; ++q) uv[q] = xrow[min(i + q, n_in - 1)];
+    for (int q = 0; q < NPAIR; ++q) uv[q] = xrow[q][i];
   };
   auto gen_phi = [&](const float (&uv)[NPAIR], unsigned char* tile) {
 #pragma unroll
     for (int q = 0; q < NPAIR; ++q) {
-      const int ii = NPAIR * ph + q, h = ii >> 2, s = ii & 3;
+      const int pb = psm + 32 * q, h = pin >> 2, s = pin & 3;
       const BasisW bw = basis_fast(uv[q], a.rule);
       const int l = bw.span;
       const float w0 = bw.w0, w1 = bw.w1, w2 = bw.w2, w3 = bw.w3;
