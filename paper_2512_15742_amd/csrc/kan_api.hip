@@ -182,7 +182,7 @@ constexpr int kMfmaMinRows = 64;
 constexpr int kMfmaMaxSteps = 256;            // steps of 16 inputs per workgroup of the streaming contraction
 constexpr int64_t kHalfFusedMaxBatch = 64;   // fp16 path: fused kernel up to here, streaming contraction above
 constexpr long long kFusedMinEdgesForResidency = 1 << 17;   // ... for layers of at least this many edges per head
-constexpr int kFusedMinWgsPerHead = 24;      // fused kernel, several heads: workgroups per head (L2 residency of the codebooks)
+constexpr int kFusedMinWgsPerHead = 20;      // fused kernel, several heads: workgroups per head (L2 residency of the codebooks)
 // Precise path: from this batch on the split-operand matrix-core form.  Its time hardly depends on
 // the batch below 128 (config 3: 96 us, config 2: 44 us) while the fused fp32 kernel's doubles with
 // its second tile of 64 samples (config 3: 97 us at 64, 113 at 80; config 2: 33 and 57).
