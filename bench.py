@@ -339,6 +339,25 @@ def run_leg(kb, torch, sets, x, path, steps, warmup, layer_edges, layer_meta, fa
             "workspace_bytes": ws_bytes}
 
 
+def two_stream_leg(kb, torch, sets, x, path, steps, warmup, edge_evals):
+    """Throughput with two requests in flight: the same steps dealt alternately to two streams of equal
+    (default) priority, each with its own workspace and output, so that one step's latency-bound phases
+    overlap the other's.  Reported beside the one-stream figures, which stay the headline."""
+    B = x.shape[0]
+    heads0 = sets[0]
+    streams = [torch.cuda.Stream() for _ in range(2)]
+    wss = [torch.empty(max(kb.kan_vq_workspace_bytes(heads0, B, path), 256), dtype=torch.uint8, device="cuda") for _ in range(2)]
+    ys = [torch.empty((len(heads0), B, heads0[0][-1].n_out), dtype=torch.float32, device="cuda") for _ in range(2)]
+    torch.cuda.synchronize()
+
+    def step(s):
+        with torch.cuda.stream(streams[s & 1]):
+            kb.kan_vq_head_forward(sets[s % len(sets)], x, path=path, ws=wss[s & 1], y=ys[s & 1])
+
+    t = time_steps(torch, step, steps, warmup)
+    return {"streams": 2, "ms_per_step": 1e3 * t, "edge_evals_per_s": edge_evals / t}
+
+
 def dense_leg(kb, torch, dims, n_heads, x, steps, warmup):
     """The same shapes through the dense-coefficient baseline (40 bytes per edge): one
     kan_dense_layer_forward per head and layer, tanh (torch) between the layers.  The time does not
@@ -475,6 +494,8 @@ def config3_legs(kb, torch, synth, args, path, facts, with_cpu):
         warm = run_leg(kb, torch, sets, x, path, steps, args.warmup, edges, meta, facts, "config3", cold=False) \
             if not args.only else None
         r["prepared_layers"] = bool(prepared)
+        if not args.only and B >= 4:
+            r["two_streams"] = two_stream_leg(kb, torch, sets, x, path, steps, args.warmup, sum(edges) * B)
         if warm:
             r["ms_per_step_cache_warm"] = warm["ms_per_step"]
             r["edge_evals_per_s_cache_warm"] = warm["edge_evals_per_s"]
