@@ -21,6 +21,11 @@
  *     runtime malloc: paper section 4.3).  ws must be 256-byte aligned.
  *   - Work is enqueued on `stream` (a hipStream_t passed as void*; NULL is the
  *     default stream).  No call synchronises the device or reads results back.
+ *   - The forward calls keep no state between calls, on the host or on the device: calls
+ *     from different host threads or on different streams are independent as long as each
+ *     has its own workspace and output, and may overlap on the GPU (the timing hooks
+ *     kan_prof_begin / kan_prof_end, and kan_vq_head_forward_static with its one scratch
+ *     array per GPU, are the exceptions: see there).
  *   - Arguments are validated on the host first: every status but KAN_OK and
  *     KAN_ERR_LAUNCH means that nothing has been enqueued.  KAN_ERR_LAUNCH (the HIP
  *     runtime rejected a kernel launch) can come after earlier kernels of the same

@@ -841,10 +841,10 @@ kan_status head_forward(const kan_vq_layer* layers, int32_t n_layers, int32_t n_
   }
 
   struct LayerScope {      // launches of the loop below are timed per layer
-    ~LayerScope() { g_prof.cur_layer = 0; }
+    ~LayerScope() { if (g_prof.on) g_prof.cur_layer = 0; }
   } layer_scope;
   for (int l = 0; l < n_layers; ++l) {
-    g_prof.cur_layer = l + 1;
+    if (g_prof.on) g_prof.cur_layer = l + 1;       // (timing hooks: one thread, nothing else in flight)
     const kan_vq_layer& R = layers[l];
     const bool last = (l + 1 == n_layers);
     w.cf = cf_base + wl.cf_off[l] / sizeof(uint4);

@@ -48,3 +48,43 @@ def test_two_streams_give_the_serial_bits(kb, B, path, prepared):
     torch.cuda.synchronize()
     for r in range(2):
         assert torch.equal(ys[r], serial[r]), r
+
+
+def test_two_host_threads_give_the_serial_bits(kb):
+    """The same from two host threads (ctypes releases the interpreter lock during a call)."""
+    import threading
+    dims = [(520, 264), (264, 21)]
+    Ps = [synth.make_layer(240 + l, i, o, 20000, cb_dtype="i8", gb_dtype="f16") for l, (i, o) in enumerate(dims)]
+    Ls = [kb.VQLayer(p) for p in Ps]
+    cases = [(16, kb.KAN_PATH_GATHER), (200, kb.KAN_PATH_MFMA)]
+    xs = [torch.from_numpy(synth.make_x(270 + r, B, 520)).cuda() for r, (B, _) in enumerate(cases)]
+    wss = [torch.empty(max(kb.kan_vq_workspace_bytes([Ls], B, p), 256), dtype=torch.uint8, device="cuda") for B, p in cases]
+    serial = []
+    for r, (B, p) in enumerate(cases):
+        y = torch.empty((1, B, 21), dtype=torch.float32, device="cuda")
+        kb.kan_vq_head_forward([Ls], xs[r], path=p, ws=wss[r], y=y)
+        serial.append(y)
+    torch.cuda.synchronize()
+    streams = [torch.cuda.Stream() for _ in cases]
+    ys = [torch.full((1, B, 21), float("nan"), dtype=torch.float32, device="cuda") for B, _ in cases]
+    torch.cuda.synchronize()
+    errors = []
+
+    def work(r):
+        try:
+            B, p = cases[r]
+            with torch.cuda.stream(streams[r]):
+                for _ in range(20):
+                    kb.kan_vq_head_forward([Ls], xs[r], path=p, ws=wss[r], y=ys[r])
+        except Exception as e:           # pragma: no cover
+            errors.append(e)
+
+    threads = [threading.Thread(target=work, args=(r,)) for r in range(len(cases))]
+    for t in threads:
+        t.start()
+    for t in threads:
+        t.join()
+    torch.cuda.synchronize()
+    assert not errors, errors
+    for r in range(len(cases)):
+        assert torch.equal(ys[r], serial[r]), r
