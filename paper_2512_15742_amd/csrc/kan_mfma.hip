@@ -299,20 +299,34 @@ __device__ __forceinline__ void prep_basis_block(const float* __restrict__ xh, c
                                                  uint2 (*tile)[33], uint2 (*tile_lo)[33]) {
   const int tx = threadIdx.x & 31, ty = threadIdx.x >> 5;      // 32 x 8
   const int ib = bx * 32, bb = by * 32;
+  // The inputs of the thread's four elements first, every load unconditional (clamped addresses): the
+  // slices of all four are in flight together instead of one element's after the other's arithmetic.
+  const float* xp[4];
+  float xs[4];
+#pragma unroll
+  for (int r = 0; r < 4; ++r) {
+    xp[r] = xh + (long long)min(bb + ty + 8 * r, B - 1) * n_in + min(ib + tx, n_in - 1);
+    xs[r] = xp[r][0];
+  }
+  for (int p0 = 1; p0 < x_parts; p0 += 8) {           // eight slices in flight per element, added in order
+    float t[8][4];
+#pragma unroll
+    for (int pp = 0; pp < 8; ++pp) {
+      const long long off = (long long)min(p0 + pp, x_parts - 1) * x_part_stride;
+#pragma unroll
+      for (int r = 0; r < 4; ++r) t[pp][r] = xp[r][off];
+    }
+#pragma unroll
+    for (int pp = 0; pp < 8; ++pp)
+#pragma unroll
+      for (int r = 0; r < 4; ++r) xs[r] += p0 + pp < x_parts ? t[pp][r] : 0.f;
+  }
 #pragma unroll
   for (int r = 0; r < 4; ++r) {
     const int b = bb + ty + 8 * r, i = ib + tx;
     uint2 v = make_uint2(0u, 0u), vlo = make_uint2(0u, 0u);
     if (b < B && i < n_in) {
-      const float* xp = xh + (long long)b * n_in + i;
-      float xv = xp[0];
-      for (int p0 = 1; p0 < x_parts; p0 += 8) {       // eight slices in flight, added in order
-        float t[8];
-#pragma unroll
-        for (int pp = 0; pp < 8; ++pp) t[pp] = xp[(long long)min(p0 + pp, x_parts - 1) * x_part_stride];
-#pragma unroll
-        for (int pp = 0; pp < 8; ++pp) xv += p0 + pp < x_parts ? t[pp] : 0.f;
-      }
+      float xv = xs[r];
       if (x_tanh) xv = tanhf(xv);
       const BasisW bw = basis_fast(xv, rule);
       const uint32_t l = (uint32_t)bw.span;
