@@ -258,7 +258,12 @@ LayerPlan plan_fused(int n_in, int n_out, int64_t B, int n_heads, int idx_u32, i
   // (64-sample tiles: with a workgroup per CU and twice the steps each, the metadata of the next
   // steps is in flight behind the gathers of the current one: config 3 at batch 64 57.8 -> 51.1 us
   // on the fp16 path, 96.7 -> 82.9 us on the precise path; 32-sample tiles are better off with two)
-  const long long target = p.cfg.bt == 64 ? kTargetWorkgroups / 2 : kTargetWorkgroups;
+  // Two per CU again where the chunks stay long even so: at least 8 steps each for the precise form
+  // (4096 x 4096 with K = 262,144 at batch 64: 338 -> 249 us; 4096 x 1024: 67.6 -> 56.5; 2048 x 2048:
+  // 65.6 -> 56.2; 8192 x 512: 67.6 -> 60.4), at least 16 for the fp16 form (4096 x 4096: 124 -> 119 us;
+  // with 8 steps each it loses: 4096 x 1024 37.8 -> 42 us, 2048 x 2048 36.8 -> 40).
+  long long target = p.cfg.bt == 64 ? kTargetWorkgroups / 2 : kTargetWorkgroups;
+  if (p.cfg.bt == 64 && (long long)(n_in / 8) * base >= (f32 ? 16 : 32) * target) target *= 2;
   long long chunks = (target + base - 1) / (base > 0 ? base : 1);
   // Several heads in one launch: the kernel gives every XCD a contiguous run of heads, and an XCD
   // (64 resident workgroups) should work on at most two or three heads at a time so that their
