@@ -38,15 +38,15 @@
  *   - idx values must be < K; they are not checked by the forward calls (use
  *     kan_vq_count_bad_indices).  y must not alias x or the workspace.
  *   - Value range on the matrix cores (KAN_PATH_MFMA at any batch; KAN_PATH_GATHER from
- *     batch 65, the dense baseline from batch 17): the coefficient operand is carried as
+ *     batch 33, the dense baseline from batch 17): the coefficient operand is carried as
  *     fp16 numbers gain * q (Int8 codebooks, q the byte code) or gain * C (floating
  *     codebooks, dense coefficients), so these products must stay below 65504 in magnitude
  *     (gains up to about 515 with Int8 codes) or the result is infinite; products below
  *     6.1e-5 in magnitude keep fewer bits (the split form of the precise path: the 11 bits
  *     of its low part).  The stated bounds hold for layers whose |gain * q| or |gain * C| lie
  *     in [6.1e-5, 65504] or are 0; kan_vq_coef_range reports the range of a layer.  The
- *     vector-ALU, bucket and fused fp32 kernels (KAN_PATH_GATHER up to batch 64) have no
- *     such limit.
+ *     vector-ALU, bucket and column kernels and the fused kernel on fp32 operands
+ *     (KAN_PATH_GATHER up to batch 32) have no such limit.
  */
 #ifndef KAN_MI355X_H
 #define KAN_MI355X_H
@@ -78,15 +78,17 @@ typedef enum kan_dtype {
  *   KAN_PATH_GATHER  the precise path: fp32 operands, fp32 accumulation; matches the
  *                    float64 definition to ~1e-6 (bound 1e-5).  Batch 1: one 4-byte
  *                    codeword-window gather per edge on the vector ALUs; from batch 2:
- *                    fused gather + fp32 matrix-core kernel; from batch 65: the kernels
- *                    of the fp16 path run on coefficients and basis weights split into
- *                    high and low fp16 parts (three products, fp32-grade sums).  Prepared
- *                    layers (see kan_vq_prepare), batch <= 4: codebook buckets in LDS.
+ *                    fused gather + matrix-core kernel (fp32 operands up to batch 32; from
+ *                    33 coefficients and basis weights split into high and low fp16 parts,
+ *                    three products, fp32-grade sums); from batch 65 (129 for layers of
+ *                    2^22 edges or more whose codebook is not fp32): the kernels of the fp16
+ *                    path on such split operands.  Prepared layers (see kan_vq_prepare),
+ *                    batch <= 4: codebook buckets in LDS.
  *   KAN_PATH_MFMA    fp16 operands on the matrix cores, fp32 accumulation; ~3e-4
- *                    relative per layer (bound 2e-2).  Batch <= 64: fused gather +
- *                    MFMA kernel; above: coefficients dequantised once per call into
- *                    the workspace in matrix-core operand order, then a streaming
- *                    contraction.
+ *                    relative per layer (bound 2e-2).  Batch <= 64 (128 for those large
+ *                    layers): fused gather + MFMA kernel; above: coefficients dequantised
+ *                    once per call into the workspace in matrix-core operand order, then a
+ *                    streaming contraction.
  *   KAN_PATH_AUTO    the precise path below batch 32, the fp16 path from there on.   */
 typedef enum kan_path { KAN_PATH_AUTO = 0, KAN_PATH_GATHER = 1, KAN_PATH_MFMA = 2 } kan_path;
 

@@ -181,6 +181,8 @@ constexpr int kMfmaTargetWorkgroups = 512;
 constexpr int kMfmaMinRows = 64;
 constexpr int kMfmaMaxSteps = 256;            // steps of 16 inputs per workgroup of the streaming contraction
 constexpr int64_t kHalfFusedMaxBatch = 64;   // fp16 path: fused kernel up to here, streaming contraction above
+constexpr int64_t kFusedTwoTilesMaxBatch = 128;            // ... and up to here (both paths) for layers of at least
+constexpr long long kFusedTwoTilesMinEdges = 1ll << 22;    // this many edges whose codeword rows are one gather each
 constexpr long long kFusedMinEdgesForResidency = 1 << 17;   // ... for layers of at least this many edges per head
 constexpr int kFusedMinWgsPerHead = 20;      // fused kernel, several heads: workgroups per head (L2 residency of the codebooks)
 // Precise path: from this batch on the split-operand matrix-core form.  Its time hardly depends on
@@ -358,22 +360,31 @@ bool layer_prepared_ok(const kan_vq_layer& L) {
 //     three passes (hi*lo, lo*hi, hi*hi: fp32-grade sums at matrix-core speed);
 //   fp16 path (KAN_PATH_MFMA, and AUTO from batch 32): up to kHalfFusedMaxBatch the fused
 //     kernel with fp16 operands, above that coefficient/basis preparation + the streaming
-//     contraction.
+//     contraction;
+//   layers of kFusedTwoTilesMinEdges edges or more (not fp32 codebooks) keep the fused kernel up to
+//     kFusedTwoTilesMaxBatch on either path.
 LayerPlan plan_vq(const kan_vq_layer& L, int64_t B, int n_heads, bool vec_ok, bool prepared_ok, int32_t path,
                   bool column_ok) {
   const int code = code_of(L);
   const int u32 = L.idx_dtype == KAN_U32, gbk = gb_kind_of(L);
   const bool half_path = path == KAN_PATH_MFMA || (path == KAN_PATH_AUTO && B >= kAutoMfmaBatch);
+  // Large layers stay on the fused kernel for a second batch tile: gathering every row twice costs less
+  // than preparing the records of 4 M edges or more and contracting them (4096 x 4096, K = 262,144, batch
+  // 96-128: 288-290 -> 210-213 us on the fp16 path, 587 -> 474-478 us precise; 4096 x 1024: 60.8 -> 57.2 and
+  // 103 -> 90-95 us; a 2048 x 1024 layer gains at batch 96 and loses at 128, config 3's head 57.5 -> 61.0 us,
+  // fp32 rows - three loads per gather - lose: config 2 at batch 128 32.4 -> 35.7 us; at batch 192 all lose).
+  const bool two_tiles = (long long)L.in * L.out >= kFusedTwoTilesMinEdges && code != kCbF32;
+  const int64_t fused_max = two_tiles ? kFusedTwoTilesMaxBatch : kHalfFusedMaxBatch;
   if (half_path) {
     // one batch tile: every edge is needed once, so nothing is staged in memory (the streaming
     // path would write 20 bytes per edge and read them back for no reuse)
-    if (B <= kHalfFusedMaxBatch) return plan_fused(L.in, L.out, B, n_heads, u32, gbk, code, false);
+    if (B <= fused_max) return plan_fused(L.in, L.out, B, n_heads, u32, gbk, code, false);
     return plan_mfma(L.in, L.out, B, n_heads, u32, gbk, code);
   }
   if (prepared_ok && B <= kBucketMaxBatch)
     return column_ok && (long long)L.in * L.out * B <= kColumnMaxWork ? plan_column(L, B) : plan_bucket(L, B, n_heads);
   // large batches: the fp16 machinery with both operands split into high and low parts
-  if (B >= kSplitMinBatch) return plan_mfma(L.in, L.out, B, n_heads, u32, gbk, code, true);
+  if (B >= kSplitMinBatch && B > fused_max) return plan_mfma(L.in, L.out, B, n_heads, u32, gbk, code, true);
   if (B >= 2) return plan_fused(L.in, L.out, B, n_heads, u32, gbk, code, true);
   return plan_gather(L.in, L.out, B, n_heads, u32, gbk, code, vec_ok);
 }

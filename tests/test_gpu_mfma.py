@@ -264,3 +264,24 @@ def test_profiled_launches_are_keyed_by_layer(kb):
     kb.kan_prof_begin(8)
     kb.kan_bspline_basis(xd[0])
     assert set(kb.kan_prof_end()) == {"kan_basis"}
+
+
+@pytest.mark.parametrize("B", [100, 128, 129])
+def test_large_layer_keeps_the_fused_kernel_for_two_batch_tiles(kb, B):
+    """A layer of 2^22 edges (Int8 rows): up to batch 128 both paths gather every row once per tile of 64
+    samples instead of preparing records; from 129 the streaming kernels take over.  Sampled outputs of
+    both tiles against the oracle, and the ragged second tile."""
+    P = synth.make_layer(610, 4096, 1024, 65536, cb_dtype="i8", gb_dtype="f16")
+    L = kb.VQLayer(P)
+    x = synth.make_x(611, B, 4096, "uniform")
+    xd = to_dev(x)
+    for path, tol, fused, streaming in ((kb.KAN_PATH_MFMA, TOL_MFMA, "kan_fused_f16", "kan_mfma"),
+                                        (kb.KAN_PATH_GATHER, TOL_FP32, "kan_fused_f32", "kan_mfma_split")):
+        assert kb.kan_vq_planned_kernel(L, B, 1, path) == (fused if B <= 128 else streaming)
+        y = kb.kan_vq_layer_forward(L, xd, path=path).cpu().numpy()
+        assert np.isfinite(y).all()
+        check_layer_output(y, x, P, tol, n_samples=96, seed=B, full=False)
+    small = kb.VQLayer(synth.make_layer(612, 2048, 1024, 65536, cb_dtype="i8", gb_dtype="f16"))
+    assert kb.kan_vq_planned_kernel(small, 100, 1, kb.KAN_PATH_MFMA) == "kan_mfma"
+    wide_rows = kb.VQLayer(synth.make_layer(613, 4096, 1024, 65536, cb_dtype="f32", gb_dtype="f32"))
+    assert kb.kan_vq_planned_kernel(wide_rows, 100, 1, kb.KAN_PATH_GATHER) == "kan_mfma_split"
