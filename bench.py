@@ -255,15 +255,19 @@ def sweep(kb, torch, synth):
         del coef, cb
     # a layer large enough to be bandwidth-bound at batch 1: config 5's Int8 layer (134 MB of metadata),
     # three copies taken in turn (402 MB: more than the memory-side cache holds)
-    (p5,), x5 = synth.config5("i8", B=16)
+    # (batch 64 and 128: one and two batch tiles of the fused kernel, which such a layer keeps up to 128)
+    (p5,), x5 = synth.config5("i8", B=128)
     for prepared in (False, True):
         copies = [kb.VQLayer(p5) for _ in range(3)]
         if prepared:
             for L in copies:
                 L.prepare()
-        for B in (1, 4, 16):
+        cases = [(1, "gather"), (4, "gather"), (16, "gather")]
+        if not prepared:
+            cases += [(64, "gather"), (64, "mfma"), (128, "gather"), (128, "mfma")]
+        for B, pname in cases:
             xd = torch.from_numpy(x5[:B]).cuda()
-            pth = kb.KAN_PATH_GATHER
+            pth = kb.KAN_PATH_GATHER if pname == "gather" else kb.KAN_PATH_MFMA
             ws = torch.empty(max(kb.kan_vq_workspace_bytes([[copies[0]]], B, pth), 256), dtype=torch.uint8, device="cuda")
             y = torch.empty((B, p5.n_out), dtype=torch.float32, device="cuda")
             turn = [0]
@@ -273,7 +277,7 @@ def sweep(kb, torch, synth):
                 turn[0] += 1
             t = wall(fwd, 30)
             print(json.dumps({"workload": "config5 layer 4096->4096 K=262144 i8, 3 copies in turn", "batch": B,
-                              "path": "gather", "prepared": prepared, "rule": "bspline3",
+                              "path": pname, "prepared": prepared, "rule": "bspline3",
                               "us_per_forward": round(t * 1e6, 2), "edge_evals_per_s": p5.edges * B / t,
                               "metadata_GBps": p5.metadata_bytes / t / 1e9,
                               "kernel": kb.kan_vq_planned_kernel(copies[0], B, 1, pth)}), flush=True)
