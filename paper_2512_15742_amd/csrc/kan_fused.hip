@@ -34,6 +34,8 @@
 namespace kan {
 namespace {
 
+typedef float f32x4 __attribute__((ext_vector_type(4)));
+
 constexpr int kThreads = 256;
 constexpr int IT = 8;                  // input rows per step
 constexpr int BN = kFusedTileN;        // outputs per workgroup: 4 waves x 32
@@ -46,8 +48,17 @@ constexpr int LDF = 84;                // fp32 tile: row stride in floats (336 B
 // array: 3 vector-memory instructions per two steps instead of 24 (the address unit of the CU,
 // which every such instruction occupies for its 64 lanes, is what bounds this kernel).  Needs
 // n_out % 16 == 0 and 16-byte aligned arrays.
-template <typename IdxT, typename GbT, typename CbT, bool F32, int MBLK, bool STAGE>
+// T16 (fp32 operands, batch <= 16): the tile is 16 samples high and the step runs on
+// v_mfma_f32_16x16x4_f32, half the matrix-pipe time of the 32-row instruction, whose upper rows would
+// be empty (the 40 fp32 MFMAs of a step are 8 of the 26 us that layer 1 of configuration 3 takes at
+// batch 16).  The wave's 32 columns are two blocks of 16; a lane serves column (lane % 16) of both
+// blocks and the inputs 2 kg, 2 kg + 1 of every step (kg = lane / 16 is its k index in the
+// instruction): slot s of a lane's four edges is input 2 kg + s % 2 in block s / 2, instead of input
+// 4 lh + s in one column.  (The other forms are compiled from the same text as before: every place
+// that differs is a branch on T16.)
+template <typename IdxT, typename GbT, typename CbT, bool F32, int MBLK, bool STAGE, bool T16 = false>
 __global__ __launch_bounds__(kThreads, 2) void kan_fused_kernel(const FusedArgs a) {
+  static_assert(!T16 || (F32 && MBLK == 1), "16-sample tiles: fp32 operands only");
   constexpr int BM = 32 * MBLK;
   constexpr int NPAIR = MBLK;          // (sample, input) pairs per thread and step
   // The precise path comes in two forms: fp32 operands for 32-sample tiles (one row block: the 40 fp32
@@ -110,6 +121,15 @@ __global__ __launch_bounds__(kThreads, 2) void kan_fused_kernel(const FusedArgs 
   const int j = jt * BN + wave * 32 + ln;
   const bool j_ok = j < n_out;
   const int jc = min(j, n_out - 1);
+  // T16: slot -> input of the step, column within the wave's 32, and that column's validity and clamped index
+  const int kg = lane >> 4, c16 = lane & 15;
+  auto t16_col = [&](int s) { return jt * BN + wave * 32 + 16 * (s >> 1) + c16; };
+  f32x4 acc4[T16 ? 2 : 1];             // T16: one accumulator per block of 16 columns
+  float bsum2[T16 ? 2 : 1];
+  if constexpr (T16) {
+    acc4[0] = acc4[1] = f32x4{0.f, 0.f, 0.f, 0.f};
+    bsum2[0] = bsum2[1] = 0.f;
+  }
 
   f32x16 acc[MBLK], acc_x[MBLK];       // (acc_x: the cross products of the split form)
 #pragma unroll
@@ -149,9 +169,18 @@ __global__ __launch_bounds__(kThreads, 2) void kan_fused_kernel(const FusedArgs 
   auto load_meta = [&](int k, Meta& m) {
 #pragma unroll
     for (int s = 0; s < 4; ++s) {
-      const int i = i_begin + k * IT + 4 * lh + s;
-      const bool ok = j_ok && i < i_end;
-      const long long e = (long long)min(i, i_end - 1) * n_out + jc;
+      int i;
+      bool ok;
+      long long e;
+      if constexpr (T16) {
+        i = i_begin + k * IT + 2 * kg + (s & 1);
+        ok = t16_col(s) < n_out && i < i_end;
+        e = (long long)min(i, i_end - 1) * n_out + min(t16_col(s), n_out - 1);
+      } else {
+        i = i_begin + k * IT + 4 * lh + s;
+        ok = j_ok && i < i_end;
+        e = (long long)min(i, i_end - 1) * n_out + jc;
+      }
       uint32_t id[1];
       float g[1], bv[1];
       load_idx<IdxT, 1>(idx + e, id);
@@ -189,7 +218,10 @@ __global__ __launch_bounds__(kThreads, 2) void kan_fused_kernel(const FusedArgs 
       out.h[4] = make_uint4(tail[0], tail[1], tail[2], tail[3]);
     }
 #pragma unroll
-    for (int s = 0; s < 4; ++s) bsum += m.b[s];
+    for (int s = 0; s < 4; ++s) {
+      if constexpr (T16) bsum2[s >> 1] += m.b[s];
+      else bsum += m.b[s];
+    }
   };
 
   // -- the same three pieces for the deep pipeline below (indices apart from gains and biases,
@@ -298,26 +330,50 @@ __global__ __launch_bounds__(kThreads, 2) void kan_fused_kernel(const FusedArgs 
     // column's value, which the masks below discard (gain and bias 0; the codeword it gathers is a valid row)
 #pragma unroll
     for (int s = 0; s < 4; ++s) {
-      const int r = sp * 8 + 4 * lh + s;
-      const int i = i_begin + k * IT + 4 * lh + s;
-      const bool ok = j_ok && i < i_end;
-      const IdxT idv = *(const IdxT*)(strip + (r * 32 + ln) * EI);
-      const GbT gv = *(const GbT*)(strip + 512 * EI + (r * 32 + ln) * EG);
-      const GbT bv = *(const GbT*)(strip + 512 * (EI + EG) + (r * 32 + ln) * EG);
-      float g, b;
-      if constexpr (EG == 1) {
-        g = q8_gain(gv.v, qp);
-        b = q8_bias(bv.v, qp);
-      } else if constexpr (EG == 2) {
-        g = __half2float(gv);
-        b = __half2float(bv);
+      auto decode = [&](IdxT idv, GbT gv, GbT bv, bool ok, bool col_ok) {
+        float g, b;
+        if constexpr (EG == 1) {
+          g = q8_gain(gv.v, qp);
+          b = q8_bias(bv.v, qp);
+        } else if constexpr (EG == 2) {
+          g = __half2float(gv);
+          b = __half2float(bv);
+        } else {
+          g = gv;
+          b = bv;
+        }
+        out_id[s] = (live && col_ok) ? (uint32_t)idv : 0u;
+        out_g[s] = ok ? g * gmul : 0.f;
+        out_b[s] = ok ? b : 0.f;
+      };
+      if constexpr (T16) {
+        const int r = sp * 8 + 2 * kg + (s & 1), cw = 16 * (s >> 1) + c16;
+        const int i = i_begin + k * IT + 2 * kg + (s & 1);
+        const bool col_ok = t16_col(s) < n_out;
+        decode(*(const IdxT*)(strip + (r * 32 + cw) * EI), *(const GbT*)(strip + 512 * EI + (r * 32 + cw) * EG),
+               *(const GbT*)(strip + 512 * (EI + EG) + (r * 32 + cw) * EG), col_ok && i < i_end, col_ok);
       } else {
-        g = gv;
-        b = bv;
+        const int r = sp * 8 + 4 * lh + s;
+        const int i = i_begin + k * IT + 4 * lh + s;
+        const bool ok = j_ok && i < i_end;
+        const IdxT idv = *(const IdxT*)(strip + (r * 32 + ln) * EI);
+        const GbT gv = *(const GbT*)(strip + 512 * EI + (r * 32 + ln) * EG);
+        const GbT bv = *(const GbT*)(strip + 512 * (EI + EG) + (r * 32 + ln) * EG);
+        float g, b;
+        if constexpr (EG == 1) {
+          g = q8_gain(gv.v, qp);
+          b = q8_bias(bv.v, qp);
+        } else if constexpr (EG == 2) {
+          g = __half2float(gv);
+          b = __half2float(bv);
+        } else {
+          g = gv;
+          b = bv;
+        }
+        out_id[s] = (live && j_ok) ? (uint32_t)idv : 0u;
+        out_g[s] = ok ? g * gmul : 0.f;
+        out_b[s] = ok ? b : 0.f;
       }
-      out_id[s] = (live && j_ok) ? (uint32_t)idv : 0u;
-      out_g[s] = ok ? g * gmul : 0.f;
-      out_b[s] = ok ? b : 0.f;
     }
   };
   auto stage_read = [&](int k, int sp, Ids& ids, GainBias& gb) { stage_read_into(k, sp, ids.id, gb.g, gb.b); };
@@ -374,6 +430,25 @@ __global__ __launch_bounds__(kThreads, 2) void kan_fused_kernel(const FusedArgs 
   // Precise form: cross products (high x low, low x high; they carry a factor 2048) into acc_x,
   // the main product into acc; every fp16 x fp16 product is exact in the fp32 accumulators.
   auto mfma_step = [&](const unsigned char* tile, const Frag& bf) {
+    if constexpr (T16) {            // MFMA t = 10 e + m multiplies, in lane group kg, coefficient m of input 2 kg + e
+      const float* p = (const float*)tile + c16 * LDF + kg * 20;
+      float av[20];
+#pragma unroll
+      for (int q = 0; q < 5; ++q) {
+        const float4 v = *(const float4*)(p + 4 * q);
+        av[4 * q] = v.x;
+        av[4 * q + 1] = v.y;
+        av[4 * q + 2] = v.z;
+        av[4 * q + 3] = v.w;
+      }
+#pragma unroll
+      for (int t = 0; t < 20; ++t)
+#pragma unroll
+        for (int cb = 0; cb < 2; ++cb)
+          acc4[T16 ? cb : 0] = __builtin_amdgcn_mfma_f32_16x16x4f32(av[t], bf.f[kFp32Ops ? 2 * cb + t / kG : 0][t % kG],
+                                                                   acc4[T16 ? cb : 0], 0, 0, 0);
+      return;
+    }
     if constexpr (kFp32Ops) {       // MFMA t = 10 s + m multiplies, in lane half h, coefficient m of input 4h + s
       const float* p = (const float*)tile + ln * LDF + lh * 40;
 #pragma unroll
@@ -582,6 +657,28 @@ __global__ __launch_bounds__(kThreads, 2) void kan_fused_kernel(const FusedArgs 
   const float bs = bsum + __shfl_xor(bsum, 32);      // both lane halves: all 8 input rows
   const float oscale = F32 ? 1.0f : scale;
   float* dst = a.dst + (long long)head * a.dst_head_stride + (long long)chunk * a.dst_chunk_stride;
+  if constexpr (T16) {
+    // D layout of the 16x16 MFMA: lane holds column (lane % 16) of its block, rows 4 * (lane / 16) + r
+#pragma unroll
+    for (int cb = 0; cb < 2; ++cb) {
+      float bs16 = bsum2[T16 ? cb : 0];                // the four lane groups: all 8 input rows
+      bs16 += __shfl_xor(bs16, 16);
+      bs16 += __shfl_xor(bs16, 32);
+      const int col = t16_col(2 * cb);
+      if (col < n_out) {
+#pragma unroll
+        for (int r = 0; r < 4; ++r) {
+          const int b = b0 + 4 * kg + r;
+          if (b < B) {
+            float v = acc4[T16 ? cb : 0][r] + bs16;    // (the scale went in with the gains)
+            if (a.apply_tanh) v = tanhf(v);
+            dst[(long long)b * n_out + col] = v;
+          }
+        }
+      }
+    }
+    return;
+  }
   if (j_ok) {
 #pragma unroll
     for (int m = 0; m < MBLK; ++m)
@@ -604,7 +701,10 @@ hipError_t launch_variant(const FusedArgs& a, bool f32, int mblk, bool stage_ok,
   // In the shallow pipeline the staged loads pay off for one- and two-byte gains and biases; with fp32 ones
   // (two 16-byte loads per array and pair, 20 more registers) config 2 at batch 16 went from 21.0 to 27.1 us.
   const bool stage = stage_ok && sizeof(GbT) <= 2;
-  if (f32) {
+  if (f32 && mblk == 1 && a.B <= 16) {       // 16-sample tiles
+    if (stage) hipLaunchKernelGGL((kan_fused_kernel<IdxT, GbT, CbT, true, 1, true, true>), grid, dim3(kThreads), 0, s, a);
+    else hipLaunchKernelGGL((kan_fused_kernel<IdxT, GbT, CbT, true, 1, false, true>), grid, dim3(kThreads), 0, s, a);
+  } else if (f32) {
     if (mblk == 1 && stage) hipLaunchKernelGGL((kan_fused_kernel<IdxT, GbT, CbT, true, 1, true>), grid, dim3(kThreads), 0, s, a);
     else if (mblk == 1) hipLaunchKernelGGL((kan_fused_kernel<IdxT, GbT, CbT, true, 1, false>), grid, dim3(kThreads), 0, s, a);
     else if (stage) hipLaunchKernelGGL((kan_fused_kernel<IdxT, GbT, CbT, true, 2, true>), grid, dim3(kThreads), 0, s, a);
