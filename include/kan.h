@@ -83,7 +83,8 @@ typedef enum kan_dtype {
  *                    three products, fp32-grade sums); from batch 65 (129 for layers of
  *                    2^22 edges or more whose codebook is not fp32): the kernels of the fp16
  *                    path on such split operands.  Prepared layers (see kan_vq_prepare),
- *                    batch <= 4: codebook buckets in LDS.
+ *                    batch <= 4 (<= 3 for layers of 2^23 edges or more): codebook buckets
+ *                    in LDS.
  *   KAN_PATH_MFMA    fp16 operands on the matrix cores, fp32 accumulation; ~3e-4
  *                    relative per layer (bound 2e-2).  Batch <= 64 (128 for those large
  *                    layers): fused gather + MFMA kernel; above: coefficients dequantised

@@ -293,6 +293,11 @@ LayerPlan plan_fused(int n_in, int n_out, int64_t B, int n_heads, int idx_u32, i
 // A workgroup occupies a whole CU (LDS), so the slices are cut to give every CU one: the
 // cuts come from the block table that the preparation made for this many (samples x heads).
 constexpr int64_t kBucketMaxBatch = 4;
+// A pass over the records per sample costs in proportion to the edges, the fused kernel's single pass for up to
+// 16 samples does not: on the largest layers the fourth sample tips it (4096 x 4096, K = 262,144, batch 2 / 3 / 4:
+// 61 / 89 / 117 us against 105-109 us fused; 4096 x 1024 and 2048 x 2048: 21 / 28 / 30-31 against 33-35 us).
+constexpr long long kBucketThreeSamplesMinEdges = 1ll << 23;
+constexpr int64_t bucket_max_batch(long long edges) { return edges >= kBucketThreeSamplesMinEdges ? 3 : kBucketMaxBatch; }
 
 LayerPlan plan_bucket(const kan_vq_layer& L, int64_t B, int n_heads) {
   LayerPlan p;
@@ -352,7 +357,8 @@ bool layer_prepared_ok(const kan_vq_layer& L) {
 }
 
 // Which kernels serve a layer:
-//   precise path, prepared layers, B <= kBucketMaxBatch: the bucket kernel (codebook in LDS);
+//   precise path, prepared layers, B <= kBucketMaxBatch (3 for layers of 2^23 edges or more): the bucket kernel
+//     (codebook in LDS);
 //   precise path (KAN_PATH_GATHER, and AUTO below batch 32): B = 1 the window-gather kernel,
 //     B >= 2 the fused kernel with fp32 matrix-core operands (the fp32 FMA kernel remains the
 //     dense baseline's), from kSplitMinBatch the preparation + streaming contraction of the
@@ -381,7 +387,7 @@ LayerPlan plan_vq(const kan_vq_layer& L, int64_t B, int n_heads, bool vec_ok, bo
     if (B <= fused_max) return plan_fused(L.in, L.out, B, n_heads, u32, gbk, code, false);
     return plan_mfma(L.in, L.out, B, n_heads, u32, gbk, code);
   }
-  if (prepared_ok && B <= kBucketMaxBatch)
+  if (prepared_ok && B <= bucket_max_batch((long long)L.in * L.out))
     return column_ok && (long long)L.in * L.out * B <= kColumnMaxWork ? plan_column(L, B) : plan_bucket(L, B, n_heads);
   // large batches: the fp16 machinery with both operands split into high and low parts
   if (B >= kSplitMinBatch && B > fused_max) return plan_mfma(L.in, L.out, B, n_heads, u32, gbk, code, true);

@@ -17,6 +17,8 @@
 //     32-sample tiles: fp32 operands, v_mfma_f32_32x32x2f32: MFMA t = 10*s + m multiplies, in
 //                lane half h, coefficient m of input 4h+s.  With one row block the 40 MFMAs of a
 //                step take about as long as its gathers.
+//     16-sample tiles (batch <= 16): fp32 operands, v_mfma_f32_16x16x4f32 on two blocks of 16
+//                columns per wave: half the matrix-pipe time, no empty rows (T16 below).
 //     64-sample tiles: both operands split into high and low fp16 parts (v = hi + lo / 2048,
 //                22 significant bits), three fp16 products per k-step (hi*lo and lo*hi into one
 //                set of accumulators, hi*hi into another); every fp16 x fp16 product is exact in

@@ -178,6 +178,12 @@ def test_fp16_codebook_layers_plan_and_prepare():
     assert L.kan_vq_planned_kernel(C.byref(d), 1, 1, kb.KAN_PATH_GATHER) == b"kan_bucket"
     assert L.kan_vq_planned_kernel(C.byref(d), 4, 1, kb.KAN_PATH_AUTO) == b"kan_bucket"
     assert L.kan_vq_planned_kernel(C.byref(d), 8, 1, kb.KAN_PATH_GATHER) == b"kan_fused_f32"
+    # the largest layers leave the bucket kernel one sample earlier (2^23 edges or more)
+    n_in0, n_out0 = d.n_in, d.n_out
+    d.n_in, d.n_out = 4096, 2048
+    assert L.kan_vq_planned_kernel(C.byref(d), 3, 1, kb.KAN_PATH_GATHER) == b"kan_bucket"
+    assert L.kan_vq_planned_kernel(C.byref(d), 4, 1, kb.KAN_PATH_GATHER) == b"kan_fused_f32"
+    d.n_in, d.n_out = n_in0, n_out0
 
 
 def test_precise_path_switches_and_workspace_sizes():
