@@ -111,6 +111,7 @@ enum PlanKind { kPlanGather = 0, kPlanMfma = 1, kPlanFused16 = 2, kPlanFused32 =
 struct LayerPlan {
   GatherCfg cfg;
   int n_jt, n_bt, n_chunks, rows_per_chunk;
+  int tile_n = 0;              // matrix-core path: outputs per workgroup tile (128: four waves, 256: eight)
   int kind;          // PlanKind
   bool mfma;         // kind == kPlanMfma (coefficient + basis preparation, streaming contraction)
   int products = 1;  // 3: both operands in high and low fp16 parts, hi*hi + hi*lo + lo*hi (three passes inside the kernel)
@@ -173,8 +174,8 @@ LayerPlan plan_gather(int n_in, int n_out, int64_t B, int n_heads, int idx_u32, 
   return p;
 }
 
-// Matrix-core path: 64 x 256 (samples x outputs) tiles, i split so that every CU
-// has two workgroups.
+// Matrix-core path: tiles of 64 or 128 samples x 128 outputs (128 x 256 for eight waves), i split so that
+// every CU has two workgroups of four waves (or one of eight).
 constexpr int kMfmaTileN = 128;
 constexpr int kMfmaRowsStep = kMfmaPrepRows;   // chunk boundaries coincide with partial bias sums
 constexpr int kMfmaTargetWorkgroups = 512;
@@ -214,7 +215,16 @@ LayerPlan plan_mfma(int n_in, int n_out, int64_t B, int n_heads, int idx_u32, in
   const long long rows128 = (B + 127) / 128 * 128, rows64 = (B + 63) / 64 * 64;     // sample rows the tiles cover
   p.cfg.bt = (big * 8 >= kMfmaTargetWorkgroups && rows128 * 10 <= rows64 * 11) ? 128 : 64;
   p.n_bt = (int)((B + p.cfg.bt - 1) / p.cfg.bt);
-  const long long base = (long long)n_heads * p.n_jt * p.n_bt;
+  // 128-sample tiles come 256 outputs wide, for one workgroup of eight waves per CU instead of two of four:
+  // the eight waves read one Phi tile, so it is built (and its basis words are loaded) once per CU and step, not
+  // twice (config 3 at batch 1024: layer 1 43.3 -> 38.2 us, at 4096 139 -> 121.6; config 5 2.22 -> 2.01 ms; the
+  // split form at batch 1024 103 -> 89.6 us), unless the wider tiles would pad the outputs by more than an eighth.
+  p.tile_n = kMfmaTileN;
+  if (p.cfg.bt == 128 && (long long)((n_out + 255) / 256 * 256) * 8 <= (long long)p.n_jt * kMfmaTileN * 9) {
+    p.tile_n = 2 * kMfmaTileN;
+    p.n_jt = (n_out + p.tile_n - 1) / p.tile_n;
+  }
+  const long long base = (long long)n_heads * p.n_jt * p.n_bt * (p.tile_n / kMfmaTileN);   // in workgroups of four waves
   long long chunks = kMfmaTargetWorkgroups / (base > 0 ? base : 1);
   // A workgroup that lives for hundreds of steps drifts away from the others of its XCD, which work on
   // the same rows and columns of the operands, by more steps than that XCD's L2 holds: operands are then
@@ -549,7 +559,7 @@ kan_status run_layer_group(const LayerPlan& p, GatherArgs& a, const void* const*
       m.passes = 1;
     }
     dim3 grid((unsigned)(p.n_jt * p.n_bt), (unsigned)p.n_chunks, (unsigned)heads);
-    st = run(p.name, s, [&] { return launch_mfma(m, p.cfg.bt, kMfmaTileN, grid, s); });
+    st = run(p.name, s, [&] { return launch_mfma(m, p.cfg.bt, p.tile_n ? p.tile_n : kMfmaTileN, grid, s); });
   } else if (p.kind == kPlanBucket || p.kind == kPlanColumn) {
     const BucketGeom g = bucket_geometry(a.n_in, a.n_out, (int)(a.cb_bytes / cb_row_bytes(p.cfg.code)), p.cfg.code,
                                          p.cfg.gb_kind);

@@ -131,7 +131,7 @@ hipError_t launch_prep_dense(const float* coef, uint4* cf, uint4* cf_lo, int n_i
 hipError_t launch_prep_basis(const float* x, long long x_head_stride, int x_parts, long long x_part_stride,
                              int x_tanh, uint2* W, uint2* W_lo, long long w_head_stride, int n_in, int B, int heads,
                              int rule, hipStream_t);
-hipError_t launch_mfma(const MfmaArgs&, int tile_m, int tile_n, dim3 grid, hipStream_t);   // samples (64 | 128) x outputs (128) per tile
+hipError_t launch_mfma(const MfmaArgs&, int tile_m, int tile_n, dim3 grid, hipStream_t);   // samples (64 | 128) x outputs (128; 256 with 128 samples) per tile
 
 // ---- fused gather + matrix-core kernel (batch tiles of 32 or 64 samples) --------------
 constexpr int kFusedTileN = 128;      // outputs per workgroup

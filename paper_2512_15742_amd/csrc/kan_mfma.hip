@@ -30,7 +30,10 @@
 //   kan_mfma        64 or 128 samples x 128 outputs per workgroup, 4 waves side by
 //                   side along the outputs; two or three workgroups share a CU and
 //                   drift apart, so one's MFMAs overlap the other's tile generation
-//                   and LDS latency.  Per step of 16 inputs: the Phi tile (the two
+//                   and LDS latency.  Or 128 samples x 256 outputs for one workgroup
+//                   of 8 waves per CU: the same waves per SIMD and registers per wave,
+//                   but one Phi tile per CU and step instead of two (half the tile
+//                   generation and basis-word loads).  Per step of 16 inputs: the Phi tile (the two
 //                   stored values of every group of four k-slots, plus their
 //                   positions) is built in LDS (double buffered) from the packed basis
 //                   words with byte permutes whose selectors come from a 7-entry
@@ -56,7 +59,7 @@ namespace kan {
 namespace {
 
 constexpr int kThreads = 256;          // preparation kernels
-constexpr int kMfmaThreads = 256;      // contraction kernel: 4 waves along the outputs
+constexpr int kMfmaThreads = 256;      // contraction kernel: 4 waves along the outputs (8 waves: 512)
 constexpr int IT = 16;                 // input rows per step (160 k-slots = 40 groups of four = 5 sparse MFMAs of K = 32)
 constexpr int kRowBytes = 208;         // LDS row of the Phi tile: 160 B of weights, 2 x 16 B of index words, 16 B of
                                        // padding (52 dwords: sixteen consecutive rows start in sixteen different banks)
@@ -456,13 +459,14 @@ __device__ __forceinline__ void fill_sparse_selectors(uint32_t (*sel)[8], int ti
   }
 }
 
-template <int MB, int NB, bool THREE>
-__global__ __launch_bounds__(kMfmaThreads, MB == 2 ? 3 : 2) void kan_mfma_kernel(const MfmaArgs a) {
+template <int MB, int NB, bool THREE, int NW = 4>
+__global__ __launch_bounds__(64 * NW, NW == 8 ? 1 : (MB == 2 ? 3 : 2)) void kan_mfma_kernel(const MfmaArgs a) {
+  constexpr int kThreadsWg = 64 * NW;  // NW waves side by side along the outputs, all reading one Phi tile
   constexpr int BM = 32 * MB;          // samples per workgroup tile (MB = MFMA row blocks per wave)
-  constexpr int BN = 4 * 32 * NB;      // outputs per workgroup tile
-  constexpr int NSUB = BM / 64;        // quarters of a step (inputs 4 ph .. 4 ph + 3) per thread
+  constexpr int BN = NW * 32 * NB;     // outputs per workgroup tile
+  constexpr int NSUB = BM * 4 / kThreadsWg;   // quarters of a step (inputs 4 ph .. 4 ph + 3) per thread
   constexpr int NPAIR = 4 * NSUB;      // (sample, input) pairs per thread and step
-  static_assert(BM * 4 == kMfmaThreads * NSUB && IT == 16, "threads of a sample row share out the four quarters of a step");
+  static_assert(NSUB >= 1 && BM * 4 == kThreadsWg * NSUB && IT == 16, "threads of a sample row share out the four quarters of a step");
   __shared__ __attribute__((aligned(16))) unsigned char sA[2][BM * kRowBytes];   // Phi tiles, 2 x 13 KB
   __shared__ __attribute__((aligned(16))) uint32_t sSel[kSpans][8];
   fill_sparse_selectors(sSel, threadIdx.x);
@@ -688,8 +692,8 @@ __global__ __launch_bounds__(kMfmaThreads, MB == 2 ? 3 : 2) void kan_mfma_kernel
   // of the step, so its successor (half step 2k+3) is requested in two parts.
   // The bias sums of the tile's columns are fetched ahead of everything else (thread t owns
   // column j0 + t) and parked in LDS until the epilogue, so their latency is never exposed.
-  static_assert(BN <= kMfmaThreads, "one bias column per thread (the others repeat the last column)");
-  __shared__ float sBias[kMfmaThreads];
+  static_assert(BN <= kThreadsWg, "one bias column per thread (the others repeat the last column)");
+  __shared__ float sBias[kThreadsWg];
   const float* bp = a.bias_partial + (long long)head * a.bp_head_stride + min(j0 + tid, n_out - 1);
   const int rb0 = i_begin / kMfmaPrepRows, rb1 = (i_end + kMfmaPrepRows - 1) / kMfmaPrepRows;
   float bias_v[8];
@@ -868,6 +872,17 @@ hipError_t launch_prep_basis(const float* x, long long x_head_stride, int x_part
 }
 
 hipError_t launch_mfma(const MfmaArgs& a, int tile_m, int tile_n, dim3 grid, hipStream_t s) {
+  if (tile_n == 256) {          // eight waves, one workgroup per CU (128-sample tiles only: 64 x 4 threads build a 64-row tile)
+    if (tile_m != 128) return hipErrorInvalidValue;
+    if (a.passes != 1 && (a.passes != 3 || !a.cf_lo || !a.W_lo)) return hipErrorInvalidValue;
+    if ((long long)a.n_jt * tile_n < a.n_out) return hipErrorInvalidValue;
+    if ((long long)a.n_out * 20 * (long long)sizeof(uint4) > 0x7fffffffLL ||
+        (long long)a.B * 8 * (long long)sizeof(uint2) > 0x7fffffffLL)
+      return hipErrorInvalidValue;
+    if (a.passes == 3) hipLaunchKernelGGL((kan_mfma_kernel<4, 1, true, 8>), grid, dim3(2 * kMfmaThreads), 0, s, a);
+    else hipLaunchKernelGGL((kan_mfma_kernel<4, 1, false, 8>), grid, dim3(2 * kMfmaThreads), 0, s, a);
+    return hipGetLastError();
+  }
   if ((tile_m != 64 && tile_m != 128) || tile_n != 128) return hipErrorInvalidValue;
   if (a.passes != 1 && (a.passes != 3 || !a.cf_lo || !a.W_lo)) return hipErrorInvalidValue;
   if ((long long)a.n_jt * tile_n < a.n_out) return hipErrorInvalidValue;
