@@ -467,7 +467,12 @@ __global__ __launch_bounds__(64 * NW, NW == 8 ? 1 : (MB == 2 ? 3 : 2)) void kan_
   constexpr int NSUB = BM * 4 / kThreadsWg;   // quarters of a step (inputs 4 ph .. 4 ph + 3) per thread
   constexpr int NPAIR = 4 * NSUB;      // (sample, input) pairs per thread and step
   static_assert(NSUB >= 1 && BM * 4 == kThreadsWg * NSUB && IT == 16, "threads of a sample row share out the four quarters of a step");
-  __shared__ __attribute__((aligned(16))) unsigned char sA[2][BM * kRowBytes];   // Phi tiles, 2 x 13 KB
+  // Phi tiles.  Four waves: two tiles, a barrier per step.  Eight waves (alone on their CU, so the LDS is
+  // theirs): four tiles, built two steps ahead, and a barrier every second step - between two barriers the
+  // waves read tiles k, k + 1 and write tiles k + 2, k + 3, and may drift apart by up to two steps.
+  constexpr int kAhead = NW == 8 ? 2 : 1;
+  constexpr int kTiles = 2 * kAhead;
+  __shared__ __attribute__((aligned(16))) unsigned char sA[kTiles][BM * kRowBytes];
   __shared__ __attribute__((aligned(16))) uint32_t sSel[kSpans][8];
   fill_sparse_selectors(sSel, threadIdx.x);
   __syncthreads();
@@ -555,19 +560,23 @@ __global__ __launch_bounds__(64 * NW, NW == 8 ? 1 : (MB == 2 ? 3 : 2)) void kan_
   // arithmetic.  Offsets stay below 2^31 because a resource spans one step of one head.
   const uint32_t u_off = (uint32_t)min(b0 + pb, B - 1) * (uint32_t)sizeof(uint4);
   const uint32_t w_row_bytes = (uint32_t)B * (uint32_t)sizeof(uint4);       // a pair of inputs
-  auto load_u = [&](int kv, uint2 (&uv)[NPAIR]) {      // virtual step index
+  auto u_rsrc = [&](int kv) {                            // virtual step index
     // (the rows of a ragged last step exist and hold zeros; past the chunk: valid memory, never used)
     const int k = kv - (kv >= n2 ? n2 : (kv >= n1 ? n1 : 0));
     const char* w_bytes = (const char*)((three && kv >= n1 && kv < n2) ? W_low : W_main);
     const int i = min(step0 + k, last_step) * IT + 4 * ph0;
     const char* rows = w_bytes + (size_t)(i >> 1) * w_row_bytes;
-    const __amdgpu_buffer_rsrc_t r = __builtin_amdgcn_make_buffer_rsrc((void*)rows, 0, (int)(NPAIR / 2 * w_row_bytes), kBufferFlags);
+    return __builtin_amdgcn_make_buffer_rsrc((void*)rows, 0, (int)(NPAIR / 2 * w_row_bytes), kBufferFlags);
+  };
+  auto load_u_one = [&](const __amdgpu_buffer_rsrc_t r, int q, uint2 (&uv)[NPAIR]) {      // pair q of the thread's inputs
+    const u32x4 v = __builtin_amdgcn_raw_buffer_load_b128(r, (int)u_off, (int)(q * w_row_bytes), 0);
+    uv[2 * q] = make_uint2(v.x, v.y);
+    uv[2 * q + 1] = make_uint2(v.z, v.w);
+  };
+  auto load_u = [&](int kv, uint2 (&uv)[NPAIR]) {
+    const __amdgpu_buffer_rsrc_t r = u_rsrc(kv);
 #pragma unroll
-    for (int q = 0; q < NPAIR / 2; ++q) {
-      const u32x4 v = __builtin_amdgcn_raw_buffer_load_b128(r, (int)u_off, (int)(q * w_row_bytes), 0);
-      uv[2 * q] = make_uint2(v.x, v.y);
-      uv[2 * q + 1] = make_uint2(v.z, v.w);
-    }
+    for (int q = 0; q < NPAIR / 2; ++q) load_u_one(r, q, uv);
   };
 
   // Input 4 ph + q = 4 S + 2 x + a with S = ph: its four stored values go to bytes x * 8 of
@@ -630,6 +639,15 @@ __global__ __launch_bounds__(64 * NW, NW == 8 ? 1 : (MB == 2 ? 3 : 2)) void kan_
         bf[nb][u] = make_uint4(v.x, v.y, v.z, v.w);
       }
   };
+  auto load_b_one = [&](const __amdgpu_buffer_rsrc_t r, auto HS, int u, uint4 (&bf)[NB][5]) {      // fragment u = 0..3 of the half step
+    constexpr int hs = decltype(HS)::value;
+#pragma unroll
+    for (int nb = 0; nb < NB; ++nb) {
+      const u32x4 v = __builtin_amdgcn_raw_buffer_load_b128(r, (int)b_off[nb],
+                                                            (int)((2 * hs + (u >> 1)) * s_bytes + (u & 1) * a_bytes), 0);
+      bf[nb][u] = make_uint4(v.x, v.y, v.z, v.w);
+    }
+  };
   auto load_b_tail = [&](int k, auto HS, uint4 (&bf)[NB][5]) {
     constexpr int hs = decltype(HS)::value;
     const __amdgpu_buffer_rsrc_t r = step_rsrc(k);
@@ -646,43 +664,43 @@ __global__ __launch_bounds__(64 * NW, NW == 8 ? 1 : (MB == 2 ? 3 : 2)) void kan_
 #pragma unroll
     for (int m = 0; m < MB; ++m) ix[m] = *(const uint4*)(tile + (m * 32 + ln) * kRowBytes + kIdxOffset + lh * 16);
   };
-  auto mfma_pair = [&](const unsigned char* tile, auto HS, const uint4 (&ix)[MB], const uint4 (&bf)[NB][5]) {
-    constexpr int hs = decltype(HS)::value;
-#pragma unroll
-    for (int q = 0; q < 2; ++q) {
-      h16x8 fa[MB];
-#pragma unroll
-      for (int m = 0; m < MB; ++m)
-        fa[m] = __builtin_bit_cast(h16x8, *(const uint4*)(tile + (m * 32 + ln) * kRowBytes + ((2 * hs + q) * 2 + lh) * 16));
-#pragma unroll
-      for (int n = 0; n < NB; ++n) {
-        const uint4 two[2] = {bf[n][2 * q], bf[n][2 * q + 1]};
-        const h16x16 fb = __builtin_bit_cast(h16x16, two);
-#pragma unroll
-        for (int m = 0; m < MB; ++m) {
-          const int iw = hs == 0 ? (int)ix[m].x : (int)ix[m].y;       // S = 2 hs + q: word hs, half q
-          if (q == 0) acc[m][n] = __builtin_amdgcn_smfmac_f32_32x32x32_f16(fa[m], fb, acc[m][n], iw, 0, 0);
-          else acc[m][n] = __builtin_amdgcn_smfmac_f32_32x32x32_f16(fa[m], fb, acc[m][n], iw, 0, 1);
-        }
-      }
-      if (MB > 2) __builtin_amdgcn_sched_barrier(0);     // keep the fragment reads of the next MFMA group from piling up
-    }
-  };
-  auto mfma_tail = [&](const unsigned char* tile, const uint4 (&ix)[MB], const uint4 (&bf0)[NB][5], const uint4 (&bf1)[NB][5]) {
-    h16x8 fa[MB];
+  // A fragments of MFMA group g of the step (g = 2 hs + q for the pairs, 4 for the tail): one 16-byte LDS
+  // read per row block.  The groups run through two register sets: while the matrix pipe works on group g the
+  // reads of group g + 2 are already on their way, so that no MFMA waits for an LDS round trip of its own
+  // (the compiler, left alone, reads every fragment right in front of its MFMA and waits each time).
+  auto read_a = [&](const unsigned char* tile, auto G, h16x8 (&fa)[MB]) {
+    constexpr int g = decltype(G)::value;
+    constexpr int off = g < 4 ? g * 32 : 128;
 #pragma unroll
     for (int m = 0; m < MB; ++m)
-      fa[m] = __builtin_bit_cast(h16x8, *(const uint4*)(tile + (m * 32 + ln) * kRowBytes + 128 + lh * 16));
+      fa[m] = __builtin_bit_cast(h16x8, *(const uint4*)(tile + (m * 32 + ln) * kRowBytes + off + lh * 16));
+  };
+  // (`between(m)` runs behind the m-th MFMA of the group, pinned there: the loads it issues go out in the shadow
+  // of the matrix pipe instead of in one burst at the end of the step, when every wave of the CU would queue
+  // at the address unit at once and none would have an MFMA to issue)
+  auto mfma_group = [&](auto G, const h16x8 (&fa)[MB], const uint4 (&ix)[MB], const uint4 (&bf0)[NB][5], const uint4 (&bf1)[NB][5],
+                        auto&& between) {
+    constexpr int g = decltype(G)::value;
+    constexpr int hs = g >> 1, q = g & 1;
 #pragma unroll
     for (int n = 0; n < NB; ++n) {
-      const uint4 two[2] = {bf0[n][4], bf1[n][4]};
+      // pairs: fragments 2 q, 2 q + 1 of the half step (bf0); tail: the S = 4 fragments of both half steps
+      const uint4 two[2] = {g < 4 ? bf0[n][2 * q] : bf0[n][4], g < 4 ? bf0[n][2 * q + 1] : bf1[n][4]};
       const h16x16 fb = __builtin_bit_cast(h16x16, two);
 #pragma unroll
-      for (int m = 0; m < MB; ++m)
-        acc[m][n] = __builtin_amdgcn_smfmac_f32_32x32x32_f16(fa[m], fb, acc[m][n], (int)ix[m].z, 0, 0);
+      for (int m = 0; m < MB; ++m) {
+        const int iw = g == 4 ? (int)ix[m].z : (hs == 0 ? (int)ix[m].x : (int)ix[m].y);   // S = 2 hs + q: word hs, half q
+        if (g < 4 && q == 1) acc[m][n] = __builtin_amdgcn_smfmac_f32_32x32x32_f16(fa[m], fb, acc[m][n], iw, 0, 1);
+        else acc[m][n] = __builtin_amdgcn_smfmac_f32_32x32x32_f16(fa[m], fb, acc[m][n], iw, 0, 0);
+        if (n == NB - 1) {
+          __builtin_amdgcn_sched_barrier(0);
+          between(m);
+          __builtin_amdgcn_sched_barrier(0);
+        }
+      }
     }
-    if (MB > 2) __builtin_amdgcn_sched_barrier(0);
   };
+  auto nothing = [](int) {};
 
   // ---- pipeline.  Fragments travel in half steps through a ring of three register slots
   // (half step H in slot H mod 3), basis words in whole steps through a ring of three; all
@@ -721,12 +739,17 @@ __global__ __launch_bounds__(64 * NW, NW == 8 ? 1 : (MB == 2 ? 3 : 2)) void kan_
     sBias[tid] = a.bias_on ? bs : 0.f;      // read after the barriers of the main loop
   }
   gen_phi(uv[0], sA[0]);
+  if constexpr (kAhead == 2) {
+    gen_phi(uv[1], sA[1]);
+    load_u(3, uv[0]);
+  }
 
   auto step = [&](auto T, int k) {
     constexpr int t = decltype(T)::value;          // k mod 3
     constexpr int sa = (2 * t) % 3, sb = (2 * t + 1) % 3;
-    const unsigned char* tile = sA[k & 1];
-    __syncthreads();     // tile k is complete; every wave is done reading tile k-1
+    const unsigned char* tile = sA[k & (kTiles - 1)];
+    // tiles k .. k + kAhead - 1 are complete; every wave is done reading the tiles before them
+    if (kAhead == 1 || (k & 1) == 0) __syncthreads();
     if (three && k == n2) {       // split form: the cross products are complete
       const float f = a.lo_scale;
 #pragma unroll
@@ -737,18 +760,49 @@ __global__ __launch_bounds__(64 * NW, NW == 8 ? 1 : (MB == 2 ? 3 : 2)) void kan_
           for (int r = 0; r < 16; ++r) acc[m][n][r] *= f;
     }
     uint4 ix[MB];
+    h16x8 fa0[MB], fa1[MB];
+    using G0 = std::integral_constant<int, 0>;
+    using G1 = std::integral_constant<int, 1>;
+    using G2 = std::integral_constant<int, 2>;
+    using G3 = std::integral_constant<int, 3>;
+    using G4 = std::integral_constant<int, 4>;
+    // resources of the loads of this step (scalar arithmetic, ahead of the MFMA groups)
+    const __amdgpu_buffer_rsrc_t ru = u_rsrc(k + 2 + kAhead), r1 = step_rsrc(k + 1), r2 = step_rsrc(k + 2);
+    constexpr int kUPerMfma = (NPAIR / 2 + MB - 1) / MB, kBPerMfma = 4 / MB;     // loads behind each MFMA of a group
     read_idx(tile, ix);
+    read_a(tile, G0{}, fa0);
+    read_a(tile, G1{}, fa1);
+    __builtin_amdgcn_sched_barrier(0);
     __builtin_amdgcn_s_setprio(2);     // the wave that has its operands goes first at the matrix pipe (measured: 1.5-2 %)
-    mfma_pair(tile, HS0{}, ix, bfr[sa]);
-    load_b_main(k + 1, HS1{}, bfr[sa]);            // half step 2k+3; its S = 4 fragment follows below
-    mfma_pair(tile, HS1{}, ix, bfr[sb]);
-    mfma_tail(tile, ix, bfr[sa], bfr[sb]);
+    // basis words of step k + 2 + kAhead, into the slot whose words went into a tile a step ago
+    mfma_group(G0{}, fa0, ix, bfr[sa], bfr[sa], [&](int m) {
+#pragma unroll
+      for (int q = m * kUPerMfma; q < (m + 1) * kUPerMfma; ++q)
+        if (q < NPAIR / 2) load_u_one(ru, q, uv[(t + kAhead + 2) % 3]);
+    });
+    read_a(tile, G2{}, fa0);
+    __builtin_amdgcn_sched_barrier(0);
+    mfma_group(G1{}, fa1, ix, bfr[sa], bfr[sa], nothing);
+    read_a(tile, G3{}, fa1);
+    __builtin_amdgcn_sched_barrier(0);
+    // half step 2k+3 (fragments 0..3 of this step's first half are done with; its S = 4 fragment follows below)
+    mfma_group(G2{}, fa0, ix, bfr[sb], bfr[sb], [&](int m) {
+#pragma unroll
+      for (int u = m * kBPerMfma; u < (m + 1) * kBPerMfma; ++u) load_b_one(r1, HS1{}, u, bfr[sa]);
+    });
+    read_a(tile, G4{}, fa0);
+    __builtin_amdgcn_sched_barrier(0);
+    mfma_group(G3{}, fa1, ix, bfr[sb], bfr[sb], nothing);
+    // half step 2k+4
+    mfma_group(G4{}, fa0, ix, bfr[sa], bfr[sb], [&](int m) {
+#pragma unroll
+      for (int u = m * kBPerMfma; u < (m + 1) * kBPerMfma; ++u) load_b_one(r2, HS0{}, u, bfr[sb]);
+    });
     __builtin_amdgcn_s_setprio(0);
-    gen_phi(uv[(t + 1) % 3], sA[(k + 1) & 1]);     // step k+1 basis tile
     load_b_tail(k + 1, HS1{}, bfr[sa]);
-    load_b_main(k + 2, HS0{}, bfr[sb]);            // half step 2k+4
     load_b_tail(k + 2, HS0{}, bfr[sb]);
-    load_u(k + 3, uv[t]);                          // basis words of step k were consumed a step ago
+    __builtin_amdgcn_sched_barrier(0);
+    gen_phi(uv[(t + kAhead) % 3], sA[(k + kAhead) & (kTiles - 1)]);     // basis tile of step k + kAhead
   };
   // Whole groups of three steps run without a branch between them: a branch around a step makes
   // the compiler lose count of the loads in flight and wait for all of them.
