@@ -612,6 +612,44 @@ __global__ __launch_bounds__(64 * NW, NW == 8 ? 1 : (MB == 2 ? 3 : 2)) void kan_
     }
   };
 
+  // The same in three pieces for threads that own one quarter of a step (NSUB = 1), so that the step can place
+  // them behind its MFMAs: the selector row of input q is requested (LDS), later its values are permuted and
+  // stored, last the words that collect bits of all four inputs.
+  struct PhiState {
+    uint4 sel[4];
+    uint32_t v4[4], ib[4], h4[4];
+  };
+  auto phi_request = [&](const uint2 (&uv)[NPAIR], int q, PhiState& ps) {
+    uint32_t l, w01, w23;
+    unpack_basis(uv[q], l, w01, w23);
+    ps.sel[q] = *(const uint4*)&sSel[l][0];
+  };
+  auto phi_place = [&](const uint2 (&uv)[NPAIR], int q, PhiState& ps, unsigned char* tile) {
+    unsigned char* rowp = tile + pb * kRowBytes;
+    uint32_t l, w01, w23;
+    unpack_basis(uv[q], l, w01, w23);
+    const uint4 sl = ps.sel[q];
+    uint2 st;
+    st.x = __builtin_amdgcn_perm(w23, w01, sl.x);
+    st.y = __builtin_amdgcn_perm(w23, w01, sl.y);
+    ps.v4[q] = __builtin_amdgcn_perm(w23, w01, sl.z);
+    ps.ib[q] = sl.w & 0xffu;
+    ps.h4[q] = sl.w >> 8;
+    *(uint2*)(rowp + (ph0 * 2 + (q & 1)) * 16 + (q >> 1) * 8) = st;
+  };
+  auto phi_finish = [&](const PhiState& ps, unsigned char* tile) {
+    unsigned char* rowp = tile + pb * kRowBytes;
+    const int ph = ph0;
+    uint2 t4;
+    t4.x = ps.v4[0] | (ps.v4[1] << 16);
+    t4.y = ps.v4[2] | (ps.v4[3] << 16);
+    *(uint2*)(rowp + 128 + (ph & 1) * 16 + (ph >> 1) * 8) = t4;
+    *(uint16_t*)(rowp + kIdxOffset + 0 * 16 + ph * 2) = (uint16_t)(ps.ib[0] | (ps.ib[2] << 8));
+    *(uint16_t*)(rowp + kIdxOffset + 1 * 16 + ph * 2) = (uint16_t)(ps.ib[1] | (ps.ib[3] << 8));
+    *(uint8_t*)(rowp + kIdxOffset + (ph & 1) * 16 + 8 + (ph >> 1)) =
+        (uint8_t)((ps.h4[0] | ((2u + ps.h4[1]) << 2)) | ((ps.h4[2] | ((2u + ps.h4[3]) << 2)) << 4));
+  };
+
   // Chat fragments of half a step (S = 2 hs, 2 hs + 1 and half hs of S = 4): 5 uint4 per
   // column block: [0] (S0, a=0) [1] (S0, a=1) [2] (S1, a=0) [3] (S1, a=1) [4] (S = 4, a = hs),
   // all of B lane half lh.
@@ -782,7 +820,14 @@ __global__ __launch_bounds__(64 * NW, NW == 8 ? 1 : (MB == 2 ? 3 : 2)) void kan_
     });
     read_a(tile, G2{}, fa0);
     __builtin_amdgcn_sched_barrier(0);
-    mfma_group(G1{}, fa1, ix, bfr[sa], bfr[sa], nothing);
+    // (threads with one quarter of the step: the next tile is built behind the MFMAs of groups 1 and 3)
+    constexpr bool kPhiInShadow = NSUB == 1 && MB == 4;
+    PhiState phs;
+    const uint2 (&uvn)[NPAIR] = uv[(t + kAhead) % 3];
+    unsigned char* tile_next = sA[(k + kAhead) & (kTiles - 1)];     // basis tile of step k + kAhead
+    mfma_group(G1{}, fa1, ix, bfr[sa], bfr[sa], [&](int m) {
+      if constexpr (kPhiInShadow) phi_request(uvn, m, phs);
+    });
     read_a(tile, G3{}, fa1);
     __builtin_amdgcn_sched_barrier(0);
     // half step 2k+3 (fragments 0..3 of this step's first half are done with; its S = 4 fragment follows below)
@@ -792,7 +837,9 @@ __global__ __launch_bounds__(64 * NW, NW == 8 ? 1 : (MB == 2 ? 3 : 2)) void kan_
     });
     read_a(tile, G4{}, fa0);
     __builtin_amdgcn_sched_barrier(0);
-    mfma_group(G3{}, fa1, ix, bfr[sb], bfr[sb], nothing);
+    mfma_group(G3{}, fa1, ix, bfr[sb], bfr[sb], [&](int m) {
+      if constexpr (kPhiInShadow) phi_place(uvn, m, phs, tile_next);
+    });
     // half step 2k+4
     mfma_group(G4{}, fa0, ix, bfr[sa], bfr[sb], [&](int m) {
 #pragma unroll
@@ -802,7 +849,8 @@ __global__ __launch_bounds__(64 * NW, NW == 8 ? 1 : (MB == 2 ? 3 : 2)) void kan_
     load_b_tail(k + 1, HS1{}, bfr[sa]);
     load_b_tail(k + 2, HS0{}, bfr[sb]);
     __builtin_amdgcn_sched_barrier(0);
-    gen_phi(uv[(t + kAhead) % 3], sA[(k + kAhead) & (kTiles - 1)]);     // basis tile of step k + kAhead
+    if constexpr (kPhiInShadow) phi_finish(phs, tile_next);
+    else gen_phi(uvn, tile_next);
   };
   // Whole groups of three steps run without a branch between them: a branch around a step makes
   // the compiler lose count of the loads in flight and wait for all of them.
