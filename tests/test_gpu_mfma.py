@@ -142,6 +142,10 @@ def test_mfma_config4_multi_head(kb):
     (70, 1900, 300),       # 15 x 3 tiles of 128 samples would be too few: 64-sample tiles, 15 x 5
     (200, 100, 5000),      # one column tile: 64-sample tiles, 79 of them
     (330, 129, 4100),      # one output past a tile; 128-sample tiles, the last one 4 samples
+    (96, 1000, 1100),      # 128 x 256 tiles for eight waves (four Phi tiles, a barrier every second step): 6 steps,
+    (100, 1000, 1100),     # 7 steps (a ragged last one),
+    (16, 2048, 1030),      # a single step,
+    (40, 1024, 1024),      # three steps
 ])
 def test_mfma_both_tile_heights_sampled(kb, n_in, n_out, B):
     """The contraction kernel has a 128-sample and a 64-sample tile; which one a layer gets

@@ -39,7 +39,8 @@ def test_split_takes_over_the_precise_path_at_large_batch(kb):
 @pytest.mark.parametrize("n_in,n_out,B,cb,gb,idx", [
     (8, 32, 129, "f32", "f32", "u16"), (130, 67, 200, "i8", "f16", "u16"), (257, 130, 150, "f16", "f16", "u32"),
     (64, 520, 133, "i8", "q8", "u16"), (1000, 264, 300, "f32", "f32", "u16"), (2052, 300, 200, "i8", "f32", "u32"),
-    (2048, 8, 129, "f32", "f16", "u16"), (70, 1900, 2100, "i8", "f16", "u16")])
+    (2048, 8, 129, "f32", "f16", "u16"), (70, 1900, 2100, "i8", "f16", "u16"),
+    (100, 1000, 1100, "i8", "f16", "u16"), (16, 2048, 1030, "f32", "f32", "u32")])    # eight-wave tiles: 21 and 3 passes' steps
 def test_split_shapes_and_dtypes(kb, n_in, n_out, B, cb, gb, idx):
     P = synth.make_layer(n_in * 7 + n_out, n_in, n_out, 1000, cb_dtype=cb, gb_dtype=gb, idx_dtype=idx)
     x = synth.make_x(B, B, n_in)
