@@ -742,10 +742,12 @@ __global__ __launch_bounds__(64 * NW, NW == 8 ? 1 : (MB == 2 ? 3 : 2)) void kan_
 
   // ---- pipeline.  Fragments travel in half steps through a ring of three register slots
   // (half step H in slot H mod 3), basis words in whole steps through a ring of three; all
-  // slots are compile-time, so the loop is unrolled by three steps.  Top of step k: Phi tile
-  // k and the fragments of half steps 2k, 2k+1 are ready, those of 2k+2 and the basis words of
-  // steps k+1, k+2 are in flight.  The S = 4 fragment of half step 2k is needed until the end
-  // of the step, so its successor (half step 2k+3) is requested in two parts.
+  // slots are compile-time, so the loop is unrolled by three steps.  Top of step k: Phi tiles
+  // k .. k + kAhead - 1 and the fragments of half steps 2k, 2k+1 are ready, those of 2k+2 and the
+  // basis words of steps k + kAhead, k + kAhead + 1 are in flight; the step requests the basis words
+  // of step k + kAhead + 2 (behind MFMA group 0) and the fragments of half steps 2k+3 (behind group 2)
+  // and 2k+4 (behind group 4), and builds tile k + kAhead.  The S = 4 fragment of half step 2k is
+  // needed until the end of the step, so its successor (half step 2k+3) is requested in two parts.
   // The bias sums of the tile's columns are fetched ahead of everything else (thread t owns
   // column j0 + t) and parked in LDS until the epilogue, so their latency is never exposed.
   static_assert(BN <= kThreadsWg, "one bias column per thread (the others repeat the last column)");
