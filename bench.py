@@ -224,10 +224,10 @@ def sweep(kb, torch, synth):
         vq_rows("config3 shape, fp16 codebook", [ps], synth.make_x(3950 + B, B, 2048, "uniform"), paths,
                 30 if B <= 256 else 10, prepared=prepared)
     # block-floating-point codebook rows (8-bit mantissas, one exponent byte per row: 12-byte rows)
-    for B, paths in ((1, both[:1]), (16, both), (1024, both[1:])):
+    for B, paths, prepared in ((1, both[:1], False), (1, both[:1], True), (16, both, False), (1024, both[1:], False)):
         ps = synth.config3_layers("f16", cb_dtype="bfp8")
         vq_rows("config3 shape, block-floating-point codebook", [ps], synth.make_x(3960 + B, B, 2048, "uniform"), paths,
-                30 if B <= 256 else 10)
+                30 if B <= 256 else 10, prepared=prepared)
     # residency study: a skewed (trained-like) assignment histogram instead of the uniform worst case
     for dist in ("zipf", "zipf-sorted"):
         for B, paths, prepared in ((1, both[:1], False), (1, both[:1], True), (16, both, False), (1024, both[1:], False)):

@@ -134,8 +134,8 @@ typedef struct kan_vq_layer {
    * paper defines no format, this is the one used here): a codeword row is one block of 12
    * bytes, 4-byte aligned: ten signed mantissa bytes q[0..9] in -127..127, one signed exponent
    * byte e in -126..127 shared by the row, one zero byte; entry m means q[m] * 2^e.  `scale` is
-   * ignored.  Served by the vector-ALU, fused and streaming kernels; kan_vq_prepare does not
-   * take such layers (kan_vq_prepared_bytes returns 0).                                     */
+   * ignored.  Served by every kernel family, the prepared layout of kan_vq_prepare included
+   * (buckets of 4096 such rows, 48 KB).                                                      */
 } kan_vq_layer;
 
 /* Spans and basis weights of step "index lookup" (section 4.1) for the cubic
@@ -190,7 +190,8 @@ kan_status kan_dense_layer_forward(const float* coef, int32_t in, int32_t out, i
  * batch-1 inference moves the per-edge metadata once; section 4.3: the codebook must be
  * served from on-chip memory).  The edges are regrouped by codebook bucket (8192 Int8,
  * 4096 fp16 or 2048 fp32 consecutive codewords, 80 KB: what one CU's LDS holds beside the
- * basis table; half of that for layers with more than 2048 inputs),
+ * basis table, or 4096 block-floating-point rows, 48 KB; half of that for layers with more
+ * than 2048 inputs),
  * then by output, then by input; per edge the buffer keeps (input index u16, codeword id
  * within the bucket u16, gain), and per output the sum of its biases (the bases sum to 1 on
  * [-1,1], so the bias term does not depend on x), and tables that cut the work into blocks

@@ -362,7 +362,7 @@ LayerPlan plan_column(const kan_vq_layer& L, int64_t B) {
 }
 
 bool layer_prepared_ok(const kan_vq_layer& L) {
-  return L.prepared != nullptr && L.cb_dtype != KAN_BFP8 && aligned(L.prepared, 256) && aligned(L.codebook, 16) && L.in <= kBucketMaxIn &&
+  return L.prepared != nullptr && aligned(L.prepared, 256) && aligned(L.codebook, 16) && L.in <= kBucketMaxIn &&
          (long long)L.in * L.out <= (1ll << 31);
 }
 
@@ -986,14 +986,14 @@ kan_status kan_dense_layer_forward(const float* coef, int32_t in, int32_t out, i
 
 size_t kan_vq_prepared_bytes(const kan_vq_layer* L) {
   if (validate_layer(L) != KAN_OK) return (size_t)-1;
-  if (L->in > kBucketMaxIn || (long long)L->in * L->out > (1ll << 31) || L->cb_dtype == KAN_BFP8) return 0;
+  if (L->in > kBucketMaxIn || (long long)L->in * L->out > (1ll << 31)) return 0;
   return bucket_geometry(L->in, L->out, L->K, code_of(*L), gb_kind_of(*L)).total;
 }
 
 kan_status kan_vq_prepare(const kan_vq_layer* L, void* prepared, size_t prepared_bytes, void* stream) {
   kan_status st = validate_layer(L);
   if (st != KAN_OK) return st;
-  if (L->in > kBucketMaxIn || L->cb_dtype == KAN_BFP8) return KAN_ERR_UNSUPPORTED;   // (no bucket layout for 12-byte rows)
+  if (L->in > kBucketMaxIn) return KAN_ERR_UNSUPPORTED;
   if ((long long)L->in * L->out > (1ll << 31)) return KAN_ERR_UNSUPPORTED;   // 32-bit segment offsets
   const BucketGeom g = bucket_geometry(L->in, L->out, L->K, code_of(*L), gb_kind_of(*L));
   if (!prepared || !aligned(prepared, 256) || prepared_bytes < g.total) return KAN_ERR_WORKSPACE;

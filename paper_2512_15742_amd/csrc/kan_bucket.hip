@@ -5,7 +5,8 @@
 // are limited by the rate at which a CU can issue divergent addresses, far below what the
 // metadata stream could sustain; lookups in LDS are not.  The 655 KB Int8 codebook does not
 // fit the 160 KB LDS of a CU, but an eighth of it does, so the edges are regrouped once
-// (kan_vq_prepare) by bucket = idx / 8192 (fp32 rows: idx / 2048; half of that for layers
+// (kan_vq_prepare) by bucket = idx / 8192 (fp16 and block-floating-point rows: idx / 4096, fp32 rows:
+// idx / 2048; half of that for layers
 // with more than 2048 inputs) and every workgroup serves one bucket: it copies the bucket's
 // codeword rows into LDS, builds the span/basis table of all inputs of its sample there as
 // well, and streams its block of the bucket's edges.
@@ -108,6 +109,9 @@ __device__ __forceinline__ float wave_sum_to_last_lane(float v) {
 template <int GK, int CODE, int MAXIN>
 __global__ __launch_bounds__(kBucketThreads) void kan_bucket_kernel(const BucketArgs a) {
   constexpr int kCbBytes = bucket_bytes(MAXIN);
+  // bytes from one bucket's rows to the next's in the codebook: the whole LDS share, except for the 12-byte
+  // block-floating-point rows (a power of two of them per bucket: 4096 or 2048)
+  constexpr int kCbStride = CODE == kCbBfp8 ? kCbBytes / 20 * 12 : kCbBytes;
   constexpr int kXPerThread = MAXIN / kBucketThreads;
   constexpr int kCbPerThread = (kCbBytes / 16 + kBucketThreads - 1) / kBucketThreads;   // 16-byte units per thread
   __shared__ __attribute__((aligned(16))) uint32_t cb[kCbBytes / 4 + 8];   // + 16 bytes read-ahead, + 16 spare
@@ -175,9 +179,9 @@ __global__ __launch_bounds__(kBucketThreads) void kan_bucket_kernel(const Bucket
   // ---- (2) codebook bucket, 16 bytes per thread and round.  The workgroups of a bucket
   //          start at different offsets so that they do not all ask the same L2 channel
   //          for the same line at the same moment ------------------------------------------
-  const long long cb_start = (long long)bucket * kCbBytes;
+  const long long cb_start = (long long)bucket * kCbStride;
   const long long cb_rest = a.cb_bytes - cb_start;
-  const int cb_nbytes = (int)(cb_rest < kCbBytes ? cb_rest : kCbBytes);
+  const int cb_nbytes = (int)(cb_rest < kCbStride ? cb_rest : kCbStride);
   const char* cb_src = (const char*)H.cb + cb_start;
   const int n16 = cb_nbytes >> 4;
   const int cb_tail = cb_nbytes & 15;
@@ -279,9 +283,9 @@ __global__ __launch_bounds__(kBucketThreads) void kan_bucket_kernel(const Bucket
 #pragma unroll
     for (int u = 0; u < kEpt; ++u) {
       const float4 w = bas[u16_of(c.i, u)];
-      const uint32_t at = u16_of(c.q, u) * 10u + __float_as_uint(w.w);
+      const uint32_t at = u16_of(c.q, u) * (CODE == kCbBfp8 ? 12u : 10u) + __float_as_uint(w.w);
       float c0, c1, c2, c3;
-      if constexpr (CODE == kCbI8) {
+      if constexpr (CODE == kCbI8 || CODE == kCbBfp8) {
         // bytes at .. at+3 of the bucket: two aligned dwords, funnel-shifted; q + 128 as
         // unsigned bytes (the differences below do not see the offset)
         const uint32_t lo = cb[at >> 2], hi = cb[(at >> 2) + 1];
@@ -308,10 +312,11 @@ __global__ __launch_bounds__(kBucketThreads) void kan_bucket_kernel(const Bucket
         c3 = cf[at + 3];
       }
       // sum_k w_k c_k with w3 = 1 - w0 - w1 - w2 (the bases sum to 1)
-      float s = CODE == kCbI8 ? c3 - 128.0f : c3;
+      float s = (CODE == kCbI8 || CODE == kCbBfp8) ? c3 - 128.0f : c3;
       s = fmaf(w.z, c2 - c3, s);
       s = fmaf(w.y, c1 - c3, s);
       s = fmaf(w.x, c0 - c3, s);
+      if constexpr (CODE == kCbBfp8) s *= bfp8_row_scale(cb[u16_of(c.q, u) * 3u + 2u]);     // the row's own power of two
       // Edges outside the block (groups that straddle its ends, re-read groups) contribute
       // an exact zero rather than gain * s, so that a non-finite codeword which no edge of
       // the block refers to cannot reach a sum.
@@ -824,7 +829,7 @@ hipError_t launch_bucket_prepare(const LayerPtrs& h, int idx_u32, int gb_kind, i
 
 hipError_t launch_bucket(int code, int gb_kind, const BucketArgs& a, int blocks, int heads, hipStream_t s) {
   if (a.n_in > kBucketMaxIn || a.n_buckets < 1 || blocks < a.n_buckets) return hipErrorInvalidValue;
-  if (code != kCbI8 && code != kCbF16 && code != kCbF32) return hipErrorInvalidValue;
+  if (code != kCbI8 && code != kCbF16 && code != kCbF32 && code != kCbBfp8) return hipErrorInvalidValue;
   if (gb_kind == kGbQ8 && code != kCbI8) return hipErrorInvalidValue;      // byte-coded gains go with Int8 codebooks
   dim3 grid((unsigned)blocks, (unsigned)a.B, (unsigned)heads);
   dim3 block(kBucketThreads);
@@ -841,6 +846,9 @@ hipError_t launch_bucket(int code, int gb_kind, const BucketArgs& a, int blocks,
   } else if (code == kCbF16) {
     if (gb_kind == kGbF16) KAN_LAUNCH_BUCKET(kGbF16, kCbF16);
     else KAN_LAUNCH_BUCKET(kGbF32, kCbF16);
+  } else if (code == kCbBfp8) {
+    if (gb_kind == kGbF16) KAN_LAUNCH_BUCKET(kGbF16, kCbBfp8);
+    else KAN_LAUNCH_BUCKET(kGbF32, kCbBfp8);
   } else {
     if (gb_kind == kGbF16) KAN_LAUNCH_BUCKET(kGbF16, kCbF32);
     else KAN_LAUNCH_BUCKET(kGbF32, kCbF32);
@@ -851,7 +859,7 @@ hipError_t launch_bucket(int code, int gb_kind, const BucketArgs& a, int blocks,
 
 hipError_t launch_column(int code, int gb_kind, const BucketArgs& a, int heads, hipStream_t s) {
   if ((long long)a.n_in * a.n_out > kColumnMaxEdges || a.off_ti <= 0 || a.off_tg <= 0) return hipErrorInvalidValue;
-  if (code != kCbI8 && code != kCbF16 && code != kCbF32) return hipErrorInvalidValue;
+  if (code != kCbI8 && code != kCbF16 && code != kCbF32 && code != kCbBfp8) return hipErrorInvalidValue;
   if (gb_kind == kGbQ8 && code != kCbI8) return hipErrorInvalidValue;
   dim3 grid((unsigned)a.n_out, (unsigned)a.B, (unsigned)heads);
   dim3 block(kColumnThreads);
@@ -862,6 +870,9 @@ hipError_t launch_column(int code, int gb_kind, const BucketArgs& a, int heads, 
   } else if (code == kCbF16) {
     if (gb_kind == kGbF16) hipLaunchKernelGGL((kan_column_kernel<kGbF16, __half>), grid, block, 0, s, a);
     else hipLaunchKernelGGL((kan_column_kernel<kGbF32, __half>), grid, block, 0, s, a);
+  } else if (code == kCbBfp8) {
+    if (gb_kind == kGbF16) hipLaunchKernelGGL((kan_column_kernel<kGbF16, bfp8_t>), grid, block, 0, s, a);
+    else hipLaunchKernelGGL((kan_column_kernel<kGbF32, bfp8_t>), grid, block, 0, s, a);
   } else {
     if (gb_kind == kGbF16) hipLaunchKernelGGL((kan_column_kernel<kGbF16, float>), grid, block, 0, s, a);
     else hipLaunchKernelGGL((kan_column_kernel<kGbF32, float>), grid, block, 0, s, a);

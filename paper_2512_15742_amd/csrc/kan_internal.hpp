@@ -161,7 +161,8 @@ constexpr int kBucketMaxIn = 4096;      // the basis table of all inputs lives i
 constexpr int kBucketThreads = 1024;
 constexpr int kBucketMaxJw = 1024;      // outputs per workgroup (their sums are staged in LDS)
 // Codebook bytes per bucket: 8192 Int8, 4096 fp16 or 2048 fp32 rows for layers of up to 2048
-// inputs, half of that for wider layers (whose basis table takes twice the LDS).
+// inputs, half of that for wider layers (whose basis table takes twice the LDS); 4096 (2048)
+// block-floating-point rows of 12 bytes use 48 (24) KB of it.
 constexpr int bucket_bytes(int n_in) { return n_in > 2048 ? 40960 : 81920; }
 // The preparation regroups a layer tile by tile: kPrepareRows inputs x kPrepareCols outputs per workgroup.
 constexpr int kPrepareRows = 256;
@@ -211,7 +212,8 @@ inline BucketGeom bucket_geometry(int n_in, int n_out, int K, int code, int gb_k
   // 32 bytes of slack after every array: threads load aligned groups of eight records
   auto up = [](size_t v) { return (v + 32 + 255) / 256 * 256; };
   BucketGeom g;
-  g.rows_shift = (code == kCbI8 ? 13 : (code == kCbF16 ? 12 : 11)) - (n_in > 2048 ? 1 : 0);
+  // (block-floating-point rows: 4096 rows of 12 bytes, 48 KB of the 80 KB a bucket may take)
+  g.rows_shift = (code == kCbI8 ? 13 : ((code == kCbF16 || code == kCbBfp8) ? 12 : 11)) - (n_in > 2048 ? 1 : 0);
   g.n_buckets = (K + (1 << g.rows_shift) - 1) >> g.rows_shift;
   const size_t E = (size_t)n_in * n_out;
   g.off_seg = 0;

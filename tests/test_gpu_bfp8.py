@@ -40,7 +40,7 @@ def test_bfp8_rows_and_ids_bit_exact(kb, idx_dtype, K):
     ref = ko.dequantise_codebook(P.codebook)[P.idx.reshape(-1).astype(np.int64)].astype(np.float32)
     assert np.array_equal(rows.cpu().numpy(), ref)
     assert kb.kan_vq_count_bad_indices(L) == 0
-    assert kb.kan_vq_prepared_bytes(L) == 0                  # no bucket layout for this row type
+    assert kb.kan_vq_prepared_bytes(L) > 0                   # buckets of 4096 twelve-byte rows
 
 
 @pytest.mark.parametrize("gb", ["f16", "f32"])
@@ -98,10 +98,45 @@ def test_bfp8_config3_shape_head(kb, B, path_name):
 def test_bfp8_descriptor_rules(kb):
     P = synth.make_layer(3, 16, 16, 100, cb_dtype="bfp8", gb_dtype="f16")
     L = kb.VQLayer(P)
-    with pytest.raises(kb.KanError) as e:
-        kb.kan_vq_prepare(L)
-    assert e.value.status == kb.KAN_ERR_UNSUPPORTED
     L.desc.codebook = L.codebook.data_ptr() + 2              # rows must be 4-byte aligned
     with pytest.raises(kb.KanError) as e:
         kb.kan_vq_layer_forward(L, torch.zeros((2, 16), device="cuda"))
     assert e.value.status == kb.KAN_ERR_SHAPE
+
+
+@pytest.mark.parametrize("gb", ["f16", "f32"])
+@pytest.mark.parametrize("n_in,n_out,K,B", [(130, 67, 5000, 1), (257, 130, 4097, 3), (520, 264, 9000, 4), (2100, 96, 2049, 2),
+                                             (1000, 600, 20001, 1), (64, 24, 1, 4)])
+def test_bfp8_prepared_layout(kb, gb, n_in, n_out, K, B):
+    """Prepared block-floating-point layers: buckets of 4096 twelve-byte rows (2048 for more than 2048 inputs) in
+    LDS, the row's exponent read beside its window; small layers on the column kernel, the others on the bucket
+    kernel (also forced there).  Against the oracle and against the same layer unprepared."""
+    P = synth.make_layer(11 * n_in + n_out + K, n_in, n_out, K, cb_dtype="bfp8", gb_dtype=gb)
+    P.idx.reshape(-1)[:4] = [0, K - 1, min(K - 1, 4095), min(K - 1, 4096)]       # both sides of a bucket boundary
+    x = synth.make_x(B + 5, B, n_in)
+    x[0, 0], x[-1, -1] = 1.0, -1.0
+    y_ref, A = ko.vq_layer_forward(x, **P.as_dict(), return_abs=True)
+    plain = kb.kan_vq_layer_forward(kb.VQLayer(P), to_dev(x), path=kb.KAN_PATH_GATHER).cpu().numpy()
+    for flags in (0, kb.KAN_LAYER_NO_COLUMN):
+        L = kb.VQLayer(P)
+        L.desc.flags = flags
+        L.prepare()
+        name = kb.kan_vq_planned_kernel(L, B, 1, kb.KAN_PATH_GATHER)
+        assert name in ("kan_bucket", "kan_column") and (flags == 0 or name == "kan_bucket")
+        y = kb.kan_vq_layer_forward(L, to_dev(x), path=kb.KAN_PATH_GATHER).cpu().numpy()
+        rep = ko.error_report(y, y_ref, A)
+        assert np.isfinite(y).all() and rep["headline"] <= TOL_FP32 and rep["strict"] <= TOL_FP32, (name, rep)
+        assert (np.abs(y - plain) <= 2 * TOL_FP32 * A).all()
+
+
+def test_bfp8_prepared_config3_shape_head(kb):
+    """Config 3's shapes with block-floating-point codebooks, both layers prepared: bucket kernel on the first,
+    column kernel on the second, partial sums handed over between them."""
+    Ps = synth.config3_layers("f16", cb_dtype="bfp8")
+    Ls = [kb.VQLayer(p).prepare() for p in Ps]
+    for B in (1, 4):
+        x = synth.make_x(4100 + B, B, 2048)
+        y = kb.kan_vq_head_forward([Ls], to_dev(x), path=kb.KAN_PATH_GATHER)[0].cpu().numpy()
+        y_ref = ko.vq_head_forward(x, [p.as_dict() for p in Ps])
+        assert kb.kan_vq_planned_kernel(Ls[0], B, 1, kb.KAN_PATH_GATHER) == "kan_bucket"
+        assert np.isfinite(y).all() and ko.error_report(y, y_ref)["headline"] <= TOL_FP32
