@@ -43,7 +43,22 @@ def _cases(n=120, seed=20251127):
     return out
 
 
-@pytest.mark.parametrize("case", _cases(), ids=lambda c: "-".join(str(v) for v in c.values()))
+def _cases_bfp8(n=24, seed=20251128):
+    """A second list for block-floating-point codebooks (drawn apart, so that the list above stays as it was)."""
+    rng = np.random.default_rng(seed)
+    dims = [1, 3, 8, 33, 64, 129, 257, 600, 2100]
+    out = []
+    for c in range(n):
+        out.append(dict(seed=3000 + c, n_in=int(rng.choice(dims)), n_out=int(rng.choice(dims[:-1])),
+                        K=int(rng.choice([1, 5, 2047, 2048, 2049, 4096, 4097, 20001])), cb="bfp8",
+                        gb=str(rng.choice(["f32", "f16"])), idx=str(rng.choice(["u16", "u32"])),
+                        B=int(rng.choice([1, 2, 3, 4, 5, 16, 33, 64, 65, 130])),
+                        rule=str(rng.choice(["bspline", "pli"])), dist=str(rng.choice(["uniform", "zipf", "zipf-sorted"])),
+                        prepared=bool(rng.integers(0, 2))))
+    return out
+
+
+@pytest.mark.parametrize("case", _cases() + _cases_bfp8(), ids=lambda c: "-".join(str(v) for v in c.values()))
 def test_random_case(kb, case):
     P = synth.make_layer(case["seed"], case["n_in"], case["n_out"], case["K"], cb_dtype=case["cb"],
                          gb_dtype=case["gb"], idx_dtype=case["idx"], idx_dist=case["dist"], zipf_s=1.3)
