@@ -34,6 +34,7 @@ UNITS = [
     ("kan_misc.hip", "kan_misc.o", []),
     ("kan_mfma.hip", "kan_mfma.o", []),
     ("kan_fused.hip", "kan_fused.o", []),
+    ("kan_fused.hip", "kan_fused_chained.o", ["-DKAN_FUSED_CH=1"]),
     ("kan_bucket.hip", "kan_bucket.o", []),
     ("kan_assign.hip", "kan_assign.o", []),
     ("kan_gather.hip", "kan_gather_bt1.o", ["-DKAN_BT=1"]),

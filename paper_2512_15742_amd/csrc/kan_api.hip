@@ -615,9 +615,13 @@ kan_status run_layer_group(const LayerPlan& p, GatherArgs& a, const void* const*
     f.n_jt = p.n_jt;
     f.apply_tanh = tanh_in_kernel;
     f.rule = a.rule;
+    f.x_parts = chain.in_parts;
+    f.x_part_stride = chain.in_part_stride;
+    f.x_tanh = chain.in_tanh;
     memcpy(f.h, a.h, sizeof(f.h));
     dim3 grid((unsigned)(p.n_jt * p.n_bt), (unsigned)p.n_chunks, (unsigned)heads);
-    st = run(p.name, s, [&] { return launch_fused(p.cfg, f, f32, grid, s); });
+    if (chain.in_parts > 1) st = run(p.name, s, [&] { return launch_fused_chained(p.cfg, f, f32, grid, s); });
+    else st = run(p.name, s, [&] { return launch_fused(p.cfg, f, f32, grid, s); });
   } else {
     a.dst = dst;
     a.dst_head_stride = dst_head_stride;
@@ -638,12 +642,29 @@ kan_status check_path(int32_t path) {
 }
 
 // Layer l leaves its partial sums to layer l+1 (one group of heads only: the buffers are
-// sized for one group).  Consumers: the bucket kernel (after a bucket layer) and the basis
-// preparation of the matrix-core path (after any layer that splits its inputs).
-bool chained(const std::vector<LayerPlan>& plans, int l, int n_heads) {
+// sized for one group).  Consumers: the bucket kernel (after a bucket layer), the basis
+// preparation of the matrix-core path (after any layer that splits its inputs) and the fused
+// kernel on tiles of 32 samples (after any such layer: see fused_takes_slices).
+bool fused_takes_slices(const LayerPlan& from, const LayerPlan& to, int n_in, int64_t B);
+
+bool chained(const std::vector<LayerPlan>& plans, int l, int n_heads, const kan_vq_layer* layers, int64_t B) {
   if (l < 0 || l + 1 >= (int)plans.size() || n_heads > kMaxGroup || plans[l].n_chunks <= 1) return false;
   if (plans[l + 1].kind == kPlanBucket || plans[l + 1].kind == kPlanColumn) return plans[l].kind == kPlanBucket;
+  if (plans[l + 1].kind == kPlanFused16 || plans[l + 1].kind == kPlanFused32)
+    return fused_takes_slices(plans[l], plans[l + 1], layers[l + 1].in, B);
   return plans[l + 1].kind == kPlanMfma && plans[l].n_chunks <= kMaxChainedSlices;
+}
+
+// The fused kernel adds the slices of its own chunk of inputs before its first step when that
+// is cheaper than a reduction launch in between: tiles of 32 samples, the chunk's inputs of the
+// tile within the kernel's LDS array, 16-byte loads (inputs in fours), at most 32 such loads
+// per thread (two rounds in flight), and few output tiles (every one of them adds the slices
+// again: config 3's second layer at batch 16, 2 tiles x 64 slices, reads 8 MB instead of 4).
+bool fused_takes_slices(const LayerPlan& from, const LayerPlan& to, int n_in, int64_t B) {
+  if (to.cfg.bt != 32 || from.n_chunks > kFusedChainMaxParts || to.n_jt > 8) return false;
+  if (n_in % 4 != 0 || to.rows_per_chunk % 4 != 0 || 32ll * to.rows_per_chunk > kFusedChainFloats) return false;
+  const long long rows = B < 32 ? B : 32;
+  return (long long)from.n_chunks * rows * (to.rows_per_chunk / 4) <= 32 * 256;
 }
 
 // Validates a [n_heads][n_layers] descriptor table; fills per-layer plans and scratch sizes.
@@ -693,7 +714,7 @@ kan_status plan_head(const kan_vq_layer* layers, int32_t n_layers, int32_t n_hea
   }
   // chained layers hand their partial sums straight on: two buffers, used in turn
   for (int l = 0; l + 1 < n_layers; ++l)
-    if (chained(*plans, l, n_heads)) ws->partial2 = ws->partial;
+    if (chained(*plans, l, n_heads, layers, B)) ws->partial2 = ws->partial;
   return KAN_OK;
 }
 
@@ -886,8 +907,8 @@ kan_status head_forward(const kan_vq_layer* layers, int32_t n_layers, int32_t n_
     Chain chain;
     chain.partial = (l & 1) ? w.partial2 : w.partial;
     if (!wl.partial2) chain.partial = w.partial;
-    chain.out = chained(plans, l, n_heads);
-    if (chained(plans, l - 1, n_heads)) {
+    chain.out = chained(plans, l, n_heads, layers, B);
+    if (chained(plans, l - 1, n_heads, layers, B)) {
       src = ((l - 1) & 1) ? w.partial2 : w.partial;
       chain.in_parts = plans[l - 1].n_chunks;
       chain.in_part_stride = (long long)B * R.in;

@@ -58,9 +58,18 @@ constexpr int LDF = 84;                // fp32 tile: row stride in floats (336 B
 // instruction): slot s of a lane's four edges is input 2 kg + s % 2 in block s / 2, instead of input
 // 4 lh + s in one column.  (The other forms are compiled from the same text as before: every place
 // that differs is a branch on T16.)
-template <typename IdxT, typename GbT, typename CbT, bool F32, int MBLK, bool STAGE, bool T16 = false>
+// CH (32-sample tiles): the input arrives as the previous layer's partial sums, one slice per
+// chunk of that layer's inputs.  Before its first step the workgroup adds the slices of its own
+// chunk of inputs (16-byte loads, up to 16 in flight per thread; threads that share an item take
+// consecutive runs of slices and their sums are added in run order through LDS), squashes them and
+// keeps them in dynamic shared memory, [valid sample rows][inputs of the chunk]; the steps read
+// their inputs from there.  The reduction launch between the two layers and the round trip of the
+// hidden activation through memory go.  The kernels without CH are compiled from the same text as
+// before: every place that differs is a branch on CH.
+template <typename IdxT, typename GbT, typename CbT, bool F32, int MBLK, bool STAGE, bool T16 = false, bool CH = false>
 __global__ __launch_bounds__(kThreads, 2) void kan_fused_kernel(const FusedArgs a) {
   static_assert(!T16 || (F32 && MBLK == 1), "16-sample tiles: fp32 operands only");
+  static_assert(!CH || MBLK == 1, "chained input: 32-sample tiles only");
   constexpr int BM = 32 * MBLK;
   constexpr int NPAIR = MBLK;          // (sample, input) pairs per thread and step
   // The precise path comes in two forms: fp32 operands for 32-sample tiles (one row block: the 40 fp32
@@ -119,6 +128,92 @@ __global__ __launch_bounds__(kThreads, 2) void kan_fused_kernel(const FusedArgs 
   const float* xrow[NPAIR];
 #pragma unroll
   for (int q = 0; q < NPAIR; ++q) xrow[q] = xh + (long long)min(b0 + psm + 32 * q, B - 1) * n_in;
+  extern __shared__ __attribute__((aligned(16))) float sX[];      // CH: the chunk's inputs (dynamic; none otherwise)
+  // CH: valid sample rows of the tile; inputs of the chunk, a multiple of four (the host checks n_in and the chunk length)
+  [[maybe_unused]] const int x_rows = min(BM, B - b0), x_len = i_end - i_begin;
+  // Two halves, called by the pipelines below: chain_issue once their first metadata loads are on their
+  // way (it requests the first 16 slices of the thread's first item and waits for nothing), chain_finish
+  // once the first gathers are out (it adds those slices, fetches what is left, and fills sX).
+  struct ChainItem {
+    int row, c4, p_begin, p_end;
+    bool live;
+    const float* src;
+  };
+  [[maybe_unused]] auto chain_item = [&](int q0) {
+    const int len4 = x_len >> 2;
+    const int n_items = x_rows * len4;                  // 16-byte items of the tile
+    const int parts = a.x_parts;
+    const int runs = n_items >= kThreads ? 1 : kThreads / n_items;    // threads per item
+    const int per_run = (parts + runs - 1) / runs;
+    const int q = runs > 1 ? tid % n_items : q0 + tid;
+    const int g = runs > 1 ? tid / n_items : 0;
+    ChainItem it;
+    it.live = q < n_items && g < runs;
+    const int qq = it.live ? q : 0;
+    it.row = qq / len4;
+    it.c4 = qq - it.row * len4;
+    it.src = xh + (long long)(b0 + it.row) * n_in + i_begin + 4 * it.c4;
+    it.p_begin = min(g * per_run, parts);
+    it.p_end = min(parts, it.p_begin + per_run);
+    return it;
+  };
+  [[maybe_unused]] auto chain_load = [&](const ChainItem& it, int p0, f32x4 (&t)[16]) {
+#pragma unroll
+    for (int pp = 0; pp < 16; ++pp)                     // (slices past the last one are re-reads of it, added as zero)
+      t[pp] = *(const f32x4*)(it.src + (long long)min(p0 + pp, a.x_parts - 1) * a.x_part_stride);
+  };
+  [[maybe_unused]] auto chain_issue = [&](f32x4 (&t)[16]) {
+    const ChainItem it = chain_item(0);
+    chain_load(it, it.p_begin, t);
+  };
+  [[maybe_unused]] auto chain_finish = [&](const f32x4 (&first)[16]) {
+    static_assert(!CH || kTileBytes >= kThreads * 16, "the runs' sums pass through the first tile");
+    const int n_items = x_rows * (x_len >> 2);
+    const int runs = n_items >= kThreads ? 1 : kThreads / n_items;
+    f32x4* const scr = (f32x4*)sTile[0];
+    for (int q0 = 0; q0 < n_items; q0 += kThreads) {
+      const ChainItem it = chain_item(q0);
+      f32x4 sum = {0.f, 0.f, 0.f, 0.f};
+      auto add = [&](const f32x4 (&t)[16], int p0) {
+#pragma unroll
+        for (int pp = 0; pp < 16; ++pp) {
+          const bool in = p0 + pp < it.p_end;
+          sum.x += in ? t[pp].x : 0.f;
+          sum.y += in ? t[pp].y : 0.f;
+          sum.z += in ? t[pp].z : 0.f;
+          sum.w += in ? t[pp].w : 0.f;
+        }
+      };
+      int p0 = it.p_begin;
+      if (q0 == 0) {                                    // (uniform) the slices chain_issue asked for
+        add(first, p0);
+        p0 += 16;
+      }
+      for (; p0 < it.p_end; p0 += 16) {
+        f32x4 t[16];
+        chain_load(it, p0, t);
+        add(t, p0);
+      }
+      bool owner = it.live;
+      if (runs > 1) {                                   // (uniform; the loop then has this one round)
+        scr[tid] = sum;
+        __syncthreads();
+        owner = tid < n_items;
+        if (owner)
+          for (int gg = 1; gg < runs; ++gg) sum += scr[gg * n_items + tid];
+      }
+      if (owner) {
+        if (a.x_tanh) {
+          sum.x = tanhf(sum.x);
+          sum.y = tanhf(sum.y);
+          sum.z = tanhf(sum.z);
+          sum.w = tanhf(sum.w);
+        }
+        *(f32x4*)(sX + it.row * x_len + 4 * it.c4) = sum;
+      }
+    }
+    __syncthreads();
+  };
   // coefficient operand: column jc, input rows 4*lh .. 4*lh+3 of every step
   const int j = jt * BN + wave * 32 + ln;
   const bool j_ok = j < n_out;
@@ -381,6 +476,10 @@ __global__ __launch_bounds__(kThreads, 2) void kan_fused_kernel(const FusedArgs 
   auto stage_read = [&](int k, int sp, Ids& ids, GainBias& gb) { stage_read_into(k, sp, ids.id, gb.g, gb.b); };
 
   auto load_u = [&](int k, float (&uv)[NPAIR]) {
+    if constexpr (CH) {
+      uv[0] = sX[min(psm, x_rows - 1) * x_len + min(k * IT + pin, x_len - 1)];
+      return;
+    }
     const int i = min(i_begin + k * IT + pin, n_in - 1);
 #pragma unroll
     for (int q = 0; q < NPAIR; ++q) uv[q] = xrow[q][i];
@@ -602,23 +701,30 @@ __global__ __launch_bounds__(kThreads, 2) void kan_fused_kernel(const FusedArgs 
     // Nothing is fetched for steps past the end: the address units that serve the random
     // codeword gathers are the bottleneck of this kernel, so wasted gathers are not free.
     MetaRaw mraw;                                     // STAGE: the pair of steps on its way from memory
+    [[maybe_unused]] f32x4 xfirst[CH ? 16 : 1];       // CH: the first slices of the thread's item
     if constexpr (STAGE) {
       stage_issue(0, mraw);
+      if constexpr (CH) chain_issue(xfirst);
       stage_commit(mraw);
       stage_read_into(0, 0, meta[0].id, meta[0].g, meta[0].b);
       stage_read_into(1, 1, meta[1].id, meta[1].g, meta[1].b);
       if (2 < n_steps) stage_issue(1, mraw);
-      load_u(0, uv[0]);
+      if constexpr (!CH) load_u(0, uv[0]);
       gather_rows(meta[0], rows[0]);
       if (1 < n_steps) gather_rows(meta[1], rows[1]);
     } else {
       load_meta(0, meta[0]);
       if (1 < n_steps) load_meta(1, meta[1]);
-      load_u(0, uv[0]);
+      if constexpr (CH) chain_issue(xfirst);
+      if constexpr (!CH) load_u(0, uv[0]);
       gather_rows(meta[0], rows[0]);
       if (2 < n_steps) load_meta(2, meta[2]);
       if (1 < n_steps) gather_rows(meta[1], rows[1]);
       if (3 < n_steps) load_meta(3, meta[3]);
+    }
+    if constexpr (CH) {                               // the chunk's inputs, behind the first gathers
+      chain_finish(xfirst);
+      load_u(0, uv[0]);
     }
     load_u(1, uv[1]);
     dequant_step(rows[0], meta[0], frag[0]);
@@ -698,6 +804,29 @@ __global__ __launch_bounds__(kThreads, 2) void kan_fused_kernel(const FusedArgs 
   }
 }
 
+#ifndef KAN_FUSED_CH
+#define KAN_FUSED_CH 0          // 1: this translation unit holds the kernels with chained input (launch_fused_chained)
+#endif
+
+#if KAN_FUSED_CH
+template <typename IdxT, typename GbT, typename CbT>
+hipError_t launch_variant(const FusedArgs& a, bool f32, int mblk, bool stage_ok, dim3 grid, hipStream_t s) {
+  if (mblk != 1) return hipErrorInvalidValue;
+  const bool stage = stage_ok && sizeof(GbT) <= 2;
+  const unsigned lds = 32u * (unsigned)a.rows_per_chunk * 4u;       // the chunk's inputs of the tile's 32 sample rows
+  if (f32 && a.B <= 16) {                    // 16-sample tiles
+    if (stage) hipLaunchKernelGGL((kan_fused_kernel<IdxT, GbT, CbT, true, 1, true, true, true>), grid, dim3(kThreads), lds, s, a);
+    else hipLaunchKernelGGL((kan_fused_kernel<IdxT, GbT, CbT, true, 1, false, true, true>), grid, dim3(kThreads), lds, s, a);
+  } else if (f32) {
+    if (stage) hipLaunchKernelGGL((kan_fused_kernel<IdxT, GbT, CbT, true, 1, true, false, true>), grid, dim3(kThreads), lds, s, a);
+    else hipLaunchKernelGGL((kan_fused_kernel<IdxT, GbT, CbT, true, 1, false, false, true>), grid, dim3(kThreads), lds, s, a);
+  } else {
+    if (stage) hipLaunchKernelGGL((kan_fused_kernel<IdxT, GbT, CbT, false, 1, true, false, true>), grid, dim3(kThreads), lds, s, a);
+    else hipLaunchKernelGGL((kan_fused_kernel<IdxT, GbT, CbT, false, 1, false, false, true>), grid, dim3(kThreads), lds, s, a);
+  }
+  return hipGetLastError();
+}
+#else
 template <typename IdxT, typename GbT, typename CbT>
 hipError_t launch_variant(const FusedArgs& a, bool f32, int mblk, bool stage_ok, dim3 grid, hipStream_t s) {
   // In the shallow pipeline the staged loads pay off for one- and two-byte gains and biases; with fp32 ones
@@ -723,6 +852,7 @@ hipError_t launch_variant(const FusedArgs& a, bool f32, int mblk, bool stage_ok,
   }
   return hipGetLastError();
 }
+#endif
 
 template <typename IdxT>
 hipError_t launch_types(const GatherCfg& c, const FusedArgs& a, bool f32, int mblk, bool stage, dim3 grid, hipStream_t s) {
@@ -744,8 +874,19 @@ hipError_t launch_types(const GatherCfg& c, const FusedArgs& a, bool f32, int mb
 
 }  // namespace
 
+#if KAN_FUSED_CH
+hipError_t launch_fused_chained(const GatherCfg& c, const FusedArgs& a, bool f32, dim3 grid, hipStream_t s) {
+  if (c.code == kDense || a.B < 1 || c.bt != 32) return hipErrorInvalidValue;
+  // what the kernel's 16-byte loads of the slices and its tile of inputs in LDS assume
+  if (a.x_parts < 2 || a.x_parts > kFusedChainMaxParts || a.n_in % 4 != 0 || a.rows_per_chunk % 4 != 0 ||
+      a.rows_per_chunk < 4 || 32ll * a.rows_per_chunk > kFusedChainFloats || a.x_part_stride % 4 != 0 ||
+      a.x_head_stride % 4 != 0 || (uintptr_t)a.x % 16 != 0)
+    return hipErrorInvalidValue;
+#else
 hipError_t launch_fused(const GatherCfg& c, const FusedArgs& a, bool f32, dim3 grid, hipStream_t s) {
   if (c.code == kDense || a.B < 1 || (c.bt != 32 && c.bt != 64)) return hipErrorInvalidValue;
+  if (a.x_parts > 1) return hipErrorInvalidValue;       // slices of the input: launch_fused_chained
+#endif
   const int mblk = c.bt / 32;
   // the staged metadata loads need rows of the per-edge arrays that are whole 16-byte units
   bool stage = a.n_out % 16 == 0;

@@ -146,10 +146,22 @@ struct FusedArgs {
   int n_jt;                    // output tiles; blockIdx.x = batch_tile * n_jt + jt
   int apply_tanh;
   int rule;                    // edge function: 0 cubic B-spline, 1 two-tap linear interpolation
+  // Chained input (launch_fused_chained only): x is the previous layer's partial sums,
+  // [head][x_parts][B][n_in]; a workgroup adds the slices of its own inputs in a fixed order
+  // and squashes them (x_tanh) before its first step.
+  int x_parts;                 // 0 or 1: plain x
+  long long x_part_stride;
+  int x_tanh;
   LayerPtrs h[kMaxGroup];
 };
 
 hipError_t launch_fused(const GatherCfg&, const FusedArgs&, bool f32, dim3 grid, hipStream_t);
+// The same kernels for tiles of 32 samples whose input is still in slices (x_parts > 1).  The
+// chunk's inputs are kept in LDS: 32 * rows_per_chunk floats of dynamic shared memory, at most
+// kFusedChainFloats; n_in and rows_per_chunk are multiples of four (16-byte loads).
+constexpr int kFusedChainFloats = 2048;
+constexpr int kFusedChainMaxParts = 64;
+hipError_t launch_fused_chained(const GatherCfg&, const FusedArgs&, bool f32, dim3 grid, hipStream_t);
 
 // ---- bucketed small-batch path (prepared layers) ----------------------------------
 // A prepared layer holds its edges regrouped by codebook bucket (a run of consecutive

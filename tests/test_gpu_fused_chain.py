@@ -1,0 +1,125 @@
+"""Heads of several layers at batch 2..32 on the fused kernel: a layer that cut its inputs into chunks
+hands its partial sums straight to the next layer's fused kernel, which adds the slices of its own chunk
+of inputs (fixed order), squashes them and keeps them in LDS; no reduction launch in between.  Checked:
+the launches that ran (no reduction after a chained layer; one where the hand-over does not apply), the
+head's output against the float64 head of the oracle and against the layer-by-layer chain of single-layer
+calls, bit-reproducibility, groups of heads, ragged shapes, every storage type."""
+import numpy as np
+import pytest
+
+from oracle import kan_oracle as ko
+from paper_2512_15742_amd import synth
+
+from kan_testlib import TOL_FP32, TOL_MFMA, check_head_layer_by_layer, gpu_layers, to_dev
+
+pytestmark = pytest.mark.gpu
+
+torch = pytest.importorskip("torch")
+
+
+@pytest.fixture(scope="module")
+def kb():
+    if not torch.cuda.is_available():
+        pytest.skip("no GPU")
+    from paper_2512_15742_amd import binding
+    binding.lib()
+    return binding
+
+
+def _launches(kb, heads, xd, path):
+    kb.kan_vq_head_forward(heads, xd, path=path)
+    torch.cuda.synchronize()
+    kb.kan_prof_begin(64)
+    kb.kan_vq_head_forward(heads, xd, path=path)
+    return set(kb.kan_prof_end())
+
+
+def _head(seed, dims, K, cb="i8", gb="f16", idx="u16"):
+    return [synth.make_layer(seed + l, dims[l], dims[l + 1], K, cb_dtype=cb, gb_dtype=gb, idx_dtype=idx)
+            for l in range(len(dims) - 1)]
+
+
+def _check(kb, Ps, x, path, tol, expect_reduce_after_first):
+    Ls = gpu_layers(Ps)
+    xd = to_dev(x)
+    B = x.shape[0]
+    name = "kan_fused_f32" if path == kb.KAN_PATH_GATHER else "kan_fused_f16"
+    for L in Ls:
+        assert kb.kan_vq_planned_kernel(L, B, 1, path) == name
+    rec = _launches(kb, [Ls], xd, path)
+    assert ("kan_reduce@L1" in rec) == expect_reduce_after_first, rec
+    assert f"{name}@L{len(Ps)}" in rec, rec
+    y_dev = torch.full((1, B, Ps[-1].n_out), float("nan"), device="cuda")       # an output left unwritten would show
+    ws = torch.empty(kb.kan_vq_workspace_bytes([Ls], B, path), dtype=torch.uint8, device="cuda")
+    y = kb.kan_vq_head_forward([Ls], xd, path=path, ws=ws, y=y_dev)[0].cpu().numpy()
+    assert np.isfinite(y).all()
+    y_ref = ko.vq_head_forward(x, [p.as_dict() for p in Ps])
+    rep = ko.error_report(y, y_ref)
+    assert rep["headline"] <= tol, rep
+    # every layer on identical fp32 inputs, and the head call against that chain: two GPU evaluations of
+    # the same hidden activations, which differ in the last bits (summation order)
+    y_chain, worst = check_head_layer_by_layer(kb, Ls, Ps, x, path, tol)
+    assert np.abs(y - y_chain).max() <= 2 * tol * np.abs(y_chain).max(), (worst, rep)
+    # bit-reproducible
+    y_again = kb.kan_vq_head_forward([Ls], xd, path=path, ws=ws)[0].cpu().numpy()
+    assert np.array_equal(y, y_again)
+    return y
+
+
+@pytest.mark.parametrize("B", [2, 5, 16, 17, 32])
+@pytest.mark.parametrize("path_name", ["precise", "fp16"])
+def test_config3_shapes(kb, B, path_name):
+    path, tol = (kb.KAN_PATH_GATHER, TOL_FP32) if path_name == "precise" else (kb.KAN_PATH_MFMA, TOL_MFMA)
+    Ps, x = synth.config3(B)
+    # (at batch 32 a thread would have 48 slices of 16 bytes to fetch, three rounds: the planner keeps the reduction)
+    _check(kb, Ps, x, path, tol, expect_reduce_after_first=(B == 32))
+
+
+@pytest.mark.parametrize("dims", [(256, 128, 32), (100, 60, 20), (512, 256, 128, 16), (72, 36, 130), (1000, 200, 300, 7)],
+                         ids=lambda d: "-".join(map(str, d)))
+@pytest.mark.parametrize("B", [3, 16, 29])
+def test_ragged_heads(kb, dims, B):
+    Ps = _head(8100 + B, dims, 5003)
+    x = synth.make_x(8200 + B, B, dims[0])
+    x[0, 0], x[-1, -1] = -1.0, 1.0
+    for path, tol in ((kb.KAN_PATH_GATHER, TOL_FP32), (kb.KAN_PATH_MFMA, TOL_MFMA)):
+        Ls = gpu_layers(Ps)
+        rec = _launches(kb, [Ls], to_dev(x), path)
+        _check(kb, Ps, x, path, tol, expect_reduce_after_first="kan_reduce@L1" in rec)
+    # (whether a layer is cut into chunks at all depends on its size: the shapes above cover both)
+
+
+def test_hidden_width_not_in_fours_keeps_the_reduction(kb):
+    """The hand-over needs the consumer's inputs in groups of four (16-byte loads of the slices)."""
+    Ps = _head(8300, (512, 130, 40), 4099)
+    x = synth.make_x(8301, 16, 512)
+    for path, tol in ((kb.KAN_PATH_GATHER, TOL_FP32), (kb.KAN_PATH_MFMA, TOL_MFMA)):
+        _check(kb, Ps, x, path, tol, expect_reduce_after_first=True)
+
+
+@pytest.mark.parametrize("cb,gb,idx,K", [("f32", "f32", "u32", 70001), ("f16", "f16", "u16", 300), ("i8", "q8", "u16", 65536),
+                                         ("bfp8", "f16", "u16", 1000), ("f16", "f32", "u16", 2000)])
+def test_storage_types(kb, cb, gb, idx, K):
+    Ps = _head(8400, (768, 256, 64), K, cb=cb, gb=gb, idx=idx)
+    for B in (4, 16, 24):
+        x = synth.make_x(8401 + B, B, 768)
+        for path, tol in ((kb.KAN_PATH_GATHER, TOL_FP32), (kb.KAN_PATH_MFMA, TOL_MFMA)):
+            _check(kb, Ps, x, path, tol, expect_reduce_after_first=False)
+
+
+def test_group_of_heads(kb):
+    """Three heads in one grouped call: each one's slices are its own."""
+    B = 12
+    heads_P = [_head(8500 + 10 * h, (1024, 256, 48), 4096) for h in range(3)]
+    x = synth.make_x(8501, B, 1024)
+    heads_L = [gpu_layers(Ps) for Ps in heads_P]
+    for path, tol in ((kb.KAN_PATH_GATHER, TOL_FP32), (kb.KAN_PATH_MFMA, TOL_MFMA)):
+        rec = _launches(kb, heads_L, to_dev(x), path)
+        assert "kan_reduce@L1" not in rec, rec
+        y = kb.kan_vq_head_forward(heads_L, to_dev(x), path=path).cpu().numpy()
+        for h, Ps in enumerate(heads_P):
+            y_ref = ko.vq_head_forward(x, [p.as_dict() for p in Ps])
+            rep = ko.error_report(y[h], y_ref)
+            assert np.isfinite(y[h]).all() and rep["headline"] <= tol, (h, rep)
+            y_one = kb.kan_vq_head_forward([heads_L[h]], to_dev(x), path=path)[0].cpu().numpy()
+            assert np.abs(y[h] - y_one).max() <= 2 * tol * np.abs(y_ref).max()
