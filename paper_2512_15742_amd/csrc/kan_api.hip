@@ -658,8 +658,8 @@ bool chained(const std::vector<LayerPlan>& plans, int l, int n_heads, const kan_
 // The fused kernel adds the slices of its own chunk of inputs before its first step when that
 // is cheaper than a reduction launch in between: tiles of 32 samples, the chunk's inputs of the
 // tile within the kernel's LDS array, 16-byte loads (inputs in fours), at most 32 such loads
-// per thread (two rounds in flight), and few output tiles (every one of them adds the slices
-// again: config 3's second layer at batch 16, 2 tiles x 64 slices, reads 8 MB instead of 4).
+// per thread (two rounds in flight; with three, batch 32 of config 3, nothing was gained), and
+// few output tiles (every one of them adds the slices again).
 bool fused_takes_slices(const LayerPlan& from, const LayerPlan& to, int n_in, int64_t B) {
   if (to.cfg.bt != 32 || from.n_chunks > kFusedChainMaxParts || to.n_jt > 8) return false;
   if (n_in % 4 != 0 || to.rows_per_chunk % 4 != 0 || 32ll * to.rows_per_chunk > kFusedChainFloats) return false;

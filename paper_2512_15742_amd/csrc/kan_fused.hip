@@ -93,8 +93,12 @@ __global__ __launch_bounds__(kThreads, 2) void kan_fused_kernel(const FusedArgs 
   // of all of them (655 KB each as Int8) would compete for each L2.  Instead the list of work
   // items, sorted by head, is cut into eight contiguous runs, one per XCD, taken in order: an XCD
   // then works on two or three heads at a time and a codebook enters one L2 only.
+  // (CH: the same renumbering for a single head: the output tiles of a chunk read the same slices of
+  // the input, and neighbouring chunks the two halves of the same 128-byte lines when a chunk is 16
+  // inputs long, so runs of consecutive (chunk, tile) items on one XCD fetch every line once: config
+  // 3's second layer at batch 16 fetched 22.8 MiB with the plain order, 4 MiB of slices four times over.)
   int head = blockIdx.z, chunk = blockIdx.y, tile = blockIdx.x;
-  if (gridDim.z > 1) {
+  if (gridDim.z > 1 || CH) {
     const unsigned T = gridDim.x, C = gridDim.y, W = T * C * gridDim.z;
     const unsigned L = blockIdx.x + T * (blockIdx.y + C * blockIdx.z);
     const unsigned xcd = L & 7u, m = L >> 3, q = W >> 3, r = W & 7u;
