@@ -627,6 +627,9 @@ kan_status run_layer_group(const LayerPlan& p, GatherArgs& a, const void* const*
     a.dst_head_stride = dst_head_stride;
     a.dst_chunk_stride = dst_chunk_stride;
     a.apply_tanh = tanh_in_kernel;
+    a.x_parts = chain.in_parts;
+    a.x_part_stride = chain.in_part_stride;
+    a.x_tanh = chain.in_tanh;
     st = run(p.name, s, [&] { return launch_gather(p, a, heads, s); });
   }
   if (st != KAN_OK || !split || chain.out) return st;
@@ -643,8 +646,9 @@ kan_status check_path(int32_t path) {
 
 // Layer l leaves its partial sums to layer l+1 (one group of heads only: the buffers are
 // sized for one group).  Consumers: the bucket kernel (after a bucket layer), the basis
-// preparation of the matrix-core path (after any layer that splits its inputs) and the fused
-// kernel on tiles of 32 samples (after any such layer: see fused_takes_slices).
+// preparation of the matrix-core path (after any layer that splits its inputs), the fused
+// kernel on tiles of 32 samples (after any such layer: see fused_takes_slices) and the
+// vector-ALU kernel at batch 1.
 bool fused_takes_slices(const LayerPlan& from, const LayerPlan& to, int n_in, int64_t B);
 
 bool chained(const std::vector<LayerPlan>& plans, int l, int n_heads, const kan_vq_layer* layers, int64_t B) {
@@ -652,6 +656,11 @@ bool chained(const std::vector<LayerPlan>& plans, int l, int n_heads, const kan_
   if (plans[l + 1].kind == kPlanBucket || plans[l + 1].kind == kPlanColumn) return plans[l].kind == kPlanBucket;
   if (plans[l + 1].kind == kPlanFused16 || plans[l + 1].kind == kPlanFused32)
     return fused_takes_slices(plans[l], plans[l + 1], layers[l + 1].in, B);
+  // the vector-ALU kernel at batch 1: the threads that share a row of the basis table split the
+  // slices; few output tiles (each adds the slices again)
+  if (plans[l + 1].kind == kPlanGather)
+    return plans[l + 1].cfg.bt == 1 && plans[l + 1].cfg.code != kDense && plans[l].n_chunks <= kGatherChainMaxParts &&
+           plans[l + 1].n_jt <= 4;
   return plans[l + 1].kind == kPlanMfma && plans[l].n_chunks <= kMaxChainedSlices;
 }
 

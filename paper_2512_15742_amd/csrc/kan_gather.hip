@@ -34,8 +34,10 @@ constexpr int kThreads = 256;
 constexpr int kWaves = kThreads / kWave;
 constexpr int kSub = 32;   // i-rows whose basis data is staged in LDS at a time
 
-template <typename IdxT, typename GbT, typename CbT, int CODE, int BT, int JPL>
+// SL (window form only): the input is still in slices, the previous layer's partial sums.
+template <typename IdxT, typename GbT, typename CbT, int CODE, int BT, int JPL, bool SL = false>
 __global__ __launch_bounds__(kThreads) void kan_gather_kernel(const GatherArgs a, const int wj_count) {
+  static_assert(!SL || (BT == 1 && CODE != kDense), "slices of the input: VQ layers, one sample per tile");
   // LDS: basis data for kSub rows x BT samples; later reused for the cross-wave sum.
   constexpr bool kWindow = (BT == 1 && CODE != kDense);
   constexpr int kWStride = kWindow ? 5 : 12;             // floats of basis data per (row, sample)
@@ -101,14 +103,43 @@ __global__ __launch_bounds__(kThreads) void kan_gather_kernel(const GatherArgs a
     for (int bb = 0; bb < BT; ++bb) acc[bb][p] = 0.f;
   }
 
+  // SL: the kRuns threads that share a row take consecutive runs of slices, up to 16 loads in
+  // flight each; their sums are added in run order when the row's basis data is built.
+  constexpr int kRuns = kThreads / kSub;
+  __shared__ float sxr[SL ? kRuns : 1][SL ? kSub : 1];
+
   for (int s0 = i_begin; s0 < i_end; s0 += kSub) {
     const int rows = min(kSub, i_end - s0);
     __syncthreads();
+    if constexpr (SL) {
+      const int r = tid % kSub, g = tid / kSub;
+      const int per_run = (a.x_parts + kRuns - 1) / kRuns;
+      const int p_begin = min(g * per_run, a.x_parts), p_end = min(a.x_parts, p_begin + per_run);
+      const float* src = xh + (long long)b0 * n_in + s0 + min(r, rows - 1);
+      float sum = 0.f;
+      for (int p0 = p_begin; p0 < p_end; p0 += 16) {
+        float t[16];
+#pragma unroll
+        for (int pp = 0; pp < 16; ++pp)               // (slices past the last one are re-reads of it, added as zero)
+          t[pp] = src[(long long)min(p0 + pp, a.x_parts - 1) * a.x_part_stride];
+#pragma unroll
+        for (int pp = 0; pp < 16; ++pp) sum += (p0 + pp < p_end) ? t[pp] : 0.f;
+      }
+      sxr[g][r] = sum;
+      __syncthreads();
+    }
     // ---- span + weights for (row, sample) of this sub-chunk ----------------------
     for (int t = tid; t < kSub * BT; t += kThreads) {
       const int bb = t / kSub, r = t % kSub;
       BasisW bw = {0.f, 0.f, 0.f, 0.f, 0};
-      if (r < rows && b0 + bb < a.B) bw = basis_eval_rule(xh[(long long)(b0 + bb) * n_in + s0 + r], a.rule);
+      if constexpr (SL) {
+        float xv = sxr[0][r];
+#pragma unroll
+        for (int g = 1; g < kRuns; ++g) xv += sxr[g][r];
+        if (r < rows) bw = basis_eval_rule(a.x_tanh ? tanhf(xv) : xv, a.rule);
+      } else {
+        if (r < rows && b0 + bb < a.B) bw = basis_eval_rule(xh[(long long)(b0 + bb) * n_in + s0 + r], a.rule);
+      }
       if constexpr (kWindow) {
         sw[r] = make_float4(bw.w0, bw.w1, bw.w2, bw.w3);
         ss[r] = bw.span;
@@ -283,6 +314,13 @@ __global__ __launch_bounds__(kThreads) void kan_gather_kernel(const GatherArgs a
 
 template <typename IdxT, typename GbT, typename CbT, int CODE, int JPL>
 hipError_t launch_one(const GatherCfg& c, const GatherArgs& a, dim3 grid, hipStream_t s) {
+  if constexpr (KAN_BT == 1 && CODE != kDense) {
+    if (a.x_parts > 1) {
+      hipLaunchKernelGGL((kan_gather_kernel<IdxT, GbT, CbT, CODE, KAN_BT, JPL, true>), grid, dim3(kThreads), 0, s,
+                         a, c.wj);
+      return hipGetLastError();
+    }
+  }
   hipLaunchKernelGGL((kan_gather_kernel<IdxT, GbT, CbT, CODE, KAN_BT, JPL>), grid, dim3(kThreads), 0, s,
                      a, c.wj);
   return hipGetLastError();
@@ -331,6 +369,8 @@ hipError_t launch_types(const GatherCfg& c, const GatherArgs& a, dim3 grid, hipS
 hipError_t KAN_CAT(launch_gather_bt, KAN_BT)(const GatherCfg& c, const GatherArgs& a, dim3 grid,
                                               hipStream_t s) {
   if (c.bt != KAN_BT) return hipErrorInvalidValue;
+  // slices of the input: the window form only (VQ layers, one sample per tile)
+  if (a.x_parts > 1 && (KAN_BT != 1 || c.code == kDense || a.x_parts > kGatherChainMaxParts)) return hipErrorInvalidValue;
   if (c.code == kDense) return launch_jpl<uint16_t, float, float, kDense>(c, a, grid, s);
 #if KAN_BT == 1
   return c.idx_u32 ? launch_types<uint32_t>(c, a, grid, s) : launch_types<uint16_t>(c, a, grid, s);

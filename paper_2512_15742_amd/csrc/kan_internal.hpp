@@ -47,8 +47,15 @@ struct GatherArgs {
   int apply_tanh;              // only honoured when the kernel writes final values
   long long cb_bytes;          // codebook bytes per head (0: no L2 warm-up of the codebook)
   int rule;                    // edge function: 0 cubic B-spline, 1 two-tap linear interpolation
+  // Chained input (VQ layers at batch tile 1 only): x is the previous layer's partial sums,
+  // [head][x_parts][B][n_in]; a workgroup adds the slices of its own rows in a fixed order and
+  // squashes them (x_tanh) while it builds its basis data.
+  int x_parts;                 // 0 or 1: plain x
+  long long x_part_stride;
+  int x_tanh;
   LayerPtrs h[kMaxGroup];
 };
+constexpr int kGatherChainMaxParts = 256;
 
 hipError_t launch_gather_bt1(const GatherCfg&, const GatherArgs&, dim3 grid, hipStream_t);
 hipError_t launch_gather_bt4(const GatherCfg&, const GatherArgs&, dim3 grid, hipStream_t);

@@ -1,4 +1,4 @@
-"""Heads of several layers at batch 2..32 on the fused kernel: a layer that cut its inputs into chunks
+"""Heads of several layers at batch 2..32 on the fused kernel (and at batch 1 on the vector-ALU kernel): a layer that cut its inputs into chunks
 hands its partial sums straight to the next layer's fused kernel, which adds the slices of its own chunk
 of inputs (fixed order), squashes them and keeps them in LDS; no reduction launch in between.  Checked:
 the launches that ran (no reduction after a chained layer; one where the hand-over does not apply), the
@@ -44,6 +44,8 @@ def _check(kb, Ps, x, path, tol, expect_reduce_after_first):
     xd = to_dev(x)
     B = x.shape[0]
     name = "kan_fused_f32" if path == kb.KAN_PATH_GATHER else "kan_fused_f16"
+    if B == 1 and path == kb.KAN_PATH_GATHER:
+        name = "kan_gather_bt1"
     for L in Ls:
         assert kb.kan_vq_planned_kernel(L, B, 1, path) == name
     rec = _launches(kb, [Ls], xd, path)
@@ -123,3 +125,39 @@ def test_group_of_heads(kb):
             assert np.isfinite(y[h]).all() and rep["headline"] <= tol, (h, rep)
             y_one = kb.kan_vq_head_forward([heads_L[h]], to_dev(x), path=path)[0].cpu().numpy()
             assert np.abs(y[h] - y_one).max() <= 2 * tol * np.abs(y_ref).max()
+
+
+@pytest.mark.parametrize("dims", [(2048, 1024, 256), (256, 128, 32), (100, 61, 20), (520, 300, 129, 16), (1000, 200, 7)],
+                         ids=lambda d: "-".join(map(str, d)))
+def test_batch1_vector_alu_kernel(kb, dims):
+    """Batch 1 on layers as given: the vector-ALU kernel of the next layer adds the slices itself (the threads
+    that share a row of its basis table split them), whatever the hidden width."""
+    Ps = _head(8600, dims, 5003)
+    x = synth.make_x(8601, 1, dims[0])
+    Ls = gpu_layers(Ps)
+    rec = _launches(kb, [Ls], to_dev(x), kb.KAN_PATH_GATHER)
+    # a layer that was cut into chunks is followed by no reduction unless it is the last one
+    for l in range(1, len(Ps)):
+        assert f"kan_reduce@L{l}" not in rec, rec
+    _check(kb, Ps, x, kb.KAN_PATH_GATHER, TOL_FP32, expect_reduce_after_first=False)
+
+
+@pytest.mark.parametrize("cb,gb,idx,K", [("f32", "f32", "u32", 70001), ("f16", "f16", "u16", 300), ("i8", "q8", "u16", 65536),
+                                         ("bfp8", "f16", "u16", 1000)])
+def test_batch1_storage_types(kb, cb, gb, idx, K):
+    Ps = _head(8700, (768, 256, 64), K, cb=cb, gb=gb, idx=idx)
+    x = synth.make_x(8701, 1, 768)
+    _check(kb, Ps, x, kb.KAN_PATH_GATHER, TOL_FP32, expect_reduce_after_first=False)
+
+
+def test_batch1_group_of_heads(kb):
+    heads_P = [_head(8800 + 10 * h, (1024, 256, 48), 4096) for h in range(3)]
+    x = synth.make_x(8801, 1, 1024)
+    heads_L = [gpu_layers(Ps) for Ps in heads_P]
+    rec = _launches(kb, heads_L, to_dev(x), kb.KAN_PATH_GATHER)
+    assert "kan_reduce@L1" not in rec and "kan_gather_bt1@L2" in rec, rec
+    y = kb.kan_vq_head_forward(heads_L, to_dev(x), path=kb.KAN_PATH_GATHER).cpu().numpy()
+    for h, Ps in enumerate(heads_P):
+        y_ref = ko.vq_head_forward(x, [p.as_dict() for p in Ps])
+        rep = ko.error_report(y[h], y_ref)
+        assert np.isfinite(y[h]).all() and rep["headline"] <= TOL_FP32, (h, rep)
