@@ -55,10 +55,23 @@ __global__ __launch_bounds__(kThreads) void kan_gather_kernel(const GatherArgs a
   const int wj = wave % wj_count;
   const int wi = wave / wj_count;
 
-  const int head = blockIdx.z;
-  const int chunk = blockIdx.y;
-  const int jt = blockIdx.x % a.n_jt;
-  const int btile = blockIdx.x / a.n_jt;
+  int head = blockIdx.z, chunk = blockIdx.y, tile = blockIdx.x;
+  if constexpr (SL) {
+    // Workgroups go to the eight XCDs in turn (linear id mod 8), each with an L2 of its own.  The output
+    // tiles of a chunk read the same slices, and a chunk of 16 rows is half a 128-byte line per slice,
+    // whose other half the next chunk reads: runs of consecutive (chunk, tile) items per XCD fetch every
+    // line once.
+    const unsigned T = gridDim.x, C = gridDim.y, W = T * C * gridDim.z;
+    const unsigned L = blockIdx.x + T * (blockIdx.y + C * blockIdx.z);
+    const unsigned xcd = L & 7u, m = L >> 3, q = W >> 3, r = W & 7u;
+    const unsigned item = xcd * q + min(xcd, r) + m;          // XCD x owns q + (x < r) items
+    head = (int)(item / (T * C));
+    const unsigned rem = item % (T * C);
+    chunk = (int)(rem / T);
+    tile = (int)(rem % T);
+  }
+  const int jt = tile % a.n_jt;
+  const int btile = tile / a.n_jt;
 
   const LayerPtrs hp = a.h[head];
   const int n_in = a.n_in, n_out = a.n_out;
