@@ -461,9 +461,10 @@ __global__ __launch_bounds__(kBucketThreads) void kan_bucket_kernel(const Bucket
 // codebook in L2 (Eq. (1); a thousand gathers per CU are a microsecond) and adds the products
 // in a fixed order: per thread by ascending input, then across the lanes, then the waves.
 // It writes the finished output - bias sum, activation - so no reduction pass follows.
-constexpr int kColumnPer = 8;          // edges per thread and round (2048 inputs per round)
+// PER: edges per thread and round, 8 (2048 inputs per round) or 4 for layers of at most 1024 inputs, whose
+// upper four slots would only re-read the last input (the address units see every load, used or not).
 
-template <int GK, typename CbT>
+template <int GK, typename CbT, int PER>
 __global__ __launch_bounds__(kColumnThreads) void kan_column_kernel(const BucketArgs a) {
   __shared__ float wave_sum[kColumnThreads / kWave];
   const int tid = threadIdx.x, lane = tid & (kWave - 1), wave = tid >> 6;
@@ -479,14 +480,14 @@ __global__ __launch_bounds__(kColumnThreads) void kan_column_kernel(const Bucket
   const float bias_sum = ((const float*)(prep + a.off_bias))[j];
 
   float acc = 0.f;
-  for (int i0 = 0; i0 < a.n_in; i0 += kColumnThreads * kColumnPer) {       // one round for up to 2048 inputs
+  for (int i0 = 0; i0 < a.n_in; i0 += kColumnThreads * PER) {       // one round for up to 256 * PER inputs
     // ---- everything the round needs from memory except the windows: unconditional loads,
     //      clamped addresses (inputs past the end re-read the last one and count as zero) ----
-    int xi[kColumnPer];
-    float xv[kColumnPer], gain[kColumnPer];
-    uint32_t row[kColumnPer];
+    int xi[PER];
+    float xv[PER], gain[PER];
+    uint32_t row[PER];
 #pragma unroll
-    for (int r = 0; r < kColumnPer; ++r) {
+    for (int r = 0; r < PER; ++r) {
       xi[r] = min(i0 + tid + r * kColumnThreads, a.n_in - 1);
       xv[r] = xr[xi[r]];
       row[r] = ti[xi[r]];
@@ -496,28 +497,28 @@ __global__ __launch_bounds__(kColumnThreads) void kan_column_kernel(const Bucket
     }
     // the input is x itself, or the previous layer's per-bucket sums still to be added (in order) and squashed
     for (int p0 = 1; p0 < a.x_parts; p0 += 8) {
-      float t[8][kColumnPer];
+      float t[8][PER];
 #pragma unroll
       for (int pp = 0; pp < 8; ++pp) {
         const float* xp = xr + (long long)min(p0 + pp, a.x_parts - 1) * a.x_part_stride;
 #pragma unroll
-        for (int r = 0; r < kColumnPer; ++r) t[pp][r] = xp[xi[r]];
+        for (int r = 0; r < PER; ++r) t[pp][r] = xp[xi[r]];
       }
 #pragma unroll
       for (int pp = 0; pp < 8; ++pp)
 #pragma unroll
-        for (int r = 0; r < kColumnPer; ++r) xv[r] += (p0 + pp < a.x_parts) ? t[pp][r] : 0.f;
+        for (int r = 0; r < PER; ++r) xv[r] += (p0 + pp < a.x_parts) ? t[pp][r] : 0.f;
     }
     // ---- basis of the thread's own inputs, then the windows of its edges ----------------------
-    BasisW w[kColumnPer];
-    typename WindowRaw<CbT>::type raw[kColumnPer];
+    BasisW w[PER];
+    typename WindowRaw<CbT>::type raw[PER];
 #pragma unroll
-    for (int r = 0; r < kColumnPer; ++r) {
+    for (int r = 0; r < PER; ++r) {
       w[r] = basis_eval_rule(a.x_tanh ? tanhf(xv[r]) : xv[r], a.rule);
       raw[r] = load_window<CbT>(cbk, row[r], w[r].span);
     }
 #pragma unroll
-    for (int r = 0; r < kColumnPer; ++r) {
+    for (int r = 0; r < PER; ++r) {
       float c[4];
       dequant_window<CbT>(raw[r], 1.0f, c);
       // sum_k w_k c_k with w3 = 1 - w0 - w1 - w2 (the bases sum to 1)
@@ -863,20 +864,26 @@ hipError_t launch_column(int code, int gb_kind, const BucketArgs& a, int heads, 
   if (gb_kind == kGbQ8 && code != kCbI8) return hipErrorInvalidValue;
   dim3 grid((unsigned)a.n_out, (unsigned)a.B, (unsigned)heads);
   dim3 block(kColumnThreads);
+#define KAN_LAUNCH_COLUMN(GK, CB)                                                                                  \
+  do {                                                                                                             \
+    if (a.n_in <= 4 * kColumnThreads) hipLaunchKernelGGL((kan_column_kernel<GK, CB, 4>), grid, block, 0, s, a);    \
+    else hipLaunchKernelGGL((kan_column_kernel<GK, CB, 8>), grid, block, 0, s, a);                                 \
+  } while (0)
   if (code == kCbI8) {
-    if (gb_kind == kGbQ8) hipLaunchKernelGGL((kan_column_kernel<kGbQ8, int8_t>), grid, block, 0, s, a);
-    else if (gb_kind == kGbF16) hipLaunchKernelGGL((kan_column_kernel<kGbF16, int8_t>), grid, block, 0, s, a);
-    else hipLaunchKernelGGL((kan_column_kernel<kGbF32, int8_t>), grid, block, 0, s, a);
+    if (gb_kind == kGbQ8) KAN_LAUNCH_COLUMN(kGbQ8, int8_t);
+    else if (gb_kind == kGbF16) KAN_LAUNCH_COLUMN(kGbF16, int8_t);
+    else KAN_LAUNCH_COLUMN(kGbF32, int8_t);
   } else if (code == kCbF16) {
-    if (gb_kind == kGbF16) hipLaunchKernelGGL((kan_column_kernel<kGbF16, __half>), grid, block, 0, s, a);
-    else hipLaunchKernelGGL((kan_column_kernel<kGbF32, __half>), grid, block, 0, s, a);
+    if (gb_kind == kGbF16) KAN_LAUNCH_COLUMN(kGbF16, __half);
+    else KAN_LAUNCH_COLUMN(kGbF32, __half);
   } else if (code == kCbBfp8) {
-    if (gb_kind == kGbF16) hipLaunchKernelGGL((kan_column_kernel<kGbF16, bfp8_t>), grid, block, 0, s, a);
-    else hipLaunchKernelGGL((kan_column_kernel<kGbF32, bfp8_t>), grid, block, 0, s, a);
+    if (gb_kind == kGbF16) KAN_LAUNCH_COLUMN(kGbF16, bfp8_t);
+    else KAN_LAUNCH_COLUMN(kGbF32, bfp8_t);
   } else {
-    if (gb_kind == kGbF16) hipLaunchKernelGGL((kan_column_kernel<kGbF16, float>), grid, block, 0, s, a);
-    else hipLaunchKernelGGL((kan_column_kernel<kGbF32, float>), grid, block, 0, s, a);
+    if (gb_kind == kGbF16) KAN_LAUNCH_COLUMN(kGbF16, float);
+    else KAN_LAUNCH_COLUMN(kGbF32, float);
   }
+#undef KAN_LAUNCH_COLUMN
   return hipGetLastError();
 }
 
