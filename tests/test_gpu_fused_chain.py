@@ -161,3 +161,21 @@ def test_batch1_group_of_heads(kb):
         y_ref = ko.vq_head_forward(x, [p.as_dict() for p in Ps])
         rep = ko.error_report(y[h], y_ref)
         assert np.isfinite(y[h]).all() and rep["headline"] <= TOL_FP32, (h, rep)
+
+
+@pytest.mark.parametrize("B", [1, 7, 16, 24])
+def test_two_tap_rule_with_handed_over_sums(kb, B):
+    """The two-tap rule (linear interpolation between two grid points) through the same hand-over."""
+    Ps, x = synth.config3(B)
+    Ls = [kb.VQLayer(p, rule=kb.KAN_RULE_PLI2) for p in Ps]
+    xd = to_dev(x)
+    for path, tol in ((kb.KAN_PATH_GATHER, TOL_FP32), (kb.KAN_PATH_MFMA, TOL_MFMA)):
+        rec = _launches(kb, [Ls], xd, path)
+        assert "kan_reduce@L1" not in rec, rec
+        y_dev = torch.full((1, B, Ps[-1].n_out), float("nan"), device="cuda")
+        y = kb.kan_vq_head_forward([Ls], xd, path=path, y=y_dev)[0].cpu().numpy()
+        y_ref = ko.vq_head_forward(x, [p.as_dict() for p in Ps], rule="pli")
+        rep = ko.error_report(y, y_ref)
+        assert np.isfinite(y).all() and rep["headline"] <= tol, (path, rep)
+        y_chain, _ = check_head_layer_by_layer(kb, Ls, Ps, x, path, tol, rule="pli")
+        assert np.abs(y - y_chain).max() <= 2 * tol * np.abs(y_chain).max()
