@@ -179,3 +179,40 @@ def test_two_tap_rule_with_handed_over_sums(kb, B):
         assert np.isfinite(y).all() and rep["headline"] <= tol, (path, rep)
         y_chain, _ = check_head_layer_by_layer(kb, Ls, Ps, x, path, tol, rule="pli")
         assert np.abs(y - y_chain).max() <= 2 * tol * np.abs(y_chain).max()
+
+
+def _random_heads(n, seed):
+    rng = np.random.default_rng(seed)
+    kinds = [("i8", "f16", "u16"), ("i8", "q8", "u16"), ("f16", "f16", "u16"), ("bfp8", "f16", "u16"), ("f32", "f32", "u32"),
+             ("i8", "f32", "u32"), ("f16", "f32", "u16")]
+    out = []
+    for c in range(n):
+        depth = int(rng.integers(2, 5))
+        dims = [int(rng.choice([int(rng.integers(8, 1500)), 4 * int(rng.integers(2, 375)), 16 * int(rng.integers(1, 90))]))
+                for _ in range(depth + 1)]
+        cb, gb, idx = kinds[int(rng.integers(len(kinds)))]
+        K = int(rng.integers(2, 66000 if idx == "u32" else 60000))
+        B = int(rng.choice([1, 1, 2, 3, 8, 13, 16, 17, 25, 32]))
+        out.append(pytest.param(dims, cb, gb, idx, K, B, 9000 + 17 * c, id=f"{c}-{'x'.join(map(str, dims))}-{cb}-{gb}-B{B}"))
+    return out
+
+
+@pytest.mark.parametrize("dims,cb,gb,idx,K,B,seed", _random_heads(24, 20251129))
+def test_random_heads(kb, dims, cb, gb, idx, K, B, seed):
+    """Seeded random heads (depth 2..4, widths with and without a factor of four, every storage type, batch
+    1..32): whichever layers hand their partial sums on, the head matches the float64 head and the chain of
+    single-layer calls, and leaves no output unwritten."""
+    Ps = _head(seed, dims, K, cb=cb, gb=gb, idx=idx)
+    x = synth.make_x(seed + 7, B, dims[0])
+    Ls = gpu_layers(Ps)
+    xd = to_dev(x)
+    for path, tol in ((kb.KAN_PATH_GATHER, TOL_FP32), (kb.KAN_PATH_MFMA, TOL_MFMA)):
+        y_dev = torch.full((1, B, dims[-1]), float("nan"), device="cuda")
+        y = kb.kan_vq_head_forward([Ls], xd, path=path, y=y_dev)[0].cpu().numpy()
+        assert np.isfinite(y).all()
+        y_ref = ko.vq_head_forward(x, [p.as_dict() for p in Ps])
+        rep = ko.error_report(y, y_ref)
+        assert rep["headline"] <= tol, (path, rep)
+        y_chain, _ = check_head_layer_by_layer(kb, Ls, Ps, x, path, tol)
+        assert np.abs(y - y_chain).max() <= 2 * tol * max(np.abs(y_chain).max(), 1e-30)
+        assert np.array_equal(y, kb.kan_vq_head_forward([Ls], xd, path=path)[0].cpu().numpy())
