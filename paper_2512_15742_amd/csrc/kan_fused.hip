@@ -81,8 +81,13 @@ __global__ __launch_bounds__(kThreads, 2) void kan_fused_kernel(const FusedArgs 
   constexpr int kTileBytes = kFp32Ops ? BM * LDF * 4 : (kSplit ? 2 * kHalfTile : kHalfTile);   // split form: high parts, then low parts
   __shared__ __attribute__((aligned(16))) unsigned char sTile[2][kTileBytes];
   __shared__ __attribute__((aligned(16))) uint32_t sSel[kSpans][8];
-  if constexpr (!kFp32Ops) fill_weight_selectors(sSel, threadIdx.x);
-  __syncthreads();
+  // (filled by the pipelines below once their first loads are on their way: nothing reads it before the first tile)
+  [[maybe_unused]] auto fill_selectors = [&]() {
+    if constexpr (!kFp32Ops) {
+      fill_weight_selectors(sSel, threadIdx.x);
+      __syncthreads();
+    }
+  };
 
   const int tid = threadIdx.x;
   const int lane = tid & 63, wave = tid >> 6;
@@ -637,6 +642,7 @@ __global__ __launch_bounds__(kThreads, 2) void kan_fused_kernel(const FusedArgs 
   #pragma unroll
       for (int q = RD; q < RD + 2; ++q) load_meta_deep(q, ids[q & 3], gbr[q & 7]);     // (the gathers above have read slots 0, 1)
     }
+    fill_selectors();
     dequant_deep(rows[0], odd[0], gbr[0], frag[0]);
     gen_phi(uv[0], sTile[0]);
 
@@ -745,6 +751,7 @@ __global__ __launch_bounds__(kThreads, 2) void kan_fused_kernel(const FusedArgs 
       load_u(0, uv[0]);
     }
     load_u(1, uv[1]);
+    fill_selectors();
     dequant_step(rows[0], meta[0], frag[0]);
     gen_phi(uv[0], sTile[0]);
 
