@@ -185,6 +185,7 @@ constexpr int64_t kHalfFusedMaxBatch = 64;   // fp16 path: fused kernel up to he
 constexpr int64_t kFusedTwoTilesMaxBatch = 128;            // ... and up to here (both paths) for layers of at least
 constexpr long long kFusedTwoTilesMinEdges = 1ll << 22;    // this many edges whose codeword rows are one gather each
 constexpr long long kFusedMinEdgesForResidency = 1 << 17;   // ... for layers of at least this many edges per head
+constexpr long long kFusedSmallLayerEdges = 1 << 19;   // fused kernel: layers up to here may write partial sums as large as their stream
 constexpr int kFusedMinWgsPerHead = 20;      // fused kernel, several heads: workgroups per head (L2 residency of the codebooks)
 // Precise path: from this batch on the split-operand matrix-core form.  Its time hardly depends on
 // the batch below 128 (config 3: 96 us, config 2: 44 us) while the fused fp32 kernel's doubles with
@@ -288,7 +289,14 @@ LayerPlan plan_fused(int n_in, int n_out, int64_t B, int n_heads, int idx_u32, i
     if (chunks < want) chunks = want;
   }
   const long long max_by_rows = n_in / 16;                                   // at least two steps each
-  const long long max_by_bytes = (long long)n_in * bytes_per_edge / (4 * B);
+  // Partial sums up to a quarter of the parameter stream - up to the whole of it for small layers, whose
+  // launch is a latency chain and not a stream: capped at a quarter, config 3's second layer (262,144 edges) ran
+  // on 48 workgroups at batch 64 and took 17-28 us; with the cap at the stream's size it runs on 128 and takes
+  // 12.5-14.7 us (the head at batch 32 / 48 / 64: 39.9 / 57.5 / 60.0 against 46.7 / 62.8 / 71.5 us precise, 30.3 /
+  // 41.0 / 43.8 against 36.9 / 43.5 / 47.6 us fp16; at batch 32 its chunks also become short enough to take the
+  // first layer's partial sums as they are).  Layers of a million edges and more gain nothing from it.
+  const long long max_by_bytes =
+      (long long)n_in * bytes_per_edge / ((long long)n_in * n_out <= kFusedSmallLayerEdges ? B : 4 * B);
   if (chunks > max_by_rows) chunks = max_by_rows;
   if (chunks > max_by_bytes) chunks = max_by_bytes;
   if (chunks < 1) chunks = 1;
